@@ -1,0 +1,364 @@
+"""fp64 CPU oracle for streaming-constrained attention (StreamingThinker).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition the HIP
+kernels are checked against.  It may be imported by tests/, by the smoke check
+and by the bench's cpu_baseline leg -- never by the product package, and it
+imports nothing from it.  Everything is numpy in float64, one definition per
+function, no blocking / fusion / reordering.
+
+What the paper fixes and where:
+  * which token may attend to which      -- Eq. 1 (conditioning sets), Eq. 2
+    (streaming mask on top of the causal mask), Sec. 3.2 "Streaming Attention
+    Mask Matrix", Appendix E.1, Alg. 1 (N_EOS == N_EOT + 1)
+  * stream-local position ids for RoPE    -- Sec. 3.2 "Streaming Position
+    Encoding" (input and reasoning tokens are numbered independently from 0)
+  * two KV caches read jointly at decode  -- Sec. 3.3 "Parallel KV caches",
+    Alg. 1 (merge of the source slice and the reasoning cache before decoding)
+
+Readings taken where the paper is silent (softmax scale 1/sqrt(D), grouped-query
+head mapping, rotate-half RoPE pairing, base 1e6) are pinned to the textbook /
+library convention by tests/test_oracle_pins.py.
+
+Pins (all in tests/test_oracle_pins.py): brute-force gather, layout
+equivariance, Eq. 2 as printed, reduction to library causal attention,
+closed-form visible-pair counts, LSE-merge == concatenation, RoPE identities,
+decode == last prefill row, paged gather == contiguous.  No function here is
+"parity unpinned".
+"""
+import numpy as np
+
+SRC = 0  # token of the input ("source") stream
+RSN = 1  # token of the reasoning stream
+
+PAGE = 16  # tokens per KV-cache page
+
+
+# --------------------------------------------------------------------------
+# Visibility (Eq. 1 / Eq. 2 / Alg. 1)
+# --------------------------------------------------------------------------
+def visible(stream_i, seg_i, pos_i, stream_j, seg_j, pos_j):
+    """May query token i attend to key token j (same sequence)?
+
+    Eq. 1: reasoning unit R_t conditions on C_{<=t} and R_{<=t-1} (plus itself,
+    causally); input sentences condition on earlier input only.  Eq. 2 states
+    the same thing as a mask: causal everywhere, and in the reasoning-rows x
+    input-columns block the inputs of later steps are removed.
+    """
+    if stream_i == SRC:
+        # a source row never sees reasoning; among sources it is causal
+        return stream_j == SRC and pos_j <= pos_i
+    # reasoning row
+    if stream_j == RSN:
+        return pos_j <= pos_i           # causal over the whole reasoning stream
+    return seg_j <= seg_i               # source segments up to the row's own step
+
+
+def dense_mask(stream, seg, pos):
+    """bool[n, n]: mask[i, j] = visible(i, j), for one sequence.
+
+    Same rule as visible(), written with broadcasting.
+    """
+    stream = np.asarray(stream); seg = np.asarray(seg); pos = np.asarray(pos)
+    si, sj = stream[:, None], stream[None, :]
+    src_row = (si == SRC) & (sj == SRC) & (pos[None, :] <= pos[:, None])
+    rsn_rsn = (si == RSN) & (sj == RSN) & (pos[None, :] <= pos[:, None])
+    rsn_src = (si == RSN) & (sj == SRC) & (seg[None, :] <= seg[:, None])
+    return src_row | rsn_rsn | rsn_src
+
+
+def mask_rows(stream, seg, pos, rows):
+    """bool[len(rows), n]: the rows `rows` of dense_mask, without building it all."""
+    stream = np.asarray(stream); seg = np.asarray(seg); pos = np.asarray(pos)
+    rows = np.asarray(rows)
+    si, sj = stream[rows][:, None], stream[None, :]
+    pi, gi = pos[rows][:, None], seg[rows][:, None]
+    return (((si == SRC) & (sj == SRC) & (pos[None, :] <= pi))
+            | ((si == RSN) & (sj == RSN) & (pos[None, :] <= pi))
+            | ((si == RSN) & (sj == SRC) & (seg[None, :] <= gi)))
+
+
+# --------------------------------------------------------------------------
+# Masked softmax attention (plain definition)
+# --------------------------------------------------------------------------
+def _softmax_attend(scores, mask, v):
+    """scores[m, n] (already scaled), mask[m, n] bool, v[n, D] -> out[m, D], lse[m].
+
+    Max-subtracted softmax over the visible columns.  A row with no visible
+    column gives out = 0 and lse = -inf.
+    """
+    s = np.where(mask, scores, -np.inf)
+    mx = s.max(axis=1, keepdims=True, initial=-np.inf)
+    mx_safe = np.where(np.isfinite(mx), mx, 0.0)
+    e = np.where(mask, np.exp(s - mx_safe), 0.0)
+    den = e.sum(axis=1, keepdims=True)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        out = np.where(den > 0, (e @ v) / np.where(den > 0, den, 1.0), 0.0)
+        lse = np.where(den[:, 0] > 0, mx_safe[:, 0] + np.log(np.where(den[:, 0] > 0, den[:, 0], 1.0)), -np.inf)
+    return out, lse
+
+
+def attention_dense(q, k, v, stream, seg, pos, scale=None, rows=None):
+    """Streaming-mask attention for ONE sequence.
+
+    q[n, Hq, D], k[n, Hkv, D], v[n, Hkv, D] (any float dtype; promoted to fp64).
+    Query head h reads KV head h // (Hq // Hkv).  Returns out[m, Hq, D] and
+    lse[m, Hq] (natural log of the softmax denominator), m = n or len(rows).
+    """
+    q = np.asarray(q, dtype=np.float64); k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    n, hq, d = q.shape
+    hkv = k.shape[1]
+    group = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    if rows is None:
+        rows = np.arange(n)
+        mask = dense_mask(stream, seg, pos)
+    else:
+        rows = np.asarray(rows)
+        mask = mask_rows(stream, seg, pos, rows)
+    out = np.zeros((len(rows), hq, d)); lse = np.zeros((len(rows), hq))
+    for h in range(hq):
+        hk = h // group
+        scores = scale * (q[rows, h, :] @ k[:, hk, :].T)
+        out[:, h, :], lse[:, h] = _softmax_attend(scores, mask, v[:, hk, :])
+    return out, lse
+
+
+def attention_varlen(q, k, v, stream, seg, pos, cu_seqlens, scale=None):
+    """attention_dense over a packed batch; cu_seqlens has B + 1 entries."""
+    q = np.asarray(q); out = np.zeros(q.shape, dtype=np.float64)
+    lse = np.zeros(q.shape[:2], dtype=np.float64)
+    for b in range(len(cu_seqlens) - 1):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        out[s:e], lse[s:e] = attention_dense(q[s:e], k[s:e], v[s:e], stream[s:e], seg[s:e], pos[s:e], scale)
+    return out, lse
+
+
+def attention_bruteforce(q, k, v, stream, seg, pos, scale=None):
+    """Same result as attention_dense, from the conditioning SETS of Eq. 1.
+
+    No mask matrix: for each row the list of visible token indices is gathered
+    by walking the segments (source steps <= the row's step; reasoning tokens
+    up to and including the row), then a softmax over that list.  Pure-Python
+    loops; tiny inputs only.
+    """
+    q = np.asarray(q, dtype=np.float64); k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    n, hq, d = q.shape
+    group = hq // k.shape[1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((n, hq, d)); lse = np.zeros((n, hq))
+    for i in range(n):
+        vis = [j for j in range(n)
+               if visible(stream[i], seg[i], pos[i], stream[j], seg[j], pos[j])]
+        for h in range(hq):
+            hk = h // group
+            sc = [scale * sum(q[i, h, t] * k[j, hk, t] for t in range(d)) for j in vis]
+            mx = max(sc)
+            w = [np.exp(x - mx) for x in sc]
+            den = sum(w)
+            for t in range(d):
+                out[i, h, t] = sum(w[a] * v[vis[a], hk, t] for a in range(len(vis))) / den
+            lse[i, h] = mx + np.log(den)
+    return out, lse
+
+
+# --------------------------------------------------------------------------
+# RoPE with stream-local positions (Sec. 3.2 "Streaming Position Encoding")
+# --------------------------------------------------------------------------
+def rope(x, positions, theta=1.0e6):
+    """Rotate x[n, H, D] by positions[n]; rotate-half pairing (i, i + D/2).
+
+    f_i = theta ** (-2 i / D); a = p * f_i;
+    y_i       = x_i cos a - x_{i+D/2} sin a
+    y_{i+D/2} = x_{i+D/2} cos a + x_i sin a
+    The positions are whatever the caller assigns; the paper's assignment is
+    one counter per stream, both starting at 0 (see stream_local_positions).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    half = d // 2
+    i = np.arange(half, dtype=np.float64)
+    freq = theta ** (-2.0 * i / d)
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * freq[None, :]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def stream_local_positions(stream):
+    """The paper's position ids: the n-th token of each stream gets id n (0-based)."""
+    stream = np.asarray(stream)
+    pos = np.zeros(len(stream), dtype=np.int64)
+    for kind in (SRC, RSN):
+        idx = np.nonzero(stream == kind)[0]
+        pos[idx] = np.arange(len(idx))
+    return pos
+
+
+# --------------------------------------------------------------------------
+# Dual-cache decode (Sec. 3.3 "Parallel KV caches"; Alg. 1 merge + decode)
+# --------------------------------------------------------------------------
+def decode_dual_concat(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, scale=None):
+    """One sequence.  q[q_len, Hq, D]; caches [len, Hkv, D] (logical order).
+
+    The merged cache of Alg. 1 written out: keys = visible source slice
+    followed by the reasoning cache.  Query row t (of q_len, the LAST q_len
+    reasoning tokens, already appended) sees the whole source slice and
+    reasoning tokens [0, rsn_len - q_len + t].  Returns out[q_len, Hq, D],
+    lse[q_len, Hq].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    q_len, hq, d = q.shape
+    sk = np.asarray(src_k, dtype=np.float64)[:src_visible_len]
+    sv = np.asarray(src_v, dtype=np.float64)[:src_visible_len]
+    rk = np.asarray(rsn_k, dtype=np.float64)[:rsn_len]
+    rv = np.asarray(rsn_v, dtype=np.float64)[:rsn_len]
+    kk = np.concatenate([sk, rk], axis=0); vv = np.concatenate([sv, rv], axis=0)
+    hkv = kk.shape[1]
+    group = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    n = kk.shape[0]
+    col = np.arange(n)[None, :]
+    limit = src_visible_len + rsn_len - q_len + np.arange(q_len)[:, None]   # last visible column
+    mask = col <= limit
+    out = np.zeros((q_len, hq, d)); lse = np.zeros((q_len, hq))
+    for h in range(hq):
+        hk = h // group
+        scores = scale * (q[:, h, :] @ kk[:, hk, :].T)
+        out[:, h, :], lse[:, h] = _softmax_attend(scores, mask, vv[:, hk, :])
+    return out, lse
+
+
+def attend_one_cache(q, k, v, mask, scale=None):
+    """Softmax attention of q[m, Hq, D] over ONE cache k, v[n, Hkv, D] -> (out, lse)."""
+    q = np.asarray(q, dtype=np.float64); k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    m, hq, d = q.shape
+    group = hq // k.shape[1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((m, hq, d)); lse = np.zeros((m, hq))
+    for h in range(hq):
+        hk = h // group
+        scores = scale * (q[:, h, :] @ k[:, hk, :].T)
+        out[:, h, :], lse[:, h] = _softmax_attend(scores, mask, v[:, hk, :])
+    return out, lse
+
+
+def lse_merge(o1, lse1, o2, lse2):
+    """Combine two partial attentions over disjoint key sets.
+
+    m = max(lse1, lse2); w_c = exp(lse_c - m); o = (w1 o1 + w2 o2) / (w1 + w2);
+    lse = m + log(w1 + w2).  An empty set has lse = -inf, weight 0.
+    """
+    m = np.maximum(lse1, lse2)
+    m_safe = np.where(np.isfinite(m), m, 0.0)
+    w1 = np.where(np.isfinite(lse1), np.exp(lse1 - m_safe), 0.0)
+    w2 = np.where(np.isfinite(lse2), np.exp(lse2 - m_safe), 0.0)
+    den = w1 + w2
+    den_safe = np.where(den > 0, den, 1.0)
+    o = np.where(den[..., None] > 0, (w1[..., None] * o1 + w2[..., None] * o2) / den_safe[..., None], 0.0)
+    with np.errstate(divide="ignore"):
+        lse = np.where(den > 0, m_safe + np.log(den_safe), -np.inf)
+    return o, lse
+
+
+def decode_dual_merged(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, scale=None):
+    """decode_dual_concat computed as two separate softmaxes + lse_merge."""
+    q = np.asarray(q, dtype=np.float64)
+    q_len = q.shape[0]
+    m_src = np.ones((q_len, src_visible_len), dtype=bool)
+    col = np.arange(rsn_len)[None, :]
+    m_rsn = col <= (rsn_len - q_len + np.arange(q_len)[:, None])
+    o1, l1 = attend_one_cache(q, np.asarray(src_k)[:src_visible_len], np.asarray(src_v)[:src_visible_len], m_src, scale)
+    o2, l2 = attend_one_cache(q, np.asarray(rsn_k)[:rsn_len], np.asarray(rsn_v)[:rsn_len], m_rsn, scale)
+    return lse_merge(o1, l1, o2, l2)
+
+
+# --------------------------------------------------------------------------
+# Paged cache model (append / gather)
+# --------------------------------------------------------------------------
+def paged_append(pool, page_table, lens, b, new_rows):
+    """Write new_rows[n_new, Hkv, D] at logical positions lens[b].. of sequence b.
+
+    pool[n_pages, PAGE, Hkv, D] is the LOGICAL pool (page, slot); logical
+    position p of sequence b lives in page page_table[b][p // PAGE], slot
+    p % PAGE.  lens[b] is advanced.
+    """
+    for t in range(new_rows.shape[0]):
+        p = int(lens[b]) + t
+        pool[page_table[b][p // PAGE], p % PAGE] = new_rows[t]
+    lens[b] += new_rows.shape[0]
+
+
+def paged_gather(pool, page_table, b, length):
+    """Logical rows [0, length) of sequence b as a contiguous [length, Hkv, D] array."""
+    out = np.zeros((length,) + pool.shape[2:], dtype=pool.dtype)
+    for p in range(length):
+        out[p] = pool[page_table[b][p // PAGE], p % PAGE]
+    return out
+
+
+# --------------------------------------------------------------------------
+# Canonical skip metadata, derived by REDUCING the dense mask
+# --------------------------------------------------------------------------
+SKIP, FULL, PARTIAL = 0, 1, 2
+
+
+def _tile_classes(block, bm, bn):
+    """block[m, n] bool -> uint8[ceil(m/bm), ceil(n/bn)] of SKIP / FULL / PARTIAL.
+
+    Ragged edge tiles are judged on their in-range elements only.
+    """
+    m, n = block.shape
+    tq, tk = -(-m // bm), -(-n // bn)
+    cls = np.zeros((tq, tk), dtype=np.uint8)
+    for a in range(tq):
+        for c in range(tk):
+            t = block[a * bm:(a + 1) * bm, c * bn:(c + 1) * bn]
+            cls[a, c] = FULL if t.all() else (PARTIAL if t.any() else SKIP)
+    return cls
+
+
+def canonical_metadata(stream, seg, pos, bm, bn):
+    """Segment-skip metadata of ONE sequence in grouped stream-compact order.
+
+    The sequence is permuted to [all source tokens by position | all reasoning
+    tokens by position] (the paper's grouped training layout, Appendix E.1),
+    the dense mask is built there, and everything is read off that matrix:
+      src_idx, rsn_idx : physical index of each compact row
+      vis_src[r]       : number of source columns row r (reasoning) can see
+      classes of the three blocks SS (source rows x source cols),
+      RS (reasoning rows x source cols), RR (reasoning x reasoning)
+      visible_pairs    : number of True entries of the mask
+    """
+    stream = np.asarray(stream); seg = np.asarray(seg); pos = np.asarray(pos)
+    src_idx = np.nonzero(stream == SRC)[0]
+    rsn_idx = np.nonzero(stream == RSN)[0]
+    src_idx = src_idx[np.argsort(pos[src_idx], kind="stable")]
+    rsn_idx = rsn_idx[np.argsort(pos[rsn_idx], kind="stable")]
+    perm = np.concatenate([src_idx, rsn_idx])
+    mask = dense_mask(stream[perm], seg[perm], pos[perm])
+    s = len(src_idx)
+    ss, rs, rr = mask[:s, :s], mask[s:, :s], mask[s:, s:]
+    assert not mask[:s, s:].any()
+    return {
+        "src_idx": src_idx.astype(np.int32),
+        "rsn_idx": rsn_idx.astype(np.int32),
+        "vis_src": rs.sum(axis=1).astype(np.int32),
+        "SS": _tile_classes(ss, bm, bn),
+        "RS": _tile_classes(rs, bm, bn),
+        "RR": _tile_classes(rr, bm, bn),
+        "visible_pairs": int(mask.sum()),
+    }
+
+
+def source_prefix_table(stream, seg):
+    """P[g] = number of source tokens with segment id <= g, g = 0 .. max id."""
+    stream = np.asarray(stream); seg = np.asarray(seg)
+    gmax = int(seg.max()) if len(seg) else -1
+    return np.array([int(((stream == SRC) & (seg <= g)).sum()) for g in range(gmax + 1)], dtype=np.int32)

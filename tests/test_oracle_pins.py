@@ -1,0 +1,326 @@
+"""Pins for the fp64 oracle: each test ties one part of oracle/ to something the
+paper or plain mathematics fixes (brute force, closed forms, library routines,
+invariants), so a dropped term, wrong sign / index or transposed operand in the
+oracle fails at least one of them.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import streaming_attention as O
+import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_case(seed, n_pairs, src_rng, rsn_rng, hq, hkv, d, layout="interleaved"):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    s, r = W.draw_pairs(rng, n_pairs, src_rng, rsn_rng)
+    stream, seg, pos = W.tokens_from_segments(s, r, layout)
+    n = len(stream)
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    return s, r, stream, seg, pos, q, k, v
+
+
+# ---- P1: dense-mask attention == brute force over the explicit visible sets (Eq. 1)
+def test_p1_bruteforce_config1():
+    cfg = W.config1()
+    q, k, v = cfg.tensors()
+    o_d, l_d = O.attention_dense(q, k, v, cfg.stream_ids, cfg.segment_ids, cfg.positions)
+    o_b, l_b = O.attention_bruteforce(q, k, v, cfg.stream_ids, cfg.segment_ids, cfg.positions)
+    assert np.abs(o_d - o_b).max() < 1e-12
+    assert np.abs(l_d - l_b).max() < 1e-12
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_p1_bruteforce_random(seed):
+    # 0-length and 1-token segments allowed
+    s, r, stream, seg, pos, q, k, v = _rand_case(seed, 5, (0, 5), (0, 6), 4, 2, 8)
+    if len(stream) == 0:
+        pytest.skip("empty draw")
+    o_d, l_d = O.attention_dense(q, k, v, stream, seg, pos)
+    o_b, l_b = O.attention_bruteforce(q, k, v, stream, seg, pos)
+    assert np.abs(o_d - o_b).max() < 1e-12
+    assert np.abs(l_d - l_b).max() < 1e-12
+
+
+def test_p1_visible_sets_match_eq1():
+    """Conditioning sets of Eq. 1 written out: R_t sees C_{<=t}, R_{<t} and its own prefix; C_t sees C only."""
+    s = [2, 3, 1]; r = [2, 1, 3]
+    stream, seg, pos = W.tokens_from_segments(s, r, "interleaved")
+    mask = O.dense_mask(stream, seg, pos)
+    # physical order: S1(0,1) R1(2,3) S2(4,5,6) R2(7) S3(8) R3(9,10,11)
+    expect = {
+        0: [0], 1: [0, 1],
+        2: [0, 1, 2], 3: [0, 1, 2, 3],
+        4: [0, 1, 4], 5: [0, 1, 4, 5], 6: [0, 1, 4, 5, 6],
+        7: [0, 1, 4, 5, 6, 2, 3, 7],
+        8: [0, 1, 4, 5, 6, 8],
+        9: [0, 1, 4, 5, 6, 8, 2, 3, 7, 9],
+        10: [0, 1, 4, 5, 6, 8, 2, 3, 7, 9, 10],
+        11: [0, 1, 4, 5, 6, 8, 2, 3, 7, 9, 10, 11],
+    }
+    for i, cols in expect.items():
+        assert sorted(np.nonzero(mask[i])[0].tolist()) == sorted(cols), i
+
+
+# ---- P2: the result does not depend on the physical layout (interleaved vs grouped)
+@pytest.mark.parametrize("seed", [21, 22])
+def test_p2_layout_equivariance(seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    s, r = W.draw_pairs(rng, 4, (1, 6), (1, 7))
+    st_i, sg_i, ps_i = W.tokens_from_segments(s, r, "interleaved")
+    st_g, sg_g, ps_g = W.tokens_from_segments(s, r, "grouped")
+    n = len(st_i)
+    q = rng.standard_normal((n, 4, 16)); k = rng.standard_normal((n, 2, 16)); v = rng.standard_normal((n, 2, 16))
+    # map interleaved token -> grouped slot via (stream, pos)
+    key_i = st_i.astype(np.int64) * 10**6 + ps_i
+    key_g = st_g.astype(np.int64) * 10**6 + ps_g
+    slot = {kk: a for a, kk in enumerate(key_g)}
+    to_g = np.array([slot[kk] for kk in key_i])
+    qg = np.zeros_like(q); kg = np.zeros_like(k); vg = np.zeros_like(v)
+    qg[to_g], kg[to_g], vg[to_g] = q, k, v
+    o_i, l_i = O.attention_dense(q, k, v, st_i, sg_i, ps_i)
+    o_g, l_g = O.attention_dense(qg, kg, vg, st_g, sg_g, ps_g)
+    assert np.abs(o_i - o_g[to_g]).max() < 1e-12
+    assert np.abs(l_i - l_g[to_g]).max() < 1e-12
+
+
+# ---- P3: Eq. 2 exactly as printed (1-token segments, grouped layout)
+def _eq2_as_printed(T, L):
+    n = T + L
+    m = np.zeros((n, n), dtype=bool)
+    for i in range(1, n + 1):
+        for j in range(1, n + 1):
+            causal = j <= i
+            removed = (i > T) and (j < T) and (j > i - T + 1)
+            m[i - 1, j - 1] = causal and not removed
+    return m
+
+
+def test_p3_eq2_golden_file():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq2_mask_T6_L4.txt")) if l.strip() and not l.startswith("#")]
+    golden = np.array(rows, dtype=int).astype(bool)
+    assert (golden == _eq2_as_printed(6, 4)).all()
+    _check_eq2(6, 4, golden)
+
+
+def _check_eq2(T, L, printed):
+    # reasoning token r (1-based) carries segment id r + 1: the row that holds the
+    # last token of unit r predicts the first token of unit r + 1 (Alg. 1 re-merges
+    # with a longer source slice before the next sentence).
+    stream = np.array([O.SRC] * T + [O.RSN] * L)
+    seg = np.array(list(range(1, T + 1)) + [r + 1 for r in range(1, L + 1)])
+    pos = np.array(list(range(T)) + list(range(L)))
+    mask = O.dense_mask(stream, seg, pos)
+    cols = np.arange(T + L) != (T - 1)          # every column except j == T (strict "j < T" in the print)
+    assert (mask[:, cols] == printed[:, cols]).all()
+    # the one column the printed rule never removes: the oracle follows Eq. 1 there
+    for r in range(1, L + 1):
+        assert mask[T + r - 1, T - 1] == (T <= r + 1)
+
+
+@pytest.mark.parametrize("T,L", [(1, 1), (3, 7), (9, 4), (12, 12)])
+def test_p3_eq2_literal(T, L):
+    _check_eq2(T, L, _eq2_as_printed(T, L))
+
+
+# ---- P4: with every source visible the result is textbook causal attention (library routine)
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (4, 2), (6, 1)])
+def test_p4_reduces_to_library_causal(hq, hkv):
+    rng = np.random.Generator(np.random.PCG64(40 + hq + hkv))
+    S, R, d = 9, 14, 16
+    stream, seg, pos = W.tokens_from_segments([S], [R], "grouped")
+    n = S + R
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    o, lse = O.attention_dense(q, k, v, stream, seg, pos)
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    g = hq // hkv
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(g, dim=0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(g, dim=0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.abs(o - ref).max() < 1e-12
+    # lse against torch.logsumexp of the causal scores
+    sc = torch.einsum("hid,hjd->hij", tq[0], tk[0]) / np.sqrt(d)
+    sc = sc.masked_fill(~torch.tril(torch.ones(n, n, dtype=torch.bool)), float("-inf"))
+    assert np.abs(lse - torch.logsumexp(sc, dim=-1).T.numpy()).max() < 1e-12
+
+
+# ---- P5: closed-form visible-pair counts
+def test_p5_pairs_config1():
+    cfg = W.config1()
+    mask = O.dense_mask(cfg.stream_ids, cfg.segment_ids, cfg.positions)
+    assert int(mask.sum()) == 2080 + 2080 + 2560 == 6720
+    assert cfg.closed_form_pairs() == [6720]
+    # physically-causal pairs that the streaming rule removes: source rows x earlier reasoning columns
+    n = 128
+    assert n * (n + 1) // 2 - 6720 == 1536
+    md = O.canonical_metadata(cfg.stream_ids, cfg.segment_ids, cfg.positions, 16, 16)
+    assert md["visible_pairs"] == 6720
+
+
+@pytest.mark.parametrize("seed", [51, 52, 53])
+def test_p5_pairs_random(seed):
+    cfg = W.random_prefill(seed, 3, 6, (0, 9), (0, 11), 2, 1, 8, "f32")
+    for b in range(cfg.batch):
+        s, e = cfg.cu_seqlens[b], cfg.cu_seqlens[b + 1]
+        mask = O.dense_mask(cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e])
+        assert int(mask.sum()) == cfg.closed_form_pairs()[b]
+
+
+# ---- P6: LSE merge of two caches == attention over the concatenated cache
+@pytest.mark.parametrize("ls,lr,q_len", [(7, 5, 1), (0, 6, 1), (9, 1, 1), (12, 9, 3), (0, 4, 4)])
+def test_p6_lse_merge_equals_concat(ls, lr, q_len):
+    rng = np.random.Generator(np.random.PCG64(60 + ls + lr))
+    hq, hkv, d = 4, 2, 16
+    sk = rng.standard_normal((ls + 3, hkv, d)); sv = rng.standard_normal((ls + 3, hkv, d))   # 3 not-yet-visible rows
+    rk = rng.standard_normal((lr, hkv, d)); rv = rng.standard_normal((lr, hkv, d))
+    q = rng.standard_normal((q_len, hq, d))
+    o_c, l_c = O.decode_dual_concat(q, sk, sv, rk, rv, ls, lr)
+    o_m, l_m = O.decode_dual_merged(q, sk, sv, rk, rv, ls, lr)
+    assert np.abs(o_c - o_m).max() < 1e-13
+    assert np.abs(l_c - l_m).max() < 1e-13
+
+
+def test_p6_split_anywhere_and_both_empty():
+    rng = np.random.Generator(np.random.PCG64(66))
+    hq, hkv, d, n = 2, 1, 8, 11
+    k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d)); q = rng.standard_normal((1, hq, d))
+    full_o, full_l = O.attend_one_cache(q, k, v, np.ones((1, n), bool))
+    for cut in range(n + 1):
+        o1, l1 = O.attend_one_cache(q, k[:cut], v[:cut], np.ones((1, cut), bool))
+        o2, l2 = O.attend_one_cache(q, k[cut:], v[cut:], np.ones((1, n - cut), bool))
+        o, l = O.lse_merge(o1, l1, o2, l2)
+        assert np.abs(o - full_o).max() < 1e-13 and np.abs(l - full_l).max() < 1e-13
+    o, l = O.decode_dual_concat(q, k[:0], v[:0], k[:0], v[:0], 0, 0)
+    assert (o == 0).all() and np.isneginf(l).all()
+    # softmax weights of the plain definition, written independently
+    s = (q[0, 0] @ k[:, 0].T) / np.sqrt(d)
+    w = np.exp(s - s.max()); w /= w.sum()
+    assert np.abs(full_o[0, 0] - w @ v[:, 0]).max() < 1e-13
+    assert abs(full_l[0, 0] - np.log(np.exp(s).sum())) < 1e-12
+
+
+# ---- P7: RoPE identities
+def test_p7_rope_identities():
+    rng = np.random.Generator(np.random.PCG64(70))
+    d, h = 32, 3
+    x = rng.standard_normal((5, h, d)); y = rng.standard_normal((5, h, d))
+    # (i) position 0 is the identity
+    assert np.array_equal(O.rope(x, np.zeros(5, int)), x)
+    # (ii) each (i, i + D/2) pair keeps its norm
+    p = np.array([1, 7, 100, 5000, 123456])
+    rx = O.rope(x, p)
+    n0 = x[..., :d // 2] ** 2 + x[..., d // 2:] ** 2
+    n1 = rx[..., :d // 2] ** 2 + rx[..., d // 2:] ** 2
+    assert np.abs(n0 - n1).max() < 1e-9
+    # (iii) <rope(q, m), rope(k, n)> depends on m - n only
+    a = np.einsum("nhd,nhd->nh", O.rope(x, np.full(5, 40)), O.rope(y, np.full(5, 33)))
+    b = np.einsum("nhd,nhd->nh", O.rope(x, np.full(5, 1007)), O.rope(y, np.full(5, 1000)))
+    assert np.abs(a - b).max() < 1e-9
+    # (iv) equal stream-local ids: R(t - t) = I, the score equals the un-rotated one
+    c = np.einsum("nhd,nhd->nh", O.rope(x, p), O.rope(y, p))
+    assert np.abs(c - np.einsum("nhd,nhd->nh", x, y)).max() < 1e-8
+    # (v) standard ids (T + t, t) give R(T): same as rotating q alone by T
+    T = 77
+    e = np.einsum("nhd,nhd->nh", O.rope(x, T + p), O.rope(y, p))
+    f = np.einsum("nhd,nhd->nh", O.rope(x, np.full(5, T)), y)
+    assert np.abs(e - f).max() < 1e-8
+
+
+def test_p7_rope_matches_complex_rotation_and_known_values():
+    rng = np.random.Generator(np.random.PCG64(71))
+    d, theta = 16, 1.0e6
+    x = rng.standard_normal((4, 2, d)); p = np.array([0, 3, 19, 511])
+    z = x[..., :d // 2] + 1j * x[..., d // 2:]
+    freq = np.array([theta ** (-(2 * i) / d) for i in range(d // 2)])
+    zr = z * np.exp(1j * p[:, None, None] * freq[None, None, :])
+    ref = np.concatenate([zr.real, zr.imag], axis=-1)
+    assert np.abs(O.rope(x, p, theta) - ref).max() < 1e-12
+    # D = 2, p = 1: a rotation by exactly one radian, counter-clockwise
+    out = O.rope(np.array([[[1.0, 0.0]]]), np.array([1]), theta)
+    assert np.allclose(out[0, 0], [np.cos(1.0), np.sin(1.0)], atol=1e-15)
+    # slowest pair of D = 4 at base 1e6 turns by p / 1000
+    out = O.rope(np.array([[[0.0, 1.0, 0.0, 0.0]]]), np.array([500]), theta)
+    assert np.allclose(out[0, 0], [0.0, np.cos(0.5), 0.0, np.sin(0.5)], atol=1e-15)
+
+
+def test_p7_stream_local_positions():
+    stream, seg, pos = W.tokens_from_segments([2, 1], [3, 2], "interleaved")
+    assert O.stream_local_positions(stream).tolist() == pos.tolist() == [0, 1, 0, 1, 2, 2, 3, 4]
+
+
+# ---- P8: decode over the two caches == last reasoning row of prefill
+@pytest.mark.parametrize("layout", ["grouped", "interleaved"])
+def test_p8_decode_equals_last_prefill_row(layout):
+    rng = np.random.Generator(np.random.PCG64(80))
+    s = [3, 4, 2, 5]; r = [4, 1, 6, 3]
+    stream, seg, pos = W.tokens_from_segments(s, r, layout)
+    n, hq, hkv, d = len(stream), 4, 2, 16
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    o, lse = O.attention_dense(q, k, v, stream, seg, pos)
+    src = np.nonzero(stream == O.SRC)[0]; rsn = np.nonzero(stream == O.RSN)[0]
+    # a row in the third reasoning segment: sees sources of segments 1..3 only
+    row = rsn[4 + 1 + 2]
+    n_rsn = 4 + 1 + 3
+    o_d, l_d = O.decode_dual_concat(q[row][None], k[src], v[src], k[rsn], v[rsn], 3 + 4 + 2, n_rsn)
+    assert np.abs(o_d[0] - o[row]).max() < 1e-13 and np.abs(l_d[0] - lse[row]).max() < 1e-13
+    # q_len = 3: the last three reasoning rows at once
+    last3 = rsn[-3:]
+    o_d, l_d = O.decode_dual_concat(q[last3], k[src], v[src], k[rsn], v[rsn], sum(s), len(rsn))
+    assert np.abs(o_d - o[last3]).max() < 1e-13 and np.abs(l_d - lse[last3]).max() < 1e-13
+
+
+# ---- P9: paged append + gather == contiguous cache
+def test_p9_paged_gather():
+    rng = np.random.Generator(np.random.PCG64(90))
+    batch, pages_per_seq, hkv, d = 3, 5, 2, 4
+    table = W.shuffled_page_table(rng, batch, pages_per_seq)
+    pool = np.full((batch * pages_per_seq, O.PAGE, hkv, d), np.nan)
+    lens = np.zeros(batch, dtype=np.int64)
+    contiguous = [np.zeros((0, hkv, d)) for _ in range(batch)]
+    for chunk in [1, 15, 17, 3, 16, 9]:
+        for b in range(batch):
+            n_new = max(0, min(chunk + b, pages_per_seq * O.PAGE - int(lens[b])))
+            rows = rng.standard_normal((n_new, hkv, d))
+            O.paged_append(pool, table, lens, b, rows)
+            contiguous[b] = np.concatenate([contiguous[b], rows])
+    for b in range(batch):
+        assert lens[b] == len(contiguous[b])
+        assert np.array_equal(O.paged_gather(pool, table, b, int(lens[b])), contiguous[b])
+    assert len(set(table.flatten().tolist())) == batch * pages_per_seq
+
+
+# ---- metadata derived from the dense mask: closed forms for config 1
+def test_metadata_config1_closed_form():
+    cfg = W.config1()
+    md = O.canonical_metadata(cfg.stream_ids, cfg.segment_ids, cfg.positions, 16, 16)
+    # source tokens sit at physical 0-15, 32-47, ...; reasoning at 16-31, 48-63, ...
+    assert md["src_idx"].tolist() == [32 * (i // 16) + i % 16 for i in range(64)]
+    assert md["rsn_idx"].tolist() == [32 * (i // 16) + 16 + i % 16 for i in range(64)]
+    assert md["vis_src"].tolist() == [16 * (i // 16 + 1) for i in range(64)]
+    tri = np.array([[O.PARTIAL if a == c else (O.FULL if c < a else O.SKIP) for c in range(4)] for a in range(4)])
+    rect = np.array([[O.FULL if c <= a else O.SKIP for c in range(4)] for a in range(4)])
+    assert (md["SS"] == tri).all() and (md["RR"] == tri).all() and (md["RS"] == rect).all()
+    assert O.source_prefix_table(cfg.stream_ids, cfg.segment_ids).tolist() == [0, 16, 32, 48, 64]
+
+
+def test_metadata_vis_src_is_prefix_of_segment():
+    cfg = W.random_prefill(97, 1, 7, (0, 20), (0, 30), 2, 1, 8, "f32")
+    md = O.canonical_metadata(cfg.stream_ids, cfg.segment_ids, cfg.positions, 32, 16)
+    P = O.source_prefix_table(cfg.stream_ids, cfg.segment_ids)
+    rsn_seg = cfg.segment_ids[md["rsn_idx"]]
+    assert md["vis_src"].tolist() == [int(P[g]) for g in rsn_seg]
+    # ragged tiles: a tile made only of in-range visible entries is FULL
+    s_tot = int((cfg.stream_ids == O.SRC).sum())
+    if s_tot:
+        assert md["SS"][0, 0] in (O.PARTIAL, O.FULL)
+
+
+def test_bf16_rounding_helper_roundtrip():
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.14159, 1e-30, 65504.0], dtype=np.float32)
+    r = W.bf16_round(x)
+    t = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(r, t)
+    assert np.array_equal(W.bf16_from_bits(W.bf16_bits(r)), r)
