@@ -1,0 +1,267 @@
+/*
+ * st.h -- C ABI of the streaming-constrained attention library (MI355X / gfx950).
+ *
+ * The library computes the attention operator of StreamingThinker ("think while
+ * reading"): a decoder attends over an INPUT ("source") stream and a REASONING
+ * stream such that a reasoning step never sees input sentences that arrive after
+ * it (paper Eq. 1, Eq. 2), with position ids counted separately per stream
+ * (Sec. 3.2, "Streaming Position Encoding"), and at inference reads two KV
+ * caches -- one per stream -- jointly while the source cache keeps growing
+ * (Sec. 3.3, "Parallel KV caches"; Appendix E.2, Alg. 1).
+ *
+ * Conventions common to every call
+ *   - Pointers are DEVICE pointers unless the comment says "host".
+ *   - Every device buffer is owned by the caller.  The library owns only st_plan
+ *     objects and a thread-local error string.
+ *   - Calls only ENQUEUE work on `hip_stream` (a hipStream_t passed as void*; NULL
+ *     is the default stream) and return without waiting, unless stated otherwise.
+ *   - Argument errors are found on the host before anything is launched; the
+ *     return value says which kind, st_last_error() gives the text.  Nothing
+ *     aborts or throws across this boundary.
+ *   - Tensors are dense row-major with the listed dimension order, 16-byte aligned.
+ *   - Grouped-query attention: query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Softmax scale: scale <= 0 selects 1 / sqrt(head_dim).
+ *   - head_dim is 64 or 128.
+ */
+#ifndef ST_H
+#define ST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum st_status {
+    ST_OK = 0,
+    ST_ERR_INVALID_ARG = 1,  /* null / misaligned pointer, negative size */
+    ST_ERR_SHAPE = 2,        /* head counts / dims that do not fit together */
+    ST_ERR_LAYOUT = 3,       /* malformed token metadata (found by validation) */
+    ST_ERR_CAPACITY = 4,     /* append past the page table, workspace too small */
+    ST_ERR_UNSUPPORTED = 5,  /* dtype / head_dim / page size the kernels do not cover */
+    ST_ERR_RUNTIME = 6       /* a HIP call failed; text in st_last_error() */
+} st_status;
+
+typedef enum st_dtype { ST_F32 = 0, ST_BF16 = 1 } st_dtype;
+
+/* The two streams of the method; also the value set of stream_ids[]. */
+typedef enum st_stream_kind { ST_SOURCE = 0, ST_REASONING = 1 } st_stream_kind;
+
+/* Tile classes reported by st_plan_tile_classes. */
+enum { ST_TILE_SKIP = 0, ST_TILE_FULL = 1, ST_TILE_PARTIAL = 2 };
+
+/* Blocks of the mask in grouped stream-compact coordinates. */
+enum { ST_BLOCK_SS = 0, ST_BLOCK_RS = 1, ST_BLOCK_RR = 2 };
+
+/* Text of the last error on the calling thread; never NULL. */
+const char* st_last_error(void);
+
+/* Library version (major * 100 + minor). */
+int32_t st_version(void);
+
+/* ------------------------------------------------------------------------
+ * st_rope_apply -- rotary position encoding with caller-supplied (stream-local)
+ * position ids.  Sec. 3.2 "Streaming Position Encoding": input tokens and
+ * reasoning tokens are numbered independently, both from 0, so that a reasoning
+ * token and its input token at the same index have relative rotation R(0).
+ *
+ *   x, out    : [n_tokens, n_heads, head_dim], dtype dt; out may equal x (in place)
+ *   positions : int32 [n_tokens], >= 0
+ *   Pairing is (i, i + head_dim/2); angle = position * theta_base^(-2 i / head_dim),
+ *   evaluated in fp64 and applied in fp32; bf16 results are rounded to nearest even.
+ * ---------------------------------------------------------------------- */
+st_status st_rope_apply(void* out, const void* x, const int32_t* positions,
+                        int64_t n_tokens, int32_t n_heads, int32_t head_dim,
+                        double theta_base, st_dtype dt, void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * st_plan -- segment tables of one packed batch, replacing the dense additive
+ * mask of Eq. 2.  The mask depends only on the training / prefill instance
+ * (Appendix E.1), so one plan serves every layer and head.
+ *
+ * Visibility rule encoded (Eq. 1; Eq. 2; Alg. 1's N_EOS == N_EOT + 1):
+ *   a SOURCE token sees source tokens at positions <= its own;
+ *   a REASONING token sees reasoning tokens at positions <= its own, and source
+ *   tokens whose segment id is <= its own segment id.
+ *
+ * Inputs (device int32 [n_tokens], n_tokens = cu_seqlens[batch]):
+ *   segment_ids : sentence / reasoning-unit index of each token, >= 0
+ *   stream_ids  : ST_SOURCE or ST_REASONING
+ *   positions   : stream-local position id
+ *   Within one sequence the tokens of each stream must appear in memory in
+ *   strictly increasing position order with non-decreasing segment ids; the two
+ *   streams may be interleaved or grouped in any way.
+ * cu_seqlens : HOST int32 [batch + 1], cu_seqlens[0] = 0, non-decreasing.
+ *
+ * The plan holds, per sequence, in "grouped stream-compact order" (all source
+ * tokens by position, then all reasoning tokens by position):
+ *   the token index of every compact row, the number of source tokens each
+ *   reasoning row may see, the per-tile SKIP / FULL / PARTIAL extents of the three
+ *   mask blocks SS, RS, RR, a longest-first work list, and the visible-pair count.
+ * All of it is built by device kernels on hip_stream; st_plan_create itself does
+ * not wait for them.
+ *
+ * workspace: device memory of at least st_plan_workspace_bytes(batch, n_tokens)
+ * bytes, 256-byte aligned, which must outlive the plan; or NULL, in which case the
+ * plan allocates its own (hipMalloc) and frees it in st_plan_destroy.
+ * validate != 0: additionally checks the ordering rules above on the device and
+ * WAITS for the result; returns ST_ERR_LAYOUT (and no plan) if they are violated.
+ * ---------------------------------------------------------------------- */
+typedef struct st_plan st_plan;
+
+size_t st_plan_workspace_bytes(int32_t batch, int64_t n_tokens);
+
+st_status st_plan_create(st_plan** plan,
+                         const int32_t* segment_ids, const int32_t* stream_ids,
+                         const int32_t* positions, const int32_t* cu_seqlens_host,
+                         int32_t batch, void* workspace, size_t workspace_bytes,
+                         int32_t validate, void* hip_stream);
+
+/* Frees the plan (and its own workspace, if it allocated one).  The caller must
+ * make sure no kernel that uses the plan is still running.  NULL is ignored. */
+void st_plan_destroy(st_plan* plan);
+
+/* Query tile size (rows of a query tile, columns of a key tile). */
+st_status st_plan_tile_shape(const st_plan* plan, int32_t* tile_m, int32_t* tile_n);
+
+/* The getters below copy plan tables to HOST buffers and wait for the plan's
+ * stream first.  They exist for inspection and bit-exact checks. */
+
+/* n_src[b], n_rsn[b]: tokens per stream; host int32 [batch] each. */
+st_status st_plan_stream_counts(const st_plan* plan, int32_t* n_src_host, int32_t* n_rsn_host);
+/* compact_index[cu_seqlens[b] + r] = token index (into the packed batch) of compact
+ * row r of sequence b: rows [0, n_src) are the source stream, the rest reasoning.
+ * host int32 [n_tokens]. */
+st_status st_plan_compact_index(const st_plan* plan, int32_t* index_host);
+/* visible_source[cu_seqlens[b] + r]: for a reasoning row, the number of source
+ * tokens it sees (a prefix of the compact source stream); for a source row r,
+ * r + 1.  host int32 [n_tokens]. */
+st_status st_plan_visible_source(const st_plan* plan, int32_t* vis_host);
+/* visible (query, key) pairs per sequence; host uint64 [batch]. */
+st_status st_plan_visible_pairs(const st_plan* plan, uint64_t* pairs_host);
+/* Class map of one block (ST_BLOCK_*) of sequence seq, row-major
+ * [n_q_tiles][n_k_tiles] uint8 of ST_TILE_*.  Call with classes_host == NULL to
+ * get the two counts, then with a buffer of n_q_tiles * n_k_tiles bytes.  The map
+ * is expanded from the same per-tile extents the attention kernel loops over. */
+st_status st_plan_tile_classes(const st_plan* plan, int32_t seq, int32_t block,
+                               uint8_t* classes_host, int32_t* n_q_tiles, int32_t* n_k_tiles);
+
+/* ------------------------------------------------------------------------
+ * st_attn_prefill -- streaming-mask attention over a packed batch (prefill /
+ * training forward shape).  Sec. 3.2 "Streaming Attention Mask Matrix", Eq. 2:
+ * softmax(scale * q k^T + M_streaming) v, with M_streaming given by the plan.
+ *
+ *   q, out : [n_tokens, n_q_heads, head_dim]      (dtype dt; already rotated)
+ *   k, v   : [n_tokens, n_kv_heads, head_dim]
+ *   lse    : fp32 [n_tokens, n_q_heads] natural-log softmax denominator, or NULL
+ * Key tiles that the plan marks SKIP are never read.  bf16: MFMA products with
+ * fp32 accumulation and fp32 softmax state, probabilities rounded to bf16 before
+ * the second product.  f32: plain fp32 arithmetic.
+ * ---------------------------------------------------------------------- */
+st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, const void* v,
+                          const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads,
+                          int32_t head_dim, float scale, st_dtype dt, void* hip_stream);
+
+/* Same, taking the token metadata directly: builds a plan, runs the attention,
+ * WAITS for it and frees the plan.  For one-off calls; a caller with several
+ * layers should create the plan once. */
+st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* k, const void* v,
+                              const int32_t* segment_ids, const int32_t* stream_ids,
+                              const int32_t* positions, const int32_t* cu_seqlens_host,
+                              int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                              int32_t head_dim, float scale, st_dtype dt, void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Paged KV caches.  Sec. 3.3: a source cache for input tokens and a separate
+ * cache for reasoning tokens.  Logical position p of sequence b lives in page
+ * page_table[b * max_pages_per_seq + p / 16], slot p % 16.  bf16 only.
+ *
+ * Pool layouts (fixed; chosen so that the decode kernel's matrix-core operands are
+ * contiguous 16-byte loads), with c = d / 8, e = d % 8:
+ *   k_pool : [n_pages][n_kv_heads][head_dim / 8][16 slots][8]   element (page,h,c,slot,e)
+ *   v_pool : [n_pages][n_kv_heads][head_dim][16 slots]          element (page,h,d,slot)
+ * appended_len[b] is advanced only by st_kv_append.
+ * ---------------------------------------------------------------------- */
+typedef struct st_kv_cache {
+    void* k_pool;
+    void* v_pool;
+    const int32_t* page_table; /* device int32 [batch][max_pages_per_seq] */
+    int32_t* appended_len;     /* device int32 [batch] */
+    int32_t max_pages_per_seq;
+    int32_t n_pages;           /* pages in the pools (page ids must be < n_pages) */
+    int32_t page_size;         /* must be 16 */
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;             /* st_dtype; must be ST_BF16 */
+} st_kv_cache;
+
+typedef struct st_dual_cache {
+    st_kv_cache source;
+    st_kv_cache reasoning;
+} st_dual_cache;
+
+/* ------------------------------------------------------------------------
+ * st_kv_append -- append tokens to the source or the reasoning cache.
+ * Sec. 3.3 / Alg. 1: arriving input sentences are stored in the source cache in
+ * arrival order; decoded reasoning tokens are stored in the reasoning cache.
+ *
+ *   k_new, v_new : bf16 [batch, max_new, n_kv_heads, head_dim] (already rotated)
+ *   n_new        : device int32 [batch], tokens to take from each row of k_new
+ *                  (0 .. max_new), or NULL for max_new everywhere
+ *   host_len_upper_bound : the caller's bound on max_b(appended_len[b] + n_new[b]);
+ *                  more than max_pages_per_seq * 16 gives ST_ERR_CAPACITY without
+ *                  touching the device.  Tokens that would still fall outside the
+ *                  page table on the device are dropped, never written.
+ * Page-table entries for the pages written must be valid before the call.
+ * Writes only slots [appended_len, appended_len + n_new) and then advances
+ * appended_len; it may run on another stream concurrently with
+ * st_attn_decode_dual as long as the decode's src_visible_len does not reach into
+ * the range being written.
+ * ---------------------------------------------------------------------- */
+st_status st_kv_append(const st_dual_cache* caches, st_stream_kind which,
+                       const void* k_new, const void* v_new, const int32_t* n_new,
+                       int32_t max_new, int32_t batch, int32_t host_len_upper_bound,
+                       void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * st_attn_decode_dual -- one decode step over both caches.  Alg. 1: the slice of
+ * the source cache that keeps N_EOS == N_EOT + 1 and the reasoning cache are read
+ * as one merged cache.  Here nothing is copied: partial softmaxes over chunks of
+ * either cache are merged by log-sum-exp, which equals attention over the
+ * concatenation.
+ *
+ *   q, out : bf16 [batch, q_len, n_q_heads, head_dim]
+ *   lse    : fp32 [batch, q_len, n_q_heads] or NULL
+ *   src_visible_len[b] : source tokens visible to this step (the caller's snapshot,
+ *                        NOT the cache's appended_len; 0 allowed)
+ *   rsn_len[b]         : reasoning tokens including the q_len tokens being decoded
+ *                        (they are appended first); row t of q_len sees reasoning
+ *                        tokens [0, rsn_len - q_len + t]
+ *   q_len * (n_q_heads / n_kv_heads) must be <= 32.
+ *   max_src_len / max_rsn_len : host upper bounds on the two length vectors (grid size).
+ * A row that sees nothing (both lengths 0) gets out = 0, lse = -inf.  Cache slots
+ * outside the visible ranges are never used, whatever bit patterns they hold.
+ * workspace: at least st_decode_workspace_bytes(...) bytes, 256-byte aligned.
+ * ---------------------------------------------------------------------- */
+typedef struct st_dual_lens {
+    const int32_t* src_visible_len; /* device int32 [batch] */
+    const int32_t* rsn_len;         /* device int32 [batch] */
+    int32_t q_len;
+    int32_t max_src_len;
+    int32_t max_rsn_len;
+} st_dual_lens;
+
+size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                 int32_t head_dim, int32_t q_len,
+                                 int32_t max_src_len, int32_t max_rsn_len);
+
+st_status st_attn_decode_dual(void* out, float* lse, const void* q,
+                              const st_dual_cache* caches, const st_dual_lens* lens,
+                              int32_t batch, int32_t n_q_heads, float scale,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ST_H */

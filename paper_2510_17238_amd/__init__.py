@@ -1,0 +1,15 @@
+"""Streaming-constrained attention for MI355X (gfx950): thin Python binding over libst.so.
+
+Every step of the path runs in the HIP kernels of the C-ABI library; this package only
+marshals arguments (torch tensors -> device pointers, the current HIP stream).  There is
+no CPU or PyTorch fallback: importing the binding without a built library raises.
+"""
+from .binding import (  # noqa: F401
+    ST_SOURCE, ST_REASONING, ST_F32, ST_BF16, ST_BLOCK_SS, ST_BLOCK_RS, ST_BLOCK_RR,
+    ST_TILE_SKIP, ST_TILE_FULL, ST_TILE_PARTIAL, PAGE,
+    StError, Plan, KVCache, DualCache, library_path, load_library,
+    st_version, st_last_error, st_rope_apply, st_plan_workspace_bytes, st_plan_create,
+    st_attn_prefill, st_attn_prefill_ids, st_kv_append, st_decode_workspace_bytes,
+    st_attn_decode_dual, k_pool_to_logical, v_pool_to_logical, k_pool_from_logical,
+    v_pool_from_logical,
+)

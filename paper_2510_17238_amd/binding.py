@@ -1,0 +1,349 @@
+"""ctypes binding of include/st.h.  Function names and argument order follow the header."""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+ST_OK = 0
+ST_F32, ST_BF16 = 0, 1
+ST_SOURCE, ST_REASONING = 0, 1
+ST_TILE_SKIP, ST_TILE_FULL, ST_TILE_PARTIAL = 0, 1, 2
+ST_BLOCK_SS, ST_BLOCK_RS, ST_BLOCK_RR = 0, 1, 2
+PAGE = 16
+
+_STATUS_NAMES = {1: "ST_ERR_INVALID_ARG", 2: "ST_ERR_SHAPE", 3: "ST_ERR_LAYOUT", 4: "ST_ERR_CAPACITY",
+                 5: "ST_ERR_UNSUPPORTED", 6: "ST_ERR_RUNTIME"}
+
+
+class StError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+class _KVCacheStruct(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p),
+                ("appended_len", C.c_void_p), ("max_pages_per_seq", C.c_int32), ("n_pages", C.c_int32),
+                ("page_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+
+
+class _DualCacheStruct(C.Structure):
+    _fields_ = [("source", _KVCacheStruct), ("reasoning", _KVCacheStruct)]
+
+
+class _DualLensStruct(C.Structure):
+    _fields_ = [("src_visible_len", C.c_void_p), ("rsn_len", C.c_void_p), ("q_len", C.c_int32),
+                ("max_src_len", C.c_int32), ("max_rsn_len", C.c_int32)]
+
+
+_lib = None
+
+
+def library_path():
+    return os.path.join(HERE, "libst.so")
+
+
+def load_library():
+    """Load libst.so; raise if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2510_17238_amd.build` "
+                           "(or __graft_entry__.build()); the HIP library is the only implementation")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32, f64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_double, C.c_size_t
+    lib.st_last_error.restype = C.c_char_p
+    lib.st_last_error.argtypes = []
+    lib.st_version.restype = i32
+    lib.st_version.argtypes = []
+    lib.st_rope_apply.restype = i32
+    lib.st_rope_apply.argtypes = [vp, vp, vp, i64, i32, i32, f64, i32, vp]
+    lib.st_plan_workspace_bytes.restype = sz
+    lib.st_plan_workspace_bytes.argtypes = [i32, i64]
+    lib.st_plan_create.restype = i32
+    lib.st_plan_create.argtypes = [C.POINTER(vp), vp, vp, vp, vp, i32, vp, sz, i32, vp]
+    lib.st_plan_destroy.restype = None
+    lib.st_plan_destroy.argtypes = [vp]
+    lib.st_plan_tile_shape.restype = i32
+    lib.st_plan_tile_shape.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+    for name in ("st_plan_compact_index", "st_plan_visible_source", "st_plan_visible_pairs"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = [vp, vp]
+    lib.st_plan_stream_counts.restype = i32
+    lib.st_plan_stream_counts.argtypes = [vp, vp, vp]
+    lib.st_plan_tile_classes.restype = i32
+    lib.st_plan_tile_classes.argtypes = [vp, i32, i32, vp, C.POINTER(i32), C.POINTER(i32)]
+    lib.st_attn_prefill.restype = i32
+    lib.st_attn_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp]
+    lib.st_attn_prefill_ids.restype = i32
+    lib.st_attn_prefill_ids.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp]
+    lib.st_kv_append.restype = i32
+    lib.st_kv_append.argtypes = [C.POINTER(_DualCacheStruct), i32, vp, vp, vp, i32, i32, i32, vp]
+    lib.st_decode_workspace_bytes.restype = sz
+    lib.st_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
+    lib.st_attn_decode_dual.restype = i32
+    lib.st_attn_decode_dual.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
+                                        f32, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != ST_OK:
+        raise StError(status, load_library().st_last_error().decode())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return ST_F32
+    if t.dtype == torch.bfloat16:
+        return ST_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dev_i32(t, name):
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous int32 device tensor")
+    return t
+
+
+def st_version():
+    return int(load_library().st_version())
+
+
+def st_last_error():
+    return load_library().st_last_error().decode()
+
+
+# ------------------------------------------------------------------ RoPE --
+def st_rope_apply(x, positions, theta_base=1.0e6, out=None, stream=None):
+    """x[n_tokens, n_heads, head_dim] rotated by positions[n_tokens]; out defaults to in place."""
+    lib = load_library()
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 3
+    _dev_i32(positions, "positions")
+    if out is None:
+        out = x
+    assert out.shape == x.shape and out.dtype == x.dtype and out.is_contiguous()
+    n, h, d = x.shape
+    _check(lib.st_rope_apply(_ptr(out), _ptr(x), _ptr(positions), n, h, d, float(theta_base), _dtype_code(x), _stream(stream)))
+    return out
+
+
+# ------------------------------------------------------------------ plan --
+def st_plan_workspace_bytes(batch, n_tokens):
+    return int(load_library().st_plan_workspace_bytes(batch, n_tokens))
+
+
+class Plan:
+    """Owner of one st_plan handle."""
+
+    def __init__(self, handle, batch, n_tokens, cu_seqlens, keep):
+        self.handle = handle
+        self.batch = batch
+        self.n_tokens = n_tokens
+        self.cu_seqlens = cu_seqlens
+        self._keep = keep   # tensors the plan's kernels read / its workspace
+
+    def destroy(self):
+        if self.handle:
+            load_library().st_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def tile_shape(self):
+        m, n = C.c_int32(), C.c_int32()
+        _check(load_library().st_plan_tile_shape(self.handle, C.byref(m), C.byref(n)))
+        return m.value, n.value
+
+    def stream_counts(self):
+        a = np.zeros(self.batch, np.int32); b = np.zeros(self.batch, np.int32)
+        _check(load_library().st_plan_stream_counts(self.handle, a.ctypes.data, b.ctypes.data))
+        return a, b
+
+    def compact_index(self):
+        a = np.zeros(self.n_tokens, np.int32)
+        _check(load_library().st_plan_compact_index(self.handle, a.ctypes.data))
+        return a
+
+    def visible_source(self):
+        a = np.zeros(self.n_tokens, np.int32)
+        _check(load_library().st_plan_visible_source(self.handle, a.ctypes.data))
+        return a
+
+    def visible_pairs(self):
+        a = np.zeros(self.batch, np.uint64)
+        _check(load_library().st_plan_visible_pairs(self.handle, a.ctypes.data))
+        return a
+
+    def tile_classes(self, seq, block):
+        tq, tk = C.c_int32(), C.c_int32()
+        lib = load_library()
+        _check(lib.st_plan_tile_classes(self.handle, seq, block, None, C.byref(tq), C.byref(tk)))
+        out = np.zeros((tq.value, tk.value), np.uint8)
+        if out.size:
+            _check(lib.st_plan_tile_classes(self.handle, seq, block, out.ctypes.data, C.byref(tq), C.byref(tk)))
+        return out
+
+
+def st_plan_create(segment_ids, stream_ids, positions, cu_seqlens, workspace=None, validate=False, stream=None):
+    """cu_seqlens: host sequence (list / numpy) of batch + 1 offsets.  Returns a Plan."""
+    lib = load_library()
+    for t, name in ((segment_ids, "segment_ids"), (stream_ids, "stream_ids"), (positions, "positions")):
+        _dev_i32(t, name)
+    cu = np.ascontiguousarray(np.asarray(cu_seqlens, dtype=np.int32))
+    batch = len(cu) - 1
+    n_tokens = int(cu[-1]) if batch >= 0 and len(cu) else 0
+    if not (segment_ids.numel() == stream_ids.numel() == positions.numel() == n_tokens):
+        raise ValueError("metadata arrays must have cu_seqlens[-1] entries")
+    handle = C.c_void_p()
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
+    _check(lib.st_plan_create(C.byref(handle), _ptr(segment_ids), _ptr(stream_ids), _ptr(positions), cu.ctypes.data,
+                              batch, ws_ptr, ws_bytes, 1 if validate else 0, _stream(stream)))
+    return Plan(handle, batch, n_tokens, cu, (segment_ids, stream_ids, positions, workspace))
+
+
+# --------------------------------------------------------------- prefill --
+def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, stream=None):
+    """q[N, Hq, D], k, v[N, Hkv, D] -> out[N, Hq, D]; lse: fp32 [N, Hq] tensor to fill, or None."""
+    lib = load_library()
+    assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    assert q.dtype == k.dtype == v.dtype
+    n, hq, d = q.shape
+    assert k.shape == v.shape and k.shape[0] == n and k.shape[2] == d and n == plan.n_tokens
+    hkv = k.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is not None:
+        assert lse.dtype == torch.float32 and lse.shape == (n, hq) and lse.is_contiguous()
+    _check(lib.st_attn_prefill(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), plan.handle, hq, hkv, d, float(scale),
+                               _dtype_code(q), _stream(stream)))
+    return out
+
+
+def st_attn_prefill_ids(q, k, v, segment_ids, stream_ids, positions, cu_seqlens, scale=0.0, out=None, lse=None, stream=None):
+    """One-off form taking the token metadata directly (builds and frees a plan; waits)."""
+    lib = load_library()
+    cu = np.ascontiguousarray(np.asarray(cu_seqlens, dtype=np.int32))
+    n, hq, d = q.shape
+    hkv = k.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib.st_attn_prefill_ids(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), _ptr(_dev_i32(segment_ids, "segment_ids")),
+                                   _ptr(_dev_i32(stream_ids, "stream_ids")), _ptr(_dev_i32(positions, "positions")),
+                                   cu.ctypes.data, len(cu) - 1, hq, hkv, d, float(scale), _dtype_code(q), _stream(stream)))
+    return out
+
+
+# ------------------------------------------------------------ KV caches --
+class KVCache:
+    """Caller-owned paged cache: pools, page table and length vector are torch tensors."""
+
+    def __init__(self, n_pages, batch, max_pages_per_seq, n_kv_heads, head_dim, page_table, device="cuda", fill=None):
+        self.n_pages, self.batch, self.max_pages_per_seq = n_pages, batch, max_pages_per_seq
+        self.n_kv_heads, self.head_dim = n_kv_heads, head_dim
+        shape_k = (n_pages, n_kv_heads, head_dim // 8, PAGE, 8)
+        shape_v = (n_pages, n_kv_heads, head_dim, PAGE)
+        if fill is None:
+            self.k_pool = torch.empty(shape_k, dtype=torch.bfloat16, device=device)
+            self.v_pool = torch.empty(shape_v, dtype=torch.bfloat16, device=device)
+        else:
+            self.k_pool = torch.full(shape_k, fill, dtype=torch.bfloat16, device=device)
+            self.v_pool = torch.full(shape_v, fill, dtype=torch.bfloat16, device=device)
+        self.page_table = _dev_i32(page_table, "page_table")
+        assert tuple(page_table.shape) == (batch, max_pages_per_seq)
+        self.appended_len = torch.zeros(batch, dtype=torch.int32, device=device)
+
+    def struct(self):
+        return _KVCacheStruct(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.page_table.data_ptr(),
+                              self.appended_len.data_ptr(), self.max_pages_per_seq, self.n_pages, PAGE,
+                              self.n_kv_heads, self.head_dim, ST_BF16)
+
+
+class DualCache:
+    def __init__(self, source, reasoning):
+        self.source, self.reasoning = source, reasoning
+
+    def struct(self):
+        return _DualCacheStruct(self.source.struct(), self.reasoning.struct())
+
+
+def k_pool_to_logical(k_pool):
+    """[n_pages, Hkv, D/8, 16, 8] -> [n_pages, 16, Hkv, D] (a pure permutation of the pool)."""
+    p, h, c, s, e = k_pool.shape
+    return k_pool.permute(0, 3, 1, 2, 4).reshape(p, s, h, c * e)
+
+
+def v_pool_to_logical(v_pool):
+    """[n_pages, Hkv, D, 16] -> [n_pages, 16, Hkv, D]."""
+    return v_pool.permute(0, 3, 1, 2)
+
+
+def k_pool_from_logical(x):
+    """[n_pages, 16, Hkv, D] -> pool layout [n_pages, Hkv, D/8, 16, 8]."""
+    p, s, h, d = x.shape
+    return x.reshape(p, s, h, d // 8, 8).permute(0, 2, 3, 1, 4).contiguous()
+
+
+def v_pool_from_logical(x):
+    return x.permute(0, 2, 3, 1).contiguous()
+
+
+def st_kv_append(caches, which, k_new, v_new, n_new=None, host_len_upper_bound=None, stream=None):
+    """k_new, v_new: bf16 [batch, max_new, Hkv, D]; n_new: int32 [batch] device tensor or None."""
+    lib = load_library()
+    assert k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    batch, max_new = k_new.shape[0], k_new.shape[1]
+    cache = caches.source if which == ST_SOURCE else caches.reasoning
+    if host_len_upper_bound is None:
+        host_len_upper_bound = cache.max_pages_per_seq * PAGE
+    if n_new is not None:
+        _dev_i32(n_new, "n_new")
+    st = caches.struct()
+    _check(lib.st_kv_append(C.byref(st), which, _ptr(k_new), _ptr(v_new), _ptr(n_new), max_new, batch,
+                            int(host_len_upper_bound), _stream(stream)))
+
+
+def st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len):
+    return int(load_library().st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len))
+
+
+def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, scale=0.0, out=None, lse=None,
+                        workspace=None, stream=None):
+    """q[batch, q_len, Hq, D] bf16 -> out of the same shape; lengths are int32 device tensors."""
+    lib = load_library()
+    assert q.is_cuda and q.is_contiguous() and q.dtype == torch.bfloat16 and q.dim() == 4
+    batch, q_len, hq, d = q.shape
+    _dev_i32(src_visible_len, "src_visible_len"); _dev_i32(rsn_len, "rsn_len")
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = st_decode_workspace_bytes(batch, hq, caches.source.n_kv_heads, d, q_len, max_src_len, max_rsn_len)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    st = caches.struct()
+    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
+    _check(lib.st_attn_decode_dual(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out

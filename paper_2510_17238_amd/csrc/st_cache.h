@@ -1,0 +1,20 @@
+// Kernel-side view of one paged KV cache (internal).
+#pragma once
+#include "st_internal.h"
+
+namespace st {
+
+struct CacheView {
+    uint16_t* k_pool;            // [n_pages][Hkv][D/8][16][8] bf16 bits
+    uint16_t* v_pool;            // [n_pages][Hkv][D][16]
+    const int32_t* page_table;   // [batch][max_pages]
+    int32_t* appended_len;       // [batch]
+    int32_t max_pages;
+    int32_t n_pages;
+    int32_t n_kv_heads;
+};
+
+st_status check_cache(const st_kv_cache& c, const char* who, const char* which);
+CacheView cache_view(const st_kv_cache& c);
+
+}  // namespace st

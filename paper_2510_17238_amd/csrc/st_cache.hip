@@ -1,0 +1,142 @@
+// Paged append to the source / reasoning KV cache (Sec. 3.3 "Parallel KV caches";
+// Alg. 1: arriving input sentences go to the source cache, decoded tokens to the
+// reasoning cache).
+//
+// Pure data movement, HBM-bound.  One workgroup handles the slots of ONE page of ONE
+// KV head that the append touches, and rewrites the rows from token-major
+// [token][head][d] into the pool layouts the decode kernel reads with contiguous
+// 16-byte loads:
+//   K: [page][head][d / 8][slot][8]      V: [page][head][d][slot]
+// The new length is written by a second, tiny kernel so that every workgroup of the
+// first one sees the old length.
+#include "st_cache.h"
+
+namespace st {
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_kernel(CacheView cache, const uint16_t* __restrict__ k_new,
+                                                        const uint16_t* __restrict__ v_new,
+                                                        const int32_t* __restrict__ n_new, int max_new,
+                                                        int pages_per_seq_touched) {
+    constexpr int KCH = D / 8;
+    __shared__ uint16_t s_v[kPage][D + 2];
+    const int pi = blockIdx.x % pages_per_seq_touched;
+    const int h = (blockIdx.x / pages_per_seq_touched) % cache.n_kv_heads;
+    const int b = blockIdx.x / (pages_per_seq_touched * cache.n_kv_heads);
+    const int capacity = cache.max_pages * kPage;
+    const int start = min(max(cache.appended_len[b], 0), capacity);
+    int n = n_new ? min(max(n_new[b], 0), max_new) : max_new;
+    n = min(n, capacity - start);                       // tokens past the page table are dropped
+    const int page = start / kPage + pi;
+    const int lo = max(start, page * kPage), hi = min(start + n, (page + 1) * kPage);
+    if (lo >= hi) return;
+    const int id = cache.page_table[int64_t(b) * cache.max_pages + page];
+    if (id < 0 || id >= cache.n_pages) return;          // never write outside the pool
+    const int slot_lo = lo - page * kPage, cnt = hi - lo;
+    const int64_t row0 = int64_t(b) * max_new + (lo - start);        // first source row in k_new / v_new
+    const int64_t row_stride = int64_t(cache.n_kv_heads) * D;
+    const int tid = threadIdx.x;
+
+    // K: 16-byte pieces, consecutive threads -> consecutive slots of one d-chunk
+    for (int w = tid; w < KCH * kPage; w += 256) {
+        const int c8 = w / kPage, s = w % kPage;
+        if (s < cnt) {
+            const u32x4 val = *reinterpret_cast<const u32x4*>(k_new + (row0 + s) * row_stride + h * D + c8 * 8);
+            uint16_t* dst = cache.k_pool + ((int64_t(id) * cache.n_kv_heads + h) * KCH + c8) * (kPage * 8) + (slot_lo + s) * 8;
+            *reinterpret_cast<u32x4*>(dst) = val;
+        }
+    }
+    // V: transpose through LDS
+    for (int w = tid; w < kPage * D; w += 256) {
+        const int s = w / D, d = w % D;
+        if (s < cnt) s_v[s][d] = v_new[(row0 + s) * row_stride + h * D + d];
+    }
+    __syncthreads();
+    uint16_t* vdst = cache.v_pool + (int64_t(id) * cache.n_kv_heads + h) * (D * kPage);
+    if (cnt == kPage) {
+        // whole page: every d row is 32 contiguous bytes
+        for (int w = tid; w < D * 2; w += 256) {
+            const int d = w >> 1, half = w & 1;
+            u32x4 val;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                val[e] = uint32_t(s_v[half * 8 + 2 * e][d]) | (uint32_t(s_v[half * 8 + 2 * e + 1][d]) << 16);
+            *reinterpret_cast<u32x4*>(vdst + d * kPage + half * 8) = val;
+        }
+    } else {
+        for (int w = tid; w < D * kPage; w += 256) {
+            const int d = w / kPage, s = w % kPage;
+            if (s < cnt) vdst[d * kPage + slot_lo + s] = s_v[s][d];
+        }
+    }
+}
+
+__global__ void kv_append_bump_kernel(int32_t* __restrict__ appended_len, const int32_t* __restrict__ n_new,
+                                      int max_new, int batch, int capacity) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    const int start = min(max(appended_len[b], 0), capacity);
+    int n = n_new ? min(max(n_new[b], 0), max_new) : max_new;
+    n = min(n, capacity - start);
+    appended_len[b] = start + n;
+}
+
+st_status check_cache(const st_kv_cache& c, const char* who, const char* which) {
+    if (!c.k_pool || !c.v_pool || !c.page_table) return fail(ST_ERR_INVALID_ARG, "%s: %s cache has a null pointer", who, which);
+    if (!aligned16(c.k_pool) || !aligned16(c.v_pool)) return fail(ST_ERR_INVALID_ARG, "%s: %s pools must be 16-byte aligned", who, which);
+    if (c.page_size != kPage) return fail(ST_ERR_UNSUPPORTED, "%s: page_size %d (must be %d)", who, c.page_size, kPage);
+    if (c.dtype != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "%s: cache dtype %d (bf16 only)", who, c.dtype);
+    if (c.head_dim != 64 && c.head_dim != 128) return fail(ST_ERR_UNSUPPORTED, "%s: head_dim %d (64 or 128)", who, c.head_dim);
+    if (c.n_kv_heads <= 0 || c.max_pages_per_seq <= 0 || c.n_pages <= 0) return fail(ST_ERR_INVALID_ARG, "%s: %s cache has non-positive sizes", who, which);
+    return ST_OK;
+}
+
+CacheView cache_view(const st_kv_cache& c) {
+    CacheView v;
+    v.k_pool = static_cast<uint16_t*>(c.k_pool);
+    v.v_pool = static_cast<uint16_t*>(c.v_pool);
+    v.page_table = c.page_table;
+    v.appended_len = c.appended_len;
+    v.max_pages = c.max_pages_per_seq;
+    v.n_pages = c.n_pages;
+    v.n_kv_heads = c.n_kv_heads;
+    return v;
+}
+
+}  // namespace st
+
+using namespace st;
+
+extern "C" st_status st_kv_append(const st_dual_cache* caches, st_stream_kind which, const void* k_new,
+                                  const void* v_new, const int32_t* n_new, int32_t max_new, int32_t batch,
+                                  int32_t host_len_upper_bound, void* hip_stream) {
+    if (!caches || !k_new || !v_new) return fail(ST_ERR_INVALID_ARG, "st_kv_append: null pointer");
+    if (which != ST_SOURCE && which != ST_REASONING) return fail(ST_ERR_INVALID_ARG, "st_kv_append: which = %d", int(which));
+    const st_kv_cache& c = which == ST_SOURCE ? caches->source : caches->reasoning;
+    st_status r = check_cache(c, "st_kv_append", which == ST_SOURCE ? "source" : "reasoning");
+    if (r != ST_OK) return r;
+    if (!c.appended_len) return fail(ST_ERR_INVALID_ARG, "st_kv_append: appended_len is null");
+    if (!aligned16(k_new) || !aligned16(v_new)) return fail(ST_ERR_INVALID_ARG, "st_kv_append: k_new / v_new must be 16-byte aligned");
+    if (batch <= 0 || max_new < 0) return fail(ST_ERR_INVALID_ARG, "st_kv_append: bad sizes");
+    const int64_t capacity = int64_t(c.max_pages_per_seq) * kPage;
+    if (host_len_upper_bound < 0 || host_len_upper_bound > capacity)
+        return fail(ST_ERR_CAPACITY, "st_kv_append: length bound %d exceeds the page table (%lld tokens per sequence)",
+                    host_len_upper_bound, (long long)capacity);
+    if (max_new == 0) return ST_OK;
+    const int touched = (max_new + kPage - 1) / kPage + 1;
+    const int64_t blocks = int64_t(batch) * c.n_kv_heads * touched;
+    if (blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_kv_append: grid too large");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const CacheView cv = cache_view(c);
+    if (c.head_dim == 64)
+        hipLaunchKernelGGL((kv_append_kernel<64>), dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new,
+                           (const uint16_t*)v_new, n_new, max_new, touched);
+    else
+        hipLaunchKernelGGL((kv_append_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new,
+                           (const uint16_t*)v_new, n_new, max_new, touched);
+    ST_LAUNCH_CHECK("kv_append_kernel");
+    hipLaunchKernelGGL(kv_append_bump_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, c.appended_len, n_new, max_new,
+                       batch, int(capacity));
+    ST_LAUNCH_CHECK("kv_append_bump_kernel");
+    return ST_OK;
+}

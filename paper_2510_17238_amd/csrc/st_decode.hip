@@ -1,0 +1,319 @@
+// Dual-cache decode (Sec. 3.3 "Parallel KV caches"; Alg. 1: merge the visible source
+// slice with the reasoning cache, then decode).
+//
+// Nothing is merged in memory.  The two caches are cut into chunks of 256 tokens; one
+// WAVE takes one (sequence, KV head, chunk), streams that chunk's K and V pages from HBM
+// exactly once for all query heads of the group, and emits an un-normalised partial
+// (o, m, l).  A second kernel merges all partials of BOTH caches per (sequence, query
+// row, head) by log-sum-exp -- identical to a softmax over the concatenated cache.
+//
+// HBM-bound: 4 * D bytes per cached token and KV head, 2 * G * D useful flops for it.
+// The arithmetic rides on the matrix cores only to keep the vector ALUs out of the
+// way: S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, where the 32
+// columns are the (up to 32) query rows q_len * G.  The pool layouts make every operand
+// a contiguous 16-byte load straight from global memory into MFMA registers:
+//   K [page][head][d/8][slot][8] : lane (m, hg) reads slot m of d-chunk 2 j + hg
+//   V [page][head][d][slot]      : lane (n, hg) reads slots 8 hg .. 8 hg + 7 of row d
+#include "st_cache.h"
+
+namespace st {
+
+constexpr int kChunk = 256;                 // tokens per work unit
+constexpr int kStepsPerChunk = kChunk / 32; // 32 tokens (two pages) per MFMA step
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+struct DecodeArgs {
+    CacheView src, rsn;
+    const int32_t* src_len;
+    const int32_t* rsn_len;
+    const uint16_t* q;
+    float* part_o;     // [B][Hkv][nc][rows][D]
+    float* part_ml;    // [B][Hkv][nc][rows][2]
+    int batch, q_len, n_q_heads, n_kv_heads, group, rows;
+    int ncs, ncr;      // chunk slots per (sequence, head) for the two caches
+    float scale_log2;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
+    constexpr int KS = D / 16, DB = D / 32, KCH = D / 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nc = a.ncs + a.ncr;
+    const int64_t unit = int64_t(blockIdx.x) * 4 + wave;
+    const int c = int(unit % nc);
+    const int64_t bh = unit / nc;
+    const int h = int(bh % a.n_kv_heads);
+    const int b = int(bh / a.n_kv_heads);
+    if (b >= a.batch) return;
+    const bool is_src = c < a.ncs;
+    const CacheView& cv = is_src ? a.src : a.rsn;
+    const int cc = is_src ? c : c - a.ncs;
+    const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
+    const int tok0 = cc * kChunk;
+    if (tok0 >= len) return;
+    const int tok_end = min(len, tok0 + kChunk);
+
+    const int n = lane & 31, hg = lane >> 5;
+    const int t_row = n / a.group;
+    const bool valid_row = n < a.rows;
+    const int hq = h * a.group + n % a.group;
+    // visible reasoning tokens of query row t: [0, len - q_len + t]; the source slice is seen whole
+    const int limit = !valid_row ? 0 : (is_src ? len : max(len - a.q_len + t_row + 1, 0));
+
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (valid_row)
+            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
+        qf[j] = __builtin_bit_cast(bf16x8, z);
+    }
+    f32x16 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int32_t* table = cv.page_table + int64_t(b) * cv.max_pages;
+    const int64_t head_k = int64_t(h) * KCH * (kPage * 8);
+    const int64_t page_k = int64_t(cv.n_kv_heads) * KCH * (kPage * 8);
+    const int64_t head_v = int64_t(h) * D * kPage;
+    const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
+    const int k_slot = swap23(n & 15);
+
+    for (int tok = tok0; tok < tok_end; tok += 32) {
+        // ---- K operand: lane (m = n, hg) -> page tok/16 + m/16, slot swap23(m % 16) ----
+        const int pg_k = tok / kPage + (n >> 4);
+        int id_k = -1;
+        if (pg_k * kPage < tok_end) id_k = table[pg_k];
+        const bool ok_k = id_k >= 0 && id_k < cv.n_pages;
+        f32x16 s_acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_acc[i] = 0.f;
+        {
+            const uint16_t* kp = cv.k_pool + int64_t(ok_k ? id_k : 0) * page_k + head_k + k_slot * 8;
+            bf16x8 ak[KS];
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                u32x4 z = {0u, 0u, 0u, 0u};
+                if (ok_k) z = *reinterpret_cast<const u32x4*>(kp + (2 * j + hg) * (kPage * 8));
+                ak[j] = __builtin_bit_cast(bf16x8, z);
+            }
+#pragma unroll
+            for (int j = 0; j < KS; ++j) s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[j], qf[j], s_acc, 0, 0, 0);
+        }
+        // ---- V operand: page t, lane (d = 32 db + n, hg) -> slots 8 hg .. 8 hg + 7 ----
+        bf16x8 av[2][DB];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int pg_v = tok / kPage + t;
+            int id_v = -1;
+            if (pg_v * kPage < tok_end) id_v = table[pg_v];
+            const bool ok_v = id_v >= 0 && id_v < cv.n_pages;
+            const uint16_t* vp = cv.v_pool + int64_t(ok_v ? id_v : 0) * page_v + head_v + n * kPage + 8 * hg;
+            const int first = tok + 16 * t + 8 * hg;     // token held in element 0
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                u32x4 z = {0u, 0u, 0u, 0u};
+                if (ok_v) z = *reinterpret_cast<const u32x4*>(vp + db * 32 * kPage);
+                if (first + 8 > len) {
+                    // slots past the visible length may hold anything: select them away
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t keep_lo = first + 2 * e < len ? 0x0000ffffu : 0u;
+                        const uint32_t keep_hi = first + 2 * e + 1 < len ? 0xffff0000u : 0u;
+                        z[e] &= keep_lo | keep_hi;
+                    }
+                }
+                av[t][db] = __builtin_bit_cast(bf16x8, z);
+            }
+        }
+        // ---- mask + online softmax; register i <-> token tok + 16 (i/8) + 8 hg + i%8 ----
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int kv = tok + 16 * (i >> 3) + 8 * hg + (i & 7);
+            s_acc[i] = kv < limit ? s_acc[i] : -INFINITY;
+            mx = fmaxf(mx, s_acc[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 pb[2];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[i], a.scale_log2, -m_use));
+            psum += p;
+            pb[i >> 3][i & 7] = (__bf16)p;
+        }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[t][db], pb[t], o_acc[db], 0, 0, 0);
+        }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (!valid_row) return;
+    const int64_t slot = ((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n;
+    float* po = a.part_o + slot * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            f32x4 o4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o4[e] = o_acc[db][4 * q4 + e];
+            *reinterpret_cast<f32x4*>(po + 32 * db + 8 * q4 + 4 * hg) = o4;
+        }
+    if (hg == 0) {
+        a.part_ml[slot * 2] = m_run;
+        a.part_ml[slot * 2 + 1] = l_tot;
+    }
+}
+
+// One wave per (sequence, query row, query head): log-sum-exp merge of the partials of
+// both caches, in a fixed order (run-to-run identical results).
+template <int D>
+__global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a, uint16_t* __restrict__ out,
+                                                             float* __restrict__ lse) {
+    constexpr int PER = D / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t unit = int64_t(blockIdx.x) * 4 + wave;
+    const int hq = int(unit % a.n_q_heads);
+    const int t = int((unit / a.n_q_heads) % a.q_len);
+    const int b = int(unit / (int64_t(a.n_q_heads) * a.q_len));
+    if (b >= a.batch) return;
+    const int h = hq / a.group, n = t * a.group + hq % a.group;
+    const int nc = a.ncs + a.ncr;
+    const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
+    const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+    const int n_s = min((len_s + kChunk - 1) / kChunk, a.ncs), n_r = min((len_r + kChunk - 1) / kChunk, a.ncr);
+    const int64_t base = (int64_t(b) * a.n_kv_heads + h) * nc;
+
+    float mx = -INFINITY;
+    for (int i = lane; i < n_s + n_r; i += 64) {
+        const int c = i < n_s ? i : a.ncs + (i - n_s);
+        mx = fmaxf(mx, a.part_ml[((base + c) * a.rows + n) * 2]);
+    }
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+
+    float acc[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+    float den = 0.f;
+    if (mx != -INFINITY) {
+        for (int i = 0; i < n_s + n_r; ++i) {
+            const int c = i < n_s ? i : a.ncs + (i - n_s);
+            const int64_t slot = (base + c) * a.rows + n;
+            const float w = __builtin_amdgcn_exp2f(a.part_ml[slot * 2] - mx);
+            den = fmaf(w, a.part_ml[slot * 2 + 1], den);
+            const float* po = a.part_o + slot * D + lane * PER;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) acc[e] = fmaf(w, po[e], acc[e]);
+        }
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    uint16_t* op = out + ((int64_t(b) * a.q_len + t) * a.n_q_heads + hq) * D + lane * PER;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) op[e] = f32_to_bf16_bits(acc[e] * inv);
+    if (lse && lane == 0)
+        lse[(int64_t(b) * a.q_len + t) * a.n_q_heads + hq] = den > 0.f ? (mx + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+static inline int chunks_of(int len) { return (len + kChunk - 1) / kChunk; }
+
+}  // namespace st
+
+using namespace st;
+
+extern "C" size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                            int32_t q_len, int32_t max_src_len, int32_t max_rsn_len) {
+    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || q_len <= 0 || head_dim <= 0 || max_src_len < 0 || max_rsn_len < 0)
+        return 0;
+    const size_t nc = size_t(chunks_of(max_src_len)) + size_t(chunks_of(max_rsn_len));
+    const size_t rows = size_t(q_len) * (n_q_heads / n_kv_heads);
+    const size_t slots = size_t(batch) * n_kv_heads * nc * rows;
+    return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
+}
+
+extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                         const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out || !q || !caches || !lens) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null pointer");
+    if (!lens->src_visible_len || !lens->rsn_len) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null length vector");
+    if (!aligned16(out) || !aligned16(q)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: q / out must be 16-byte aligned");
+    st_status r = check_cache(caches->source, "st_attn_decode_dual", "source");
+    if (r != ST_OK) return r;
+    r = check_cache(caches->reasoning, "st_attn_decode_dual", "reasoning");
+    if (r != ST_OK) return r;
+    const st_kv_cache& cs = caches->source;
+    const st_kv_cache& cr = caches->reasoning;
+    if (cs.n_kv_heads != cr.n_kv_heads || cs.head_dim != cr.head_dim)
+        return fail(ST_ERR_SHAPE, "st_attn_decode_dual: the two caches differ in head geometry");
+    const int hkv = cs.n_kv_heads, d = cs.head_dim;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % hkv != 0)
+        return fail(ST_ERR_SHAPE, "st_attn_decode_dual: n_q_heads %d must be a positive multiple of n_kv_heads %d", n_q_heads, hkv);
+    const int group = n_q_heads / hkv;
+    if (lens->q_len <= 0 || lens->q_len * group > 32)
+        return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual: q_len %d x group %d must be in 1..32", lens->q_len, group);
+    if (lens->max_src_len < 0 || lens->max_rsn_len < 0) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: negative length bound");
+    if (int64_t(lens->max_src_len) > int64_t(cs.max_pages_per_seq) * kPage || int64_t(lens->max_rsn_len) > int64_t(cr.max_pages_per_seq) * kPage)
+        return fail(ST_ERR_CAPACITY, "st_attn_decode_dual: length bound exceeds the page table");
+    const size_t need = st_decode_workspace_bytes(batch, n_q_heads, hkv, d, lens->q_len, lens->max_src_len, lens->max_rsn_len);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: workspace must be non-null and 256-byte aligned");
+    if (workspace_bytes < need) return fail(ST_ERR_CAPACITY, "st_attn_decode_dual: workspace has %zu bytes, needs %zu", workspace_bytes, need);
+    if (scale <= 0.f) scale = 1.f / sqrtf(float(d));
+
+    DecodeArgs a;
+    a.src = cache_view(cs);
+    a.rsn = cache_view(cr);
+    a.src_len = lens->src_visible_len;
+    a.rsn_len = lens->rsn_len;
+    a.q = static_cast<const uint16_t*>(q);
+    a.batch = batch;
+    a.q_len = lens->q_len;
+    a.n_q_heads = n_q_heads;
+    a.n_kv_heads = hkv;
+    a.group = group;
+    a.rows = lens->q_len * group;
+    a.ncs = chunks_of(lens->max_src_len);
+    a.ncr = chunks_of(lens->max_rsn_len);
+    a.scale_log2 = scale * kLog2e;
+    const size_t slots = size_t(batch) * hkv * size_t(a.ncs + a.ncr) * a.rows;
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int64_t units = int64_t(batch) * hkv * (a.ncs + a.ncr);
+    const int64_t out_units = int64_t(batch) * a.q_len * n_q_heads;
+    if (units / 4 + 1 > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
+    if (units > 0) {
+        if (d == 64)
+            hipLaunchKernelGGL((decode_split_kernel<64>), dim3((unsigned)((units + 3) / 4)), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((decode_split_kernel<128>), dim3((unsigned)((units + 3) / 4)), dim3(256), 0, s, a);
+        ST_LAUNCH_CHECK("decode_split_kernel");
+    }
+    if (d == 64)
+        hipLaunchKernelGGL((decode_combine_kernel<64>), dim3((unsigned)((out_units + 3) / 4)), dim3(256), 0, s, a,
+                           static_cast<uint16_t*>(out), lse);
+    else
+        hipLaunchKernelGGL((decode_combine_kernel<128>), dim3((unsigned)((out_units + 3) / 4)), dim3(256), 0, s, a,
+                           static_cast<uint16_t*>(out), lse);
+    ST_LAUNCH_CHECK("decode_combine_kernel");
+    return ST_OK;
+}

@@ -1,0 +1,49 @@
+// Device-resident segment tables of one packed batch (internal view of st_plan).
+#pragma once
+#include <vector>
+
+#include "st_internal.h"
+
+namespace st {
+
+// One query tile of one stream of one sequence, in stream-compact coordinates.
+// Block A is the causal block over the row's own stream (SS for source rows, RR
+// for reasoning rows); block B is the rectangular source prefix of reasoning rows
+// (RS) and is empty for source rows.  Key tiles [0, full) of a block need no mask,
+// [full, total) are compared element-wise, the rest is never visited.
+struct WorkItem {
+    int32_t seq;
+    int32_t kind;     // ST_SOURCE / ST_REASONING
+    int32_t row0;     // first row, relative to the start of the row's stream
+    int32_t n_rows;   // 0 marks an unused slot
+    int32_t a_full, a_total;
+    int32_t b_full, b_total;
+};
+
+struct PlanView {  // what kernels need
+    const int32_t* cu;       // [B+1] token offsets
+    const int32_t* n_src;    // [B]
+    const int32_t* perm;     // [N] compact row -> token index
+    const int32_t* vis;      // [N] visible source count per compact row
+    const WorkItem* items;   // [m_max]
+    const int32_t* order;    // [m_max] longest-first permutation of item slots
+    int32_t m_max;
+};
+
+}  // namespace st
+
+struct st_plan {
+    int32_t batch = 0;
+    int64_t n_tokens = 0;
+    int32_t m_max = 0;
+    std::vector<int32_t> cu_host, slot_base_host;
+    void* ws = nullptr;
+    bool owns_ws = false;
+    hipStream_t stream = nullptr;
+    int32_t *cu = nullptr, *slot_base = nullptr, *n_src = nullptr, *n_rsn = nullptr;
+    int32_t *perm = nullptr, *seg_c = nullptr, *vis = nullptr, *order = nullptr, *cost = nullptr, *flag = nullptr;
+    unsigned long long* pairs = nullptr;
+    st::WorkItem* items = nullptr;
+
+    st::PlanView view() const { return st::PlanView{cu, n_src, perm, vis, items, order, m_max}; }
+};

@@ -1,0 +1,406 @@
+// Segment-table builder: turns per-token (stream, segment, position) ids into the
+// tables that replace the dense additive mask of Eq. 2 (Sec. 3.2; Appendix E.1).
+//
+// Attention is indifferent to the order of keys, and the streaming mask is a pure
+// function of the ids, so everything is expressed in "grouped stream-compact
+// order": per sequence, the source tokens by position, then the reasoning tokens
+// by position -- the paper's own training layout.  There the mask is two causal
+// triangles (source x source, reasoning x reasoning) plus a staircase rectangle
+// (reasoning rows x a prefix of the source stream), and a reasoning row needs just
+// one number: how many source tokens it sees.
+//
+// All tables are built by four small integer kernels, O(N) work, no host round trip.
+#include <new>
+
+#include "st_plan.h"
+
+namespace st {
+
+static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+static int32_t m_max_bound(int32_t batch, int64_t n_tokens) { return int32_t(n_tokens / kTileM) + 2 * batch; }
+
+struct WsLayout {
+    size_t cu, slot_base, n_src, n_rsn, pairs, flag, perm, seg_c, vis, order, cost, items, total;
+};
+
+static WsLayout ws_layout(int32_t batch, int64_t n_tokens) {
+    WsLayout L;
+    const size_t m = size_t(m_max_bound(batch, n_tokens));
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+    L.cu = take(sizeof(int32_t) * (batch + 1));
+    L.slot_base = take(sizeof(int32_t) * (batch + 1));
+    L.n_src = take(sizeof(int32_t) * batch);
+    L.n_rsn = take(sizeof(int32_t) * batch);
+    L.pairs = take(sizeof(unsigned long long) * batch);
+    L.flag = take(sizeof(int32_t));
+    L.perm = take(sizeof(int32_t) * n_tokens);
+    L.seg_c = take(sizeof(int32_t) * n_tokens);
+    L.vis = take(sizeof(int32_t) * n_tokens);
+    L.order = take(sizeof(int32_t) * m);
+    L.cost = take(sizeof(int32_t) * m);
+    L.items = take(sizeof(WorkItem) * m);
+    L.total = off;
+    return L;
+}
+
+// ---- kernel 0: clear the validation flag (a fill kernel, so that the whole
+// build can be recorded into a HIP graph) --------------------------------------
+__global__ void plan_clear_kernel(int32_t* flag) {
+    if (threadIdx.x == 0) *flag = 0;
+}
+
+// ---- kernel 1: per sequence, rank every token inside its stream ------------
+// One workgroup per sequence.  Writes perm / seg_c in grouped compact order and
+// the two stream sizes; clears the pair counter.
+__global__ __launch_bounds__(256) void plan_scan_kernel(const int32_t* __restrict__ stream_ids,
+                                                        const int32_t* __restrict__ segment_ids,
+                                                        const int32_t* __restrict__ cu,
+                                                        int32_t* __restrict__ n_src, int32_t* __restrict__ n_rsn,
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ seg_c,
+                                                        unsigned long long* __restrict__ pairs,
+                                                        int32_t* __restrict__ flag) {
+    __shared__ int s_wave[4];
+    __shared__ int s_total;
+    const int b = blockIdx.x;
+    const int t0 = cu[b], t1 = cu[b + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    // pass 1: number of source tokens
+    int cnt = 0;
+    for (int t = t0 + threadIdx.x; t < t1; t += 256) {
+        const int s = stream_ids[t];
+        if (s != ST_SOURCE && s != ST_REASONING) atomicOr(flag, 1);
+        cnt += (s == ST_SOURCE);
+    }
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    if (lane == 0) s_wave[wave] = cnt;
+    __syncthreads();
+    const int S = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        n_src[b] = S;
+        n_rsn[b] = (t1 - t0) - S;
+        pairs[b] = 0ull;
+        s_total = 0;
+    }
+    __syncthreads();
+
+    // pass 2: running rank of source tokens; reasoning rank = index - source rank
+    for (int base = t0; base < t1; base += 256) {
+        const int t = base + threadIdx.x;
+        const bool in = t < t1;
+        const bool is_src = in && stream_ids[t] == ST_SOURCE;
+        const unsigned long long mask = __ballot(is_src);
+        const int before_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) s_wave[wave] = __popcll(mask);
+        __syncthreads();
+        int before = s_total;
+        for (int w = 0; w < wave; ++w) before += s_wave[w];
+        const int src_rank = before + before_in_wave;          // sources strictly before t
+        if (in) {
+            const int r = is_src ? src_rank : S + ((t - t0) - src_rank);
+            perm[t0 + r] = t;
+            seg_c[t0 + r] = segment_ids[t];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) s_total += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ int find_seq(const int32_t* cu, int batch, int c) {
+    int lo = 0, hi = batch;  // largest b with cu[b] <= c
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= c) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ---- kernel 2: visible source count per compact row, pair counts, validation --
+__global__ __launch_bounds__(256) void plan_vis_kernel(const int32_t* __restrict__ cu, int batch, int n_tokens,
+                                                       const int32_t* __restrict__ n_src,
+                                                       const int32_t* __restrict__ seg_c,
+                                                       const int32_t* __restrict__ perm,
+                                                       const int32_t* __restrict__ positions,
+                                                       int32_t* __restrict__ vis,
+                                                       unsigned long long* __restrict__ pairs,
+                                                       int32_t* __restrict__ flag, int validate) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= n_tokens) return;
+    const int b = find_seq(cu, batch, c);
+    const int t0 = cu[b], S = n_src[b];
+    const int r = c - t0;
+    int v;
+    unsigned long long mine;
+    if (r < S) {
+        v = r + 1;
+        mine = (unsigned long long)(r + 1);
+    } else {
+        const int g = seg_c[c];
+        int lo = 0, hi = S;  // first source index whose segment id is > g
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (seg_c[t0 + mid] <= g) lo = mid + 1; else hi = mid;
+        }
+        v = lo;
+        mine = (unsigned long long)v + (unsigned long long)(r - S + 1);
+    }
+    vis[c] = v;
+    atomicAdd(&pairs[b], mine);
+    if (validate) {
+        // neighbours inside one stream: positions strictly increase, segment ids do not decrease
+        const int n = cu[b + 1] - t0;
+        const bool has_next = (r + 1 < n) && ((r < S) == (r + 1 < S));
+        if (has_next) {
+            const int p0 = positions[perm[c]], p1 = positions[perm[c + 1]];
+            if (!(p0 < p1) || seg_c[c] > seg_c[c + 1]) atomicOr(flag, 2);
+        }
+        if (positions[perm[c]] < 0 || seg_c[c] < 0) atomicOr(flag, 4);
+    }
+}
+
+// ---- kernel 3: one work item per query tile --------------------------------
+__device__ __forceinline__ int full_tiles(int limit, int n_cols) {
+    // key tiles whose in-range columns are all < limit
+    return n_cols <= limit ? (n_cols + kTileN - 1) / kTileN : limit / kTileN;
+}
+
+__global__ __launch_bounds__(256) void plan_items_kernel(const int32_t* __restrict__ cu,
+                                                         const int32_t* __restrict__ slot_base, int batch,
+                                                         int m_max, const int32_t* __restrict__ n_src,
+                                                         const int32_t* __restrict__ n_rsn,
+                                                         const int32_t* __restrict__ vis,
+                                                         WorkItem* __restrict__ items, int32_t* __restrict__ cost) {
+    const int slot = blockIdx.x * 256 + threadIdx.x;
+    if (slot >= m_max) return;
+    WorkItem it = {0, 0, 0, 0, 0, 0, 0, 0};
+    int c = 0;
+    if (slot < slot_base[batch]) {
+        const int b = find_seq(slot_base, batch, slot);
+        const int local = slot - slot_base[b];
+        const int S = n_src[b], R = n_rsn[b];
+        const int ts = (S + kTileM - 1) / kTileM, tr = (R + kTileM - 1) / kTileM;
+        if (local < ts + tr) {
+            const bool src = local < ts;
+            const int n_stream = src ? S : R;
+            it.seq = b;
+            it.kind = src ? ST_SOURCE : ST_REASONING;
+            it.row0 = (src ? local : local - ts) * kTileM;
+            it.n_rows = min(kTileM, n_stream - it.row0);
+            const int last = it.row0 + it.n_rows - 1;
+            it.a_total = last / kTileN + 1;
+            it.a_full = full_tiles(it.row0 + 1, n_stream);
+            if (!src) {
+                const int base = cu[b] + S;
+                const int vmin = vis[base + it.row0], vmax = vis[base + last];
+                it.b_total = (vmax + kTileN - 1) / kTileN;
+                it.b_full = full_tiles(vmin, S);
+            }
+            c = it.a_total + it.b_total;
+        }
+    }
+    items[slot] = it;
+    cost[slot] = c;
+}
+
+// ---- kernel 4: longest-first order (stable rank by counting) ----------------
+__global__ __launch_bounds__(256) void plan_order_kernel(const int32_t* __restrict__ cost, int m_max,
+                                                         int32_t* __restrict__ order) {
+    __shared__ int s_cost[256];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int ci = i < m_max ? cost[i] : 0;
+    int rank = 0;
+    for (int base = 0; base < m_max; base += 256) {
+        const int j = base + threadIdx.x;
+        s_cost[threadIdx.x] = j < m_max ? cost[j] : -1;
+        __syncthreads();
+        const int n = min(256, m_max - base);
+        for (int k = 0; k < n; ++k) {
+            const int cj = s_cost[k];
+            rank += (cj > ci) || (cj == ci && base + k < i);
+        }
+        __syncthreads();
+    }
+    if (i < m_max) order[rank] = i;
+}
+
+}  // namespace st
+
+using namespace st;
+
+extern "C" size_t st_plan_workspace_bytes(int32_t batch, int64_t n_tokens) {
+    if (batch <= 0 || n_tokens < 0) return 0;
+    return ws_layout(batch, n_tokens).total;
+}
+
+extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_ids, const int32_t* stream_ids,
+                                    const int32_t* positions, const int32_t* cu_seqlens_host, int32_t batch,
+                                    void* workspace, size_t workspace_bytes, int32_t validate, void* hip_stream) {
+    if (!plan_out) return fail(ST_ERR_INVALID_ARG, "st_plan_create: plan is null");
+    *plan_out = nullptr;
+    if (!segment_ids || !stream_ids || !positions || !cu_seqlens_host)
+        return fail(ST_ERR_INVALID_ARG, "st_plan_create: null pointer");
+    if (batch <= 0) return fail(ST_ERR_INVALID_ARG, "st_plan_create: batch must be positive");
+    if (cu_seqlens_host[0] != 0) return fail(ST_ERR_LAYOUT, "st_plan_create: cu_seqlens[0] must be 0");
+    for (int b = 0; b < batch; ++b)
+        if (cu_seqlens_host[b + 1] < cu_seqlens_host[b])
+            return fail(ST_ERR_LAYOUT, "st_plan_create: cu_seqlens must be non-decreasing (entry %d)", b + 1);
+    const int64_t n_tokens = cu_seqlens_host[batch];
+    const WsLayout L = ws_layout(batch, n_tokens);
+    if (workspace) {
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+            return fail(ST_ERR_INVALID_ARG, "st_plan_create: workspace must be 256-byte aligned");
+        if (workspace_bytes < L.total)
+            return fail(ST_ERR_CAPACITY, "st_plan_create: workspace has %zu bytes, needs %zu", workspace_bytes, L.total);
+    }
+    st_plan* p = new (std::nothrow) st_plan();
+    if (!p) return fail(ST_ERR_RUNTIME, "st_plan_create: out of host memory");
+    p->batch = batch;
+    p->n_tokens = n_tokens;
+    p->stream = static_cast<hipStream_t>(hip_stream);
+    p->cu_host.assign(cu_seqlens_host, cu_seqlens_host + batch + 1);
+    p->slot_base_host.resize(batch + 1);
+    p->slot_base_host[0] = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int n = p->cu_host[b + 1] - p->cu_host[b];
+        p->slot_base_host[b + 1] = p->slot_base_host[b] + (n + kTileM - 1) / kTileM + 1;
+    }
+    p->m_max = p->slot_base_host[batch];   // <= m_max_bound(batch, n_tokens)
+    if (workspace) {
+        p->ws = workspace;
+    } else {
+        hipError_t e = hipMalloc(&p->ws, L.total);
+        if (e != hipSuccess) {
+            delete p;
+            return fail(ST_ERR_RUNTIME, "st_plan_create: hipMalloc(%zu) failed: %s", L.total, hipGetErrorString(e));
+        }
+        p->owns_ws = true;
+    }
+    char* w = static_cast<char*>(p->ws);
+    p->cu = reinterpret_cast<int32_t*>(w + L.cu);
+    p->slot_base = reinterpret_cast<int32_t*>(w + L.slot_base);
+    p->n_src = reinterpret_cast<int32_t*>(w + L.n_src);
+    p->n_rsn = reinterpret_cast<int32_t*>(w + L.n_rsn);
+    p->pairs = reinterpret_cast<unsigned long long*>(w + L.pairs);
+    p->flag = reinterpret_cast<int32_t*>(w + L.flag);
+    p->perm = reinterpret_cast<int32_t*>(w + L.perm);
+    p->seg_c = reinterpret_cast<int32_t*>(w + L.seg_c);
+    p->vis = reinterpret_cast<int32_t*>(w + L.vis);
+    p->order = reinterpret_cast<int32_t*>(w + L.order);
+    p->cost = reinterpret_cast<int32_t*>(w + L.cost);
+    p->items = reinterpret_cast<WorkItem*>(w + L.items);
+
+    hipStream_t s = p->stream;
+    auto bail = [&](hipError_t e, const char* what) {
+        st_status r = fail(ST_ERR_RUNTIME, "st_plan_create: %s failed: %s", what, hipGetErrorString(e));
+        st_plan_destroy(p);
+        return r;
+    };
+    hipError_t e;
+    if ((e = hipMemcpyAsync(p->cu, p->cu_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
+        return bail(e, "copy of cu_seqlens");
+    if ((e = hipMemcpyAsync(p->slot_base, p->slot_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
+        return bail(e, "copy of slot table");
+    const int nt = int(n_tokens);
+    hipLaunchKernelGGL(plan_clear_kernel, dim3(1), dim3(64), 0, s, p->flag);
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(batch), dim3(256), 0, s, stream_ids, segment_ids, p->cu, p->n_src,
+                       p->n_rsn, p->perm, p->seg_c, p->pairs, p->flag);
+    if (nt > 0)
+        hipLaunchKernelGGL(plan_vis_kernel, dim3((nt + 255) / 256), dim3(256), 0, s, p->cu, batch, nt, p->n_src,
+                           p->seg_c, p->perm, positions, p->vis, p->pairs, p->flag, validate ? 1 : 0);
+    const int mb = (p->m_max + 255) / 256;
+    hipLaunchKernelGGL(plan_items_kernel, dim3(mb), dim3(256), 0, s, p->cu, p->slot_base, batch, p->m_max, p->n_src,
+                       p->n_rsn, p->vis, p->items, p->cost);
+    hipLaunchKernelGGL(plan_order_kernel, dim3(mb), dim3(256), 0, s, p->cost, p->m_max, p->order);
+    if ((e = hipGetLastError()) != hipSuccess) return bail(e, "launch of plan kernels");
+    if (validate) {
+        int32_t flag = 0;
+        if ((e = hipMemcpyAsync(&flag, p->flag, sizeof(flag), hipMemcpyDeviceToHost, s)) != hipSuccess)
+            return bail(e, "copy of validation flag");
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) return bail(e, "hipStreamSynchronize");
+        if (flag) {
+            st_plan_destroy(p);
+            return fail(ST_ERR_LAYOUT,
+                        "st_plan_create: malformed token metadata (%s%s%s)", (flag & 1) ? "stream id outside {0,1}; " : "",
+                        (flag & 2) ? "positions not strictly increasing or segment ids decreasing inside a stream; " : "",
+                        (flag & 4) ? "negative id" : "");
+        }
+    }
+    *plan_out = p;
+    return ST_OK;
+}
+
+extern "C" void st_plan_destroy(st_plan* plan) {
+    if (!plan) return;
+    if (plan->owns_ws && plan->ws) (void)hipFree(plan->ws);
+    delete plan;
+}
+
+extern "C" st_status st_plan_tile_shape(const st_plan* plan, int32_t* tile_m, int32_t* tile_n) {
+    if (!plan || !tile_m || !tile_n) return fail(ST_ERR_INVALID_ARG, "st_plan_tile_shape: null pointer");
+    *tile_m = kTileM;
+    *tile_n = kTileN;
+    return ST_OK;
+}
+
+static st_status fetch(const st_plan* plan, void* dst, const void* src, size_t bytes) {
+    if (bytes == 0) return ST_OK;
+    ST_HIP(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, plan->stream));
+    ST_HIP(hipStreamSynchronize(plan->stream));
+    return ST_OK;
+}
+
+extern "C" st_status st_plan_stream_counts(const st_plan* plan, int32_t* n_src_host, int32_t* n_rsn_host) {
+    if (!plan || !n_src_host || !n_rsn_host) return fail(ST_ERR_INVALID_ARG, "st_plan_stream_counts: null pointer");
+    st_status r = fetch(plan, n_src_host, plan->n_src, sizeof(int32_t) * plan->batch);
+    if (r != ST_OK) return r;
+    return fetch(plan, n_rsn_host, plan->n_rsn, sizeof(int32_t) * plan->batch);
+}
+
+extern "C" st_status st_plan_compact_index(const st_plan* plan, int32_t* index_host) {
+    if (!plan || !index_host) return fail(ST_ERR_INVALID_ARG, "st_plan_compact_index: null pointer");
+    return fetch(plan, index_host, plan->perm, sizeof(int32_t) * plan->n_tokens);
+}
+
+extern "C" st_status st_plan_visible_source(const st_plan* plan, int32_t* vis_host) {
+    if (!plan || !vis_host) return fail(ST_ERR_INVALID_ARG, "st_plan_visible_source: null pointer");
+    return fetch(plan, vis_host, plan->vis, sizeof(int32_t) * plan->n_tokens);
+}
+
+extern "C" st_status st_plan_visible_pairs(const st_plan* plan, uint64_t* pairs_host) {
+    if (!plan || !pairs_host) return fail(ST_ERR_INVALID_ARG, "st_plan_visible_pairs: null pointer");
+    return fetch(plan, pairs_host, plan->pairs, sizeof(uint64_t) * plan->batch);
+}
+
+extern "C" st_status st_plan_tile_classes(const st_plan* plan, int32_t seq, int32_t block, uint8_t* classes_host,
+                                          int32_t* n_q_tiles, int32_t* n_k_tiles) {
+    if (!plan || !n_q_tiles || !n_k_tiles) return fail(ST_ERR_INVALID_ARG, "st_plan_tile_classes: null pointer");
+    if (seq < 0 || seq >= plan->batch) return fail(ST_ERR_INVALID_ARG, "st_plan_tile_classes: seq %d out of range", seq);
+    if (block != ST_BLOCK_SS && block != ST_BLOCK_RS && block != ST_BLOCK_RR)
+        return fail(ST_ERR_INVALID_ARG, "st_plan_tile_classes: block %d", block);
+    int32_t S = 0, R = 0;
+    st_status r = fetch(plan, &S, plan->n_src + seq, sizeof(int32_t));
+    if (r != ST_OK) return r;
+    r = fetch(plan, &R, plan->n_rsn + seq, sizeof(int32_t));
+    if (r != ST_OK) return r;
+    const int ts = (S + kTileM - 1) / kTileM, tr = (R + kTileM - 1) / kTileM;
+    const int tq = block == ST_BLOCK_SS ? ts : tr;
+    const int tk = ((block == ST_BLOCK_RR ? R : S) + kTileN - 1) / kTileN;
+    *n_q_tiles = tq;
+    *n_k_tiles = tk;
+    if (!classes_host || tq == 0) return ST_OK;
+    std::vector<WorkItem> items(tq);
+    const int first = plan->slot_base_host[seq] + (block == ST_BLOCK_SS ? 0 : ts);
+    r = fetch(plan, items.data(), plan->items + first, sizeof(WorkItem) * tq);
+    if (r != ST_OK) return r;
+    for (int a = 0; a < tq; ++a) {
+        const int full = block == ST_BLOCK_RS ? items[a].b_full : items[a].a_full;
+        const int total = block == ST_BLOCK_RS ? items[a].b_total : items[a].a_total;
+        for (int c = 0; c < tk; ++c)
+            classes_host[size_t(a) * tk + c] = c < full ? ST_TILE_FULL : (c < total ? ST_TILE_PARTIAL : ST_TILE_SKIP);
+    }
+    return ST_OK;
+}

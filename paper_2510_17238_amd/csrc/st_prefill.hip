@@ -1,0 +1,425 @@
+// Streaming-mask prefill attention (Sec. 3.2, "Streaming Attention Mask Matrix", Eq. 2).
+//
+// The dense additive mask of Eq. 2 never exists here.  Work is cut into query tiles
+// of one stream of one sequence (st::WorkItem), and each item walks two runs of key
+// tiles in stream-compact coordinates:
+//   block A -- causal over the row's own stream (source x source, or reasoning x
+//              reasoning),
+//   block B -- for reasoning rows, the prefix of the source stream they may see.
+// Inside a run, tiles [0, full) need no mask, tiles [full, total) compare the column
+// index with a per-row limit, tiles past `total` are never read.
+//
+// Two kernels:
+//   prefill_mfma_kernel   bf16, 4 waves x 32 query rows, K and V^T tiles double-buffered
+//                         in LDS, QK^T and PV on v_mfma_f32_32x32x16_bf16, fp32 online
+//                         softmax.  Both products are computed TRANSPOSED (S^T = K Q^T,
+//                         O^T = V^T P^T): a lane then owns one query row, so the row max /
+//                         row sum are in-register reductions plus one exchange with lane^32,
+//                         and the S^T accumulators are already laid out as the B operand of
+//                         the second product.
+//   prefill_simple_kernel any dtype, one thread per query row, plain fp32 arithmetic.  It is
+//                         the fp32 path (tolerance 1e-4) and walks the same work items.
+#include "st_plan.h"
+
+namespace st {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct ItemGeom {
+    int t0;          // first compact row of the sequence
+    int S;           // source tokens
+    int n_stream;    // tokens of the row's own stream
+    int a_base;      // compact row of column 0 of block A
+    int b_base;      // compact row of column 0 of block B (the source stream)
+};
+
+__device__ __forceinline__ ItemGeom item_geom(const PlanView& pv, const WorkItem& it) {
+    ItemGeom g;
+    g.t0 = pv.cu[it.seq];
+    g.S = pv.n_src[it.seq];
+    const int n = pv.cu[it.seq + 1] - g.t0;
+    g.n_stream = it.kind == ST_SOURCE ? g.S : n - g.S;
+    g.a_base = g.t0 + (it.kind == ST_SOURCE ? 0 : g.S);
+    g.b_base = g.t0;
+    return g;
+}
+
+// --------------------------------------------------------------------------
+// Plain kernel: one thread per query row.
+// --------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float load_f32(const T* p);
+template <>
+__device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_f32<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+template <typename T>
+__device__ __forceinline__ void store_f32(T* p, float x);
+template <>
+__device__ __forceinline__ void store_f32<float>(float* p, float x) { *p = x; }
+template <>
+__device__ __forceinline__ void store_f32<uint16_t>(uint16_t* p, float x) { *p = f32_to_bf16_bits(x); }
+
+template <typename T, int D>
+__global__ __launch_bounds__(kTileM) void prefill_simple_kernel(T* __restrict__ out, float* __restrict__ lse,
+                                                               const T* __restrict__ q, const T* __restrict__ k,
+                                                               const T* __restrict__ v, PlanView pv, int n_q_heads,
+                                                               int n_kv_heads, float scale) {
+    constexpr int CH = 16;  // keys per softmax update
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float (*s_q)[D + 1] = reinterpret_cast<float (*)[D + 1]>(smem_raw);
+    const int rank = blockIdx.x / n_q_heads;
+    const int hq = blockIdx.x % n_q_heads;
+    const int hk = hq / (n_q_heads / n_kv_heads);
+    const WorkItem it = pv.items[pv.order[rank]];
+    if (it.n_rows == 0) return;
+    const ItemGeom g = item_geom(pv, it);
+    const int r = threadIdx.x;
+    const bool active = r < it.n_rows;
+    const int my_row = it.row0 + min(r, it.n_rows - 1);        // relative to the row's stream
+    const int tok_q = pv.perm[g.a_base + my_row];
+    for (int d = 0; d < D; ++d) s_q[r][d] = load_f32(q + (int64_t(tok_q) * n_q_heads + hq) * D + d);
+    const int my_vis = pv.vis[g.a_base + my_row];
+
+    float o[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) o[d] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int n_tiles = it.a_total + it.b_total;
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        const bool in_a = ti < it.a_total;
+        const int kt = in_a ? ti : ti - it.a_total;
+        const bool partial = kt >= (in_a ? it.a_full : it.b_full);
+        const int base = in_a ? g.a_base : g.b_base;
+        const int n_cols = in_a ? g.n_stream : g.S;
+        const int limit = in_a ? my_row + 1 : my_vis;          // columns < limit are visible
+        const int c_end = min((kt + 1) * kTileN, n_cols);
+        for (int c0 = kt * kTileN; c0 < c_end; c0 += CH) {
+            float s[CH];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                const int col = c0 + u;
+                s[u] = -INFINITY;
+                if (col < c_end) {
+                    const int tok_k = pv.perm[base + col];
+                    const T* kp = k + (int64_t(tok_k) * n_kv_heads + hk) * D;
+                    float acc = 0.f;
+                    for (int d = 0; d < D; ++d) acc = fmaf(s_q[r][d], load_f32(kp + d), acc);
+                    if (!partial || col < limit) s[u] = acc * scale;
+                }
+                mx = fmaxf(mx, s[u]);
+            }
+            if (mx == -INFINITY) continue;
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = expf(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int d = 0; d < D; ++d) o[d] *= alpha;
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                const int col = c0 + u;
+                if (col < c_end && s[u] != -INFINITY) {
+                    const float p = expf(s[u] - m_new);
+                    l_run += p;
+                    const int tok_k = pv.perm[base + col];
+                    const T* vp = v + (int64_t(tok_k) * n_kv_heads + hk) * D;
+#pragma unroll
+                    for (int d = 0; d < D; ++d) o[d] = fmaf(p, load_f32(vp + d), o[d]);
+                }
+            }
+            m_run = m_new;
+        }
+    }
+    if (!active) return;
+    const float inv = 1.f / l_run;
+    T* op = out + (int64_t(tok_q) * n_q_heads + hq) * D;
+#pragma unroll
+    for (int d = 0; d < D; ++d) store_f32(op + d, o[d] * inv);
+    if (lse) lse[int64_t(tok_q) * n_q_heads + hq] = m_run + logf(l_run);
+}
+
+// --------------------------------------------------------------------------
+// MFMA kernel (bf16).
+// --------------------------------------------------------------------------
+template <int D>
+struct MfmaSmem {
+    static constexpr int KP = D + 8;            // K row pitch (elements): 16 B of padding
+    static constexpr int VP = kTileN + 8;       // V^T row pitch
+    uint16_t k[2][kTileN][KP];
+    uint16_t vt[2][D][VP];
+};
+
+// swap bits 2 and 3: the row order in which K is parked in LDS, so that after the
+// first MFMA each half-wave holds 8 CONSECUTIVE keys per 16-key step
+__device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                              const uint16_t* __restrict__ q,
+                                                              const uint16_t* __restrict__ k,
+                                                              const uint16_t* __restrict__ v, PlanView pv,
+                                                              int n_q_heads, int n_kv_heads, float scale_log2) {
+    constexpr int KS = D / 16;        // MFMA steps of the first product
+    constexpr int DB = D / 32;        // 32-wide blocks of the head dimension
+    constexpr int SB = kTileN / 32;   // 32-wide blocks of the key tile
+    constexpr int KCH = D / 8;        // 16-byte chunks per K row
+    constexpr int K_PER_THREAD = kTileN * KCH / 256;
+    constexpr int VQ = D / 4;         // 4-element groups per V row
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    MfmaSmem<D>& sm = *reinterpret_cast<MfmaSmem<D>*>(smem_raw);
+
+    const int rank = blockIdx.x / n_q_heads;
+    const int hh = blockIdx.x % n_q_heads;
+    const int group = n_q_heads / n_kv_heads;
+    const int hk = hh % n_kv_heads;                 // consecutive workgroups -> consecutive KV heads
+    const int hq = hk * group + hh / n_kv_heads;
+    const WorkItem it = pv.items[pv.order[rank]];
+    if (it.n_rows == 0) return;
+    const ItemGeom g = item_geom(pv, it);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hg = lane >> 5;        // query column of the wave tile, half-wave
+
+    const int row_in_tile = wave * 32 + n;
+    const bool active = row_in_tile < it.n_rows;
+    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
+    const int tok_q = pv.perm[g.a_base + my_row];
+    const int my_vis = pv.vis[g.a_base + my_row];
+
+    // Q^T operand: lane (n, hg) holds Q[row n][16 j + 8 hg .. + 8)
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq) * D + 8 * hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 16 * j);
+    }
+
+    f32x16 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int n_tiles = it.a_total + it.b_total;
+
+    // ---- tile loader: global -> registers -> LDS ---------------------------
+    u32x4 kreg[K_PER_THREAD];
+    u32x2 vreg[8];
+    const int v_kvb = tid & 7, v_dq = tid >> 3;     // 8-key block, 4-wide d group
+    const bool v_thread = v_dq < VQ;
+
+    auto load_tile = [&](int ti) {
+        const bool in_a = ti < it.a_total;
+        const int kt = in_a ? ti : ti - it.a_total;
+        const int base = in_a ? g.a_base : g.b_base;
+        const int last = (in_a ? g.n_stream : g.S) - 1;
+#pragma unroll
+        for (int u = 0; u < K_PER_THREAD; ++u) {
+            const int c = tid + 256 * u;
+            const int row = c / KCH, ch = c % KCH;
+            const int tok = pv.perm[base + min(kt * kTileN + row, last)];
+            kreg[u] = *reinterpret_cast<const u32x4*>(k + (int64_t(tok) * n_kv_heads + hk) * D + ch * 8);
+        }
+        if (v_thread) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int tok = pv.perm[base + min(kt * kTileN + v_kvb * 8 + r, last)];
+                vreg[r] = *reinterpret_cast<const u32x2*>(v + (int64_t(tok) * n_kv_heads + hk) * D + v_dq * 4);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < K_PER_THREAD; ++u) {
+            const int c = tid + 256 * u;
+            const int row = c / KCH, ch = c % KCH;
+            *reinterpret_cast<u32x4*>(&sm.k[buf][swap23(row)][ch * 8]) = kreg[u];
+        }
+        if (v_thread) {
+            // 8 keys x 4 d  ->  4 d x 8 keys
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+                u32x4 even, odd;
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    const uint32_t a = vreg[2 * pr][w], b = vreg[2 * pr + 1][w];
+                    even[pr] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // low halves
+                    odd[pr] = __builtin_amdgcn_perm(b, a, 0x07060302u);    // high halves
+                }
+                *reinterpret_cast<u32x4*>(&sm.vt[buf][v_dq * 4 + 2 * w][v_kvb * 8]) = even;
+                *reinterpret_cast<u32x4*>(&sm.vt[buf][v_dq * 4 + 2 * w + 1][v_kvb * 8]) = odd;
+            }
+        }
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        const int buf = ti & 1;
+        const bool more = ti + 1 < n_tiles;
+        if (more) load_tile(ti + 1);
+
+        const bool in_a = ti < it.a_total;
+        const int kt = in_a ? ti : ti - it.a_total;
+        const bool partial = kt >= (in_a ? it.a_full : it.b_full);
+
+        // ---- S^T = K Q^T : rows = keys, columns = query rows ----------------
+        f32x16 s_acc[SB];
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s_acc[sb][i] = 0.f;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sm.k[buf][32 * sb + n][16 * j + 8 * hg]);
+                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], s_acc[sb], 0, 0, 0);
+            }
+        }
+        // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
+        if (partial) {
+            const int limit = in_a ? my_row + 1 : my_vis;
+            const int c0 = kt * kTileN + 8 * hg;
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int col = c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
+                    s_acc[sb][i] = col < limit ? s_acc[sb][i] : -INFINITY;
+                }
+        }
+        // ---- online softmax (base-2, scale folded in) ----------------------
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[sb][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * scale_log2);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 pb[SB][2];
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[sb][i], scale_log2, -m_use));
+                psum += p;
+                pb[sb][i >> 3][i & 7] = (__bf16)p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+
+        // ---- O^T += V^T P^T --------------------------------------------------
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const bf16x8 a =
+                        *reinterpret_cast<const bf16x8*>(&sm.vt[buf][32 * db + n][32 * sb + 16 * t + 8 * hg]);
+                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[sb][t], o_acc[db], 0, 0, 0);
+                }
+
+        if (more) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue ------------------------------------------------------------
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (!active) return;
+    const float inv = 1.f / l_tot;
+    uint16_t* op = out + (int64_t(tok_q) * n_q_heads + hq) * D;
+    // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 o4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o4[c] = (__bf16)(o_acc[db][4 * q4 + c] * inv);
+            *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * hg) = o4;
+        }
+    if (lse && hg == 0) lse[int64_t(tok_q) * n_q_heads + hq] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
+}
+
+}  // namespace st
+
+using namespace st;
+
+extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, const void* v,
+                                     const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     float scale, st_dtype dt, void* hip_stream) {
+    if (!out || !q || !k || !v || !plan) return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: null pointer");
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k) || !aligned16(v))
+        return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: tensors must be 16-byte aligned");
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0)
+        return fail(ST_ERR_SHAPE, "st_attn_prefill: n_q_heads %d must be a positive multiple of n_kv_heads %d", n_q_heads, n_kv_heads);
+    if (head_dim != 64 && head_dim != 128) return fail(ST_ERR_UNSUPPORTED, "st_attn_prefill: head_dim %d (64 or 128)", head_dim);
+    if (dt != ST_F32 && dt != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "st_attn_prefill: dtype %d", int(dt));
+    if (plan->n_tokens == 0) return ST_OK;
+    if (scale <= 0.f) scale = 1.f / sqrtf(float(head_dim));
+    const int64_t blocks = int64_t(plan->m_max) * n_q_heads;
+    if (blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_prefill: grid too large");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const PlanView pv = plan->view();
+    if (dt == ST_F32) {
+        const size_t smem = sizeof(float) * kTileM * (head_dim + 1);
+        if (head_dim == 64) {
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_simple_kernel<float, 64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            hipLaunchKernelGGL((prefill_simple_kernel<float, 64>), dim3((unsigned)blocks), dim3(kTileM), smem, s, (float*)out, lse,
+                               (const float*)q, (const float*)k, (const float*)v, pv, n_q_heads, n_kv_heads, scale);
+        } else {
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_simple_kernel<float, 128>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            hipLaunchKernelGGL((prefill_simple_kernel<float, 128>), dim3((unsigned)blocks), dim3(kTileM), smem, s, (float*)out, lse,
+                               (const float*)q, (const float*)k, (const float*)v, pv, n_q_heads, n_kv_heads, scale);
+        }
+        ST_LAUNCH_CHECK("prefill_simple_kernel");
+        return ST_OK;
+    }
+    const float scale_log2 = scale * kLog2e;
+    if (head_dim == 64) {
+        const size_t smem = sizeof(MfmaSmem<64>);
+        ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<64>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+        hipLaunchKernelGGL((prefill_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
+                           (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, pv, n_q_heads, n_kv_heads, scale_log2);
+    } else {
+        const size_t smem = sizeof(MfmaSmem<128>);
+        ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<128>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+        hipLaunchKernelGGL((prefill_mfma_kernel<128>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
+                           (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, pv, n_q_heads, n_kv_heads, scale_log2);
+    }
+    ST_LAUNCH_CHECK("prefill_mfma_kernel");
+    return ST_OK;
+}
+
+extern "C" st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* k, const void* v,
+                                         const int32_t* segment_ids, const int32_t* stream_ids,
+                                         const int32_t* positions, const int32_t* cu_seqlens_host, int32_t batch,
+                                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float scale,
+                                         st_dtype dt, void* hip_stream) {
+    st_plan* plan = nullptr;
+    st_status r = st_plan_create(&plan, segment_ids, stream_ids, positions, cu_seqlens_host, batch, nullptr, 0, 1, hip_stream);
+    if (r != ST_OK) return r;
+    r = st_attn_prefill(out, lse, q, k, v, plan, n_q_heads, n_kv_heads, head_dim, scale, dt, hip_stream);
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    st_plan_destroy(plan);
+    if (r == ST_OK && e != hipSuccess) return fail(ST_ERR_RUNTIME, "st_attn_prefill_ids: %s", hipGetErrorString(e));
+    return r;
+}

@@ -1,0 +1,359 @@
+"""GPU parity: every call goes through the C-ABI library and is compared with the fp64
+oracle on the same seeded inputs.  Tolerances (max-abs): 1e-4 for fp32 inputs, 2e-2 for
+bf16 inputs with fp32 accumulation; integer metadata bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import streaming_attention as O
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def st():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2510_17238_amd as st_
+    st_.load_library()
+    return st_
+
+
+from gpu_helpers import DEV, ids_to_dev, make_cache, to_dev, to_f64  # noqa: E402
+
+
+# ------------------------------------------------------------------ RoPE --
+@pytest.mark.parametrize("dtype,n,h,d,pmax", [("f32", 128, 2, 64, 64), ("f32", 77, 3, 128, 200000),
+                                              ("bf16", 1000, 24, 128, 40000), ("bf16", 5, 1, 64, 7)])
+def test_rope(st, dtype, n, h, d, pmax):
+    rng = np.random.Generator(np.random.PCG64(100 + n))
+    x = W.normal(rng, (n, h, d), dtype)
+    pos = rng.integers(0, pmax, size=n).astype(np.int32)
+    pos[0] = 0
+    tx = to_dev(x, dtype)
+    out = torch.empty_like(tx)
+    st.st_rope_apply(tx, torch.from_numpy(pos).to(DEV), 1.0e6, out=out)
+    ref = O.rope(x, pos, 1.0e6)
+    tol = 2e-6 * max(1.0, np.abs(ref).max()) if dtype == "f32" else 2e-2
+    assert np.abs(to_f64(out) - ref).max() <= tol
+    if dtype == "bf16":
+        # correctly rounded up to one bf16 ulp
+        assert np.abs(to_f64(out) - ref).max() <= np.abs(ref).max() * 2.0 ** -8
+    # in place gives the same bits
+    st.st_rope_apply(tx, torch.from_numpy(pos).to(DEV), 1.0e6)
+    assert torch.equal(tx, out)
+
+
+# -------------------------------------------------------------- metadata --
+def _check_metadata(st, cfg):
+    seg, strm, pos = ids_to_dev(cfg)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, validate=True)
+    bm, bn = plan.tile_shape()
+    n_src, n_rsn = plan.stream_counts()
+    perm = plan.compact_index(); vis = plan.visible_source(); pairs = plan.visible_pairs()
+    closed = cfg.closed_form_pairs()
+    for b in range(cfg.batch):
+        s, e = int(cfg.cu_seqlens[b]), int(cfg.cu_seqlens[b + 1])
+        md = O.canonical_metadata(cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e], bm, bn)
+        S = len(md["src_idx"])
+        assert n_src[b] == S and n_rsn[b] == len(md["rsn_idx"])
+        assert np.array_equal(perm[s:s + S] - s, md["src_idx"])
+        assert np.array_equal(perm[s + S:e] - s, md["rsn_idx"])
+        assert np.array_equal(vis[s + S:e], md["vis_src"])
+        assert np.array_equal(vis[s:s + S], np.arange(1, S + 1))
+        assert int(pairs[b]) == md["visible_pairs"] == closed[b]
+        for blk, name in ((st.ST_BLOCK_SS, "SS"), (st.ST_BLOCK_RS, "RS"), (st.ST_BLOCK_RR, "RR")):
+            got = plan.tile_classes(b, blk)
+            assert got.shape == md[name].shape, (name, got.shape, md[name].shape)
+            assert np.array_equal(got, md[name]), name
+    plan.destroy()
+
+
+def test_metadata_config1(st):
+    _check_metadata(st, W.config1())
+    _check_metadata(st, W.config1("grouped"))
+
+
+def test_metadata_config2(st):
+    _check_metadata(st, W.config2())
+
+
+@pytest.mark.parametrize("seed", [201, 202, 203, 204])
+def test_metadata_random_ragged(st, seed):
+    # empty and 1-token segments, sequences shorter than one tile, several tiles with ragged tails
+    _check_metadata(st, W.random_prefill(seed, 5, 9, (0, 70), (0, 90), 2, 1, 64, "f32"))
+
+
+def test_metadata_edge_structures(st):
+    # only sources / only reasoning / empty sequence in the middle of a batch
+    lists = [(np.array([5, 130]), np.array([0, 0])), (np.array([0]), np.array([200])), (np.array([], int), np.array([], int)),
+             (np.array([1]), np.array([1]))]
+    cfg = W._assemble("edges", "f32", 2, 1, 64, lists, "interleaved", 7)
+    _check_metadata(st, cfg)
+
+
+def test_plan_validation_rejects_bad_metadata(st):
+    cfg = W.config1()
+    seg, strm, pos = ids_to_dev(cfg)
+    bad = pos.clone(); bad[5] = 0          # positions no longer increase inside the source stream
+    with pytest.raises(st.StError) as e:
+        st.st_plan_create(seg, strm, bad, cfg.cu_seqlens, validate=True)
+    assert e.value.status == 3
+    bad = strm.clone(); bad[9] = 2
+    with pytest.raises(st.StError):
+        st.st_plan_create(seg, bad, pos, cfg.cu_seqlens, validate=True)
+    bad = seg.clone(); bad[40] = 0         # segment ids decrease inside a stream
+    with pytest.raises(st.StError):
+        st.st_plan_create(bad, strm, pos, cfg.cu_seqlens, validate=True)
+
+
+# --------------------------------------------------------------- prefill --
+def _run_prefill(st, cfg, rope=True, check_lse=True):
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv = to_dev(q, cfg.dtype), to_dev(k, cfg.dtype), to_dev(v, cfg.dtype)
+    if rope:
+        st.st_rope_apply(tq, pos, cfg.theta)
+        st.st_rope_apply(tk, pos, cfg.theta)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, validate=True)
+    lse = torch.empty((cfg.n_tokens, cfg.n_q_heads), dtype=torch.float32, device=DEV)
+    out = st.st_attn_prefill(tq, tk, tv, plan, lse=lse)
+    torch.cuda.synchronize()
+    # the oracle takes the attention stage's actual inputs (rotated, in the storage dtype)
+    ref, ref_lse = O.attention_varlen(to_f64(tq), to_f64(tk), to_f64(tv), cfg.stream_ids, cfg.segment_ids, cfg.positions,
+                                      cfg.cu_seqlens)
+    err = np.abs(to_f64(out) - ref).max()
+    assert err <= TOL[cfg.dtype], err
+    if check_lse:
+        assert np.abs(to_f64(lse) - ref_lse).max() <= TOL[cfg.dtype]
+    return tq, tk, tv, out, plan
+
+
+def test_prefill_config1_fp32(st):
+    cfg = W.config1()
+    tq, tk, tv, out, plan = _run_prefill(st, cfg)
+    # chained check: rope + attention against the oracle's own rope (fp32 end to end)
+    q, k, v = cfg.tensors()
+    ref, _ = O.attention_dense(O.rope(q, cfg.positions, cfg.theta), O.rope(k, cfg.positions, cfg.theta), v,
+                               cfg.stream_ids, cfg.segment_ids, cfg.positions)
+    assert np.abs(to_f64(out) - ref).max() <= 1e-4
+    # one-off form with ids gives the same bits
+    seg, strm, pos = ids_to_dev(cfg)
+    out2 = st.st_attn_prefill_ids(tq, tk, tv, seg, strm, pos, cfg.cu_seqlens)
+    assert torch.equal(out, out2)
+
+
+def test_prefill_config1_grouped_layout(st):
+    _run_prefill(st, W.config1("grouped"))
+
+
+def test_prefill_config1_as_bf16(st):
+    cfg = W.config1()
+    cfg.dtype = "bf16"
+    _run_prefill(st, cfg)
+
+
+@pytest.mark.parametrize("seed,d,dtype", [(301, 64, "bf16"), (302, 128, "bf16"), (303, 128, "f32"), (304, 64, "f32"),
+                                          (305, 128, "bf16")])
+def test_prefill_random_ragged(st, seed, d, dtype):
+    cfg = W.random_prefill(seed, 3, 8, (0, 90), (0, 120), 4, 2, d, dtype)
+    _run_prefill(st, cfg)
+
+
+def test_prefill_edge_structures(st):
+    lists = [(np.array([5, 130]), np.array([0, 0])), (np.array([0]), np.array([200])), (np.array([], int), np.array([], int)),
+             (np.array([1]), np.array([1])), (np.array([64, 64]), np.array([128, 1]))]
+    for dtype in ("bf16", "f32"):
+        cfg = W._assemble("edges", dtype, 4, 4, 128, lists, "interleaved", 7)
+        _run_prefill(st, cfg)
+
+
+def test_prefill_config2_bf16_full(st):
+    cfg = W.config2()
+    tq, tk, tv, out, plan = _run_prefill(st, cfg)
+    # determinism: a second launch gives identical bits
+    out2 = st.st_attn_prefill(tq, tk, tv, plan)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+def test_prefill_mfma_agrees_with_plain_kernel(st):
+    """bf16 inputs through the MFMA kernel vs the same values through the fp32 kernel."""
+    cfg = W.random_prefill(311, 2, 10, (10, 80), (10, 100), 4, 2, 128, "bf16")
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    o_b = st.st_attn_prefill(to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16"), plan)
+    o_f = st.st_attn_prefill(to_dev(q, "f32"), to_dev(k, "f32"), to_dev(v, "f32"), plan)
+    torch.cuda.synchronize()
+    assert (o_b.float() - o_f).abs().max().item() <= 2e-2
+
+
+# ------------------------------------------------------- append / decode --
+def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3)):
+    """Fill both caches through st_kv_append in uneven chunks; returns caches and the oracle's contiguous copies."""
+    pages_s = (int(max(src_lens)) + src_extra + 15) // 16 + 1
+    pages_r = (int(max(rsn_lens)) + 15) // 16 + 1
+    cs, tab_s = make_cache(batch, pages_s, hkv, d, rng, fill=float("nan"))
+    cr, tab_r = make_cache(batch, pages_r, hkv, d, rng, fill=float("nan"))
+    caches = st.DualCache(cs, cr)
+    ref = {}
+    for which, lens, cache in ((st.ST_SOURCE, src_lens, cs), (st.ST_REASONING, rsn_lens, cr)):
+        total = int(max(lens)) if len(lens) else 0
+        kk = W.normal(rng, (batch, total, hkv, d), "bf16"); vv = W.normal(rng, (batch, total, hkv, d), "bf16")
+        ref[which] = (kk, vv)
+        done = np.zeros(batch, np.int64); ci = 0
+        while (done < lens).any():
+            step = chunks[ci % len(chunks)]; ci += 1
+            n_new = np.minimum(step, lens - done).astype(np.int32)
+            kn = np.zeros((batch, step, hkv, d), np.float32); vn = np.zeros((batch, step, hkv, d), np.float32)
+            for b in range(batch):
+                kn[b, :n_new[b]] = kk[b, done[b]:done[b] + n_new[b]]
+                vn[b, :n_new[b]] = vv[b, done[b]:done[b] + n_new[b]]
+            st.st_kv_append(caches, which, to_dev(kn, "bf16"), to_dev(vn, "bf16"), torch.from_numpy(n_new).to(DEV))
+            done += n_new
+        torch.cuda.synchronize()
+        assert np.array_equal(cache.appended_len.cpu().numpy(), lens)
+    return caches, ref, (tab_s, tab_r)
+
+
+def test_kv_append_matches_paged_model(st):
+    rng = np.random.Generator(np.random.PCG64(400))
+    batch, hkv, d = 3, 2, 128
+    src_lens = np.array([70, 33, 16]); rsn_lens = np.array([5, 100, 48])
+    caches, ref, (tab_s, tab_r) = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens)
+    for cache, which, lens, tab in ((caches.source, st.ST_SOURCE, src_lens, tab_s), (caches.reasoning, st.ST_REASONING, rsn_lens, tab_r)):
+        kl = st.k_pool_to_logical(cache.k_pool).float().cpu().numpy()
+        vl = st.v_pool_to_logical(cache.v_pool).float().cpu().numpy()
+        # the oracle's paged model, filled in one go from the same rows
+        pool_k = np.full(kl.shape, np.nan, np.float32); pool_v = np.full(vl.shape, np.nan, np.float32)
+        olen = np.zeros(batch, np.int64)
+        for b in range(batch):
+            O.paged_append(pool_k, tab, olen.copy(), b, ref[which][0][b, :lens[b]])
+            O.paged_append(pool_v, tab, olen, b, ref[which][1][b, :lens[b]])
+        # written slots are bit-identical, unwritten slots still hold the NaN fill
+        assert np.array_equal(np.isnan(kl), np.isnan(pool_k)) and np.array_equal(np.isnan(vl), np.isnan(pool_v))
+        assert np.array_equal(np.nan_to_num(kl), np.nan_to_num(pool_k))
+        assert np.array_equal(np.nan_to_num(vl), np.nan_to_num(pool_v))
+        for b in range(batch):
+            assert np.array_equal(O.paged_gather(kl, tab, b, int(lens[b])), ref[which][0][b, :lens[b]])
+
+
+def test_kv_append_capacity(st):
+    rng = np.random.Generator(np.random.PCG64(401))
+    cs, _ = make_cache(2, 2, 1, 64, rng); cr, _ = make_cache(2, 2, 1, 64, rng)
+    caches = st.DualCache(cs, cr)
+    kn = torch.zeros((2, 40, 1, 64), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(st.StError) as e:
+        st.st_kv_append(caches, st.ST_SOURCE, kn, kn, host_len_upper_bound=40)
+    assert e.value.status == 4
+    # a wrong host bound cannot make the device write past the page table: the overflow is dropped
+    st.st_kv_append(caches, st.ST_SOURCE, kn, kn, host_len_upper_bound=32)
+    torch.cuda.synchronize()
+    assert cs.appended_len.cpu().tolist() == [32, 32]
+
+
+def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0):
+    caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra)
+    q = W.normal(rng, (batch, q_len, hq, d), "bf16")
+    tq = to_dev(q, "bf16")
+    lse = torch.empty((batch, q_len, hq), dtype=torch.float32, device=DEV)
+    vis_t = torch.from_numpy(src_vis.astype(np.int32)).to(DEV); rl_t = torch.from_numpy(rsn_lens.astype(np.int32)).to(DEV)
+    out = st.st_attn_decode_dual(tq, caches, vis_t, rl_t, int(max(src_lens)), int(max(rsn_lens)), lse=lse)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        o_ref, l_ref = O.decode_dual_concat(q[b], ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
+                                            ref[st.ST_REASONING][1][b], int(src_vis[b]), int(rsn_lens[b]))
+        assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
+        got_l = to_f64(lse[b])
+        both = np.isfinite(l_ref)
+        assert np.array_equal(np.isfinite(got_l), both)
+        assert np.abs(got_l[both] - l_ref[both]).max(initial=0.0) <= 2e-2
+    return caches, tq, out
+
+
+def test_decode_small_ragged(st):
+    rng = np.random.Generator(np.random.PCG64(410))
+    src_lens = np.array([70, 33, 16, 300, 1]); rsn_lens = np.array([5, 100, 48, 257, 1])
+    # visible source prefix: 0, page - 1, page, page + 1, everything
+    src_vis = np.array([0, 15, 16, 17, 1])
+    _check_decode(st, rng, 5, 4, 2, 128, src_lens, rsn_lens, src_vis)
+
+
+def test_decode_head_dim_64_and_group_4(st):
+    rng = np.random.Generator(np.random.PCG64(411))
+    _check_decode(st, rng, 2, 8, 2, 64, np.array([100, 513]), np.array([700, 31]), np.array([100, 500]))
+
+
+def test_decode_q_len_8(st):
+    rng = np.random.Generator(np.random.PCG64(412))
+    _check_decode(st, rng, 3, 8, 2, 128, np.array([64, 10, 290]), np.array([8, 300, 40]), np.array([64, 0, 290]), q_len=8)
+
+
+def test_decode_empty_row(st):
+    """Both lengths zero: out = 0, lse = -inf."""
+    rng = np.random.Generator(np.random.PCG64(413))
+    cs, _ = make_cache(2, 2, 2, 128, rng, fill=float("nan")); cr, _ = make_cache(2, 2, 2, 128, rng, fill=float("nan"))
+    caches = st.DualCache(cs, cr)
+    kn = to_dev(W.normal(rng, (2, 3, 2, 128), "bf16"), "bf16")
+    st.st_kv_append(caches, st.ST_REASONING, kn, kn, torch.tensor([3, 0], dtype=torch.int32, device=DEV))
+    q = to_dev(W.normal(rng, (2, 1, 4, 128), "bf16"), "bf16")
+    lse = torch.empty((2, 1, 4), dtype=torch.float32, device=DEV)
+    zero = torch.zeros(2, dtype=torch.int32, device=DEV)
+    out = st.st_attn_decode_dual(q, caches, zero, torch.tensor([3, 0], dtype=torch.int32, device=DEV), 32, 32, lse=lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and (out[1] == 0).all() and torch.isinf(lse[1]).all() and torch.isfinite(lse[0]).all()
+
+
+def test_decode_ignores_poison_beyond_lens(st):
+    """NaN bit patterns in slots that are not visible must not reach the output: the pools start
+    NaN-filled, so the unwritten tail of each last page (source: slots 8..15 of page 2; reasoning:
+    slots 1..15 / 7..15) is poison sitting right next to visible data."""
+    rng = np.random.Generator(np.random.PCG64(414))
+    src_lens = np.array([40, 64]); rsn_lens = np.array([33, 7]); src_vis = np.array([40, 48])
+    caches, tq, out = _check_decode(st, rng, 2, 4, 2, 128, src_lens, rsn_lens, src_vis)
+    assert torch.isfinite(out).all()
+
+
+def test_decode_concurrent_append_is_bitwise_serial(st):
+    """Source append on a second stream while decoding: same bits as the serial order."""
+    rng = np.random.Generator(np.random.PCG64(415))
+    batch, hq, hkv, d = 4, 4, 2, 128
+    src_lens = np.array([200, 64, 130, 17]); rsn_lens = np.array([300, 50, 7, 260])
+    caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=64)
+    q = to_dev(W.normal(rng, (batch, 1, hq, d), "bf16"), "bf16")
+    vis = torch.from_numpy(src_lens.astype(np.int32)).to(DEV); rl = torch.from_numpy(rsn_lens.astype(np.int32)).to(DEV)
+    serial = st.st_attn_decode_dual(q, caches, vis, rl, int(src_lens.max()), int(rsn_lens.max()))
+    torch.cuda.synchronize()
+    kn = to_dev(W.normal(rng, (batch, 64, hkv, d), "bf16"), "bf16")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.st_kv_append(caches, st.ST_SOURCE, kn, kn, stream=side)
+    conc = st.st_attn_decode_dual(q, caches, vis, rl, int(src_lens.max()), int(rsn_lens.max()))
+    torch.cuda.synchronize()
+    assert torch.equal(serial, conc)
+    assert caches.source.appended_len.cpu().tolist() == (src_lens + 64).tolist()
+
+
+def test_decode_equals_last_prefill_row(st):
+    """The two halves of the path agree: decode over caches filled from a prefill's K/V == that prefill's last row."""
+    cfg = W.random_prefill(420, 1, 6, (5, 40), (5, 60), 4, 2, 128, "bf16", layout="grouped")
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    out = st.st_attn_prefill(tq, tk, tv, plan)
+    S = int((cfg.stream_ids == O.SRC).sum()); R = cfg.n_tokens - S
+    rng = np.random.Generator(np.random.PCG64(421))
+    cs, _ = make_cache(1, (S + 15) // 16, 2, 128, rng); cr, _ = make_cache(1, (R + 15) // 16, 2, 128, rng)
+    caches = st.DualCache(cs, cr)
+    st.st_kv_append(caches, st.ST_SOURCE, tk[:S][None].contiguous(), tv[:S][None].contiguous())
+    st.st_kv_append(caches, st.ST_REASONING, tk[S:][None].contiguous(), tv[S:][None].contiguous())
+    one = lambda x: torch.tensor([x], dtype=torch.int32, device=DEV)
+    dec = st.st_attn_decode_dual(tq[-1][None, None].contiguous(), caches, one(S), one(R), S, R)
+    torch.cuda.synchronize()
+    assert (dec[0, 0].float() - out[-1].float()).abs().max().item() <= 2e-2
