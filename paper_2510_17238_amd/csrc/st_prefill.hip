@@ -268,7 +268,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
 
         const bool in_a = ti < it.a_total;
         const int kt = in_a ? ti : ti - it.a_total;
-        const bool partial = kt >= (in_a ? it.a_full : it.b_full);
+        // a ragged last tile is FULL as far as the mask goes, but its out-of-range columns
+        // (filled with a repeated row by the loader) still have to be compared away
+        const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? g.n_stream : g.S);
 
         // ---- S^T = K Q^T : rows = keys, columns = query rows ----------------
         f32x16 s_acc[SB];
