@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""Benchmark of the streaming-constrained attention path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+  plan build -> RoPE(q), RoPE(k) -> streaming-mask prefill attention   (Qwen3-0.6B-shaped layer,
+  batch 4, 16/8 heads, D = 128, bf16, 32 source + 32 reasoning segments per sequence)
+  -> paged append of a 64-token source chunk (second stream) and of one reasoning token
+  -> dual-cache decode of that token over the batch's own source / reasoning caches.
+`value` is the effective (unmasked) prefill FLOPs divided by the WHOLE step time.  The decode half
+of the metric is measured in the same run on the Qwen3-1.7B-shaped decode workload (28 layers,
+batch 32, source cache 2K + reasoning cache 1-6K, concurrent 64-token source append) and reported
+in the "decode" object as GB/s of algorithmic cache bytes.
+
+Prints ONE JSON line.  All inputs are seeded, synthetic and resident in HBM before timing starts.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+
+def _median(xs):
+    return float(np.median(np.asarray(xs, dtype=np.float64)))
+
+
+def bench_prefill_step(st, torch, W, steps, warmup):
+    dev = "cuda"
+    cfg = W.config2()
+    hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    n, batch = cfg.n_tokens, cfg.batch
+    g = torch.Generator(device=dev); g.manual_seed(cfg.seed)
+    q = torch.randn((n, hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((n, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((n, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    seg = torch.from_numpy(cfg.segment_ids).to(dev); strm = torch.from_numpy(cfg.stream_ids).to(dev)
+    pos = torch.from_numpy(cfg.positions).to(dev)
+    q_rot = torch.empty_like(q); k_rot = torch.empty_like(k); out = torch.empty_like(q)
+    plan_ws = torch.empty(st.st_plan_workspace_bytes(batch, n), dtype=torch.uint8, device=dev)
+
+    # the batch's own caches: source / reasoning K, V of each sequence, paged with shuffled ids
+    S = np.array([int(s.sum()) for s in cfg.src_lens]); R = np.array([int(r.sum()) for r in cfg.rsn_lens])
+    chunk = 64
+    pages_s = (int(S.max()) + chunk + 15) // 16; pages_r = (int(R.max()) + 1 + 15) // 16
+    rng = np.random.Generator(np.random.PCG64(cfg.seed))
+    cs = st.KVCache(batch * pages_s, batch, pages_s, hkv, d, torch.from_numpy(W.shuffled_page_table(rng, batch, pages_s)).to(dev))
+    cr = st.KVCache(batch * pages_r, batch, pages_r, hkv, d, torch.from_numpy(W.shuffled_page_table(rng, batch, pages_r)).to(dev))
+    caches = st.DualCache(cs, cr)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, validate=True)
+    st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
+    perm = torch.from_numpy(plan.compact_index().astype(np.int64)).to(dev)
+    for which, lens, off in ((st.ST_SOURCE, S, 0), (st.ST_REASONING, R, 1)):
+        mx = int(lens.max())
+        kn = torch.zeros((batch, mx, hkv, d), dtype=torch.bfloat16, device=dev); vn = torch.zeros_like(kn)
+        for b in range(batch):
+            c0 = int(cfg.cu_seqlens[b]) + (0 if off == 0 else int(S[b]))
+            idx = perm[c0:c0 + int(lens[b])]
+            kn[b, :int(lens[b])] = k_rot[idx]; vn[b, :int(lens[b])] = v[idx]
+        st.st_kv_append(caches, which, kn, vn, torch.from_numpy(lens.astype(np.int32)).to(dev))
+    torch.cuda.synchronize()
+    pairs = plan.visible_pairs()
+    assert [int(x) for x in pairs] == cfg.closed_form_pairs()
+    flops = 4.0 * d * hq * float(pairs.sum())
+    plan.destroy()
+
+    len_s0 = cs.appended_len.clone(); len_r0 = cr.appended_len.clone()
+    src_vis = len_s0.clone(); rsn_len = (len_r0 + 1).contiguous()
+    k_src_new = torch.randn((batch, chunk, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_src_new = torch.randn((batch, chunk, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q_tok = torch.randn((batch, 1, hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k_tok = torch.randn((batch, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_tok = torch.randn((batch, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    pos_tok = torch.from_numpy(R.astype(np.int32)).to(dev)
+    out_tok = torch.empty_like(q_tok)
+    max_s, max_r = int(S.max()), int(R.max()) + 1
+    dec_ws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+
+    def step(i_timed):
+        cs.appended_len.copy_(len_s0); cr.appended_len.copy_(len_r0)      # same state every step
+        side.wait_stream(main)
+        with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
+            st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk, stream=side)
+        p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+        st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
+        st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
+        if i_timed is not None:
+            ev[i_timed][0].record()
+        st.st_attn_prefill(q_rot, k_rot, v, p, out=out)
+        if i_timed is not None:
+            ev[i_timed][1].record()
+        st.st_rope_apply(q_tok.view(batch, hq, d), pos_tok, cfg.theta)
+        st.st_rope_apply(k_tok.view(batch, hkv, d), pos_tok, cfg.theta)
+        st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
+        st.st_attn_decode_dual(q_tok, caches, src_vis, rsn_len, max_s, max_r, out=out_tok, workspace=dec_ws)
+        main.wait_stream(side)
+        return p
+
+    plans = []
+    for _ in range(warmup):
+        plans.append(step(None))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        plans.append(step(i))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    for p in plans:
+        p.destroy()
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": float(np.mean(kern_ms)),
+            "prefill_kernel_ms_median": _median(kern_ms), "n_tokens": n}
+
+
+def bench_decode(st, torch, W, steps, warmup):
+    dev = "cuda"
+    shp = W.config3()
+    B, L, hq, hkv, d = shp.batch, shp.n_layers, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
+    rng = np.random.Generator(np.random.PCG64(shp.seed))
+    pages_s = (shp.max_src_len + 15) // 16; pages_r = (shp.max_rsn_len + 15) // 16
+    tab_s = torch.from_numpy(W.shuffled_page_table(rng, B, pages_s)).to(dev)
+    tab_r = torch.from_numpy(W.shuffled_page_table(rng, B, pages_r)).to(dev)
+    g = torch.Generator(device=dev); g.manual_seed(shp.seed)
+    layers = []
+    len_s_all = torch.zeros((L, B), dtype=torch.int32, device=dev); len_r_all = torch.zeros((L, B), dtype=torch.int32, device=dev)
+    for li in range(L):
+        cs = st.KVCache(B * pages_s, B, pages_s, hkv, d, tab_s); cr = st.KVCache(B * pages_r, B, pages_r, hkv, d, tab_r)
+        cs.appended_len = len_s_all[li]; cr.appended_len = len_r_all[li]      # one tensor for all layers: one reset per step
+        for c in (cs, cr):                                  # any bit pattern is valid cache content: fill in place
+            c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
+        layers.append(st.DualCache(cs, cr))
+    src_vis = torch.from_numpy(shp.src_visible_len).to(dev)
+    rsn_len = torch.from_numpy(shp.rsn_len).to(dev)
+    rsn_before = (rsn_len - 1).contiguous()
+    q = torch.randn((B, 1, hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k_tok = torch.randn((B, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_tok = torch.randn((B, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k_src = torch.randn((B, shp.src_append, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_src = torch.randn((B, shp.src_append, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    max_s, max_r = int(shp.src_visible_len.max()), int(shp.rsn_len.max())
+    ws = torch.empty(st.st_decode_workspace_bytes(B, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream(); main = torch.cuda.current_stream()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+
+    def step(i_timed):
+        len_s_all.copy_(src_vis.expand(L, B)); len_r_all.copy_(rsn_before.expand(L, B))
+        side.wait_stream(main)
+        for li, dc in enumerate(layers):
+            with torch.cuda.stream(side):
+                st.st_kv_append(dc, st.ST_SOURCE, k_src, v_src, host_len_upper_bound=shp.max_src_len, stream=side)
+            st.st_kv_append(dc, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
+            if i_timed is not None and li == L - 1:
+                ev[i_timed][0].record()
+            st.st_attn_decode_dual(q, dc, src_vis, rsn_len, max_s, max_r, out=out, workspace=ws)
+            if i_timed is not None and li == L - 1:
+                ev[i_timed][1].record()
+        main.wait_stream(side)
+
+    for _ in range(warmup):
+        step(None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tokens = float((shp.src_visible_len.astype(np.int64) + shp.rsn_len).sum())
+    per_layer = tokens * 2 * hkv * d * 2
+    append_bytes = float(B * (shp.src_append + 1)) * 2 * hkv * d * 2 * 2 * L
+    layer_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    return {"shape": shp, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
+            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer}
+
+
+def cpu_baseline(W, O, flops_per_pair_head):
+    """The fp64 oracle, as it stands, on sequence 0 of the prefill workload (all heads)."""
+    cfg = W.config2()
+    q, k, v = cfg.tensors()
+    e = int(cfg.cu_seqlens[1])
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    qr = O.rope(q[:e], cfg.positions[:e], cfg.theta); kr = O.rope(k[:e], cfg.positions[:e], cfg.theta)
+    O.attention_dense(qr, kr, v[:e], cfg.stream_ids[:e], cfg.segment_ids[:e], cfg.positions[:e])
+    dt = time.perf_counter() - t0
+    fl = flops_per_pair_head * cfg.n_q_heads * cfg.closed_form_pairs()[0]
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"sequence 0 of {cfg.batch} ({e} tokens, all {cfg.n_q_heads} heads): RoPE + dense-mask fp64 attention, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--decode-steps", type=int, default=None, help="steps of the 28-layer decode workload (default: min(steps, 10))")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on ONE GPU; there is no multi-GPU mode (sequences and KV heads shard "
+              "without communication, see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2510_17238_amd as st
+    import workloads as W
+    st.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    pre = bench_prefill_step(st, torch, W, args.steps, args.warmup)
+    cfg = pre["cfg"]
+    tflops_step = pre["flops"] / pre["sec_per_step"] / 1e12
+    tflops_kernel = pre["flops"] / (pre["prefill_kernel_ms"] * 1e-3) / 1e12
+    line = {
+        "metric": "streaming-mask prefill TFLOP/s + dual-cache decode GB/s, % of MI355X peak",
+        "value": round(tflops_step, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(pre["sec_per_step"] * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Qwen3-0.6B-shaped layer, batch 4, 16 q / 8 kv heads, head_dim 128, bf16, "
+                               "32 source (24-64 tok) + 32 reasoning (32-128 tok) segments per sequence, interleaved; "
+                               "step = plan + RoPE + streaming-mask prefill + paged append (64-token source chunk, 1 reasoning "
+                               "token) + dual-cache decode of one token",
+                   "n_tokens": pre["n_tokens"], "effective_flops_per_step": pre["flops"]},
+        "prefill_pct_of_peak": round(100.0 * tflops_kernel / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"kernel": "prefill_mfma_kernel<128>", "bound": "mfma", "achieved": round(tflops_kernel, 3),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4)},
+    }
+    if not args.no_decode:
+        dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
+        dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3))
+        gbps_step = dec["bytes_per_step"] / dec["sec_per_step"] / 1e9
+        gbps_kernel = dec["bytes_per_layer"] / (dec["layer_decode_ms"] * 1e-3) / 1e9
+        shp = dec["shape"]
+        line["decode"] = {
+            "workload": "configs[2]: Qwen3-1.7B-shaped decode, 28 layers, batch 32, 16 q / 8 kv heads, head_dim 128, bf16, "
+                        "source cache 2048 + reasoning cache U[1024,6144], 16-token pages (shuffled), one token per step, "
+                        "concurrent 64-token source append per layer on a second stream",
+            "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
+            "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
+            "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
+            "roofline": {"kernel": "decode_split_kernel<128> + decode_combine_kernel<128> (one layer)", "bound": "hbm",
+                         "achieved": round(gbps_kernel, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                         "frac": round(gbps_kernel / PEAK_HBM_GBPS, 4), "traffic": None,
+                         "avg_kernel_ms": round(dec["layer_decode_ms"], 4)},
+        }
+    if not args.no_cpu_baseline:
+        from oracle import streaming_attention as O
+        line["cpu_baseline"] = cpu_baseline(W, O, 4.0 * cfg.head_dim)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -282,11 +282,20 @@ class KVCache:
 
 
 class DualCache:
+    """The source cache and the reasoning cache of one layer."""
+
     def __init__(self, source, reasoning):
         self.source, self.reasoning = source, reasoning
+        self._struct = None
 
     def struct(self):
-        return _DualCacheStruct(self.source.struct(), self.reasoning.struct())
+        # built once: the tensors behind a cache are fixed after construction (call refresh() otherwise)
+        if self._struct is None:
+            self._struct = _DualCacheStruct(self.source.struct(), self.reasoning.struct())
+        return self._struct
+
+    def refresh(self):
+        self._struct = None
 
 
 def k_pool_to_logical(k_pool):
