@@ -122,9 +122,9 @@ def bench_prefill_step(st, torch, W, steps, warmup):
             "prefill_kernel_ms_median": _median(kern_ms), "n_tokens": n}
 
 
-def bench_decode(st, torch, W, steps, warmup):
+def bench_decode(st, torch, W, steps, warmup, n_layers=None):
     dev = "cuda"
-    shp = W.config3()
+    shp = W.config3() if n_layers is None else W.config3(n_layers=n_layers)
     B, L, hq, hkv, d = shp.batch, shp.n_layers, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
     rng = np.random.Generator(np.random.PCG64(shp.seed))
     pages_s = (shp.max_src_len + 15) // 16; pages_r = (shp.max_rsn_len + 15) // 16
@@ -187,7 +187,7 @@ def cpu_baseline(W, O, flops_per_pair_head):
     """The fp64 oracle, as it stands, on sequence 0 of the prefill workload (all heads)."""
     cfg = W.config2()
     q, k, v = cfg.tensors()
-    e = int(cfg.cu_seqlens[1])
+    e = int(cfg.cu_seqlens[-1])
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -195,11 +195,11 @@ def cpu_baseline(W, O, flops_per_pair_head):
         cores = os.cpu_count() or 1
     t0 = time.perf_counter()
     qr = O.rope(q[:e], cfg.positions[:e], cfg.theta); kr = O.rope(k[:e], cfg.positions[:e], cfg.theta)
-    O.attention_dense(qr, kr, v[:e], cfg.stream_ids[:e], cfg.segment_ids[:e], cfg.positions[:e])
+    O.attention_varlen(qr, kr, v[:e], cfg.stream_ids[:e], cfg.segment_ids[:e], cfg.positions[:e], cfg.cu_seqlens)
     dt = time.perf_counter() - t0
-    fl = flops_per_pair_head * cfg.n_q_heads * cfg.closed_form_pairs()[0]
+    fl = flops_per_pair_head * cfg.n_q_heads * sum(cfg.closed_form_pairs())
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"sequence 0 of {cfg.batch} ({e} tokens, all {cfg.n_q_heads} heads): RoPE + dense-mask fp64 attention, {dt:.1f} s"}
+            "sample": f"the whole prefill batch ({cfg.batch} sequences, {e} tokens, all {cfg.n_q_heads} heads): RoPE + dense-mask fp64 attention, {dt:.1f} s"}
 
 
 def main():
@@ -210,6 +210,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None, help="steps of the 28-layer decode workload (default: min(steps, 10))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU; there is no multi-GPU mode (sequences and KV heads shard "
@@ -244,7 +245,7 @@ def main():
     }
     if not args.no_decode:
         dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
-        dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3))
+        dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers)
         gbps_step = dec["bytes_per_step"] / dec["sec_per_step"] / 1e9
         gbps_kernel = dec["bytes_per_layer"] / (dec["layer_decode_ms"] * 1e-3) / 1e9
         shp = dec["shape"]

@@ -183,6 +183,172 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     }
 }
 
+// Variant for q_len * G <= 16 query rows (the one-token decode step): the same scheme on
+// v_mfma_f32_16x16x32_bf16.  A wave takes 32 tokens (two pages) per step with two first-product
+// MFMAs X and Y whose 16 key rows are chosen so that afterwards quarter-wave g4 (lanes 16 g4 ..
+// 16 g4 + 15) holds, for its query column, the 8 CONSECUTIVE slots 8 (g4 % 2) .. + 7 of page
+// g4 / 2: X gives slots +0..3, Y gives slots +4..7.  Those 8 probabilities are exactly one B
+// operand of the second product, whose A operand (V^T) is then one contiguous 16-byte load.
+// The chunk's page ids are fetched once up front, and the loads of step s + 1 are issued before
+// the arithmetic of step s.
+template <int D>
+struct KvRegs {
+    u32x4 kx[D / 32], ky[D / 32];   // K operands of MFMA X / Y, one per 32-wide d step
+    u32x4 v[D / 16];                // V^T operands, one per 16-wide d block
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void decode_split16_kernel(DecodeArgs a) {
+    constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nc = a.ncs + a.ncr;
+    const int64_t unit = int64_t(blockIdx.x) * 4 + wave;
+    const int c = int(unit % nc);
+    const int64_t bh = unit / nc;
+    const int h = int(bh % a.n_kv_heads);
+    const int b = int(bh / a.n_kv_heads);
+    if (b >= a.batch) return;
+    const bool is_src = c < a.ncs;
+    const CacheView& cv = is_src ? a.src : a.rsn;
+    const int cc = is_src ? c : c - a.ncs;
+    const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
+    const int tok0 = cc * kChunk;
+    if (tok0 >= len) return;
+    const int tok_end = min(len, tok0 + kChunk);
+    const int n_steps = (tok_end - tok0 + 31) / 32;
+
+    const int n = lane & 15, g4 = lane >> 4;
+    const int t_row = n / a.group;
+    const bool valid_row = n < a.rows;
+    const int hq = h * a.group + n % a.group;
+    const int limit = !valid_row ? 0 : (is_src ? len : max(len - a.q_len + t_row + 1, 0));
+
+    // page ids of the chunk: lane i < 16 holds the id of page tok0 / 16 + i (or -1)
+    int my_id = -1;
+    {
+        const int pg = tok0 / kPage + n;
+        if (lane < 16 && pg * kPage < tok_end) my_id = cv.page_table[int64_t(b) * cv.max_pages + pg];
+        if (my_id < 0 || my_id >= cv.n_pages) my_id = -1;
+    }
+
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (valid_row)
+            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 32 * j + 8 * g4);
+        qf[j] = __builtin_bit_cast(bf16x8, z);
+    }
+    f32x4 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int64_t page_k = int64_t(cv.n_kv_heads) * KCH * (kPage * 8);
+    const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
+    // K: lane (m = n, g4) reads d-chunk 4 j + g4 of key row m; row m = 4 gq + i lives in page
+    // gq / 2, slot 8 (gq % 2) + i for X and + 4 for Y
+    const int k_page_sel = n >> 3;
+    const int64_t k_lane_off = int64_t(h) * KCH * (kPage * 8) + g4 * (kPage * 8) + (8 * ((n >> 2) & 1) + (n & 3)) * 8;
+    // V: lane (m = n, g4) reads slots 8 (g4 % 2) .. + 7 of row d = 16 db + m in page g4 / 2
+    const int v_page_sel = g4 >> 1;
+    const int64_t v_lane_off = int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
+
+    auto load_step = [&](int s, KvRegs<D>& r) {
+        const int id_k = __shfl(my_id, 2 * s + k_page_sel);
+        const int id_v = __shfl(my_id, 2 * s + v_page_sel);
+        const uint16_t* kp = cv.k_pool + int64_t(max(id_k, 0)) * page_k + k_lane_off;
+        const uint16_t* vp = cv.v_pool + int64_t(max(id_v, 0)) * page_v + v_lane_off;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            r.kx[j] = u32x4{0u, 0u, 0u, 0u};
+            r.ky[j] = u32x4{0u, 0u, 0u, 0u};
+            if (id_k >= 0) {
+                r.kx[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8));
+                r.ky[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8) + 4 * 8);
+            }
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            r.v[db] = u32x4{0u, 0u, 0u, 0u};
+            if (id_v >= 0) r.v[db] = *reinterpret_cast<const u32x4*>(vp + db * 16 * kPage);
+        }
+    };
+
+    auto compute_step = [&](int s, KvRegs<D>& r) {
+        const int first = tok0 + 32 * s + 8 * g4;       // token of this lane's first slot
+        f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.kx[j]), qf[j], sx, 0, 0, 0);
+            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.ky[j]), qf[j], sy, 0, 0, 0);
+        }
+        float sc[8];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float raw = e < 4 ? sx[e] : sy[e - 4];
+            sc[e] = first + e < limit ? raw : -INFINITY;
+            mx = fmaxf(mx, sc[e]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale_log2, -m_use));
+            psum += p;
+            pb[e] = (__bf16)p;
+        }
+        l_run = l_run * alpha + psum;
+        const bool tail = first + 8 > len;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            u32x4 z = r.v[db];
+            if (tail) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t keep_lo = first + 2 * e < len ? 0x0000ffffu : 0u;
+                    const uint32_t keep_hi = first + 2 * e + 1 < len ? 0xffff0000u : 0u;
+                    z[e] &= keep_lo | keep_hi;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o_acc[db][i] *= alpha;
+            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, z), pb, o_acc[db], 0, 0, 0);
+        }
+    };
+
+    KvRegs<D> r0, r1;
+    load_step(0, r0);
+    for (int s = 0; s < n_steps; s += 2) {
+        if (s + 1 < n_steps) load_step(s + 1, r1);
+        compute_step(s, r0);
+        if (s + 1 < n_steps) {
+            if (s + 2 < n_steps) load_step(s + 2, r0);
+            compute_step(s + 1, r1);
+        }
+    }
+
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (!valid_row) return;
+    const int64_t slot = ((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n;
+    float* po = a.part_o + slot * D;
+    // lane (n, g4), block db, register i  <->  d = 16 db + 4 g4 + i
+#pragma unroll
+    for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db + 4 * g4) = o_acc[db];
+    if (g4 == 0) {
+        a.part_ml[slot * 2] = m_run;
+        a.part_ml[slot * 2 + 1] = l_tot;
+    }
+}
+
 // One wave per (sequence, query row, query head): log-sum-exp merge of the partials of
 // both caches, in a fixed order (run-to-run identical results).
 template <int D>
@@ -202,8 +368,9 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a, uint1
     const int n_s = min((len_s + kChunk - 1) / kChunk, a.ncs), n_r = min((len_r + kChunk - 1) / kChunk, a.ncr);
     const int64_t base = (int64_t(b) * a.n_kv_heads + h) * nc;
 
+    const int n_tot = n_s + n_r;
     float mx = -INFINITY;
-    for (int i = lane; i < n_s + n_r; i += 64) {
+    for (int i = lane; i < n_tot; i += 64) {
         const int c = i < n_s ? i : a.ncs + (i - n_s);
         mx = fmaxf(mx, a.part_ml[((base + c) * a.rows + n) * 2]);
     }
@@ -214,14 +381,28 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a, uint1
     for (int e = 0; e < PER; ++e) acc[e] = 0.f;
     float den = 0.f;
     if (mx != -INFINITY) {
-        for (int i = 0; i < n_s + n_r; ++i) {
-            const int c = i < n_s ? i : a.ncs + (i - n_s);
-            const int64_t slot = (base + c) * a.rows + n;
-            const float w = __builtin_amdgcn_exp2f(a.part_ml[slot * 2] - mx);
-            den = fmaf(w, a.part_ml[slot * 2 + 1], den);
-            const float* po = a.part_o + slot * D + lane * PER;
+        for (int i0 = 0; i0 < n_tot; i0 += 64) {
+            // lane i owns the weight of partial i0 + i; the rows are then added in index order
+            float w_mine = 0.f, wl = 0.f;
+            if (i0 + lane < n_tot) {
+                const int i = i0 + lane;
+                const int c = i < n_s ? i : a.ncs + (i - n_s);
+                const int64_t slot = (base + c) * a.rows + n;
+                w_mine = __builtin_amdgcn_exp2f(a.part_ml[slot * 2] - mx);
+                wl = w_mine * a.part_ml[slot * 2 + 1];
+            }
+            for (int o = 32; o > 0; o >>= 1) wl += __shfl_xor(wl, o);
+            den += wl;
+            const int cnt = min(64, n_tot - i0);
+#pragma unroll 8
+            for (int u = 0; u < cnt; ++u) {
+                const int i = i0 + u;
+                const int c = i < n_s ? i : a.ncs + (i - n_s);
+                const float w = __shfl(w_mine, u);
+                const float* po = a.part_o + ((base + c) * a.rows + n) * D + lane * PER;
 #pragma unroll
-            for (int e = 0; e < PER; ++e) acc[e] = fmaf(w, po[e], acc[e]);
+                for (int e = 0; e < PER; ++e) acc[e] = fmaf(w, po[e], acc[e]);
+            }
         }
     }
     const float inv = den > 0.f ? 1.f / den : 0.f;
@@ -302,10 +483,14 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
     const int64_t out_units = int64_t(batch) * a.q_len * n_q_heads;
     if (units / 4 + 1 > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
     if (units > 0) {
-        if (d == 64)
-            hipLaunchKernelGGL((decode_split_kernel<64>), dim3((unsigned)((units + 3) / 4)), dim3(256), 0, s, a);
-        else
-            hipLaunchKernelGGL((decode_split_kernel<128>), dim3((unsigned)((units + 3) / 4)), dim3(256), 0, s, a);
+        const dim3 grid((unsigned)((units + 3) / 4)), block(256);
+        if (a.rows <= 16) {
+            if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((decode_split16_kernel<128>), grid, block, 0, s, a);
+        } else {
+            if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((decode_split_kernel<128>), grid, block, 0, s, a);
+        }
         ST_LAUNCH_CHECK("decode_split_kernel");
     }
     if (d == 64)

@@ -149,7 +149,15 @@ __global__ __launch_bounds__(256) void plan_vis_kernel(const int32_t* __restrict
         mine = (unsigned long long)v + (unsigned long long)(r - S + 1);
     }
     vis[c] = v;
-    atomicAdd(&pairs[b], mine);
+    // pair count: one atomic per wave when the whole wave sits in one sequence (the usual case)
+    const int b_first = __builtin_amdgcn_readfirstlane(b);
+    if (__all(b == b_first) && __popcll(__ballot(1)) == 64) {
+        unsigned long long sum = mine;
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if ((threadIdx.x & 63) == 0) atomicAdd(&pairs[b], sum);
+    } else {
+        atomicAdd(&pairs[b], mine);
+    }
     if (validate) {
         // neighbours inside one stream: positions strictly increase, segment ids do not decrease
         const int n = cu[b + 1] - t0;
