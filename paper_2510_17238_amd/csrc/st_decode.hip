@@ -18,7 +18,7 @@
 
 namespace st {
 
-constexpr int kChunk = 256;                 // tokens per work unit
+constexpr int kChunk = 512;                 // tokens per work unit
 constexpr int kStepsPerChunk = kChunk / 32; // 32 tokens (two pages) per MFMA step
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -184,30 +184,26 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 }
 
 // Variant for q_len * G <= 16 query rows (the one-token decode step): the same scheme on
-// v_mfma_f32_16x16x32_bf16.  A wave takes 32 tokens (two pages) per step with two first-product
-// MFMAs X and Y whose 16 key rows are chosen so that afterwards quarter-wave g4 (lanes 16 g4 ..
-// 16 g4 + 15) holds, for its query column, the 8 CONSECUTIVE slots 8 (g4 % 2) .. + 7 of page
-// g4 / 2: X gives slots +0..3, Y gives slots +4..7.  Those 8 probabilities are exactly one B
-// operand of the second product, whose A operand (V^T) is then one contiguous 16-byte load.
-// The chunk's page ids are fetched once up front, and the loads of step s + 1 are issued before
-// the arithmetic of step s.
+// v_mfma_f32_16x16x32_bf16, ONE WAVE PER WORKGROUP.  With a single wave everything that selects
+// the work unit is uniform (scalar registers, scalar branches), a finished unit frees its slot
+// at once, and at <= 128 VGPRs sixteen such waves share a CU, each with 16 KB of loads in flight.
+//
+// A wave takes 32 tokens (two pages) per step with two first-product MFMAs X and Y whose 16 key
+// rows are chosen so that afterwards quarter-wave g4 (lanes 16 g4 .. 16 g4 + 15) holds, for its
+// query column, the 8 CONSECUTIVE slots 8 (g4 % 2) .. + 7 of page g4 / 2: X gives slots +0..3,
+// Y gives slots +4..7.  Those 8 probabilities are exactly one B operand of the second product,
+// whose A operand (V^T) is then one contiguous 16-byte load.  All loads are unconditional (page
+// ids are clamped into the pool); what lies beyond the visible length is removed afterwards by
+// index: scores by select, V by bit mask.
 template <int D>
-struct KvRegs {
-    u32x4 kx[D / 32], ky[D / 32];   // K operands of MFMA X / Y, one per 32-wide d step
-    u32x4 v[D / 16];                // V^T operands, one per 16-wide d block
-};
-
-template <int D>
-__global__ __launch_bounds__(256, 2) void decode_split16_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr;
-    const int64_t unit = int64_t(blockIdx.x) * 4 + wave;
-    const int c = int(unit % nc);
-    const int64_t bh = unit / nc;
-    const int h = int(bh % a.n_kv_heads);
-    const int b = int(bh / a.n_kv_heads);
-    if (b >= a.batch) return;
+    const int c = int(blockIdx.x % unsigned(nc));
+    const unsigned bh = blockIdx.x / unsigned(nc);
+    const int h = int(bh % unsigned(a.n_kv_heads));
+    const int b = int(bh / unsigned(a.n_kv_heads));
     const bool is_src = c < a.ncs;
     const CacheView& cv = is_src ? a.src : a.rsn;
     const int cc = is_src ? c : c - a.ncs;
@@ -218,70 +214,57 @@ __global__ __launch_bounds__(256, 2) void decode_split16_kernel(DecodeArgs a) {
     const int n_steps = (tok_end - tok0 + 31) / 32;
 
     const int n = lane & 15, g4 = lane >> 4;
-    const int t_row = n / a.group;
     const bool valid_row = n < a.rows;
-    const int hq = h * a.group + n % a.group;
-    const int limit = !valid_row ? 0 : (is_src ? len : max(len - a.q_len + t_row + 1, 0));
-
-    // page ids of the chunk: lane i < 16 holds the id of page tok0 / 16 + i (or -1)
-    int my_id = -1;
-    {
-        const int pg = tok0 / kPage + n;
-        if (lane < 16 && pg * kPage < tok_end) my_id = cv.page_table[int64_t(b) * cv.max_pages + pg];
-        if (my_id < 0 || my_id >= cv.n_pages) my_id = -1;
-    }
+    const int nr = min(n, a.rows - 1);                  // rows past the end repeat the last one (never stored)
+    const int t_row = nr / a.group;
+    const int hq = h * a.group + nr % a.group;
+    const int limit = is_src ? len : max(len - a.q_len + t_row + 1, 0);
 
     bf16x8 qf[KS];
+    {
+        const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
 #pragma unroll
-    for (int j = 0; j < KS; ++j) {
-        u32x4 z = {0u, 0u, 0u, 0u};
-        if (valid_row)
-            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 32 * j + 8 * g4);
-        qf[j] = __builtin_bit_cast(bf16x8, z);
+        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
     }
     f32x4 o_acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
+    const int32_t* table = cv.page_table + int64_t(b) * cv.max_pages + tok0 / kPage;
+    const int last_page = (tok_end - 1) / kPage - tok0 / kPage;      // last page of the chunk that holds visible tokens
     const int64_t page_k = int64_t(cv.n_kv_heads) * KCH * (kPage * 8);
     const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
     // K: lane (m = n, g4) reads d-chunk 4 j + g4 of key row m; row m = 4 gq + i lives in page
     // gq / 2, slot 8 (gq % 2) + i for X and + 4 for Y
-    const int k_page_sel = n >> 3;
-    const int64_t k_lane_off = int64_t(h) * KCH * (kPage * 8) + g4 * (kPage * 8) + (8 * ((n >> 2) & 1) + (n & 3)) * 8;
+    const bool k_second_page = (n >> 3) != 0;
+    const uint16_t* k_lane = cv.k_pool + int64_t(h) * KCH * (kPage * 8) + g4 * (kPage * 8) + (8 * ((n >> 2) & 1) + (n & 3)) * 8;
     // V: lane (m = n, g4) reads slots 8 (g4 % 2) .. + 7 of row d = 16 db + m in page g4 / 2
-    const int v_page_sel = g4 >> 1;
-    const int64_t v_lane_off = int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
+    const bool v_second_page = (g4 >> 1) != 0;
+    const uint16_t* v_lane = cv.v_pool + int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
 
-    auto load_step = [&](int s, KvRegs<D>& r) {
-        const int id_k = __shfl(my_id, 2 * s + k_page_sel);
-        const int id_v = __shfl(my_id, 2 * s + v_page_sel);
-        const uint16_t* kp = cv.k_pool + int64_t(max(id_k, 0)) * page_k + k_lane_off;
-        const uint16_t* vp = cv.v_pool + int64_t(max(id_v, 0)) * page_v + v_lane_off;
+    for (int s = 0; s < n_steps; ++s) {
+        // page ids of this step (uniform); pages past the visible length fall back to the last visible one
+        int id0 = table[min(2 * s, last_page)], id1 = table[min(2 * s + 1, last_page)];
+        id0 = min(max(id0, 0), cv.n_pages - 1);
+        id1 = min(max(id1, 0), cv.n_pages - 1);
+        const uint16_t* kp = k_lane + int64_t(k_second_page ? id1 : id0) * page_k;
+        const uint16_t* vp = v_lane + int64_t(v_second_page ? id1 : id0) * page_v;
+        u32x4 kx[KS], ky[KS], vv[DB];
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
-            r.kx[j] = u32x4{0u, 0u, 0u, 0u};
-            r.ky[j] = u32x4{0u, 0u, 0u, 0u};
-            if (id_k >= 0) {
-                r.kx[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8));
-                r.ky[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8) + 4 * 8);
-            }
+            kx[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8));
+            ky[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8) + 4 * 8);
         }
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            r.v[db] = u32x4{0u, 0u, 0u, 0u};
-            if (id_v >= 0) r.v[db] = *reinterpret_cast<const u32x4*>(vp + db * 16 * kPage);
-        }
-    };
+        for (int db = 0; db < DB; ++db) vv[db] = *reinterpret_cast<const u32x4*>(vp + db * 16 * kPage);
 
-    auto compute_step = [&](int s, KvRegs<D>& r) {
         const int first = tok0 + 32 * s + 8 * g4;       // token of this lane's first slot
         f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
-            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.kx[j]), qf[j], sx, 0, 0, 0);
-            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.ky[j]), qf[j], sy, 0, 0, 0);
+            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kx[j]), qf[j], sx, 0, 0, 0);
+            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ky[j]), qf[j], sy, 0, 0, 0);
         }
         float sc[8];
         float mx = -INFINITY;
@@ -306,32 +289,19 @@ __global__ __launch_bounds__(256, 2) void decode_split16_kernel(DecodeArgs a) {
             pb[e] = (__bf16)p;
         }
         l_run = l_run * alpha + psum;
-        const bool tail = first + 8 > len;
+        if (tok0 + 32 * s + 32 > len) {                 // uniform: only the step that holds the end of the cache
+            u32x4 keep;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                keep[e] = (first + 2 * e < len ? 0x0000ffffu : 0u) | (first + 2 * e + 1 < len ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) vv[db] &= keep;
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-            u32x4 z = r.v[db];
-            if (tail) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t keep_lo = first + 2 * e < len ? 0x0000ffffu : 0u;
-                    const uint32_t keep_hi = first + 2 * e + 1 < len ? 0xffff0000u : 0u;
-                    z[e] &= keep_lo | keep_hi;
-                }
-            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) o_acc[db][i] *= alpha;
-            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, z), pb, o_acc[db], 0, 0, 0);
-        }
-    };
-
-    KvRegs<D> r0, r1;
-    load_step(0, r0);
-    for (int s = 0; s < n_steps; s += 2) {
-        if (s + 1 < n_steps) load_step(s + 1, r1);
-        compute_step(s, r0);
-        if (s + 1 < n_steps) {
-            if (s + 2 < n_steps) load_step(s + 2, r0);
-            compute_step(s + 1, r1);
+            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv[db]), pb, o_acc[db], 0, 0, 0);
         }
     }
 
@@ -349,60 +319,68 @@ __global__ __launch_bounds__(256, 2) void decode_split16_kernel(DecodeArgs a) {
     }
 }
 
-// One wave per (sequence, query row, query head): log-sum-exp merge of the partials of
-// both caches, in a fixed order (run-to-run identical results).
+// One wave (one workgroup) per (sequence, query row, query head): log-sum-exp merge of the
+// partials of both caches, in a fixed order (run-to-run identical results).  The partial rows are
+// fetched 32 at a time with independent loads -- one memory round trip per batch instead of one
+// per partial -- and folded with a running maximum across batches.
 template <int D>
-__global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a, uint16_t* __restrict__ out,
-                                                             float* __restrict__ lse) {
+__global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16_t* __restrict__ out,
+                                                            float* __restrict__ lse) {
     constexpr int PER = D / 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t unit = int64_t(blockIdx.x) * 4 + wave;
-    const int hq = int(unit % a.n_q_heads);
-    const int t = int((unit / a.n_q_heads) % a.q_len);
-    const int b = int(unit / (int64_t(a.n_q_heads) * a.q_len));
-    if (b >= a.batch) return;
+    constexpr int BATCH = 32;
+    const int lane = threadIdx.x;
+    const int hq = int(blockIdx.x % unsigned(a.n_q_heads));
+    const int t = int((blockIdx.x / unsigned(a.n_q_heads)) % unsigned(a.q_len));
+    const int b = int(blockIdx.x / unsigned(a.n_q_heads * a.q_len));
     const int h = hq / a.group, n = t * a.group + hq % a.group;
     const int nc = a.ncs + a.ncr;
     const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
     const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
     const int n_s = min((len_s + kChunk - 1) / kChunk, a.ncs), n_r = min((len_r + kChunk - 1) / kChunk, a.ncr);
-    const int64_t base = (int64_t(b) * a.n_kv_heads + h) * nc;
-
     const int n_tot = n_s + n_r;
-    float mx = -INFINITY;
-    for (int i = lane; i < n_tot; i += 64) {
-        const int c = i < n_s ? i : a.ncs + (i - n_s);
-        mx = fmaxf(mx, a.part_ml[((base + c) * a.rows + n) * 2]);
-    }
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    const int64_t base = (int64_t(b) * a.n_kv_heads + h) * nc;
 
     float acc[PER];
 #pragma unroll
     for (int e = 0; e < PER; ++e) acc[e] = 0.f;
-    float den = 0.f;
-    if (mx != -INFINITY) {
-        for (int i0 = 0; i0 < n_tot; i0 += 64) {
-            // lane i owns the weight of partial i0 + i; the rows are then added in index order
-            float w_mine = 0.f, wl = 0.f;
-            if (i0 + lane < n_tot) {
-                const int i = i0 + lane;
-                const int c = i < n_s ? i : a.ncs + (i - n_s);
-                const int64_t slot = (base + c) * a.rows + n;
-                w_mine = __builtin_amdgcn_exp2f(a.part_ml[slot * 2] - mx);
-                wl = w_mine * a.part_ml[slot * 2 + 1];
-            }
-            for (int o = 32; o > 0; o >>= 1) wl += __shfl_xor(wl, o);
-            den += wl;
-            const int cnt = min(64, n_tot - i0);
-#pragma unroll 8
-            for (int u = 0; u < cnt; ++u) {
-                const int i = i0 + u;
-                const int c = i < n_s ? i : a.ncs + (i - n_s);
-                const float w = __shfl(w_mine, u);
-                const float* po = a.part_o + ((base + c) * a.rows + n) * D + lane * PER;
+    float den = 0.f, m_run = -INFINITY;
+    for (int i0 = 0; i0 < n_tot; i0 += BATCH) {
+        const int cnt = min(BATCH, n_tot - i0);
+        // lane u < cnt owns (m, l) of partial i0 + u
+        float m_mine = -INFINITY, l_mine = 0.f;
+        if (lane < cnt) {
+            const int i = i0 + lane;
+            const int c = i < n_s ? i : a.ncs + (i - n_s);
+            const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + ((base + c) * a.rows + n) * 2);
+            m_mine = ml[0];
+            l_mine = ml[1];
+        }
+        float rows[BATCH][PER];
 #pragma unroll
-                for (int e = 0; e < PER; ++e) acc[e] = fmaf(w, po[e], acc[e]);
-            }
+        for (int u = 0; u < BATCH; ++u) {
+            const int i = i0 + min(u, cnt - 1);          // rows past the end repeat the last one, with weight 0
+            const int c = i < n_s ? i : a.ncs + (i - n_s);
+            const float* po = a.part_o + ((base + c) * a.rows + n) * D + lane * PER;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) rows[u][e] = po[e];
+        }
+        float bm = m_mine;
+        for (int o = 32; o > 0; o >>= 1) bm = fmaxf(bm, __shfl_xor(bm, o));
+        const float m_new = fmaxf(m_run, bm);
+        if (m_new == -INFINITY) continue;                // nothing visible in this batch or before
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        const float w_mine = __builtin_amdgcn_exp2f(m_mine - m_new);     // 0 for lanes >= cnt
+        float wl = w_mine * l_mine;
+        for (int o = 32; o > 0; o >>= 1) wl += __shfl_xor(wl, o);
+        den = den * alpha + wl;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const float w = __shfl(w_mine, u);
+#pragma unroll
+            for (int e = 0; e < PER; ++e) acc[e] = fmaf(w, rows[u][e], acc[e]);
         }
     }
     const float inv = den > 0.f ? 1.f / den : 0.f;
@@ -410,7 +388,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeArgs a, uint1
 #pragma unroll
     for (int e = 0; e < PER; ++e) op[e] = f32_to_bf16_bits(acc[e] * inv);
     if (lse && lane == 0)
-        lse[(int64_t(b) * a.q_len + t) * a.n_q_heads + hq] = den > 0.f ? (mx + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
+        lse[(int64_t(b) * a.q_len + t) * a.n_q_heads + hq] = den > 0.f ? (m_run + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
 }
 
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -485,19 +463,21 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
     if (units > 0) {
         const dim3 grid((unsigned)((units + 3) / 4)), block(256);
         if (a.rows <= 16) {
-            if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((decode_split16_kernel<128>), grid, block, 0, s, a);
+            if (units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
+            if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
+            else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
         } else {
             if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
             else hipLaunchKernelGGL((decode_split_kernel<128>), grid, block, 0, s, a);
         }
         ST_LAUNCH_CHECK("decode_split_kernel");
     }
+    if (out_units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
     if (d == 64)
-        hipLaunchKernelGGL((decode_combine_kernel<64>), dim3((unsigned)((out_units + 3) / 4)), dim3(256), 0, s, a,
+        hipLaunchKernelGGL((decode_combine_kernel<64>), dim3((unsigned)out_units), dim3(64), 0, s, a,
                            static_cast<uint16_t*>(out), lse);
     else
-        hipLaunchKernelGGL((decode_combine_kernel<128>), dim3((unsigned)((out_units + 3) / 4)), dim3(256), 0, s, a,
+        hipLaunchKernelGGL((decode_combine_kernel<128>), dim3((unsigned)out_units), dim3(64), 0, s, a,
                            static_cast<uint16_t*>(out), lse);
     ST_LAUNCH_CHECK("decode_combine_kernel");
     return ST_OK;

@@ -357,3 +357,23 @@ def test_decode_equals_last_prefill_row(st):
     dec = st.st_attn_decode_dual(tq[-1][None, None].contiguous(), caches, one(S), one(R), S, R)
     torch.cuda.synchronize()
     assert (dec[0, 0].float() - out[-1].float()).abs().max().item() <= 2e-2
+
+
+def test_decode_workspace_reuse(st):
+    """One workspace (never cleared, garbage at first) serves many calls of different shapes."""
+    rng = np.random.Generator(np.random.PCG64(430))
+    batch, hq, hkv, d = 3, 4, 2, 128
+    src_lens = np.array([600, 40, 257]); rsn_lens = np.array([30, 900, 512])
+    caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens)
+    need = st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, 600, 900)
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=DEV)
+    q = W.normal(rng, (batch, 1, hq, d), "bf16")
+    tq = to_dev(q, "bf16")
+    for vis, rl in ((src_lens, rsn_lens), (np.array([100, 0, 256]), np.array([1, 700, 255])), (src_lens, rsn_lens)):
+        out = st.st_attn_decode_dual(tq, caches, torch.from_numpy(vis.astype(np.int32)).to(DEV),
+                                     torch.from_numpy(rl.astype(np.int32)).to(DEV), 600, 900, workspace=ws)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            o_ref, _ = O.decode_dual_concat(q[b], ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
+                                            ref[st.ST_REASONING][1][b], int(vis[b]), int(rl[b]))
+            assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
