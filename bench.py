@@ -45,6 +45,7 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     pos = torch.from_numpy(cfg.positions).to(dev)
     q_rot = torch.empty_like(q); k_rot = torch.empty_like(k); out = torch.empty_like(q)
     plan_ws = torch.empty(st.st_plan_workspace_bytes(batch, n), dtype=torch.uint8, device=dev)
+    pre_ws = None
 
     # the batch's own caches: source / reasoning K, V of each sequence, paged with shuffled ids
     S = np.array([int(s.sum()) for s in cfg.src_lens]); R = np.array([int(r.sum()) for r in cfg.rsn_lens])
@@ -68,6 +69,7 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     torch.cuda.synchronize()
     pairs = plan.visible_pairs()
     assert [int(x) for x in pairs] == cfg.closed_form_pairs()
+    pre_ws = torch.empty(st.st_prefill_workspace_bytes(plan, hkv, d, st.ST_BF16), dtype=torch.uint8, device=dev)
     flops = 4.0 * d * hq * float(pairs.sum())
     plan.destroy()
 
@@ -96,7 +98,7 @@ def bench_prefill_step(st, torch, W, steps, warmup):
         st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
         if i_timed is not None:
             ev[i_timed][0].record()
-        st.st_attn_prefill(q_rot, k_rot, v, p, out=out)
+        st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         if i_timed is not None:
             ev[i_timed][1].record()
         st.st_rope_apply(q_tok.view(batch, hq, d), pos_tok, cfg.theta)

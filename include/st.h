@@ -158,14 +158,21 @@ st_status st_plan_tile_classes(const st_plan* plan, int32_t seq, int32_t block,
  * Key tiles that the plan marks SKIP are never read.  bf16: MFMA products with
  * fp32 accumulation and fp32 softmax state, probabilities rounded to bf16 before
  * the second product.  f32: plain fp32 arithmetic.
+ *
+ * workspace (bf16 only): at least st_prefill_workspace_bytes(...) bytes, 256-byte
+ * aligned; holds K and V^T regrouped into contiguous key tiles for the duration of
+ * the call (about the size of k plus v).  Not needed for f32 (may be NULL).
  * ---------------------------------------------------------------------- */
+size_t st_prefill_workspace_bytes(const st_plan* plan, int32_t n_kv_heads, int32_t head_dim, st_dtype dt);
+
 st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, const void* v,
                           const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads,
-                          int32_t head_dim, float scale, st_dtype dt, void* hip_stream);
+                          int32_t head_dim, float scale, st_dtype dt,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Same, taking the token metadata directly: builds a plan, runs the attention,
- * WAITS for it and frees the plan.  For one-off calls; a caller with several
- * layers should create the plan once. */
+ * WAITS for it and frees the plan (and a workspace it allocates itself).  For one-off
+ * calls; a caller with several layers should create the plan once. */
 st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* k, const void* v,
                               const int32_t* segment_ids, const int32_t* stream_ids,
                               const int32_t* positions, const int32_t* cu_seqlens_host,

@@ -79,7 +79,9 @@ def load_library():
     lib.st_plan_tile_classes.restype = i32
     lib.st_plan_tile_classes.argtypes = [vp, i32, i32, vp, C.POINTER(i32), C.POINTER(i32)]
     lib.st_attn_prefill.restype = i32
-    lib.st_attn_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp]
+    lib.st_attn_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, sz, vp]
+    lib.st_prefill_workspace_bytes.restype = sz
+    lib.st_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.st_attn_prefill_ids.restype = i32
     lib.st_attn_prefill_ids.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp]
     lib.st_kv_append.restype = i32
@@ -225,7 +227,11 @@ def st_plan_create(segment_ids, stream_ids, positions, cu_seqlens, workspace=Non
 
 
 # --------------------------------------------------------------- prefill --
-def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, stream=None):
+def st_prefill_workspace_bytes(plan, n_kv_heads, head_dim, dtype_code):
+    return int(load_library().st_prefill_workspace_bytes(plan.handle, n_kv_heads, head_dim, dtype_code))
+
+
+def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, workspace=None, stream=None):
     """q[N, Hq, D], k, v[N, Hkv, D] -> out[N, Hq, D]; lse: fp32 [N, Hq] tensor to fill, or None."""
     lib = load_library()
     assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
@@ -237,8 +243,15 @@ def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, stream=None):
         out = torch.empty_like(q)
     if lse is not None:
         assert lse.dtype == torch.float32 and lse.shape == (n, hq) and lse.is_contiguous()
+    ws_bytes = 0
+    if workspace is None:
+        need = st_prefill_workspace_bytes(plan, hkv, d, _dtype_code(q))
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.st_attn_prefill(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), plan.handle, hq, hkv, d, float(scale),
-                               _dtype_code(q), _stream(stream)))
+                               _dtype_code(q), _ptr(workspace), ws_bytes, _stream(stream)))
     return out
 
 

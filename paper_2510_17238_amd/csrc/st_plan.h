@@ -28,7 +28,22 @@ struct PlanView {  // what kernels need
     const WorkItem* items;   // [m_max]
     const int32_t* order;    // [m_max] longest-first permutation of item slots
     int32_t m_max;
+    // Packed K / V^T buffers (bf16 path): sequence b owns key tiles [pack_base[b], pack_base[b+1]) of
+    // kTileN rows each: first ceil(S / kTileN) source tiles, then the reasoning tiles.
+    const int32_t* pack_base;  // [B+1]
+    int32_t pack_tiles;        // = pack_base[B]
+    int32_t batch;
 };
+
+// largest b in [0, batch) with table[b] <= c, for a non-decreasing table of batch + 1 offsets
+__device__ __forceinline__ int find_seq(const int32_t* table, int batch, int c) {
+    int lo = 0, hi = batch;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (table[mid] <= c) lo = mid; else hi = mid;
+    }
+    return lo;
+}
 
 }  // namespace st
 
@@ -36,14 +51,15 @@ struct st_plan {
     int32_t batch = 0;
     int64_t n_tokens = 0;
     int32_t m_max = 0;
-    std::vector<int32_t> cu_host, slot_base_host;
+    std::vector<int32_t> cu_host, slot_base_host, pack_base_host;
+    int32_t pack_tiles = 0;
     void* ws = nullptr;
     bool owns_ws = false;
     hipStream_t stream = nullptr;
-    int32_t *cu = nullptr, *slot_base = nullptr, *n_src = nullptr, *n_rsn = nullptr;
+    int32_t *cu = nullptr, *slot_base = nullptr, *pack_base = nullptr, *n_src = nullptr, *n_rsn = nullptr;
     int32_t *perm = nullptr, *seg_c = nullptr, *vis = nullptr, *order = nullptr, *cost = nullptr, *flag = nullptr;
     unsigned long long* pairs = nullptr;
     st::WorkItem* items = nullptr;
 
-    st::PlanView view() const { return st::PlanView{cu, n_src, perm, vis, items, order, m_max}; }
+    st::PlanView view() const { return st::PlanView{cu, n_src, perm, vis, items, order, m_max, pack_base, pack_tiles, batch}; }
 };

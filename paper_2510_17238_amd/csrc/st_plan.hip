@@ -21,7 +21,7 @@ static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 static int32_t m_max_bound(int32_t batch, int64_t n_tokens) { return int32_t(n_tokens / kTileM) + 2 * batch; }
 
 struct WsLayout {
-    size_t cu, slot_base, n_src, n_rsn, pairs, flag, perm, seg_c, vis, order, cost, items, total;
+    size_t cu, slot_base, pack_base, n_src, n_rsn, pairs, flag, perm, seg_c, vis, order, cost, items, total;
 };
 
 static WsLayout ws_layout(int32_t batch, int64_t n_tokens) {
@@ -31,6 +31,7 @@ static WsLayout ws_layout(int32_t batch, int64_t n_tokens) {
     auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
     L.cu = take(sizeof(int32_t) * (batch + 1));
     L.slot_base = take(sizeof(int32_t) * (batch + 1));
+    L.pack_base = take(sizeof(int32_t) * (batch + 1));
     L.n_src = take(sizeof(int32_t) * batch);
     L.n_rsn = take(sizeof(int32_t) * batch);
     L.pairs = take(sizeof(unsigned long long) * batch);
@@ -108,15 +109,6 @@ __global__ __launch_bounds__(256) void plan_scan_kernel(const int32_t* __restric
         if (threadIdx.x == 0) s_total += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
         __syncthreads();
     }
-}
-
-__device__ __forceinline__ int find_seq(const int32_t* cu, int batch, int c) {
-    int lo = 0, hi = batch;  // largest b with cu[b] <= c
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (cu[mid] <= c) lo = mid; else hi = mid;
-    }
-    return lo;
 }
 
 // ---- kernel 2: visible source count per compact row, pair counts, validation --
@@ -277,6 +269,14 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
         p->slot_base_host[b + 1] = p->slot_base_host[b] + (n + kTileM - 1) / kTileM + 1;
     }
     p->m_max = p->slot_base_host[batch];   // <= m_max_bound(batch, n_tokens)
+    // key tiles of the packed K / V^T buffers: ceil(S / 64) + ceil(R / 64) <= ceil(N / 64) + 1 per sequence
+    p->pack_base_host.resize(batch + 1);
+    p->pack_base_host[0] = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int n = p->cu_host[b + 1] - p->cu_host[b];
+        p->pack_base_host[b + 1] = p->pack_base_host[b] + (n + kTileN - 1) / kTileN + 1;
+    }
+    p->pack_tiles = p->pack_base_host[batch];
     if (workspace) {
         p->ws = workspace;
     } else {
@@ -290,6 +290,7 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
     char* w = static_cast<char*>(p->ws);
     p->cu = reinterpret_cast<int32_t*>(w + L.cu);
     p->slot_base = reinterpret_cast<int32_t*>(w + L.slot_base);
+    p->pack_base = reinterpret_cast<int32_t*>(w + L.pack_base);
     p->n_src = reinterpret_cast<int32_t*>(w + L.n_src);
     p->n_rsn = reinterpret_cast<int32_t*>(w + L.n_rsn);
     p->pairs = reinterpret_cast<unsigned long long*>(w + L.pairs);
@@ -312,6 +313,8 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
         return bail(e, "copy of cu_seqlens");
     if ((e = hipMemcpyAsync(p->slot_base, p->slot_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
         return bail(e, "copy of slot table");
+    if ((e = hipMemcpyAsync(p->pack_base, p->pack_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
+        return bail(e, "copy of pack table");
     const int nt = int(n_tokens);
     hipLaunchKernelGGL(plan_clear_kernel, dim3(1), dim3(64), 0, s, p->flag);
     hipLaunchKernelGGL(plan_scan_kernel, dim3(batch), dim3(256), 0, s, stream_ids, segment_ids, p->cu, p->n_src,

@@ -9,7 +9,11 @@
 // Inside a run, tiles [0, full) need no mask, tiles [full, total) compare the column
 // index with a per-row limit, tiles past `total` are never read.
 //
-// Two kernels:
+// Kernels:
+//   prefill_pack_kernel   bf16, O(N) bytes: gathers the K rows and the TRANSPOSED V rows of every
+//                         64-row key tile (stream-compact order) into contiguous 16 KB blocks, so
+//                         that the attention kernel streams tiles with plain linear loads and needs
+//                         no per-row token lookup and no transpose in its inner loop.
 //   prefill_mfma_kernel   bf16, 4 waves x 32 query rows, K and V^T tiles double-buffered
 //                         in LDS, QK^T and PV on v_mfma_f32_32x32x16_bf16, fp32 online
 //                         softmax.  Both products are computed TRANSPOSED (S^T = K Q^T,
@@ -157,17 +161,74 @@ struct MfmaSmem {
 __device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 template <int D>
+__global__ __launch_bounds__(256) void prefill_pack_kernel(uint16_t* __restrict__ kc, uint16_t* __restrict__ vc,
+                                                           const uint16_t* __restrict__ k,
+                                                           const uint16_t* __restrict__ v, PlanView pv,
+                                                           int n_kv_heads) {
+    constexpr int KCH = D / 8;
+    constexpr int K_PER_THREAD = kTileN * KCH / 256;
+    constexpr int VQ = D / 4;
+    const int tile = blockIdx.x / n_kv_heads;
+    const int h = blockIdx.x % n_kv_heads;
+    const int b = find_seq(pv.pack_base, pv.batch, tile);
+    const int lt = tile - pv.pack_base[b];
+    const int t0 = pv.cu[b], S = pv.n_src[b], R = pv.cu[b + 1] - t0 - S;
+    const int ts = (S + kTileN - 1) / kTileN, tr = (R + kTileN - 1) / kTileN;
+    if (lt >= ts + tr) return;                      // spare tile of this sequence: never read
+    const bool src = lt < ts;
+    const int kt = src ? lt : lt - ts;
+    const int base = t0 + (src ? 0 : S) + kt * kTileN;
+    const int valid = min(kTileN, (src ? S : R) - kt * kTileN);
+    const int tid = threadIdx.x;
+    const uint32_t row_stride = uint32_t(n_kv_heads) * D;
+    uint16_t* kdst = kc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
+    uint16_t* vdst = vc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
+    // K rows, parked in the row order the first MFMA wants (bits 2 and 3 of the row swapped);
+    // rows past the end of the stream are zero (they are masked, but must be finite)
+#pragma unroll
+    for (int u = 0; u < K_PER_THREAD; ++u) {
+        const int c = tid + 256 * u;
+        const int row = c / KCH, ch = c % KCH;
+        u32x4 val = {0u, 0u, 0u, 0u};
+        if (row < valid) val = *reinterpret_cast<const u32x4*>(k + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + ch * 8));
+        *reinterpret_cast<u32x4*>(kdst + swap23(row) * D + ch * 8) = val;
+    }
+    // V: 8 keys x 4 d per thread, transposed in registers to 4 d x 8 keys
+    const int kvb = tid & 7, dq = tid >> 3;
+    if (dq < VQ) {
+        u32x2 vreg[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int row = kvb * 8 + r;
+            vreg[r] = u32x2{0u, 0u};
+            if (row < valid) vreg[r] = *reinterpret_cast<const u32x2*>(v + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + dq * 4));
+        }
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            u32x4 even, odd;
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                const uint32_t a = vreg[2 * pr][w], bb = vreg[2 * pr + 1][w];
+                even[pr] = __builtin_amdgcn_perm(bb, a, 0x05040100u);   // low halves
+                odd[pr] = __builtin_amdgcn_perm(bb, a, 0x07060302u);    // high halves
+            }
+            *reinterpret_cast<u32x4*>(vdst + (dq * 4 + 2 * w) * kTileN + kvb * 8) = even;
+            *reinterpret_cast<u32x4*>(vdst + (dq * 4 + 2 * w + 1) * kTileN + kvb * 8) = odd;
+        }
+    }
+}
+
+template <int D>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
                                                               const uint16_t* __restrict__ q,
-                                                              const uint16_t* __restrict__ k,
-                                                              const uint16_t* __restrict__ v, PlanView pv,
+                                                              const uint16_t* __restrict__ kc,
+                                                              const uint16_t* __restrict__ vc, PlanView pv,
                                                               int n_q_heads, int n_kv_heads, float scale_log2) {
     constexpr int KS = D / 16;        // MFMA steps of the first product
     constexpr int DB = D / 32;        // 32-wide blocks of the head dimension
     constexpr int SB = kTileN / 32;   // 32-wide blocks of the key tile
     constexpr int KCH = D / 8;        // 16-byte chunks per K row
     constexpr int K_PER_THREAD = kTileN * KCH / 256;
-    constexpr int VQ = D / 4;         // 4-element groups per V row
     extern __shared__ __align__(16) unsigned char smem_raw[];
     MfmaSmem<D>& sm = *reinterpret_cast<MfmaSmem<D>*>(smem_raw);
 
@@ -207,53 +268,33 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
 
     const int n_tiles = it.a_total + it.b_total;
 
-    // ---- tile loader: global -> registers -> LDS ---------------------------
-    u32x4 kreg[K_PER_THREAD];
-    u32x2 vreg[8];
-    const int v_kvb = tid & 7, v_dq = tid >> 3;     // 8-key block, 4-wide d group
-    const bool v_thread = v_dq < VQ;
+    // ---- tile loader: packed tile (16 KB of K, 16 KB of V^T) -> registers -> LDS ----
+    constexpr int V_PER_THREAD = D * kTileN / 8 / 256;
+    u32x4 kreg[K_PER_THREAD], vreg[V_PER_THREAD];
+    const int tile_a0 = pv.pack_base[it.seq] + (it.kind == ST_SOURCE ? 0 : (g.S + kTileN - 1) / kTileN);
+    const int tile_b0 = pv.pack_base[it.seq];
+    const uint16_t* kc_head = kc + size_t(hk) * pv.pack_tiles * (kTileN * D) + tid * 8;
+    const uint16_t* vc_head = vc + size_t(hk) * pv.pack_tiles * (kTileN * D) + tid * 8;
 
     auto load_tile = [&](int ti) {
-        const bool in_a = ti < it.a_total;
-        const int kt = in_a ? ti : ti - it.a_total;
-        const int base = in_a ? g.a_base : g.b_base;
-        const int last = (in_a ? g.n_stream : g.S) - 1;
+        const int tile = ti < it.a_total ? tile_a0 + ti : tile_b0 + (ti - it.a_total);
+        const uint16_t* kp = kc_head + size_t(tile) * (kTileN * D);
+        const uint16_t* vp = vc_head + size_t(tile) * (kTileN * D);
 #pragma unroll
-        for (int u = 0; u < K_PER_THREAD; ++u) {
-            const int c = tid + 256 * u;
-            const int row = c / KCH, ch = c % KCH;
-            const int tok = pv.perm[base + min(kt * kTileN + row, last)];
-            kreg[u] = *reinterpret_cast<const u32x4*>(k + (int64_t(tok) * n_kv_heads + hk) * D + ch * 8);
-        }
-        if (v_thread) {
+        for (int u = 0; u < K_PER_THREAD; ++u) kreg[u] = *reinterpret_cast<const u32x4*>(kp + 256 * 8 * u);
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const int tok = pv.perm[base + min(kt * kTileN + v_kvb * 8 + r, last)];
-                vreg[r] = *reinterpret_cast<const u32x2*>(v + (int64_t(tok) * n_kv_heads + hk) * D + v_dq * 4);
-            }
-        }
+        for (int u = 0; u < V_PER_THREAD; ++u) vreg[u] = *reinterpret_cast<const u32x4*>(vp + 256 * 8 * u);
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < K_PER_THREAD; ++u) {
             const int c = tid + 256 * u;
-            const int row = c / KCH, ch = c % KCH;
-            *reinterpret_cast<u32x4*>(&sm.k[buf][swap23(row)][ch * 8]) = kreg[u];
+            *reinterpret_cast<u32x4*>(&sm.k[buf][c / KCH][(c % KCH) * 8]) = kreg[u];
         }
-        if (v_thread) {
-            // 8 keys x 4 d  ->  4 d x 8 keys
 #pragma unroll
-            for (int w = 0; w < 2; ++w) {
-                u32x4 even, odd;
-#pragma unroll
-                for (int pr = 0; pr < 4; ++pr) {
-                    const uint32_t a = vreg[2 * pr][w], b = vreg[2 * pr + 1][w];
-                    even[pr] = __builtin_amdgcn_perm(b, a, 0x05040100u);   // low halves
-                    odd[pr] = __builtin_amdgcn_perm(b, a, 0x07060302u);    // high halves
-                }
-                *reinterpret_cast<u32x4*>(&sm.vt[buf][v_dq * 4 + 2 * w][v_kvb * 8]) = even;
-                *reinterpret_cast<u32x4*>(&sm.vt[buf][v_dq * 4 + 2 * w + 1][v_kvb * 8]) = odd;
-            }
+        for (int u = 0; u < V_PER_THREAD; ++u) {
+            const int c = tid + 256 * u;
+            *reinterpret_cast<u32x4*>(&sm.vt[buf][c / 8][(c % 8) * 8]) = vreg[u];
         }
     };
 
@@ -261,6 +302,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     store_tile(0);
     __syncthreads();
 
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int ti = 0; ti < n_tiles; ++ti) {
         const int buf = ti & 1;
         const bool more = ti + 1 < n_tiles;
@@ -277,11 +319,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s_acc[sb][i] = 0.f;
-#pragma unroll
             for (int j = 0; j < KS; ++j) {
                 const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sm.k[buf][32 * sb + n][16 * j + 8 * hg]);
-                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], s_acc[sb], 0, 0, 0);
+                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
             }
         }
         // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
@@ -306,6 +346,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         const float m_new = fmaxf(m_run, mx * scale_log2);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        const bool grew = m_new > m_run;                 // the running maximum moved for this row
         m_run = m_new;
         float psum = 0.f;
         bf16x8 pb[SB][2];
@@ -318,10 +359,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
                 pb[sb][i >> 3][i & 7] = (__bf16)p;
             }
         l_run = l_run * alpha + psum;
+        if (__any(grew)) {                               // otherwise alpha == 1 in every lane: skip the rescale
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+                for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+        }
 
         // ---- O^T += V^T P^T --------------------------------------------------
 #pragma unroll
@@ -361,9 +404,20 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
 
 using namespace st;
 
+static size_t prefill_ws_bytes(const st_plan* plan, int n_kv_heads, int head_dim, st_dtype dt) {
+    if (dt != ST_BF16) return 0;                     // the fp32 path reads q / k / v in place
+    return 2 * size_t(n_kv_heads) * size_t(plan->pack_tiles) * kTileN * size_t(head_dim) * sizeof(uint16_t);
+}
+
+extern "C" size_t st_prefill_workspace_bytes(const st_plan* plan, int32_t n_kv_heads, int32_t head_dim, st_dtype dt) {
+    if (!plan || n_kv_heads <= 0 || head_dim <= 0) return 0;
+    return prefill_ws_bytes(plan, n_kv_heads, head_dim, dt);
+}
+
 extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, const void* v,
                                      const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                     float scale, st_dtype dt, void* hip_stream) {
+                                     float scale, st_dtype dt, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
     if (!out || !q || !k || !v || !plan) return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: null pointer");
     if (!aligned16(out) || !aligned16(q) || !aligned16(k) || !aligned16(v))
         return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: tensors must be 16-byte aligned");
@@ -372,9 +426,19 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
     if (head_dim != 64 && head_dim != 128) return fail(ST_ERR_UNSUPPORTED, "st_attn_prefill: head_dim %d (64 or 128)", head_dim);
     if (dt != ST_F32 && dt != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "st_attn_prefill: dtype %d", int(dt));
     if (plan->n_tokens == 0) return ST_OK;
+    if (plan->n_tokens * int64_t(n_q_heads) * head_dim >= (int64_t(1) << 31))
+        return fail(ST_ERR_SHAPE, "st_attn_prefill: n_tokens * n_q_heads * head_dim must stay below 2^31 elements");
+    const size_t need = prefill_ws_bytes(plan, n_kv_heads, head_dim, dt);
+    if (need > 0) {
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+            return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: workspace must be non-null and 256-byte aligned");
+        if (workspace_bytes < need)
+            return fail(ST_ERR_CAPACITY, "st_attn_prefill: workspace has %zu bytes, needs %zu", workspace_bytes, need);
+    }
     if (scale <= 0.f) scale = 1.f / sqrtf(float(head_dim));
     const int64_t blocks = int64_t(plan->m_max) * n_q_heads;
-    if (blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_prefill: grid too large");
+    const int64_t pack_blocks = int64_t(plan->pack_tiles) * n_kv_heads;
+    if (blocks > 0x7fffffff || pack_blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_prefill: grid too large");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const PlanView pv = plan->view();
     if (dt == ST_F32) {
@@ -393,21 +457,27 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
         ST_LAUNCH_CHECK("prefill_simple_kernel");
         return ST_OK;
     }
+    uint16_t* kc = static_cast<uint16_t*>(workspace);
+    uint16_t* vc = kc + need / (2 * sizeof(uint16_t));
     const float scale_log2 = scale * kLog2e;
     if (head_dim == 64) {
         const size_t smem = sizeof(MfmaSmem<64>);
         ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<64>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+        hipLaunchKernelGGL((prefill_pack_kernel<64>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
+                           (const uint16_t*)v, pv, n_kv_heads);
         hipLaunchKernelGGL((prefill_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
-                           (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, pv, n_q_heads, n_kv_heads, scale_log2);
+                           (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
     } else {
         const size_t smem = sizeof(MfmaSmem<128>);
         ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<128>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+        hipLaunchKernelGGL((prefill_pack_kernel<128>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
+                           (const uint16_t*)v, pv, n_kv_heads);
         hipLaunchKernelGGL((prefill_mfma_kernel<128>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
-                           (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, pv, n_q_heads, n_kv_heads, scale_log2);
+                           (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
     }
-    ST_LAUNCH_CHECK("prefill_mfma_kernel");
+    ST_LAUNCH_CHECK("prefill_pack_kernel / prefill_mfma_kernel");
     return ST_OK;
 }
 
@@ -419,8 +489,18 @@ extern "C" st_status st_attn_prefill_ids(void* out, float* lse, const void* q, c
     st_plan* plan = nullptr;
     st_status r = st_plan_create(&plan, segment_ids, stream_ids, positions, cu_seqlens_host, batch, nullptr, 0, 1, hip_stream);
     if (r != ST_OK) return r;
-    r = st_attn_prefill(out, lse, q, k, v, plan, n_q_heads, n_kv_heads, head_dim, scale, dt, hip_stream);
+    void* ws = nullptr;
+    const size_t ws_bytes = (n_kv_heads > 0 && head_dim > 0) ? prefill_ws_bytes(plan, n_kv_heads, head_dim, dt) : 0;
+    if (ws_bytes > 0) {
+        hipError_t e = hipMalloc(&ws, ws_bytes);
+        if (e != hipSuccess) {
+            st_plan_destroy(plan);
+            return fail(ST_ERR_RUNTIME, "st_attn_prefill_ids: hipMalloc(%zu) failed: %s", ws_bytes, hipGetErrorString(e));
+        }
+    }
+    r = st_attn_prefill(out, lse, q, k, v, plan, n_q_heads, n_kv_heads, head_dim, scale, dt, ws, ws_bytes, hip_stream);
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    if (ws) (void)hipFree(ws);
     st_plan_destroy(plan);
     if (r == ST_OK && e != hipSuccess) return fail(ST_ERR_RUNTIME, "st_attn_prefill_ids: %s", hipGetErrorString(e));
     return r;

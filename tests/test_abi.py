@@ -53,7 +53,7 @@ def test_host_side_argument_checks(lib):
     cu = np.array([1, 5], np.int32)
     assert lib.st_plan_create(C.byref(handle), fake, fake, fake, cu.ctypes.data, 1, None, 0, 0, None) == 3
     assert lib.st_plan_workspace_bytes(4, 16000) > 3 * 4 * 16000
-    assert lib.st_attn_prefill(fake, None, fake, fake, fake, None, 4, 2, 64, 0.0, B.ST_BF16, None) == 1
+    assert lib.st_attn_prefill(fake, None, fake, fake, fake, None, 4, 2, 64, 0.0, B.ST_BF16, None, 0, None) == 1
     lib.st_plan_destroy(None)   # ignored
 
 
