@@ -301,6 +301,18 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     load_tile(0);
     store_tile(0);
     __syncthreads();
+    // everything fetched once per work item must have landed before the loop, or the compiler
+    // re-checks for it (and with it for the tile loads in flight) inside every iteration
+    {
+        int t0 = my_vis, t1 = tok_q;
+        asm volatile("" : "+v"(t0), "+v"(t1));
+    }
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        u32x4 t = __builtin_bit_cast(u32x4, qf[j]);
+        asm volatile("" : "+v"(t));
+        qf[j] = __builtin_bit_cast(bf16x8, t);
+    }
 
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int ti = 0; ti < n_tiles; ++ti) {
@@ -315,14 +327,30 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? g.n_stream : g.S);
 
         // ---- S^T = K Q^T : rows = keys, columns = query rows ----------------
+        // the K fragments are fetched from LDS four MFMAs ahead of their use
         f32x16 s_acc[SB];
+        {
+            constexpr int NF = SB * KS, AHEAD = 4;
+            bf16x8 a[NF];
 #pragma unroll
-        for (int sb = 0; sb < SB; ++sb) {
+            for (int f = 0; f < AHEAD; ++f)
+                a[f] = *reinterpret_cast<const bf16x8*>(&sm.k[buf][32 * (f / KS) + n][16 * (f % KS) + 8 * hg]);
 #pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sm.k[buf][32 * sb + n][16 * j + 8 * hg]);
-                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
+            for (int f = 0; f < NF; ++f) {
+                if (f + AHEAD < NF)
+                    a[f + AHEAD] = *reinterpret_cast<const bf16x8*>(
+                        &sm.k[buf][32 * ((f + AHEAD) / KS) + n][16 * ((f + AHEAD) % KS) + 8 * hg]);
+                const int sb = f / KS, j = f % KS;
+                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
             }
+            // keep that order in the instruction stream: AHEAD LDS reads, then one read per MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+            for (int f = 0; f < NF - AHEAD; ++f) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
         }
         // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
         if (partial) {
@@ -367,16 +395,21 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         }
 
         // ---- O^T += V^T P^T --------------------------------------------------
+        {
+            constexpr int NF = DB * SB * 2, AHEAD = 4;
+            bf16x8 a[NF];
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int f = 0; f < AHEAD; ++f)
+                a[f] = *reinterpret_cast<const bf16x8*>(&sm.vt[buf][32 * (f / (SB * 2)) + n][16 * (f % (SB * 2)) + 8 * hg]);
 #pragma unroll
-            for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const bf16x8 a =
-                        *reinterpret_cast<const bf16x8*>(&sm.vt[buf][32 * db + n][32 * sb + 16 * t + 8 * hg]);
-                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[sb][t], o_acc[db], 0, 0, 0);
-                }
+            for (int f = 0; f < NF; ++f) {
+                if (f + AHEAD < NF)
+                    a[f + AHEAD] = *reinterpret_cast<const bf16x8*>(
+                        &sm.vt[buf][32 * ((f + AHEAD) / (SB * 2)) + n][16 * ((f + AHEAD) % (SB * 2)) + 8 * hg]);
+                const int db = f / (SB * 2), st = f % (SB * 2);      // st = 2 sb + t: keys 16 st .. 16 st + 15
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[st >> 1][st & 1], o_acc[db], 0, 0, 0);
+            }
+        }
 
         if (more) store_tile(buf ^ 1);
         __syncthreads();

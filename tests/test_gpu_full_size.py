@@ -1,0 +1,159 @@
+"""Parity at the benchmark configurations' FULL sizes, in the launch configuration bench.py times.
+The oracle cannot run these whole, so outputs are checked on samples it computes row by row
+(first / last rows of segments, rows next to tile boundaries, the final row), and the integer
+metadata is checked in full against the dense-mask reduction or against closed forms.
+Inputs are drawn on the device with a seeded generator and copied to the host for the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import streaming_attention as O
+
+pytestmark = pytest.mark.gpu
+
+from gpu_helpers import DEV, ids_to_dev, to_f64  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def st():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2510_17238_amd as st_
+    st_.load_library()
+    return st_
+
+
+def _device_normal(shape, seed):
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    return torch.randn(shape, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+
+
+def _sample_rows(cfg, b, tile_m, n_extra, rng):
+    """Rows of sequence b (local indices): segment starts / ends, tile-boundary neighbours, last row, random."""
+    s, e = int(cfg.cu_seqlens[b]), int(cfg.cu_seqlens[b + 1])
+    n = e - s
+    seg = cfg.segment_ids[s:e]; strm = cfg.stream_ids[s:e]
+    change = np.nonzero((np.diff(seg) != 0) | (np.diff(strm) != 0))[0]
+    rows = {0, n - 1}
+    for c in change[:: max(1, len(change) // 12)]:
+        rows.update({int(c), int(c) + 1})
+    # rows whose stream-local position sits next to a query-tile boundary
+    pos = cfg.positions[s:e]
+    near = np.nonzero((pos % tile_m == 0) | (pos % tile_m == tile_m - 1))[0]
+    rows.update(int(x) for x in near[:: max(1, len(near) // 12)])
+    rows.update(int(x) for x in rng.integers(0, n, size=n_extra))
+    return np.array(sorted(r for r in rows if 0 <= r < n))
+
+
+def _prefill_full(st, cfg, meta_seqs, n_extra=24):
+    hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
+    q = _device_normal((n, hq, d), cfg.seed); k = _device_normal((n, hkv, d), cfg.seed + 1); v = _device_normal((n, hkv, d), cfg.seed + 2)
+    seg, strm, pos = ids_to_dev(cfg)
+    st.st_rope_apply(q, pos, cfg.theta); st.st_rope_apply(k, pos, cfg.theta)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, validate=True)
+    lse = torch.empty((n, hq), dtype=torch.float32, device=DEV)
+    out = st.st_attn_prefill(q, k, v, plan, lse=lse)
+    torch.cuda.synchronize()
+    bm, bn = plan.tile_shape()
+    # --- metadata: pair counts for every sequence (closed form), full tables for `meta_seqs`
+    assert [int(x) for x in plan.visible_pairs()] == cfg.closed_form_pairs()
+    n_src, n_rsn = plan.stream_counts(); perm = plan.compact_index(); vis = plan.visible_source()
+    for b in range(cfg.batch):
+        assert n_src[b] == int(cfg.src_lens[b].sum()) and n_rsn[b] == int(cfg.rsn_lens[b].sum())
+    for b in meta_seqs:
+        s, e = int(cfg.cu_seqlens[b]), int(cfg.cu_seqlens[b + 1])
+        md = O.canonical_metadata(cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e], bm, bn)
+        S = len(md["src_idx"])
+        assert np.array_equal(perm[s:s + S] - s, md["src_idx"]) and np.array_equal(perm[s + S:e] - s, md["rsn_idx"])
+        assert np.array_equal(vis[s + S:e], md["vis_src"]) and md["visible_pairs"] == cfg.closed_form_pairs()[b]
+        for blk, name in ((st.ST_BLOCK_SS, "SS"), (st.ST_BLOCK_RS, "RS"), (st.ST_BLOCK_RR, "RR")):
+            assert np.array_equal(plan.tile_classes(b, blk), md[name]), (b, name)
+    # --- outputs on sampled rows, every head
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 77))
+    worst = 0.0
+    for b in range(cfg.batch):
+        s, e = int(cfg.cu_seqlens[b]), int(cfg.cu_seqlens[b + 1])
+        rows = _sample_rows(cfg, b, bm, n_extra, rng)
+        ref, ref_lse = O.attention_dense(to_f64(q[s:e]), to_f64(k[s:e]), to_f64(v[s:e]), cfg.stream_ids[s:e],
+                                         cfg.segment_ids[s:e], cfg.positions[s:e], rows=rows)
+        idx = torch.from_numpy(rows + s).to(DEV)
+        err = np.abs(to_f64(out[idx]) - ref).max()
+        worst = max(worst, err)
+        assert err <= 2e-2, (b, err)
+        assert np.abs(to_f64(lse[idx]) - ref_lse).max() <= 2e-2
+    return worst
+
+
+def test_config4a_prefill_16k(st):
+    """Qwen3-4B-shaped layer, 8 x 16,384 tokens: full metadata for two sequences, sampled rows for all."""
+    _prefill_full(st, W.config4a(), meta_seqs=(0, 5))
+
+
+def test_config4b_prefill_128_pairs(st):
+    """Count-pinned variant (128 pairs, about 37K tokens per sequence): full metadata for one sequence."""
+    _prefill_full(st, W.config4b(), meta_seqs=(3,), n_extra=12)
+
+
+def _decode_full(st, shp, q_len, check_seqs, seed):
+    B, hq, hkv, d = shp.batch, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
+    rng = np.random.Generator(np.random.PCG64(seed))
+    pages_s = (shp.max_src_len + 15) // 16; pages_r = (shp.max_rsn_len + 15) // 16
+    tab_s = W.shuffled_page_table(rng, B, pages_s); tab_r = W.shuffled_page_table(rng, B, pages_r)
+    cs = st.KVCache(B * pages_s, B, pages_s, hkv, d, torch.from_numpy(tab_s).to(DEV))
+    cr = st.KVCache(B * pages_r, B, pages_r, hkv, d, torch.from_numpy(tab_r).to(DEV))
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    for c in (cs, cr):       # any bit pattern is a valid cache content: draw the pools directly
+        c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
+    caches = st.DualCache(cs, cr)
+    # the step itself: append the q_len new reasoning tokens, then attend
+    rsn_before = (shp.rsn_len - q_len).astype(np.int32)
+    cs.appended_len.copy_(torch.from_numpy(shp.src_visible_len)); cr.appended_len.copy_(torch.from_numpy(rsn_before))
+    k_tok = _device_normal((B, q_len, hkv, d), seed + 1); v_tok = _device_normal((B, q_len, hkv, d), seed + 2)
+    q = _device_normal((B, q_len, hq, d), seed + 3)
+    st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=int(shp.rsn_len.max()))
+    # a source chunk arriving on a second stream while the decode runs (not yet visible)
+    k_src = _device_normal((B, shp.src_append, hkv, d), seed + 4)
+    side = torch.cuda.Stream(); side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.st_kv_append(caches, st.ST_SOURCE, k_src, k_src, host_len_upper_bound=shp.max_src_len, stream=side)
+    vis = torch.from_numpy(shp.src_visible_len).to(DEV); rl = torch.from_numpy(shp.rsn_len).to(DEV)
+    lse = torch.empty((B, q_len, hq), dtype=torch.float32, device=DEV)
+    out = st.st_attn_decode_dual(q, caches, vis, rl, int(shp.src_visible_len.max()), int(shp.rsn_len.max()), lse=lse)
+    torch.cuda.synchronize()
+    assert cr.appended_len.cpu().tolist() == shp.rsn_len.tolist()
+    assert cs.appended_len.cpu().tolist() == (shp.src_visible_len + shp.src_append).tolist()
+    assert torch.isfinite(out).all()
+    for b in check_seqs:
+        def gather(cache, tab, length):
+            ids = torch.from_numpy(tab[b, :(length + 15) // 16].astype(np.int64)).to(DEV)
+            kl = st.k_pool_to_logical(cache.k_pool[ids]).reshape(-1, hkv, d)[:length]
+            vl = st.v_pool_to_logical(cache.v_pool[ids]).reshape(-1, hkv, d)[:length]
+            return to_f64(kl), to_f64(vl)
+        sk, sv = gather(cs, tab_s, int(shp.src_visible_len[b]))
+        rk, rv = gather(cr, tab_r, int(shp.rsn_len[b]))
+        # the appended tokens really are the last q_len rows of the reasoning cache
+        assert np.array_equal(rk[-q_len:], to_f64(k_tok[b])) and np.array_equal(rv[-q_len:], to_f64(v_tok[b]))
+        o_ref, l_ref = O.decode_dual_concat(to_f64(q[b]), sk, sv, rk, rv, int(shp.src_visible_len[b]), int(shp.rsn_len[b]))
+        assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
+        assert np.abs(to_f64(lse[b]) - l_ref).max() <= 2e-2, b
+
+
+def test_config3_decode_one_layer(st):
+    """Qwen3-1.7B-shaped decode step (batch 32, 2K source + 1-6K reasoning), one of the 28 identical layers."""
+    shp = W.config3()
+    longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
+    _decode_full(st, shp, 1, sorted({0, 7, longest, shortest}), seed=31)
+
+
+def test_config5_stream_step_one_layer(st):
+    """Qwen3-8B-shaped streaming step (batch 64, caches to 8K / 16K, 32-token appends), one layer, q_len = 1."""
+    shp = W.config5()
+    longest = int(np.argmax(shp.rsn_len + shp.src_visible_len))
+    _decode_full(st, shp, 1, sorted({1, 33, longest}), seed=51)
+
+
+def test_config5_eight_tokens_in_one_call(st):
+    """The same shape with the step's 8 reasoning tokens decoded in a single call (q_len = 8, causal among them)."""
+    shp = W.config5(batch=16)
+    _decode_full(st, shp, 8, [0, 9], seed=52)
