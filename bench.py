@@ -27,6 +27,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
+# HBM bytes per launch of the two dominant kernels on the default workloads, from the FETCH_SIZE and
+# WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB copy (x2.000 and x1.000);
+# see profiles/hbm_traffic_prefill_cfg2_decode_cfg3.txt for the runs.
+MEASURED_TRAFFIC = {"prefill_mfma_kernel<128>": 261.9e6 + 65.7e6, "decode_split16_kernel<128>": 702.5e6 + 3.0e6}
+
 
 def _median(xs):
     return float(np.median(np.asarray(xs, dtype=np.float64)))
@@ -86,7 +91,6 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     dec_ws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream()
     main = torch.cuda.current_stream()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
 
     def step(i_timed):
         cs.appended_len.copy_(len_s0); cr.appended_len.copy_(len_r0)      # same state every step
@@ -96,11 +100,7 @@ def bench_prefill_step(st, torch, W, steps, warmup):
         p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
         st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
         st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
-        if i_timed is not None:
-            ev[i_timed][0].record()
         st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
-        if i_timed is not None:
-            ev[i_timed][1].record()
         st.st_rope_apply(q_tok.view(batch, hq, d), pos_tok, cfg.theta)
         st.st_rope_apply(k_tok.view(batch, hkv, d), pos_tok, cfg.theta)
         st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
@@ -112,16 +112,19 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     for _ in range(warmup):
         plans.append(step(None))
     torch.cuda.synchronize()
+    st.st_profile_enable(True)            # HIP events around the attention kernel, on its launch stream
     t0 = time.perf_counter()
     for i in range(steps):
         plans.append(step(i))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    st.st_profile_enable(False)
+    kern_ms, n_rec = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    assert n_rec == steps
     for p in plans:
         p.destroy()
-    kern_ms = [a.elapsed_time(b) for a, b in ev]
-    return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": float(np.mean(kern_ms)),
-            "prefill_kernel_ms_median": _median(kern_ms), "n_tokens": n}
+    return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": kern_ms, "n_tokens": n}
 
 
 def bench_decode(st, torch, W, steps, warmup, n_layers=None):
@@ -153,7 +156,6 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None):
     max_s, max_r = int(shp.src_visible_len.max()), int(shp.rsn_len.max())
     ws = torch.empty(st.st_decode_workspace_bytes(B, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream(); main = torch.cuda.current_stream()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
 
     def step(i_timed):
         len_s_all.copy_(src_vis.expand(L, B)); len_r_all.copy_(rsn_before.expand(L, B))
@@ -162,25 +164,24 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None):
             with torch.cuda.stream(side):
                 st.st_kv_append(dc, st.ST_SOURCE, k_src, v_src, host_len_upper_bound=shp.max_src_len, stream=side)
             st.st_kv_append(dc, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
-            if i_timed is not None and li == L - 1:
-                ev[i_timed][0].record()
             st.st_attn_decode_dual(q, dc, src_vis, rsn_len, max_s, max_r, out=out, workspace=ws)
-            if i_timed is not None and li == L - 1:
-                ev[i_timed][1].record()
         main.wait_stream(side)
 
     for _ in range(warmup):
         step(None)
     torch.cuda.synchronize()
+    st.st_profile_enable(True)            # HIP events around every layer's split kernel
     t0 = time.perf_counter()
     for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    st.st_profile_enable(False)
+    layer_ms, n_rec = st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    assert n_rec == steps * L
     tokens = float((shp.src_visible_len.astype(np.int64) + shp.rsn_len).sum())
     per_layer = tokens * 2 * hkv * d * 2
     append_bytes = float(B * (shp.src_append + 1)) * 2 * hkv * d * 2 * 2 * L
-    layer_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
     return {"shape": shp, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
             "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer}
 
@@ -213,6 +214,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU; there is no multi-GPU mode (sequences and KV heads shard "
@@ -226,6 +229,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
 
+    if args.copy_calibration:
+        a = torch.full((1 << 29,), 1.0, dtype=torch.bfloat16, device="cuda"); b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": a.numel() * 2, "bytes_written_per_copy": a.numel() * 2, "copies": 5}))
+        return
     pre = bench_prefill_step(st, torch, W, args.steps, args.warmup)
     cfg = pre["cfg"]
     tflops_step = pre["flops"] / pre["sec_per_step"] / 1e12
@@ -243,7 +253,7 @@ def main():
         "prefill_pct_of_peak": round(100.0 * tflops_kernel / PEAK_BF16_TFLOPS, 2),
         "roofline": {"kernel": "prefill_mfma_kernel<128>", "bound": "mfma", "achieved": round(tflops_kernel, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4)},
+                     "traffic": MEASURED_TRAFFIC["prefill_mfma_kernel<128>"], "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4)},
     }
     if not args.no_decode:
         dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
@@ -258,9 +268,9 @@ def main():
             "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
             "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
             "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
-            "roofline": {"kernel": "decode_split_kernel<128> + decode_combine_kernel<128> (one layer)", "bound": "hbm",
+            "roofline": {"kernel": "decode_split16_kernel<128> (one layer)", "bound": "hbm",
                          "achieved": round(gbps_kernel, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                         "frac": round(gbps_kernel / PEAK_HBM_GBPS, 4), "traffic": None,
+                         "frac": round(gbps_kernel / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["decode_split16_kernel<128>"],
                          "avg_kernel_ms": round(dec["layer_decode_ms"], 4)},
         }
     if not args.no_cpu_baseline:

@@ -60,6 +60,14 @@ const char* st_last_error(void);
 /* Library version (major * 100 + minor). */
 int32_t st_version(void);
 
+/* Optional kernel timing for benchmarks.  While enabled, st_attn_prefill brackets its attention
+ * kernel (ST_PROF_PREFILL_ATTN) and st_attn_decode_dual its split kernel (ST_PROF_DECODE_SPLIT)
+ * with HIP events on the launch stream.  st_profile_read WAITS for the recorded launches, returns
+ * their mean duration in milliseconds and their number in host variables, and forgets them. */
+enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1 };
+void st_profile_enable(int32_t on);
+st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
+
 /* ------------------------------------------------------------------------
  * st_rope_apply -- rotary position encoding with caller-supplied (stream-local)
  * position ids.  Sec. 3.2 "Streaming Position Encoding": input tokens and

@@ -61,6 +61,10 @@ def load_library():
     lib.st_last_error.argtypes = []
     lib.st_version.restype = i32
     lib.st_version.argtypes = []
+    lib.st_profile_enable.restype = None
+    lib.st_profile_enable.argtypes = [i32]
+    lib.st_profile_read.restype = i32
+    lib.st_profile_read.argtypes = [i32, C.POINTER(f64), C.POINTER(i32)]
     lib.st_rope_apply.restype = i32
     lib.st_rope_apply.argtypes = [vp, vp, vp, i64, i32, i32, f64, i32, vp]
     lib.st_plan_workspace_bytes.restype = sz
@@ -130,6 +134,20 @@ def st_version():
 
 def st_last_error():
     return load_library().st_last_error().decode()
+
+
+ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT = 0, 1
+
+
+def st_profile_enable(on):
+    load_library().st_profile_enable(1 if on else 0)
+
+
+def st_profile_read(which):
+    """(mean milliseconds, count) of the kernel launches recorded since the last read."""
+    ms, n = C.c_double(), C.c_int32()
+    _check(load_library().st_profile_read(which, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 # ------------------------------------------------------------------ RoPE --

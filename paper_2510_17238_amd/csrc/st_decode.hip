@@ -464,8 +464,10 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
         const dim3 grid((unsigned)((units + 3) / 4)), block(256);
         if (a.rows <= 16) {
             if (units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
+            prof_begin(kProfDecodeSplit, s);
             if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
             else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
+            prof_end(kProfDecodeSplit, s);
         } else {
             if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
             else hipLaunchKernelGGL((decode_split_kernel<128>), grid, block, 0, s, a);

@@ -1,6 +1,9 @@
 // Error text and version of the C ABI.
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "st_internal.h"
 
 namespace st {
@@ -14,6 +17,58 @@ void set_error(const char* fmt, ...) {
 }
 const char* get_error() { return g_error; }
 }  // namespace st
+
+namespace st {
+namespace {
+struct Region { hipEvent_t a, b; };
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<Region> g_regions[kProfCount];
+}  // namespace
+
+bool prof_enabled() { return g_prof_on; }
+
+void prof_begin(int which, hipStream_t stream) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    Region r{};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    (void)hipEventRecord(r.a, stream);
+    g_regions[which].push_back(r);
+}
+
+void prof_end(int which, hipStream_t stream) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_regions[which].empty()) (void)hipEventRecord(g_regions[which].back().b, stream);
+}
+}  // namespace st
+
+extern "C" void st_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lock(st::g_prof_mutex);
+    st::g_prof_on = on != 0;
+}
+
+extern "C" st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count) {
+    using namespace st;
+    if (which < 0 || which >= kProfCount || !mean_ms || !count) return fail(ST_ERR_INVALID_ARG, "st_profile_read: bad argument");
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    double total = 0.0;
+    int n = 0;
+    for (Region& r : g_regions[which]) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            total += ms;
+            ++n;
+        }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_regions[which].clear();
+    *mean_ms = n ? total / n : 0.0;
+    *count = n;
+    return ST_OK;
+}
 
 extern "C" const char* st_last_error(void) { return st::get_error(); }
 extern "C" int32_t st_version(void) { return 1; }

@@ -37,6 +37,13 @@ inline st_status fail(st_status code, const char* fmt, ...) {
             return st::fail(ST_ERR_RUNTIME, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
     } while (0)
 
+// Optional kernel timing (st_profile_enable): HIP events recorded on the launch stream right
+// before and after one kernel, read back by st_profile_read.
+enum { kProfPrefillAttn = 0, kProfDecodeSplit = 1, kProfCount = 2 };
+bool prof_enabled();
+void prof_begin(int which, hipStream_t stream);
+void prof_end(int which, hipStream_t stream);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---- device-side vector types -------------------------------------------

@@ -499,16 +499,20 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
         hipLaunchKernelGGL((prefill_pack_kernel<64>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
                            (const uint16_t*)v, pv, n_kv_heads);
+        prof_begin(kProfPrefillAttn, s);
         hipLaunchKernelGGL((prefill_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
                            (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
+        prof_end(kProfPrefillAttn, s);
     } else {
         const size_t smem = sizeof(MfmaSmem<128>);
         ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<128>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
         hipLaunchKernelGGL((prefill_pack_kernel<128>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
                            (const uint16_t*)v, pv, n_kv_heads);
+        prof_begin(kProfPrefillAttn, s);
         hipLaunchKernelGGL((prefill_mfma_kernel<128>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
                            (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
+        prof_end(kProfPrefillAttn, s);
     }
     ST_LAUNCH_CHECK("prefill_pack_kernel / prefill_mfma_kernel");
     return ST_OK;
