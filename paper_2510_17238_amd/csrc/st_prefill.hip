@@ -148,12 +148,29 @@ __global__ __launch_bounds__(kTileM) void prefill_simple_kernel(T* __restrict__ 
 // --------------------------------------------------------------------------
 // MFMA kernel (bf16).
 // --------------------------------------------------------------------------
+// One wave-wide asynchronous copy global -> LDS: lane l's 16 bytes at `g` land at LDS byte offset
+// lds_off + 16 l (lds_off must be wave-uniform).  Completion is counted by vmcnt like any load.
+__device__ __forceinline__ void async_copy16(const void* g, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_off) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// LDS tiles of the MFMA kernel: no padding; inside every row the 16-byte chunks are stored at
+// position chunk ^ key(row).  The LDS has 64 four-byte banks, so a 16-byte operand read serves 16
+// lanes (16 consecutive rows) per cycle, and the key must send those 16 rows to 16 different
+// 16-byte columns of the 256-byte bank line: key = row % 16 for 256-byte rows, (row / 2) % 8 for
+// 128-byte rows (two rows per bank line).  The packed global tiles already have this arrangement,
+// so a tile travels global -> LDS as a plain linear copy.
+template <int ROW_BYTES>
+__device__ __forceinline__ int swizzle_key(int row) { return ROW_BYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
+
 template <int D>
 struct MfmaSmem {
-    static constexpr int KP = D + 8;            // K row pitch (elements): 16 B of padding
-    static constexpr int VP = kTileN + 8;       // V^T row pitch
-    uint16_t k[2][kTileN][KP];
-    uint16_t vt[2][D][VP];
+    uint16_t k[2][kTileN * D];        // [row][D], rows in MFMA order
+    uint16_t vt[2][D * kTileN];       // [d][64 keys]
 };
 
 // swap bits 2 and 3: the row order in which K is parked in LDS, so that after the
@@ -183,15 +200,17 @@ __global__ __launch_bounds__(256) void prefill_pack_kernel(uint16_t* __restrict_
     const uint32_t row_stride = uint32_t(n_kv_heads) * D;
     uint16_t* kdst = kc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
     uint16_t* vdst = vc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
-    // K rows, parked in the row order the first MFMA wants (bits 2 and 3 of the row swapped);
-    // rows past the end of the stream are zero (they are masked, but must be finite)
+    // K rows, parked in the row order the first MFMA wants (bits 2 and 3 of the row swapped) and with
+    // the chunk swizzle of the LDS tile; rows past the end of the stream are zero (they are masked,
+    // but must be finite)
 #pragma unroll
     for (int u = 0; u < K_PER_THREAD; ++u) {
         const int c = tid + 256 * u;
         const int row = c / KCH, ch = c % KCH;
         u32x4 val = {0u, 0u, 0u, 0u};
         if (row < valid) val = *reinterpret_cast<const u32x4*>(k + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + ch * 8));
-        *reinterpret_cast<u32x4*>(kdst + swap23(row) * D + ch * 8) = val;
+        const int lr = swap23(row);                                    // row position in the tile
+        *reinterpret_cast<u32x4*>(kdst + lr * D + (ch ^ swizzle_key<2 * D>(lr)) * 8) = val;
     }
     // V: 8 keys x 4 d per thread, transposed in registers to 4 d x 8 keys
     const int kvb = tid & 7, dq = tid >> 3;
@@ -212,8 +231,9 @@ __global__ __launch_bounds__(256) void prefill_pack_kernel(uint16_t* __restrict_
                 even[pr] = __builtin_amdgcn_perm(bb, a, 0x05040100u);   // low halves
                 odd[pr] = __builtin_amdgcn_perm(bb, a, 0x07060302u);    // high halves
             }
-            *reinterpret_cast<u32x4*>(vdst + (dq * 4 + 2 * w) * kTileN + kvb * 8) = even;
-            *reinterpret_cast<u32x4*>(vdst + (dq * 4 + 2 * w + 1) * kTileN + kvb * 8) = odd;
+            const int d0 = dq * 4 + 2 * w;
+            *reinterpret_cast<u32x4*>(vdst + d0 * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0)) * 8) = even;
+            *reinterpret_cast<u32x4*>(vdst + (d0 + 1) * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0 + 1)) * 8) = odd;
         }
     }
 }
@@ -227,8 +247,6 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     constexpr int KS = D / 16;        // MFMA steps of the first product
     constexpr int DB = D / 32;        // 32-wide blocks of the head dimension
     constexpr int SB = kTileN / 32;   // 32-wide blocks of the key tile
-    constexpr int KCH = D / 8;        // 16-byte chunks per K row
-    constexpr int K_PER_THREAD = kTileN * KCH / 256;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     MfmaSmem<D>& sm = *reinterpret_cast<MfmaSmem<D>*>(smem_raw);
 
@@ -268,41 +286,54 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
 
     const int n_tiles = it.a_total + it.b_total;
 
-    // ---- tile loader: packed tile (16 KB of K, 16 KB of V^T) -> registers -> LDS ----
-    constexpr int V_PER_THREAD = D * kTileN / 8 / 256;
-    u32x4 kreg[K_PER_THREAD], vreg[V_PER_THREAD];
+    // ---- tile loader: packed tile -> LDS, asynchronously, no registers in between ----
+    // Every wave copies a quarter of each tile with global_load_lds_dwordx4 (lane l of one such load
+    // deposits its 16 bytes at LDS base + 16 l).  Two K and two V^T buffers; a buffer is refilled as
+    // soon as its tile has been consumed by all four waves:
+    //   K(t+2) is requested right after the first product of tile t, V^T(t+1) at the top of tile t,
+    // which gives every tile more than one full iteration to arrive.  The loads of one wave complete
+    // in order, so "my part of tile X has landed" is s_waitcnt vmcnt(<loads issued after X>), and the
+    // barrier that follows makes all four parts visible to everybody.
+    constexpr int NL = kTileN * D * 2 / 1024 / 4;    // 1 KB loads per wave per tile (K or V^T)
     const int tile_a0 = pv.pack_base[it.seq] + (it.kind == ST_SOURCE ? 0 : (g.S + kTileN - 1) / kTileN);
     const int tile_b0 = pv.pack_base[it.seq];
-    const uint16_t* kc_head = kc + size_t(hk) * pv.pack_tiles * (kTileN * D) + tid * 8;
-    const uint16_t* vc_head = vc + size_t(hk) * pv.pack_tiles * (kTileN * D) + tid * 8;
-
-    auto load_tile = [&](int ti) {
-        const int tile = ti < it.a_total ? tile_a0 + ti : tile_b0 + (ti - it.a_total);
-        const uint16_t* kp = kc_head + size_t(tile) * (kTileN * D);
-        const uint16_t* vp = vc_head + size_t(tile) * (kTileN * D);
-#pragma unroll
-        for (int u = 0; u < K_PER_THREAD; ++u) kreg[u] = *reinterpret_cast<const u32x4*>(kp + 256 * 8 * u);
-#pragma unroll
-        for (int u = 0; u < V_PER_THREAD; ++u) vreg[u] = *reinterpret_cast<const u32x4*>(vp + 256 * 8 * u);
+    const size_t head_off = size_t(hk) * pv.pack_tiles * (kTileN * D) + (wave * NL) * 512 + lane * 8;
+    const uint16_t* kc_lane = kc + head_off;
+    const uint16_t* vc_lane = vc + head_off;
+    auto tile_of = [&](int ti) {
+        ti = min(ti, n_tiles - 1);                   // past the end: fetch the last tile again (never read)
+        return ti < it.a_total ? tile_a0 + ti : tile_b0 + (ti - it.a_total);
     };
-    auto store_tile = [&](int buf) {
+    // (the copies are issued through inline assembly so that the compiler does not track them: knowing
+    // of a pending copy into LDS it would wait for ALL of them before every barrier)
+    const uint32_t lds_k0 = uint32_t(uintptr_t(&sm.k[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
+    const uint32_t lds_v0 = uint32_t(uintptr_t(&sm.vt[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
+    auto issue_k = [&](int ti, int buf) {
+        const uint16_t* src = kc_lane + size_t(tile_of(ti)) * (kTileN * D);
 #pragma unroll
-        for (int u = 0; u < K_PER_THREAD; ++u) {
-            const int c = tid + 256 * u;
-            *reinterpret_cast<u32x4*>(&sm.k[buf][c / KCH][(c % KCH) * 8]) = kreg[u];
-        }
+        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_k0 + buf * (kTileN * D * 2) + u * 1024);
+    };
+    auto issue_v = [&](int ti, int buf) {
+        const uint16_t* src = vc_lane + size_t(tile_of(ti)) * (kTileN * D);
 #pragma unroll
-        for (int u = 0; u < V_PER_THREAD; ++u) {
-            const int c = tid + 256 * u;
-            *reinterpret_cast<u32x4*>(&sm.vt[buf][c / 8][(c % 8) * 8]) = vreg[u];
-        }
+        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_v0 + buf * (kTileN * D * 2) + u * 1024);
     };
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
+    // operand addresses: lane (n, hg) reads chunk (2 j + hg) ^ key(row) = (2 j) ^ (key ^ hg) of its row
+    int koff[KS], voff[4];
+    {
+        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
+    }
+
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
     // everything fetched once per work item must have landed before the loop, or the compiler
-    // re-checks for it (and with it for the tile loads in flight) inside every iteration
+    // re-checks for it inside every iteration
     {
         int t0 = my_vis, t1 = tok_q;
         asm volatile("" : "+v"(t0), "+v"(t1));
@@ -317,13 +348,15 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int ti = 0; ti < n_tiles; ++ti) {
         const int buf = ti & 1;
-        const bool more = ti + 1 < n_tiles;
-        if (more) load_tile(ti + 1);
+        // K(ti) has landed (still in flight behind it: V^T(ti), K(ti+1)); everybody is done with tile ti-1
+        wait_vmcnt<2 * NL>();
+        __syncthreads();
+        issue_v(ti + 1, buf ^ 1);
 
         const bool in_a = ti < it.a_total;
         const int kt = in_a ? ti : ti - it.a_total;
         // a ragged last tile is FULL as far as the mask goes, but its out-of-range columns
-        // (filled with a repeated row by the loader) still have to be compared away
+        // (zero rows in the packed tile) still have to be compared away
         const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? g.n_stream : g.S);
 
         // ---- S^T = K Q^T : rows = keys, columns = query rows ----------------
@@ -331,15 +364,17 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         f32x16 s_acc[SB];
         {
             constexpr int NF = SB * KS, AHEAD = 4;
+            const uint16_t* kb = &sm.k[buf][0];
             bf16x8 a[NF];
 #pragma unroll
             for (int f = 0; f < AHEAD; ++f)
-                a[f] = *reinterpret_cast<const bf16x8*>(&sm.k[buf][32 * (f / KS) + n][16 * (f % KS) + 8 * hg]);
+                a[f] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f / KS) * D + koff[f % KS]);
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
-                if (f + AHEAD < NF)
-                    a[f + AHEAD] = *reinterpret_cast<const bf16x8*>(
-                        &sm.k[buf][32 * ((f + AHEAD) / KS) + n][16 * ((f + AHEAD) % KS) + 8 * hg]);
+                if (f + AHEAD < NF) {
+                    const int f2 = f + AHEAD;
+                    a[f2] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f2 / KS) * D + koff[f2 % KS]);
+                }
                 const int sb = f / KS, j = f % KS;
                 s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
             }
@@ -352,6 +387,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
             }
             __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
         }
+        // V^T(ti) has landed (behind it: K(ti+1), V^T(ti+1)); everybody has read K(ti)
+        wait_vmcnt<2 * NL>();
+        __syncthreads();
+        issue_k(ti + 2, buf);
+
         // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
         if (partial) {
             const int limit = in_a ? my_row + 1 : my_vis;
@@ -397,23 +437,22 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         // ---- O^T += V^T P^T --------------------------------------------------
         {
             constexpr int NF = DB * SB * 2, AHEAD = 4;
+            const uint16_t* vb = &sm.vt[buf][0];
             bf16x8 a[NF];
 #pragma unroll
-            for (int f = 0; f < AHEAD; ++f)
-                a[f] = *reinterpret_cast<const bf16x8*>(&sm.vt[buf][32 * (f / (SB * 2)) + n][16 * (f % (SB * 2)) + 8 * hg]);
+            for (int f = 0; f < AHEAD; ++f) a[f] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f / (SB * 2)) * kTileN + voff[f % (SB * 2)]);
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
-                if (f + AHEAD < NF)
-                    a[f + AHEAD] = *reinterpret_cast<const bf16x8*>(
-                        &sm.vt[buf][32 * ((f + AHEAD) / (SB * 2)) + n][16 * ((f + AHEAD) % (SB * 2)) + 8 * hg]);
+                if (f + AHEAD < NF) {
+                    const int f2 = f + AHEAD;
+                    a[f2] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f2 / (SB * 2)) * kTileN + voff[f2 % (SB * 2)]);
+                }
                 const int db = f / (SB * 2), st = f % (SB * 2);      // st = 2 sb + t: keys 16 st .. 16 st + 15
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[st >> 1][st & 1], o_acc[db], 0, 0, 0);
             }
         }
-
-        if (more) store_tile(buf ^ 1);
-        __syncthreads();
     }
+    wait_vmcnt<0>();                                     // no copy into LDS may outlive the workgroup
 
     // ---- epilogue ------------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
