@@ -18,15 +18,23 @@ struct WorkItem {
     int32_t n_rows;   // 0 marks an unused slot
     int32_t a_full, a_total;
     int32_t b_full, b_total;
+    // everything else a kernel needs about the item's sequence, so that one 64-byte load suffices
+    int32_t a_base;   // compact row of column 0 of block A (start of the row's own stream)
+    int32_t b_base;   // compact row of column 0 of block B (start of the source stream)
+    int32_t n_stream; // tokens of the row's own stream
+    int32_t n_src;    // source tokens of the sequence
+    int32_t tile_a0;  // packed key tile of column 0 of block A
+    int32_t tile_b0;  // packed key tile of column 0 of block B
+    int32_t pad0, pad1;
 };
+static_assert(sizeof(WorkItem) == 64, "WorkItem is one 64-byte record");
 
 struct PlanView {  // what kernels need
     const int32_t* cu;       // [B+1] token offsets
     const int32_t* n_src;    // [B]
     const int32_t* perm;     // [N] compact row -> token index
     const int32_t* vis;      // [N] visible source count per compact row
-    const WorkItem* items;   // [m_max]
-    const int32_t* order;    // [m_max] longest-first permutation of item slots
+    const WorkItem* sorted;  // [m_max] work items, longest first (unused slots last)
     int32_t m_max;
     // Packed K / V^T buffers (bf16 path): sequence b owns key tiles [pack_base[b], pack_base[b+1]) of
     // kTileN rows each: first ceil(S / kTileN) source tiles, then the reasoning tiles.
@@ -57,9 +65,10 @@ struct st_plan {
     bool owns_ws = false;
     hipStream_t stream = nullptr;
     int32_t *cu = nullptr, *slot_base = nullptr, *pack_base = nullptr, *n_src = nullptr, *n_rsn = nullptr;
-    int32_t *perm = nullptr, *seg_c = nullptr, *vis = nullptr, *order = nullptr, *cost = nullptr, *flag = nullptr;
+    int32_t *perm = nullptr, *seg_c = nullptr, *vis = nullptr, *cost = nullptr, *flag = nullptr;
     unsigned long long* pairs = nullptr;
-    st::WorkItem* items = nullptr;
+    st::WorkItem* items = nullptr;    // slot order (sequence by sequence)
+    st::WorkItem* sorted = nullptr;   // longest first
 
-    st::PlanView view() const { return st::PlanView{cu, n_src, perm, vis, items, order, m_max, pack_base, pack_tiles, batch}; }
+    st::PlanView view() const { return st::PlanView{cu, n_src, perm, vis, sorted, m_max, pack_base, pack_tiles, batch}; }
 };

@@ -9,7 +9,8 @@
 // (reasoning rows x a prefix of the source stream), and a reasoning row needs just
 // one number: how many source tokens it sees.
 //
-// All tables are built by four small integer kernels, O(N) work, no host round trip.
+// All tables are built by three small integer kernels (init, per-sequence scan, work items), O(N)
+// work, no host round trip.
 #include <new>
 
 #include "st_plan.h"
@@ -21,7 +22,7 @@ static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 static int32_t m_max_bound(int32_t batch, int64_t n_tokens) { return int32_t(n_tokens / kTileM) + 2 * batch; }
 
 struct WsLayout {
-    size_t cu, slot_base, pack_base, n_src, n_rsn, pairs, flag, perm, seg_c, vis, order, cost, items, total;
+    size_t cu, slot_base, pack_base, n_src, n_rsn, pairs, flag, perm, seg_c, vis, cost, items, sorted, total;
 };
 
 static WsLayout ws_layout(int32_t batch, int64_t n_tokens) {
@@ -39,57 +40,83 @@ static WsLayout ws_layout(int32_t batch, int64_t n_tokens) {
     L.perm = take(sizeof(int32_t) * n_tokens);
     L.seg_c = take(sizeof(int32_t) * n_tokens);
     L.vis = take(sizeof(int32_t) * n_tokens);
-    L.order = take(sizeof(int32_t) * m);
     L.cost = take(sizeof(int32_t) * m);
     L.items = take(sizeof(WorkItem) * m);
+    L.sorted = take(sizeof(WorkItem) * m);
     L.total = off;
     return L;
 }
 
-// ---- kernel 0: clear the validation flag (a fill kernel, so that the whole
-// build can be recorded into a HIP graph) --------------------------------------
+constexpr int kPlanThreads = 1024;
+constexpr int kTablesMaxBatch = 64;      // up to this batch the three host tables travel as kernel arguments
+
+struct HostTables {                      // cu_seqlens | item slot bases | packed tile bases, batch + 1 entries each
+    int32_t v[3 * (kTablesMaxBatch + 1)];
+};
+
+// ---- kernel 0: publish the host tables (passed by value, no copy engine involved) and clear the
+// validation flag; a fill kernel, so that the whole build can be recorded into a HIP graph ----------
+__global__ void plan_init_kernel(HostTables t, int batch, int32_t* __restrict__ cu, int32_t* __restrict__ slot_base,
+                                 int32_t* __restrict__ pack_base, int32_t* __restrict__ flag) {
+    for (int i = threadIdx.x; i <= batch; i += blockDim.x) {
+        cu[i] = t.v[i];
+        slot_base[i] = t.v[(batch + 1) + i];
+        pack_base[i] = t.v[2 * (batch + 1) + i];
+    }
+    if (threadIdx.x == 0) *flag = 0;
+}
 __global__ void plan_clear_kernel(int32_t* flag) {
     if (threadIdx.x == 0) *flag = 0;
 }
 
-// ---- kernel 1: per sequence, rank every token inside its stream ------------
-// One workgroup per sequence.  Writes perm / seg_c in grouped compact order and
-// the two stream sizes; clears the pair counter.
-__global__ __launch_bounds__(256) void plan_scan_kernel(const int32_t* __restrict__ stream_ids,
-                                                        const int32_t* __restrict__ segment_ids,
-                                                        const int32_t* __restrict__ cu,
-                                                        int32_t* __restrict__ n_src, int32_t* __restrict__ n_rsn,
-                                                        int32_t* __restrict__ perm, int32_t* __restrict__ seg_c,
-                                                        unsigned long long* __restrict__ pairs,
-                                                        int32_t* __restrict__ flag) {
-    __shared__ int s_wave[4];
+__device__ __forceinline__ int block_sum(int v, int* s_wave) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if (lane == 0) s_wave[wave] = v;
+    __syncthreads();
+    int tot = 0;
+    for (int w = 0; w < kPlanThreads / 64; ++w) tot += s_wave[w];
+    return tot;
+}
+
+// ---- kernel 1: one workgroup per sequence ------------------------------------------------------
+// (1) rank every token inside its stream -> perm / seg_c in grouped compact order, stream sizes;
+// (2) per compact row the number of visible source tokens (binary search over the source segment
+//     ids), the visible-pair count of the sequence, and the optional ordering checks.
+__global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32_t* __restrict__ stream_ids,
+                                                                     const int32_t* __restrict__ segment_ids,
+                                                                     const int32_t* __restrict__ positions,
+                                                                     const int32_t* __restrict__ cu,
+                                                                     int32_t* __restrict__ n_src, int32_t* __restrict__ n_rsn,
+                                                                     int32_t* __restrict__ perm, int32_t* __restrict__ seg_c,
+                                                                     int32_t* __restrict__ vis,
+                                                                     unsigned long long* __restrict__ pairs,
+                                                                     int32_t* __restrict__ flag, int validate) {
+    __shared__ int s_wave[kPlanThreads / 64];
     __shared__ int s_total;
+    __shared__ unsigned long long s_pairs[kPlanThreads / 64];
     const int b = blockIdx.x;
     const int t0 = cu[b], t1 = cu[b + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // pass 1: number of source tokens
     int cnt = 0;
-    for (int t = t0 + threadIdx.x; t < t1; t += 256) {
+    for (int t = t0 + threadIdx.x; t < t1; t += kPlanThreads) {
         const int s = stream_ids[t];
         if (s != ST_SOURCE && s != ST_REASONING) atomicOr(flag, 1);
         cnt += (s == ST_SOURCE);
     }
-    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
-    if (lane == 0) s_wave[wave] = cnt;
-    __syncthreads();
-    const int S = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
-    __syncthreads();
+    const int S = block_sum(cnt, s_wave);
     if (threadIdx.x == 0) {
         n_src[b] = S;
         n_rsn[b] = (t1 - t0) - S;
-        pairs[b] = 0ull;
         s_total = 0;
     }
     __syncthreads();
 
     // pass 2: running rank of source tokens; reasoning rank = index - source rank
-    for (int base = t0; base < t1; base += 256) {
+    for (int base = t0; base < t1; base += kPlanThreads) {
         const int t = base + threadIdx.x;
         const bool in = t < t1;
         const bool is_src = in && stream_ids[t] == ST_SOURCE;
@@ -97,8 +124,11 @@ __global__ __launch_bounds__(256) void plan_scan_kernel(const int32_t* __restric
         const int before_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
         if (lane == 0) s_wave[wave] = __popcll(mask);
         __syncthreads();
-        int before = s_total;
-        for (int w = 0; w < wave; ++w) before += s_wave[w];
+        int before = s_total, all = 0;
+        for (int w = 0; w < kPlanThreads / 64; ++w) {
+            before += w < wave ? s_wave[w] : 0;
+            all += s_wave[w];
+        }
         const int src_rank = before + before_in_wave;          // sources strictly before t
         if (in) {
             const int r = is_src ? src_rank : S + ((t - t0) - src_rank);
@@ -106,109 +136,139 @@ __global__ __launch_bounds__(256) void plan_scan_kernel(const int32_t* __restric
             seg_c[t0 + r] = segment_ids[t];
         }
         __syncthreads();
-        if (threadIdx.x == 0) s_total += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        if (threadIdx.x == 0) s_total += all;
         __syncthreads();
     }
-}
+    __threadfence_block();      // perm / seg_c of this sequence are read back below by other threads
+    __syncthreads();
 
-// ---- kernel 2: visible source count per compact row, pair counts, validation --
-__global__ __launch_bounds__(256) void plan_vis_kernel(const int32_t* __restrict__ cu, int batch, int n_tokens,
-                                                       const int32_t* __restrict__ n_src,
-                                                       const int32_t* __restrict__ seg_c,
-                                                       const int32_t* __restrict__ perm,
-                                                       const int32_t* __restrict__ positions,
-                                                       int32_t* __restrict__ vis,
-                                                       unsigned long long* __restrict__ pairs,
-                                                       int32_t* __restrict__ flag, int validate) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= n_tokens) return;
-    const int b = find_seq(cu, batch, c);
-    const int t0 = cu[b], S = n_src[b];
-    const int r = c - t0;
-    int v;
-    unsigned long long mine;
-    if (r < S) {
-        v = r + 1;
-        mine = (unsigned long long)(r + 1);
-    } else {
-        const int g = seg_c[c];
-        int lo = 0, hi = S;  // first source index whose segment id is > g
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (seg_c[t0 + mid] <= g) lo = mid + 1; else hi = mid;
+    // pass 3: visible source count per compact row, pair count, validation
+    const int n = t1 - t0;
+    unsigned long long mine = 0ull;
+    for (int r = threadIdx.x; r < n; r += kPlanThreads) {
+        const int c = t0 + r;
+        int v;
+        if (r < S) {
+            v = r + 1;
+            mine += (unsigned long long)(r + 1);
+        } else {
+            const int g = seg_c[c];
+            int lo = 0, hi = S;  // first source index whose segment id is > g
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (seg_c[t0 + mid] <= g) lo = mid + 1; else hi = mid;
+            }
+            v = lo;
+            mine += (unsigned long long)v + (unsigned long long)(r - S + 1);
         }
-        v = lo;
-        mine = (unsigned long long)v + (unsigned long long)(r - S + 1);
-    }
-    vis[c] = v;
-    // pair count: one atomic per wave when the whole wave sits in one sequence (the usual case)
-    const int b_first = __builtin_amdgcn_readfirstlane(b);
-    if (__all(b == b_first) && __popcll(__ballot(1)) == 64) {
-        unsigned long long sum = mine;
-        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        if ((threadIdx.x & 63) == 0) atomicAdd(&pairs[b], sum);
-    } else {
-        atomicAdd(&pairs[b], mine);
-    }
-    if (validate) {
-        // neighbours inside one stream: positions strictly increase, segment ids do not decrease
-        const int n = cu[b + 1] - t0;
-        const bool has_next = (r + 1 < n) && ((r < S) == (r + 1 < S));
-        if (has_next) {
-            const int p0 = positions[perm[c]], p1 = positions[perm[c + 1]];
-            if (!(p0 < p1) || seg_c[c] > seg_c[c + 1]) atomicOr(flag, 2);
+        vis[c] = v;
+        if (validate) {
+            // neighbours inside one stream: positions strictly increase, segment ids do not decrease
+            const bool has_next = (r + 1 < n) && ((r < S) == (r + 1 < S));
+            if (has_next) {
+                const int p0 = positions[perm[c]], p1 = positions[perm[c + 1]];
+                if (!(p0 < p1) || seg_c[c] > seg_c[c + 1]) atomicOr(flag, 2);
+            }
+            if (positions[perm[c]] < 0 || seg_c[c] < 0) atomicOr(flag, 4);
         }
-        if (positions[perm[c]] < 0 || seg_c[c] < 0) atomicOr(flag, 4);
+    }
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+    if (lane == 0) s_pairs[wave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long tot = 0ull;
+        for (int w = 0; w < kPlanThreads / 64; ++w) tot += s_pairs[w];
+        pairs[b] = tot;
     }
 }
 
-// ---- kernel 3: one work item per query tile --------------------------------
+// ---- work items ---------------------------------------------------------------------------------
 __device__ __forceinline__ int full_tiles(int limit, int n_cols) {
     // key tiles whose in-range columns are all < limit
     return n_cols <= limit ? (n_cols + kTileN - 1) / kTileN : limit / kTileN;
 }
 
+__device__ __forceinline__ WorkItem make_item(int slot, const int32_t* cu, const int32_t* slot_base,
+                                              const int32_t* pack_base, int batch, const int32_t* n_src,
+                                              const int32_t* n_rsn, const int32_t* vis, int* cost) {
+    WorkItem it = {};
+    *cost = 0;
+    if (slot >= slot_base[batch]) return it;
+    const int b = find_seq(slot_base, batch, slot);
+    const int local = slot - slot_base[b];
+    const int S = n_src[b], R = n_rsn[b];
+    const int ts = (S + kTileM - 1) / kTileM, tr = (R + kTileM - 1) / kTileM;
+    if (local >= ts + tr) return it;
+    const bool src = local < ts;
+    const int n_stream = src ? S : R;
+    it.seq = b;
+    it.kind = src ? ST_SOURCE : ST_REASONING;
+    it.row0 = (src ? local : local - ts) * kTileM;
+    it.n_rows = min(kTileM, n_stream - it.row0);
+    const int last = it.row0 + it.n_rows - 1;
+    it.a_total = last / kTileN + 1;
+    it.a_full = full_tiles(it.row0 + 1, n_stream);
+    it.a_base = cu[b] + (src ? 0 : S);
+    it.b_base = cu[b];
+    it.n_stream = n_stream;
+    it.n_src = S;
+    it.tile_b0 = pack_base[b];
+    it.tile_a0 = pack_base[b] + (src ? 0 : (S + kTileN - 1) / kTileN);
+    if (!src) {
+        const int vmin = vis[it.a_base + it.row0], vmax = vis[it.a_base + last];
+        it.b_total = (vmax + kTileN - 1) / kTileN;
+        it.b_full = full_tiles(vmin, S);
+    }
+    *cost = it.a_total + it.b_total;
+    return it;
+}
+
+// ---- kernel 2 (small plans): one workgroup builds every work item and writes them longest first
+// (stable rank by counting; unused slots have cost 0 and come last) -----------------------------
+__global__ __launch_bounds__(kPlanThreads) void plan_items_sorted_kernel(const int32_t* __restrict__ cu,
+                                                                         const int32_t* __restrict__ slot_base,
+                                                                         const int32_t* __restrict__ pack_base, int batch,
+                                                                         int m_max, const int32_t* __restrict__ n_src,
+                                                                         const int32_t* __restrict__ n_rsn,
+                                                                         const int32_t* __restrict__ vis,
+                                                                         WorkItem* __restrict__ items, int32_t* __restrict__ cost,
+                                                                         WorkItem* __restrict__ sorted) {
+    for (int slot = threadIdx.x; slot < m_max; slot += kPlanThreads) {
+        int c;
+        items[slot] = make_item(slot, cu, slot_base, pack_base, batch, n_src, n_rsn, vis, &c);
+        cost[slot] = c;
+    }
+    __threadfence_block();
+    __syncthreads();
+    for (int i = threadIdx.x; i < m_max; i += kPlanThreads) {
+        const int ci = cost[i];
+        int rank = 0;
+        for (int j = 0; j < m_max; ++j) {
+            const int cj = cost[j];
+            rank += (cj > ci) || (cj == ci && j < i);
+        }
+        sorted[rank] = items[i];
+    }
+}
+
+// ---- kernels 2a / 2b (large plans): the same in two grid-wide steps ---------------------------------
 __global__ __launch_bounds__(256) void plan_items_kernel(const int32_t* __restrict__ cu,
-                                                         const int32_t* __restrict__ slot_base, int batch,
-                                                         int m_max, const int32_t* __restrict__ n_src,
+                                                         const int32_t* __restrict__ slot_base,
+                                                         const int32_t* __restrict__ pack_base, int batch, int m_max,
+                                                         const int32_t* __restrict__ n_src,
                                                          const int32_t* __restrict__ n_rsn,
                                                          const int32_t* __restrict__ vis,
                                                          WorkItem* __restrict__ items, int32_t* __restrict__ cost) {
     const int slot = blockIdx.x * 256 + threadIdx.x;
     if (slot >= m_max) return;
-    WorkItem it = {0, 0, 0, 0, 0, 0, 0, 0};
-    int c = 0;
-    if (slot < slot_base[batch]) {
-        const int b = find_seq(slot_base, batch, slot);
-        const int local = slot - slot_base[b];
-        const int S = n_src[b], R = n_rsn[b];
-        const int ts = (S + kTileM - 1) / kTileM, tr = (R + kTileM - 1) / kTileM;
-        if (local < ts + tr) {
-            const bool src = local < ts;
-            const int n_stream = src ? S : R;
-            it.seq = b;
-            it.kind = src ? ST_SOURCE : ST_REASONING;
-            it.row0 = (src ? local : local - ts) * kTileM;
-            it.n_rows = min(kTileM, n_stream - it.row0);
-            const int last = it.row0 + it.n_rows - 1;
-            it.a_total = last / kTileN + 1;
-            it.a_full = full_tiles(it.row0 + 1, n_stream);
-            if (!src) {
-                const int base = cu[b] + S;
-                const int vmin = vis[base + it.row0], vmax = vis[base + last];
-                it.b_total = (vmax + kTileN - 1) / kTileN;
-                it.b_full = full_tiles(vmin, S);
-            }
-            c = it.a_total + it.b_total;
-        }
-    }
-    items[slot] = it;
+    int c;
+    items[slot] = make_item(slot, cu, slot_base, pack_base, batch, n_src, n_rsn, vis, &c);
     cost[slot] = c;
 }
 
-// ---- kernel 4: longest-first order (stable rank by counting) ----------------
 __global__ __launch_bounds__(256) void plan_order_kernel(const int32_t* __restrict__ cost, int m_max,
-                                                         int32_t* __restrict__ order) {
+                                                         const WorkItem* __restrict__ items,
+                                                         WorkItem* __restrict__ sorted) {
     __shared__ int s_cost[256];
     const int i = blockIdx.x * 256 + threadIdx.x;
     const int ci = i < m_max ? cost[i] : 0;
@@ -224,7 +284,7 @@ __global__ __launch_bounds__(256) void plan_order_kernel(const int32_t* __restri
         }
         __syncthreads();
     }
-    if (i < m_max) order[rank] = i;
+    if (i < m_max) sorted[rank] = items[i];
 }
 
 }  // namespace st
@@ -298,9 +358,9 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
     p->perm = reinterpret_cast<int32_t*>(w + L.perm);
     p->seg_c = reinterpret_cast<int32_t*>(w + L.seg_c);
     p->vis = reinterpret_cast<int32_t*>(w + L.vis);
-    p->order = reinterpret_cast<int32_t*>(w + L.order);
     p->cost = reinterpret_cast<int32_t*>(w + L.cost);
     p->items = reinterpret_cast<WorkItem*>(w + L.items);
+    p->sorted = reinterpret_cast<WorkItem*>(w + L.sorted);
 
     hipStream_t s = p->stream;
     auto bail = [&](hipError_t e, const char* what) {
@@ -309,23 +369,35 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
         return r;
     };
     hipError_t e;
-    if ((e = hipMemcpyAsync(p->cu, p->cu_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
-        return bail(e, "copy of cu_seqlens");
-    if ((e = hipMemcpyAsync(p->slot_base, p->slot_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
-        return bail(e, "copy of slot table");
-    if ((e = hipMemcpyAsync(p->pack_base, p->pack_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
-        return bail(e, "copy of pack table");
-    const int nt = int(n_tokens);
-    hipLaunchKernelGGL(plan_clear_kernel, dim3(1), dim3(64), 0, s, p->flag);
-    hipLaunchKernelGGL(plan_scan_kernel, dim3(batch), dim3(256), 0, s, stream_ids, segment_ids, p->cu, p->n_src,
-                       p->n_rsn, p->perm, p->seg_c, p->pairs, p->flag);
-    if (nt > 0)
-        hipLaunchKernelGGL(plan_vis_kernel, dim3((nt + 255) / 256), dim3(256), 0, s, p->cu, batch, nt, p->n_src,
-                           p->seg_c, p->perm, positions, p->vis, p->pairs, p->flag, validate ? 1 : 0);
-    const int mb = (p->m_max + 255) / 256;
-    hipLaunchKernelGGL(plan_items_kernel, dim3(mb), dim3(256), 0, s, p->cu, p->slot_base, batch, p->m_max, p->n_src,
-                       p->n_rsn, p->vis, p->items, p->cost);
-    hipLaunchKernelGGL(plan_order_kernel, dim3(mb), dim3(256), 0, s, p->cost, p->m_max, p->order);
+    if (batch <= kTablesMaxBatch) {
+        HostTables t;
+        for (int i = 0; i <= batch; ++i) {
+            t.v[i] = p->cu_host[i];
+            t.v[(batch + 1) + i] = p->slot_base_host[i];
+            t.v[2 * (batch + 1) + i] = p->pack_base_host[i];
+        }
+        hipLaunchKernelGGL(plan_init_kernel, dim3(1), dim3(256), 0, s, t, batch, p->cu, p->slot_base, p->pack_base, p->flag);
+    } else {
+        // the host vectors live as long as the plan, so the asynchronous copies may read them later
+        if ((e = hipMemcpyAsync(p->cu, p->cu_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
+            return bail(e, "copy of cu_seqlens");
+        if ((e = hipMemcpyAsync(p->slot_base, p->slot_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
+            return bail(e, "copy of slot table");
+        if ((e = hipMemcpyAsync(p->pack_base, p->pack_base_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
+            return bail(e, "copy of pack table");
+        hipLaunchKernelGGL(plan_clear_kernel, dim3(1), dim3(64), 0, s, p->flag);
+    }
+    hipLaunchKernelGGL(plan_sequence_kernel, dim3(batch), dim3(kPlanThreads), 0, s, stream_ids, segment_ids, positions, p->cu,
+                       p->n_src, p->n_rsn, p->perm, p->seg_c, p->vis, p->pairs, p->flag, validate ? 1 : 0);
+    if (p->m_max <= 4096) {
+        hipLaunchKernelGGL(plan_items_sorted_kernel, dim3(1), dim3(kPlanThreads), 0, s, p->cu, p->slot_base, p->pack_base, batch,
+                           p->m_max, p->n_src, p->n_rsn, p->vis, p->items, p->cost, p->sorted);
+    } else {
+        const int mb = (p->m_max + 255) / 256;
+        hipLaunchKernelGGL(plan_items_kernel, dim3(mb), dim3(256), 0, s, p->cu, p->slot_base, p->pack_base, batch, p->m_max,
+                           p->n_src, p->n_rsn, p->vis, p->items, p->cost);
+        hipLaunchKernelGGL(plan_order_kernel, dim3(mb), dim3(256), 0, s, p->cost, p->m_max, p->items, p->sorted);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "launch of plan kernels");
     if (validate) {
         int32_t flag = 0;

@@ -31,22 +31,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 struct ItemGeom {
-    int t0;          // first compact row of the sequence
     int S;           // source tokens
     int n_stream;    // tokens of the row's own stream
     int a_base;      // compact row of column 0 of block A
     int b_base;      // compact row of column 0 of block B (the source stream)
 };
 
-__device__ __forceinline__ ItemGeom item_geom(const PlanView& pv, const WorkItem& it) {
-    ItemGeom g;
-    g.t0 = pv.cu[it.seq];
-    g.S = pv.n_src[it.seq];
-    const int n = pv.cu[it.seq + 1] - g.t0;
-    g.n_stream = it.kind == ST_SOURCE ? g.S : n - g.S;
-    g.a_base = g.t0 + (it.kind == ST_SOURCE ? 0 : g.S);
-    g.b_base = g.t0;
-    return g;
+__device__ __forceinline__ ItemGeom item_geom(const PlanView&, const WorkItem& it) {
+    return ItemGeom{it.n_src, it.n_stream, it.a_base, it.b_base};
 }
 
 // --------------------------------------------------------------------------
@@ -76,7 +68,7 @@ __global__ __launch_bounds__(kTileM) void prefill_simple_kernel(T* __restrict__ 
     const int rank = blockIdx.x / n_q_heads;
     const int hq = blockIdx.x % n_q_heads;
     const int hk = hq / (n_q_heads / n_kv_heads);
-    const WorkItem it = pv.items[pv.order[rank]];
+    const WorkItem it = pv.sorted[rank];
     if (it.n_rows == 0) return;
     const ItemGeom g = item_geom(pv, it);
     const int r = threadIdx.x;
@@ -255,34 +247,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     const int group = n_q_heads / n_kv_heads;
     const int hk = hh % n_kv_heads;                 // consecutive workgroups -> consecutive KV heads
     const int hq = hk * group + hh / n_kv_heads;
-    const WorkItem it = pv.items[pv.order[rank]];
+    const WorkItem it = pv.sorted[rank];
     if (it.n_rows == 0) return;
     const ItemGeom g = item_geom(pv, it);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, hg = lane >> 5;        // query column of the wave tile, half-wave
-
-    const int row_in_tile = wave * 32 + n;
-    const bool active = row_in_tile < it.n_rows;
-    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
-    const int tok_q = pv.perm[g.a_base + my_row];
-    const int my_vis = pv.vis[g.a_base + my_row];
-
-    // Q^T operand: lane (n, hg) holds Q[row n][16 j + 8 hg .. + 8)
-    bf16x8 qf[KS];
-    {
-        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq) * D + 8 * hg;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 16 * j);
-    }
-
-    f32x16 o_acc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
 
     const int n_tiles = it.a_total + it.b_total;
 
@@ -295,8 +266,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     // in order, so "my part of tile X has landed" is s_waitcnt vmcnt(<loads issued after X>), and the
     // barrier that follows makes all four parts visible to everybody.
     constexpr int NL = kTileN * D * 2 / 1024 / 4;    // 1 KB loads per wave per tile (K or V^T)
-    const int tile_a0 = pv.pack_base[it.seq] + (it.kind == ST_SOURCE ? 0 : (g.S + kTileN - 1) / kTileN);
-    const int tile_b0 = pv.pack_base[it.seq];
+    const int tile_a0 = it.tile_a0, tile_b0 = it.tile_b0;
     const size_t head_off = size_t(hk) * pv.pack_tiles * (kTileN * D) + (wave * NL) * 512 + lane * 8;
     const uint16_t* kc_lane = kc + head_off;
     const uint16_t* vc_lane = vc + head_off;
@@ -319,6 +289,32 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_v0 + buf * (kTileN * D * 2) + u * 1024);
     };
 
+    // the first tiles are requested before anything else is looked up for this work item
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
+
+    const int row_in_tile = wave * 32 + n;
+    const bool active = row_in_tile < it.n_rows;
+    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
+    const int tok_q = pv.perm[g.a_base + my_row];
+    const int my_vis = pv.vis[g.a_base + my_row];
+
+    // Q^T operand: lane (n, hg) holds Q[row n][16 j + 8 hg .. + 8)
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq) * D + 8 * hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 16 * j);
+    }
+
+    f32x16 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
     // operand addresses: lane (n, hg) reads chunk (2 j + hg) ^ key(row) = (2 j) ^ (key ^ hg) of its row
     int koff[KS], voff[4];
     {
@@ -329,9 +325,6 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
         for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
     }
 
-    issue_k(0, 0);
-    issue_v(0, 0);
-    issue_k(1, 1);
     // everything fetched once per work item must have landed before the loop, or the compiler
     // re-checks for it inside every iteration
     {
