@@ -276,6 +276,32 @@ st_status st_attn_decode_dual(void* out, float* lse, const void* q,
                               int32_t batch, int32_t n_q_heads, float scale,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------
+ * st_attn_source_chunk -- attention of an arriving source chunk over the paged source
+ * cache.  Alg. 1, prefill loop ("read the input sentence and save hidden state to the
+ * input KV cache"; Sec. 3.3: the model "performs prefill in arrival order"): the tokens of
+ * the new sentence attend causally to the source stream only, never to reasoning.
+ *
+ * Call order: st_kv_append(ST_SOURCE, chunk) first, then this call with
+ *   src_len[b]  : device int32 [batch], source tokens in the cache INCLUDING the chunk
+ *   n_new[b]    : device int32 [batch], tokens of the chunk (0 .. max_new), or NULL for max_new
+ *   q, out      : bf16 [batch, max_new, n_q_heads, head_dim]; row t < n_new[b] sees source
+ *                 positions [0, src_len[b] - n_new[b] + t]; rows t >= n_new[b] are not written
+ *   lse         : fp32 [batch, max_new, n_q_heads] or NULL
+ *   max_src_len : host upper bound on src_len
+ * The reasoning cache of `caches` is not touched.  The same machinery as the decode step
+ * (split over 512-token chunks of the cache, log-sum-exp merge) with the queries cut into
+ * blocks of 32 (token, head) rows.
+ * workspace: at least st_source_chunk_workspace_bytes(...) bytes, 256-byte aligned.
+ * ---------------------------------------------------------------------- */
+size_t st_source_chunk_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                       int32_t head_dim, int32_t max_new, int32_t max_src_len);
+
+st_status st_attn_source_chunk(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                               const int32_t* src_len, const int32_t* n_new, int32_t max_new,
+                               int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ head mapping, rotate-half RoPE pairing, base 1e6) are pinned to the textbook /
 library convention by tests/test_oracle_pins.py.
 
 Pins (all in tests/test_oracle_pins.py): brute-force gather, layout
-equivariance, Eq. 2 as printed, reduction to library causal attention,
+equivariance, Eq. 2 as printed, reduction to library causal attention, source chunk == source rows of prefill,
 closed-form visible-pair counts, LSE-merge == concatenation, RoPE identities,
 decode == last prefill row, paged gather == contiguous.  No function here is
 "parity unpinned".
@@ -277,6 +277,21 @@ def decode_dual_merged(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, 
     o1, l1 = attend_one_cache(q, np.asarray(src_k)[:src_visible_len], np.asarray(src_v)[:src_visible_len], m_src, scale)
     o2, l2 = attend_one_cache(q, np.asarray(rsn_k)[:rsn_len], np.asarray(rsn_v)[:rsn_len], m_rsn, scale)
     return lse_merge(o1, l1, o2, l2)
+
+
+def source_chunk_attention(q, src_k, src_v, src_len, scale=None):
+    """Attention of an arriving source chunk (Alg. 1, prefill loop), one sequence.
+
+    q[n_new, Hq, D] are the queries of the n_new NEWEST source tokens, whose keys / values are
+    already rows src_len - n_new .. src_len - 1 of the source cache [src_len, Hkv, D].  Source
+    tokens see source tokens at positions <= their own and nothing else (Eq. 1: C_t conditions
+    on earlier input only), so row t sees cache rows [0, src_len - n_new + t].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    n_new = q.shape[0]
+    col = np.arange(src_len)[None, :]
+    mask = col <= (src_len - n_new + np.arange(n_new)[:, None])
+    return attend_one_cache(q, np.asarray(src_k)[:src_len], np.asarray(src_v)[:src_len], mask, scale)
 
 
 # --------------------------------------------------------------------------

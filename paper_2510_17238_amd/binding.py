@@ -95,6 +95,10 @@ def load_library():
     lib.st_attn_decode_dual.restype = i32
     lib.st_attn_decode_dual.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
                                         f32, vp, sz, vp]
+    lib.st_source_chunk_workspace_bytes.restype = sz
+    lib.st_source_chunk_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.st_attn_source_chunk.restype = i32
+    lib.st_attn_source_chunk.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -386,4 +390,28 @@ def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rs
     lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
     _check(lib.st_attn_decode_dual(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+def st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, max_new, max_src_len):
+    return int(load_library().st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, max_new, max_src_len))
+
+
+def st_attn_source_chunk(q, caches, src_len, max_src_len, n_new=None, scale=0.0, out=None, lse=None, workspace=None, stream=None):
+    """q[batch, max_new, Hq, D] bf16: the newest source tokens attend causally over the source cache."""
+    lib = load_library()
+    assert q.is_cuda and q.is_contiguous() and q.dtype == torch.bfloat16 and q.dim() == 4
+    batch, max_new, hq, d = q.shape
+    _dev_i32(src_len, "src_len")
+    if n_new is not None:
+        _dev_i32(n_new, "n_new")
+    if out is None:
+        out = torch.zeros_like(q)
+    if workspace is None:
+        need = st_source_chunk_workspace_bytes(batch, hq, caches.source.n_kv_heads, d, max_new, max_src_len)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    st = caches.struct()
+    _check(lib.st_attn_source_chunk(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), _ptr(src_len), _ptr(n_new), max_new,
+                                    int(max_src_len), batch, hq, float(scale), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
     return out

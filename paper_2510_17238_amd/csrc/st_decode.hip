@@ -35,18 +35,31 @@ struct DecodeArgs {
     int batch, q_len, n_q_heads, n_kv_heads, group, rows;
     int ncs, ncr;      // chunk slots per (sequence, head) for the two caches
     float scale_log2;
+    // source-chunk prefill only (CHUNKED kernels): ragged query counts and 32-row blocks
+    const int32_t* n_new;   // [B] query tokens per sequence, or null for max_new everywhere
+    int max_new;            // token stride of q / out
+    int row_blocks;         // ceil(max_new * group / 32)
 };
 
-template <int D>
+// CHUNKED = false: the decode step (up to 32 query rows q_len * G per sequence and KV head, both caches).
+// CHUNKED = true : source-chunk prefill (Alg. 1, prefill loop): the n_new[b] newest source tokens are the
+//                  queries, cut into blocks of 32 rows; only the source cache is read, causally
+//                  (row t sees source positions [0, len - n_new + t]).
+template <int D, bool CHUNKED>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     constexpr int KS = D / 16, DB = D / 32, KCH = D / 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nc = a.ncs + a.ncr;
-    const int64_t unit = int64_t(blockIdx.x) * 4 + wave;
+    int64_t unit = int64_t(blockIdx.x) * 4 + wave;
     const int c = int(unit % nc);
-    const int64_t bh = unit / nc;
-    const int h = int(bh % a.n_kv_heads);
-    const int b = int(bh / a.n_kv_heads);
+    unit /= nc;
+    int rb = 0;
+    if (CHUNKED) {
+        rb = int(unit % a.row_blocks);
+        unit /= a.row_blocks;
+    }
+    const int h = int(unit % a.n_kv_heads);
+    const int b = int(unit / a.n_kv_heads);
     if (b >= a.batch) return;
     const bool is_src = c < a.ncs;
     const CacheView& cv = is_src ? a.src : a.rsn;
@@ -54,21 +67,29 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
     const int tok0 = cc * kChunk;
     if (tok0 >= len) return;
-    const int tok_end = min(len, tok0 + kChunk);
 
     const int n = lane & 31, hg = lane >> 5;
-    const int t_row = n / a.group;
-    const bool valid_row = n < a.rows;
-    const int hq = h * a.group + n % a.group;
+    const int q_len = CHUNKED ? min(min(max(a.n_new ? a.n_new[b] : a.max_new, 0), a.max_new), len) : a.q_len;
+    const int r = rb * 32 + n;                      // query row of this (sequence, KV head): token r / G, head r % G
+    const int t_row = r / a.group;
+    const bool valid_row = r < q_len * a.group;
+    const int hq = h * a.group + r % a.group;
+    if (CHUNKED) {
+        // the block's last row sees the most: chunks past its limit hold nothing for this block
+        const int last_t = min(q_len - 1, (rb * 32 + 31) / a.group);
+        if (rb * 32 >= q_len * a.group || tok0 >= len - q_len + last_t + 1) return;
+    }
+    const int tok_end = min(len, tok0 + kChunk);
     // visible reasoning tokens of query row t: [0, len - q_len + t]; the source slice is seen whole
-    const int limit = !valid_row ? 0 : (is_src ? len : max(len - a.q_len + t_row + 1, 0));
+    // by a decode step, causally by a source chunk
+    const int limit = !valid_row ? 0 : ((is_src && !CHUNKED) ? len : max(len - q_len + t_row + 1, 0));
 
     bf16x8 qf[KS];
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
         u32x4 z = {0u, 0u, 0u, 0u};
         if (valid_row)
-            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
+            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * (CHUNKED ? a.max_new : a.q_len) + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
         qf[j] = __builtin_bit_cast(bf16x8, z);
     }
     f32x16 o_acc[DB];
@@ -166,7 +187,8 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (!valid_row) return;
-    const int64_t slot = ((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n;
+    const int64_t slot = CHUNKED ? ((((int64_t(b) * a.n_kv_heads + h) * a.row_blocks + rb) * nc + c) * 32 + n)
+                                 : (((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n);
     float* po = a.part_o + slot * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -391,6 +413,71 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
         lse[(int64_t(b) * a.q_len + t) * a.n_q_heads + hq] = den > 0.f ? (m_run + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
 }
 
+// Merge for the source-chunk prefill: one wave per (sequence, query token, query head).
+template <int D>
+__global__ __launch_bounds__(64) void chunk_combine_kernel(DecodeArgs a, uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse) {
+    constexpr int PER = D / 64;
+    constexpr int BATCH = 32;
+    const int lane = threadIdx.x;
+    const int hq = int(blockIdx.x % unsigned(a.n_q_heads));
+    const int t = int((blockIdx.x / unsigned(a.n_q_heads)) % unsigned(a.max_new));
+    const int b = int(blockIdx.x / unsigned(a.n_q_heads * a.max_new));
+    const int len = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
+    const int q_len = min(min(max(a.n_new ? a.n_new[b] : a.max_new, 0), a.max_new), len);
+    if (t >= q_len) return;                          // rows past n_new[b] are left untouched
+    const int h = hq / a.group;
+    const int r = t * a.group + hq % a.group, rb = r / 32, n = r % 32;
+    const int last_t = min(q_len - 1, (rb * 32 + 31) / a.group);
+    const int n_tot = min((len - q_len + last_t + 1 + kChunk - 1) / kChunk, a.ncs);   // chunks the split kernel wrote for this block
+    const int64_t base = ((int64_t(b) * a.n_kv_heads + h) * a.row_blocks + rb) * a.ncs;
+
+    float acc[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+    float den = 0.f, m_run = -INFINITY;
+    for (int i0 = 0; i0 < n_tot; i0 += BATCH) {
+        const int cnt = min(BATCH, n_tot - i0);
+        float m_mine = -INFINITY, l_mine = 0.f;
+        if (lane < cnt) {
+            const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + ((base + i0 + lane) * 32 + n) * 2);
+            m_mine = ml[0];
+            l_mine = ml[1];
+        }
+        float rows[BATCH][PER];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const float* po = a.part_o + ((base + i0 + min(u, cnt - 1)) * 32 + n) * D + lane * PER;
+#pragma unroll
+            for (int e = 0; e < PER; ++e) rows[u][e] = po[e];
+        }
+        float bm = m_mine;
+        for (int o = 32; o > 0; o >>= 1) bm = fmaxf(bm, __shfl_xor(bm, o));
+        const float m_new = fmaxf(m_run, bm);
+        if (m_new == -INFINITY) continue;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        const float w_mine = __builtin_amdgcn_exp2f(m_mine - m_new);
+        float wl = w_mine * l_mine;
+        for (int o = 32; o > 0; o >>= 1) wl += __shfl_xor(wl, o);
+        den = den * alpha + wl;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const float w = __shfl(w_mine, u);
+#pragma unroll
+            for (int e = 0; e < PER; ++e) acc[e] = fmaf(w, rows[u][e], acc[e]);
+        }
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    uint16_t* op = out + ((int64_t(b) * a.max_new + t) * a.n_q_heads + hq) * D + lane * PER;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) op[e] = f32_to_bf16_bits(acc[e] * inv);
+    if (lse && lane == 0)
+        lse[(int64_t(b) * a.max_new + t) * a.n_q_heads + hq] = den > 0.f ? (m_run + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
+}
+
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 static inline int chunks_of(int len) { return (len + kChunk - 1) / kChunk; }
 
@@ -452,6 +539,9 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
     a.ncs = chunks_of(lens->max_src_len);
     a.ncr = chunks_of(lens->max_rsn_len);
     a.scale_log2 = scale * kLog2e;
+    a.n_new = nullptr;
+    a.max_new = lens->q_len;
+    a.row_blocks = 1;
     const size_t slots = size_t(batch) * hkv * size_t(a.ncs + a.ncr) * a.rows;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
@@ -469,8 +559,8 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
             else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
             prof_end(kProfDecodeSplit, s);
         } else {
-            if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((decode_split_kernel<128>), grid, block, 0, s, a);
+            if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64, false>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((decode_split_kernel<128, false>), grid, block, 0, s, a);
         }
         ST_LAUNCH_CHECK("decode_split_kernel");
     }
@@ -482,5 +572,72 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
         hipLaunchKernelGGL((decode_combine_kernel<128>), dim3((unsigned)out_units), dim3(64), 0, s, a,
                            static_cast<uint16_t*>(out), lse);
     ST_LAUNCH_CHECK("decode_combine_kernel");
+    return ST_OK;
+}
+
+extern "C" size_t st_source_chunk_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                                  int32_t max_new, int32_t max_src_len) {
+    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0 || max_new <= 0 || max_src_len < 0) return 0;
+    const size_t rb = (size_t(max_new) * (n_q_heads / n_kv_heads) + 31) / 32;
+    const size_t slots = size_t(batch) * n_kv_heads * rb * size_t(chunks_of(max_src_len)) * 32;
+    return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
+}
+
+extern "C" st_status st_attn_source_chunk(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                          const int32_t* src_len, const int32_t* n_new, int32_t max_new,
+                                          int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!out || !q || !caches || !src_len) return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk: null pointer");
+    if (!aligned16(out) || !aligned16(q)) return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk: q / out must be 16-byte aligned");
+    st_status r = check_cache(caches->source, "st_attn_source_chunk", "source");
+    if (r != ST_OK) return r;
+    const st_kv_cache& cs = caches->source;
+    const int hkv = cs.n_kv_heads, d = cs.head_dim;
+    if (batch <= 0 || n_q_heads <= 0 || n_q_heads % hkv != 0)
+        return fail(ST_ERR_SHAPE, "st_attn_source_chunk: n_q_heads %d must be a positive multiple of n_kv_heads %d", n_q_heads, hkv);
+    if (max_new <= 0 || max_src_len < 0) return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk: bad sizes");
+    if (int64_t(max_src_len) > int64_t(cs.max_pages_per_seq) * kPage)
+        return fail(ST_ERR_CAPACITY, "st_attn_source_chunk: length bound exceeds the page table");
+    const size_t need = st_source_chunk_workspace_bytes(batch, n_q_heads, hkv, d, max_new, max_src_len);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk: workspace must be non-null and 256-byte aligned");
+    if (workspace_bytes < need) return fail(ST_ERR_CAPACITY, "st_attn_source_chunk: workspace has %zu bytes, needs %zu", workspace_bytes, need);
+    if (scale <= 0.f) scale = 1.f / sqrtf(float(d));
+
+    DecodeArgs a;
+    a.src = cache_view(cs);
+    a.rsn = a.src;                       // unused: there are no reasoning chunk slots
+    a.src_len = src_len;
+    a.rsn_len = src_len;
+    a.q = static_cast<const uint16_t*>(q);
+    a.batch = batch;
+    a.q_len = max_new;
+    a.n_q_heads = n_q_heads;
+    a.n_kv_heads = hkv;
+    a.group = n_q_heads / hkv;
+    a.rows = 32;
+    a.ncs = chunks_of(max_src_len);
+    a.ncr = 0;
+    a.scale_log2 = scale * kLog2e;
+    a.n_new = n_new;
+    a.max_new = max_new;
+    a.row_blocks = (max_new * a.group + 31) / 32;
+    const size_t slots = size_t(batch) * hkv * a.row_blocks * size_t(a.ncs) * 32;
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int64_t units = int64_t(batch) * hkv * a.row_blocks * a.ncs;
+    const int64_t out_units = int64_t(batch) * max_new * n_q_heads;
+    if (units / 4 + 1 > 0x7fffffff || out_units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_source_chunk: grid too large");
+    if (units > 0) {
+        const dim3 grid((unsigned)((units + 3) / 4)), block(256);
+        if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((decode_split_kernel<128, true>), grid, block, 0, s, a);
+        ST_LAUNCH_CHECK("decode_split_kernel (chunked)");
+    }
+    if (d == 64) hipLaunchKernelGGL((chunk_combine_kernel<64>), dim3((unsigned)out_units), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
+    else hipLaunchKernelGGL((chunk_combine_kernel<128>), dim3((unsigned)out_units), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
+    ST_LAUNCH_CHECK("chunk_combine_kernel");
     return ST_OK;
 }

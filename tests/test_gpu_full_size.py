@@ -157,3 +157,34 @@ def test_config5_eight_tokens_in_one_call(st):
     """The same shape with the step's 8 reasoning tokens decoded in a single call (q_len = 8, causal among them)."""
     shp = W.config5(batch=16)
     _decode_full(st, shp, 8, [0, 9], seed=52)
+
+
+def test_config5_source_chunk_one_layer(st):
+    """Config 5's concurrent source side at full size: batch 64, 32-token chunks arriving on source caches of
+    1-8K tokens (32 query heads, group 4 -> 128 rows = 4 blocks per sequence and KV head), one layer."""
+    shp = W.config5()
+    B, hq, hkv, d, n_new = shp.batch, shp.n_q_heads, shp.n_kv_heads, shp.head_dim, shp.src_append
+    rng = np.random.Generator(np.random.PCG64(53))
+    pages = (shp.max_src_len + 15) // 16
+    tab = W.shuffled_page_table(rng, B, pages)
+    cs = st.KVCache(B * pages, B, pages, hkv, d, torch.from_numpy(tab).to(DEV))
+    cr = st.KVCache(B, B, 1, hkv, d, torch.arange(B, dtype=torch.int32, device=DEV).reshape(B, 1).contiguous())
+    g = torch.Generator(device=DEV); g.manual_seed(53)
+    cs.k_pool.normal_(generator=g); cs.v_pool.normal_(generator=g)
+    caches = st.DualCache(cs, cr)
+    cs.appended_len.copy_(torch.from_numpy(shp.src_visible_len))
+    k_new = _device_normal((B, n_new, hkv, d), 54); v_new = _device_normal((B, n_new, hkv, d), 55); q = _device_normal((B, n_new, hq, d), 56)
+    st.st_kv_append(caches, st.ST_SOURCE, k_new, v_new, host_len_upper_bound=shp.max_src_len)
+    total = (shp.src_visible_len + n_new).astype(np.int32)
+    lse = torch.empty((B, n_new, hq), dtype=torch.float32, device=DEV)
+    out = st.st_attn_source_chunk(q, caches, torch.from_numpy(total).to(DEV), int(total.max()), lse=lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    for b in sorted({0, 21, int(np.argmax(total)), int(np.argmin(total))}):
+        ids = torch.from_numpy(tab[b, :(int(total[b]) + 15) // 16].astype(np.int64)).to(DEV)
+        kl = to_f64(st.k_pool_to_logical(cs.k_pool[ids]).reshape(-1, hkv, d)[:int(total[b])])
+        vl = to_f64(st.v_pool_to_logical(cs.v_pool[ids]).reshape(-1, hkv, d)[:int(total[b])])
+        assert np.array_equal(kl[-n_new:], to_f64(k_new[b]))
+        o_ref, l_ref = O.source_chunk_attention(to_f64(q[b]), kl, vl, int(total[b]))
+        assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
+        assert np.abs(to_f64(lse[b]) - l_ref).max() <= 2e-2, b

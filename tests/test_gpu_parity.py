@@ -377,3 +377,73 @@ def test_decode_workspace_reuse(st):
             o_ref, _ = O.decode_dual_concat(q[b], ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
                                             ref[st.ST_REASONING][1][b], int(vis[b]), int(rl[b]))
             assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
+
+
+# ------------------------------------------------- source-chunk prefill --
+def _check_source_chunk(st, rng, batch, hq, hkv, d, src_before, n_new, max_new):
+    """Append a ragged chunk to the source cache, then let its tokens attend over the cache."""
+    src_before = np.asarray(src_before); n_new = np.asarray(n_new)
+    total = src_before + n_new
+    pages = (int(total.max()) + 15) // 16 + 1
+    cs, _ = make_cache(batch, pages, hkv, d, rng, fill=float("nan")); cr, _ = make_cache(batch, 1, hkv, d, rng, fill=float("nan"))
+    caches = st.DualCache(cs, cr)
+    kk = W.normal(rng, (batch, int(total.max()), hkv, d), "bf16"); vv = W.normal(rng, (batch, int(total.max()), hkv, d), "bf16")
+    # history first, then the chunk (two appends, as Alg. 1 does sentence by sentence)
+    hist = int(src_before.max())
+    if hist:
+        st.st_kv_append(caches, st.ST_SOURCE, to_dev(kk[:, :hist], "bf16"), to_dev(vv[:, :hist], "bf16"),
+                        torch.from_numpy(src_before.astype(np.int32)).to(DEV))
+    kn = np.zeros((batch, max_new, hkv, d), np.float32); vn = np.zeros_like(kn)
+    for b in range(batch):
+        kn[b, :n_new[b]] = kk[b, src_before[b]:total[b]]; vn[b, :n_new[b]] = vv[b, src_before[b]:total[b]]
+        kk[b, :total[b]] = np.concatenate([kk[b, :src_before[b]], kn[b, :n_new[b]]]); vv[b, :total[b]] = np.concatenate([vv[b, :src_before[b]], vn[b, :n_new[b]]])
+    nn = torch.from_numpy(n_new.astype(np.int32)).to(DEV)
+    st.st_kv_append(caches, st.ST_SOURCE, to_dev(kn, "bf16"), to_dev(vn, "bf16"), nn)
+    q = W.normal(rng, (batch, max_new, hq, d), "bf16")
+    tq = to_dev(q, "bf16")
+    lse = torch.full((batch, max_new, hq), 7.0, dtype=torch.float32, device=DEV)
+    out = torch.full_like(tq, 3.0)
+    st.st_attn_source_chunk(tq, caches, torch.from_numpy(total.astype(np.int32)).to(DEV), int(total.max()), n_new=nn, out=out, lse=lse)
+    torch.cuda.synchronize()
+    assert cs.appended_len.cpu().tolist() == total.tolist()
+    for b in range(batch):
+        nb = int(n_new[b])
+        if nb:
+            o_ref, l_ref = O.source_chunk_attention(q[b, :nb], kk[b], vv[b], int(total[b]))
+            assert np.abs(to_f64(out[b, :nb]) - o_ref).max() <= 2e-2, b
+            assert np.abs(to_f64(lse[b, :nb]) - l_ref).max() <= 2e-2, b
+        # rows past n_new[b] are not written
+        assert (out[b, nb:] == 3.0).all() and (lse[b, nb:] == 7.0).all()
+
+
+def test_source_chunk_small_ragged(st):
+    rng = np.random.Generator(np.random.PCG64(440))
+    # first sentence (empty cache), mid-page starts, a chunk crossing the 512-token split, an empty chunk
+    _check_source_chunk(st, rng, 5, 4, 2, 128, [0, 5, 500, 33, 100], [7, 16, 40, 0, 1], 40)
+
+
+def test_source_chunk_many_row_blocks(st):
+    """64 tokens x group 4 = 256 (token, head) rows = 8 blocks of 32; head_dim 64 as well."""
+    rng = np.random.Generator(np.random.PCG64(441))
+    _check_source_chunk(st, rng, 2, 8, 2, 128, [1000, 17], [64, 61], 64)
+    _check_source_chunk(st, rng, 2, 4, 4, 64, [70, 0], [33, 64], 64)
+
+
+def test_source_chunk_equals_prefill_source_rows(st):
+    """The streaming path agrees with the batch path: chunk prefill over the cache == the same source rows of st_attn_prefill."""
+    cfg = W.random_prefill(442, 1, 6, (20, 50), (5, 30), 4, 2, 128, "bf16", layout="interleaved")
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    out = st.st_attn_prefill(tq, tk, tv, plan)
+    src = torch.from_numpy(np.nonzero(cfg.stream_ids == O.SRC)[0]).to(DEV)
+    S = len(src); last = int(cfg.src_lens[0][-1])         # the last sentence arrives as a chunk
+    rng = np.random.Generator(np.random.PCG64(443))
+    cs, _ = make_cache(1, (S + 15) // 16, 2, 128, rng); cr, _ = make_cache(1, 1, 2, 128, rng)
+    caches = st.DualCache(cs, cr)
+    st.st_kv_append(caches, st.ST_SOURCE, tk[src][None].contiguous(), tv[src][None].contiguous())
+    one = torch.tensor([S], dtype=torch.int32, device=DEV)
+    got = st.st_attn_source_chunk(tq[src[S - last:]][None].contiguous(), caches, one, S)
+    torch.cuda.synchronize()
+    assert (got[0].float() - out[src[S - last:]].float()).abs().max().item() <= 2e-2

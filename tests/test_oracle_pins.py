@@ -272,6 +272,29 @@ def test_p8_decode_equals_last_prefill_row(layout):
     assert np.abs(o_d - o[last3]).max() < 1e-13 and np.abs(l_d - lse[last3]).max() < 1e-13
 
 
+# ---- P8b: an arriving source chunk (Alg. 1, prefill loop) == the same source rows of the full prefill
+@pytest.mark.parametrize("layout", ["grouped", "interleaved"])
+def test_p8b_source_chunk_equals_prefill_source_rows(layout):
+    rng = np.random.Generator(np.random.PCG64(81))
+    s = [3, 4, 2, 5]; r = [4, 1, 6, 3]
+    stream, seg, pos = W.tokens_from_segments(s, r, layout)
+    n, hq, hkv, d = len(stream), 4, 2, 16
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    o, lse = O.attention_dense(q, k, v, stream, seg, pos)
+    src = np.nonzero(stream == O.SRC)[0]
+    # the third sentence (2 tokens) arrives when 7 source tokens are cached: cache then holds 9
+    chunk = src[7:9]
+    o_c, l_c = O.source_chunk_attention(q[chunk], k[src], v[src], 9)
+    assert np.abs(o_c - o[chunk]).max() < 1e-13 and np.abs(l_c - lse[chunk]).max() < 1e-13
+    # the whole source stream as one chunk is plain causal attention over the sources
+    o_all, _ = O.source_chunk_attention(q[src], k[src], v[src], len(src))
+    assert np.abs(o_all - o[src]).max() < 1e-13
+    # and reasoning never leaks in: perturbing reasoning K/V leaves the chunk unchanged
+    k2 = k.copy(); k2[stream == O.RSN] += 5.0
+    o2, _ = O.attention_dense(q, k2, v, stream, seg, pos)
+    assert np.abs(o2[chunk] - o[chunk]).max() < 1e-13
+
+
 # ---- P9: paged append + gather == contiguous cache
 def test_p9_paged_gather():
     rng = np.random.Generator(np.random.PCG64(90))
