@@ -127,7 +127,7 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": kern_ms, "n_tokens": n}
 
 
-def bench_decode(st, torch, W, steps, warmup, n_layers=None):
+def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
     dev = "cuda"
     shp = W.config3() if n_layers is None else W.config3(n_layers=n_layers)
     B, L, hq, hkv, d = shp.batch, shp.n_layers, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
@@ -170,20 +170,92 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None):
     for _ in range(warmup):
         step(None)
     torch.cuda.synchronize()
-    st.st_profile_enable(True)            # HIP events around every layer's split kernel
-    t0 = time.perf_counter()
-    for i in range(steps):
+    # kernel-only duration of the split kernel (HIP events on the launch stream), from eager steps
+    st.st_profile_enable(True)
+    for i in range(min(steps, 3)):
         step(i)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
     st.st_profile_enable(False)
     layer_ms, n_rec = st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
-    assert n_rec == steps * L
+    assert n_rec == min(steps, 3) * L
+    # the timed steps: the whole 28-layer step (both streams) recorded once into a HIP graph and replayed,
+    # which removes the per-launch gaps of this launch-bound loop; eager launches if capture is unavailable
+    mode = "hip-graph"
+    graph = None
+    if use_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step(None)
+            step(None)                                     # eager result of the same step
+            torch.cuda.synchronize()
+            ref = out.clone()
+            for _ in range(3):                             # every replay, with eager work in between, must reproduce it
+                out.zero_()
+                graph.replay()
+                torch.cuda.synchronize()
+                if not torch.equal(ref, out):
+                    raise RuntimeError("graph replay differs from the eager step")
+                step(None)
+                torch.cuda.synchronize()
+        except Exception as exc:                           # noqa: BLE001
+            print(f"bench.py: HIP graph capture not used ({exc}); timing eager launches", file=sys.stderr)
+            graph = None
+    if graph is None:
+        mode = "eager"
+    run = graph.replay if graph is not None else (lambda: step(None))
+    run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
     tokens = float((shp.src_visible_len.astype(np.int64) + shp.rsn_len).sum())
     per_layer = tokens * 2 * hkv * d * 2
     append_bytes = float(B * (shp.src_append + 1)) * 2 * hkv * d * 2 * 2 * L
     return {"shape": shp, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
-            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer}
+            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode}
+
+
+def bench_source_chunk(st, torch, W, steps, warmup):
+    """Alg. 1's prefill loop on the Qwen3-8B-shaped streaming shape (configs[4]), one layer: a 32-token source chunk per
+    sequence is appended and attends causally over source caches of 1-8K tokens."""
+    dev = "cuda"
+    shp = W.config5()
+    B, hq, hkv, d, n_new = shp.batch, shp.n_q_heads, shp.n_kv_heads, shp.head_dim, shp.src_append
+    rng = np.random.Generator(np.random.PCG64(shp.seed))
+    pages = (shp.max_src_len + 15) // 16
+    cs = st.KVCache(B * pages, B, pages, hkv, d, torch.from_numpy(W.shuffled_page_table(rng, B, pages)).to(dev))
+    cr = st.KVCache(B, B, 1, hkv, d, torch.arange(B, dtype=torch.int32, device=dev).reshape(B, 1).contiguous())
+    g = torch.Generator(device=dev); g.manual_seed(shp.seed)
+    cs.k_pool.normal_(generator=g); cs.v_pool.normal_(generator=g)
+    caches = st.DualCache(cs, cr)
+    before = torch.from_numpy(shp.src_visible_len).to(dev)
+    total = torch.from_numpy((shp.src_visible_len + n_new).astype(np.int32)).to(dev)
+    k_new = torch.randn((B, n_new, hkv, d), generator=g, device=dev).to(torch.bfloat16)
+    v_new = torch.randn((B, n_new, hkv, d), generator=g, device=dev).to(torch.bfloat16)
+    q = torch.randn((B, n_new, hq, d), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    max_s = int(shp.src_visible_len.max()) + n_new
+    ws = torch.empty(st.st_source_chunk_workspace_bytes(B, hq, hkv, d, n_new, max_s), dtype=torch.uint8, device=dev)
+
+    def step():
+        cs.appended_len.copy_(before)
+        st.st_kv_append(caches, st.ST_SOURCE, k_new, v_new, host_len_upper_bound=shp.max_src_len)
+        st.st_attn_source_chunk(q, caches, total, max_s, out=out, workspace=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    tok = shp.src_visible_len.astype(np.float64) + n_new
+    flops = 4.0 * d * hq * float((n_new * tok - n_new * (n_new - 1) / 2).sum())      # causal inside the chunk
+    return {"ms_per_step": dt * 1e3, "cache_bytes": float(tok.sum()) * 2 * hkv * d * 2, "flops": flops, "batch": B, "n_new": n_new}
 
 
 def cpu_baseline(W, O, flops_per_pair_head):
@@ -213,6 +285,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None, help="steps of the 28-layer decode workload (default: min(steps, 10))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches of the decode step instead of a HIP graph replay")
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -257,7 +330,7 @@ def main():
     }
     if not args.no_decode:
         dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
-        dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers)
+        dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph)
         gbps_step = dec["bytes_per_step"] / dec["sec_per_step"] / 1e9
         gbps_kernel = dec["bytes_per_layer"] / (dec["layer_decode_ms"] * 1e-3) / 1e9
         shp = dec["shape"]
@@ -265,7 +338,7 @@ def main():
             "workload": "configs[2]: Qwen3-1.7B-shaped decode, 28 layers, batch 32, 16 q / 8 kv heads, head_dim 128, bf16, "
                         "source cache 2048 + reasoning cache U[1024,6144], 16-token pages (shuffled), one token per step, "
                         "concurrent 64-token source append per layer on a second stream",
-            "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
+            "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "launch": dec["mode"], "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
             "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
             "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
             "roofline": {"kernel": "decode_split16_kernel<128> (one layer)", "bound": "hbm",
@@ -273,6 +346,15 @@ def main():
                          "frac": round(gbps_kernel / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["decode_split16_kernel<128>"],
                          "avg_kernel_ms": round(dec["layer_decode_ms"], 4)},
         }
+    if not args.no_decode:
+        sc = bench_source_chunk(st, torch, W, min(args.steps, 20), min(args.warmup, 3))
+        line["source_chunk"] = {
+            "workload": "configs[4] source side, one layer: batch 64, 32 q / 8 kv heads, 32-token chunk appended to source caches "
+                        "U[1024,8192] (16-token pages) and attended causally over them (Alg. 1 prefill loop)",
+            "ms_per_step": round(sc["ms_per_step"], 4), "tflops": round(sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12, 2),
+            "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
+            "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
+                    "each of which streams the cache again"}
     if not args.no_cpu_baseline:
         from oracle import streaming_attention as O
         line["cpu_baseline"] = cpu_baseline(W, O, 4.0 * cfg.head_dim)
