@@ -37,7 +37,7 @@ def _median(xs):
     return float(np.median(np.asarray(xs, dtype=np.float64)))
 
 
-def bench_prefill_step(st, torch, W, steps, warmup):
+def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
     dev = "cuda"
     cfg = W.config2()
     hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -86,7 +86,7 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     k_tok = torch.randn((batch, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     v_tok = torch.randn((batch, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     pos_tok = torch.from_numpy(R.astype(np.int32)).to(dev)
-    out_tok = torch.empty_like(q_tok)
+    out_tok = torch.empty_like(q_tok); q_tok_rot = torch.empty_like(q_tok); k_tok_rot = torch.empty_like(k_tok)
     max_s, max_r = int(S.max()), int(R.max()) + 1
     dec_ws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream()
@@ -101,10 +101,10 @@ def bench_prefill_step(st, torch, W, steps, warmup):
         st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
         st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
         st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
-        st.st_rope_apply(q_tok.view(batch, hq, d), pos_tok, cfg.theta)
-        st.st_rope_apply(k_tok.view(batch, hkv, d), pos_tok, cfg.theta)
-        st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
-        st.st_attn_decode_dual(q_tok, caches, src_vis, rsn_len, max_s, max_r, out=out_tok, workspace=dec_ws)
+        st.st_rope_apply(q_tok.view(batch, hq, d), pos_tok, cfg.theta, out=q_tok_rot.view(batch, hq, d))
+        st.st_rope_apply(k_tok.view(batch, hkv, d), pos_tok, cfg.theta, out=k_tok_rot.view(batch, hkv, d))
+        st.st_kv_append(caches, st.ST_REASONING, k_tok_rot, v_tok, host_len_upper_bound=max_r)
+        st.st_attn_decode_dual(q_tok_rot, caches, src_vis, rsn_len, max_s, max_r, out=out_tok, workspace=dec_ws)
         main.wait_stream(side)
         return p
 
@@ -112,19 +112,48 @@ def bench_prefill_step(st, torch, W, steps, warmup):
     for _ in range(warmup):
         plans.append(step(None))
     torch.cuda.synchronize()
-    st.st_profile_enable(True)            # HIP events around the attention kernel, on its launch stream
-    t0 = time.perf_counter()
-    for i in range(steps):
+    # kernel-only duration of the attention kernel (HIP events on its launch stream), from eager steps
+    st.st_profile_enable(True)
+    n_prof = min(steps, 10)
+    for i in range(n_prof):
         plans.append(step(i))
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
     st.st_profile_enable(False)
     kern_ms, n_rec = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
     st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
-    assert n_rec == steps
+    assert n_rec == n_prof
+    # the timed steps: the whole step (13 kernels on two streams) recorded once into a HIP graph and replayed;
+    # every replay is first checked against the eager step, and eager launches are timed if capture is unavailable
+    mode, graph = "eager", None
+    if use_graph:
+        try:
+            ref_out, ref_tok = out.clone(), out_tok.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                plans.append(step(None))
+            for _ in range(3):
+                out.zero_(); out_tok.zero_()
+                graph.replay()
+                torch.cuda.synchronize()
+                if not (torch.equal(ref_out, out) and torch.equal(ref_tok, out_tok)):
+                    raise RuntimeError("graph replay differs from the eager step")
+                plans.append(step(None))
+                torch.cuda.synchronize()
+            mode = "hip-graph"
+        except Exception as exc:                           # noqa: BLE001
+            print(f"bench.py: HIP graph capture not used ({exc}); timing eager launches", file=sys.stderr)
+            graph = None
+    run = graph.replay if graph is not None else (lambda: plans.append(step(None)))
+    run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
     for p in plans:
         p.destroy()
-    return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": kern_ms, "n_tokens": n}
+    return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": kern_ms, "n_tokens": n, "mode": mode}
 
 
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
@@ -285,7 +314,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None, help="steps of the 28-layer decode workload (default: min(steps, 10))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches of the decode step instead of a HIP graph replay")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays of the steps")
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -309,7 +338,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": a.numel() * 2, "bytes_written_per_copy": a.numel() * 2, "copies": 5}))
         return
-    pre = bench_prefill_step(st, torch, W, args.steps, args.warmup)
+    pre = bench_prefill_step(st, torch, W, args.steps, args.warmup, not args.no_graph)
     cfg = pre["cfg"]
     tflops_step = pre["flops"] / pre["sec_per_step"] / 1e12
     tflops_kernel = pre["flops"] / (pre["prefill_kernel_ms"] * 1e-3) / 1e12
@@ -317,7 +346,7 @@ def main():
         "metric": "streaming-mask prefill TFLOP/s + dual-cache decode GB/s, % of MI355X peak",
         "value": round(tflops_step, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(pre["sec_per_step"] * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": pre["mode"],
         "config": {"workload": "configs[1]: Qwen3-0.6B-shaped layer, batch 4, 16 q / 8 kv heads, head_dim 128, bf16, "
                                "32 source (24-64 tok) + 32 reasoning (32-128 tok) segments per sequence, interleaved; "
                                "step = plan + RoPE + streaming-mask prefill + paged append (64-token source chunk, 1 reasoning "
