@@ -23,6 +23,10 @@
 //                         the second product.
 //   prefill_simple_kernel any dtype, one thread per query row, plain fp32 arithmetic.  It is
 //                         the fp32 path (tolerance 1e-4) and walks the same work items.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "st_plan.h"
 
 namespace st {
@@ -465,9 +469,393 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     if (lse && hg == 0) lse[int64_t(tok_q) * n_q_heads + hq] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
 }
 
+
+// --------------------------------------------------------------------------
+// MFMA kernel, two query heads per workgroup (bf16, grouped-query attention with an even group).
+// --------------------------------------------------------------------------
+// Same work items, same packed tiles, same transposed products as prefill_mfma_kernel, but every
+// wave owns its 32 query rows for TWO query heads that share one KV head.  A K (or V^T) operand
+// fragment read from LDS then feeds two MFMAs, and one tile copied into LDS serves twice the
+// arithmetic: the LDS read traffic and the L2 -> LDS copy traffic per flop are both halved, which is
+// what bounds the single-head kernel.  The price is registers (two output accumulators, two score
+// blocks, two Q operands), so only one wave runs per SIMD and nothing but the wave's own
+// instruction stream can hide latency.  The loop is therefore software-pipelined by hand:
+//   phase X of tile t:  scores of tile t+1 (matrix pipe)  beside  exp / row sum / bf16 P of tile t
+//   phase Y of tile t:  O^T += V^T P^T of tile t (matrix pipe)  beside  exponents and row maximum of tile t+1
+// with three K and three V^T buffers and ONE barrier per key tile (tile copies are requested two
+// iterations ahead).
+// The running maximum of a row is only raised when the tile maximum exceeds it by more than
+// kLazyMax (base-2 exponent units).  Probabilities then reach at most 2^kLazyMax, far inside
+// fp32 / bf16 range, the normalisation by l at the end is unchanged, and the rescale of the
+// output accumulator becomes a rare event instead of a per-tile one.
+template <int D>
+struct PairSmem {
+    uint16_t k[3][kTileN * D];
+    uint16_t vt[3][D * kTileN];
+};
+constexpr float kLazyMax = 8.f;
+
+template <int D>
+__global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                                   const uint16_t* __restrict__ q,
+                                                                   const uint16_t* __restrict__ kc,
+                                                                   const uint16_t* __restrict__ vc, PlanView pv,
+                                                                   int n_q_heads, int n_kv_heads, float scale_log2) {
+    constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
+    constexpr int TILE = kTileN * D;              // elements of one K or V^T tile
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    PairSmem<D>& sm = *reinterpret_cast<PairSmem<D>*>(smem_raw);
+
+    const int n_pairs = n_q_heads >> 1;
+    const int rank = blockIdx.x / n_pairs;
+    const int hh = blockIdx.x % n_pairs;
+    const int group = n_q_heads / n_kv_heads;
+    const int hk = hh % n_kv_heads;                 // consecutive workgroups -> consecutive KV heads
+    const int hq0 = hk * group + 2 * (hh / n_kv_heads);
+    const WorkItem it = pv.sorted[rank];
+    if (it.n_rows == 0) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hg = lane >> 5;
+    const int n_tiles = it.a_total + it.b_total;
+
+    constexpr int NL = TILE * 2 / 1024 / 4;         // 1 KB copies per wave per tile
+    const int tile_a0 = it.tile_a0, tile_b0 = it.tile_b0;
+    const size_t head_off = size_t(hk) * pv.pack_tiles * TILE + (wave * NL) * 512 + lane * 8;
+    const uint16_t* kc_lane = kc + head_off;
+    const uint16_t* vc_lane = vc + head_off;
+    auto tile_of = [&](int ti) {
+        ti = min(ti, n_tiles - 1);                   // past the end: fetch the last tile again (never used)
+        return ti < it.a_total ? tile_a0 + ti : tile_b0 + (ti - it.a_total);
+    };
+    const uint32_t lds_k0 = uint32_t(uintptr_t(&sm.k[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
+    const uint32_t lds_v0 = uint32_t(uintptr_t(&sm.vt[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
+    auto issue_k = [&](int ti, int stage) {
+        const uint16_t* src = kc_lane + size_t(tile_of(ti)) * TILE;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_k0 + stage * (TILE * 2) + u * 1024);
+    };
+    auto issue_v = [&](int ti, int stage) {
+        const uint16_t* src = vc_lane + size_t(tile_of(ti)) * TILE;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_v0 + stage * (TILE * 2) + u * 1024);
+    };
+    // copy order: K0 V0 K1 V1 K2 | V2 K3 | V3 K4 | ...   (tile x lives in buffer x % 3)
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
+    issue_v(1, 1);
+    issue_k(2, 2);
+
+    const int row_in_tile = wave * 32 + n;
+    const bool active = row_in_tile < it.n_rows;
+    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
+    const int tok_q = pv.perm[it.a_base + my_row];
+    const int my_vis = pv.vis[it.a_base + my_row];
+
+    bf16x8 qf[2][KS];
+    {
+        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq0) * D + 8 * hg;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < KS; ++j) qf[h][j] = *reinterpret_cast<const bf16x8*>(qp + h * D + 16 * j);
+    }
+
+    f32x16 o_acc[2][DB];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[h][db][i] = 0.f;
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+
+    int koff[KS], voff[4];
+    {
+        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
+    }
+    {
+        int t0 = my_vis, t1 = tok_q;
+        asm volatile("" : "+v"(t0), "+v"(t1));
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            u32x4 t = __builtin_bit_cast(u32x4, qf[h][j]);
+            asm volatile("" : "+v"(t));
+            qf[h][j] = __builtin_bit_cast(bf16x8, t);
+        }
+
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // scores of the tile in buffer `stage`, both heads: every K fragment feeds two MFMAs
+    auto scores = [&](f32x16 (&s)[2][SB], int stage) {
+        const uint16_t* kb = &sm.k[0][0] + stage * TILE;
+#pragma unroll
+        for (int f = 0; f < SB * KS; ++f) {
+            const int sb = f % SB, j = f / SB;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + 32 * sb * D + koff[j]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                s[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[h][j], j == 0 ? zero16 : s[h][sb], 0, 0, 0);
+        }
+    };
+    // tile parameters
+    struct TileInfo { bool partial; int limit; int c0; };
+    auto tile_info = [&](int ti) {
+        ti = min(ti, n_tiles - 1);
+        const bool in_a = ti < it.a_total;
+        const int kt = in_a ? ti : ti - it.a_total;
+        const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? it.n_stream : it.n_src);
+        return TileInfo{partial, in_a ? my_row + 1 : my_vis, kt * kTileN + 8 * hg};
+    };
+    // Softmax state of a row, per head, in base-2 exponent units: m_run is the reference maximum
+    // (-inf until the row has seen a finite score), m_ref the finite value actually subtracted
+    // (0 while m_run is -inf).  Scores are turned into exponents t = s * scale - m_ref the moment
+    // they leave the accumulation registers, i.e. BEFORE the maximum of their tile is known; in the
+    // common case the tile maximum stays within kLazyMax of the reference and t is final.
+    // Otherwise (first tile of a row, or a real jump of the maximum) settle() moves the reference
+    // and repairs t, l and the output accumulator, out of line.
+    float m_ref[2] = {0.f, 0.f};
+    // value of lane ^ 32 (v_permlane32_swap exchanges the upper half of its first operand with the
+    // lower half of its second one; with both set to x, each lane finds its partner's x in one of them)
+    auto max_with_partner = [&](float x) {
+        float a = x, b = x;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+        return fmaxf(a, b);
+    };
+    auto rescale_acc = [&](int h, float alpha) {
+        // The accumulators live in accumulation registers, which the vector ALU cannot multiply in
+        // place: each element goes through a temporary by hand, so that nothing here asks for the
+        // accumulators in ordinary vector registers (the register allocator would then shuttle all
+        // 128 of them back and forth in every iteration).  The idle cycles in front let the last
+        // matrix instructions retire before their results are read, the ones behind separate the
+        // last write from the next matrix instruction.
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float x = o_acc[h][db][i], tmp;
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                             : "+a"(x), "=&v"(tmp) : "v"(alpha));
+                o_acc[h][db][i] = x;
+            }
+        asm volatile("s_nop 7" ::: "memory");
+    };
+    // sv holds the exponents of a fresh tile relative to m_ref, mx their per-lane maximum
+    auto settle = [&](f32x16 (&sv)[2][SB], float (&mx)[2], const TileInfo& ti) {
+        if (ti.partial) {
+            // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                mx[h] = -INFINITY;
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int col = ti.c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
+                        sv[h][sb][i] = col < ti.limit ? sv[h][sb][i] : -INFINITY;
+                        mx[h] = fmaxf(mx[h], sv[h][sb][i]);
+                    }
+            }
+        }
+        float rise[2];
+        bool g[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            rise[h] = max_with_partner(mx[h]);                   // tile maximum of the row, relative to m_ref
+            g[h] = m_run[h] == -INFINITY ? rise[h] > -INFINITY : rise[h] > kLazyMax;
+        }
+        if (__any(g[0] || g[1])) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float shift = g[h] ? rise[h] : 0.f;        // rows that stay put: shift 0, alpha 1
+                const float m_new = m_ref[h] + shift;
+                const float alpha = g[h] ? __builtin_amdgcn_exp2f(m_run[h] - m_new) : 1.f;
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sv[h][sb][i] -= shift;
+                l_run[h] *= alpha;
+                rescale_acc(h, alpha);
+                m_run[h] = g[h] ? m_new : m_run[h];
+                m_ref[h] = g[h] ? m_new : m_ref[h];
+            }
+        }
+    };
+
+    // ---- prologue: exponents and row maximum of tile 0 ----
+    f32x16 sv[2][SB];
+    wait_vmcnt<4 * NL>();                                // K0 has landed
+    __syncthreads();
+    scores(sv, 0);
+    {
+        float mx[2] = {-INFINITY, -INFINITY};
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float x = sv[h][sb][i];
+                    asm volatile("" : "+v"(x));                   // in vector registers from here on
+                    x *= scale_log2;
+                    sv[h][sb][i] = x;
+                    mx[h] = fmaxf(mx[h], x);
+                }
+        settle(sv, mx, tile_info(0));
+    }
+
+    int stage = 0;                                       // buffer of tile ti
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        // K(ti+1) and V^T(ti) have landed (in flight behind them: V^T(ti+1), K(ti+2)); everybody is
+        // done with K(ti) and V^T(ti-1), whose buffers the next two copies go to
+#ifndef ST_ABL_NOWAIT
+        wait_vmcnt<2 * NL>();
+#endif
+#ifndef ST_ABL_NOBARRIER
+        __syncthreads();
+#endif
+        const int stage1 = stage == 2 ? 0 : stage + 1, stage2 = stage == 0 ? 2 : stage - 1;
+#ifndef ST_ABL_NOLOAD
+        issue_v(ti + 2, stage2);
+        issue_k(ti + 3, stage);
+#endif
+
+        // The two phases below are written in the exact instruction order wanted -- per matrix
+        // instruction one small piece of vector work, LDS operand reads kPF fragments ahead -- and
+        // every piece ends in a scheduling barrier so that the compiler keeps that order.
+        // ---- phase X: scores of tile ti+1  |  probabilities of tile ti ----
+        constexpr int kPF = 3;
+        f32x16 s_next[2][SB];
+        bf16x8 pb[2][SB][2];
+        float psum[2] = {0.f, 0.f};
+        {
+            constexpr int NF = SB * KS;                          // fragment f: key block f % SB, k-step f / SB
+            const uint16_t* kb = &sm.k[0][0] + stage1 * TILE;
+            bf16x8 a[NF];
+#pragma unroll
+            for (int f = 0; f < kPF; ++f) a[f] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f % SB) * D + koff[f / SB]);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                if (f + kPF < NF) {
+                    const int f2 = f + kPF;
+#ifdef ST_ABL_NOLDS
+                    a[f2] = qf[0][f2 % KS];
+#else
+                    a[f2] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f2 % SB) * D + koff[f2 / SB]);
+#endif
+                }
+                const int sb = f % SB, j = f / SB;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    s_next[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[h][j], j == 0 ? zero16 : s_next[h][sb], 0, 0, 0);
+                    // slot 2 f + h of 2 NF: its share of the probabilities of tile ti
+                    constexpr int PER = 16 * SB / NF;            // elements per slot (one head has 16 SB of them, in NF slots)
+                    const int slot = 2 * f + h;
+                    const int hh = slot / NF, e0 = (slot % NF) * PER;
+#pragma unroll
+                    for (int e = e0; e < e0 + PER; ++e) {
+                        const int sb2 = e / 16, i = e % 16;
+#ifdef ST_ABL_NOEXP
+                        const float pr = sv[hh][sb2][i];
+#else
+                        const float pr = __builtin_amdgcn_exp2f(sv[hh][sb2][i]);
+#endif
+                        psum[hh] += pr;
+                        pb[hh][sb2][i >> 3][i & 7] = (__bf16)pr;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        // (the sums are wanted HERE: left alone, the optimiser defers them past the second phase and
+        //  recomputes the exponentials they are made of)
+        asm volatile("" : "+v"(psum[0]), "+v"(psum[1]));
+#pragma unroll
+        for (int h = 0; h < 2; ++h) l_run[h] += psum[h];
+
+        // ---- phase Y: O^T += V^T P^T of tile ti  |  row maximum of tile ti+1 ----
+        float mx[2] = {-INFINITY, -INFINITY};
+        {
+            constexpr int NF = DB * SB * 2;                      // fragment f: d block f % DB, 16-key step f / DB
+            const uint16_t* vb = &sm.vt[0][0] + stage * TILE;
+            bf16x8 a[NF];
+#pragma unroll
+            for (int f = 0; f < kPF; ++f) a[f] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f % DB) * kTileN + voff[f / DB]);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                if (f + kPF < NF) {
+                    const int f2 = f + kPF;
+#ifdef ST_ABL_NOLDS
+                    a[f2] = qf[1][f2 % KS];
+#else
+                    a[f2] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f2 % DB) * kTileN + voff[f2 / DB]);
+#endif
+                }
+                const int db = f % DB, st = f / DB;              // keys 16 st .. 16 st + 15
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    o_acc[h][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[h][st >> 1][st & 1], o_acc[h][db], 0, 0, 0);
+                    constexpr int PER = 16 * SB / NF;
+                    const int slot = 2 * f + h;
+                    const int hh = slot / NF, e0 = (slot % NF) * PER;
+#pragma unroll
+                    for (int e = e0; e < e0 + PER; ++e) {
+                        const int sb2 = e / 16, i = e % 16;
+                        float x = s_next[hh][sb2][i];
+                        asm volatile("" : "+v"(x));               // ONE move out of the accumulation registers
+                        x = fmaf(x, scale_log2, -m_ref[hh]);
+                        sv[hh][sb2][i] = x;
+                        mx[hh] = fmaxf(mx[hh], x);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        asm volatile("" : "+v"(mx[0]), "+v"(mx[1]));        // computed above, not in a later block
+        settle(sv, mx, tile_info(ti + 1));
+        stage = stage1;
+    }
+    wait_vmcnt<0>();                                     // no copy into LDS may outlive the workgroup
+
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float l_tot = l_run[h] + __shfl_xor(l_run[h], 32);   // wave-wide exchange: inactive rows take part
+        if (!active) continue;
+        const float inv = 1.f / l_tot;
+        uint16_t* op = out + (int64_t(tok_q) * n_q_heads + hq0 + h) * D;
+        // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o4[c] = (__bf16)(o_acc[h][db][4 * q4 + c] * inv);
+                *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * hg) = o4;
+            }
+        if (lse && hg == 0) lse[int64_t(tok_q) * n_q_heads + hq0 + h] = (m_run[h] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    }
+}
+
 }  // namespace st
 
 using namespace st;
+
+// ST_PREFILL_SINGLE=1 in the environment keeps the one-head-per-workgroup kernel (for comparisons)
+static bool prefill_force_single() {
+    static const bool v = [] { const char* e = getenv("ST_PREFILL_SINGLE"); return e && e[0] == '1'; }();
+    return v;
+}
 
 static size_t prefill_ws_bytes(const st_plan* plan, int n_kv_heads, int head_dim, st_dtype dt) {
     if (dt != ST_BF16) return 0;                     // the fp32 path reads q / k / v in place
@@ -525,27 +913,33 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
     uint16_t* kc = static_cast<uint16_t*>(workspace);
     uint16_t* vc = kc + need / (2 * sizeof(uint16_t));
     const float scale_log2 = scale * kLog2e;
-    if (head_dim == 64) {
-        const size_t smem = sizeof(MfmaSmem<64>);
-        ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<64>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
-        hipLaunchKernelGGL((prefill_pack_kernel<64>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
+    // two query heads per workgroup whenever heads come in pairs over a KV head
+    const bool pair = ((n_q_heads / n_kv_heads) % 2 == 0) && !prefill_force_single();
+    auto launch = [&](auto dtag) -> st_status {
+        constexpr int HD = decltype(dtag)::value;
+        hipLaunchKernelGGL((prefill_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
                            (const uint16_t*)v, pv, n_kv_heads);
-        prof_begin(kProfPrefillAttn, s);
-        hipLaunchKernelGGL((prefill_mfma_kernel<64>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
-                           (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
-        prof_end(kProfPrefillAttn, s);
-    } else {
-        const size_t smem = sizeof(MfmaSmem<128>);
-        ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<128>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
-        hipLaunchKernelGGL((prefill_pack_kernel<128>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
-                           (const uint16_t*)v, pv, n_kv_heads);
-        prof_begin(kProfPrefillAttn, s);
-        hipLaunchKernelGGL((prefill_mfma_kernel<128>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
-                           (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
-        prof_end(kProfPrefillAttn, s);
-    }
+        if (pair) {
+            const size_t smem = sizeof(PairSmem<HD>);
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_pair_kernel<HD>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            prof_begin(kProfPrefillAttn, s);
+            hipLaunchKernelGGL((prefill_mfma_pair_kernel<HD>), dim3((unsigned)(blocks / 2)), dim3(256), smem, s, (uint16_t*)out, lse,
+                               (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
+            prof_end(kProfPrefillAttn, s);
+        } else {
+            const size_t smem = sizeof(MfmaSmem<HD>);
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<HD>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            prof_begin(kProfPrefillAttn, s);
+            hipLaunchKernelGGL((prefill_mfma_kernel<HD>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
+                               (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
+            prof_end(kProfPrefillAttn, s);
+        }
+        return ST_OK;
+    };
+    const st_status lr = head_dim == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});
+    if (lr != ST_OK) return lr;
     ST_LAUNCH_CHECK("prefill_pack_kernel / prefill_mfma_kernel");
     return ST_OK;
 }
