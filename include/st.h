@@ -60,6 +60,15 @@ const char* st_last_error(void);
 /* Library version (major * 100 + minor). */
 int32_t st_version(void);
 
+/* Which bf16 attention kernel st_attn_prefill launches: ST_PREFILL_AUTO (default) chooses by problem
+ * size, ST_PREFILL_ONE_HEAD keeps one query head per workgroup, ST_PREFILL_TWO_HEADS serves two
+ * query heads of one KV head per workgroup wherever n_q_heads / n_kv_heads is even (otherwise it
+ * falls back to one head).  Results agree within rounding.  Process-wide; the environment variable
+ * ST_PREFILL_VARIANT (1 or 2) sets the initial value.  Returns the previous setting; values other
+ * than the three below leave the setting unchanged. */
+enum { ST_PREFILL_AUTO = 0, ST_PREFILL_ONE_HEAD = 1, ST_PREFILL_TWO_HEADS = 2 };
+int32_t st_prefill_variant_set(int32_t variant);
+
 /* Optional kernel timing for benchmarks.  While enabled, st_attn_prefill brackets its attention
  * kernel (ST_PROF_PREFILL_ATTN) and st_attn_decode_dual its split kernel (ST_PROF_DECODE_SPLIT)
  * with HIP events on the launch stream.  st_profile_read WAITS for the recorded launches, returns

@@ -61,6 +61,8 @@ def load_library():
     lib.st_last_error.argtypes = []
     lib.st_version.restype = i32
     lib.st_version.argtypes = []
+    lib.st_prefill_variant_set.restype = i32
+    lib.st_prefill_variant_set.argtypes = [i32]
     lib.st_profile_enable.restype = None
     lib.st_profile_enable.argtypes = [i32]
     lib.st_profile_read.restype = i32
@@ -141,6 +143,14 @@ def st_last_error():
 
 
 ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT = 0, 1
+
+
+ST_PREFILL_AUTO, ST_PREFILL_ONE_HEAD, ST_PREFILL_TWO_HEADS = 0, 1, 2
+
+
+def st_prefill_variant_set(variant):
+    """Select the bf16 prefill attention kernel; returns the previous setting."""
+    return int(load_library().st_prefill_variant_set(int(variant)))
 
 
 def st_profile_enable(on):

@@ -25,6 +25,7 @@
 //                         the fp32 path (tolerance 1e-4) and walks the same work items.
 #include <stdlib.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "st_plan.h"
@@ -33,6 +34,7 @@ namespace st {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazyMax = 8.f;                   // exponent units a tile maximum may exceed the running one
 
 struct ItemGeom {
     int S;           // source tokens
@@ -343,6 +345,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
     }
 
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bf16x2 ones2;
+    ones2[0] = (__bf16)1.f;
+    ones2[1] = (__bf16)1.f;
     for (int ti = 0; ti < n_tiles; ++ti) {
         const int buf = ti & 1;
         // K(ti) has landed (still in flight behind it: V^T(ti), K(ti+1)); everybody is done with tile ti-1
@@ -402,34 +407,44 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restri
                 }
         }
         // ---- online softmax (base-2, scale folded in) ----------------------
+        // Lazy running maximum: it is only raised when the tile maximum exceeds it by more than
+        // kLazyMax exponent units.  Probabilities are then bounded by 2^kLazyMax instead of 1 (harmless
+        // in fp32 / bf16, and the final division by l is unchanged), and the rescale of the output
+        // accumulator -- 64 multiplications per lane -- becomes a rare event instead of a per-tile one.
         float mx = -INFINITY;
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[sb][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * scale_log2);
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+        const bool grew = mx > m_run + kLazyMax;         // also true for the first finite maximum
+        const float m_new = grew ? mx : m_run;
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        const bool grew = m_new > m_run;                 // the running maximum moved for this row
         m_run = m_new;
+        // the row sum is taken over the bf16-rounded probabilities, two per v_dot2c_f32_bf16: half the
+        // additions, and l then matches the P that multiplies V
         float psum = 0.f;
         bf16x8 pb[SB][2];
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[sb][i], scale_log2, -m_use));
-                psum += p;
-                pb[sb][i >> 3][i & 7] = (__bf16)p;
+            for (int i = 0; i < 16; i += 2) {
+                bf16x2 p2;
+                p2[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_acc[sb][i], scale_log2, -m_use));
+                p2[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_acc[sb][i + 1], scale_log2, -m_use));
+                psum = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, psum, false);
+                pb[sb][i >> 3][i & 7] = p2[0];
+                pb[sb][i >> 3][(i & 7) + 1] = p2[1];
             }
-        l_run = l_run * alpha + psum;
-        if (__any(grew)) {                               // otherwise alpha == 1 in every lane: skip the rescale
+        if (__any(grew)) {                               // otherwise alpha == 1 in every lane
+            l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
         }
+        l_run += psum;
 
         // ---- O^T += V^T P^T --------------------------------------------------
         {
@@ -493,8 +508,6 @@ struct PairSmem {
     uint16_t k[3][kTileN * D];
     uint16_t vt[3][D * kTileN];
 };
-constexpr float kLazyMax = 8.f;
-
 template <int D>
 __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
                                                                    const uint16_t* __restrict__ q,
@@ -718,17 +731,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
     for (int ti = 0; ti < n_tiles; ++ti) {
         // K(ti+1) and V^T(ti) have landed (in flight behind them: V^T(ti+1), K(ti+2)); everybody is
         // done with K(ti) and V^T(ti-1), whose buffers the next two copies go to
-#ifndef ST_ABL_NOWAIT
         wait_vmcnt<2 * NL>();
-#endif
-#ifndef ST_ABL_NOBARRIER
         __syncthreads();
-#endif
         const int stage1 = stage == 2 ? 0 : stage + 1, stage2 = stage == 0 ? 2 : stage - 1;
-#ifndef ST_ABL_NOLOAD
         issue_v(ti + 2, stage2);
         issue_k(ti + 3, stage);
-#endif
 
         // The two phases below are written in the exact instruction order wanted -- per matrix
         // instruction one small piece of vector work, LDS operand reads kPF fragments ahead -- and
@@ -748,11 +755,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
             for (int f = 0; f < NF; ++f) {
                 if (f + kPF < NF) {
                     const int f2 = f + kPF;
-#ifdef ST_ABL_NOLDS
-                    a[f2] = qf[0][f2 % KS];
-#else
                     a[f2] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f2 % SB) * D + koff[f2 / SB]);
-#endif
                 }
                 const int sb = f % SB, j = f / SB;
 #pragma unroll
@@ -765,11 +768,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
 #pragma unroll
                     for (int e = e0; e < e0 + PER; ++e) {
                         const int sb2 = e / 16, i = e % 16;
-#ifdef ST_ABL_NOEXP
-                        const float pr = sv[hh][sb2][i];
-#else
                         const float pr = __builtin_amdgcn_exp2f(sv[hh][sb2][i]);
-#endif
                         psum[hh] += pr;
                         pb[hh][sb2][i >> 3][i & 7] = (__bf16)pr;
                     }
@@ -795,11 +794,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
             for (int f = 0; f < NF; ++f) {
                 if (f + kPF < NF) {
                     const int f2 = f + kPF;
-#ifdef ST_ABL_NOLDS
-                    a[f2] = qf[1][f2 % KS];
-#else
                     a[f2] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f2 % DB) * kTileN + voff[f2 / DB]);
-#endif
                 }
                 const int db = f % DB, st = f / DB;              // keys 16 st .. 16 st + 15
 #pragma unroll
@@ -851,10 +846,22 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
 
 using namespace st;
 
-// ST_PREFILL_SINGLE=1 in the environment keeps the one-head-per-workgroup kernel (for comparisons)
-static bool prefill_force_single() {
-    static const bool v = [] { const char* e = getenv("ST_PREFILL_SINGLE"); return e && e[0] == '1'; }();
+// Kernel choice of the bf16 path: ST_PREFILL_AUTO / ONE_HEAD / TWO_HEADS, initialised from the
+// environment variable ST_PREFILL_VARIANT (1 or 2), changed by st_prefill_variant_set.
+static std::atomic<int>& prefill_variant_ref() {
+    static std::atomic<int> v{[] {
+        const char* e = getenv("ST_PREFILL_VARIANT");
+        return (e && (e[0] == '1' || e[0] == '2') && e[1] == 0) ? e[0] - '0' : int(ST_PREFILL_AUTO);
+    }()};
     return v;
+}
+static int prefill_variant() { return prefill_variant_ref().load(std::memory_order_relaxed); }
+
+extern "C" int32_t st_prefill_variant_set(int32_t variant) {
+    const int prev = prefill_variant();
+    if (variant == ST_PREFILL_AUTO || variant == ST_PREFILL_ONE_HEAD || variant == ST_PREFILL_TWO_HEADS)
+        prefill_variant_ref().store(variant, std::memory_order_relaxed);
+    return prev;
 }
 
 static size_t prefill_ws_bytes(const st_plan* plan, int n_kv_heads, int head_dim, st_dtype dt) {
@@ -913,8 +920,11 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
     uint16_t* kc = static_cast<uint16_t*>(workspace);
     uint16_t* vc = kc + need / (2 * sizeof(uint16_t));
     const float scale_log2 = scale * kLog2e;
-    // two query heads per workgroup whenever heads come in pairs over a KV head
-    const bool pair = ((n_q_heads / n_kv_heads) % 2 == 0) && !prefill_force_single();
+    // Two query heads per workgroup when heads come in pairs over a KV head and the batch is large
+    // enough to keep every compute unit busy for several rounds of such (one per CU) workgroups;
+    // small batches finish sooner with twice as many, lighter workgroups.
+    const int variant = prefill_variant();
+    const bool pair = ((n_q_heads / n_kv_heads) % 2 == 0) && (variant == ST_PREFILL_TWO_HEADS || (variant == ST_PREFILL_AUTO && blocks / 2 >= 2048));
     auto launch = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
         hipLaunchKernelGGL((prefill_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,

@@ -90,6 +90,15 @@ def test_config4a_prefill_16k(st):
     _prefill_full(st, W.config4a(), meta_seqs=(0, 5))
 
 
+def test_config4a_prefill_16k_one_head_kernel(st):
+    """The same batch through the kernel the automatic choice does NOT take at this size."""
+    prev = st.st_prefill_variant_set(st.ST_PREFILL_ONE_HEAD)
+    try:
+        _prefill_full(st, W.config4a(), meta_seqs=())
+    finally:
+        st.st_prefill_variant_set(prev)
+
+
 def test_config4b_prefill_128_pairs(st):
     """Count-pinned variant (128 pairs, about 37K tokens per sequence): full metadata for one sequence."""
     _prefill_full(st, W.config4b(), meta_seqs=(3,), n_extra=12)

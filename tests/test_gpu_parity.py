@@ -180,6 +180,29 @@ def test_prefill_config2_bf16_full(st):
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("variant", ["ST_PREFILL_ONE_HEAD", "ST_PREFILL_TWO_HEADS"])
+def test_prefill_each_bf16_kernel(st, variant):
+    """Both bf16 attention kernels, pinned in turn, against the oracle: small tiles (head_dim 64), ragged
+    random structures (two heads per KV head), degenerate structures, and the full configs[1] batch."""
+    prev = st.st_prefill_variant_set(getattr(st, variant))
+    try:
+        assert st.st_prefill_variant_set(getattr(st, variant)) == getattr(st, variant)
+        cfg = W.config1()
+        cfg.dtype = "bf16"
+        _run_prefill(st, cfg)
+        for seed, d in ((301, 64), (302, 128), (305, 128)):
+            _run_prefill(st, W.random_prefill(seed, 3, 8, (0, 90), (0, 120), 4, 2, d, "bf16"))
+        lists = [(np.array([5, 130]), np.array([0, 0])), (np.array([0]), np.array([200])), (np.array([], int), np.array([], int)),
+                 (np.array([1]), np.array([1])), (np.array([64, 64]), np.array([128, 1]))]
+        _run_prefill(st, W._assemble("edges", "bf16", 4, 2, 128, lists, "interleaved", 7))
+        _run_prefill(st, W.config2())
+    finally:
+        st.st_prefill_variant_set(prev)
+    assert st.st_prefill_variant_set(prev) == prev
+    assert st.st_prefill_variant_set(17) == prev          # unknown values change nothing
+    assert st.st_prefill_variant_set(prev) == prev
+
+
 def test_prefill_mfma_agrees_with_plain_kernel(st):
     """bf16 inputs through the MFMA kernel vs the same values through the fp32 kernel."""
     cfg = W.random_prefill(311, 2, 10, (10, 80), (10, 100), 4, 2, 128, "bf16")
