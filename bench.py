@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # HBM bytes per launch of the two dominant kernels on the default workloads, from the FETCH_SIZE and
 # WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB copy (x2.000 and x1.000);
 # see profiles/hbm_traffic_prefill_cfg2_decode_cfg3.txt for the runs.
-MEASURED_TRAFFIC = {"prefill_mfma_kernel<128>": 261.9e6 + 65.7e6, "decode_split16_kernel<128>": 702.5e6 + 3.0e6}
+MEASURED_TRAFFIC = {"prefill_mfma_kernel<128>": 249.2e6 + 65.8e6, "decode_split16_kernel<128>": 702.6e6 + 3.0e6}
 
 
 def _median(xs):
@@ -154,6 +154,38 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
     for p in plans:
         p.destroy()
     return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": kern_ms, "n_tokens": n, "mode": mode}
+
+
+def bench_prefill_long(st, torch, W, reps):
+    """Attention stage alone on configs[3] (8 x 16,384 tokens, 32 q / 8 kv heads): the size at which
+    st_attn_prefill takes its two-heads-per-workgroup kernel."""
+    dev = "cuda"
+    cfg = W.config4a()
+    hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
+    g = torch.Generator(device=dev); g.manual_seed(cfg.seed)
+    q = torch.randn((n, hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((n, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((n, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    seg = torch.from_numpy(cfg.segment_ids).to(dev); strm = torch.from_numpy(cfg.stream_ids).to(dev)
+    pos = torch.from_numpy(cfg.positions).to(dev)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    pairs = plan.visible_pairs()
+    assert [int(x) for x in pairs] == cfg.closed_form_pairs()
+    flops = 4.0 * d * hq * float(pairs.sum())
+    out = torch.empty_like(q)
+    ws = torch.empty(st.st_prefill_workspace_bytes(plan, hkv, d, st.ST_BF16), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    st.st_profile_enable(True)
+    for _ in range(reps):
+        st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    st.st_profile_enable(False)
+    ms, cnt = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    plan.destroy()
+    return {"kernel_ms": ms, "flops": flops, "n_tokens": n, "launches": cnt}
 
 
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
@@ -316,6 +348,8 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays of the steps")
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
+    ap.add_argument("--long-prefill", action="store_true",
+                    help="also time the attention kernel on configs[3] (8 x 16,384 tokens) and report it under 'prefill_long'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -384,6 +418,15 @@ def main():
             "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
             "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
                     "each of which streams the cache again"}
+    if args.long_prefill:
+        lp = bench_prefill_long(st, torch, W, 5)
+        tf = lp["flops"] / (lp["kernel_ms"] * 1e-3) / 1e12
+        line["prefill_long"] = {
+            "workload": "configs[3]: Qwen3-4B-shaped long-context prefill layer, 8 sequences x 16,384 tokens, 32 q / 8 kv heads, "
+                        "head_dim 128, bf16; attention kernel only (two query heads per workgroup)",
+            "avg_kernel_ms": round(lp["kernel_ms"], 3), "effective_flops": lp["flops"],
+            "roofline": {"kernel": "prefill_mfma_pair_kernel<128>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
     if not args.no_cpu_baseline:
         from oracle import streaming_attention as O
         line["cpu_baseline"] = cpu_baseline(W, O, 4.0 * cfg.head_dim)
