@@ -22,8 +22,8 @@ library convention by tests/test_oracle_pins.py.
 Pins (all in tests/test_oracle_pins.py): brute-force gather, layout
 equivariance, Eq. 2 as printed, reduction to library causal attention, source chunk == source rows of prefill,
 closed-form visible-pair counts, LSE-merge == concatenation, RoPE identities,
-decode == last prefill row, paged gather == contiguous.  No function here is
-"parity unpinned".
+decode == last prefill row, paged gather == contiguous, rotate-on-append / rotate-in-decode ==
+the unfused pipeline.  No function here is "parity unpinned".
 """
 import numpy as np
 
@@ -316,6 +316,29 @@ def paged_gather(pool, page_table, b, length):
     for p in range(length):
         out[p] = pool[page_table[b][p // PAGE], p % PAGE]
     return out
+
+
+def paged_append_rotated(k_pool, v_pool, page_table, lens, b, k_rows, v_rows, theta=1.0e6):
+    """Append UNROTATED keys: key t of the call gets the position id of its stream, which is
+    its index in that stream's cache, lens[b] + t (Sec. 3.2: the ids of a stream count its own
+    tokens from 0, so they never change when caches are merged or split), is rotated by it and
+    stored; values are stored as they are.  lens[b] is advanced once.
+    """
+    n = k_rows.shape[0]
+    positions = int(lens[b]) + np.arange(n)
+    start = lens.copy()
+    paged_append(k_pool, page_table, lens, b, rope(k_rows, positions, theta))
+    paged_append(v_pool, page_table, start, b, v_rows)
+
+
+def decode_dual_rotated(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, theta=1.0e6, scale=None):
+    """decode_dual_concat for UNROTATED queries: query row t of the q_len rows is the reasoning
+    token at index rsn_len - q_len + t of its stream (it is already in the reasoning cache, Alg. 1),
+    and that index is its position id.
+    """
+    q_len = q.shape[0]
+    positions = rsn_len - q_len + np.arange(q_len)
+    return decode_dual_concat(rope(q, positions, theta), src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, scale)
 
 
 # --------------------------------------------------------------------------

@@ -315,6 +315,47 @@ def test_p9_paged_gather():
     assert len(set(table.flatten().tolist())) == batch * pages_per_seq
 
 
+# ---- P10: the fused forms (rotate-on-append, rotate-the-query-in-decode) == the unfused pipeline.
+# The position id of a token is its index in its own stream's cache (Sec. 3.2), so caches filled piece by
+# piece from UNROTATED keys hold exactly RoPE(k, stream-local ids), and decoding unrotated queries over them
+# gives the prefill rows of the same tokens.
+@pytest.mark.parametrize("layout", ["grouped", "interleaved"])
+def test_p10_rotate_on_append_and_in_decode_equal_prefill(layout):
+    rng = np.random.Generator(np.random.PCG64(100))
+    s = [3, 20, 2, 9]; r = [4, 1, 17, 3]
+    stream, seg, pos = W.tokens_from_segments(s, r, layout)
+    n, hq, hkv, d, theta = len(stream), 4, 2, 16, 1.0e4
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    # unfused: rotate everything by the paper's ids, dense-mask attention
+    o, lse = O.attention_dense(O.rope(q, pos, theta), O.rope(k, pos, theta), v, stream, seg, pos)
+    src = np.nonzero(stream == O.SRC)[0]; rsn = np.nonzero(stream == O.RSN)[0]
+    # fused: two paged caches filled from the UNROTATED keys in uneven pieces (pages shuffled)
+    n_pages = 8
+    table = rng.permutation(2 * n_pages).reshape(2, n_pages)
+    caches = {}
+    for b, idx, cuts in ((0, src, [0, 1, 17, 18, len(src)]), (1, rsn, [0, 5, 6, 22, len(rsn)])):
+        kp = np.zeros((2 * n_pages, O.PAGE, hkv, d)); vp = np.zeros_like(kp)
+        lens = np.zeros(2, dtype=np.int64)
+        for a, e in zip(cuts[:-1], cuts[1:]):
+            O.paged_append_rotated(kp, vp, table, lens, b, k[idx[a:e]], v[idx[a:e]], theta)
+        assert lens[b] == len(idx)
+        caches[b] = (O.paged_gather(kp, table, b, len(idx)), O.paged_gather(vp, table, b, len(idx)))
+        # the cache holds RoPE(k, stream-local ids) and the values untouched
+        assert np.abs(caches[b][0] - O.rope(k[idx], pos[idx], theta)).max() < 1e-12
+        assert np.array_equal(caches[b][1], v[idx])
+        assert np.array_equal(pos[idx], np.arange(len(idx)))
+    (sk, sv), (rk, rv) = caches[0], caches[1]
+    # last three reasoning rows (all in the last segment: every source token visible), unrotated queries
+    last3 = rsn[-3:]
+    o_d, l_d = O.decode_dual_rotated(q[last3], sk, sv, rk, rv, len(src), len(rsn), theta)
+    assert np.abs(o_d - o[last3]).max() < 1e-12 and np.abs(l_d - lse[last3]).max() < 1e-12
+    # one row in the middle of the third reasoning segment: reasoning cache as it was then, sources of segments 1..3
+    row = rsn[4 + 1 + 8]
+    n_then = 4 + 1 + 9
+    o_d, l_d = O.decode_dual_rotated(q[row][None], sk, sv, rk[:n_then], rv[:n_then], 3 + 20 + 2, n_then, theta)
+    assert np.abs(o_d[0] - o[row]).max() < 1e-12 and np.abs(l_d[0] - lse[row]).max() < 1e-12
+
+
 # ---- metadata derived from the dense mask: closed forms for config 1
 def test_metadata_config1_closed_form():
     cfg = W.config1()
