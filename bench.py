@@ -85,8 +85,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
     q_tok = torch.randn((batch, 1, hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     k_tok = torch.randn((batch, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     v_tok = torch.randn((batch, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    pos_tok = torch.from_numpy(R.astype(np.int32)).to(dev)
-    out_tok = torch.empty_like(q_tok); q_tok_rot = torch.empty_like(q_tok); k_tok_rot = torch.empty_like(k_tok)
+    out_tok = torch.empty_like(q_tok)
     max_s, max_r = int(S.max()), int(R.max()) + 1
     dec_ws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream()
@@ -101,10 +100,10 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
         st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
         st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
         st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
-        st.st_rope_apply(q_tok.view(batch, hq, d), pos_tok, cfg.theta, out=q_tok_rot.view(batch, hq, d))
-        st.st_rope_apply(k_tok.view(batch, hkv, d), pos_tok, cfg.theta, out=k_tok_rot.view(batch, hkv, d))
-        st.st_kv_append(caches, st.ST_REASONING, k_tok_rot, v_tok, host_len_upper_bound=max_r)
-        st.st_attn_decode_dual(q_tok_rot, caches, src_vis, rsn_len, max_s, max_r, out=out_tok, workspace=dec_ws)
+        # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
+        # kernel, both by the token's index in the reasoning stream (its position id)
+        st.st_kv_append_rope(caches, st.ST_REASONING, k_tok, v_tok, cfg.theta, host_len_upper_bound=max_r)
+        st.st_attn_decode_dual_rope(q_tok, caches, src_vis, rsn_len, max_s, max_r, cfg.theta, out=out_tok, workspace=dec_ws)
         main.wait_stream(side)
         return p
 

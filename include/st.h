@@ -249,6 +249,22 @@ st_status st_kv_append(const st_dual_cache* caches, st_stream_kind which,
                        void* hip_stream);
 
 /* ------------------------------------------------------------------------
+ * st_kv_append_rope -- st_kv_append with the rotation fused in.
+ * Sec. 3.2 "Streaming Position Encoding": the tokens of each stream are numbered
+ * from 0 independently of the other stream, so the position id of a token is its
+ * index in its own cache and a key, once rotated and stored, is never rotated
+ * again.  k_new holds UNROTATED keys; key i of sequence b is rotated by position
+ * appended_len[b] + i with base theta_base (same pairing (i, i + D/2) and angle as
+ * st_rope_apply; the angle is reduced in fp64, cos / sin are fp32) and stored;
+ * v_new is stored as it is.  All other arguments, limits and errors as for
+ * st_kv_append; theta_base <= 0 gives ST_ERR_INVALID_ARG.
+ * ---------------------------------------------------------------------- */
+st_status st_kv_append_rope(const st_dual_cache* caches, st_stream_kind which,
+                            const void* k_new, const void* v_new, const int32_t* n_new,
+                            int32_t max_new, int32_t batch, int32_t host_len_upper_bound,
+                            double theta_base, void* hip_stream);
+
+/* ------------------------------------------------------------------------
  * st_attn_decode_dual -- one decode step over both caches.  Alg. 1: the slice of
  * the source cache that keeps N_EOS == N_EOT + 1 and the reasoning cache are read
  * as one merged cache.  Here nothing is copied: partial softmaxes over chunks of
@@ -284,6 +300,16 @@ st_status st_attn_decode_dual(void* out, float* lse, const void* q,
                               const st_dual_cache* caches, const st_dual_lens* lens,
                               int32_t batch, int32_t n_q_heads, float scale,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* st_attn_decode_dual with the query rotation fused in (Sec. 3.2): q holds UNROTATED
+ * queries; row t of sequence b is the reasoning token at index rsn_len[b] - q_len + t of
+ * its stream (already appended, Alg. 1), and is rotated by that position id with base
+ * theta_base before it is used.  Everything else as for st_attn_decode_dual;
+ * theta_base <= 0 gives ST_ERR_INVALID_ARG. */
+st_status st_attn_decode_dual_rope(void* out, float* lse, const void* q,
+                                   const st_dual_cache* caches, const st_dual_lens* lens,
+                                   int32_t batch, int32_t n_q_heads, float scale, double theta_base,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------
  * st_attn_source_chunk -- attention of an arriving source chunk over the paged source

@@ -92,6 +92,11 @@ def load_library():
     lib.st_attn_prefill_ids.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp]
     lib.st_kv_append.restype = i32
     lib.st_kv_append.argtypes = [C.POINTER(_DualCacheStruct), i32, vp, vp, vp, i32, i32, i32, vp]
+    lib.st_kv_append_rope.restype = i32
+    lib.st_kv_append_rope.argtypes = [C.POINTER(_DualCacheStruct), i32, vp, vp, vp, i32, i32, i32, C.c_double, vp]
+    lib.st_attn_decode_dual_rope.restype = i32
+    lib.st_attn_decode_dual_rope.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
+                                             f32, C.c_double, vp, sz, vp]
     lib.st_decode_workspace_bytes.restype = sz
     lib.st_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
     lib.st_attn_decode_dual.restype = i32
@@ -364,8 +369,9 @@ def v_pool_from_logical(x):
     return x.permute(0, 2, 3, 1).contiguous()
 
 
-def st_kv_append(caches, which, k_new, v_new, n_new=None, host_len_upper_bound=None, stream=None):
-    """k_new, v_new: bf16 [batch, max_new, Hkv, D]; n_new: int32 [batch] device tensor or None."""
+def st_kv_append(caches, which, k_new, v_new, n_new=None, host_len_upper_bound=None, stream=None, rope_theta=None):
+    """k_new, v_new: bf16 [batch, max_new, Hkv, D]; n_new: int32 [batch] device tensor or None.
+    rope_theta: None for st_kv_append (keys already rotated), a base for st_kv_append_rope (unrotated keys)."""
     lib = load_library()
     assert k_new.is_cuda and k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
     assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
@@ -376,8 +382,17 @@ def st_kv_append(caches, which, k_new, v_new, n_new=None, host_len_upper_bound=N
     if n_new is not None:
         _dev_i32(n_new, "n_new")
     st = caches.struct()
-    _check(lib.st_kv_append(C.byref(st), which, _ptr(k_new), _ptr(v_new), _ptr(n_new), max_new, batch,
-                            int(host_len_upper_bound), _stream(stream)))
+    if rope_theta is None:
+        _check(lib.st_kv_append(C.byref(st), which, _ptr(k_new), _ptr(v_new), _ptr(n_new), max_new, batch,
+                                int(host_len_upper_bound), _stream(stream)))
+    else:
+        _check(lib.st_kv_append_rope(C.byref(st), which, _ptr(k_new), _ptr(v_new), _ptr(n_new), max_new, batch,
+                                     int(host_len_upper_bound), float(rope_theta), _stream(stream)))
+
+
+def st_kv_append_rope(caches, which, k_new, v_new, theta_base, n_new=None, host_len_upper_bound=None, stream=None):
+    """st_kv_append for UNROTATED keys: each key is rotated by its index in the cache on the way in."""
+    st_kv_append(caches, which, k_new, v_new, n_new, host_len_upper_bound, stream, rope_theta=theta_base)
 
 
 def st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len):
@@ -385,8 +400,9 @@ def st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max
 
 
 def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, scale=0.0, out=None, lse=None,
-                        workspace=None, stream=None):
-    """q[batch, q_len, Hq, D] bf16 -> out of the same shape; lengths are int32 device tensors."""
+                        workspace=None, stream=None, rope_theta=None):
+    """q[batch, q_len, Hq, D] bf16 -> out of the same shape; lengths are int32 device tensors.
+    rope_theta: None for st_attn_decode_dual (rotated queries), a base for st_attn_decode_dual_rope."""
     lib = load_library()
     assert q.is_cuda and q.is_contiguous() and q.dtype == torch.bfloat16 and q.dim() == 4
     batch, q_len, hq, d = q.shape
@@ -398,9 +414,19 @@ def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rs
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     st = caches.struct()
     lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
-    _check(lib.st_attn_decode_dual(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
-                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    if rope_theta is None:
+        _check(lib.st_attn_decode_dual(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    else:
+        _check(lib.st_attn_decode_dual_rope(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
+                                            float(rope_theta), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream)))
     return out
+
+
+def st_attn_decode_dual_rope(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, theta_base, **kw):
+    """st_attn_decode_dual for UNROTATED queries (rotated in the kernel by their index in the reasoning stream)."""
+    return st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, rope_theta=theta_base, **kw)
 
 
 def st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, max_new, max_src_len):

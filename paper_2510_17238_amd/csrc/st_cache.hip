@@ -9,15 +9,26 @@
 //   K: [page][head][d / 8][slot][8]      V: [page][head][d][slot]
 // The new length is written by a second, tiny kernel so that every workgroup of the
 // first one sees the old length.
+//
+// ROPE = true is the fused form: k_new holds UNROTATED keys and each key is rotated on its way
+// into the pool by its position id, which is its index in this cache (Sec. 3.2 numbers the tokens
+// of a stream from 0, independently of the other stream, so a stored key never has to be rotated
+// again).  One full read + write of K by a separate rotation kernel disappears.
+#include <math.h>
+
 #include "st_cache.h"
 
 namespace st {
 
-template <int D>
+struct alignas(16) Piece {
+    uint16_t v[8];
+};
+
+template <int D, bool ROPE>
 __global__ __launch_bounds__(256) void kv_append_kernel(CacheView cache, const uint16_t* __restrict__ k_new,
                                                         const uint16_t* __restrict__ v_new,
                                                         const int32_t* __restrict__ n_new, int max_new,
-                                                        int pages_per_seq_touched) {
+                                                        int pages_per_seq_touched, RopeFreq freq) {
     constexpr int KCH = D / 8;
     __shared__ uint16_t s_v[kPage][D + 2];
     const int pi = blockIdx.x % pages_per_seq_touched;
@@ -37,6 +48,29 @@ __global__ __launch_bounds__(256) void kv_append_kernel(CacheView cache, const u
     const int64_t row_stride = int64_t(cache.n_kv_heads) * D;
     const int tid = threadIdx.x;
 
+    if (ROPE) {
+        // K: a thread takes the two 16-byte pieces d = 8 c .. + 7 and D/2 + 8 c .. + 7 of one token --
+        // the two halves of eight rotation pairs
+        for (int w = tid; w < (KCH / 2) * kPage; w += 256) {
+            const int c8 = w / kPage, s = w % kPage;
+            if (s >= cnt) continue;
+            const uint16_t* src = k_new + (row0 + s) * row_stride + h * D + c8 * 8;
+            const Piece lo_in = *reinterpret_cast<const Piece*>(src), hi_in = *reinterpret_cast<const Piece*>(src + D / 2);
+            Piece lo_out, hi_out;
+            const int pos = lo + s;                              // index in this cache == position id
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float cs, sn;
+                rope_cos_sin(pos, freq.f[c8 * 8 + e], &cs, &sn);
+                const float a = bf16_bits_to_f32(lo_in.v[e]), b2 = bf16_bits_to_f32(hi_in.v[e]);
+                lo_out.v[e] = f32_to_bf16_bits(a * cs - b2 * sn);
+                hi_out.v[e] = f32_to_bf16_bits(b2 * cs + a * sn);
+            }
+            uint16_t* dst = cache.k_pool + ((int64_t(id) * cache.n_kv_heads + h) * KCH + c8) * (kPage * 8) + (slot_lo + s) * 8;
+            *reinterpret_cast<Piece*>(dst) = lo_out;
+            *reinterpret_cast<Piece*>(dst + (KCH / 2) * (kPage * 8)) = hi_out;
+        }
+    } else
     // K: 16-byte pieces, consecutive threads -> consecutive slots of one d-chunk
     for (int w = tid; w < KCH * kPage; w += 256) {
         const int c8 = w / kPage, s = w % kPage;
@@ -107,36 +141,55 @@ CacheView cache_view(const st_kv_cache& c) {
 
 using namespace st;
 
-extern "C" st_status st_kv_append(const st_dual_cache* caches, st_stream_kind which, const void* k_new,
-                                  const void* v_new, const int32_t* n_new, int32_t max_new, int32_t batch,
-                                  int32_t host_len_upper_bound, void* hip_stream) {
-    if (!caches || !k_new || !v_new) return fail(ST_ERR_INVALID_ARG, "st_kv_append: null pointer");
-    if (which != ST_SOURCE && which != ST_REASONING) return fail(ST_ERR_INVALID_ARG, "st_kv_append: which = %d", int(which));
+static st_status kv_append_impl(const char* who, const st_dual_cache* caches, st_stream_kind which, const void* k_new,
+                                const void* v_new, const int32_t* n_new, int32_t max_new, int32_t batch,
+                                int32_t host_len_upper_bound, bool rotate, double theta_base, void* hip_stream) {
+    if (!caches || !k_new || !v_new) return fail(ST_ERR_INVALID_ARG, "%s: null pointer", who);
+    if (which != ST_SOURCE && which != ST_REASONING) return fail(ST_ERR_INVALID_ARG, "%s: which = %d", who, int(which));
     const st_kv_cache& c = which == ST_SOURCE ? caches->source : caches->reasoning;
-    st_status r = check_cache(c, "st_kv_append", which == ST_SOURCE ? "source" : "reasoning");
+    st_status r = check_cache(c, who, which == ST_SOURCE ? "source" : "reasoning");
     if (r != ST_OK) return r;
-    if (!c.appended_len) return fail(ST_ERR_INVALID_ARG, "st_kv_append: appended_len is null");
-    if (!aligned16(k_new) || !aligned16(v_new)) return fail(ST_ERR_INVALID_ARG, "st_kv_append: k_new / v_new must be 16-byte aligned");
-    if (batch <= 0 || max_new < 0) return fail(ST_ERR_INVALID_ARG, "st_kv_append: bad sizes");
+    if (!c.appended_len) return fail(ST_ERR_INVALID_ARG, "%s: appended_len is null", who);
+    if (!aligned16(k_new) || !aligned16(v_new)) return fail(ST_ERR_INVALID_ARG, "%s: k_new / v_new must be 16-byte aligned", who);
+    if (batch <= 0 || max_new < 0) return fail(ST_ERR_INVALID_ARG, "%s: bad sizes", who);
     const int64_t capacity = int64_t(c.max_pages_per_seq) * kPage;
     if (host_len_upper_bound < 0 || host_len_upper_bound > capacity)
-        return fail(ST_ERR_CAPACITY, "st_kv_append: length bound %d exceeds the page table (%lld tokens per sequence)",
+        return fail(ST_ERR_CAPACITY, "%s: length bound %d exceeds the page table (%lld tokens per sequence)", who,
                     host_len_upper_bound, (long long)capacity);
+    if (rotate && !(theta_base > 0.0)) return fail(ST_ERR_INVALID_ARG, "%s: theta_base must be positive", who);
     if (max_new == 0) return ST_OK;
     const int touched = (max_new + kPage - 1) / kPage + 1;
     const int64_t blocks = int64_t(batch) * c.n_kv_heads * touched;
-    if (blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_kv_append: grid too large");
+    if (blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "%s: grid too large", who);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const CacheView cv = cache_view(c);
-    if (c.head_dim == 64)
-        hipLaunchKernelGGL((kv_append_kernel<64>), dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new,
-                           (const uint16_t*)v_new, n_new, max_new, touched);
-    else
-        hipLaunchKernelGGL((kv_append_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new,
-                           (const uint16_t*)v_new, n_new, max_new, touched);
+    const RopeFreq freq = rotate ? make_rope_freq(theta_base, c.head_dim) : RopeFreq{};
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new,
+                           n_new, max_new, touched, freq);
+    };
+    if (c.head_dim == 64) {
+        if (rotate) launch(kv_append_kernel<64, true>); else launch(kv_append_kernel<64, false>);
+    } else {
+        if (rotate) launch(kv_append_kernel<128, true>); else launch(kv_append_kernel<128, false>);
+    }
     ST_LAUNCH_CHECK("kv_append_kernel");
     hipLaunchKernelGGL(kv_append_bump_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, c.appended_len, n_new, max_new,
                        batch, int(capacity));
     ST_LAUNCH_CHECK("kv_append_bump_kernel");
     return ST_OK;
+}
+
+extern "C" st_status st_kv_append(const st_dual_cache* caches, st_stream_kind which, const void* k_new,
+                                  const void* v_new, const int32_t* n_new, int32_t max_new, int32_t batch,
+                                  int32_t host_len_upper_bound, void* hip_stream) {
+    return kv_append_impl("st_kv_append", caches, which, k_new, v_new, n_new, max_new, batch, host_len_upper_bound, false, 0.0,
+                          hip_stream);
+}
+
+extern "C" st_status st_kv_append_rope(const st_dual_cache* caches, st_stream_kind which, const void* k_new,
+                                       const void* v_new, const int32_t* n_new, int32_t max_new, int32_t batch,
+                                       int32_t host_len_upper_bound, double theta_base, void* hip_stream) {
+    return kv_append_impl("st_kv_append_rope", caches, which, k_new, v_new, n_new, max_new, batch, host_len_upper_bound, true,
+                          theta_base, hip_stream);
 }

@@ -39,7 +39,27 @@ struct DecodeArgs {
     const int32_t* n_new;   // [B] query tokens per sequence, or null for max_new everywhere
     int max_new;            // token stride of q / out
     int row_blocks;         // ceil(max_new * group / 32)
+    // fused query rotation (decode step only): q holds unrotated queries, row t is the reasoning token at
+    // index rsn_len - q_len + t of its stream, which is its position id
+    int rope;
+    RopeFreq freq;
 };
+
+// Fused query rotation (Sec. 3.2, stream-local position ids): fragments j and j + KS/2 of a lane hold the
+// two halves of eight rotation pairs, head dims STRIDE j + off + e and D/2 + the same.
+template <int KS, int STRIDE>
+__device__ __forceinline__ void rotate_query(bf16x8 (&qf)[KS], int off, int pos, const RopeFreq& fr) {
+#pragma unroll
+    for (int j = 0; j < KS / 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float cs, sn;
+            rope_cos_sin(pos, fr.f[STRIDE * j + off + e], &cs, &sn);
+            const float x = float(qf[j][e]), y = float(qf[j + KS / 2][e]);
+            qf[j][e] = (__bf16)(x * cs - y * sn);
+            qf[j + KS / 2][e] = (__bf16)(y * cs + x * sn);
+        }
+}
 
 // CHUNKED = false: the decode step (up to 32 query rows q_len * G per sequence and KV head, both caches).
 // CHUNKED = true : source-chunk prefill (Alg. 1, prefill loop): the n_new[b] newest source tokens are the
@@ -91,6 +111,10 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
         if (valid_row)
             z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * (CHUNKED ? a.max_new : a.q_len) + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
         qf[j] = __builtin_bit_cast(bf16x8, z);
+    }
+    if (!CHUNKED && a.rope) {
+        const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+        rotate_query<KS, 16>(qf, 8 * hg, max(len_r - a.q_len + t_row, 0), a.freq);
     }
     f32x16 o_acc[DB];
 #pragma unroll
@@ -247,6 +271,10 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
         const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
 #pragma unroll
         for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
+    }
+    if (a.rope) {
+        const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+        rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
     }
     f32x4 o_acc[DB];
 #pragma unroll
@@ -495,9 +523,9 @@ extern "C" size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, in
     return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
 }
 
-extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, const st_dual_cache* caches,
-                                         const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale,
-                                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+static st_status decode_dual_impl(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                  const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale, bool rotate,
+                                  double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!out || !q || !caches || !lens) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null pointer");
     if (!lens->src_visible_len || !lens->rsn_len) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null length vector");
     if (!aligned16(out) || !aligned16(q)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: q / out must be 16-byte aligned");
@@ -542,6 +570,8 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
     a.n_new = nullptr;
     a.max_new = lens->q_len;
     a.row_blocks = 1;
+    a.rope = rotate ? 1 : 0;
+    a.freq = rotate ? make_rope_freq(theta_base, d) : RopeFreq{};
     const size_t slots = size_t(batch) * hkv * size_t(a.ncs + a.ncr) * a.rows;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
@@ -573,6 +603,20 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
                            static_cast<uint16_t*>(out), lse);
     ST_LAUNCH_CHECK("decode_combine_kernel");
     return ST_OK;
+}
+
+extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                         const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return decode_dual_impl(out, lse, q, caches, lens, batch, n_q_heads, scale, false, 0.0, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" st_status st_attn_decode_dual_rope(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                              const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale,
+                                              double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!(theta_base > 0.0)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_rope: theta_base must be positive");
+    return decode_dual_impl(out, lse, q, caches, lens, batch, n_q_heads, scale, true, theta_base, workspace, workspace_bytes,
+                            hip_stream);
 }
 
 extern "C" size_t st_source_chunk_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
@@ -622,6 +666,8 @@ extern "C" st_status st_attn_source_chunk(void* out, float* lse, const void* q, 
     a.n_new = n_new;
     a.max_new = max_new;
     a.row_blocks = (max_new * a.group + 31) / 32;
+    a.rope = 0;
+    a.freq = RopeFreq{};
     const size_t slots = size_t(batch) * hkv * a.row_blocks * size_t(a.ncs) * 32;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));

@@ -71,4 +71,18 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     return uint16_t(u >> 16);
 }
 
+// ---- RoPE frequencies (Sec. 3.2), shared by the rotation kernel and the fused forms ----
+struct RopeFreq {
+    double f[64];  // theta^(-2 i / D), i < D/2 <= 64
+};
+RopeFreq make_rope_freq(double theta_base, int head_dim);
+
+// cos / sin of position * f for the fused kernels: the angle (up to 1e5 rad at long contexts, where an
+// fp32 product would be off by 1e-3 rad) is reduced to [-pi, pi] in fp64, the functions themselves are fp32
+__device__ __forceinline__ void rope_cos_sin(int pos, double f, float* c, float* s) {
+    const double rev = double(pos) * f * 0.15915494309189535;     // angle / 2 pi
+    const double r = rev - rint(rev);
+    sincosf(float(r * 6.283185307179586), s, c);
+}
+
 }  // namespace st

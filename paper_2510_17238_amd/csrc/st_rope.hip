@@ -11,9 +11,11 @@
 
 namespace st {
 
-struct RopeFreq {
-    double f[64];  // theta^(-2 i / D), i < D/2 <= 64
-};
+RopeFreq make_rope_freq(double theta_base, int head_dim) {
+    RopeFreq freq;
+    for (int i = 0; i < 64; ++i) freq.f[i] = i < head_dim / 2 ? pow(theta_base, -2.0 * double(i) / double(head_dim)) : 0.0;
+    return freq;
+}
 
 template <typename T>
 struct Vec16;  // 16 bytes of T
@@ -103,8 +105,7 @@ extern "C" st_status st_rope_apply(void* out, const void* x, const int32_t* posi
     if (!(theta_base > 0.0)) return fail(ST_ERR_INVALID_ARG, "st_rope_apply: theta_base must be positive");
     if (dt != ST_F32 && dt != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "st_rope_apply: dtype %d", int(dt));
     if (n_tokens == 0) return ST_OK;
-    RopeFreq freq;
-    for (int i = 0; i < head_dim / 2; ++i) freq.f[i] = pow(theta_base, -2.0 * double(i) / double(head_dim));
+    const RopeFreq freq = make_rope_freq(theta_base, head_dim);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (dt == ST_F32) {
         return head_dim == 64 ? launch_rope<float, 64>(out, x, positions, n_tokens, n_heads, freq, stream)

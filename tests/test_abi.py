@@ -86,3 +86,9 @@ def test_cache_argument_checks(lib):
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, fp, 1 << 20, None) == 2
     need = lib.st_decode_workspace_bytes(1, 8, 2, 128, 1, 64, 64)
     assert need >= 2 * 4 * (128 + 2) * 4
+    # the fused forms take the same checks, plus the rotation base
+    assert lib.st_kv_append_rope(C.byref(good), B.ST_SOURCE, fp, fp, None, 8, 1, 65, 1.0e6, None) == 4
+    assert lib.st_kv_append_rope(C.byref(good), B.ST_SOURCE, fp, fp, None, 8, 1, 64, 0.0, None) == 1
+    assert b"theta" in lib.st_last_error() and b"st_kv_append_rope" in lib.st_last_error()
+    assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, -2.0, fp, 1 << 20, None) == 1
+    assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 1.0e6, fp, 1 << 20, None) == 2

@@ -216,8 +216,10 @@ def test_prefill_mfma_agrees_with_plain_kernel(st):
 
 
 # ------------------------------------------------------- append / decode --
-def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3)):
-    """Fill both caches through st_kv_append in uneven chunks; returns caches and the oracle's contiguous copies."""
+def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3), rope_theta=None):
+    """Fill both caches through st_kv_append in uneven chunks; returns caches and the oracle's contiguous copies.
+    With rope_theta the keys go in UNROTATED through st_kv_append_rope, and the oracle's copy of K is what
+    paged_append_rotated stores: RoPE(k, index in the cache), in fp64."""
     pages_s = (int(max(src_lens)) + src_extra + 15) // 16 + 1
     pages_r = (int(max(rsn_lens)) + 15) // 16 + 1
     cs, tab_s = make_cache(batch, pages_s, hkv, d, rng, fill=float("nan"))
@@ -236,10 +238,22 @@ def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(
             for b in range(batch):
                 kn[b, :n_new[b]] = kk[b, done[b]:done[b] + n_new[b]]
                 vn[b, :n_new[b]] = vv[b, done[b]:done[b] + n_new[b]]
-            st.st_kv_append(caches, which, to_dev(kn, "bf16"), to_dev(vn, "bf16"), torch.from_numpy(n_new).to(DEV))
+            st.st_kv_append(caches, which, to_dev(kn, "bf16"), to_dev(vn, "bf16"), torch.from_numpy(n_new).to(DEV),
+                            rope_theta=rope_theta)
             done += n_new
         torch.cuda.synchronize()
         assert np.array_equal(cache.appended_len.cpu().numpy(), lens)
+        if rope_theta is not None:
+            tab = tab_s if which == st.ST_SOURCE else tab_r
+            n_pages = batch * cache.max_pages_per_seq
+            pk = np.zeros((n_pages, O.PAGE, hkv, d)); pv = np.zeros_like(pk)
+            olen = np.zeros(batch, np.int64)
+            rot = np.zeros(kk.shape, np.float64)
+            for b in range(batch):
+                O.paged_append_rotated(pk, pv, tab, olen, b, kk[b, :lens[b]].astype(np.float64), vv[b, :lens[b]].astype(np.float64),
+                                       rope_theta)
+                rot[b, :lens[b]] = O.paged_gather(pk, tab, b, int(lens[b]))
+            ref[which] = (rot, vv)
     return caches, ref, (tab_s, tab_r)
 
 
@@ -279,17 +293,23 @@ def test_kv_append_capacity(st):
     assert cs.appended_len.cpu().tolist() == [32, 32]
 
 
-def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0):
-    caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra)
+def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0, rope_theta=None):
+    caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra, rope_theta=rope_theta)
     q = W.normal(rng, (batch, q_len, hq, d), "bf16")
     tq = to_dev(q, "bf16")
     lse = torch.empty((batch, q_len, hq), dtype=torch.float32, device=DEV)
     vis_t = torch.from_numpy(src_vis.astype(np.int32)).to(DEV); rl_t = torch.from_numpy(rsn_lens.astype(np.int32)).to(DEV)
-    out = st.st_attn_decode_dual(tq, caches, vis_t, rl_t, int(max(src_lens)), int(max(rsn_lens)), lse=lse)
+    out = st.st_attn_decode_dual(tq, caches, vis_t, rl_t, int(max(src_lens)), int(max(rsn_lens)), lse=lse, rope_theta=rope_theta)
     torch.cuda.synchronize()
     for b in range(batch):
-        o_ref, l_ref = O.decode_dual_concat(q[b], ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
-                                            ref[st.ST_REASONING][1][b], int(src_vis[b]), int(rsn_lens[b]))
+        args = (q[b].astype(np.float64), ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
+                ref[st.ST_REASONING][1][b], int(src_vis[b]), int(rsn_lens[b]))
+        if rope_theta is None:
+            o_ref, l_ref = O.decode_dual_concat(*args)
+        elif rsn_lens[b] >= q_len:
+            o_ref, l_ref = O.decode_dual_rotated(*args, rope_theta)
+        else:
+            continue          # fewer cached reasoning tokens than query rows: positions undefined
         assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
         got_l = to_f64(lse[b])
         both = np.isfinite(l_ref)
@@ -314,6 +334,50 @@ def test_decode_head_dim_64_and_group_4(st):
 def test_decode_q_len_8(st):
     rng = np.random.Generator(np.random.PCG64(412))
     _check_decode(st, rng, 3, 8, 2, 128, np.array([64, 10, 290]), np.array([8, 300, 40]), np.array([64, 0, 290]), q_len=8)
+
+
+def test_kv_append_rope_matches_oracle_and_unfused_path(st):
+    """Rotate-on-append: stored keys == RoPE(k, index in the cache) of the oracle within one bf16 ulp, values
+    bit-identical; and the unfused pair st_rope_apply + st_kv_append stores (almost always) the same bits."""
+    rng = np.random.Generator(np.random.PCG64(420))
+    theta = 1.0e6
+    for batch, hkv, d, src_lens, rsn_lens in ((3, 2, 128, np.array([70, 33, 16]), np.array([5, 100, 48])),
+                                               (2, 1, 64, np.array([40000, 1]), np.array([17, 3000]))):
+        state = rng.bit_generator.state
+        caches, ref, (tab_s, tab_r) = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, chunks=(1, 15, 17, 64, 3, 4096),
+                                                 rope_theta=theta)
+        rng.bit_generator.state = state                      # the same pools, tables and rows again
+        caches_u, ref_u, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, chunks=(1, 15, 17, 64, 3, 4096))
+        for which, cache, cache_u, lens, tab in ((st.ST_SOURCE, caches.source, caches_u.source, src_lens, tab_s),
+                                                 (st.ST_REASONING, caches.reasoning, caches_u.reasoning, rsn_lens, tab_r)):
+            kl = st.k_pool_to_logical(cache.k_pool).float().cpu().numpy()
+            vl = st.v_pool_to_logical(cache.v_pool).float().cpu().numpy()
+            for b in range(batch):
+                n = int(lens[b])
+                got = O.paged_gather(kl, tab, b, n).astype(np.float64)
+                want = ref[which][0][b, :n]
+                # one bf16 ulp (or more) of |want|, plus the fp32 rounding of the two products where they cancel
+                ulp = np.abs(want) * 2.0 ** -7 + 4e-6
+                assert (np.abs(got - want) <= ulp).all(), (which, b)
+                assert (np.abs(got - want) <= 0.51 * ulp).mean() > 0.999          # round-to-nearest almost everywhere
+                assert np.array_equal(O.paged_gather(vl, tab, b, n), ref[which][1][b, :n])
+                # unfused: rotate the same rows with st_rope_apply, append with st_kv_append
+                raw = to_dev(ref_u[which][0][b, :n], "bf16")
+                pos = torch.arange(n, dtype=torch.int32, device=DEV)
+                rot = st.st_rope_apply(raw, pos, theta).float().cpu().numpy().astype(np.float64) if n else np.zeros_like(got)
+                assert (np.abs(got - rot) <= ulp).all() and (got == rot).mean() > 0.995
+        assert np.array_equal(np.isnan(st.k_pool_to_logical(caches.source.k_pool).float().cpu().numpy()),
+                              np.isnan(st.k_pool_to_logical(caches_u.source.k_pool).float().cpu().numpy()))
+
+
+@pytest.mark.parametrize("q_len,hq,hkv,d", [(1, 4, 2, 128), (1, 8, 2, 64), (8, 8, 2, 128), (3, 4, 1, 64)])
+def test_decode_rope_fused(st, q_len, hq, hkv, d):
+    """Unrotated keys through st_kv_append_rope, unrotated queries through st_attn_decode_dual_rope, against the
+    oracle's rotate-then-attend with position id = index in the stream."""
+    rng = np.random.Generator(np.random.PCG64(430 + q_len + d))
+    src_lens = np.array([70, 33, 600, 1]); rsn_lens = np.array([9, 100, 1500, 8])
+    src_vis = np.array([64, 0, 600, 1])
+    _check_decode(st, rng, 4, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=q_len, rope_theta=1.0e6)
 
 
 def test_decode_empty_row(st):
