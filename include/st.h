@@ -337,6 +337,16 @@ st_status st_attn_source_chunk(void* out, float* lse, const void* q, const st_du
                                int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* st_attn_source_chunk with the query rotation fused in (Sec. 3.2): q holds UNROTATED
+ * queries; row t of sequence b is the source token at index src_len[b] - n_new[b] + t of the
+ * source stream and is rotated by that position id with base theta_base.  Together with
+ * st_kv_append_rope the prefill loop of Alg. 1 then needs no separate rotation pass.
+ * theta_base <= 0 gives ST_ERR_INVALID_ARG; everything else as for st_attn_source_chunk. */
+st_status st_attn_source_chunk_rope(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                    const int32_t* src_len, const int32_t* n_new, int32_t max_new,
+                                    int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
+                                    double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

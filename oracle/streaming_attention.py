@@ -294,6 +294,13 @@ def source_chunk_attention(q, src_k, src_v, src_len, scale=None):
     return attend_one_cache(q, np.asarray(src_k)[:src_len], np.asarray(src_v)[:src_len], mask, scale)
 
 
+def source_chunk_attention_rotated(q, src_k, src_v, src_len, theta=1.0e6, scale=None):
+    """source_chunk_attention for UNROTATED queries: query row t is the source token at index
+    src_len - n_new + t of the source stream, and that index is its position id (Sec. 3.2)."""
+    n_new = np.asarray(q).shape[0]
+    return source_chunk_attention(rope(q, src_len - n_new + np.arange(n_new), theta), src_k, src_v, src_len, scale)
+
+
 # --------------------------------------------------------------------------
 # Paged cache model (append / gather)
 # --------------------------------------------------------------------------

@@ -106,6 +106,9 @@ def load_library():
     lib.st_source_chunk_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
     lib.st_attn_source_chunk.restype = i32
     lib.st_attn_source_chunk.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
+    lib.st_attn_source_chunk_rope.restype = i32
+    lib.st_attn_source_chunk_rope.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), vp, vp, i32, i32, i32, i32, f32, C.c_double,
+                                              vp, sz, vp]
     _lib = lib
     return lib
 
@@ -433,8 +436,10 @@ def st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, max_
     return int(load_library().st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, max_new, max_src_len))
 
 
-def st_attn_source_chunk(q, caches, src_len, max_src_len, n_new=None, scale=0.0, out=None, lse=None, workspace=None, stream=None):
-    """q[batch, max_new, Hq, D] bf16: the newest source tokens attend causally over the source cache."""
+def st_attn_source_chunk(q, caches, src_len, max_src_len, n_new=None, scale=0.0, out=None, lse=None, workspace=None, stream=None,
+                         rope_theta=None):
+    """q[batch, max_new, Hq, D] bf16: the newest source tokens attend causally over the source cache.
+    rope_theta: None for st_attn_source_chunk (rotated queries), a base for st_attn_source_chunk_rope."""
     lib = load_library()
     assert q.is_cuda and q.is_contiguous() and q.dtype == torch.bfloat16 and q.dim() == 4
     batch, max_new, hq, d = q.shape
@@ -447,7 +452,17 @@ def st_attn_source_chunk(q, caches, src_len, max_src_len, n_new=None, scale=0.0,
         need = st_source_chunk_workspace_bytes(batch, hq, caches.source.n_kv_heads, d, max_new, max_src_len)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     st = caches.struct()
-    _check(lib.st_attn_source_chunk(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), _ptr(src_len), _ptr(n_new), max_new,
-                                    int(max_src_len), batch, hq, float(scale), _ptr(workspace),
-                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+    if rope_theta is None:
+        _check(lib.st_attn_source_chunk(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), _ptr(src_len), _ptr(n_new), max_new,
+                                        int(max_src_len), batch, hq, float(scale), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)))
+    else:
+        _check(lib.st_attn_source_chunk_rope(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), _ptr(src_len), _ptr(n_new), max_new,
+                                             int(max_src_len), batch, hq, float(scale), float(rope_theta), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)))
     return out
+
+
+def st_attn_source_chunk_rope(q, caches, src_len, max_src_len, theta_base, **kw):
+    """st_attn_source_chunk for UNROTATED queries (rotated in the kernel by their index in the source stream)."""
+    return st_attn_source_chunk(q, caches, src_len, max_src_len, rope_theta=theta_base, **kw)

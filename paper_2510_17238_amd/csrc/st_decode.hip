@@ -39,8 +39,8 @@ struct DecodeArgs {
     const int32_t* n_new;   // [B] query tokens per sequence, or null for max_new everywhere
     int max_new;            // token stride of q / out
     int row_blocks;         // ceil(max_new * group / 32)
-    // fused query rotation (decode step only): q holds unrotated queries, row t is the reasoning token at
-    // index rsn_len - q_len + t of its stream, which is its position id
+    // fused query rotation: q holds unrotated queries; row t is the token at index len - q_len + t of its own
+    // stream (reasoning for a decode step, source for a source chunk), which is its position id
     int rope;
     RopeFreq freq;
 };
@@ -112,9 +112,11 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
             z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * (CHUNKED ? a.max_new : a.q_len) + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
         qf[j] = __builtin_bit_cast(bf16x8, z);
     }
-    if (!CHUNKED && a.rope) {
-        const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
-        rotate_query<KS, 16>(qf, 8 * hg, max(len_r - a.q_len + t_row, 0), a.freq);
+    if (a.rope) {
+        // the row's position id: its index in its own stream -- the reasoning stream for a decode step,
+        // the source stream for a source chunk
+        const int len_own = CHUNKED ? len : min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+        rotate_query<KS, 16>(qf, 8 * hg, max(len_own - q_len + t_row, 0), a.freq);
     }
     f32x16 o_acc[DB];
 #pragma unroll
@@ -627,10 +629,10 @@ extern "C" size_t st_source_chunk_workspace_bytes(int32_t batch, int32_t n_q_hea
     return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
 }
 
-extern "C" st_status st_attn_source_chunk(void* out, float* lse, const void* q, const st_dual_cache* caches,
-                                          const int32_t* src_len, const int32_t* n_new, int32_t max_new,
-                                          int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
-                                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+static st_status source_chunk_impl(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                   const int32_t* src_len, const int32_t* n_new, int32_t max_new,
+                                   int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale, bool rotate,
+                                   double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!out || !q || !caches || !src_len) return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk: null pointer");
     if (!aligned16(out) || !aligned16(q)) return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk: q / out must be 16-byte aligned");
     st_status r = check_cache(caches->source, "st_attn_source_chunk", "source");
@@ -666,8 +668,8 @@ extern "C" st_status st_attn_source_chunk(void* out, float* lse, const void* q, 
     a.n_new = n_new;
     a.max_new = max_new;
     a.row_blocks = (max_new * a.group + 31) / 32;
-    a.rope = 0;
-    a.freq = RopeFreq{};
+    a.rope = rotate ? 1 : 0;
+    a.freq = rotate ? make_rope_freq(theta_base, d) : RopeFreq{};
     const size_t slots = size_t(batch) * hkv * a.row_blocks * size_t(a.ncs) * 32;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
@@ -686,4 +688,21 @@ extern "C" st_status st_attn_source_chunk(void* out, float* lse, const void* q, 
     else hipLaunchKernelGGL((chunk_combine_kernel<128>), dim3((unsigned)out_units), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
     ST_LAUNCH_CHECK("chunk_combine_kernel");
     return ST_OK;
+}
+
+extern "C" st_status st_attn_source_chunk(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                          const int32_t* src_len, const int32_t* n_new, int32_t max_new,
+                                          int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return source_chunk_impl(out, lse, q, caches, src_len, n_new, max_new, max_src_len, batch, n_q_heads, scale, false, 0.0,
+                             workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" st_status st_attn_source_chunk_rope(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                               const int32_t* src_len, const int32_t* n_new, int32_t max_new,
+                                               int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
+                                               double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!(theta_base > 0.0)) return fail(ST_ERR_INVALID_ARG, "st_attn_source_chunk_rope: theta_base must be positive");
+    return source_chunk_impl(out, lse, q, caches, src_len, n_new, max_new, max_src_len, batch, n_q_heads, scale, true, theta_base,
+                             workspace, workspace_bytes, hip_stream);
 }

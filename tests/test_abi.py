@@ -92,3 +92,5 @@ def test_cache_argument_checks(lib):
     assert b"theta" in lib.st_last_error() and b"st_kv_append_rope" in lib.st_last_error()
     assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, -2.0, fp, 1 << 20, None) == 1
     assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 1.0e6, fp, 1 << 20, None) == 2
+    assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 64, 1, 8, 0.0, 0.0, fp, 1 << 20, None) == 1
+    assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 65, 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 4

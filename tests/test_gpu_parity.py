@@ -467,8 +467,9 @@ def test_decode_workspace_reuse(st):
 
 
 # ------------------------------------------------- source-chunk prefill --
-def _check_source_chunk(st, rng, batch, hq, hkv, d, src_before, n_new, max_new):
-    """Append a ragged chunk to the source cache, then let its tokens attend over the cache."""
+def _check_source_chunk(st, rng, batch, hq, hkv, d, src_before, n_new, max_new, rope_theta=None):
+    """Append a ragged chunk to the source cache, then let its tokens attend over the cache.
+    With rope_theta, keys and queries go in UNROTATED through the fused entry points."""
     src_before = np.asarray(src_before); n_new = np.asarray(n_new)
     total = src_before + n_new
     pages = (int(total.max()) + 15) // 16 + 1
@@ -479,23 +480,29 @@ def _check_source_chunk(st, rng, batch, hq, hkv, d, src_before, n_new, max_new):
     hist = int(src_before.max())
     if hist:
         st.st_kv_append(caches, st.ST_SOURCE, to_dev(kk[:, :hist], "bf16"), to_dev(vv[:, :hist], "bf16"),
-                        torch.from_numpy(src_before.astype(np.int32)).to(DEV))
+                        torch.from_numpy(src_before.astype(np.int32)).to(DEV), rope_theta=rope_theta)
     kn = np.zeros((batch, max_new, hkv, d), np.float32); vn = np.zeros_like(kn)
     for b in range(batch):
         kn[b, :n_new[b]] = kk[b, src_before[b]:total[b]]; vn[b, :n_new[b]] = vv[b, src_before[b]:total[b]]
         kk[b, :total[b]] = np.concatenate([kk[b, :src_before[b]], kn[b, :n_new[b]]]); vv[b, :total[b]] = np.concatenate([vv[b, :src_before[b]], vn[b, :n_new[b]]])
     nn = torch.from_numpy(n_new.astype(np.int32)).to(DEV)
-    st.st_kv_append(caches, st.ST_SOURCE, to_dev(kn, "bf16"), to_dev(vn, "bf16"), nn)
+    st.st_kv_append(caches, st.ST_SOURCE, to_dev(kn, "bf16"), to_dev(vn, "bf16"), nn, rope_theta=rope_theta)
     q = W.normal(rng, (batch, max_new, hq, d), "bf16")
     tq = to_dev(q, "bf16")
     lse = torch.full((batch, max_new, hq), 7.0, dtype=torch.float32, device=DEV)
     out = torch.full_like(tq, 3.0)
-    st.st_attn_source_chunk(tq, caches, torch.from_numpy(total.astype(np.int32)).to(DEV), int(total.max()), n_new=nn, out=out, lse=lse)
+    st.st_attn_source_chunk(tq, caches, torch.from_numpy(total.astype(np.int32)).to(DEV), int(total.max()), n_new=nn, out=out, lse=lse,
+                            rope_theta=rope_theta)
     torch.cuda.synchronize()
     assert cs.appended_len.cpu().tolist() == total.tolist()
     for b in range(batch):
         nb = int(n_new[b])
-        if nb:
+        if nb and rope_theta is not None:
+            k_rot = O.rope(kk[b, :total[b]].astype(np.float64), np.arange(total[b]), rope_theta)
+            o_ref, l_ref = O.source_chunk_attention_rotated(q[b, :nb].astype(np.float64), k_rot, vv[b], int(total[b]), rope_theta)
+            assert np.abs(to_f64(out[b, :nb]) - o_ref).max() <= 2e-2, b
+            assert np.abs(to_f64(lse[b, :nb]) - l_ref).max() <= 2e-2, b
+        elif nb:
             o_ref, l_ref = O.source_chunk_attention(q[b, :nb], kk[b], vv[b], int(total[b]))
             assert np.abs(to_f64(out[b, :nb]) - o_ref).max() <= 2e-2, b
             assert np.abs(to_f64(lse[b, :nb]) - l_ref).max() <= 2e-2, b
@@ -514,6 +521,13 @@ def test_source_chunk_many_row_blocks(st):
     rng = np.random.Generator(np.random.PCG64(441))
     _check_source_chunk(st, rng, 2, 8, 2, 128, [1000, 17], [64, 61], 64)
     _check_source_chunk(st, rng, 2, 4, 4, 64, [70, 0], [33, 64], 64)
+
+
+def test_source_chunk_rope_fused(st):
+    """Unrotated keys and queries through st_kv_append_rope + st_attn_source_chunk_rope."""
+    rng = np.random.Generator(np.random.PCG64(444))
+    _check_source_chunk(st, rng, 5, 4, 2, 128, [0, 5, 500, 33, 100], [7, 16, 40, 0, 1], 40, rope_theta=1.0e6)
+    _check_source_chunk(st, rng, 2, 4, 4, 64, [70, 0], [33, 64], 64, rope_theta=1.0e4)
 
 
 def test_source_chunk_equals_prefill_source_rows(st):

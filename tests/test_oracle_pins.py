@@ -349,6 +349,10 @@ def test_p10_rotate_on_append_and_in_decode_equal_prefill(layout):
     last3 = rsn[-3:]
     o_d, l_d = O.decode_dual_rotated(q[last3], sk, sv, rk, rv, len(src), len(rsn), theta)
     assert np.abs(o_d - o[last3]).max() < 1e-12 and np.abs(l_d - lse[last3]).max() < 1e-12
+    # the second sentence (20 tokens) arriving as a chunk, unrotated queries, over the cache as it was then
+    chunk = src[3:23]
+    o_c, l_c = O.source_chunk_attention_rotated(q[chunk], sk, sv, 23, theta)
+    assert np.abs(o_c - o[chunk]).max() < 1e-12 and np.abs(l_c - lse[chunk]).max() < 1e-12
     # one row in the middle of the third reasoning segment: reasoning cache as it was then, sources of segments 1..3
     row = rsn[4 + 1 + 8]
     n_then = 4 + 1 + 9
