@@ -23,7 +23,8 @@ Pins (all in tests/test_oracle_pins.py): brute-force gather, layout
 equivariance, Eq. 2 as printed, reduction to library causal attention, source chunk == source rows of prefill,
 closed-form visible-pair counts, LSE-merge == concatenation, RoPE identities,
 decode == last prefill row, paged gather == contiguous, rotate-on-append / rotate-in-decode ==
-the unfused pipeline.  No function here is "parity unpinned".
+the unfused pipeline, Alg. 1 timeline == hand-worked schedules and the paper's Table 4 latencies.
+No function here is "parity unpinned".
 """
 import numpy as np
 
@@ -346,6 +347,72 @@ def decode_dual_rotated(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len,
     q_len = q.shape[0]
     positions = rsn_len - q_len + np.arange(q_len)
     return decode_dual_concat(rope(q, positions, theta), src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, scale)
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 as a timeline: when does each reasoning unit start, given when sentences arrive
+# --------------------------------------------------------------------------
+STREAMING, SERIAL, BATCH = 0, 1, 2
+
+
+def alg1_timeline(arrival, prefill_s, n_decode, decode_s, mode=STREAMING):
+    """Event times of Alg. 1 for one stream, with the two loops on resources of their own.
+
+    arrival[k]   time sentence k has been read completely (non-decreasing)
+    prefill_s[k] time to prefill sentence k into the input cache
+    n_decode[k]  decoding steps of reasoning unit k, each taking decode_s
+
+    STREAMING (Alg. 1): the prefill loop takes sentences in arrival order, one at a time; the
+    decoding loop starts unit t when unit t-1 is finished AND sentence t is prefilled
+    (N_EOS >= N_EOT + 1).  `waited[t]`: the loop had to wait for the prefill (N_EOS < N_EOT + 1
+    when it got there); `sliced[t]`: later sentences were already cached when unit t started, so
+    a slice of the input cache had to be selected (N_EOS > N_EOT + 1).
+    SERIAL: one worker alternates -- prefill sentence k, decode unit k -- and sentences that
+    arrive meanwhile wait.  BATCH: everything is read first, then prefilled, then decoded.
+    Returns a dict of lists: prefill_done, unit_start, first_token, unit_done, waited, sliced.
+    """
+    K = len(arrival)
+    pf_done, start, first, done, waited, sliced = [], [], [], [], [], []
+    if mode == STREAMING:
+        t_free = 0.0
+        for k in range(K):
+            t_free = max(arrival[k], t_free) + prefill_s[k]
+            pf_done.append(t_free)
+        ready = 0.0
+        for t in range(K):
+            waited.append(pf_done[t] > ready)
+            st = max(ready, pf_done[t])
+            sliced.append(t + 1 < K and pf_done[t + 1] <= st)
+            start.append(st)
+            first.append(st + decode_s if n_decode[t] > 0 else st)
+            ready = st + n_decode[t] * decode_s
+            done.append(ready)
+    elif mode == SERIAL:
+        t_free = 0.0
+        for k in range(K):
+            pf = max(arrival[k], t_free) + prefill_s[k]
+            pf_done.append(pf)
+            waited.append(arrival[k] > t_free)
+            sliced.append(False)
+            start.append(pf)
+            first.append(pf + decode_s if n_decode[k] > 0 else pf)
+            t_free = pf + n_decode[k] * decode_s
+            done.append(t_free)
+    elif mode == BATCH:
+        t_free = arrival[K - 1] if K else 0.0
+        for k in range(K):
+            t_free += prefill_s[k]
+            pf_done.append(t_free)
+        for t in range(K):
+            waited.append(t == 0)
+            sliced.append(False)
+            start.append(t_free)
+            first.append(t_free + decode_s if n_decode[t] > 0 else t_free)
+            t_free += n_decode[t] * decode_s
+            done.append(t_free)
+    else:
+        raise ValueError(mode)
+    return dict(prefill_done=pf_done, unit_start=start, first_token=first, unit_done=done, waited=waited, sliced=sliced)
 
 
 # --------------------------------------------------------------------------

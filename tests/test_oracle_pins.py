@@ -360,6 +360,80 @@ def test_p10_rotate_on_append_and_in_decode_equal_prefill(layout):
     assert np.abs(o_d[0] - o[row]).max() < 1e-12 and np.abs(l_d[0] - lse[row]).max() < 1e-12
 
 
+# ---- P11: Alg. 1 as a timeline -- hand-worked schedules, invariants, and the latencies of the paper's Table 4
+def test_p11_alg1_timeline_hand_worked():
+    arrival, prefill, n_dec = [1.0, 2.0, 10.0], [1.0, 1.0, 1.0], [3, 2, 1]
+    t = O.alg1_timeline(arrival, prefill, n_dec, 1.0, O.STREAMING)
+    assert t["prefill_done"] == [2.0, 3.0, 11.0]
+    assert t["unit_start"] == [2.0, 5.0, 11.0] and t["first_token"] == [3.0, 6.0, 12.0] and t["unit_done"] == [5.0, 7.0, 12.0]
+    assert t["waited"] == [True, False, True] and t["sliced"] == [False, False, False]
+    # sentences arrive faster than they are reasoned about: a slice of the input cache is selected
+    t = O.alg1_timeline([0.0, 0.0, 0.0], [1.0, 1.0, 1.0], [5, 1, 1], 1.0, O.STREAMING)
+    assert t["prefill_done"] == [1.0, 2.0, 3.0] and t["unit_start"] == [1.0, 6.0, 7.0] and t["unit_done"] == [6.0, 7.0, 8.0]
+    assert t["waited"] == [True, False, False] and t["sliced"] == [False, True, False]
+    # one worker alternating prefill and decoding
+    t = O.alg1_timeline(arrival, prefill, n_dec, 1.0, O.SERIAL)
+    assert t["prefill_done"] == [2.0, 6.0, 11.0] and t["first_token"] == [3.0, 7.0, 12.0] and t["unit_done"] == [5.0, 8.0, 12.0]
+    assert t["waited"] == [True, False, True]
+    # read everything, then prefill, then decode
+    t = O.alg1_timeline(arrival, prefill, n_dec, 1.0, O.BATCH)
+    assert t["prefill_done"] == [11.0, 12.0, 13.0] and t["first_token"] == [14.0, 17.0, 19.0] and t["unit_done"] == [16.0, 18.0, 19.0]
+    # a unit without tokens produces none
+    t = O.alg1_timeline([0.0, 1.0], [1.0, 1.0], [0, 2], 1.0, O.STREAMING)
+    assert t["first_token"] == [1.0, 3.0] and t["unit_done"] == [1.0, 4.0]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_p11_alg1_timeline_invariants(seed):
+    rng = np.random.Generator(np.random.PCG64(1100 + seed))
+    K = 7
+    arrival = np.cumsum(rng.uniform(0.0, 2.0, K)).tolist()
+    prefill = rng.uniform(0.05, 0.5, K).tolist()
+    n_dec = rng.integers(1, 30, K).tolist()
+    d = 0.07
+    st, se, ba = (O.alg1_timeline(arrival, prefill, n_dec, d, m) for m in (O.STREAMING, O.SERIAL, O.BATCH))
+    for t in range(K):
+        # a unit never starts before its sentence is in the cache, nor before the previous unit ended
+        assert st["unit_start"][t] >= st["prefill_done"][t] and (t == 0 or st["unit_start"][t] >= st["unit_done"][t - 1])
+        assert st["unit_start"][t] == max(st["prefill_done"][t], st["unit_done"][t - 1] if t else 0.0)
+        assert abs(st["unit_done"][t] - st["unit_start"][t] - n_dec[t] * d) < 1e-12
+        # overlapping the two loops is never slower than alternating, which is never slower than batch
+        assert st["first_token"][t] <= se["first_token"][t] + 1e-12 <= ba["first_token"][t] + 2e-12
+        # exactly one of: waited for the prefill / started straight after the previous unit
+        assert st["waited"][t] == (st["unit_start"][t] > (st["unit_done"][t - 1] if t else 0.0))
+    assert abs(st["first_token"][0] - (arrival[0] + prefill[0] + d)) < 1e-12
+    assert abs(ba["first_token"][0] - (arrival[-1] + sum(prefill) + d)) < 1e-12
+    # with instant decoding nothing is ever sliced; with instant arrival and prefill nothing waits after unit 0
+    quick = O.alg1_timeline(arrival, prefill, n_dec, 0.0, O.STREAMING)
+    assert all(quick["waited"])
+    slow = O.alg1_timeline([0.0] * K, [0.0] * K, n_dec, d, O.STREAMING)
+    assert slow["waited"] == [False] * K and slow["sliced"] == [True] * (K - 1) + [False]
+
+
+def test_p11_alg1_timeline_reproduces_table4_latencies():
+    """First-token latency of the batch and of the streaming paradigm from the stage times the paper reports
+    (Table 4): sentences of average length arriving at 0.4 s per word."""
+    vals = {}
+    with open(os.path.join(GOLDEN, "table4_efficiency_qwen3_4b.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, v = line.split()
+                vals[name] = float(v)
+    words, n_sent = vals["read_count_words"], vals["sentences"]
+    K = 5                                             # 4.65 sentences: four of average length and a shorter one
+    per = words / n_sent
+    w = [per] * 4 + [words - 4 * per]
+    arrival = (vals["read_avg_s"] * np.cumsum(w)).tolist()
+    units = [int(round(vals["stream_decode_count"] / n_sent))] * 4
+    units.append(int(vals["stream_decode_count"]) - sum(units))
+    st = O.alg1_timeline(arrival, [vals["stream_prefill_avg_s"]] * K, units, vals["stream_decode_avg_s"], O.STREAMING)
+    ba = O.alg1_timeline(arrival, [vals["batch_prefill_avg_s"]] + [0.0] * (K - 1), units, vals["batch_decode_avg_s"], O.BATCH)
+    assert abs(st["first_token"][0] - vals["stream_first_token_s"]) / vals["stream_first_token_s"] < 0.03
+    assert abs(ba["first_token"][0] - vals["batch_first_token_s"]) / vals["batch_first_token_s"] < 0.005
+    # the reading time dominates: decoding of every unit but the last ends before the next sentence has been read
+    assert st["waited"] == [True] * K
+
+
 # ---- metadata derived from the dense mask: closed forms for config 1
 def test_metadata_config1_closed_form():
     cfg = W.config1()
