@@ -347,6 +347,90 @@ st_status st_attn_source_chunk_rope(void* out, float* lse, const void* q, const 
                                     int32_t max_src_len, int32_t batch, int32_t n_q_heads, float scale,
                                     double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------------
+ * Alg. 1 ("Streaming thinking with parallel KV caches") as a host scheduler.
+ *
+ * st_stream_run drives the attention path of n_layers layers through one streaming session
+ * of a batch of identical streams: input sentence k has src_tokens[k] tokens and becomes
+ * available arrival_s[k] seconds after the start; reasoning unit k has rsn_tokens[k] tokens
+ * (Alg. 1 takes the source and target length lists as input).  Schedules:
+ *   ST_SCHED_STREAMING  Alg. 1: a prefill loop (host thread + prefill_stream) appends every
+ *                       sentence as soon as it has arrived and lets it attend over the source
+ *                       cache; a decoding loop (host thread + decode_stream) starts unit t when
+ *                       unit t-1 has ended and sentence t is prefilled (N_EOS >= N_EOT + 1): it
+ *                       waits for the prefill if necessary, and selects the slice of the source
+ *                       cache ending with sentence t if later sentences are already cached.
+ *   ST_SCHED_SERIAL     one worker alternates: prefill sentence k, decode unit k.  Same results
+ *                       as ST_SCHED_STREAMING, bit for bit.
+ *   ST_SCHED_BATCH      the batch paradigm: wait for the last sentence, prefill everything,
+ *                       then decode every unit with the WHOLE input visible.
+ * The keys and queries are given unrotated and are rotated inside the kernels by their index in
+ * their stream (st_kv_append_rope, st_attn_source_chunk_rope, st_attn_decode_dual_rope).
+ * Every layer is fed the same activations (projections and MLP need weights and are outside this
+ * path); outputs are those of the last layer.  All caches must be empty at the start.
+ *
+ * Tensor layouts (device, bf16), with S_k = src_tokens[k], step g = decoded token number g overall:
+ *   src_q, src_out : concatenation over k of [batch, S_k, n_q_heads,  head_dim]
+ *   src_k, src_v   : concatenation over k of [batch, S_k, n_kv_heads, head_dim]
+ *   rsn_q, rsn_out : [total steps][batch, n_q_heads,  head_dim]
+ *   rsn_k, rsn_v   : [total steps][batch, n_kv_heads, head_dim]
+ * Workspaces: prefill_workspace >= st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads,
+ * head_dim, max_k S_k, sum_k S_k), decode_workspace >= st_decode_workspace_bytes(batch, ..., 1,
+ * sum_k S_k, total steps); the two are used concurrently and must not overlap.
+ * The call BLOCKS until the session has run; it creates host threads and a few device words of
+ * its own.  report: host arrays of n_sentences entries each, seconds since the start (GPU event
+ * times): prefill_done_s, first_token_s, unit_done_s; waited[t] = the decoding loop found sentence
+ * t not yet prefilled, sliced[t] = it found sentence t+1 already prefilled; total_s = wall time.
+ * ---------------------------------------------------------------------- */
+enum { ST_SCHED_STREAMING = 0, ST_SCHED_SERIAL = 1, ST_SCHED_BATCH = 2 };
+
+typedef struct st_stream_job {
+    int32_t n_layers;
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_sentences;
+    const st_dual_cache* caches;   /* host array [n_layers] */
+    const int32_t* src_tokens;     /* host [n_sentences] */
+    const int32_t* rsn_tokens;     /* host [n_sentences] */
+    const double* arrival_s;       /* host [n_sentences], non-decreasing, or NULL (everything present at the start) */
+    const void* src_q;
+    const void* src_k;
+    const void* src_v;
+    void* src_out;
+    const void* rsn_q;
+    const void* rsn_k;
+    const void* rsn_v;
+    void* rsn_out;
+    float scale;                   /* <= 0: 1 / sqrt(head_dim) */
+    double theta_base;
+    void* prefill_workspace;
+    size_t prefill_workspace_bytes;
+    void* decode_workspace;
+    size_t decode_workspace_bytes;
+    void* prefill_stream;          /* hipStream_t */
+    void* decode_stream;           /* hipStream_t, different from prefill_stream for ST_SCHED_STREAMING */
+} st_stream_job;
+
+typedef struct st_stream_report {
+    double* prefill_done_s;
+    double* first_token_s;
+    double* unit_done_s;
+    int32_t* waited;
+    int32_t* sliced;
+    double total_s;
+} st_stream_report;
+
+st_status st_stream_run(const st_stream_job* job, int32_t mode, st_stream_report* report);
+
+/* The control logic of the three schedules as a pure host model (no GPU): event times for given
+ * stage durations -- sentence k takes prefill_s[k] to prefill, every decoded token decode_s -- with
+ * the two loops of ST_SCHED_STREAMING on resources of their own.  Output arrays (n_sentences
+ * entries each) may be NULL.  unit_start_s[t] = max(end of unit t-1, prefill of sentence t). */
+st_status st_stream_timeline(int32_t mode, int32_t n_sentences, const double* arrival_s,
+                             const double* prefill_s, const int32_t* n_decode, double decode_s,
+                             double* prefill_done_s, double* unit_start_s, double* first_token_s,
+                             double* unit_done_s, int32_t* waited, int32_t* sliced);
+
 #ifdef __cplusplus
 }
 #endif

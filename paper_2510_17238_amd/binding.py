@@ -34,6 +34,22 @@ class _DualCacheStruct(C.Structure):
     _fields_ = [("source", _KVCacheStruct), ("reasoning", _KVCacheStruct)]
 
 
+class _StreamJobStruct(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_sentences", C.c_int32),
+                ("caches", C.c_void_p), ("src_tokens", C.c_void_p), ("rsn_tokens", C.c_void_p), ("arrival_s", C.c_void_p),
+                ("src_q", C.c_void_p), ("src_k", C.c_void_p), ("src_v", C.c_void_p), ("src_out", C.c_void_p),
+                ("rsn_q", C.c_void_p), ("rsn_k", C.c_void_p), ("rsn_v", C.c_void_p), ("rsn_out", C.c_void_p),
+                ("scale", C.c_float), ("theta_base", C.c_double),
+                ("prefill_workspace", C.c_void_p), ("prefill_workspace_bytes", C.c_size_t),
+                ("decode_workspace", C.c_void_p), ("decode_workspace_bytes", C.c_size_t),
+                ("prefill_stream", C.c_void_p), ("decode_stream", C.c_void_p)]
+
+
+class _StreamReportStruct(C.Structure):
+    _fields_ = [("prefill_done_s", C.c_void_p), ("first_token_s", C.c_void_p), ("unit_done_s", C.c_void_p),
+                ("waited", C.c_void_p), ("sliced", C.c_void_p), ("total_s", C.c_double)]
+
+
 class _DualLensStruct(C.Structure):
     _fields_ = [("src_visible_len", C.c_void_p), ("rsn_len", C.c_void_p), ("q_len", C.c_int32),
                 ("max_src_len", C.c_int32), ("max_rsn_len", C.c_int32)]
@@ -109,6 +125,10 @@ def load_library():
     lib.st_attn_source_chunk_rope.restype = i32
     lib.st_attn_source_chunk_rope.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), vp, vp, i32, i32, i32, i32, f32, C.c_double,
                                               vp, sz, vp]
+    lib.st_stream_run.restype = i32
+    lib.st_stream_run.argtypes = [C.POINTER(_StreamJobStruct), i32, C.POINTER(_StreamReportStruct)]
+    lib.st_stream_timeline.restype = i32
+    lib.st_stream_timeline.argtypes = [i32, i32, vp, vp, vp, C.c_double, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -466,3 +486,70 @@ def st_attn_source_chunk(q, caches, src_len, max_src_len, n_new=None, scale=0.0,
 def st_attn_source_chunk_rope(q, caches, src_len, max_src_len, theta_base, **kw):
     """st_attn_source_chunk for UNROTATED queries (rotated in the kernel by their index in the source stream)."""
     return st_attn_source_chunk(q, caches, src_len, max_src_len, rope_theta=theta_base, **kw)
+
+
+# ------------------------------------------------------- Alg. 1 scheduler --
+ST_SCHED_STREAMING, ST_SCHED_SERIAL, ST_SCHED_BATCH = 0, 1, 2
+
+
+def st_stream_timeline(mode, arrival_s, prefill_s, n_decode, decode_s):
+    """Event times of a schedule for given stage durations (host model, no GPU): dict of numpy arrays."""
+    import numpy as np
+    a = np.ascontiguousarray(arrival_s, dtype=np.float64); p = np.ascontiguousarray(prefill_s, dtype=np.float64)
+    n = np.ascontiguousarray(n_decode, dtype=np.int32)
+    k = len(a)
+    assert len(p) == k and len(n) == k
+    out = {name: np.zeros(k, np.float64) for name in ("prefill_done", "unit_start", "first_token", "unit_done")}
+    flags = {name: np.zeros(k, np.int32) for name in ("waited", "sliced")}
+    ptr = lambda x: x.ctypes.data if k else None
+    _check(load_library().st_stream_timeline(int(mode), k, ptr(a), ptr(p), ptr(n), float(decode_s), ptr(out["prefill_done"]),
+                                             ptr(out["unit_start"]), ptr(out["first_token"]), ptr(out["unit_done"]),
+                                             ptr(flags["waited"]), ptr(flags["sliced"])))
+    out.update({name: v.astype(bool) for name, v in flags.items()})
+    return out
+
+
+def st_stream_run(mode, layers, n_q_heads, src_tokens, rsn_tokens, src_q, src_k, src_v, rsn_q, rsn_k, rsn_v, theta_base=1.0e6,
+                  arrival_s=None, scale=0.0, prefill_stream=None, decode_stream=None):
+    """Run one streaming session (Alg. 1) over `layers` (a list of DualCache, all empty).
+
+    src_*: flat bf16 device tensors in the sentence-major layout of st.h, rsn_*: [steps, batch, heads, D].
+    Returns (src_out, rsn_out, report dict).  Blocks until the session is over."""
+    import numpy as np
+    lib = load_library()
+    src_tokens = np.ascontiguousarray(src_tokens, dtype=np.int32); rsn_tokens = np.ascontiguousarray(rsn_tokens, dtype=np.int32)
+    k = len(src_tokens)
+    assert len(rsn_tokens) == k and len(layers) > 0
+    arr = None if arrival_s is None else np.ascontiguousarray(arrival_s, dtype=np.float64)
+    batch = layers[0].source.batch
+    hkv, d = layers[0].source.n_kv_heads, layers[0].source.head_dim
+    for t in (src_q, src_k, src_v, rsn_q, rsn_k, rsn_v):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16
+    total_src, steps = int(src_tokens.sum()), int(rsn_tokens.sum())
+    assert src_q.numel() == total_src * batch * n_q_heads * d and src_k.numel() == total_src * batch * hkv * d == src_v.numel()
+    assert rsn_q.numel() == steps * batch * n_q_heads * d and rsn_k.numel() == steps * batch * hkv * d == rsn_v.numel()
+    src_out = torch.zeros_like(src_q); rsn_out = torch.zeros_like(rsn_q)
+    dev = rsn_q.device
+    pws = torch.empty(max(256, st_source_chunk_workspace_bytes(batch, n_q_heads, hkv, d, max(1, int(src_tokens.max(initial=0))),
+                                                               total_src)), dtype=torch.uint8, device=dev)
+    dws = torch.empty(max(256, st_decode_workspace_bytes(batch, n_q_heads, hkv, d, 1, total_src, steps)), dtype=torch.uint8, device=dev)
+    if prefill_stream is None:
+        prefill_stream = torch.cuda.Stream(device=dev)
+    if decode_stream is None:
+        decode_stream = torch.cuda.Stream(device=dev)
+    cache_arr = (_DualCacheStruct * len(layers))(*[c.struct() for c in layers])
+    rep = {name: np.zeros(k, np.float64) for name in ("prefill_done", "first_token", "unit_done")}
+    flags = {name: np.zeros(k, np.int32) for name in ("waited", "sliced")}
+    ptr = lambda x: x.ctypes.data if (x is not None and len(x)) else None
+    dp = lambda t: t.data_ptr()
+    job = _StreamJobStruct(len(layers), batch, n_q_heads, k, C.addressof(cache_arr), ptr(src_tokens), ptr(rsn_tokens), ptr(arr),
+                           dp(src_q), dp(src_k), dp(src_v), dp(src_out), dp(rsn_q), dp(rsn_k), dp(rsn_v), dp(rsn_out),
+                           float(scale), float(theta_base), dp(pws), pws.numel(), dp(dws), dws.numel(),
+                           prefill_stream.cuda_stream, decode_stream.cuda_stream)
+    report = _StreamReportStruct(ptr(rep["prefill_done"]), ptr(rep["first_token"]), ptr(rep["unit_done"]), ptr(flags["waited"]),
+                                 ptr(flags["sliced"]), 0.0)
+    torch.cuda.synchronize(dev)
+    _check(lib.st_stream_run(C.byref(job), int(mode), C.byref(report)))
+    rep.update({name: v.astype(bool) for name, v in flags.items()})
+    rep["total_s"] = report.total_s
+    return src_out, rsn_out, rep

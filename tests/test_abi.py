@@ -94,3 +94,41 @@ def test_cache_argument_checks(lib):
     assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 1.0e6, fp, 1 << 20, None) == 2
     assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 64, 1, 8, 0.0, 0.0, fp, 1 << 20, None) == 1
     assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 65, 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 4
+
+
+def test_stream_timeline_matches_oracle():
+    """The scheduler's control logic (host model, no GPU) against the oracle's Alg. 1 timeline."""
+    import paper_2510_17238_amd as st
+    from oracle import streaming_attention as O
+    rng = np.random.Generator(np.random.PCG64(1200))
+    for trial in range(40):
+        k = int(rng.integers(0, 9))
+        arrival = np.cumsum(rng.uniform(0.0, 2.0, k)) * float(rng.integers(0, 2))       # sometimes everything at t = 0
+        prefill = rng.uniform(0.0, 0.6, k)
+        n_dec = rng.integers(0, 25, k)
+        d = float(rng.uniform(0.0, 0.2))
+        for mode, omode in ((st.ST_SCHED_STREAMING, O.STREAMING), (st.ST_SCHED_SERIAL, O.SERIAL), (st.ST_SCHED_BATCH, O.BATCH)):
+            got = st.st_stream_timeline(mode, arrival, prefill, n_dec, d)
+            want = O.alg1_timeline(arrival.tolist(), prefill.tolist(), n_dec.tolist(), d, omode)
+            for name in ("prefill_done", "unit_start", "first_token", "unit_done"):
+                assert np.allclose(got[name], np.asarray(want[name], dtype=np.float64), rtol=0, atol=1e-12), (trial, mode, name)
+            for name in ("waited", "sliced"):
+                assert got[name].tolist() == [bool(x) for x in want[name]], (trial, mode, name)
+    # the worked example of the pins, through the library
+    got = st.st_stream_timeline(st.ST_SCHED_STREAMING, [1.0, 2.0, 10.0], [1.0, 1.0, 1.0], [3, 2, 1], 1.0)
+    assert got["unit_start"].tolist() == [2.0, 5.0, 11.0] and got["waited"].tolist() == [True, False, True]
+
+
+def test_stream_argument_checks(lib):
+    import paper_2510_17238_amd.binding as B
+    a = np.array([1.0, 0.5]); p = np.array([0.1, 0.1]); n = np.array([1, 1], np.int32)
+    assert lib.st_stream_timeline(0, 2, a.ctypes.data, p.ctypes.data, n.ctypes.data, 0.1, None, None, None, None, None, None) == 1   # decreasing
+    a = np.array([0.5, 1.0])
+    assert lib.st_stream_timeline(7, 2, a.ctypes.data, p.ctypes.data, n.ctypes.data, 0.1, None, None, None, None, None, None) == 1
+    assert lib.st_stream_timeline(0, 2, a.ctypes.data, p.ctypes.data, n.ctypes.data, -1.0, None, None, None, None, None, None) == 1
+    assert lib.st_stream_timeline(0, 2, a.ctypes.data, p.ctypes.data, n.ctypes.data, 0.1, None, None, None, None, None, None) == 0
+    assert lib.st_stream_run(None, 0, None) == 1
+    job = B._StreamJobStruct()
+    rep = B._StreamReportStruct()
+    assert lib.st_stream_run(C.byref(job), 5, C.byref(rep)) == 1
+    assert lib.st_stream_run(C.byref(job), 0, C.byref(rep)) == 1 and b"sizes" in lib.st_last_error()
