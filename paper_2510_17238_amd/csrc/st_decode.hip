@@ -19,7 +19,7 @@
 namespace st {
 
 constexpr int kChunk = 512;                 // tokens per work unit
-constexpr int kStepsPerChunk = kChunk / 32; // 32 tokens (two pages) per MFMA step
+constexpr int kChunkLong = 1024;            // ... of the one-token decode step when there is plenty of work (64 pages: one id per lane)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -34,6 +34,7 @@ struct DecodeArgs {
     float* part_ml;    // [B][Hkv][nc][rows][2]
     int batch, q_len, n_q_heads, n_kv_heads, group, rows;
     int ncs, ncr;      // chunk slots per (sequence, head) for the two caches
+    int chunk;         // tokens per work unit (kChunk, or kChunkLong for the one-wave decode kernel)
     float scale_log2;
     // source-chunk prefill only (CHUNKED kernels): ragged query counts and 32-row blocks
     const int32_t* n_new;   // [B] query tokens per sequence, or null for max_new everywhere
@@ -256,9 +257,9 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
     const CacheView& cv = is_src ? a.src : a.rsn;
     const int cc = is_src ? c : c - a.ncs;
     const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
-    const int tok0 = cc * kChunk;
+    const int tok0 = cc * a.chunk;
     if (tok0 >= len) return;
-    const int tok_end = min(len, tok0 + kChunk);
+    const int tok_end = min(len, tok0 + a.chunk);
     const int n_steps = (tok_end - tok0 + 31) / 32;
 
     const int n = lane & 15, g4 = lane >> 4;
@@ -267,6 +268,10 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
     const int t_row = nr / a.group;
     const int hq = h * a.group + nr % a.group;
     const int limit = is_src ? len : max(len - a.q_len + t_row + 1, 0);
+    const int limit_min = is_src ? len : max(len - a.q_len + 1, 0);     // the smallest limit of any row (row 0's)
+    bf16x2 ones2;
+    ones2[0] = (__bf16)1.f;
+    ones2[1] = (__bf16)1.f;
 
     bf16x8 qf[KS];
     {
@@ -281,10 +286,19 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
     f32x4 o_acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    // Softmax state in base-2 exponent units.  m_ref is the row's reference exponent (the same in the four
+    // lanes of a query column); it starts at 0 with has_ref = false and is moved, out of line, only when a
+    // step brings an exponent more than kLazyRise above it (or the first finite score): the common step then
+    // needs no exchange between lanes and no rescale of the accumulator -- probabilities are bounded by
+    // 2^kLazyRise instead of 1, which fp32 and bf16 do not mind, and the merge kernel divides by l anyway.
+    constexpr float kLazyRise = 8.f;
+    float m_ref = 0.f, l_run = 0.f;
+    bool has_ref = false;
 
-    const int32_t* table = cv.page_table + int64_t(b) * cv.max_pages + tok0 / kPage;
+    // the page ids of the whole unit, one per lane, fetched once: no dependent scalar load per step
     const int last_page = (tok_end - 1) / kPage - tok0 / kPage;      // last page of the chunk that holds visible tokens
+    int my_page = cv.page_table[int64_t(b) * cv.max_pages + tok0 / kPage + min(lane, last_page)];
+    my_page = min(max(my_page, 0), cv.n_pages - 1);
     const int64_t page_k = int64_t(cv.n_kv_heads) * KCH * (kPage * 8);
     const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
     // K: lane (m = n, g4) reads d-chunk 4 j + g4 of key row m; row m = 4 gq + i lives in page
@@ -295,11 +309,21 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
     const bool v_second_page = (g4 >> 1) != 0;
     const uint16_t* v_lane = cv.v_pool + int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
 
+    // value of the three other lanes of a query column folded in (lanes n, n + 16, n + 32, n + 48):
+    // v_permlane16_swap / v_permlane32_swap exchange 16- / 32-lane rows between their two operands; with
+    // both operands set to x, every lane finds x of lane ^ 16 (^ 32) in one of the two results
+    auto column_max = [&](float x) {
+        float a1 = x, b1 = x;
+        asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a1), "+v"(b1));
+        float a2 = fmaxf(a1, b1), b2 = a2;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a2), "+v"(b2));
+        return fmaxf(a2, b2);
+    };
+
     for (int s = 0; s < n_steps; ++s) {
         // page ids of this step (uniform); pages past the visible length fall back to the last visible one
-        int id0 = table[min(2 * s, last_page)], id1 = table[min(2 * s + 1, last_page)];
-        id0 = min(max(id0, 0), cv.n_pages - 1);
-        id1 = min(max(id1, 0), cv.n_pages - 1);
+        const int id0 = __builtin_amdgcn_readlane(my_page, min(2 * s, last_page));
+        const int id1 = __builtin_amdgcn_readlane(my_page, min(2 * s + 1, last_page));
         const uint16_t* kp = k_lane + int64_t(k_second_page ? id1 : id0) * page_k;
         const uint16_t* vp = v_lane + int64_t(v_second_page ? id1 : id0) * page_v;
         u32x4 kx[KS], ky[KS], vv[DB];
@@ -318,29 +342,42 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
             sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kx[j]), qf[j], sx, 0, 0, 0);
             sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ky[j]), qf[j], sy, 0, 0, 0);
         }
-        float sc[8];
+        float t[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = fmaf(e < 4 ? sx[e] : sy[e - 4], a.scale_log2, -m_ref);
+        if (tok0 + 32 * s + 32 > limit_min) {           // uniform: a step that reaches some row's limit
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = first + e < limit ? t[e] : -INFINITY;
+        }
         float mx = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float raw = e < 4 ? sx[e] : sy[e - 4];
-            sc[e] = first + e < limit ? raw : -INFINITY;
-            mx = fmaxf(mx, sc[e]);
+        for (int e = 0; e < 8; ++e) mx = fmaxf(mx, t[e]);
+        if (__any(mx > kLazyRise || (!has_ref && mx > -INFINITY))) {
+            // out of line: move the reference of the rows that need it, rescale what they have accumulated
+            const float rise = column_max(mx);
+            const bool move = has_ref ? rise > 0.f : rise > -INFINITY;
+            const float shift = move ? rise : 0.f;
+            const float alpha = has_ref ? __builtin_amdgcn_exp2f(-shift) : 1.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] -= shift;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o_acc[db][i] *= alpha;
+            m_ref += shift;
+            has_ref = has_ref || move;
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * a.scale_log2);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
         bf16x8 pb;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale_log2, -m_use));
-            psum += p;
-            pb[e] = (__bf16)p;
+        for (int e = 0; e < 8; e += 2) {
+            bf16x2 p2;
+            p2[0] = (__bf16)__builtin_amdgcn_exp2f(t[e]);
+            p2[1] = (__bf16)__builtin_amdgcn_exp2f(t[e + 1]);
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, l_run, false);
+            pb[e] = p2[0];
+            pb[e + 1] = p2[1];
         }
-        l_run = l_run * alpha + psum;
         if (tok0 + 32 * s + 32 > len) {                 // uniform: only the step that holds the end of the cache
             u32x4 keep;
 #pragma unroll
@@ -350,11 +387,8 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
             for (int db = 0; db < DB; ++db) vv[db] &= keep;
         }
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o_acc[db][i] *= alpha;
+        for (int db = 0; db < DB; ++db)
             o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv[db]), pb, o_acc[db], 0, 0, 0);
-        }
     }
 
     float l_tot = l_run + __shfl_xor(l_run, 16);
@@ -366,7 +400,7 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
 #pragma unroll
     for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db + 4 * g4) = o_acc[db];
     if (g4 == 0) {
-        a.part_ml[slot * 2] = m_run;
+        a.part_ml[slot * 2] = has_ref ? m_ref : -INFINITY;
         a.part_ml[slot * 2 + 1] = l_tot;
     }
 }
@@ -388,7 +422,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
     const int nc = a.ncs + a.ncr;
     const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
     const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
-    const int n_s = min((len_s + kChunk - 1) / kChunk, a.ncs), n_r = min((len_r + kChunk - 1) / kChunk, a.ncr);
+    const int n_s = min((len_s + a.chunk - 1) / a.chunk, a.ncs), n_r = min((len_r + a.chunk - 1) / a.chunk, a.ncr);
     const int n_tot = n_s + n_r;
     const int64_t base = (int64_t(b) * a.n_kv_heads + h) * nc;
 
@@ -566,8 +600,14 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.n_kv_heads = hkv;
     a.group = group;
     a.rows = lens->q_len * group;
-    a.ncs = chunks_of(lens->max_src_len);
-    a.ncr = chunks_of(lens->max_rsn_len);
+    // Work unit: 512 tokens of one cache; 1024 for the one-wave kernel when that still leaves a thousand
+    // units or more -- its duration does not depend on the unit size, and half as many partial results
+    // have to be written and merged.  (The workspace is sized for the smaller unit.)
+    a.chunk = kChunk;
+    if (a.rows <= 16 && int64_t(batch) * hkv * ((lens->max_src_len + kChunkLong - 1) / kChunkLong + (lens->max_rsn_len + kChunkLong - 1) / kChunkLong) >= 1024)
+        a.chunk = kChunkLong;
+    a.ncs = (lens->max_src_len + a.chunk - 1) / a.chunk;
+    a.ncr = (lens->max_rsn_len + a.chunk - 1) / a.chunk;
     a.scale_log2 = scale * kLog2e;
     a.n_new = nullptr;
     a.max_new = lens->q_len;
@@ -662,6 +702,7 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
     a.n_kv_heads = hkv;
     a.group = n_q_heads / hkv;
     a.rows = 32;
+    a.chunk = kChunk;
     a.ncs = chunks_of(max_src_len);
     a.ncr = 0;
     a.scale_log2 = scale * kLog2e;
