@@ -95,6 +95,23 @@ def test_metadata_edge_structures(st):
     _check_metadata(st, cfg)
 
 
+def test_many_short_sequences_take_the_large_plan_paths(st):
+    """2,800 sequences of a few tokens each: more than 64 sequences (segment tables copied to the device instead of
+    passed by value) and more than 4,096 work items (items and their longest-first order built by the multi-workgroup
+    kernels).  Metadata bit-exact, attention against the oracle for both dtypes."""
+    rng = np.random.Generator(np.random.PCG64(250))
+    lists = [W.draw_pairs(rng, int(rng.integers(1, 2, endpoint=True)), (0, 3), (0, 3)) for _ in range(2800)]
+    lists[7] = (np.array([150]), np.array([140]))            # one sequence with several tiles among them
+    for dtype in ("f32", "bf16"):
+        cfg = W._assemble("many-short", dtype, 2, 1, 64, lists, "interleaved", 250)
+        assert cfg.batch == 2800
+        items = sum(-(-int(sl.sum()) // 128) + -(-int(rl.sum()) // 128) for sl, rl in lists)
+        assert items > 4096
+        if dtype == "f32":
+            _check_metadata(st, cfg)
+        _run_prefill(st, cfg)
+
+
 def test_plan_validation_rejects_bad_metadata(st):
     cfg = W.config1()
     seg, strm, pos = ids_to_dev(cfg)
