@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # HBM bytes per launch of the two dominant kernels on the default workloads, from the FETCH_SIZE and
 # WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB copy (x2.000 and x1.000);
 # see profiles/hbm_traffic_prefill_cfg2_decode_cfg3.txt for the runs.
-MEASURED_TRAFFIC = {"prefill_mfma_kernel<128>": 249.2e6 + 65.8e6, "decode_split16_kernel<128>": 702.6e6 + 3.0e6}
+MEASURED_TRAFFIC = {"prefill_mfma_pipe_kernel<128, 1>": 249.2e6 + 65.8e6, "decode_split16_kernel<128>": 702.6e6 + 3.0e6}
 
 
 def _median(xs):
@@ -439,9 +439,9 @@ def main():
                                "token) + dual-cache decode of one token",
                    "n_tokens": pre["n_tokens"], "effective_flops_per_step": pre["flops"]},
         "prefill_pct_of_peak": round(100.0 * tflops_kernel / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "prefill_mfma_kernel<128>", "bound": "mfma", "achieved": round(tflops_kernel, 3),
+        "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 1>", "bound": "mfma", "achieved": round(tflops_kernel, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC["prefill_mfma_kernel<128>"], "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4)},
+                     "traffic": MEASURED_TRAFFIC["prefill_mfma_pipe_kernel<128, 1>"], "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4)},
     }
     if not args.no_decode:
         dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
@@ -479,7 +479,7 @@ def main():
             "workload": "configs[3]: Qwen3-4B-shaped long-context prefill layer, 8 sequences x 16,384 tokens, 32 q / 8 kv heads, "
                         "head_dim 128, bf16; attention kernel only (two query heads per workgroup)",
             "avg_kernel_ms": round(lp["kernel_ms"], 3), "effective_flops": lp["flops"],
-            "roofline": {"kernel": "prefill_mfma_pair_kernel<128>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
+            "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 2>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
     if not args.no_cpu_baseline:
         from oracle import streaming_attention as O

@@ -14,13 +14,14 @@
 //                         64-row key tile (stream-compact order) into contiguous 16 KB blocks, so
 //                         that the attention kernel streams tiles with plain linear loads and needs
 //                         no per-row token lookup and no transpose in its inner loop.
-//   prefill_mfma_kernel   bf16, 4 waves x 32 query rows, K and V^T tiles double-buffered
-//                         in LDS, QK^T and PV on v_mfma_f32_32x32x16_bf16, fp32 online
-//                         softmax.  Both products are computed TRANSPOSED (S^T = K Q^T,
-//                         O^T = V^T P^T): a lane then owns one query row, so the row max /
-//                         row sum are in-register reductions plus one exchange with lane^32,
-//                         and the S^T accumulators are already laid out as the B operand of
-//                         the second product.
+//   prefill_mfma_pipe_kernel<D, NH>
+//                         bf16, 4 waves x 32 query rows x NH query heads (1 or 2) of one KV head; K and V^T
+//                         tiles copied asynchronously into swizzled LDS buffers; QK^T and PV on
+//                         v_mfma_f32_32x32x16_bf16, fp32 softmax state.  Both products are computed
+//                         TRANSPOSED (S^T = K Q^T, O^T = V^T P^T): a lane then owns one query row, so the
+//                         row max / row sum are in-register reductions plus one exchange with lane^32,
+//                         and the S^T accumulators are already laid out as the B operand of the second
+//                         product.  The loop is software-pipelined by hand (see the kernel).
 //   prefill_simple_kernel any dtype, one thread per query row, plain fp32 arithmetic.  It is
 //                         the fp32 path (tolerance 1e-4) and walks the same work items.
 #include <stdlib.h>
@@ -165,12 +166,6 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int ROW_BYTES>
 __device__ __forceinline__ int swizzle_key(int row) { return ROW_BYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
 
-template <int D>
-struct MfmaSmem {
-    uint16_t k[2][kTileN * D];        // [row][D], rows in MFMA order
-    uint16_t vt[2][D * kTileN];       // [d][64 keys]
-};
-
 // swap bits 2 and 3: the row order in which K is parked in LDS, so that after the
 // first MFMA each half-wave holds 8 CONSECUTIVE keys per 16-key step
 __device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
@@ -236,295 +231,50 @@ __global__ __launch_bounds__(256) void prefill_pack_kernel(uint16_t* __restrict_
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
-                                                              const uint16_t* __restrict__ q,
-                                                              const uint16_t* __restrict__ kc,
-                                                              const uint16_t* __restrict__ vc, PlanView pv,
-                                                              int n_q_heads, int n_kv_heads, float scale_log2) {
-    constexpr int KS = D / 16;        // MFMA steps of the first product
-    constexpr int DB = D / 32;        // 32-wide blocks of the head dimension
-    constexpr int SB = kTileN / 32;   // 32-wide blocks of the key tile
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    MfmaSmem<D>& sm = *reinterpret_cast<MfmaSmem<D>*>(smem_raw);
-
-    const int rank = blockIdx.x / n_q_heads;
-    const int hh = blockIdx.x % n_q_heads;
-    const int group = n_q_heads / n_kv_heads;
-    const int hk = hh % n_kv_heads;                 // consecutive workgroups -> consecutive KV heads
-    const int hq = hk * group + hh / n_kv_heads;
-    const WorkItem it = pv.sorted[rank];
-    if (it.n_rows == 0) return;
-    const ItemGeom g = item_geom(pv, it);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int n = lane & 31, hg = lane >> 5;        // query column of the wave tile, half-wave
-
-    const int n_tiles = it.a_total + it.b_total;
-
-    // ---- tile loader: packed tile -> LDS, asynchronously, no registers in between ----
-    // Every wave copies a quarter of each tile with global_load_lds_dwordx4 (lane l of one such load
-    // deposits its 16 bytes at LDS base + 16 l).  Two K and two V^T buffers; a buffer is refilled as
-    // soon as its tile has been consumed by all four waves:
-    //   K(t+2) is requested right after the first product of tile t, V^T(t+1) at the top of tile t,
-    // which gives every tile more than one full iteration to arrive.  The loads of one wave complete
-    // in order, so "my part of tile X has landed" is s_waitcnt vmcnt(<loads issued after X>), and the
-    // barrier that follows makes all four parts visible to everybody.
-    constexpr int NL = kTileN * D * 2 / 1024 / 4;    // 1 KB loads per wave per tile (K or V^T)
-    const int tile_a0 = it.tile_a0, tile_b0 = it.tile_b0;
-    const size_t head_off = size_t(hk) * pv.pack_tiles * (kTileN * D) + (wave * NL) * 512 + lane * 8;
-    const uint16_t* kc_lane = kc + head_off;
-    const uint16_t* vc_lane = vc + head_off;
-    auto tile_of = [&](int ti) {
-        ti = min(ti, n_tiles - 1);                   // past the end: fetch the last tile again (never read)
-        return ti < it.a_total ? tile_a0 + ti : tile_b0 + (ti - it.a_total);
-    };
-    // (the copies are issued through inline assembly so that the compiler does not track them: knowing
-    // of a pending copy into LDS it would wait for ALL of them before every barrier)
-    const uint32_t lds_k0 = uint32_t(uintptr_t(&sm.k[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
-    const uint32_t lds_v0 = uint32_t(uintptr_t(&sm.vt[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
-    auto issue_k = [&](int ti, int buf) {
-        const uint16_t* src = kc_lane + size_t(tile_of(ti)) * (kTileN * D);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_k0 + buf * (kTileN * D * 2) + u * 1024);
-    };
-    auto issue_v = [&](int ti, int buf) {
-        const uint16_t* src = vc_lane + size_t(tile_of(ti)) * (kTileN * D);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_v0 + buf * (kTileN * D * 2) + u * 1024);
-    };
-
-    // the first tiles are requested before anything else is looked up for this work item
-    issue_k(0, 0);
-    issue_v(0, 0);
-    issue_k(1, 1);
-
-    const int row_in_tile = wave * 32 + n;
-    const bool active = row_in_tile < it.n_rows;
-    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
-    const int tok_q = pv.perm[g.a_base + my_row];
-    const int my_vis = pv.vis[g.a_base + my_row];
-
-    // Q^T operand: lane (n, hg) holds Q[row n][16 j + 8 hg .. + 8)
-    bf16x8 qf[KS];
-    {
-        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq) * D + 8 * hg;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 16 * j);
-    }
-
-    f32x16 o_acc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    // operand addresses: lane (n, hg) reads chunk (2 j + hg) ^ key(row) = (2 j) ^ (key ^ hg) of its row
-    int koff[KS], voff[4];
-    {
-        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
-    }
-
-    // everything fetched once per work item must have landed before the loop, or the compiler
-    // re-checks for it inside every iteration
-    {
-        int t0 = my_vis, t1 = tok_q;
-        asm volatile("" : "+v"(t0), "+v"(t1));
-    }
-#pragma unroll
-    for (int j = 0; j < KS; ++j) {
-        u32x4 t = __builtin_bit_cast(u32x4, qf[j]);
-        asm volatile("" : "+v"(t));
-        qf[j] = __builtin_bit_cast(bf16x8, t);
-    }
-
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    bf16x2 ones2;
-    ones2[0] = (__bf16)1.f;
-    ones2[1] = (__bf16)1.f;
-    for (int ti = 0; ti < n_tiles; ++ti) {
-        const int buf = ti & 1;
-        // K(ti) has landed (still in flight behind it: V^T(ti), K(ti+1)); everybody is done with tile ti-1
-        wait_vmcnt<2 * NL>();
-        __syncthreads();
-        issue_v(ti + 1, buf ^ 1);
-
-        const bool in_a = ti < it.a_total;
-        const int kt = in_a ? ti : ti - it.a_total;
-        // a ragged last tile is FULL as far as the mask goes, but its out-of-range columns
-        // (zero rows in the packed tile) still have to be compared away
-        const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? g.n_stream : g.S);
-
-        // ---- S^T = K Q^T : rows = keys, columns = query rows ----------------
-        // the K fragments are fetched from LDS four MFMAs ahead of their use
-        f32x16 s_acc[SB];
-        {
-            constexpr int NF = SB * KS, AHEAD = 4;
-            const uint16_t* kb = &sm.k[buf][0];
-            bf16x8 a[NF];
-#pragma unroll
-            for (int f = 0; f < AHEAD; ++f)
-                a[f] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f / KS) * D + koff[f % KS]);
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                if (f + AHEAD < NF) {
-                    const int f2 = f + AHEAD;
-                    a[f2] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f2 / KS) * D + koff[f2 % KS]);
-                }
-                const int sb = f / KS, j = f % KS;
-                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
-            }
-            // keep that order in the instruction stream: AHEAD LDS reads, then one read per MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
-#pragma unroll
-            for (int f = 0; f < NF - AHEAD; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
-        }
-        // V^T(ti) has landed (behind it: K(ti+1), V^T(ti+1)); everybody has read K(ti)
-        wait_vmcnt<2 * NL>();
-        __syncthreads();
-        issue_k(ti + 2, buf);
-
-        // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
-        if (partial) {
-            const int limit = in_a ? my_row + 1 : my_vis;
-            const int c0 = kt * kTileN + 8 * hg;
-#pragma unroll
-            for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int col = c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
-                    s_acc[sb][i] = col < limit ? s_acc[sb][i] : -INFINITY;
-                }
-        }
-        // ---- online softmax (base-2, scale folded in) ----------------------
-        // Lazy running maximum: it is only raised when the tile maximum exceeds it by more than
-        // kLazyMax exponent units.  Probabilities are then bounded by 2^kLazyMax instead of 1 (harmless
-        // in fp32 / bf16, and the final division by l is unchanged), and the rescale of the output
-        // accumulator -- 64 multiplications per lane -- becomes a rare event instead of a per-tile one.
-        float mx = -INFINITY;
-#pragma unroll
-        for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[sb][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-        const bool grew = mx > m_run + kLazyMax;         // also true for the first finite maximum
-        const float m_new = grew ? mx : m_run;
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        // the row sum is taken over the bf16-rounded probabilities, two per v_dot2c_f32_bf16: half the
-        // additions, and l then matches the P that multiplies V
-        float psum = 0.f;
-        bf16x8 pb[SB][2];
-#pragma unroll
-        for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                bf16x2 p2;
-                p2[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_acc[sb][i], scale_log2, -m_use));
-                p2[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_acc[sb][i + 1], scale_log2, -m_use));
-                psum = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, psum, false);
-                pb[sb][i >> 3][i & 7] = p2[0];
-                pb[sb][i >> 3][(i & 7) + 1] = p2[1];
-            }
-        if (__any(grew)) {                               // otherwise alpha == 1 in every lane
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
-        }
-        l_run += psum;
-
-        // ---- O^T += V^T P^T --------------------------------------------------
-        {
-            constexpr int NF = DB * SB * 2, AHEAD = 4;
-            const uint16_t* vb = &sm.vt[buf][0];
-            bf16x8 a[NF];
-#pragma unroll
-            for (int f = 0; f < AHEAD; ++f) a[f] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f / (SB * 2)) * kTileN + voff[f % (SB * 2)]);
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                if (f + AHEAD < NF) {
-                    const int f2 = f + AHEAD;
-                    a[f2] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f2 / (SB * 2)) * kTileN + voff[f2 % (SB * 2)]);
-                }
-                const int db = f / (SB * 2), st = f % (SB * 2);      // st = 2 sb + t: keys 16 st .. 16 st + 15
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[st >> 1][st & 1], o_acc[db], 0, 0, 0);
-            }
-        }
-    }
-    wait_vmcnt<0>();                                     // no copy into LDS may outlive the workgroup
-
-    // ---- epilogue ------------------------------------------------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (!active) return;
-    const float inv = 1.f / l_tot;
-    uint16_t* op = out + (int64_t(tok_q) * n_q_heads + hq) * D;
-    // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            bf16x4 o4;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) o4[c] = (__bf16)(o_acc[db][4 * q4 + c] * inv);
-            *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * hg) = o4;
-        }
-    if (lse && hg == 0) lse[int64_t(tok_q) * n_q_heads + hq] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
-}
-
-
 // --------------------------------------------------------------------------
-// MFMA kernel, two query heads per workgroup (bf16, grouped-query attention with an even group).
+// MFMA kernel (bf16): NH = 1 or 2 query heads of one KV head per workgroup.
 // --------------------------------------------------------------------------
-// Same work items, same packed tiles, same transposed products as prefill_mfma_kernel, but every
-// wave owns its 32 query rows for TWO query heads that share one KV head.  A K (or V^T) operand
-// fragment read from LDS then feeds two MFMAs, and one tile copied into LDS serves twice the
-// arithmetic: the LDS read traffic and the L2 -> LDS copy traffic per flop are both halved, which is
-// what bounds the single-head kernel.  The price is registers (two output accumulators, two score
-// blocks, two Q operands), so only one wave runs per SIMD and nothing but the wave's own
-// instruction stream can hide latency.  The loop is therefore software-pipelined by hand:
-//   phase X of tile t:  scores of tile t+1 (matrix pipe)  beside  exp / row sum / bf16 P of tile t
-//   phase Y of tile t:  O^T += V^T P^T of tile t (matrix pipe)  beside  exponents and row maximum of tile t+1
-// with three K and three V^T buffers and ONE barrier per key tile (tile copies are requested two
-// iterations ahead).
-// The running maximum of a row is only raised when the tile maximum exceeds it by more than
-// kLazyMax (base-2 exponent units).  Probabilities then reach at most 2^kLazyMax, far inside
-// fp32 / bf16 range, the normalisation by l at the end is unchanged, and the rescale of the
-// output accumulator becomes a rare event instead of a per-tile one.
-template <int D>
-struct PairSmem {
-    uint16_t k[3][kTileN * D];
-    uint16_t vt[3][D * kTileN];
+// Every wave owns 32 query rows of a work item for NH query heads that share a KV head.
+//   NH = 2  A K (or V^T) operand fragment read from LDS feeds two MFMAs and one tile copied into LDS
+//           serves twice the arithmetic: LDS read traffic and L2 -> LDS copy traffic per flop are both
+//           halved.  The price is registers (two output accumulators, two score blocks, two Q operands:
+//           about 440 per lane, the output accumulators in accumulation registers), so one wave per SIMD;
+//           three K and three V^T buffers (96 KB), copies two tiles ahead.
+//   NH = 1  fits the ordinary vector registers twice per SIMD: two workgroups per CU, two buffers each
+//           (64 KB), copies one tile ahead.
+// Either way a wave cannot count on other waves to fill the matrix pipe while it does its softmax, so
+// the loop is software-pipelined by hand, in the exact instruction order wanted:
+//   phase X of tile t:  scores of tile t+1   beside  exp2 / bf16 P / row sum of tile t
+//   phase Y of tile t:  O^T += V^T P^T        beside  exponents and row maximum of tile t+1
+// with ONE barrier per key tile.
+// The running maximum of a row is lazy: the reference exponent m_ref is only moved when the maximum of a
+// new tile exceeds it by more than kLazyMax (base-2 exponent units).  Probabilities are then bounded by
+// 2^kLazyMax instead of 1, which neither fp32 nor bf16 minds, the final division by l is unchanged, and
+// the rescale of l and of the output accumulator (an out-of-line block) becomes a rare event instead of a
+// per-tile one.
+template <int D, int STAGES>
+struct PipeSmem {
+    uint16_t k[STAGES][kTileN * D];
+    uint16_t vt[STAGES][D * kTileN];
 };
-template <int D>
-__global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
+template <int D, int NH>
+__global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_mfma_pipe_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
                                                                    const uint16_t* __restrict__ q,
                                                                    const uint16_t* __restrict__ kc,
                                                                    const uint16_t* __restrict__ vc, PlanView pv,
                                                                    int n_q_heads, int n_kv_heads, float scale_log2) {
     constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
     constexpr int TILE = kTileN * D;              // elements of one K or V^T tile
+    constexpr int STAGES = NH == 2 ? 3 : 2;       // K / V^T buffers: the one-head form must fit two workgroups per CU
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    PairSmem<D>& sm = *reinterpret_cast<PairSmem<D>*>(smem_raw);
+    PipeSmem<D, STAGES>& sm = *reinterpret_cast<PipeSmem<D, STAGES>*>(smem_raw);
 
-    const int n_pairs = n_q_heads >> 1;
-    const int rank = blockIdx.x / n_pairs;
-    const int hh = blockIdx.x % n_pairs;
+    const int n_sets = n_q_heads / NH;
+    const int rank = blockIdx.x / n_sets;
+    const int hh = blockIdx.x % n_sets;
     const int group = n_q_heads / n_kv_heads;
     const int hk = hh % n_kv_heads;                 // consecutive workgroups -> consecutive KV heads
-    const int hq0 = hk * group + 2 * (hh / n_kv_heads);
+    const int hq0 = hk * group + NH * (hh / n_kv_heads);
     const WorkItem it = pv.sorted[rank];
     if (it.n_rows == 0) return;
 
@@ -554,12 +304,16 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
 #pragma unroll
         for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_v0 + stage * (TILE * 2) + u * 1024);
     };
-    // copy order: K0 V0 K1 V1 K2 | V2 K3 | V3 K4 | ...   (tile x lives in buffer x % 3)
+    // copy order (tile x lives in buffer x % STAGES):
+    //   three buffers: K0 V0 K1 V1 K2 | V2 K3 | V3 K4 | ...  two tiles ahead
+    //   two buffers:   K0 V0 K1       | V1 K2 | V2 K3 | ...  one tile ahead
     issue_k(0, 0);
     issue_v(0, 0);
     issue_k(1, 1);
-    issue_v(1, 1);
-    issue_k(2, 2);
+    if (STAGES == 3) {
+        issue_v(1, 1);
+        issue_k(2, 2);
+    }
 
     const int row_in_tile = wave * 32 + n;
     const bool active = row_in_tile < it.n_rows;
@@ -567,23 +321,29 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
     const int tok_q = pv.perm[it.a_base + my_row];
     const int my_vis = pv.vis[it.a_base + my_row];
 
-    bf16x8 qf[2][KS];
+    bf16x8 qf[NH][KS];
     {
         const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq0) * D + 8 * hg;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int j = 0; j < KS; ++j) qf[h][j] = *reinterpret_cast<const bf16x8*>(qp + h * D + 16 * j);
     }
 
-    f32x16 o_acc[2][DB];
+    f32x16 o_acc[NH][DB];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < NH; ++h)
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int i = 0; i < 16; ++i) o_acc[h][db][i] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    float m_run[NH], l_run[NH], m_ref[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        m_run[h] = -INFINITY;
+        l_run[h] = 0.f;
+        m_ref[h] = 0.f;
+    }
 
     int koff[KS], voff[4];
     {
@@ -598,7 +358,7 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
         asm volatile("" : "+v"(t0), "+v"(t1));
     }
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < NH; ++h)
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
             u32x4 t = __builtin_bit_cast(u32x4, qf[h][j]);
@@ -609,14 +369,14 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // scores of the tile in buffer `stage`, both heads: every K fragment feeds two MFMAs
-    auto scores = [&](f32x16 (&s)[2][SB], int stage) {
+    auto scores = [&](f32x16 (&s)[NH][SB], int stage) {
         const uint16_t* kb = &sm.k[0][0] + stage * TILE;
 #pragma unroll
         for (int f = 0; f < SB * KS; ++f) {
             const int sb = f % SB, j = f / SB;
             const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + 32 * sb * D + koff[j]);
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int h = 0; h < NH; ++h)
                 s[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[h][j], j == 0 ? zero16 : s[h][sb], 0, 0, 0);
         }
     };
@@ -636,7 +396,6 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
     // common case the tile maximum stays within kLazyMax of the reference and t is final.
     // Otherwise (first tile of a row, or a real jump of the maximum) settle() moves the reference
     // and repairs t, l and the output accumulator, out of line.
-    float m_ref[2] = {0.f, 0.f};
     // value of lane ^ 32 (v_permlane32_swap exchanges the upper half of its first operand with the
     // lower half of its second one; with both set to x, each lane finds its partner's x in one of them)
     auto max_with_partner = [&](float x) {
@@ -651,24 +410,32 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
         // 128 of them back and forth in every iteration).  The idle cycles in front let the last
         // matrix instructions retire before their results are read, the ones behind separate the
         // last write from the next matrix instruction.
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        // (The one-head form fits the ordinary vector registers and multiplies there.)
+        if constexpr (NH == 2) {
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float x = o_acc[h][db][i], tmp;
-                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
-                             : "+a"(x), "=&v"(tmp) : "v"(alpha));
-                o_acc[h][db][i] = x;
-            }
-        asm volatile("s_nop 7" ::: "memory");
+                for (int i = 0; i < 16; ++i) {
+                    float x = o_acc[h][db][i], tmp;
+                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                                 : "+a"(x), "=&v"(tmp) : "v"(alpha));
+                    o_acc[h][db][i] = x;
+                }
+            asm volatile("s_nop 7" ::: "memory");
+        } else {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o_acc[h][db][i] *= alpha;
+        }
     };
     // sv holds the exponents of a fresh tile relative to m_ref, mx their per-lane maximum
-    auto settle = [&](f32x16 (&sv)[2][SB], float (&mx)[2], const TileInfo& ti) {
+    auto settle = [&](f32x16 (&sv)[NH][SB], float (&mx)[NH], const TileInfo& ti) {
         if (ti.partial) {
             // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < NH; ++h) {
                 mx[h] = -INFINITY;
 #pragma unroll
                 for (int sb = 0; sb < SB; ++sb)
@@ -680,16 +447,17 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
                     }
             }
         }
-        float rise[2];
-        bool g[2];
+        float rise[NH];
+        bool g[NH], any_g = false;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < NH; ++h) {
             rise[h] = max_with_partner(mx[h]);                   // tile maximum of the row, relative to m_ref
             g[h] = m_run[h] == -INFINITY ? rise[h] > -INFINITY : rise[h] > kLazyMax;
+            any_g = any_g || g[h];
         }
-        if (__any(g[0] || g[1])) {
+        if (__any(any_g)) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < NH; ++h) {
                 const float shift = g[h] ? rise[h] : 0.f;        // rows that stay put: shift 0, alpha 1
                 const float m_new = m_ref[h] + shift;
                 const float alpha = g[h] ? __builtin_amdgcn_exp2f(m_run[h] - m_new) : 1.f;
@@ -706,14 +474,16 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
     };
 
     // ---- prologue: exponents and row maximum of tile 0 ----
-    f32x16 sv[2][SB];
-    wait_vmcnt<4 * NL>();                                // K0 has landed
+    f32x16 sv[NH][SB];
+    wait_vmcnt<(STAGES == 3 ? 4 : 2) * NL>();            // K0 has landed
     __syncthreads();
     scores(sv, 0);
     {
-        float mx[2] = {-INFINITY, -INFINITY};
+        float mx[NH];
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < NH; ++h) mx[h] = -INFINITY;
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
@@ -729,22 +499,29 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
 
     int stage = 0;                                       // buffer of tile ti
     for (int ti = 0; ti < n_tiles; ++ti) {
-        // K(ti+1) and V^T(ti) have landed (in flight behind them: V^T(ti+1), K(ti+2)); everybody is
-        // done with K(ti) and V^T(ti-1), whose buffers the next two copies go to
-        wait_vmcnt<2 * NL>();
+        // K(ti+1) and V^T(ti) have landed (with three buffers V^T(ti+1), K(ti+2) are in flight behind them);
+        // everybody is done with K(ti) and V^T(ti-1), whose buffers the next two copies go to
+        wait_vmcnt<(STAGES == 3 ? 2 : 0) * NL>();
         __syncthreads();
-        const int stage1 = stage == 2 ? 0 : stage + 1, stage2 = stage == 0 ? 2 : stage - 1;
-        issue_v(ti + 2, stage2);
-        issue_k(ti + 3, stage);
+        const int stage1 = stage == STAGES - 1 ? 0 : stage + 1;
+        if (STAGES == 3) {
+            issue_v(ti + 2, stage == 0 ? 2 : stage - 1);
+            issue_k(ti + 3, stage);
+        } else {
+            issue_v(ti + 1, stage1);
+            issue_k(ti + 2, stage);
+        }
 
         // The two phases below are written in the exact instruction order wanted -- per matrix
         // instruction one small piece of vector work, LDS operand reads kPF fragments ahead -- and
         // every piece ends in a scheduling barrier so that the compiler keeps that order.
         // ---- phase X: scores of tile ti+1  |  probabilities of tile ti ----
         constexpr int kPF = 3;
-        f32x16 s_next[2][SB];
-        bf16x8 pb[2][SB][2];
-        float psum[2] = {0.f, 0.f};
+        f32x16 s_next[NH][SB];
+        bf16x8 pb[NH][SB][2];
+        float psum[NH];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) psum[h] = 0.f;
         {
             constexpr int NF = SB * KS;                          // fragment f: key block f % SB, k-step f / SB
             const uint16_t* kb = &sm.k[0][0] + stage1 * TILE;
@@ -759,11 +536,11 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
                 }
                 const int sb = f % SB, j = f / SB;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < NH; ++h) {
                     s_next[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[h][j], j == 0 ? zero16 : s_next[h][sb], 0, 0, 0);
-                    // slot 2 f + h of 2 NF: its share of the probabilities of tile ti
+                    // slot NH f + h of NH NF: its share of the probabilities of tile ti
                     constexpr int PER = 16 * SB / NF;            // elements per slot (one head has 16 SB of them, in NF slots)
-                    const int slot = 2 * f + h;
+                    const int slot = NH * f + h;
                     const int hh = slot / NF, e0 = (slot % NF) * PER;
 #pragma unroll
                     for (int e = e0; e < e0 + PER; ++e) {
@@ -778,12 +555,15 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
         }
         // (the sums are wanted HERE: left alone, the optimiser defers them past the second phase and
         //  recomputes the exponentials they are made of)
-        asm volatile("" : "+v"(psum[0]), "+v"(psum[1]));
 #pragma unroll
-        for (int h = 0; h < 2; ++h) l_run[h] += psum[h];
+        for (int h = 0; h < NH; ++h) asm volatile("" : "+v"(psum[h]));
+#pragma unroll
+        for (int h = 0; h < NH; ++h) l_run[h] += psum[h];
 
         // ---- phase Y: O^T += V^T P^T of tile ti  |  row maximum of tile ti+1 ----
-        float mx[2] = {-INFINITY, -INFINITY};
+        float mx[NH];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) mx[h] = -INFINITY;
         {
             constexpr int NF = DB * SB * 2;                      // fragment f: d block f % DB, 16-key step f / DB
             const uint16_t* vb = &sm.vt[0][0] + stage * TILE;
@@ -798,10 +578,10 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
                 }
                 const int db = f % DB, st = f / DB;              // keys 16 st .. 16 st + 15
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < NH; ++h) {
                     o_acc[h][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[h][st >> 1][st & 1], o_acc[h][db], 0, 0, 0);
                     constexpr int PER = 16 * SB / NF;
-                    const int slot = 2 * f + h;
+                    const int slot = NH * f + h;
                     const int hh = slot / NF, e0 = (slot % NF) * PER;
 #pragma unroll
                     for (int e = e0; e < e0 + PER; ++e) {
@@ -816,14 +596,15 @@ __global__ __launch_bounds__(256, 1) void prefill_mfma_pair_kernel(uint16_t* __r
                 }
             }
         }
-        asm volatile("" : "+v"(mx[0]), "+v"(mx[1]));        // computed above, not in a later block
+#pragma unroll
+        for (int h = 0; h < NH; ++h) asm volatile("" : "+v"(mx[h]));   // computed above, not in a later block
         settle(sv, mx, tile_info(ti + 1));
         stage = stage1;
     }
     wait_vmcnt<0>();                                     // no copy into LDS may outlive the workgroup
 
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NH; ++h) {
         const float l_tot = l_run[h] + __shfl_xor(l_run[h], 32);   // wave-wide exchange: inactive rows take part
         if (!active) continue;
         const float inv = 1.f / l_tot;
@@ -929,28 +710,24 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
         constexpr int HD = decltype(dtag)::value;
         hipLaunchKernelGGL((prefill_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
                            (const uint16_t*)v, pv, n_kv_heads);
-        if (pair) {
-            const size_t smem = sizeof(PairSmem<HD>);
-            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_pair_kernel<HD>),
+        auto run = [&](auto nh_tag) -> st_status {
+            constexpr int NH = decltype(nh_tag)::value;
+            const size_t smem = sizeof(PipeSmem<HD, NH == 2 ? 3 : 2>);
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_pipe_kernel<HD, NH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfPrefillAttn, s);
-            hipLaunchKernelGGL((prefill_mfma_pair_kernel<HD>), dim3((unsigned)(blocks / 2)), dim3(256), smem, s, (uint16_t*)out, lse,
-                               (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
+            hipLaunchKernelGGL((prefill_mfma_pipe_kernel<HD, NH>), dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
+                               lse, (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
             prof_end(kProfPrefillAttn, s);
-        } else {
-            const size_t smem = sizeof(MfmaSmem<HD>);
-            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_kernel<HD>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
-            prof_begin(kProfPrefillAttn, s);
-            hipLaunchKernelGGL((prefill_mfma_kernel<HD>), dim3((unsigned)blocks), dim3(256), smem, s, (uint16_t*)out, lse,
-                               (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
-            prof_end(kProfPrefillAttn, s);
-        }
+            return ST_OK;
+        };
+        const st_status rr = pair ? run(std::integral_constant<int, 2>{}) : run(std::integral_constant<int, 1>{});
+        if (rr != ST_OK) return rr;
         return ST_OK;
     };
     const st_status lr = head_dim == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});
     if (lr != ST_OK) return lr;
-    ST_LAUNCH_CHECK("prefill_pack_kernel / prefill_mfma_kernel");
+    ST_LAUNCH_CHECK("prefill_pack_kernel / prefill_mfma_pipe_kernel");
     return ST_OK;
 }
 
