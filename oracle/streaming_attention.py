@@ -23,7 +23,8 @@ Pins (all in tests/test_oracle_pins.py): brute-force gather, layout
 equivariance, Eq. 2 as printed, reduction to library causal attention, source chunk == source rows of prefill,
 closed-form visible-pair counts, LSE-merge == concatenation, RoPE identities,
 decode == last prefill row, paged gather == contiguous, rotate-on-append / rotate-in-decode ==
-the unfused pipeline, Alg. 1 timeline == hand-worked schedules and the paper's Table 4 latencies.
+the unfused pipeline, Alg. 1 timeline == hand-worked schedules and the paper's Table 4 latencies,
+backward == central differences of the forward and == library autograd of a dense-mask softmax.
 No function here is "parity unpinned".
 """
 import numpy as np
@@ -164,6 +165,52 @@ def attention_bruteforce(q, k, v, stream, seg, pos, scale=None):
                 out[i, h, t] = sum(w[a] * v[vis[a], hk, t] for a in range(len(vis))) / den
             lse[i, h] = mx + np.log(den)
     return out, lse
+
+
+def attention_dense_backward(q, k, v, d_out, stream, seg, pos, scale=None):
+    """Gradients of attention_dense for ONE sequence (streaming-constrained training, Sec. 3.2: the
+    mask of Eq. 2 is applied in the forward pass, so masked pairs carry no gradient).
+
+    Given d_out = dL/d out [n, Hq, D], returns dq [n, Hq, D], dk, dv [n, Hkv, D] (summed over the
+    query heads of a KV group).  With P = softmax over the visible keys and delta_i = sum_d d_out_i * out_i:
+        dV_j = sum_i P_ij d_out_i        dP_ij = d_out_i . V_j        dS_ij = P_ij (dP_ij - delta_i)
+        dQ_i = scale sum_j dS_ij K_j     dK_j = scale sum_i dS_ij Q_i
+    which is the chain rule through out = P V, P = softmax(scale Q K^T) written out.
+    """
+    q = np.asarray(q, dtype=np.float64); k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64); d_out = np.asarray(d_out, dtype=np.float64)
+    n, hq, d = q.shape
+    hkv = k.shape[1]
+    group = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    mask = dense_mask(stream, seg, pos)
+    dq = np.zeros_like(q); dk = np.zeros_like(k); dv = np.zeros_like(v)
+    for h in range(hq):
+        hk = h // group
+        s = np.where(mask, scale * (q[:, h, :] @ k[:, hk, :].T), -np.inf)
+        mx = s.max(axis=1, keepdims=True, initial=-np.inf)
+        mx = np.where(np.isfinite(mx), mx, 0.0)
+        e = np.where(mask, np.exp(s - mx), 0.0)
+        den = e.sum(axis=1, keepdims=True)
+        p = e / np.where(den > 0, den, 1.0)
+        out = p @ v[:, hk, :]
+        delta = (d_out[:, h, :] * out).sum(axis=1, keepdims=True)
+        d_p = d_out[:, h, :] @ v[:, hk, :].T
+        d_s = p * (d_p - delta)
+        dv[:, hk, :] += p.T @ d_out[:, h, :]
+        dq[:, h, :] = scale * (d_s @ k[:, hk, :])
+        dk[:, hk, :] += scale * (d_s.T @ q[:, h, :])
+    return dq, dk, dv
+
+
+def attention_varlen_backward(q, k, v, d_out, stream, seg, pos, cu_seqlens, scale=None):
+    """attention_dense_backward over a packed batch."""
+    dq = np.zeros(np.asarray(q).shape); dk = np.zeros(np.asarray(k).shape); dv = np.zeros(np.asarray(v).shape)
+    for b in range(len(cu_seqlens) - 1):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        dq[s:e], dk[s:e], dv[s:e] = attention_dense_backward(q[s:e], k[s:e], v[s:e], d_out[s:e], stream[s:e], seg[s:e], pos[s:e], scale)
+    return dq, dk, dv
 
 
 # --------------------------------------------------------------------------

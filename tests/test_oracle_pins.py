@@ -434,6 +434,53 @@ def test_p11_alg1_timeline_reproduces_table4_latencies():
     assert st["waited"] == [True] * K
 
 
+# ---- P12: backward of the streaming-mask attention == numerical derivative of the forward, == library autograd
+def test_p12_backward_matches_central_differences():
+    rng = np.random.Generator(np.random.PCG64(1200))
+    stream, seg, pos = W.tokens_from_segments([2, 3, 1], [3, 1, 2], "interleaved")
+    n, hq, hkv, d = len(stream), 4, 2, 6
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    g = rng.standard_normal((n, hq, d))                     # dL/d out for L = sum(g * out)
+    dq, dk, dv = O.attention_dense_backward(q, k, v, g, stream, seg, pos)
+    loss = lambda q_, k_, v_: float((g * O.attention_dense(q_, k_, v_, stream, seg, pos)[0]).sum())
+    eps = 1e-6
+    for name, x, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        idx = [tuple(rng.integers(0, s) for s in x.shape) for _ in range(25)]
+        for i in idx:
+            xp = x.copy(); xm = x.copy(); xp[i] += eps; xm[i] -= eps
+            args_p = {"q": (xp, k, v), "k": (q, xp, v), "v": (q, k, xp)}[name]
+            args_m = {"q": (xm, k, v), "k": (q, xm, v), "v": (q, k, xm)}[name]
+            num = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(num - grad[i]) < 1e-7, (name, i, num, grad[i])
+    # what a token cannot see gets no gradient from it: the first source token's K only receives gradient,
+    # the last reasoning token's K / V only from itself
+    last = n - 1
+    only_last = np.zeros_like(g); only_last[last] = g[last]
+    _, dk1, dv1 = O.attention_dense_backward(q, k, v, only_last, stream, seg, pos)
+    vis = O.dense_mask(stream, seg, pos)[last]
+    assert np.all(dk1[~vis] == 0) and np.all(dv1[~vis] == 0) and np.abs(dv1[vis]).min() > 0
+
+
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 1)])
+def test_p12_backward_matches_library_autograd(hq, hkv):
+    """torch autograd (fp64, CPU) through an explicit additive -inf mask, softmax and two matmuls."""
+    rng = np.random.Generator(np.random.PCG64(1210 + hq))
+    stream, seg, pos = W.tokens_from_segments([4, 1, 5], [2, 6, 3], "grouped")
+    n, d = len(stream), 8
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    g = rng.standard_normal((n, hq, d))
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    add = torch.tensor(np.where(O.dense_mask(stream, seg, pos), 0.0, -np.inf))
+    rep = hq // hkv
+    scores = torch.einsum("ihd,jhd->hij", tq, tk.repeat_interleave(rep, dim=1)) / np.sqrt(d) + add
+    out = torch.einsum("hij,jhd->ihd", torch.softmax(scores, dim=-1), tv.repeat_interleave(rep, dim=1))
+    (out * torch.tensor(g)).sum().backward()
+    dq, dk, dv = O.attention_dense_backward(q, k, v, g, stream, seg, pos)
+    assert np.abs(dq - tq.grad.numpy()).max() < 1e-12
+    assert np.abs(dk - tk.grad.numpy()).max() < 1e-12
+    assert np.abs(dv - tv.grad.numpy()).max() < 1e-12
+
+
 # ---- metadata derived from the dense mask: closed forms for config 1
 def test_metadata_config1_closed_form():
     cfg = W.config1()
