@@ -237,6 +237,31 @@ def bench_stream_session(st, torch, W, time_scale):
                                                 "the paper reports 6.231 s (streaming) vs 28.003 s (batch) for the whole model"}}
 
 
+def bench_prefill_backward(st, torch, W, reps):
+    """Forward + backward of the attention stage on configs[1] (the plain backward path)."""
+    dev = "cuda"
+    cfg = W.config2()
+    hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
+    g = torch.Generator(device=dev); g.manual_seed(cfg.seed + 9)
+    rnd = lambda h: torch.randn((n, h, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, go = rnd(hq), rnd(hkv), rnd(hkv), rnd(hq)
+    seg = torch.from_numpy(cfg.segment_ids).to(dev); strm = torch.from_numpy(cfg.stream_ids).to(dev)
+    pos = torch.from_numpy(cfg.positions).to(dev)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    flops_fwd = 4.0 * d * hq * float(plan.visible_pairs().sum())
+    lse = torch.empty((n, hq), dtype=torch.float32, device=dev)
+    out = st.st_attn_prefill(q, k, v, plan, lse=lse)
+    st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
+    e1.record(); torch.cuda.synchronize()
+    plan.destroy()
+    return {"ms": e0.elapsed_time(e1) / reps, "flops": 2.5 * flops_fwd}
+
+
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
     dev = "cuda"
     shp = W.config3() if n_layers is None else W.config3(n_layers=n_layers)
@@ -399,6 +424,8 @@ def main():
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     ap.add_argument("--long-prefill", action="store_true",
                     help="also time the attention kernel on configs[3] (8 x 16,384 tokens) and report it under 'prefill_long'")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time st_attn_prefill_bwd on configs[1] and report it under 'prefill_backward'")
     ap.add_argument("--stream-session", action="store_true",
                     help="also run one Alg. 1 session (streaming / alternating / batch schedules) and report it under 'stream_session'")
     ap.add_argument("--stream-time-scale", type=float, default=0.01, help="compression of the arrival times of --stream-session")
@@ -470,6 +497,15 @@ def main():
             "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
             "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
                     "each of which streams the cache again"}
+    if args.backward:
+        bw = bench_prefill_backward(st, torch, W, 3)
+        tf = bw["flops"] / (bw["ms"] * 1e-3) / 1e12
+        line["prefill_backward"] = {
+            "workload": "configs[1], gradients dq / dk / dv of the attention stage (plain one-thread-per-row kernels, fp32 arithmetic)",
+            "ms": round(bw["ms"], 3), "algorithmic_flops": bw["flops"],
+            "roofline": {"kernel": "bwd_dq_kernel + bwd_dkv_kernel x 2", "bound": "alu", "achieved": round(tf, 2), "peak": 157.3,
+                         "unit": "TFLOP/s", "frac": round(tf / 157.3, 4), "traffic": None,
+                         "note": "10 D flop per visible (query, key, head) triple; the kernels recompute the scores three times"}}
     if args.stream_session:
         line["stream_session"] = bench_stream_session(st, torch, W, args.stream_time_scale)
     if args.long_prefill:

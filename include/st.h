@@ -197,6 +197,30 @@ st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* 
                               int32_t head_dim, float scale, st_dtype dt, void* hip_stream);
 
 /* ------------------------------------------------------------------------
+ * st_attn_prefill_bwd -- gradients of st_attn_prefill (streaming-constrained training,
+ * Sec. 3.2: the mask of Eq. 2 is applied in the forward pass of fine-tuning, so only visible
+ * pairs carry gradient).
+ *
+ *   d_out        : [N, n_q_heads,  head_dim]   dL / d out
+ *   q, out       : [N, n_q_heads,  head_dim]   the forward's input and output
+ *   k, v         : [N, n_kv_heads, head_dim]
+ *   lse          : fp32 [N, n_q_heads]         the forward's log-sum-exp (natural log)
+ *   dq           : [N, n_q_heads,  head_dim]   (written)
+ *   dk, dv       : [N, n_kv_heads, head_dim]   (written; summed over the query heads of a KV group)
+ * all of dtype dt (fp32 arithmetic inside), same plan as the forward.  Deterministic (no atomics).
+ * This is the plain one-thread-per-row path, not tuned.
+ * workspace: at least st_prefill_bwd_workspace_bytes(plan, n_q_heads) bytes, 256-byte aligned.
+ * Errors as for st_attn_prefill.
+ * ---------------------------------------------------------------------- */
+size_t st_prefill_bwd_workspace_bytes(const st_plan* plan, int32_t n_q_heads);
+
+st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const void* d_out, const void* q,
+                              const void* k, const void* v, const void* out, const float* lse,
+                              const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads,
+                              int32_t head_dim, float scale, st_dtype dt,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------
  * Paged KV caches.  Sec. 3.3: a source cache for input tokens and a separate
  * cache for reasoning tokens.  Logical position p of sequence b lives in page
  * page_table[b * max_pages_per_seq + p / 16], slot p % 16.  bf16 only.

@@ -106,6 +106,10 @@ def load_library():
     lib.st_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.st_attn_prefill_ids.restype = i32
     lib.st_attn_prefill_ids.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp]
+    lib.st_prefill_bwd_workspace_bytes.restype = sz
+    lib.st_prefill_bwd_workspace_bytes.argtypes = [vp, i32]
+    lib.st_attn_prefill_bwd.restype = i32
+    lib.st_attn_prefill_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, sz, vp]
     lib.st_kv_append.restype = i32
     lib.st_kv_append.argtypes = [C.POINTER(_DualCacheStruct), i32, vp, vp, vp, i32, i32, i32, vp]
     lib.st_kv_append_rope.restype = i32
@@ -313,6 +317,24 @@ def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, workspace=None
     _check(lib.st_attn_prefill(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), plan.handle, hq, hkv, d, float(scale),
                                _dtype_code(q), _ptr(workspace), ws_bytes, _stream(stream)))
     return out
+
+
+def st_attn_prefill_bwd(d_out, q, k, v, out, lse, plan, scale=0.0, workspace=None, stream=None):
+    """Gradients (dq, dk, dv) of st_attn_prefill; `out` and `lse` are the forward's results."""
+    lib = load_library()
+    for t in (d_out, q, k, v, out):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == q.dtype and t.dim() == 3
+    assert lse.dtype == torch.float32 and lse.is_contiguous()
+    n, hq, d = q.shape
+    hkv = k.shape[1]
+    assert d_out.shape == q.shape == out.shape and k.shape == v.shape and tuple(lse.shape) == (n, hq)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    if workspace is None:
+        workspace = torch.empty(max(256, int(lib.st_prefill_bwd_workspace_bytes(plan.handle, hq))), dtype=torch.uint8, device=q.device)
+    _check(lib.st_attn_prefill_bwd(_ptr(dq), _ptr(dk), _ptr(dv), _ptr(d_out), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
+                                   plan.handle, hq, hkv, d, float(scale), _dtype_code(q), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)))
+    return dq, dk, dv
 
 
 def st_attn_prefill_ids(q, k, v, segment_ids, stream_ids, positions, cu_seqlens, scale=0.0, out=None, lse=None, stream=None):

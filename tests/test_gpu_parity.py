@@ -232,6 +232,61 @@ def test_prefill_mfma_agrees_with_plain_kernel(st):
     assert (o_b.float() - o_f).abs().max().item() <= 2e-2
 
 
+# ------------------------------------------------------------- backward --
+def _run_prefill_bwd(st, cfg, tol_scale=1.0):
+    """Forward then backward through the library; gradients against the oracle's, element by element."""
+    q, k, v = cfg.tensors()
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 77))
+    g = W.normal(rng, q.shape, cfg.dtype)
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv, tg = (to_dev(x, cfg.dtype) for x in (q, k, v, g))
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    lse = torch.empty((cfg.n_tokens, cfg.n_q_heads), dtype=torch.float32, device=DEV)
+    out = st.st_attn_prefill(tq, tk, tv, plan, lse=lse)
+    dq, dk, dv = st.st_attn_prefill_bwd(tg, tq, tk, tv, out, lse, plan)
+    torch.cuda.synchronize()
+    rq, rk, rv = O.attention_varlen_backward(q, k, v, g, cfg.stream_ids, cfg.segment_ids, cfg.positions, cfg.cu_seqlens)
+    # fp32: rounding of the sums only.  bf16: the forward's out / lse carry bf16 / MFMA rounding (2e-2 on out), and
+    # the gradients are rounded to bf16; a gradient sums up to a few hundred terms of that accuracy.
+    tol = (2e-4 if cfg.dtype == "f32" else 6e-2) * tol_scale
+    for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        err = np.abs(to_f64(got) - ref).max()
+        assert err <= tol * max(1.0, np.abs(ref).max()), (name, err, np.abs(ref).max())
+    return dq, dk, dv
+
+
+def test_prefill_bwd_config1_fp32(st):
+    _run_prefill_bwd(st, W.config1())
+
+
+@pytest.mark.parametrize("seed,d,dtype,hq,hkv", [(601, 64, "f32", 4, 2), (602, 128, "f32", 2, 1), (603, 128, "bf16", 4, 2),
+                                                  (604, 64, "bf16", 4, 4)])
+def test_prefill_bwd_random_ragged(st, seed, d, dtype, hq, hkv):
+    _run_prefill_bwd(st, W.random_prefill(seed, 3, 8, (0, 90), (0, 120), hq, hkv, d, dtype))
+
+
+def test_prefill_bwd_edge_structures(st):
+    lists = [(np.array([5, 130]), np.array([0, 0])), (np.array([0]), np.array([200])), (np.array([], int), np.array([], int)),
+             (np.array([1]), np.array([1])), (np.array([64, 64]), np.array([128, 1]))]
+    _run_prefill_bwd(st, W._assemble("edges", "f32", 2, 1, 64, lists, "interleaved", 7))
+    _run_prefill_bwd(st, W._assemble("edges", "f32", 2, 2, 128, lists, "grouped", 8))
+
+
+def test_prefill_bwd_is_deterministic_and_checks_arguments(st):
+    cfg = W.random_prefill(605, 2, 6, (5, 60), (5, 70), 4, 2, 128, "bf16")
+    a = _run_prefill_bwd(st, cfg)
+    b = _run_prefill_bwd(st, cfg)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv = (to_dev(x, "bf16") for x in (q, k, v))
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    lse = torch.zeros((cfg.n_tokens, 4), dtype=torch.float32, device=DEV)
+    with pytest.raises(st.StError) as e:
+        st.st_attn_prefill_bwd(tq, tq, tk, tv, tq, lse, plan, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.status == 4
+
+
 # ------------------------------------------------------- append / decode --
 def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3), rope_theta=None):
     """Fill both caches through st_kv_append in uneven chunks; returns caches and the oracle's contiguous copies.
