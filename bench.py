@@ -254,12 +254,17 @@ def bench_prefill_backward(st, torch, W, reps):
     st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    st.st_profile_read(st.ST_PROF_BWD_DQ); st.st_profile_read(st.ST_PROF_BWD_DKV)
+    st.st_profile_enable(True)
     e0.record()
     for _ in range(reps):
         st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
     e1.record(); torch.cuda.synchronize()
+    st.st_profile_enable(False)
+    dq_ms, _ = st.st_profile_read(st.ST_PROF_BWD_DQ)
+    dkv_ms, _ = st.st_profile_read(st.ST_PROF_BWD_DKV)
     plan.destroy()
-    return {"ms": e0.elapsed_time(e1) / reps, "flops": 2.5 * flops_fwd}
+    return {"ms": e0.elapsed_time(e1) / reps, "flops": 2.5 * flops_fwd, "dq_ms": dq_ms, "dkv_ms": dkv_ms, "flops_fwd": flops_fwd}
 
 
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
@@ -498,14 +503,22 @@ def main():
             "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
                     "each of which streams the cache again"}
     if args.backward:
-        bw = bench_prefill_backward(st, torch, W, 3)
+        bw = bench_prefill_backward(st, torch, W, 10)
         tf = bw["flops"] / (bw["ms"] * 1e-3) / 1e12
+        tf_dq = 1.5 * bw["flops_fwd"] / (bw["dq_ms"] * 1e-3) / 1e12
+        tf_dkv = 2.0 * bw["flops_fwd"] / (bw["dkv_ms"] * 1e-3) / 1e12
         line["prefill_backward"] = {
-            "workload": "configs[1], gradients dq / dk / dv of the attention stage (plain one-thread-per-row kernels, fp32 arithmetic)",
-            "ms": round(bw["ms"], 3), "algorithmic_flops": bw["flops"],
-            "roofline": {"kernel": "bwd_dq_kernel + bwd_dkv_kernel x 2", "bound": "alu", "achieved": round(tf, 2), "peak": 157.3,
-                         "unit": "TFLOP/s", "frac": round(tf / 157.3, 4), "traffic": None,
-                         "note": "10 D flop per visible (query, key, head) triple; the kernels recompute the scores three times"}}
+            "workload": "configs[1], gradients dq / dk / dv of the attention stage, bf16 (tile gathering, row statistics and "
+                        "both matrix-core kernels)",
+            "ms": round(bw["ms"], 3), "algorithmic_flops": bw["flops"], "tflops": round(tf, 1),
+            "kernels": {"bwd_dq_mfma_kernel<128>": {"avg_ms": round(bw["dq_ms"], 4), "executed_tflops": round(tf_dq, 1)},
+                        "bwd_dkv_mfma_kernel<128>": {"avg_ms": round(bw["dkv_ms"], 4), "executed_tflops": round(tf_dkv, 1)}},
+            "roofline": {"kernel": "bwd_dq_mfma_kernel<128> + bwd_dkv_mfma_kernel<128>", "bound": "mfma",
+                         "achieved": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12, 1), "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                         "traffic": None,
+                         "note": "algorithmic = 5 products of 2 D flop per visible (query, key, head) triple (2.5x the forward); the two "
+                                 "kernels execute 7 (scores and dP are recomputed on the key side); executed_tflops counts those"}}
     if args.stream_session:
         line["stream_session"] = bench_stream_session(st, torch, W, args.stream_time_scale)
     if args.long_prefill:

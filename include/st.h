@@ -70,10 +70,11 @@ enum { ST_PREFILL_AUTO = 0, ST_PREFILL_ONE_HEAD = 1, ST_PREFILL_TWO_HEADS = 2 };
 int32_t st_prefill_variant_set(int32_t variant);
 
 /* Optional kernel timing for benchmarks.  While enabled, st_attn_prefill brackets its attention
- * kernel (ST_PROF_PREFILL_ATTN) and st_attn_decode_dual its split kernel (ST_PROF_DECODE_SPLIT)
+ * kernel (ST_PROF_PREFILL_ATTN), st_attn_decode_dual its split kernel (ST_PROF_DECODE_SPLIT) and
+ * the bf16 st_attn_prefill_bwd its two attention kernels (ST_PROF_BWD_DQ, ST_PROF_BWD_DKV)
  * with HIP events on the launch stream.  st_profile_read WAITS for the recorded launches, returns
  * their mean duration in milliseconds and their number in host variables, and forgets them. */
-enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1 };
+enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1, ST_PROF_BWD_DQ = 2, ST_PROF_BWD_DKV = 3 };
 void st_profile_enable(int32_t on);
 st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
 
@@ -207,12 +208,16 @@ st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* 
  *   lse          : fp32 [N, n_q_heads]         the forward's log-sum-exp (natural log)
  *   dq           : [N, n_q_heads,  head_dim]   (written)
  *   dk, dv       : [N, n_kv_heads, head_dim]   (written; summed over the query heads of a KV group)
- * all of dtype dt (fp32 arithmetic inside), same plan as the forward.  Deterministic (no atomics).
- * This is the plain one-thread-per-row path, not tuned.
- * workspace: at least st_prefill_bwd_workspace_bytes(plan, n_q_heads) bytes, 256-byte aligned.
- * Errors as for st_attn_prefill.
+ * all of dtype dt, same plan as the forward.  Deterministic (no atomics).
+ * ST_BF16: products on the matrix cores (bf16 operands -- P and dS are rounded to bf16 before the
+ * second products, as the forward rounds P -- fp32 accumulation); every operand is first gathered
+ * into 64-row tiles in the workspace, which therefore holds about 2.2x the bytes of q, k, v, d_out.
+ * ST_F32: a plain one-thread-per-row path in fp32, not tuned.
+ * workspace: at least st_prefill_bwd_workspace_bytes(plan, n_q_heads, n_kv_heads, head_dim, dt)
+ * bytes, 256-byte aligned.  Errors as for st_attn_prefill.
  * ---------------------------------------------------------------------- */
-size_t st_prefill_bwd_workspace_bytes(const st_plan* plan, int32_t n_q_heads);
+size_t st_prefill_bwd_workspace_bytes(const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads,
+                                      int32_t head_dim, st_dtype dt);
 
 st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const void* d_out, const void* q,
                               const void* k, const void* v, const void* out, const float* lse,

@@ -107,7 +107,7 @@ def load_library():
     lib.st_attn_prefill_ids.restype = i32
     lib.st_attn_prefill_ids.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp]
     lib.st_prefill_bwd_workspace_bytes.restype = sz
-    lib.st_prefill_bwd_workspace_bytes.argtypes = [vp, i32]
+    lib.st_prefill_bwd_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
     lib.st_attn_prefill_bwd.restype = i32
     lib.st_attn_prefill_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, sz, vp]
     lib.st_kv_append.restype = i32
@@ -174,7 +174,7 @@ def st_last_error():
     return load_library().st_last_error().decode()
 
 
-ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT = 0, 1
+ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT, ST_PROF_BWD_DQ, ST_PROF_BWD_DKV = 0, 1, 2, 3
 
 
 ST_PREFILL_AUTO, ST_PREFILL_ONE_HEAD, ST_PREFILL_TWO_HEADS = 0, 1, 2
@@ -330,7 +330,7 @@ def st_attn_prefill_bwd(d_out, q, k, v, out, lse, plan, scale=0.0, workspace=Non
     assert d_out.shape == q.shape == out.shape and k.shape == v.shape and tuple(lse.shape) == (n, hq)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     if workspace is None:
-        workspace = torch.empty(max(256, int(lib.st_prefill_bwd_workspace_bytes(plan.handle, hq))), dtype=torch.uint8, device=q.device)
+        workspace = torch.empty(max(256, int(lib.st_prefill_bwd_workspace_bytes(plan.handle, hq, hkv, d, _dtype_code(q)))), dtype=torch.uint8, device=q.device)
     _check(lib.st_attn_prefill_bwd(_ptr(dq), _ptr(dk), _ptr(dv), _ptr(d_out), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                    plan.handle, hq, hkv, d, float(scale), _dtype_code(q), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)))

@@ -39,7 +39,7 @@ inline st_status fail(st_status code, const char* fmt, ...) {
 
 // Optional kernel timing (st_profile_enable): HIP events recorded on the launch stream right
 // before and after one kernel, read back by st_profile_read.
-enum { kProfPrefillAttn = 0, kProfDecodeSplit = 1, kProfCount = 2 };
+enum { kProfPrefillAttn = 0, kProfDecodeSplit = 1, kProfBwdDq = 2, kProfBwdDkv = 3, kProfCount = 4 };
 bool prof_enabled();
 void prof_begin(int which, hipStream_t stream);
 void prof_end(int which, hipStream_t stream);

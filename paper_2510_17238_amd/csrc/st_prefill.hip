@@ -10,7 +10,7 @@
 // index with a per-row limit, tiles past `total` are never read.
 //
 // Kernels:
-//   prefill_pack_kernel   bf16, O(N) bytes: gathers the K rows and the TRANSPOSED V rows of every
+//   tile_pack_kernel   bf16, O(N) bytes: gathers the K rows and the TRANSPOSED V rows of every
 //                         64-row key tile (stream-compact order) into contiguous 16 KB blocks, so
 //                         that the attention kernel streams tiles with plain linear loads and needs
 //                         no per-row token lookup and no transpose in its inner loop.
@@ -29,12 +29,10 @@
 #include <atomic>
 #include <type_traits>
 
-#include "st_plan.h"
+#include "st_tiles.h"
 
 namespace st {
 
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kLazyMax = 8.f;                   // exponent units a tile maximum may exceed the running one
 
 struct ItemGeom {
@@ -142,93 +140,6 @@ __global__ __launch_bounds__(kTileM) void prefill_simple_kernel(T* __restrict__ 
 #pragma unroll
     for (int d = 0; d < D; ++d) store_f32(op + d, o[d] * inv);
     if (lse) lse[int64_t(tok_q) * n_q_heads + hq] = m_run + logf(l_run);
-}
-
-// --------------------------------------------------------------------------
-// MFMA kernel (bf16).
-// --------------------------------------------------------------------------
-// One wave-wide asynchronous copy global -> LDS: lane l's 16 bytes at `g` land at LDS byte offset
-// lds_off + 16 l (lds_off must be wave-uniform).  Completion is counted by vmcnt like any load.
-__device__ __forceinline__ void async_copy16(const void* g, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_off) : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// LDS tiles of the MFMA kernel: no padding; inside every row the 16-byte chunks are stored at
-// position chunk ^ key(row).  The LDS has 64 four-byte banks, so a 16-byte operand read serves 16
-// lanes (16 consecutive rows) per cycle, and the key must send those 16 rows to 16 different
-// 16-byte columns of the 256-byte bank line: key = row % 16 for 256-byte rows, (row / 2) % 8 for
-// 128-byte rows (two rows per bank line).  The packed global tiles already have this arrangement,
-// so a tile travels global -> LDS as a plain linear copy.
-template <int ROW_BYTES>
-__device__ __forceinline__ int swizzle_key(int row) { return ROW_BYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
-
-// swap bits 2 and 3: the row order in which K is parked in LDS, so that after the
-// first MFMA each half-wave holds 8 CONSECUTIVE keys per 16-key step
-__device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
-
-template <int D>
-__global__ __launch_bounds__(256) void prefill_pack_kernel(uint16_t* __restrict__ kc, uint16_t* __restrict__ vc,
-                                                           const uint16_t* __restrict__ k,
-                                                           const uint16_t* __restrict__ v, PlanView pv,
-                                                           int n_kv_heads) {
-    constexpr int KCH = D / 8;
-    constexpr int K_PER_THREAD = kTileN * KCH / 256;
-    constexpr int VQ = D / 4;
-    const int tile = blockIdx.x / n_kv_heads;
-    const int h = blockIdx.x % n_kv_heads;
-    const int b = find_seq(pv.pack_base, pv.batch, tile);
-    const int lt = tile - pv.pack_base[b];
-    const int t0 = pv.cu[b], S = pv.n_src[b], R = pv.cu[b + 1] - t0 - S;
-    const int ts = (S + kTileN - 1) / kTileN, tr = (R + kTileN - 1) / kTileN;
-    if (lt >= ts + tr) return;                      // spare tile of this sequence: never read
-    const bool src = lt < ts;
-    const int kt = src ? lt : lt - ts;
-    const int base = t0 + (src ? 0 : S) + kt * kTileN;
-    const int valid = min(kTileN, (src ? S : R) - kt * kTileN);
-    const int tid = threadIdx.x;
-    const uint32_t row_stride = uint32_t(n_kv_heads) * D;
-    uint16_t* kdst = kc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
-    uint16_t* vdst = vc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
-    // K rows, parked in the row order the first MFMA wants (bits 2 and 3 of the row swapped) and with
-    // the chunk swizzle of the LDS tile; rows past the end of the stream are zero (they are masked,
-    // but must be finite)
-#pragma unroll
-    for (int u = 0; u < K_PER_THREAD; ++u) {
-        const int c = tid + 256 * u;
-        const int row = c / KCH, ch = c % KCH;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (row < valid) val = *reinterpret_cast<const u32x4*>(k + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + ch * 8));
-        const int lr = swap23(row);                                    // row position in the tile
-        *reinterpret_cast<u32x4*>(kdst + lr * D + (ch ^ swizzle_key<2 * D>(lr)) * 8) = val;
-    }
-    // V: 8 keys x 4 d per thread, transposed in registers to 4 d x 8 keys
-    const int kvb = tid & 7, dq = tid >> 3;
-    if (dq < VQ) {
-        u32x2 vreg[8];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int row = kvb * 8 + r;
-            vreg[r] = u32x2{0u, 0u};
-            if (row < valid) vreg[r] = *reinterpret_cast<const u32x2*>(v + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + dq * 4));
-        }
-#pragma unroll
-        for (int w = 0; w < 2; ++w) {
-            u32x4 even, odd;
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr) {
-                const uint32_t a = vreg[2 * pr][w], bb = vreg[2 * pr + 1][w];
-                even[pr] = __builtin_amdgcn_perm(bb, a, 0x05040100u);   // low halves
-                odd[pr] = __builtin_amdgcn_perm(bb, a, 0x07060302u);    // high halves
-            }
-            const int d0 = dq * 4 + 2 * w;
-            *reinterpret_cast<u32x4*>(vdst + d0 * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0)) * 8) = even;
-            *reinterpret_cast<u32x4*>(vdst + (d0 + 1) * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0 + 1)) * 8) = odd;
-        }
-    }
 }
 
 // --------------------------------------------------------------------------
@@ -708,7 +619,7 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
     const bool pair = ((n_q_heads / n_kv_heads) % 2 == 0) && (variant == ST_PREFILL_TWO_HEADS || (variant == ST_PREFILL_AUTO && blocks / 2 >= 2048));
     auto launch = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
-        hipLaunchKernelGGL((prefill_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
                            (const uint16_t*)v, pv, n_kv_heads);
         auto run = [&](auto nh_tag) -> st_status {
             constexpr int NH = decltype(nh_tag)::value;
@@ -727,7 +638,7 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
     };
     const st_status lr = head_dim == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});
     if (lr != ST_OK) return lr;
-    ST_LAUNCH_CHECK("prefill_pack_kernel / prefill_mfma_pipe_kernel");
+    ST_LAUNCH_CHECK("tile_pack_kernel / prefill_mfma_pipe_kernel");
     return ST_OK;
 }
 

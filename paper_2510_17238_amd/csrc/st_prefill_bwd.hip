@@ -14,7 +14,9 @@
 //   bwd_dkv_kernel   thread = key row of one KV head, all query heads of its group: dV (pass 0) or dK (pass 1)
 #include <math.h>
 
-#include "st_plan.h"
+#include <type_traits>
+
+#include "st_tiles.h"
 
 namespace st {
 
@@ -169,13 +171,459 @@ __global__ __launch_bounds__(kTileM) void bwd_dkv_kernel(T* __restrict__ dkv, co
     for (int d = 0; d < D; ++d) stf(dkv + koff + d, acc[d]);
 }
 
+
+// --------------------------------------------------------------------------
+// MFMA path (bf16).
+// --------------------------------------------------------------------------
+// dQ: the forward's loop over the key tiles of a query tile (same work items, same transposed products, a lane
+// owns one query row), with three products per key tile:
+//   S^T  = K  Q^T     (K row tile from LDS, Q^T in registers)        -> P^T = exp2(S^T scale - lse)
+//   dP^T = V  dO^T    (V row tile from LDS, dO^T in registers)       -> dS^T = P^T (dP^T - delta)
+//   dQ^T += K^T dS^T  (K^T tile from LDS, dS^T from the accumulators, rounded to bf16)
+// Two buffers per tile kind (96 KB), one barrier per key tile, copies one tile ahead.
+template <int D>
+struct BwdDqSmem {
+    uint16_t k[2][kTileN * D];        // K rows
+    uint16_t v[2][kTileN * D];        // V rows
+    uint16_t kt[2][D * kTileN];       // K^T
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restrict__ dq, const uint16_t* __restrict__ d_out,
+                                                             const uint16_t* __restrict__ q, const uint16_t* __restrict__ krows,
+                                                             const uint16_t* __restrict__ vrows, const uint16_t* __restrict__ ktr,
+                                                             const float* __restrict__ lse, const float* __restrict__ delta,
+                                                             PlanView pv, int n_q_heads, int n_kv_heads, float scale) {
+    constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
+    constexpr int TILE = kTileN * D;
+    constexpr int NL = TILE * 2 / 1024 / 4;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    BwdDqSmem<D>& sm = *reinterpret_cast<BwdDqSmem<D>*>(smem_raw);
+
+    const int rank = blockIdx.x / n_q_heads;
+    const int hh = blockIdx.x % n_q_heads;
+    const int group = n_q_heads / n_kv_heads;
+    const int hk = hh % n_kv_heads;
+    const int hq = hk * group + hh / n_kv_heads;
+    const WorkItem it = pv.sorted[rank];
+    if (it.n_rows == 0) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hg = lane >> 5;
+    const int n_tiles = it.a_total + it.b_total;
+
+    const size_t head_off = size_t(hk) * pv.pack_tiles * TILE + (wave * NL) * 512 + lane * 8;
+    auto tile_of = [&](int ti) {
+        ti = min(ti, n_tiles - 1);
+        return ti < it.a_total ? it.tile_a0 + ti : it.tile_b0 + (ti - it.a_total);
+    };
+    const uint32_t wave_off = uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
+    const uint32_t lds_k = uint32_t(uintptr_t(&sm.k[0][0])) + wave_off, lds_v = uint32_t(uintptr_t(&sm.v[0][0])) + wave_off,
+                   lds_kt = uint32_t(uintptr_t(&sm.kt[0][0])) + wave_off;
+    auto issue = [&](int ti, int buf) {
+        const size_t off = head_off + size_t(tile_of(ti)) * TILE;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(krows + off + u * 512, lds_k + buf * (TILE * 2) + u * 1024);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(vrows + off + u * 512, lds_v + buf * (TILE * 2) + u * 1024);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(ktr + off + u * 512, lds_kt + buf * (TILE * 2) + u * 1024);
+    };
+    issue(0, 0);
+
+    const int row_in_tile = wave * 32 + n;
+    const bool active = row_in_tile < it.n_rows;
+    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
+    const int tok_q = pv.perm[it.a_base + my_row];
+    const int my_vis = pv.vis[it.a_base + my_row];
+    const int64_t rowhead = int64_t(tok_q) * n_q_heads + hq;
+    const float lse2 = lse[rowhead] * kLog2e, my_delta = delta[rowhead];
+    const float scale_log2 = scale * kLog2e;
+
+    bf16x8 qf[KS], dof[KS];
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        qf[j] = *reinterpret_cast<const bf16x8*>(q + rowhead * D + 8 * hg + 16 * j);
+        dof[j] = *reinterpret_cast<const bf16x8*>(d_out + rowhead * D + 8 * hg + 16 * j);
+    }
+    f32x16 acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+
+    int koff[KS], voff[4];
+    {
+        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
+    }
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        const int buf = ti & 1;
+        wait_vmcnt<0>();                 // tile ti has landed; everybody is done with tile ti - 1
+        __syncthreads();
+        if (ti + 1 < n_tiles) issue(ti + 1, buf ^ 1);
+
+        const bool in_a = ti < it.a_total;
+        const int kt = in_a ? ti : ti - it.a_total;
+        const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? it.n_stream : it.n_src);
+        const int limit = in_a ? my_row + 1 : my_vis;
+
+        f32x16 s_acc[SB], dp_acc[SB];
+        const uint16_t* kb = &sm.k[buf][0];
+        const uint16_t* vb = &sm.v[buf][0];
+#pragma unroll
+        for (int f = 0; f < SB * KS; ++f) {
+            const int sb = f % SB, j = f / SB;
+            const bf16x8 ak = *reinterpret_cast<const bf16x8*>(kb + 32 * sb * D + koff[j]);
+            const bf16x8 av = *reinterpret_cast<const bf16x8*>(vb + 32 * sb * D + koff[j]);
+            s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
+            dp_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[j], j == 0 ? zero16 : dp_acc[sb], 0, 0, 0);
+        }
+        // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
+        bf16x8 dsb[SB][2];
+        const int c0 = kt * kTileN + 8 * hg;
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float p = __builtin_amdgcn_exp2f(fmaf(s_acc[sb][i], scale_log2, -lse2));
+                if (partial) {
+                    const int col = c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
+                    p = col < limit ? p : 0.f;
+                }
+                dsb[sb][i >> 3][i & 7] = (__bf16)(p * (dp_acc[sb][i] - my_delta));
+            }
+        const uint16_t* tb = &sm.kt[buf][0];
+#pragma unroll
+        for (int f = 0; f < DB * SB * 2; ++f) {
+            const int db = f % DB, st = f / DB;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(tb + 32 * db * kTileN + voff[st]);
+            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[st >> 1][st & 1], acc[db], 0, 0, 0);
+        }
+    }
+    wait_vmcnt<0>();
+    if (!active) return;
+    uint16_t* op = dq + rowhead * D;
+    // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 o4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o4[c] = (__bf16)(acc[db][4 * q4 + c] * scale);
+            *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * hg) = o4;
+        }
+}
+
+
+// Row statistics of the backward in tile order: for every 64-row tile of a stream and every query head one
+// 1 KB block of 256 floats -- [0, 64) lse in base-2 units (+inf for rows past the end of the stream: their
+// probabilities become 0), [64, 128) delta, [128, 192) the visible-source count of the row (as int bits) --
+// so that the key-side kernel fetches them with ONE asynchronous copy per tile.  delta is also written in
+// token order for the query-side kernel.
+template <int D>
+__global__ __launch_bounds__(64) void bwd_rowstats_kernel(float* __restrict__ stats, float* __restrict__ delta_tok,
+                                                         const uint16_t* __restrict__ d_out, const uint16_t* __restrict__ out,
+                                                         const float* __restrict__ lse, PlanView pv, int n_q_heads) {
+    const int tile = blockIdx.x / n_q_heads;
+    const int h = blockIdx.x % n_q_heads;
+    const int b = find_seq(pv.pack_base, pv.batch, tile);
+    const int lt = tile - pv.pack_base[b];
+    const int t0 = pv.cu[b], S = pv.n_src[b], R = pv.cu[b + 1] - t0 - S;
+    const int ts = (S + kTileN - 1) / kTileN, tr = (R + kTileN - 1) / kTileN;
+    if (lt >= ts + tr) return;
+    const bool src = lt < ts;
+    const int kt = src ? lt : lt - ts;
+    const int base = t0 + (src ? 0 : S) + kt * kTileN;
+    const int valid = min(kTileN, (src ? S : R) - kt * kTileN);
+    const int r = threadIdx.x;
+    float l2 = INFINITY, dl = 0.f;
+    int vs = 0;
+    if (r < valid) {
+        const int tok = pv.perm[base + r];
+        const int64_t rh = int64_t(tok) * n_q_heads + h;
+        const uint16_t* a = d_out + rh * D;
+        const uint16_t* o = out + rh * D;
+#pragma unroll
+        for (int c = 0; c < D / 8; ++c) {
+            const bf16x8 x = *reinterpret_cast<const bf16x8*>(a + 8 * c), y = *reinterpret_cast<const bf16x8*>(o + 8 * c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dl = fmaf(float(x[e]), float(y[e]), dl);
+        }
+        l2 = lse[rh] * kLog2e;
+        vs = pv.vis[base + r];
+        delta_tok[rh] = dl;
+    }
+    float* blk = stats + (size_t(h) * pv.pack_tiles + tile) * 256;
+    blk[r] = l2;
+    blk[64 + r] = dl;
+    blk[128 + r] = __int_as_float(vs);
+    blk[192 + r] = 0.f;
+}
+
+// dK, dV: one workgroup per (128 keys of one stream of one sequence, KV head) -- the forward's work items read
+// as KEYS -- 4 waves x 32 keys, a lane owns one key.  It loops over the 64-row query tiles that can see its keys
+// (own stream: tiles from the one holding its first key on; for source keys also the reasoning tiles from the
+// first row whose visible-source count exceeds its first key on), for every query head of its group:
+//   S   = Q  K^T    (Q row tile from LDS, K^T in registers)      -> P  = exp2(S scale - lse_row)
+//   dP  = dO V^T    (dO row tile from LDS, V^T in registers)     -> dS = P (dP - delta_row)
+//   dV^T += dO^T P  (dO^T tile from LDS, P from the accumulators, rounded to bf16)
+//   dK^T += Q^T dS  (Q^T tile from LDS, dS from the accumulators)
+// Rows run along the accumulator registers here, so lse / delta / visible count of the rows come from the
+// tile's 1 KB statistics block in LDS.  Two buffers per tile kind (130 KB), one barrier per query tile.
+template <int D>
+struct BwdDkvSmem {
+    uint16_t qr[2][kTileN * D];       // Q rows
+    uint16_t dor[2][kTileN * D];      // dO rows
+    uint16_t qt[2][D * kTileN];       // Q^T
+    uint16_t dot[2][D * kTileN];      // dO^T
+    float stats[2][256];
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
+                                                              const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                              const uint16_t* __restrict__ qrows, const uint16_t* __restrict__ qtr,
+                                                              const uint16_t* __restrict__ dorows, const uint16_t* __restrict__ dotr,
+                                                              const float* __restrict__ stats, PlanView pv, int n_q_heads,
+                                                              int n_kv_heads, float scale) {
+    constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
+    constexpr int TILE = kTileN * D;
+    constexpr int NL = TILE * 2 / 1024 / 4;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    BwdDkvSmem<D>& sm = *reinterpret_cast<BwdDkvSmem<D>*>(smem_raw);
+
+    const int rank = blockIdx.x / n_kv_heads;
+    const int hk = blockIdx.x % n_kv_heads;
+    const int group = n_q_heads / n_kv_heads;
+    const WorkItem it = pv.sorted[rank];
+    if (it.n_rows == 0) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hg = lane >> 5;
+    const bool key_is_src = it.kind == ST_SOURCE;
+    const int S = it.n_src;
+    const int n_rsn = key_is_src ? (pv.cu[it.seq + 1] - pv.cu[it.seq] - S) : it.n_stream;
+
+    // query tiles that can see keys >= row0: run A over the own stream, run B (source keys) over the reasoning stream
+    const int a_first = it.row0 / kTileN, a_end = (it.n_stream + kTileN - 1) / kTileN;
+    int b_first = 0, b_end = 0;
+    if (key_is_src) {
+        int lo = 0, hi = n_rsn;                                 // first reasoning row whose visible count exceeds row0
+        const int32_t* vr = pv.vis + it.b_base + S;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (vr[mid] > it.row0) hi = mid; else lo = mid + 1;
+        }
+        b_first = lo / kTileN;
+        b_end = (n_rsn + kTileN - 1) / kTileN;
+        if (lo >= n_rsn) b_first = b_end;
+    }
+    const int n_a = a_end - a_first, n_b = b_end - b_first;
+    const int n_iter = (n_a + n_b) * group;
+    const int tile_own0 = it.tile_a0;                           // packed tile of row 0 of the own stream
+    const int tile_rsn0 = it.tile_b0 + (S + kTileN - 1) / kTileN;   // ... of the reasoning stream (source keys)
+
+    const int key_in_tile = wave * 32 + n;
+    const bool active = key_in_tile < it.n_rows;
+    const int my_key = it.row0 + min(key_in_tile, it.n_rows - 1);
+    const int tok_k = pv.perm[it.a_base + my_key];
+    const int64_t keyhead = int64_t(tok_k) * n_kv_heads + hk;
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        kf[j] = *reinterpret_cast<const bf16x8*>(k + keyhead * D + 8 * hg + 16 * j);
+        vf[j] = *reinterpret_cast<const bf16x8*>(v + keyhead * D + 8 * hg + 16 * j);
+    }
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {                              // landed before the loop (it counts its own copies)
+        u32x4 t = __builtin_bit_cast(u32x4, kf[j]), u = __builtin_bit_cast(u32x4, vf[j]);
+        asm volatile("" : "+v"(t), "+v"(u));
+        kf[j] = __builtin_bit_cast(bf16x8, t);
+        vf[j] = __builtin_bit_cast(bf16x8, u);
+    }
+
+    // iteration -> (query tile, head): heads fastest, so that a tile's row statistics change slowest
+    struct Iter { int tile; int hq; int row0; bool rs; };
+    auto iter_of = [&](int x) {
+        x = min(x, n_iter - 1);
+        const int t = x / group, g = x % group;
+        Iter r;
+        r.hq = hk * group + g;
+        if (t < n_a) {
+            r.tile = tile_own0 + a_first + t;
+            r.row0 = (a_first + t) * kTileN;
+            r.rs = false;
+        } else {
+            r.tile = tile_rsn0 + b_first + (t - n_a);
+            r.row0 = (b_first + (t - n_a)) * kTileN;
+            r.rs = true;
+        }
+        return r;
+    };
+    const uint32_t wave_off = uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
+    const uint32_t lds_qr = uint32_t(uintptr_t(&sm.qr[0][0])) + wave_off, lds_dor = uint32_t(uintptr_t(&sm.dor[0][0])) + wave_off,
+                   lds_qt = uint32_t(uintptr_t(&sm.qt[0][0])) + wave_off, lds_dot = uint32_t(uintptr_t(&sm.dot[0][0])) + wave_off,
+                   lds_st = uint32_t(uintptr_t(&sm.stats[0][0]));
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto issue = [&](int x, int buf) {
+        const Iter r = iter_of(x);
+        const size_t off = (size_t(r.hq) * pv.pack_tiles + r.tile) * TILE + (wave * NL) * 512 + lane * 8;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(qrows + off + u * 512, lds_qr + buf * (TILE * 2) + u * 1024);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(dorows + off + u * 512, lds_dor + buf * (TILE * 2) + u * 1024);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(qtr + off + u * 512, lds_qt + buf * (TILE * 2) + u * 1024);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(dotr + off + u * 512, lds_dot + buf * (TILE * 2) + u * 1024);
+        if (wave_u == 0) async_copy16(stats + (size_t(r.hq) * pv.pack_tiles + r.tile) * 256 + lane * 4, lds_st + buf * 1024);
+    };
+    if (n_iter > 0) issue(0, 0);
+
+    f32x16 dk_acc[DB], dv_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            dk_acc[db][i] = 0.f;
+            dv_acc[db][i] = 0.f;
+        }
+    int koff[KS], voff[4];
+    {
+        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
+    }
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const float scale_log2 = scale * kLog2e;
+
+    for (int x = 0; x < n_iter; ++x) {
+        const int buf = x & 1;
+        wait_vmcnt<0>();                 // the tiles of iteration x have landed; everybody is done with x - 1
+        __syncthreads();
+        if (x + 1 < n_iter) issue(x + 1, buf ^ 1);
+        const Iter cur = iter_of(x);
+
+        f32x16 s_acc[SB], dp_acc[SB];
+        const uint16_t* qb = &sm.qr[buf][0];
+        const uint16_t* ob = &sm.dor[buf][0];
+#pragma unroll
+        for (int f = 0; f < SB * KS; ++f) {
+            const int rb = f % SB, j = f / SB;
+            const bf16x8 aq = *reinterpret_cast<const bf16x8*>(qb + 32 * rb * D + koff[j]);
+            const bf16x8 ao = *reinterpret_cast<const bf16x8*>(ob + 32 * rb * D + koff[j]);
+            s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[j], j == 0 ? zero16 : s_acc[rb], 0, 0, 0);
+            dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao, vf[j], j == 0 ? zero16 : dp_acc[rb], 0, 0, 0);
+        }
+        // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key
+        bf16x8 pb[SB][2], dsb[SB][2];
+        const float* st = &sm.stats[buf][0];
+#pragma unroll
+        for (int rb = 0; rb < SB; ++rb)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int r0 = 32 * rb + 16 * half + 8 * hg;           // first of the 8 consecutive rows of these registers
+                float l2[8], dl[8];
+                int vs[8];
+#pragma unroll
+                for (int q4 = 0; q4 < 2; ++q4) {
+                    const f32x4 a = *reinterpret_cast<const f32x4*>(st + r0 + 4 * q4);
+                    const f32x4 b2 = *reinterpret_cast<const f32x4*>(st + 64 + r0 + 4 * q4);
+                    const f32x4 c2 = *reinterpret_cast<const f32x4*>(st + 128 + r0 + 4 * q4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        l2[4 * q4 + e] = a[e];
+                        dl[4 * q4 + e] = b2[e];
+                        vs[4 * q4 + e] = __float_as_int(c2[e]);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int i = 8 * half + e;
+                    const int row = cur.row0 + r0 + e;
+                    const bool seen = cur.rs ? vs[e] > my_key : row >= my_key;
+                    float p = __builtin_amdgcn_exp2f(fmaf(s_acc[rb][i], scale_log2, -l2[e]));
+                    p = seen ? p : 0.f;
+                    pb[rb][half][e] = (__bf16)p;
+                    dsb[rb][half][e] = (__bf16)(p * (dp_acc[rb][i] - dl[e]));
+                }
+            }
+        const uint16_t* tq = &sm.qt[buf][0];
+        const uint16_t* to = &sm.dot[buf][0];
+#pragma unroll
+        for (int f = 0; f < DB * SB * 2; ++f) {
+            const int db = f % DB, stp = f / DB;                 // rows 16 stp .. 16 stp + 15 of the tile
+            const bf16x8 ao = *reinterpret_cast<const bf16x8*>(to + 32 * db * kTileN + voff[stp]);
+            const bf16x8 aq = *reinterpret_cast<const bf16x8*>(tq + 32 * db * kTileN + voff[stp]);
+            dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao, pb[stp >> 1][stp & 1], dv_acc[db], 0, 0, 0);
+            dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, dsb[stp >> 1][stp & 1], dk_acc[db], 0, 0, 0);
+        }
+    }
+    wait_vmcnt<0>();
+    if (!active) return;
+    uint16_t* pk = dk + keyhead * D;
+    uint16_t* pvv = dv + keyhead * D;
+    // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 a4, b4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                a4[c] = (__bf16)(dk_acc[db][4 * q4 + c] * scale);
+                b4[c] = (__bf16)dv_acc[db][4 * q4 + c];
+            }
+            *reinterpret_cast<bf16x4*>(pk + 32 * db + 8 * q4 + 4 * hg) = a4;
+            *reinterpret_cast<bf16x4*>(pvv + 32 * db + 8 * q4 + 4 * hg) = b4;
+        }
+}
+
 }  // namespace st
 
 using namespace st;
 
-extern "C" size_t st_prefill_bwd_workspace_bytes(const st_plan* plan, int32_t n_q_heads) {
-    if (!plan || n_q_heads <= 0) return 0;
-    return ((size_t(plan->n_tokens) * size_t(n_q_heads) * sizeof(float) + 255) & ~size_t(255)) + 256;
+namespace {
+inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+// workspace of the bf16 path: delta (token order) | row statistics | K rows | K^T | V rows | Q rows | Q^T | dO rows | dO^T
+struct BwdLayout {
+    size_t delta, stats, krows, ktr, vrows, qrows, qtr, dorows, dotr, total;
+};
+BwdLayout bwd_layout(const st_plan* plan, int n_q_heads, int n_kv_heads, int head_dim, st_dtype dt) {
+    BwdLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += up256(bytes); return at; };
+    L.delta = take(size_t(plan->n_tokens) * size_t(n_q_heads) * sizeof(float));
+    if (dt == ST_BF16) {
+        const size_t tile = size_t(kTileN) * head_dim * sizeof(uint16_t);
+        const size_t kvt = size_t(n_kv_heads) * plan->pack_tiles * tile, qt = size_t(n_q_heads) * plan->pack_tiles * tile;
+        L.stats = take(size_t(n_q_heads) * plan->pack_tiles * 256 * sizeof(float));
+        L.krows = take(kvt);
+        L.ktr = take(kvt);
+        L.vrows = take(kvt);
+        L.qrows = take(qt);
+        L.qtr = take(qt);
+        L.dorows = take(qt);
+        L.dotr = take(qt);
+    }
+    L.total = off + 256;
+    return L;
+}
+}  // namespace
+
+extern "C" size_t st_prefill_bwd_workspace_bytes(const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                                 st_dtype dt) {
+    if (!plan || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0) return 0;
+    return bwd_layout(plan, n_q_heads, n_kv_heads, head_dim, dt).total;
 }
 
 extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const void* d_out, const void* q, const void* k,
@@ -191,7 +639,8 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
     if (plan->n_tokens == 0) return ST_OK;
     if (plan->n_tokens * int64_t(n_q_heads) * head_dim >= (int64_t(1) << 31))
         return fail(ST_ERR_SHAPE, "st_attn_prefill_bwd: n_tokens * n_q_heads * head_dim must stay below 2^31 elements");
-    const size_t need = st_prefill_bwd_workspace_bytes(plan, n_q_heads);
+    const BwdLayout L = bwd_layout(plan, n_q_heads, n_kv_heads, head_dim, dt);
+    const size_t need = L.total;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return fail(ST_ERR_INVALID_ARG, "st_attn_prefill_bwd: workspace must be non-null and 256-byte aligned");
     if (workspace_bytes < need) return fail(ST_ERR_CAPACITY, "st_attn_prefill_bwd: workspace has %zu bytes, needs %zu", workspace_bytes, need);
@@ -200,7 +649,7 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
     if (qblocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_prefill_bwd: grid too large");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const PlanView pv = plan->view();
-    float* delta = static_cast<float*>(workspace);
+    float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + L.delta);
     auto run = [&](auto ttag, auto dtag) -> st_status {
         using T = decltype(ttag);
         constexpr int HD = decltype(dtag)::value;
@@ -216,10 +665,41 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
                            (const T*)q, (const T*)k, (const T*)v, lse, pv, n_q_heads, n_kv_heads, scale);
         return ST_OK;
     };
+    // bf16: every operand gathered once into 64-row tiles (rows and transposed), then two MFMA kernels
+    auto run_mfma = [&](auto dtag) -> st_status {
+        constexpr int HD = decltype(dtag)::value;
+        unsigned char* w = static_cast<unsigned char*>(workspace);
+        auto at = [&](size_t o) { return reinterpret_cast<uint16_t*>(w + o); };
+        float* stats = reinterpret_cast<float*>(w + L.stats);
+        const unsigned kv_tiles = unsigned(plan->pack_tiles) * n_kv_heads, q_tiles = unsigned(plan->pack_tiles) * n_q_heads;
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(kv_tiles), dim3(256), 0, s, at(L.krows), at(L.ktr), (const uint16_t*)k,
+                           (const uint16_t*)k, pv, n_kv_heads);
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(kv_tiles), dim3(256), 0, s, at(L.vrows), (uint16_t*)nullptr, (const uint16_t*)v,
+                           (const uint16_t*)v, pv, n_kv_heads);
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.qrows), at(L.qtr), (const uint16_t*)q,
+                           (const uint16_t*)q, pv, n_q_heads);
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.dorows), at(L.dotr), (const uint16_t*)d_out,
+                           (const uint16_t*)d_out, pv, n_q_heads);
+        hipLaunchKernelGGL((bwd_rowstats_kernel<HD>), dim3(q_tiles), dim3(64), 0, s, stats, delta, (const uint16_t*)d_out,
+                           (const uint16_t*)out, lse, pv, n_q_heads);
+        const size_t smem_q = sizeof(BwdDqSmem<HD>), smem_k = sizeof(BwdDkvSmem<HD>);
+        ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dq_mfma_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem_q)));
+        ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dkv_mfma_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem_k)));
+        prof_begin(kProfBwdDq, s);
+        hipLaunchKernelGGL((bwd_dq_mfma_kernel<HD>), dim3((unsigned)qblocks), dim3(256), smem_q, s, (uint16_t*)dq, (const uint16_t*)d_out,
+                           (const uint16_t*)q, at(L.krows), at(L.vrows), at(L.ktr), lse, delta, pv, n_q_heads, n_kv_heads, scale);
+        prof_end(kProfBwdDq, s);
+        prof_begin(kProfBwdDkv, s);
+        hipLaunchKernelGGL((bwd_dkv_mfma_kernel<HD>), dim3((unsigned)kblocks), dim3(256), smem_k, s, (uint16_t*)dk, (uint16_t*)dv,
+                           (const uint16_t*)k, (const uint16_t*)v, at(L.qrows), at(L.qtr), at(L.dorows), at(L.dotr), stats, pv,
+                           n_q_heads, n_kv_heads, scale);
+        prof_end(kProfBwdDkv, s);
+        return ST_OK;
+    };
     st_status r;
     if (dt == ST_F32) r = head_dim == 64 ? run(float{}, std::integral_constant<int, 64>{}) : run(float{}, std::integral_constant<int, 128>{});
-    else r = head_dim == 64 ? run(uint16_t{}, std::integral_constant<int, 64>{}) : run(uint16_t{}, std::integral_constant<int, 128>{});
+    else r = head_dim == 64 ? run_mfma(std::integral_constant<int, 64>{}) : run_mfma(std::integral_constant<int, 128>{});
     if (r != ST_OK) return r;
-    ST_LAUNCH_CHECK("bwd_dq_kernel / bwd_dkv_kernel");
+    ST_LAUNCH_CHECK("st_attn_prefill_bwd kernels");
     return ST_OK;
 }

@@ -272,6 +272,38 @@ def test_prefill_bwd_edge_structures(st):
     _run_prefill_bwd(st, W._assemble("edges", "f32", 2, 2, 128, lists, "grouped", 8))
 
 
+def test_prefill_bwd_bf16_tiles(st):
+    """The matrix-core path over several 64-row tiles and 128-row items per stream, both head sizes, grouped heads,
+    the edge structures (empty streams, single tokens, exact tile multiples) and the small standard case."""
+    lists = [(np.array([5, 130]), np.array([0, 0])), (np.array([0]), np.array([200])), (np.array([], int), np.array([], int)),
+             (np.array([1]), np.array([1])), (np.array([64, 64]), np.array([128, 1]))]
+    _run_prefill_bwd(st, W._assemble("edges", "bf16", 4, 2, 128, lists, "interleaved", 7))
+    _run_prefill_bwd(st, W._assemble("edges", "bf16", 2, 2, 64, lists, "grouped", 8))
+    _run_prefill_bwd(st, W.random_prefill(611, 2, 5, (40, 160), (60, 200), 8, 2, 128, "bf16"))
+    _run_prefill_bwd(st, W.random_prefill(612, 2, 4, (100, 200), (30, 90), 2, 1, 64, "bf16"))
+    cfg = W.config1()
+    cfg.dtype = "bf16"
+    _run_prefill_bwd(st, cfg)
+
+
+def test_prefill_bwd_bf16_agrees_with_plain_kernels(st):
+    """bf16 inputs through the matrix-core backward vs the same values through the fp32 one-thread-per-row kernels."""
+    cfg = W.random_prefill(613, 2, 6, (30, 150), (30, 170), 4, 2, 128, "bf16")
+    q, k, v = cfg.tensors()
+    g = W.normal(np.random.Generator(np.random.PCG64(5)), q.shape, "bf16")
+    seg, strm, pos = ids_to_dev(cfg)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    grads = {}
+    for dt in ("bf16", "f32"):
+        tq, tk, tv, tg = (to_dev(x, dt) for x in (q, k, v, g))
+        lse = torch.empty((cfg.n_tokens, cfg.n_q_heads), dtype=torch.float32, device=DEV)
+        out = st.st_attn_prefill(tq, tk, tv, plan, lse=lse)
+        grads[dt] = st.st_attn_prefill_bwd(tg, tq, tk, tv, out, lse, plan)
+    torch.cuda.synchronize()
+    for a, b in zip(grads["bf16"], grads["f32"]):
+        assert (a.float() - b).abs().max().item() <= 6e-2 * max(1.0, b.abs().max().item())
+
+
 def test_prefill_bwd_is_deterministic_and_checks_arguments(st):
     cfg = W.random_prefill(605, 2, 6, (5, 60), (5, 70), 4, 2, 128, "bf16")
     a = _run_prefill_bwd(st, cfg)

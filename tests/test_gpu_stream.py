@@ -122,7 +122,8 @@ def test_stream_session_with_arrival_times(st):
     src_out, rsn_out, rep = st.st_stream_run(st.ST_SCHED_STREAMING, layers, hq, s, r, dev["sq"], dev["sk"], dev["sv"], dev["rq"],
                                              dev["rk"], dev["rv"], theta, arrival_s=arrival)
     _check_report(rep, s, r, arrival)
-    assert rep["waited"].tolist() == [True, True, True] and not rep["sliced"].any()
+    # (unit 0's sentence is there at time 0: whether its decode finds the prefill already done is up to the threads)
+    assert rep["waited"].tolist()[1:] == [True, True] and not rep["sliced"].any()
     assert rep["first_token"][2] >= arrival[2] - 2e-3 and rep["total_s"] >= arrival[2]
     o_src, o_rsn = _oracle_rows(act, 0, s, r, theta)
     assert np.abs(to_f64(rsn_out[:, 0]) - o_rsn).max() <= 2e-2
