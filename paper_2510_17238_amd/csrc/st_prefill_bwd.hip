@@ -399,7 +399,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     extern __shared__ __align__(16) unsigned char smem_raw[];
     BwdDkvSmem<D>& sm = *reinterpret_cast<BwdDkvSmem<D>*>(smem_raw);
 
-    const int rank = blockIdx.x / n_kv_heads;
+    // The table is sorted by the FORWARD's cost (late rows first); a key's cost runs the other way (early keys
+    // are seen by the most rows), so walk the table backwards: longest first again, unused slots at once.
+    const int rank = pv.m_max - 1 - int(blockIdx.x / n_kv_heads);
     const int hk = blockIdx.x % n_kv_heads;
     const int group = n_q_heads / n_kv_heads;
     const WorkItem it = pv.sorted[rank];
@@ -431,6 +433,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     const int tile_rsn0 = it.tile_b0 + (S + kTileN - 1) / kTileN;   // ... of the reasoning stream (source keys)
 
     const int key_in_tile = wave * 32 + n;
+    const int wave_last_key = it.row0 + min(__builtin_amdgcn_readfirstlane(wave) * 32 + 31, it.n_rows - 1);
     const bool active = key_in_tile < it.n_rows;
     const int my_key = it.row0 + min(key_in_tile, it.n_rows - 1);
     const int tok_k = pv.perm[it.a_base + my_key];
@@ -527,6 +530,29 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key
         bf16x8 pb[SB][2], dsb[SB][2];
         const float* st = &sm.stats[buf][0];
+        // every row of the tile sees every key of this wave?  (rows are ordered, visible counts do not decrease)
+        const int first_vis = __builtin_amdgcn_readfirstlane(__float_as_int(st[128]));
+        const bool all_seen = cur.rs ? first_vis > wave_last_key : cur.row0 >= wave_last_key;
+        if (all_seen) {
+#pragma unroll
+            for (int rb = 0; rb < SB; ++rb)
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int r0 = 32 * rb + 16 * half + 8 * hg;
+#pragma unroll
+                    for (int q4 = 0; q4 < 2; ++q4) {
+                        const f32x4 a = *reinterpret_cast<const f32x4*>(st + r0 + 4 * q4);
+                        const f32x4 b2 = *reinterpret_cast<const f32x4*>(st + 64 + r0 + 4 * q4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 8 * half + 4 * q4 + e;
+                            const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[rb][i], scale_log2, -a[e]));
+                            pb[rb][half][4 * q4 + e] = (__bf16)p;
+                            dsb[rb][half][4 * q4 + e] = (__bf16)(p * (dp_acc[rb][i] - b2[e]));
+                        }
+                    }
+                }
+        } else
 #pragma unroll
         for (int rb = 0; rb < SB; ++rb)
 #pragma unroll
