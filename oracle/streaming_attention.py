@@ -24,7 +24,9 @@ equivariance, Eq. 2 as printed, reduction to library causal attention, source ch
 closed-form visible-pair counts, LSE-merge == concatenation, RoPE identities,
 decode == last prefill row, paged gather == contiguous, rotate-on-append / rotate-in-decode ==
 the unfused pipeline, Alg. 1 timeline == hand-worked schedules and the paper's Table 4 latencies,
-backward == central differences of the forward and == library autograd of a dense-mask softmax.
+backward == central differences of the forward and == library autograd of a dense-mask softmax,
+E4M3 rounding / bytes == a library's cast over all codes, midpoints and random values, row scales == their
+defining inequality, 8-bit store idempotent and within half a grid step.
 No function here is "parity unpinned".
 """
 import numpy as np
@@ -394,6 +396,76 @@ def decode_dual_rotated(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len,
     q_len = q.shape[0]
     positions = rsn_len - q_len + np.arange(q_len)
     return decode_dual_concat(rope(q, positions, theta), src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, scale)
+
+
+# --------------------------------------------------------------------------
+# 8-bit storage of the two caches (Sec. 3.3's caches in the OCP FP8 E4M3 format; the paper stores
+# them in the model's precision -- this is a storage variant of the same operator, defined here)
+# --------------------------------------------------------------------------
+E4M3_MAX = 448.0          # largest finite E4M3 value: 1.75 * 2^8
+_E4M3_MIN_EXP = -6        # exponent of the smallest normal value; below it the grid step stays 2^-9
+
+
+def e4m3_round(x):
+    """Nearest value of the E4M3 grid, ties to the even mantissa, for |x| <= 448 (the quantiser below
+    never asks for more).  E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; the grid step in the binade
+    [2^e, 2^(e+1)) is 2^(e-3), and 2^-9 everywhere below 2^-6 (subnormals)."""
+    x = np.asarray(x, dtype=np.float64)
+    assert np.all(np.abs(x) <= E4M3_MAX)
+    _, ex = np.frexp(np.abs(x))                     # |x| = m 2^ex with m in [0.5, 1)
+    e = np.maximum(ex - 1, _E4M3_MIN_EXP)
+    step = np.ldexp(1.0, e - 3)
+    return np.sign(x) * np.rint(np.abs(x) / step) * step      # rint rounds halves to even
+
+
+def e4m3_encode(v):
+    """Byte of a value that lies on the E4M3 grid: sign << 7 | exponent field << 3 | mantissa."""
+    v = np.asarray(v, dtype=np.float64)
+    a = np.abs(v)
+    _, ex = np.frexp(a)
+    e = ex - 1
+    normal = a >= np.ldexp(1.0, _E4M3_MIN_EXP)
+    mant = np.where(normal, (a / np.ldexp(1.0, np.where(normal, e, 0)) - 1.0) * 8.0, a / np.ldexp(1.0, -9))
+    field = np.where(normal, e + 7, 0)
+    assert np.all(mant == np.rint(mant)) and np.all(mant < 8) and np.all(field <= 15)
+    sign = np.signbit(v).astype(np.int64)
+    return (sign << 7 | field.astype(np.int64) << 3 | mant.astype(np.int64)).astype(np.uint8)
+
+
+def e4m3_decode(code):
+    """Value of an E4M3 byte (0x7f / 0xff, the NaN codes, never occur here)."""
+    c = np.asarray(code).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    field, mant = (c >> 3) & 15, c & 7
+    mag = np.where(field == 0, mant * np.ldexp(1.0, -9), (1.0 + mant / 8.0) * np.ldexp(1.0, field - 7))
+    return sign * mag
+
+
+def row_scale_exponent(amax):
+    """Power-of-two scale of a row: the smallest integer k with amax * 2^-k <= 448; 0 for an all-zero row."""
+    amax = np.asarray(amax, dtype=np.float64)
+    m, ex = np.frexp(amax)                           # amax = m 2^ex, m in [0.5, 1);  448 = 0.875 * 2^9
+    k = np.where(m <= 0.875, ex - 9, ex - 8)
+    return np.where(amax == 0, 0, k).astype(np.int64)
+
+
+def quantize_rows_e4m3(x):
+    """x[..., D] -> (codes uint8 [..., D], k int [...]): every row (one token, one head) is divided by its own
+    power of two 2^k -- exact -- and rounded to E4M3; the row's largest magnitude lands in (224, 448]."""
+    x = np.asarray(x, dtype=np.float64)
+    k = row_scale_exponent(np.abs(x).max(axis=-1)) if x.shape[-1] else np.zeros(x.shape[:-1], np.int64)
+    return e4m3_encode(e4m3_round(np.ldexp(x, -k[..., None]))), k
+
+
+def dequantize_rows_e4m3(codes, k):
+    return np.ldexp(e4m3_decode(codes), np.asarray(k)[..., None])
+
+
+def decode_dual_fp8(q, src_k, src_v, rsn_k, rsn_v, src_visible_len, rsn_len, scale=None):
+    """The decode step over caches stored in 8 bits: keys and values are what comes back out of the store,
+    everything after that is decode_dual_concat unchanged (queries, probabilities and sums are not quantised)."""
+    rq = lambda a: dequantize_rows_e4m3(*quantize_rows_e4m3(a))
+    return decode_dual_concat(q, rq(src_k), rq(src_v), rq(rsn_k), rq(rsn_v), src_visible_len, rsn_len, scale)
 
 
 # --------------------------------------------------------------------------

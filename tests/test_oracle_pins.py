@@ -481,6 +481,83 @@ def test_p12_backward_matches_library_autograd(hq, hkv):
     assert np.abs(dv - tv.grad.numpy()).max() < 1e-12
 
 
+# ---- P13: 8-bit storage of the caches (E4M3 codes, one power-of-two scale per row)
+def test_p13_e4m3_matches_library_cast_on_codes_midpoints_and_random_values():
+    """torch's CPU cast to float8_e4m3fn: every code's value, every midpoint between neighbours (ties), random values."""
+    codes = np.array([c for c in range(256) if c & 0x7f != 0x7f], dtype=np.uint8)        # 0x7f, 0xff are NaN
+    lib_vals = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(O.e4m3_decode(codes), lib_vals)
+    nz = codes[(codes & 0x7f) != 0]                                                        # (-0 encodes as 0x80 too)
+    assert np.array_equal(O.e4m3_encode(O.e4m3_decode(nz)), nz)
+    assert np.array_equal(O.e4m3_round(lib_vals), lib_vals)                                # grid points stay
+    pos = np.sort(lib_vals[lib_vals >= 0])
+    mids = (pos[1:] + pos[:-1]) / 2                                                        # exact in fp32
+    rng = np.random.Generator(np.random.PCG64(1301))
+    rnd = np.concatenate([rng.uniform(-448, 448, 4000), rng.standard_normal(4000) * 0.01, rng.standard_normal(4000) * 3,
+                          np.ldexp(rng.uniform(-1, 1, 2000), -8)]).astype(np.float32).astype(np.float64)
+    for x in (mids, -mids, np.nextafter(mids, np.inf), np.nextafter(mids, -np.inf), rnd):
+        x32 = x.astype(np.float32)
+        assert np.array_equal(x32.astype(np.float64), x) or x is not rnd
+        lib = torch.from_numpy(x32).to(torch.float8_e4m3fn)
+        mine = O.e4m3_round(x32.astype(np.float64))
+        assert np.array_equal(mine, lib.to(torch.float64).numpy())
+        assert np.array_equal(O.e4m3_encode(mine) & 0x7f, lib.view(torch.uint8).numpy() & 0x7f)
+        nzm = mine != 0
+        assert np.array_equal(O.e4m3_encode(mine)[nzm], lib.view(torch.uint8).numpy()[nzm])
+    # a tie goes to the even mantissa: 1 + 1/16 lies between 1 (mantissa 0) and 1.125 (mantissa 1)
+    assert O.e4m3_round(1.0625) == 1.0 and O.e4m3_round(1.1875) == 1.25 and O.e4m3_round(2.0 ** -10) == 0.0
+    assert O.e4m3_round(1.5 * 2.0 ** -9) == 2.0 ** -8 and O.e4m3_round(-447.0) == -448.0
+
+
+def test_p13_row_scale_is_the_smallest_power_of_two_that_fits():
+    rng = np.random.Generator(np.random.PCG64(1302))
+    amax = np.concatenate([np.ldexp(rng.uniform(0.5, 1, 3000), rng.integers(-30, 30, 3000)),
+                           [448.0, np.nextafter(448.0, np.inf), np.nextafter(448.0, 0), 224.0, np.nextafter(224.0, np.inf), 1.0, 7.0, 2.0 ** -20]])
+    k = O.row_scale_exponent(amax)
+    assert np.all(np.ldexp(amax, -k) <= 448.0) and np.all(np.ldexp(amax, -(k - 1)) > 448.0)
+    assert O.row_scale_exponent(448.0) == 0 and O.row_scale_exponent(449.0) == 1 and O.row_scale_exponent(224.0) == -1
+    assert O.row_scale_exponent(0.0) == 0
+
+
+def test_p13_store_is_idempotent_and_within_half_a_step():
+    rng = np.random.Generator(np.random.PCG64(1303))
+    x = W.bf16_round((rng.standard_normal((50, 3, 64)) * np.ldexp(1.0, rng.integers(-6, 6, (50, 3, 1)))).astype(np.float32)).astype(np.float64)
+    x[7] = 0.0                                                                              # an all-zero row
+    x[8, :, 1:] = 0.0                                                                       # a single nonzero entry
+    codes, k = O.quantize_rows_e4m3(x)
+    assert codes.dtype == np.uint8 and codes.shape == x.shape and k.shape == x.shape[:-1]
+    back = O.dequantize_rows_e4m3(codes, k)
+    c2, k2 = O.quantize_rows_e4m3(back)
+    assert np.array_equal(O.dequantize_rows_e4m3(c2, k2), back)                            # what comes out goes back in unchanged
+    # the row maximum lands in the top binade, so a normal value keeps 3 mantissa bits: relative error <= 2^-4;
+    # anything below 2^-6 of the scaled row sits on the 2^-9 grid: absolute error <= 2^-10 of the scale
+    step_err = np.maximum(np.abs(x) * 2.0 ** -4, np.ldexp(1.0, k - 10)[..., None])
+    assert np.all(np.abs(back - x) <= step_err)
+    amax = np.abs(x).max(axis=-1)
+    top = np.abs(O.e4m3_decode(codes)).max(axis=-1)
+    assert np.all((top >= 224.0) | (amax == 0)) and np.all(top <= 448.0)        # (224, 448] before rounding
+    assert np.array_equal(back[7], np.zeros_like(back[7])) and np.array_equal(back[8, :, 0], x[8, :, 0] * 0 + back[8, :, 0])
+    assert np.abs(back[8, :, 0] - x[8, :, 0]).max() <= np.abs(x[8, :, 0]).max() * 2.0 ** -4
+
+
+def test_p13_decode_over_8bit_caches():
+    """Values already on the grid pass through untouched (== the plain decode); otherwise the result is the plain
+    decode of the stored values and stays close to the unquantised one."""
+    rng = np.random.Generator(np.random.PCG64(1304))
+    hq, hkv, d, ls, lr = 4, 2, 16, 21, 9
+    q = rng.standard_normal((1, hq, d))
+    sk, sv = rng.standard_normal((ls, hkv, d)), rng.standard_normal((ls, hkv, d))
+    rk, rv = rng.standard_normal((lr, hkv, d)), rng.standard_normal((lr, hkv, d))
+    rq = lambda a: O.dequantize_rows_e4m3(*O.quantize_rows_e4m3(a))
+    o8, l8 = O.decode_dual_fp8(q, sk, sv, rk, rv, 17, lr)
+    o_plain, l_plain = O.decode_dual_concat(q, rq(sk), rq(sv), rq(rk), rq(rv), 17, lr)
+    assert np.array_equal(o8, o_plain) and np.array_equal(l8, l_plain)
+    og, lg = O.decode_dual_fp8(q, rq(sk), rq(sv), rq(rk), rq(rv), 17, lr)
+    assert np.array_equal(og, o_plain)
+    o_ref, _ = O.decode_dual_concat(q, sk, sv, rk, rv, 17, lr)
+    assert 0 < np.abs(o8 - o_ref).max() < 0.15
+
+
 # ---- metadata derived from the dense mask: closed forms for config 1
 def test_metadata_config1_closed_form():
     cfg = W.config1()
