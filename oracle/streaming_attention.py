@@ -441,11 +441,15 @@ def e4m3_decode(code):
     return sign * mag
 
 
+SCALE_EXP_MIN = -100      # the scale 2^k is stored as an fp32 number and has to stay a normal one
+
+
 def row_scale_exponent(amax):
-    """Power-of-two scale of a row: the smallest integer k with amax * 2^-k <= 448; 0 for an all-zero row."""
+    """Power-of-two scale of a row: the smallest integer k with amax * 2^-k <= 448, but not below SCALE_EXP_MIN
+    (rows that small -- below 2^-91 -- lose their last bits); 0 for an all-zero row."""
     amax = np.asarray(amax, dtype=np.float64)
     m, ex = np.frexp(amax)                           # amax = m 2^ex, m in [0.5, 1);  448 = 0.875 * 2^9
-    k = np.where(m <= 0.875, ex - 9, ex - 8)
+    k = np.maximum(np.where(m <= 0.875, ex - 9, ex - 8), SCALE_EXP_MIN)
     return np.where(amax == 0, 0, k).astype(np.int64)
 
 

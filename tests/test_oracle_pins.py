@@ -517,6 +517,8 @@ def test_p13_row_scale_is_the_smallest_power_of_two_that_fits():
     assert np.all(np.ldexp(amax, -k) <= 448.0) and np.all(np.ldexp(amax, -(k - 1)) > 448.0)
     assert O.row_scale_exponent(448.0) == 0 and O.row_scale_exponent(449.0) == 1 and O.row_scale_exponent(224.0) == -1
     assert O.row_scale_exponent(0.0) == 0
+    assert O.row_scale_exponent(2.0 ** -120) == O.SCALE_EXP_MIN and O.row_scale_exponent(448 * 2.0 ** -100) == -100
+    assert O.row_scale_exponent(449 * 2.0 ** -100) == -99
 
 
 def test_p13_store_is_idempotent_and_within_half_a_step():
