@@ -267,7 +267,7 @@ def bench_prefill_backward(st, torch, W, reps):
     return {"ms": e0.elapsed_time(e1) / reps, "flops": 2.5 * flops_fwd, "dq_ms": dq_ms, "dkv_ms": dkv_ms, "flops_fwd": flops_fwd}
 
 
-def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
+def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8=False):
     dev = "cuda"
     shp = W.config3() if n_layers is None else W.config3(n_layers=n_layers)
     B, L, hq, hkv, d = shp.batch, shp.n_layers, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
@@ -279,10 +279,14 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
     layers = []
     len_s_all = torch.zeros((L, B), dtype=torch.int32, device=dev); len_r_all = torch.zeros((L, B), dtype=torch.int32, device=dev)
     for li in range(L):
-        cs = st.KVCache(B * pages_s, B, pages_s, hkv, d, tab_s); cr = st.KVCache(B * pages_r, B, pages_r, hkv, d, tab_r)
+        cs = st.KVCache(B * pages_s, B, pages_s, hkv, d, tab_s, fp8=fp8); cr = st.KVCache(B * pages_r, B, pages_r, hkv, d, tab_r, fp8=fp8)
         cs.appended_len = len_s_all[li]; cr.appended_len = len_r_all[li]      # one tensor for all layers: one reset per step
         for c in (cs, cr):                                  # any bit pattern is valid cache content: fill in place
-            c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
+            if fp8:                                         # (any finite code: 0x7f / 0xff are the NaN codes)
+                c.k_pool.random_(0, 0x7f, generator=g); c.v_pool.random_(0, 0x7f, generator=g)
+                c.k_scale.fill_(2.0 ** -7); c.v_scale.fill_(2.0 ** -7)
+            else:
+                c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
         layers.append(st.DualCache(cs, cr))
     src_vis = torch.from_numpy(shp.src_visible_len).to(dev)
     rsn_len = torch.from_numpy(shp.rsn_len).to(dev)
@@ -352,8 +356,9 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     tokens = float((shp.src_visible_len.astype(np.int64) + shp.rsn_len).sum())
-    per_layer = tokens * 2 * hkv * d * 2
-    append_bytes = float(B * (shp.src_append + 1)) * 2 * hkv * d * 2 * 2 * L
+    # bytes per cached token and KV head: K and V rows of D elements; 8-bit rows carry an fp32 scale each
+    per_layer = tokens * hkv * ((2 * d + 8) if fp8 else 2 * d * 2)
+    append_bytes = float(B * (shp.src_append + 1)) * hkv * (2 * d * 2 + ((2 * d + 8) if fp8 else 2 * d * 2)) * L
     return {"shape": shp, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
             "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode}
 
@@ -429,6 +434,8 @@ def main():
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     ap.add_argument("--long-prefill", action="store_true",
                     help="also time the attention kernel on configs[3] (8 x 16,384 tokens) and report it under 'prefill_long'")
+    ap.add_argument("--fp8-cache", action="store_true",
+                    help="also run the decode workload with 8-bit (E4M3) caches and report it under 'decode_fp8'")
     ap.add_argument("--backward", action="store_true",
                     help="also time st_attn_prefill_bwd on configs[1] and report it under 'prefill_backward'")
     ap.add_argument("--stream-session", action="store_true",
@@ -502,6 +509,19 @@ def main():
             "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
             "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
                     "each of which streams the cache again"}
+    if args.fp8_cache and not args.no_decode:
+        d8 = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph, fp8=True)
+        g8_step = d8["bytes_per_step"] / d8["sec_per_step"] / 1e9
+        g8_kernel = d8["bytes_per_layer"] / (d8["layer_decode_ms"] * 1e-3) / 1e9
+        line["decode_fp8"] = {
+            "workload": "configs[2] with both caches stored in 8 bits (E4M3 codes + one fp32 power-of-two scale per key row and per "
+                        "value row: 264 B instead of 512 B per cached token and KV head); same step as 'decode'",
+            "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"],
+            "ms_per_step": round(d8["sec_per_step"] * 1e3, 4), "algorithmic_bytes_per_step": d8["bytes_per_step"],
+            "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3),
+            "roofline": {"kernel": "decode_split16_fp8_kernel<128> (one layer)", "bound": "hbm", "achieved": round(g8_kernel, 1),
+                         "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g8_kernel / PEAK_HBM_GBPS, 4), "traffic": None,
+                         "avg_kernel_ms": round(d8["layer_decode_ms"], 4)}}
     if args.backward:
         bw = bench_prefill_backward(st, torch, W, 10)
         tf = bw["flops"] / (bw["ms"] * 1e-3) / 1e12

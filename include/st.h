@@ -43,7 +43,9 @@ typedef enum st_status {
     ST_ERR_RUNTIME = 6       /* a HIP call failed; text in st_last_error() */
 } st_status;
 
-typedef enum st_dtype { ST_F32 = 0, ST_BF16 = 1 } st_dtype;
+/* ST_FP8_E4M3 (OCP FP8 E4M3: bias 7, largest value 448, no infinities) names a STORAGE format of the
+ * KV caches only; activations are ST_BF16 or ST_F32. */
+typedef enum st_dtype { ST_F32 = 0, ST_BF16 = 1, ST_FP8_E4M3 = 2 } st_dtype;
 
 /* The two streams of the method; also the value set of stream_ids[]. */
 typedef enum st_stream_kind { ST_SOURCE = 0, ST_REASONING = 1 } st_stream_kind;
@@ -235,6 +237,18 @@ st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const void* d_out, c
  *   k_pool : [n_pages][n_kv_heads][head_dim / 8][16 slots][8]   element (page,h,c,slot,e)
  *   v_pool : [n_pages][n_kv_heads][head_dim][16 slots]          element (page,h,d,slot)
  * appended_len[b] is advanced only by st_kv_append.
+ *
+ * 8-bit caches (dtype = ST_FP8_E4M3; a storage variant, not in the paper): every row -- one token
+ * of one KV head, keys and values separately -- is stored as E4M3 codes of the row divided by a
+ * power of two 2^k, k the smallest integer (not below -100) for which the row's largest magnitude
+ * is at most 448, and 2^k is kept as an fp32 number beside it (k = 0 for an all-zero row).  The
+ * division is exact, the rounding is to nearest, ties to even.  Layouts, 1 byte per element:
+ *   k_pool  : [n_pages][n_kv_heads][head_dim / 16][16 slots][16]
+ *   v_pool  : [n_pages][n_kv_heads][head_dim][16 slots]
+ *   k_scale, v_scale : fp32 [n_pages][n_kv_heads][16 slots]
+ * st_kv_append (bf16 rows in, quantised on the way) and st_attn_decode_dual(_rope) with
+ * q_len * (n_q_heads / n_kv_heads) <= 16 accept them; every other call that takes a cache gives
+ * ST_ERR_UNSUPPORTED.  Both caches of a pair must have the same dtype.
  * ---------------------------------------------------------------------- */
 typedef struct st_kv_cache {
     void* k_pool;
@@ -246,7 +260,9 @@ typedef struct st_kv_cache {
     int32_t page_size;         /* must be 16 */
     int32_t n_kv_heads;
     int32_t head_dim;
-    int32_t dtype;             /* st_dtype; must be ST_BF16 */
+    int32_t dtype;             /* st_dtype of the pools: ST_BF16 or ST_FP8_E4M3 */
+    float* k_scale;            /* ST_FP8_E4M3 only (NULL otherwise): row scales, see above */
+    float* v_scale;
 } st_kv_cache;
 
 typedef struct st_dual_cache {

@@ -8,7 +8,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 ST_OK = 0
-ST_F32, ST_BF16 = 0, 1
+ST_F32, ST_BF16, ST_FP8_E4M3 = 0, 1, 2
 ST_SOURCE, ST_REASONING = 0, 1
 ST_TILE_SKIP, ST_TILE_FULL, ST_TILE_PARTIAL = 0, 1, 2
 ST_BLOCK_SS, ST_BLOCK_RS, ST_BLOCK_RR = 0, 1, 2
@@ -27,7 +27,8 @@ class StError(RuntimeError):
 class _KVCacheStruct(C.Structure):
     _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("page_table", C.c_void_p),
                 ("appended_len", C.c_void_p), ("max_pages_per_seq", C.c_int32), ("n_pages", C.c_int32),
-                ("page_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+                ("page_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32),
+                ("k_scale", C.c_void_p), ("v_scale", C.c_void_p)]
 
 
 class _DualCacheStruct(C.Structure):
@@ -355,12 +356,20 @@ def st_attn_prefill_ids(q, k, v, segment_ids, stream_ids, positions, cu_seqlens,
 class KVCache:
     """Caller-owned paged cache: pools, page table and length vector are torch tensors."""
 
-    def __init__(self, n_pages, batch, max_pages_per_seq, n_kv_heads, head_dim, page_table, device="cuda", fill=None):
+    def __init__(self, n_pages, batch, max_pages_per_seq, n_kv_heads, head_dim, page_table, device="cuda", fill=None, fp8=False):
         self.n_pages, self.batch, self.max_pages_per_seq = n_pages, batch, max_pages_per_seq
         self.n_kv_heads, self.head_dim = n_kv_heads, head_dim
+        self.fp8 = bool(fp8)
         shape_k = (n_pages, n_kv_heads, head_dim // 8, PAGE, 8)
         shape_v = (n_pages, n_kv_heads, head_dim, PAGE)
-        if fill is None:
+        self.k_scale = self.v_scale = None
+        if self.fp8:
+            # E4M3 codes as bytes; `fill` (a byte) pre-sets pools, and scales get NaN, to show what is never read
+            self.k_pool = torch.full((n_pages, n_kv_heads, head_dim // 16, PAGE, 16), 0 if fill is None else int(fill), dtype=torch.uint8, device=device)
+            self.v_pool = torch.full(shape_v, 0 if fill is None else int(fill), dtype=torch.uint8, device=device)
+            self.k_scale = torch.full((n_pages, n_kv_heads, PAGE), float("nan") if fill is not None else 0.0, dtype=torch.float32, device=device)
+            self.v_scale = self.k_scale.clone()
+        elif fill is None:
             self.k_pool = torch.empty(shape_k, dtype=torch.bfloat16, device=device)
             self.v_pool = torch.empty(shape_v, dtype=torch.bfloat16, device=device)
         else:
@@ -373,7 +382,8 @@ class KVCache:
     def struct(self):
         return _KVCacheStruct(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.page_table.data_ptr(),
                               self.appended_len.data_ptr(), self.max_pages_per_seq, self.n_pages, PAGE,
-                              self.n_kv_heads, self.head_dim, ST_BF16)
+                              self.n_kv_heads, self.head_dim, ST_FP8_E4M3 if self.fp8 else ST_BF16,
+                              self.k_scale.data_ptr() if self.fp8 else None, self.v_scale.data_ptr() if self.fp8 else None)
 
 
 class DualCache:
@@ -402,6 +412,17 @@ def k_pool_to_logical(k_pool):
 def v_pool_to_logical(v_pool):
     """[n_pages, Hkv, D, 16] -> [n_pages, 16, Hkv, D]."""
     return v_pool.permute(0, 3, 1, 2)
+
+
+def k_pool8_to_logical(k_pool):
+    """8-bit key pool [n_pages, Hkv, D/16, 16, 16] -> [n_pages, 16, Hkv, D] (bytes)."""
+    p, h, c, s, e = k_pool.shape
+    return k_pool.permute(0, 3, 1, 2, 4).reshape(p, s, h, c * e)
+
+
+def scale_to_logical(scale):
+    """[n_pages, Hkv, 16] -> [n_pages, 16, Hkv]."""
+    return scale.permute(0, 2, 1)
 
 
 def k_pool_from_logical(x):

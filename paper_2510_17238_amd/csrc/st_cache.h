@@ -12,9 +12,13 @@ struct CacheView {
     int32_t max_pages;
     int32_t n_pages;
     int32_t n_kv_heads;
+    // 8-bit caches: the pools hold bytes ([n_pages][Hkv][D/16][16][16] and [n_pages][Hkv][D][16]) and every
+    // (page, head, slot) has an fp32 power-of-two scale for its key row and one for its value row
+    float* k_scale;
+    float* v_scale;
 };
 
-st_status check_cache(const st_kv_cache& c, const char* who, const char* which);
+st_status check_cache(const st_kv_cache& c, const char* who, const char* which, bool allow_fp8 = false);
 CacheView cache_view(const st_kv_cache& c);
 
 }  // namespace st

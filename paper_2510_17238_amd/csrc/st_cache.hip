@@ -105,6 +105,92 @@ __global__ __launch_bounds__(256) void kv_append_kernel(CacheView cache, const u
     }
 }
 
+// 8-bit store: every key row and every value row (one token, one KV head) is divided by its own power of
+// two 2^k -- k the smallest integer, not below kScaleExpMin, with max|row| 2^-k <= 448 -- and rounded to
+// E4M3 (nearest, ties to even); 2^k goes to the scale arrays.  Same work split as above: one workgroup per
+// (page touched, KV head, sequence); the 16 x D tile of each tensor passes through LDS.
+constexpr int kScaleExpMin = -100;
+
+__device__ __forceinline__ int row_scale_exponent(float amax) {
+    if (!(amax > 0.f)) return 0;
+    int ex;
+    const float m = frexpf(amax, &ex);                  // amax = m 2^ex, m in [0.5, 1);  448 = 0.875 * 2^9
+    return max(m <= 0.875f ? ex - 9 : ex - 8, kScaleExpMin);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_append_fp8_kernel(CacheView cache, const uint16_t* __restrict__ k_new,
+                                                            const uint16_t* __restrict__ v_new,
+                                                            const int32_t* __restrict__ n_new, int max_new,
+                                                            int pages_per_seq_touched) {
+    constexpr int C16 = D / 16, C8 = D / 8;
+    __shared__ float s_x[2][kPage][D + 1];              // [0] keys, [1] values of the page's new tokens
+    __shared__ int s_exp[2][kPage];
+    const int pi = blockIdx.x % pages_per_seq_touched;
+    const int h = (blockIdx.x / pages_per_seq_touched) % cache.n_kv_heads;
+    const int b = blockIdx.x / (pages_per_seq_touched * cache.n_kv_heads);
+    const int capacity = cache.max_pages * kPage;
+    const int start = min(max(cache.appended_len[b], 0), capacity);
+    int n = n_new ? min(max(n_new[b], 0), max_new) : max_new;
+    n = min(n, capacity - start);
+    const int page = start / kPage + pi;
+    const int lo = max(start, page * kPage), hi = min(start + n, (page + 1) * kPage);
+    if (lo >= hi) return;
+    const int id = cache.page_table[int64_t(b) * cache.max_pages + page];
+    if (id < 0 || id >= cache.n_pages) return;
+    const int slot_lo = lo - page * kPage, cnt = hi - lo;
+    const int64_t row0 = int64_t(b) * max_new + (lo - start);
+    const int64_t row_stride = int64_t(cache.n_kv_heads) * D;
+    const int tid = threadIdx.x;
+
+    for (int w = tid; w < 2 * kPage * C8; w += 256) {
+        const int which = w / (kPage * C8), s = (w / C8) % kPage, c = w % C8;
+        if (s >= cnt) continue;
+        const Piece in = *reinterpret_cast<const Piece*>((which ? v_new : k_new) + (row0 + s) * row_stride + h * D + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_x[which][s][c * 8 + e] = bf16_bits_to_f32(in.v[e]);
+    }
+    __syncthreads();
+    // 8 threads per row: largest magnitude, exponent, scale
+    {
+        const int row = tid >> 3, part = tid & 7;       // 32 rows: 16 key rows, then 16 value rows
+        const int which = row >> 4, s = row & 15;
+        float amax = 0.f;
+        if (s < cnt)
+            for (int d = part; d < D; d += 8) amax = fmaxf(amax, fabsf(s_x[which][s][d]));
+#pragma unroll
+        for (int o = 4; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+        if (part == 0 && s < cnt) {
+            const int k = row_scale_exponent(amax);
+            s_exp[which][s] = k;
+            (which ? cache.v_scale : cache.k_scale)[(int64_t(id) * cache.n_kv_heads + h) * kPage + slot_lo + s] = ldexpf(1.f, k);
+        }
+    }
+    __syncthreads();
+    uint8_t* kdst = reinterpret_cast<uint8_t*>(cache.k_pool) + (int64_t(id) * cache.n_kv_heads + h) * (C16 * kPage * 16);
+    uint8_t* vdst = reinterpret_cast<uint8_t*>(cache.v_pool) + (int64_t(id) * cache.n_kv_heads + h) * (D * kPage);
+    // K: 8 codes (8 bytes) per thread: d = 8 c .. 8 c + 7 of one token -> chunk c / 2, byte 8 (c % 2)
+    for (int w = tid; w < kPage * C8; w += 256) {
+        const int c = w / kPage, s = w % kPage;
+        if (s >= cnt) continue;
+        const int k = s_exp[0][s];
+        uint32_t lo32 = 0, hi32 = 0;
+        const float* x = &s_x[0][s][c * 8];
+        lo32 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(x[0], -k), ldexpf(x[1], -k), lo32, false);
+        lo32 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(x[2], -k), ldexpf(x[3], -k), lo32, true);
+        hi32 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(x[4], -k), ldexpf(x[5], -k), hi32, false);
+        hi32 = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(x[6], -k), ldexpf(x[7], -k), hi32, true);
+        *reinterpret_cast<u32x2*>(kdst + ((c >> 1) * kPage + slot_lo + s) * 16 + 8 * (c & 1)) = u32x2{lo32, hi32};
+    }
+    // V: one byte per (d, slot)
+    for (int w = tid; w < D * kPage; w += 256) {
+        const int d = w / kPage, s = w % kPage;
+        if (s >= cnt) continue;
+        const uint32_t code = __builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(s_x[1][s][d], -s_exp[1][s]), 0.f, 0u, false);
+        vdst[d * kPage + slot_lo + s] = uint8_t(code & 0xffu);
+    }
+}
+
 __global__ void kv_append_bump_kernel(int32_t* __restrict__ appended_len, const int32_t* __restrict__ n_new,
                                       int max_new, int batch, int capacity) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -115,11 +201,17 @@ __global__ void kv_append_bump_kernel(int32_t* __restrict__ appended_len, const 
     appended_len[b] = start + n;
 }
 
-st_status check_cache(const st_kv_cache& c, const char* who, const char* which) {
+st_status check_cache(const st_kv_cache& c, const char* who, const char* which, bool allow_fp8) {
     if (!c.k_pool || !c.v_pool || !c.page_table) return fail(ST_ERR_INVALID_ARG, "%s: %s cache has a null pointer", who, which);
     if (!aligned16(c.k_pool) || !aligned16(c.v_pool)) return fail(ST_ERR_INVALID_ARG, "%s: %s pools must be 16-byte aligned", who, which);
     if (c.page_size != kPage) return fail(ST_ERR_UNSUPPORTED, "%s: page_size %d (must be %d)", who, c.page_size, kPage);
-    if (c.dtype != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "%s: cache dtype %d (bf16 only)", who, c.dtype);
+    if (c.dtype == ST_FP8_E4M3) {
+        if (!allow_fp8) return fail(ST_ERR_UNSUPPORTED, "%s: 8-bit caches are not supported by this call", who);
+        if (!c.k_scale || !c.v_scale) return fail(ST_ERR_INVALID_ARG, "%s: %s cache is ST_FP8_E4M3 but has no scale arrays", who, which);
+        if (!aligned16(c.k_scale) || !aligned16(c.v_scale)) return fail(ST_ERR_INVALID_ARG, "%s: %s scale arrays must be 16-byte aligned", who, which);
+    } else if (c.dtype != ST_BF16) {
+        return fail(ST_ERR_UNSUPPORTED, "%s: cache dtype %d (ST_BF16 or ST_FP8_E4M3)", who, c.dtype);
+    }
     if (c.head_dim != 64 && c.head_dim != 128) return fail(ST_ERR_UNSUPPORTED, "%s: head_dim %d (64 or 128)", who, c.head_dim);
     if (c.n_kv_heads <= 0 || c.max_pages_per_seq <= 0 || c.n_pages <= 0) return fail(ST_ERR_INVALID_ARG, "%s: %s cache has non-positive sizes", who, which);
     return ST_OK;
@@ -134,6 +226,8 @@ CacheView cache_view(const st_kv_cache& c) {
     v.max_pages = c.max_pages_per_seq;
     v.n_pages = c.n_pages;
     v.n_kv_heads = c.n_kv_heads;
+    v.k_scale = c.dtype == ST_FP8_E4M3 ? c.k_scale : nullptr;
+    v.v_scale = c.dtype == ST_FP8_E4M3 ? c.v_scale : nullptr;
     return v;
 }
 
@@ -147,8 +241,9 @@ static st_status kv_append_impl(const char* who, const st_dual_cache* caches, st
     if (!caches || !k_new || !v_new) return fail(ST_ERR_INVALID_ARG, "%s: null pointer", who);
     if (which != ST_SOURCE && which != ST_REASONING) return fail(ST_ERR_INVALID_ARG, "%s: which = %d", who, int(which));
     const st_kv_cache& c = which == ST_SOURCE ? caches->source : caches->reasoning;
-    st_status r = check_cache(c, who, which == ST_SOURCE ? "source" : "reasoning");
+    st_status r = check_cache(c, who, which == ST_SOURCE ? "source" : "reasoning", !rotate);
     if (r != ST_OK) return r;
+    const bool fp8 = c.dtype == ST_FP8_E4M3;
     if (!c.appended_len) return fail(ST_ERR_INVALID_ARG, "%s: appended_len is null", who);
     if (!aligned16(k_new) || !aligned16(v_new)) return fail(ST_ERR_INVALID_ARG, "%s: k_new / v_new must be 16-byte aligned", who);
     if (batch <= 0 || max_new < 0) return fail(ST_ERR_INVALID_ARG, "%s: bad sizes", who);
@@ -168,7 +263,14 @@ static st_status kv_append_impl(const char* who, const st_dual_cache* caches, st
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new,
                            n_new, max_new, touched, freq);
     };
-    if (c.head_dim == 64) {
+    if (fp8) {
+        if (c.head_dim == 64)
+            hipLaunchKernelGGL((kv_append_fp8_kernel<64>), dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new,
+                               (const uint16_t*)v_new, n_new, max_new, touched);
+        else
+            hipLaunchKernelGGL((kv_append_fp8_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new,
+                               (const uint16_t*)v_new, n_new, max_new, touched);
+    } else if (c.head_dim == 64) {
         if (rotate) launch(kv_append_kernel<64, true>); else launch(kv_append_kernel<64, false>);
     } else {
         if (rotate) launch(kv_append_kernel<128, true>); else launch(kv_append_kernel<128, false>);

@@ -405,6 +405,205 @@ __global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
     }
 }
 
+// The one-wave kernel over 8-bit caches (E4M3 codes, one power-of-two fp32 scale per key row and per value
+// row): half the bytes per token.  Codes become bf16 in registers (exact: 3 mantissa bits) and feed the same
+// two bf16 products; the key scale multiplies the score (folded into the softmax scale factor), the value
+// scale multiplies the probability before the second product -- both exact, the scales being powers of two.
+// Pool layouts [page][head][D/16][slot][16] and [page][head][D][slot] bytes keep the loads contiguous:
+//   K: lane (m, g4) reads the 16 bytes d = 64 jj + 16 g4 .. + 15 of key row m: two k-steps' worth (the query
+//      fragments use the same assignment of head dims to k-steps)
+//   V: lane (m, g4) reads the 8 bytes slots 8 (g4 % 2) .. + 7 of row d = 16 db + m in page g4 / 2
+//   scales: the 8 + 8 floats of those same slots.
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16(uint32_t lo, uint32_t hi) {
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.f, false), b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.f, false), d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.f, true);
+    bf16x8 r;
+    r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+    r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+    return r;
+}
+
+template <int D>
+__global__ __launch_bounds__(64, 16) void decode_split16_fp8_kernel(DecodeArgs a) {
+    constexpr int KS = D / 32, KP = D / 64, DB = D / 16, C16 = D / 16;
+    const int lane = threadIdx.x;
+    const int nc = a.ncs + a.ncr;
+    const int c = int(blockIdx.x % unsigned(nc));
+    const unsigned bh = blockIdx.x / unsigned(nc);
+    const int h = int(bh % unsigned(a.n_kv_heads));
+    const int b = int(bh / unsigned(a.n_kv_heads));
+    const bool is_src = c < a.ncs;
+    const CacheView& cv = is_src ? a.src : a.rsn;
+    const int cc = is_src ? c : c - a.ncs;
+    const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
+    const int tok0 = cc * a.chunk;
+    if (tok0 >= len) return;
+    const int tok_end = min(len, tok0 + a.chunk);
+    const int n_steps = (tok_end - tok0 + 31) / 32;
+
+    const int n = lane & 15, g4 = lane >> 4;
+    const bool valid_row = n < a.rows;
+    const int nr = min(n, a.rows - 1);
+    const int t_row = nr / a.group;
+    const int hq = h * a.group + nr % a.group;
+    const int limit = is_src ? len : max(len - a.q_len + t_row + 1, 0);
+    const int limit_min = is_src ? len : max(len - a.q_len + 1, 0);
+    bf16x2 ones2;
+    ones2[0] = (__bf16)1.f;
+    ones2[1] = (__bf16)1.f;
+
+    // query fragments: k-step j = 2 jj + u holds head dims 64 jj + 16 g4 + 8 u + e
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D;
+        const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+        const int pos = max(len_r - a.q_len + t_row, 0);
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            const int d0 = 64 * (j >> 1) + 16 * g4 + 8 * (j & 1);
+            qf[j] = *reinterpret_cast<const bf16x8*>(qp + d0);
+            if (a.rope) {
+                // rotation pair of head dim d: (d, d + D/2); both halves come straight from memory
+                const bool upper = d0 >= D / 2;
+                const bf16x8 other = *reinterpret_cast<const bf16x8*>(qp + (upper ? d0 - D / 2 : d0 + D / 2));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float cs, sn;
+                    rope_cos_sin(pos, a.freq.f[(upper ? d0 - D / 2 : d0) + e], &cs, &sn);
+                    const float x = float(qf[j][e]), y = float(other[e]);
+                    qf[j][e] = (__bf16)(upper ? x * cs + y * sn : x * cs - y * sn);
+                }
+            }
+        }
+    }
+    f32x4 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr float kLazyRise = 8.f;
+    float m_ref = 0.f, l_run = 0.f;
+    bool has_ref = false;
+
+    const int last_page = (tok_end - 1) / kPage - tok0 / kPage;
+    int my_page = cv.page_table[int64_t(b) * cv.max_pages + tok0 / kPage + min(lane, last_page)];
+    my_page = min(max(my_page, 0), cv.n_pages - 1);
+    const int64_t page_k = int64_t(cv.n_kv_heads) * C16 * (kPage * 16);      // bytes
+    const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
+    const int64_t page_s = int64_t(cv.n_kv_heads) * kPage;                   // floats
+    const bool k_second_page = (n >> 3) != 0;
+    const uint8_t* k_lane = reinterpret_cast<const uint8_t*>(cv.k_pool) + int64_t(h) * C16 * (kPage * 16) + g4 * (kPage * 16) +
+                            (8 * ((n >> 2) & 1) + (n & 3)) * 16;
+    const bool v_second_page = (g4 >> 1) != 0;
+    const uint8_t* v_lane = reinterpret_cast<const uint8_t*>(cv.v_pool) + int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
+    const int s_lane = h * kPage + 8 * (g4 & 1);
+
+    auto column_max = [&](float x) {
+        float a1 = x, b1 = x;
+        asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a1), "+v"(b1));
+        float a2 = fmaxf(a1, b1), b2 = a2;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a2), "+v"(b2));
+        return fmaxf(a2, b2);
+    };
+
+    for (int s = 0; s < n_steps; ++s) {
+        const int id0 = __builtin_amdgcn_readlane(my_page, min(2 * s, last_page));
+        const int id1 = __builtin_amdgcn_readlane(my_page, min(2 * s + 1, last_page));
+        const uint8_t* kp = k_lane + int64_t(k_second_page ? id1 : id0) * page_k;
+        const uint8_t* vp = v_lane + int64_t(v_second_page ? id1 : id0) * page_v;
+        const int64_t sp = int64_t(v_second_page ? id1 : id0) * page_s + s_lane;
+        u32x4 kx[KP], ky[KP];
+        u32x2 vv8[DB];
+#pragma unroll
+        for (int jj = 0; jj < KP; ++jj) {
+            kx[jj] = *reinterpret_cast<const u32x4*>(kp + 4 * jj * (kPage * 16));
+            ky[jj] = *reinterpret_cast<const u32x4*>(kp + 4 * jj * (kPage * 16) + 4 * 16);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) vv8[db] = *reinterpret_cast<const u32x2*>(vp + db * 16 * kPage);
+        f32x4 ks[2], vs[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            ks[u] = *reinterpret_cast<const f32x4*>(cv.k_scale + sp + 4 * u);
+            vs[u] = *reinterpret_cast<const f32x4*>(cv.v_scale + sp + 4 * u);
+        }
+
+        const int first = tok0 + 32 * s + 8 * g4;
+        f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            const int jj = j >> 1, u = j & 1;
+            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(kx[jj][2 * u], kx[jj][2 * u + 1]), qf[j], sx, 0, 0, 0);
+            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(ky[jj][2 * u], ky[jj][2 * u + 1]), qf[j], sy, 0, 0, 0);
+        }
+        const bool reaches_limit = tok0 + 32 * s + 32 > limit_min;      // uniform
+        float t[8], vsc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            t[e] = fmaf(e < 4 ? sx[e] : sy[e - 4], ks[e >> 2][e & 3] * a.scale_log2, -m_ref);
+            vsc[e] = vs[e >> 2][e & 3];
+        }
+        if (reaches_limit) {
+            // slots past the visible length hold anything (scales included): remove them by index
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                t[e] = first + e < limit ? t[e] : -INFINITY;
+                vsc[e] = first + e < len ? vsc[e] : 0.f;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mx = fmaxf(mx, t[e]);
+        if (__any(mx > kLazyRise || (!has_ref && mx > -INFINITY))) {
+            const float rise = column_max(mx);
+            const bool move = has_ref ? rise > 0.f : rise > -INFINITY;
+            const float shift = move ? rise : 0.f;
+            const float alpha = has_ref ? __builtin_amdgcn_exp2f(-shift) : 1.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] -= shift;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o_acc[db][i] *= alpha;
+            m_ref += shift;
+            has_ref = has_ref || move;
+        }
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(t[e]), p1 = __builtin_amdgcn_exp2f(t[e + 1]);
+            bf16x2 p2;
+            p2[0] = (__bf16)p0;
+            p2[1] = (__bf16)p1;
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, l_run, false);
+            pb[e] = (__bf16)(p0 * vsc[e]);
+            pb[e + 1] = (__bf16)(p1 * vsc[e + 1]);
+        }
+        u32x4 keep = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+        if (tok0 + 32 * s + 32 > len) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                keep[e] = (first + 2 * e < len ? 0x0000ffffu : 0u) | (first + 2 * e + 1 < len ? 0xffff0000u : 0u);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const u32x4 vb = __builtin_bit_cast(u32x4, e4m3x8_to_bf16(vv8[db][0], vv8[db][1])) & keep;
+            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vb), pb, o_acc[db], 0, 0, 0);
+        }
+    }
+
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (!valid_row) return;
+    const int64_t slot = ((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n;
+    float* po = a.part_o + slot * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db + 4 * g4) = o_acc[db];
+    if (g4 == 0) {
+        a.part_ml[slot * 2] = has_ref ? m_ref : -INFINITY;
+        a.part_ml[slot * 2 + 1] = l_tot;
+    }
+}
+
 // One wave (one workgroup) per (sequence, query row, query head): log-sum-exp merge of the
 // partials of both caches, in a fixed order (run-to-run identical results).  The partial rows are
 // fetched 32 at a time with independent loads -- one memory round trip per batch instead of one
@@ -565,20 +764,24 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     if (!out || !q || !caches || !lens) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null pointer");
     if (!lens->src_visible_len || !lens->rsn_len) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null length vector");
     if (!aligned16(out) || !aligned16(q)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: q / out must be 16-byte aligned");
-    st_status r = check_cache(caches->source, "st_attn_decode_dual", "source");
+    st_status r = check_cache(caches->source, "st_attn_decode_dual", "source", true);
     if (r != ST_OK) return r;
-    r = check_cache(caches->reasoning, "st_attn_decode_dual", "reasoning");
+    r = check_cache(caches->reasoning, "st_attn_decode_dual", "reasoning", true);
     if (r != ST_OK) return r;
     const st_kv_cache& cs = caches->source;
     const st_kv_cache& cr = caches->reasoning;
     if (cs.n_kv_heads != cr.n_kv_heads || cs.head_dim != cr.head_dim)
         return fail(ST_ERR_SHAPE, "st_attn_decode_dual: the two caches differ in head geometry");
+    if (cs.dtype != cr.dtype) return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual: the two caches differ in dtype");
+    const bool fp8 = cs.dtype == ST_FP8_E4M3;
     const int hkv = cs.n_kv_heads, d = cs.head_dim;
     if (batch <= 0 || n_q_heads <= 0 || n_q_heads % hkv != 0)
         return fail(ST_ERR_SHAPE, "st_attn_decode_dual: n_q_heads %d must be a positive multiple of n_kv_heads %d", n_q_heads, hkv);
     const int group = n_q_heads / hkv;
     if (lens->q_len <= 0 || lens->q_len * group > 32)
         return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual: q_len %d x group %d must be in 1..32", lens->q_len, group);
+    if (fp8 && lens->q_len * group > 16)
+        return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual: 8-bit caches take q_len %d x group %d up to 16", lens->q_len, group);
     if (lens->max_src_len < 0 || lens->max_rsn_len < 0) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: negative length bound");
     if (int64_t(lens->max_src_len) > int64_t(cs.max_pages_per_seq) * kPage || int64_t(lens->max_rsn_len) > int64_t(cr.max_pages_per_seq) * kPage)
         return fail(ST_ERR_CAPACITY, "st_attn_decode_dual: length bound exceeds the page table");
@@ -627,7 +830,10 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
         if (a.rows <= 16) {
             if (units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
             prof_begin(kProfDecodeSplit, s);
-            if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
+            if (fp8) {
+                if (d == 64) hipLaunchKernelGGL((decode_split16_fp8_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
+                else hipLaunchKernelGGL((decode_split16_fp8_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
+            } else if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
             else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
             prof_end(kProfDecodeSplit, s);
         } else {

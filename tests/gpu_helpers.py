@@ -23,8 +23,8 @@ def to_f64(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def make_cache(batch, max_pages_per_seq, n_kv_heads, head_dim, rng, fill=None):
+def make_cache(batch, max_pages_per_seq, n_kv_heads, head_dim, rng, fill=None, fp8=False):
     """A cache with a shuffled page table and pools of exactly batch * max_pages pages."""
     table = W.shuffled_page_table(rng, batch, max_pages_per_seq)
     return st.KVCache(batch * max_pages_per_seq, batch, max_pages_per_seq, n_kv_heads, head_dim,
-                      torch.from_numpy(table).to(DEV), fill=fill), table
+                      torch.from_numpy(table).to(DEV), fill=fill, fp8=fp8), table

@@ -94,6 +94,20 @@ def test_cache_argument_checks(lib):
     assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 1.0e6, fp, 1 << 20, None) == 2
     assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 64, 1, 8, 0.0, 0.0, fp, 1 << 20, None) == 1
     assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 65, 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 4
+    # 8-bit caches: need their scale arrays; append (unfused) and decode up to 16 rows take them, nothing else does
+    c8 = lambda **kw: cache(dtype=B.ST_FP8_E4M3, k_scale=fake, v_scale=fake, **kw)
+    eight = B._DualCacheStruct(c8(), c8())
+    assert lib.st_kv_append(C.byref(eight), B.ST_SOURCE, fp, fp, None, 8, 1, 65, None) == 4          # passes the dtype check
+    assert lib.st_kv_append(C.byref(B._DualCacheStruct(cache(dtype=B.ST_FP8_E4M3), c8())), B.ST_SOURCE, fp, fp, None, 8, 1, 64, None) == 1
+    assert b"scale" in lib.st_last_error()
+    assert lib.st_kv_append_rope(C.byref(eight), B.ST_SOURCE, fp, fp, None, 8, 1, 64, 1.0e6, None) == 5
+    assert lib.st_attn_source_chunk(fp, None, fp, C.byref(eight), fp, None, 8, 64, 1, 8, 0.0, fp, 1 << 20, None) == 5
+    lens = B._DualLensStruct(fake, fake, 5, 64, 64)                                                  # 5 x group 4 = 20 rows
+    assert lib.st_attn_decode_dual(fp, None, fp, C.byref(eight), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 5
+    assert b"16" in lib.st_last_error()
+    lens = B._DualLensStruct(fake, fake, 1, 64, 64)
+    mixed = B._DualCacheStruct(c8(), cache())
+    assert lib.st_attn_decode_dual(fp, None, fp, C.byref(mixed), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 5
 
 
 def test_stream_timeline_matches_oracle():

@@ -320,19 +320,24 @@ def test_prefill_bwd_is_deterministic_and_checks_arguments(st):
 
 
 # ------------------------------------------------------- append / decode --
-def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3), rope_theta=None):
+def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3), rope_theta=None, fp8=False,
+               row_exponents=None):
     """Fill both caches through st_kv_append in uneven chunks; returns caches and the oracle's contiguous copies.
     With rope_theta the keys go in UNROTATED through st_kv_append_rope, and the oracle's copy of K is what
     paged_append_rotated stores: RoPE(k, index in the cache), in fp64."""
     pages_s = (int(max(src_lens)) + src_extra + 15) // 16 + 1
     pages_r = (int(max(rsn_lens)) + 15) // 16 + 1
-    cs, tab_s = make_cache(batch, pages_s, hkv, d, rng, fill=float("nan"))
-    cr, tab_r = make_cache(batch, pages_r, hkv, d, rng, fill=float("nan"))
+    # never-written slots keep a fill that would poison any result: NaN (0x7f is the E4M3 NaN code; scales get NaN too)
+    cs, tab_s = make_cache(batch, pages_s, hkv, d, rng, fill=0x7f if fp8 else float("nan"), fp8=fp8)
+    cr, tab_r = make_cache(batch, pages_r, hkv, d, rng, fill=0x7f if fp8 else float("nan"), fp8=fp8)
     caches = st.DualCache(cs, cr)
     ref = {}
     for which, lens, cache in ((st.ST_SOURCE, src_lens, cs), (st.ST_REASONING, rsn_lens, cr)):
         total = int(max(lens)) if len(lens) else 0
         kk = W.normal(rng, (batch, total, hkv, d), "bf16"); vv = W.normal(rng, (batch, total, hkv, d), "bf16")
+        if row_exponents is not None:                        # rows of very different magnitude (exact: powers of two)
+            kk = np.ldexp(kk, rng.integers(row_exponents[0], row_exponents[1] + 1, (batch, total, hkv, 1))).astype(np.float32)
+            vv = np.ldexp(vv, rng.integers(row_exponents[0], row_exponents[1] + 1, (batch, total, hkv, 1))).astype(np.float32)
         ref[which] = (kk, vv)
         done = np.zeros(batch, np.int64); ci = 0
         while (done < lens).any():
@@ -397,8 +402,12 @@ def test_kv_append_capacity(st):
     assert cs.appended_len.cpu().tolist() == [32, 32]
 
 
-def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0, rope_theta=None):
-    caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra, rope_theta=rope_theta)
+def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0, rope_theta=None, fp8=False):
+    if fp8:
+        # 8-bit caches take rotated keys (the fused append is bf16 only); the fused QUERY rotation works on either
+        caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra, fp8=True, row_exponents=(-4, 1))
+    else:
+        caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra, rope_theta=rope_theta)
     q = W.normal(rng, (batch, q_len, hq, d), "bf16")
     tq = to_dev(q, "bf16")
     lse = torch.empty((batch, q_len, hq), dtype=torch.float32, device=DEV)
@@ -408,17 +417,24 @@ def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len
     for b in range(batch):
         args = (q[b].astype(np.float64), ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
                 ref[st.ST_REASONING][1][b], int(src_vis[b]), int(rsn_lens[b]))
-        if rope_theta is None:
+        if fp8:
+            if rope_theta is not None and rsn_lens[b] < q_len:
+                continue
+            qa = args[0] if rope_theta is None else O.rope(args[0], int(rsn_lens[b]) - q_len + np.arange(q_len), rope_theta)
+            o_ref, l_ref = O.decode_dual_fp8(qa, *args[1:])
+        elif rope_theta is None:
             o_ref, l_ref = O.decode_dual_concat(*args)
         elif rsn_lens[b] >= q_len:
             o_ref, l_ref = O.decode_dual_rotated(*args, rope_theta)
         else:
             continue          # fewer cached reasoning tokens than query rows: positions undefined
-        assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
+        # (the 8-bit cases scale value rows by up to 2, so outputs exceed 1: the bound follows the bf16 grid there)
+        assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2 * (max(1.0, np.abs(o_ref).max()) if fp8 else 1.0), b
         got_l = to_f64(lse[b])
         both = np.isfinite(l_ref)
         assert np.array_equal(np.isfinite(got_l), both)
-        assert np.abs(got_l[both] - l_ref[both]).max(initial=0.0) <= 2e-2
+        # (8-bit cases: key rows up to twice the unit scale, and the scores' rounding error with them)
+        assert np.abs(got_l[both] - l_ref[both]).max(initial=0.0) <= (4e-2 if fp8 else 2e-2)
     return caches, tq, out
 
 
@@ -438,6 +454,91 @@ def test_decode_head_dim_64_and_group_4(st):
 def test_decode_q_len_8(st):
     rng = np.random.Generator(np.random.PCG64(412))
     _check_decode(st, rng, 3, 8, 2, 128, np.array([64, 10, 290]), np.array([8, 300, 40]), np.array([64, 0, 290]), q_len=8)
+
+
+# ------------------------------------------------------- 8-bit caches --
+def test_kv_append_fp8_codes_and_scales_are_the_oracles(st):
+    """Bytes and scales in the pools == the oracle's E4M3 codes and powers of two, bit for bit; untouched slots keep the fill."""
+    rng = np.random.Generator(np.random.PCG64(440))
+    for batch, hkv, d, src_lens, rsn_lens in ((3, 2, 128, np.array([70, 33, 16]), np.array([5, 100, 48])),
+                                               (2, 3, 64, np.array([17, 1]), np.array([64, 31]))):
+        caches, ref, (tab_s, tab_r) = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, fp8=True, row_exponents=(-14, 14))
+        for which, cache, lens, tab in ((st.ST_SOURCE, caches.source, src_lens, tab_s), (st.ST_REASONING, caches.reasoning, rsn_lens, tab_r)):
+            kl = st.k_pool8_to_logical(cache.k_pool).cpu().numpy(); vl = st.v_pool_to_logical(cache.v_pool).cpu().numpy()
+            ksl = st.scale_to_logical(cache.k_scale).cpu().numpy(); vsl = st.scale_to_logical(cache.v_scale).cpu().numpy()
+            written = np.zeros(kl.shape[:2], bool)
+            for b in range(batch):
+                n = int(lens[b])
+                for name, pool, scl, rows in (("k", kl, ksl, ref[which][0][b, :n]), ("v", vl, vsl, ref[which][1][b, :n])):
+                    codes, k = O.quantize_rows_e4m3(rows.astype(np.float64))
+                    got_c = O.paged_gather(pool, tab, b, n); got_s = O.paged_gather(scl, tab, b, n)
+                    # -0 and +0 are the same value: compare values where the oracle's code is a zero, bytes elsewhere
+                    assert np.array_equal(got_c & 0x7f, codes & 0x7f), (which, b, name)
+                    nz = (codes & 0x7f) != 0
+                    assert np.array_equal(got_c[nz], codes[nz]), (which, b, name)
+                    assert np.array_equal(got_s.astype(np.float64), np.ldexp(1.0, k)), (which, b, name)
+                for p in range(n):
+                    written[tab[b][p // 16], p % 16] = True
+            assert np.all(kl[~written] == 0x7f) and np.all(vl[~written] == 0x7f)
+            assert np.all(np.isnan(ksl[~written])) and np.all(np.isnan(vsl[~written]))
+    # boundary rows: the largest magnitude exactly 448 2^k, just above it, 1.75 (mantissa boundary), an all-zero row
+    cs, _ = make_cache(1, 2, 1, 64, rng, fp8=True); cr, _ = make_cache(1, 2, 1, 64, rng, fp8=True)
+    rows = np.zeros((1, 5, 1, 64), np.float32)
+    rows[0, 0, 0, :4] = [448.0, -3.0, 0.001953125, 13.0]; rows[0, 1, 0, :3] = [450.0, 1.0, -225.0]
+    rows[0, 2, 0, :3] = [1.75, -1.0, 0.9375]; rows[0, 3, 0, :2] = [2.0 ** -40, 3 * 2.0 ** -44]
+    dc = st.DualCache(cs, cr)
+    st.st_kv_append(dc, st.ST_SOURCE, to_dev(rows, "bf16"), to_dev(-rows, "bf16"))
+    torch.cuda.synchronize()
+    tab = cs.page_table.cpu().numpy()
+    codes, k = O.quantize_rows_e4m3(W.bf16_round(rows[0]).astype(np.float64))
+    got = O.paged_gather(st.k_pool8_to_logical(cs.k_pool).cpu().numpy(), tab, 0, 5)
+    assert np.array_equal(got & 0x7f, codes & 0x7f) and np.array_equal(got[(codes & 0x7f) != 0], codes[(codes & 0x7f) != 0])
+    assert np.array_equal(O.paged_gather(st.scale_to_logical(cs.k_scale).cpu().numpy(), tab, 0, 5).astype(np.float64), np.ldexp(1.0, k))
+    assert k[:, 0].tolist() == [0, 1, -8, -48, 0]
+    gotv = O.paged_gather(st.v_pool_to_logical(cs.v_pool).cpu().numpy(), tab, 0, 5)
+    assert np.array_equal(O.e4m3_decode(gotv), -O.e4m3_decode(got))
+
+
+def test_decode_fp8_small_ragged(st):
+    rng = np.random.Generator(np.random.PCG64(441))
+    src_lens = np.array([70, 33, 16, 300, 1]); rsn_lens = np.array([5, 100, 48, 257, 1])
+    src_vis = np.array([0, 15, 16, 17, 1])
+    _check_decode(st, rng, 5, 4, 2, 128, src_lens, rsn_lens, src_vis, fp8=True)
+
+
+def test_decode_fp8_head_dim_64_group_4_and_long_units(st):
+    rng = np.random.Generator(np.random.PCG64(442))
+    _check_decode(st, rng, 2, 8, 2, 64, np.array([100, 1100]), np.array([1500, 31]), np.array([100, 1030]), fp8=True)
+
+
+@pytest.mark.parametrize("q_len,hq,hkv,d", [(8, 4, 2, 128), (1, 4, 2, 128), (3, 4, 1, 64)])
+def test_decode_fp8_several_rows_and_fused_query_rotation(st, q_len, hq, hkv, d):
+    rng = np.random.Generator(np.random.PCG64(443 + q_len + d))
+    args = (3, hq, hkv, d, np.array([64, 10, 290]), np.array([8, 300, 40]), np.array([64, 0, 290]))
+    _check_decode(st, rng, *args, q_len=q_len, fp8=True)
+    _check_decode(st, rng, *args, q_len=q_len, fp8=True, rope_theta=1.0e6)
+
+
+def test_decode_fp8_is_the_bf16_decode_of_the_stored_values(st):
+    """Same tokens through an 8-bit and a bf16 cache pair holding the DEQUANTISED values: the two kernels agree to rounding."""
+    rng = np.random.Generator(np.random.PCG64(447))
+    batch, hq, hkv, d = 2, 4, 2, 128
+    src_lens, rsn_lens = np.array([200, 77]), np.array([130, 600])
+    state = rng.bit_generator.state
+    c8, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, fp8=True)
+    rng.bit_generator.state = state
+    c16, _, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens)
+    rq = lambda a: O.dequantize_rows_e4m3(*O.quantize_rows_e4m3(a.astype(np.float64))).astype(np.float32)
+    for which, cache, lens in ((st.ST_SOURCE, c16.source, src_lens), (st.ST_REASONING, c16.reasoning, rsn_lens)):
+        cache.appended_len.zero_()
+        st.st_kv_append(c16, which, to_dev(rq(ref[which][0]), "bf16"), to_dev(rq(ref[which][1]), "bf16"),
+                        torch.from_numpy(lens.astype(np.int32)).to(DEV))
+    q = to_dev(W.normal(rng, (batch, 1, hq, d), "bf16"), "bf16")
+    sl = torch.from_numpy(src_lens.astype(np.int32)).to(DEV); rl = torch.from_numpy(rsn_lens.astype(np.int32)).to(DEV)
+    o8 = st.st_attn_decode_dual(q, c8, sl, rl, 200, 600)
+    o16 = st.st_attn_decode_dual(q, c16, sl, rl, 200, 600)
+    torch.cuda.synchronize()
+    assert (o8.float() - o16.float()).abs().max().item() <= 4e-3
 
 
 def test_kv_append_rope_matches_oracle_and_unfused_path(st):
