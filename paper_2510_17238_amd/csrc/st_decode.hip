@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 // ids are clamped into the pool); what lies beyond the visible length is removed afterwards by
 // index: scores by select, V by bit mask.
 template <int D>
-__global__ __launch_bounds__(64, 16) void decode_split16_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
     const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr;
@@ -424,7 +424,7 @@ __device__ __forceinline__ bf16x8 e4m3x8_to_bf16(uint32_t lo, uint32_t hi) {
 }
 
 template <int D>
-__global__ __launch_bounds__(64, 16) void decode_split16_fp8_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64, 4) void decode_split16_fp8_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, KP = D / 64, DB = D / 16, C16 = D / 16;
     const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr;
