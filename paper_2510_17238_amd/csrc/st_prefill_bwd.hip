@@ -328,9 +328,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
 // so that the key-side kernel fetches them with ONE asynchronous copy per tile.  delta is also written in
 // token order for the query-side kernel.
 template <int D>
-__global__ __launch_bounds__(64) void bwd_rowstats_kernel(float* __restrict__ stats, float* __restrict__ delta_tok,
-                                                         const uint16_t* __restrict__ d_out, const uint16_t* __restrict__ out,
-                                                         const float* __restrict__ lse, PlanView pv, int n_q_heads) {
+__global__ __launch_bounds__(256) void bwd_rowstats_kernel(float* __restrict__ stats, float* __restrict__ delta_tok,
+                                                          const uint16_t* __restrict__ d_out, const uint16_t* __restrict__ out,
+                                                          const float* __restrict__ lse, PlanView pv, int n_q_heads) {
+    constexpr int PER = D / 4;                                   // elements per thread: 4 threads share a row
     const int tile = blockIdx.x / n_q_heads;
     const int h = blockIdx.x % n_q_heads;
     const int b = find_seq(pv.pack_base, pv.batch, tile);
@@ -342,20 +343,26 @@ __global__ __launch_bounds__(64) void bwd_rowstats_kernel(float* __restrict__ st
     const int kt = src ? lt : lt - ts;
     const int base = t0 + (src ? 0 : S) + kt * kTileN;
     const int valid = min(kTileN, (src ? S : R) - kt * kTileN);
-    const int r = threadIdx.x;
+    const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
     float l2 = INFINITY, dl = 0.f;
     int vs = 0;
+    int64_t rh = 0;
     if (r < valid) {
         const int tok = pv.perm[base + r];
-        const int64_t rh = int64_t(tok) * n_q_heads + h;
-        const uint16_t* a = d_out + rh * D;
-        const uint16_t* o = out + rh * D;
+        rh = int64_t(tok) * n_q_heads + h;
+        const uint16_t* a = d_out + rh * D + part * PER;
+        const uint16_t* o = out + rh * D + part * PER;
 #pragma unroll
-        for (int c = 0; c < D / 8; ++c) {
+        for (int c = 0; c < PER / 8; ++c) {
             const bf16x8 x = *reinterpret_cast<const bf16x8*>(a + 8 * c), y = *reinterpret_cast<const bf16x8*>(o + 8 * c);
 #pragma unroll
             for (int e = 0; e < 8; ++e) dl = fmaf(float(x[e]), float(y[e]), dl);
         }
+    }
+    dl += __shfl_xor(dl, 1);
+    dl += __shfl_xor(dl, 2);
+    if (part != 0) return;
+    if (r < valid) {
         l2 = lse[rh] * kLog2e;
         vs = pv.vis[base + r];
         delta_tok[rh] = dl;
@@ -706,7 +713,7 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
                            (const uint16_t*)q, pv, n_q_heads);
         hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.dorows), at(L.dotr), (const uint16_t*)d_out,
                            (const uint16_t*)d_out, pv, n_q_heads);
-        hipLaunchKernelGGL((bwd_rowstats_kernel<HD>), dim3(q_tiles), dim3(64), 0, s, stats, delta, (const uint16_t*)d_out,
+        hipLaunchKernelGGL((bwd_rowstats_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, stats, delta, (const uint16_t*)d_out,
                            (const uint16_t*)out, lse, pv, n_q_heads);
         const size_t smem_q = sizeof(BwdDqSmem<HD>), smem_k = sizeof(BwdDkvSmem<HD>);
         ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dq_mfma_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem_q)));

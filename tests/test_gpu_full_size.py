@@ -104,16 +104,24 @@ def test_config4b_prefill_128_pairs(st):
     _prefill_full(st, W.config4b(), meta_seqs=(3,), n_extra=12)
 
 
-def _decode_full(st, shp, q_len, check_seqs, seed):
+def _decode_full(st, shp, q_len, check_seqs, seed, fp8=False):
     B, hq, hkv, d = shp.batch, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
     rng = np.random.Generator(np.random.PCG64(seed))
     pages_s = (shp.max_src_len + 15) // 16; pages_r = (shp.max_rsn_len + 15) // 16
     tab_s = W.shuffled_page_table(rng, B, pages_s); tab_r = W.shuffled_page_table(rng, B, pages_r)
-    cs = st.KVCache(B * pages_s, B, pages_s, hkv, d, torch.from_numpy(tab_s).to(DEV))
-    cr = st.KVCache(B * pages_r, B, pages_r, hkv, d, torch.from_numpy(tab_r).to(DEV))
+    cs = st.KVCache(B * pages_s, B, pages_s, hkv, d, torch.from_numpy(tab_s).to(DEV), fp8=fp8)
+    cr = st.KVCache(B * pages_r, B, pages_r, hkv, d, torch.from_numpy(tab_r).to(DEV), fp8=fp8)
     g = torch.Generator(device=DEV); g.manual_seed(seed)
     for c in (cs, cr):       # any bit pattern is a valid cache content: draw the pools directly
-        c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
+        if fp8:
+            # any code but the two NaN codes (0x7f, 0xff), scales 2^-9 .. 2^-6 (values up to +-7)
+            for pool in (c.k_pool, c.v_pool):
+                pool.random_(0, 256, generator=g)
+                pool[(pool & 0x7f) == 0x7f] = 0x3a
+            for sc in (c.k_scale, c.v_scale):
+                sc.copy_(torch.ldexp(torch.ones_like(sc), torch.randint(-9, -5, sc.shape, generator=g, device=DEV)))
+        else:
+            c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
     caches = st.DualCache(cs, cr)
     # the step itself: append the q_len new reasoning tokens, then attend
     rsn_before = (shp.rsn_len - q_len).astype(np.int32)
@@ -136,12 +144,25 @@ def _decode_full(st, shp, q_len, check_seqs, seed):
     for b in check_seqs:
         def gather(cache, tab, length):
             ids = torch.from_numpy(tab[b, :(length + 15) // 16].astype(np.int64)).to(DEV)
+            if fp8:          # stored values: code x scale
+                kc = st.k_pool8_to_logical(cache.k_pool[ids]).reshape(-1, hkv, d)[:length].cpu().numpy()
+                vc = st.v_pool_to_logical(cache.v_pool[ids]).reshape(-1, hkv, d)[:length].cpu().numpy()
+                ks = st.scale_to_logical(cache.k_scale[ids]).reshape(-1, hkv)[:length].cpu().numpy().astype(np.float64)
+                vs = st.scale_to_logical(cache.v_scale[ids]).reshape(-1, hkv)[:length].cpu().numpy().astype(np.float64)
+                return O.e4m3_decode(kc) * ks[..., None], O.e4m3_decode(vc) * vs[..., None]
             kl = st.k_pool_to_logical(cache.k_pool[ids]).reshape(-1, hkv, d)[:length]
             vl = st.v_pool_to_logical(cache.v_pool[ids]).reshape(-1, hkv, d)[:length]
             return to_f64(kl), to_f64(vl)
         sk, sv = gather(cs, tab_s, int(shp.src_visible_len[b]))
         rk, rv = gather(cr, tab_r, int(shp.rsn_len[b]))
         # the appended tokens really are the last q_len rows of the reasoning cache
+        if fp8:
+            stored = lambda x: O.dequantize_rows_e4m3(*O.quantize_rows_e4m3(to_f64(x)))
+            assert np.array_equal(rk[-q_len:], stored(k_tok[b])) and np.array_equal(rv[-q_len:], stored(v_tok[b]))
+            o_ref, l_ref = O.decode_dual_fp8(to_f64(q[b]), sk, sv, rk, rv, int(shp.src_visible_len[b]), int(shp.rsn_len[b]))
+            assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2 * max(1.0, np.abs(o_ref).max()), b
+            assert np.abs(to_f64(lse[b]) - l_ref).max() <= 4e-2, b
+            continue
         assert np.array_equal(rk[-q_len:], to_f64(k_tok[b])) and np.array_equal(rv[-q_len:], to_f64(v_tok[b]))
         o_ref, l_ref = O.decode_dual_concat(to_f64(q[b]), sk, sv, rk, rv, int(shp.src_visible_len[b]), int(shp.rsn_len[b]))
         assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
@@ -153,6 +174,38 @@ def test_config3_decode_one_layer(st):
     shp = W.config3()
     longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
     _decode_full(st, shp, 1, sorted({0, 7, longest, shortest}), seed=31)
+
+
+def test_config3_decode_one_layer_8bit_caches(st):
+    """The same step over caches stored in 8 bits (codes drawn at random, the step's own token quantised by the append)."""
+    shp = W.config3()
+    longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
+    _decode_full(st, shp, 1, sorted({3, longest, shortest}), seed=32, fp8=True)
+
+
+def test_config2_prefill_backward(st):
+    """Gradients of the attention stage on the benchmark batch (configs[1]) at full size, through the matrix-core
+    kernels: every row of dQ and every key of dK / dV of two (sequence, KV head) picks against the oracle."""
+    cfg = W.config2()
+    hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
+    q = _device_normal((n, hq, d), cfg.seed + 10); k = _device_normal((n, hkv, d), cfg.seed + 11)
+    v = _device_normal((n, hkv, d), cfg.seed + 12); go = _device_normal((n, hq, d), cfg.seed + 13)
+    seg, strm, pos = ids_to_dev(cfg)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    lse = torch.empty((n, hq), dtype=torch.float32, device=DEV)
+    out = st.st_attn_prefill(q, k, v, plan, lse=lse)
+    dq, dk, dv = st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
+    group = hq // hkv
+    for b, hk in ((0, 0), (cfg.batch - 1, hkv - 1)):
+        s, e = int(cfg.cu_seqlens[b]), int(cfg.cu_seqlens[b + 1])
+        hs = slice(hk * group, (hk + 1) * group)
+        rq, rk, rv = O.attention_dense_backward(to_f64(q[s:e, hs]), to_f64(k[s:e, hk:hk + 1]), to_f64(v[s:e, hk:hk + 1]),
+                                                to_f64(go[s:e, hs]), cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e])
+        for name, got, ref in (("dq", dq[s:e, hs], rq), ("dk", dk[s:e, hk:hk + 1], rk), ("dv", dv[s:e, hk:hk + 1], rv)):
+            err = np.abs(to_f64(got) - ref).max()
+            assert err <= 6e-2 * max(1.0, np.abs(ref).max()), (b, hk, name, err, np.abs(ref).max())
 
 
 def test_config5_stream_step_one_layer(st):
