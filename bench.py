@@ -237,6 +237,35 @@ def bench_stream_session(st, torch, W, time_scale):
                                                 "the paper reports 6.231 s (streaming) vs 28.003 s (batch) for the whole model"}}
 
 
+def bench_probes(st, torch):
+    """What this GPU sustains for the decode kernel's access pattern and for the prefill kernel's MFMA instruction."""
+    dev = "cuda"
+    pool = torch.empty(1 << 31, dtype=torch.uint8, device=dev)
+    pool.random_(0, 256)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    fsink = torch.zeros(4, dtype=torch.float32, device=dev)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    res = {}
+    # the decode kernel's launch on configs[2]: about 2,800 one-wave units of up to 1024 tokens x 4 KB;
+    # and a launch four times as large
+    for name, waves, steps in (("paged_read_decode_sized", 2816, 16), ("paged_read_large", 11264, 16)):
+        for _ in range(3):
+            st.st_probe_paged_read(pool, waves, steps, sink)
+        e0.record()
+        for _ in range(20):
+            st.st_probe_paged_read(pool, waves, steps, sink)
+        e1.record(); torch.cuda.synchronize()
+        res[name] = {"bytes_per_launch": waves * steps * 16384, "GBps": round(waves * steps * 16384 * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)}
+    st.st_probe_mfma_bf16(512, 2000, fsink)
+    torch.cuda.synchronize()
+    iters = 200000
+    e0.record(); st.st_probe_mfma_bf16(512, iters, fsink); e1.record(); torch.cuda.synchronize()
+    res["mfma_bf16_registers_only"] = {"ms": round(e0.elapsed_time(e1), 2),
+                                       "TFLOPs": round(512 * 4 * iters * 8 * 32768.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)}
+    del pool
+    return res
+
+
 def bench_prefill_backward(st, torch, W, reps):
     """Forward + backward of the attention stage on configs[1] (the plain backward path)."""
     dev = "cuda"
@@ -434,6 +463,9 @@ def main():
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     ap.add_argument("--long-prefill", action="store_true",
                     help="also time the attention kernel on configs[3] (8 x 16,384 tokens) and report it under 'prefill_long'")
+    ap.add_argument("--probes", action="store_true",
+                    help="also run the machine probes (paged read with the decode kernel's access pattern, register-only "
+                         "bf16 MFMA loop) and report them under 'probes'")
     ap.add_argument("--fp8-cache", action="store_true",
                     help="also run the decode workload with 8-bit (E4M3) caches and report it under 'decode_fp8'")
     ap.add_argument("--backward", action="store_true",
@@ -509,6 +541,8 @@ def main():
             "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
             "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
                     "each of which streams the cache again"}
+    if args.probes:
+        line["probes"] = bench_probes(st, torch)
     if args.fp8_cache and not args.no_decode:
         d8 = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph, fp8=True)
         g8_step = d8["bytes_per_step"] / d8["sec_per_step"] / 1e9

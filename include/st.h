@@ -80,6 +80,21 @@ enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1, ST_PROF_BWD_DQ = 2, S
 void st_profile_enable(int32_t on);
 st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
 
+/* Machine probes for benchmarks (they compute nothing of the method; callers that only use the
+ * operators never need them).
+ * st_probe_paged_read: n_waves one-wave workgroups each read steps_per_wave x 16 KiB from `pool`
+ *   (device memory, pool_bytes a power of two >= 4 KiB, 16-byte aligned) as the decode kernel
+ *   reads a paged bf16 cache with head_dim 128: four pseudo-random 4 KiB pages per step, 16 loads
+ *   of 16 bytes per lane with its per-lane addressing.  Bytes read per launch =
+ *   n_waves * steps_per_wave * 16384.  sink: device uint32 (practically never written).
+ * st_probe_mfma_bf16: n_workgroups x 4 waves each issue iterations x 8 v_mfma_f32_32x32x16_bf16
+ *   on register operands with random mantissas; flop per launch =
+ *   n_workgroups * 4 * iterations * 8 * 32768.  sink: device float.
+ * Both enqueue one kernel on hip_stream and return; ST_ERR_INVALID_ARG on bad arguments. */
+st_status st_probe_paged_read(const void* pool, size_t pool_bytes, int32_t n_waves,
+                              int32_t steps_per_wave, uint32_t* sink, void* hip_stream);
+st_status st_probe_mfma_bf16(int32_t n_workgroups, int32_t iterations, float* sink, void* hip_stream);
+
 /* ------------------------------------------------------------------------
  * st_rope_apply -- rotary position encoding with caller-supplied (stream-local)
  * position ids.  Sec. 3.2 "Streaming Position Encoding": input tokens and

@@ -80,6 +80,10 @@ def load_library():
     lib.st_version.argtypes = []
     lib.st_prefill_variant_set.restype = i32
     lib.st_prefill_variant_set.argtypes = [i32]
+    lib.st_probe_paged_read.restype = i32
+    lib.st_probe_paged_read.argtypes = [vp, sz, i32, i32, vp, vp]
+    lib.st_probe_mfma_bf16.restype = i32
+    lib.st_probe_mfma_bf16.argtypes = [i32, i32, vp, vp]
     lib.st_profile_enable.restype = None
     lib.st_profile_enable.argtypes = [i32]
     lib.st_profile_read.restype = i32
@@ -184,6 +188,16 @@ ST_PREFILL_AUTO, ST_PREFILL_ONE_HEAD, ST_PREFILL_TWO_HEADS = 0, 1, 2
 def st_prefill_variant_set(variant):
     """Select the bf16 prefill attention kernel; returns the previous setting."""
     return int(load_library().st_prefill_variant_set(int(variant)))
+
+
+def st_probe_paged_read(pool, n_waves, steps_per_wave, sink, stream=None):
+    """pool: uint8 device tensor whose size is a power of two; sink: uint32-sized device tensor."""
+    _check(load_library().st_probe_paged_read(_ptr(pool), pool.numel() * pool.element_size(), int(n_waves), int(steps_per_wave),
+                                              _ptr(sink), _stream(stream)))
+
+
+def st_probe_mfma_bf16(n_workgroups, iterations, sink, stream=None):
+    _check(load_library().st_probe_mfma_bf16(int(n_workgroups), int(iterations), _ptr(sink), _stream(stream)))
 
 
 def st_profile_enable(on):

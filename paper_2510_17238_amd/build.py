@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libst.so")
 
-SOURCES = ["st_error.hip", "st_rope.hip", "st_plan.hip", "st_prefill.hip", "st_prefill_bwd.hip", "st_cache.hip", "st_decode.hip", "st_sched.hip"]
+SOURCES = ["st_error.hip", "st_rope.hip", "st_plan.hip", "st_prefill.hip", "st_prefill_bwd.hip", "st_cache.hip", "st_decode.hip", "st_sched.hip", "st_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950:xnack-", "-O3", "-std=c++17", "-fPIC",
