@@ -1,6 +1,7 @@
 // Error text and version of the C ABI.
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -22,23 +23,27 @@ namespace st {
 namespace {
 struct Region { hipEvent_t a, b; };
 std::mutex g_prof_mutex;
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
 std::vector<Region> g_regions[kProfCount];
 }  // namespace
 
-bool prof_enabled() { return g_prof_on; }
+bool prof_enabled() { return g_prof_on.load(); }
 
 void prof_begin(int which, hipStream_t stream) {
-    if (!g_prof_on) return;
+    if (!g_prof_on.load()) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     Region r{};
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) {
+        (void)hipEventDestroy(r.a);
+        return;
+    }
     (void)hipEventRecord(r.a, stream);
     g_regions[which].push_back(r);
 }
 
 void prof_end(int which, hipStream_t stream) {
-    if (!g_prof_on) return;
+    if (!g_prof_on.load()) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (!g_regions[which].empty()) (void)hipEventRecord(g_regions[which].back().b, stream);
 }
@@ -46,7 +51,7 @@ void prof_end(int which, hipStream_t stream) {
 
 extern "C" void st_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lock(st::g_prof_mutex);
-    st::g_prof_on = on != 0;
+    st::g_prof_on.store(on != 0);
 }
 
 extern "C" st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count) {
