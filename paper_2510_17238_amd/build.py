@@ -19,6 +19,13 @@ FLAGS = [
 ]
 
 
+# per-file extras.  The backward kernels run one wave per SIMD and keep their big accumulators in place; with
+# the matrix instructions writing ordinary vector registers the compiler stops shuttling score blocks
+# through the accumulation registers (12 % on the query-side kernel).  The forward file manages its
+# accumulation registers by hand and must not get this.
+EXTRA_FLAGS = {"st_prefill_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _hipcc():
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
@@ -34,7 +41,7 @@ def build_library(verbose=True):
     procs = []
     for src in SOURCES:
         obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for src, p in procs:

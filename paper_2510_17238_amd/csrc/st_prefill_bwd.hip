@@ -273,16 +273,42 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
         const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? it.n_stream : it.n_src);
         const int limit = in_a ? my_row + 1 : my_vis;
 
+        // operands leave LDS a group of matrix instructions ahead of their use (one wave per SIMD: nobody else hides
+        // that latency); scheduling barriers keep the order
         f32x16 s_acc[SB], dp_acc[SB];
         const uint16_t* kb = &sm.k[buf][0];
         const uint16_t* vb = &sm.v[buf][0];
+        const uint16_t* tb = &sm.kt[buf][0];
+        constexpr int G = 4, NG1 = SB * KS / G, NG2 = DB * SB * 2 / (2 * G);
+        bf16x8 fk[2][G], fv[2][G];
+        auto load1 = [&](int g, int slot) {
 #pragma unroll
-        for (int f = 0; f < SB * KS; ++f) {
-            const int sb = f % SB, j = f / SB;
-            const bf16x8 ak = *reinterpret_cast<const bf16x8*>(kb + 32 * sb * D + koff[j]);
-            const bf16x8 av = *reinterpret_cast<const bf16x8*>(vb + 32 * sb * D + koff[j]);
-            s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
-            dp_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[j], j == 0 ? zero16 : dp_acc[sb], 0, 0, 0);
+            for (int u = 0; u < G; ++u) {
+                const int f = g * G + u, sb = f % SB, j = f / SB;
+                fk[slot][u] = *reinterpret_cast<const bf16x8*>(kb + 32 * sb * D + koff[j]);
+                fv[slot][u] = *reinterpret_cast<const bf16x8*>(vb + 32 * sb * D + koff[j]);
+            }
+        };
+        auto load2 = [&](int g, int slot) {                 // 2 G fragments of K^T: fk then fv of the slot
+#pragma unroll
+            for (int u = 0; u < 2 * G; ++u) {
+                const int f = g * 2 * G + u;
+                (u < G ? fk[slot][u] : fv[slot][u - G]) = *reinterpret_cast<const bf16x8*>(tb + 32 * (f % DB) * kTileN + voff[f / DB]);
+            }
+        };
+        load1(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < NG1; ++g) {
+            if (g + 1 < NG1) load1(g + 1, (g + 1) & 1);
+            else load2(0, NG1 & 1);
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const int f = g * G + u, sb = f % SB, j = f / SB;
+                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[g & 1][u], qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
+                dp_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[g & 1][u], dof[j], j == 0 ? zero16 : dp_acc[sb], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
         bf16x8 dsb[SB][2];
@@ -298,12 +324,17 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
                 }
                 dsb[sb][i >> 3][i & 7] = (__bf16)(p * (dp_acc[sb][i] - my_delta));
             }
-        const uint16_t* tb = &sm.kt[buf][0];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int f = 0; f < DB * SB * 2; ++f) {
-            const int db = f % DB, st = f / DB;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(tb + 32 * db * kTileN + voff[st]);
-            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsb[st >> 1][st & 1], acc[db], 0, 0, 0);
+        for (int g = 0; g < NG2; ++g) {
+            const int slot = (NG1 + g) & 1;
+            if (g + 1 < NG2) load2(g + 1, slot ^ 1);
+#pragma unroll
+            for (int u = 0; u < 2 * G; ++u) {
+                const int f = g * 2 * G + u, db = f % DB, st = f / DB;
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u < G ? fk[slot][u] : fv[slot][u - G], dsb[st >> 1][st & 1], acc[db], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     wait_vmcnt<0>();
@@ -523,16 +554,45 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         if (x + 1 < n_iter) issue(x + 1, buf ^ 1);
         const Iter cur = iter_of(x);
 
+        // Operands come out of LDS a group of matrix instructions ahead of their use (one wave per SIMD: nobody else
+        // hides that latency): groups of 4 fragments per tensor, the next group requested before the current one is
+        // multiplied; scheduling barriers keep that order.
         f32x16 s_acc[SB], dp_acc[SB];
         const uint16_t* qb = &sm.qr[buf][0];
         const uint16_t* ob = &sm.dor[buf][0];
+        const uint16_t* tq = &sm.qt[buf][0];
+        const uint16_t* to = &sm.dot[buf][0];
+        constexpr int G = 4, NG1 = SB * KS / G, NG2 = DB * SB * 2 / G;
+        bf16x8 fq[2][G], fo[2][G];
+        auto load1 = [&](int g, int slot) {
 #pragma unroll
-        for (int f = 0; f < SB * KS; ++f) {
-            const int rb = f % SB, j = f / SB;
-            const bf16x8 aq = *reinterpret_cast<const bf16x8*>(qb + 32 * rb * D + koff[j]);
-            const bf16x8 ao = *reinterpret_cast<const bf16x8*>(ob + 32 * rb * D + koff[j]);
-            s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[j], j == 0 ? zero16 : s_acc[rb], 0, 0, 0);
-            dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao, vf[j], j == 0 ? zero16 : dp_acc[rb], 0, 0, 0);
+            for (int u = 0; u < G; ++u) {
+                const int f = g * G + u, rb = f % SB, j = f / SB;
+                fq[slot][u] = *reinterpret_cast<const bf16x8*>(qb + 32 * rb * D + koff[j]);
+                fo[slot][u] = *reinterpret_cast<const bf16x8*>(ob + 32 * rb * D + koff[j]);
+            }
+        };
+        auto load2 = [&](int g, int slot) {
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const int f = g * G + u, db = f % DB, stp = f / DB;
+                fo[slot][u] = *reinterpret_cast<const bf16x8*>(to + 32 * db * kTileN + voff[stp]);
+                fq[slot][u] = *reinterpret_cast<const bf16x8*>(tq + 32 * db * kTileN + voff[stp]);
+            }
+        };
+        load1(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < NG1; ++g) {
+            if (g + 1 < NG1) load1(g + 1, (g + 1) & 1);
+            else load2(0, NG1 & 1);                          // the first group of the last two products
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const int f = g * G + u, rb = f % SB, j = f / SB;
+                s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[g & 1][u], kf[j], j == 0 ? zero16 : s_acc[rb], 0, 0, 0);
+                dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[g & 1][u], vf[j], j == 0 ? zero16 : dp_acc[rb], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key
         bf16x8 pb[SB][2], dsb[SB][2];
@@ -590,15 +650,18 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
                     dsb[rb][half][e] = (__bf16)(p * (dp_acc[rb][i] - dl[e]));
                 }
             }
-        const uint16_t* tq = &sm.qt[buf][0];
-        const uint16_t* to = &sm.dot[buf][0];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int f = 0; f < DB * SB * 2; ++f) {
-            const int db = f % DB, stp = f / DB;                 // rows 16 stp .. 16 stp + 15 of the tile
-            const bf16x8 ao = *reinterpret_cast<const bf16x8*>(to + 32 * db * kTileN + voff[stp]);
-            const bf16x8 aq = *reinterpret_cast<const bf16x8*>(tq + 32 * db * kTileN + voff[stp]);
-            dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao, pb[stp >> 1][stp & 1], dv_acc[db], 0, 0, 0);
-            dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, dsb[stp >> 1][stp & 1], dk_acc[db], 0, 0, 0);
+        for (int g = 0; g < NG2; ++g) {
+            const int slot = (NG1 + g) & 1;
+            if (g + 1 < NG2) load2(g + 1, slot ^ 1);
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+                const int f = g * G + u, db = f % DB, stp = f / DB;  // rows 16 stp .. 16 stp + 15 of the tile
+                dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[slot][u], pb[stp >> 1][stp & 1], dv_acc[db], 0, 0, 0);
+                dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[slot][u], dsb[stp >> 1][stp & 1], dk_acc[db], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     wait_vmcnt<0>();
