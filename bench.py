@@ -539,8 +539,9 @@ def main():
                         "U[1024,8192] (16-token pages) and attended causally over them (Alg. 1 prefill loop)",
             "ms_per_step": round(sc["ms_per_step"], 4), "tflops": round(sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12, 2),
             "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
-            "note": "append + attention; the 128 (token, head) rows per sequence and KV head are processed as 4 blocks of 32, "
-                    "each of which streams the cache again"}
+            "pct_of_bf16_peak": round(100.0 * sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+            "note": "append + attention; the 128 (token, head) rows of a sequence and KV head are one workgroup (4 waves x 32 rows) "
+                    "that shares the cache pages through LDS"}
     if args.probes:
         line["probes"] = bench_probes(st, torch)
     if args.fp8_cache and not args.no_decode:

@@ -14,16 +14,15 @@
 // a contiguous 16-byte load straight from global memory into MFMA registers:
 //   K [page][head][d/8][slot][8] : lane (m, hg) reads slot m of d-chunk 2 j + hg
 //   V [page][head][d][slot]      : lane (n, hg) reads slots 8 hg .. 8 hg + 7 of row d
+#include <type_traits>
+
 #include "st_cache.h"
+#include "st_tiles.h"
 
 namespace st {
 
 constexpr int kChunk = 512;                 // tokens per work unit
 constexpr int kChunkLong = 1024;            // ... of the one-token decode step when there is plenty of work (64 pages: one id per lane)
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 struct DecodeArgs {
     CacheView src, rsn;
@@ -36,7 +35,7 @@ struct DecodeArgs {
     int ncs, ncr;      // chunk slots per (sequence, head) for the two caches
     int chunk;         // tokens per work unit (kChunk, or kChunkLong for the one-wave decode kernel)
     float scale_log2;
-    // source-chunk prefill only (CHUNKED kernels): ragged query counts and 32-row blocks
+    // source-chunk prefill only: ragged query counts and 32-row blocks
     const int32_t* n_new;   // [B] query tokens per sequence, or null for max_new everywhere
     int max_new;            // token stride of q / out
     int row_blocks;         // ceil(max_new * group / 32)
@@ -62,11 +61,9 @@ __device__ __forceinline__ void rotate_query(bf16x8 (&qf)[KS], int off, int pos,
         }
 }
 
-// CHUNKED = false: the decode step (up to 32 query rows q_len * G per sequence and KV head, both caches).
-// CHUNKED = true : source-chunk prefill (Alg. 1, prefill loop): the n_new[b] newest source tokens are the
-//                  queries, cut into blocks of 32 rows; only the source cache is read, causally
-//                  (row t sees source positions [0, len - n_new + t]).
-template <int D, bool CHUNKED>
+// The decode step with 17 .. 32 query rows q_len * G per sequence and KV head, both caches: four waves per
+// workgroup, each with a unit of its own.
+template <int D>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     constexpr int KS = D / 16, DB = D / 32, KCH = D / 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -74,11 +71,6 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     int64_t unit = int64_t(blockIdx.x) * 4 + wave;
     const int c = int(unit % nc);
     unit /= nc;
-    int rb = 0;
-    if (CHUNKED) {
-        rb = int(unit % a.row_blocks);
-        unit /= a.row_blocks;
-    }
     const int h = int(unit % a.n_kv_heads);
     const int b = int(unit / a.n_kv_heads);
     if (b >= a.batch) return;
@@ -90,33 +82,26 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
     if (tok0 >= len) return;
 
     const int n = lane & 31, hg = lane >> 5;
-    const int q_len = CHUNKED ? min(min(max(a.n_new ? a.n_new[b] : a.max_new, 0), a.max_new), len) : a.q_len;
-    const int r = rb * 32 + n;                      // query row of this (sequence, KV head): token r / G, head r % G
+    const int q_len = a.q_len;
+    const int r = n;                                // query row of this (sequence, KV head): token r / G, head r % G
     const int t_row = r / a.group;
     const bool valid_row = r < q_len * a.group;
     const int hq = h * a.group + r % a.group;
-    if (CHUNKED) {
-        // the block's last row sees the most: chunks past its limit hold nothing for this block
-        const int last_t = min(q_len - 1, (rb * 32 + 31) / a.group);
-        if (rb * 32 >= q_len * a.group || tok0 >= len - q_len + last_t + 1) return;
-    }
     const int tok_end = min(len, tok0 + kChunk);
     // visible reasoning tokens of query row t: [0, len - q_len + t]; the source slice is seen whole
-    // by a decode step, causally by a source chunk
-    const int limit = !valid_row ? 0 : ((is_src && !CHUNKED) ? len : max(len - q_len + t_row + 1, 0));
+    const int limit = !valid_row ? 0 : (is_src ? len : max(len - q_len + t_row + 1, 0));
 
     bf16x8 qf[KS];
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
         u32x4 z = {0u, 0u, 0u, 0u};
         if (valid_row)
-            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * (CHUNKED ? a.max_new : a.q_len) + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
+            z = *reinterpret_cast<const u32x4*>(a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
         qf[j] = __builtin_bit_cast(bf16x8, z);
     }
     if (a.rope) {
-        // the row's position id: its index in its own stream -- the reasoning stream for a decode step,
-        // the source stream for a source chunk
-        const int len_own = CHUNKED ? len : min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+        // the row's position id: its index in the reasoning stream
+        const int len_own = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
         rotate_query<KS, 16>(qf, 8 * hg, max(len_own - q_len + t_row, 0), a.freq);
     }
     f32x16 o_acc[DB];
@@ -214,8 +199,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (!valid_row) return;
-    const int64_t slot = CHUNKED ? ((((int64_t(b) * a.n_kv_heads + h) * a.row_blocks + rb) * nc + c) * 32 + n)
-                                 : (((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n);
+    const int64_t slot = ((int64_t(b) * a.n_kv_heads + h) * nc + c) * a.rows + n;
     float* po = a.part_o + slot * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -676,12 +660,252 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
         lse[(int64_t(b) * a.q_len + t) * a.n_q_heads + hq] = den > 0.f ? (m_run + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
 }
 
+// Source-chunk prefill (Alg. 1, prefill loop) with the cache pages SHARED through LDS: one workgroup per
+// (sequence, KV head, group of 128 query rows, 512-token chunk of the source cache), wave w = the w-th block of
+// 32 (token, head) rows.  Per step the four waves copy four pages (64 tokens) of K and of V -- 4 KB each at
+// D = 128, verbatim, with asynchronous global -> LDS copies, one step ahead -- and every wave takes its matrix
+// operands from there, so a page is fetched from L2 once per workgroup and not once per row block.  The pool
+// layout of K is conflict-free as it is (16 slots x 16 bytes contiguous per 8-dim chunk); the 32-byte rows of V
+// are not, so the copy swaps the two halves of every second group of 8 rows (by choosing what each lane fetches).
+// Softmax with the lazy reference exponent of the other kernels; partial results [B][Hkv][row block][unit][32 rows],
+// merged by chunk_combine_kernel.
+#ifndef ST_CHUNK_STAGES
+#define ST_CHUNK_STAGES 2
+#endif
+#ifndef ST_CHUNK_TOK
+#define ST_CHUNK_TOK 64
+#endif
+template <int D, int STAGES, int TOK>
+struct ChunkSmem {
+    uint16_t k[STAGES][TOK * D];
+    uint16_t v[STAGES][TOK * D];
+};
+
+// TOK tokens (TOK / 16 pages) per step, STAGES buffers of one step each, copies STAGES - 1 steps ahead.
+template <int D, int STAGES, int TOK>
+__global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int PAGE = D * kPage;                   // elements of one page of one head, K or V
+    constexpr int NL = PAGE * 2 / 1024;               // 1 KB copies per page
+    constexpr int PG = TOK / kPage;                   // pages per step
+    constexpr int SBN = TOK / 32;                     // 32-key blocks per step
+    constexpr int PER_WAVE = 2 * PG / 4;              // page copies (K or V) per wave and step
+    static_assert(TOK == 32 || TOK == 64, "32 or 64 tokens per step");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    ChunkSmem<D, STAGES, TOK>& sm = *reinterpret_cast<ChunkSmem<D, STAGES, TOK>*>(smem_raw);
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rb_groups = (a.row_blocks + 3) / 4;
+    unsigned unit = blockIdx.x;
+    const int c = int(unit % unsigned(a.ncs));
+    unit /= unsigned(a.ncs);
+    const int rbg = int(unit % unsigned(rb_groups));
+    unit /= unsigned(rb_groups);
+    const int h = int(unit % unsigned(a.n_kv_heads));
+    const int b = int(unit / unsigned(a.n_kv_heads));
+    const CacheView& cv = a.src;
+    const int len = min(max(a.src_len[b], 0), cv.max_pages * kPage);
+    const int tok0 = c * a.chunk;
+    if (tok0 >= len) return;
+    const int q_len = min(min(max(a.n_new ? a.n_new[b] : a.max_new, 0), a.max_new), len);
+    const int n_rows = q_len * a.group;
+    if (rbg * 128 >= n_rows) return;
+    // the group's last row sees the most: a chunk past its limit holds nothing for any of its blocks
+    const int group_last_t = min(q_len - 1, (rbg * 128 + 127) / a.group);
+    if (tok0 >= len - q_len + group_last_t + 1) return;
+    const int tok_end = min(len, tok0 + a.chunk);
+    const int n_steps = (tok_end - tok0 + TOK - 1) / TOK;
+
+    const int n = lane & 31, hg = lane >> 5;
+    const int rb = rbg * 4 + wave;
+    const int r = rb * 32 + n;
+    const bool valid_row = r < n_rows;
+    const int t_row = min(r, n_rows - 1) / a.group;
+    const int hq = h * a.group + min(r, n_rows - 1) % a.group;
+    // this wave's block: anything to do in this chunk?  (uniform; the wave still copies and meets the barriers)
+    const int block_last_t = min(q_len - 1, (rb * 32 + 31) / a.group);
+    const bool wave_works = rb * 32 < n_rows && tok0 < len - q_len + block_last_t + 1;
+    const int limit = valid_row ? len - q_len + t_row + 1 : 0;                   // row sees tokens [0, limit)
+    const int block_first_t = min(q_len - 1, (rb * 32) / a.group);
+    const int limit_min = len - q_len + block_first_t + 1;                       // smallest limit of the block's valid rows
+
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int j = 0; j < KS; ++j)
+        qf[j] = *reinterpret_cast<const bf16x8*>(a.q + ((int64_t(b) * a.max_new + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
+    if (a.rope) rotate_query<KS, 16>(qf, 8 * hg, max(len - q_len + t_row, 0), a.freq);
+
+    // Copies.  A step is PG pages of K and PG pages of V; the four waves share them out, PER_WAVE page copies each:
+    // copy number x = wave * PER_WAVE + u is page x % PG of K (x < PG) or of V.
+    const int32_t* table = cv.page_table + int64_t(b) * cv.max_pages;
+    const int last_page = (tok_end - 1) / kPage;                                 // last page that holds visible tokens
+    const int64_t page_stride = int64_t(cv.n_kv_heads) * PAGE;
+    const uint16_t* k_src = cv.k_pool + int64_t(h) * PAGE + lane * 8;
+    // V rows are 32 bytes: read as they lie, lanes d and d + 8 of a 16-lane group would meet in the same banks.  A copy
+    // places lane l's 16 bytes at position l, but WHICH 16 bytes a lane fetches is free: position 2 d + x holds the
+    // half x ^ bit 3 of d of row d, and the readers below undo that.
+    const int v_perm = (lane & ~1) | ((lane & 1) ^ ((lane >> 4) & 1));           // chunk fetched by this lane (same for every 1 KB piece: 32 rows)
+    const uint16_t* v_src = cv.v_pool + int64_t(h) * PAGE + v_perm * 8;
+    const uint32_t lds_k = uint32_t(uintptr_t(&sm.k[0][0])), lds_v = uint32_t(uintptr_t(&sm.v[0][0]));
+    // the page ids of the whole unit, fetched once (up to 256 pages: four per lane): a load per step would make
+    // every step wait for a round trip to memory, and for all copies in flight with it
+    int my_pages[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int id = table[min(tok0 / kPage + 64 * u + lane, last_page)];
+        my_pages[u] = min(max(id, 0), cv.n_pages - 1);
+    }
+    auto issue = [&](int s, int stage) {
+        s = min(s, n_steps - 1);                                                 // past the last step: the same pages again, never used
+#pragma unroll
+        for (int w = 0; w < PER_WAVE; ++w) {
+            const int x = wave * PER_WAVE + w;                                   // (uniform)
+            const bool is_v = x >= PG;
+            const int pg = is_v ? x - PG : x;
+            const int pl = min(PG * s + pg, last_page - tok0 / kPage);          // pages past the end: the last one again (masked)
+            const int quarter = pl >> 6;
+            const int held = quarter == 0 ? my_pages[0] : quarter == 1 ? my_pages[1] : quarter == 2 ? my_pages[2] : my_pages[3];
+            const int id = __builtin_amdgcn_readlane(held, pl & 63);
+            const uint16_t* src = (is_v ? v_src : k_src) + int64_t(id) * page_stride;
+            const uint32_t dst = (is_v ? lds_v : lds_k) + uint32_t(stage) * (TOK * D * 2) + uint32_t(pg) * (PAGE * 2);
+#pragma unroll
+            for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, dst + u * 1024);
+        }
+    };
+    // The chunk streams from HBM (about 125 flop per byte: below the ridge of this machine), so the bytes in flight
+    // matter: copies run STAGES - 1 steps ahead.  Every iteration issues exactly one step's copies (clamped at the
+    // end), which keeps the count the waits rely on.
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
+
+    f32x16 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
+    constexpr float kLazyRise = 8.f;
+    float m_ref = 0.f, l_run = 0.f;
+    bool has_ref = false;
+    // operand addresses inside a stage (elements): K lane (m = n, hg): page n / 16 of the 32-key block, slot
+    // swap23(n % 16), chunk 2 j + hg; V lane (m = n, hg): row 32 db + n, slots 8 hg .. + 7 of page t (halves swapped
+    // for every second group of 8 rows, see above)
+    const int k_off = (n >> 4) * PAGE + swap23(n & 15) * 8 + hg * (kPage * 8);
+    const int v_off = n * kPage + 8 * (hg ^ ((n >> 3) & 1));
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    int stage = 0;
+    for (int s = 0; s < n_steps; ++s) {
+        wait_vmcnt<(STAGES - 2) * PER_WAVE * NL>();   // step s has landed (the STAGES - 2 younger ones may still fly) ...
+        __syncthreads();                              // ... for every wave; and everybody is done with step s - 1,
+        issue(s + STAGES - 1, stage == 0 ? STAGES - 1 : stage - 1);              // whose buffer the next copies take
+        const uint16_t* kb = &sm.k[stage][0];
+        const uint16_t* vb = &sm.v[stage][0];
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
+        const int tok = tok0 + TOK * s;
+        if (!wave_works || tok >= len - q_len + block_last_t + 1) continue;      // (uniform) nothing for this block here
+        // operands leave LDS ahead of the matrix instructions that take them: all key fragments now, all value
+        // fragments before the exponentials (scheduling barriers keep the compiler from moving them back)
+        f32x16 s_acc[SBN];
+        bf16x8 fk[SBN * KS];
+#pragma unroll
+        for (int f = 0; f < SBN * KS; ++f)
+            fk[f] = *reinterpret_cast<const bf16x8*>(kb + 2 * (f % SBN) * PAGE + k_off + 2 * (f / SBN) * (kPage * 8));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int f = 0; f < SBN * KS; ++f)
+            s_acc[f % SBN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[f], qf[f / SBN], f < SBN ? zero16 : s_acc[f % SBN], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 fv[PG * DB];
+#pragma unroll
+        for (int f = 0; f < PG * DB; ++f)
+            fv[f] = *reinterpret_cast<const u32x4*>(vb + (f / DB) * PAGE + 32 * (f % DB) * kPage + v_off);
+        __builtin_amdgcn_sched_barrier(0);
+        // block sb, register i  <->  token tok + 32 sb + 16 (i/8) + 8 hg + i%8
+        float t[SBN][16];
+        float mx = -INFINITY;
+        const bool masked = tok + TOK > limit_min || !valid_row;                 // (uniform up to the row validity)
+#pragma unroll
+        for (int sb = 0; sb < SBN; ++sb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float x = fmaf(s_acc[sb][i], a.scale_log2, -m_ref);
+                if (masked) x = tok + 32 * sb + 16 * (i >> 3) + 8 * hg + (i & 7) < limit ? x : -INFINITY;
+                t[sb][i] = x;
+                mx = fmaxf(mx, x);
+            }
+        if (__any(mx > kLazyRise || (!has_ref && mx > -INFINITY))) {
+            // out of line: move the reference of the rows that need it (a row lives in lanes n and n + 32)
+            const float rise = fmaxf(mx, __shfl_xor(mx, 32));
+            const bool move = has_ref ? rise > 0.f : rise > -INFINITY;
+            const float shift = move ? rise : 0.f;
+            const float alpha = has_ref ? __builtin_amdgcn_exp2f(-shift) : 1.f;
+#pragma unroll
+            for (int sb = 0; sb < SBN; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t[sb][i] -= shift;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+            m_ref += shift;
+            has_ref = has_ref || move;
+        }
+        bf16x8 pb[PG];
+        float psum = 0.f;
+#pragma unroll
+        for (int sb = 0; sb < SBN; ++sb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(t[sb][i]);
+                psum += p;
+                pb[2 * sb + (i >> 3)][i & 7] = (__bf16)p;
+            }
+        l_run += psum;
+        const bool tail = tok + TOK > len;                                       // (uniform) the step that holds the end of the cache
+#pragma unroll
+        for (int t4 = 0; t4 < PG; ++t4) {
+            u32x4 keep = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+            if (tail) {
+                // slots past the visible length may hold anything (0 x NaN): remove them by bit mask
+                const int first = tok + 16 * t4 + 8 * hg;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    keep[e] = (first + 2 * e < len ? 0x0000ffffu : 0u) | (first + 2 * e + 1 < len ? 0xffff0000u : 0u);
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const u32x4 av = fv[t4 * DB + db] & keep;
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb[t4], o_acc[db], 0, 0, 0);
+            }
+        }
+    }
+    wait_vmcnt<0>();
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (!valid_row || !wave_works) return;
+    const int64_t slot = (((int64_t(b) * a.n_kv_heads + h) * a.row_blocks + rb) * a.ncs + c) * 32 + n;
+    float* po = a.part_o + slot * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            f32x4 o4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o4[e] = o_acc[db][4 * q4 + e];
+            *reinterpret_cast<f32x4*>(po + 32 * db + 8 * q4 + 4 * hg) = o4;
+        }
+    if (hg == 0) {
+        a.part_ml[slot * 2] = has_ref ? m_ref : -INFINITY;
+        a.part_ml[slot * 2 + 1] = l_tot;
+    }
+}
+
 // Merge for the source-chunk prefill: one wave per (sequence, query token, query head).
 template <int D>
 __global__ __launch_bounds__(64) void chunk_combine_kernel(DecodeArgs a, uint16_t* __restrict__ out,
                                                            float* __restrict__ lse) {
     constexpr int PER = D / 64;
-    constexpr int BATCH = 32;
+    constexpr int BATCH = 8;                         // partial rows fetched per round trip (units are long: few partials per row)
     const int lane = threadIdx.x;
     const int hq = int(blockIdx.x % unsigned(a.n_q_heads));
     const int t = int((blockIdx.x / unsigned(a.n_q_heads)) % unsigned(a.max_new));
@@ -692,7 +916,7 @@ __global__ __launch_bounds__(64) void chunk_combine_kernel(DecodeArgs a, uint16_
     const int h = hq / a.group;
     const int r = t * a.group + hq % a.group, rb = r / 32, n = r % 32;
     const int last_t = min(q_len - 1, (rb * 32 + 31) / a.group);
-    const int n_tot = min((len - q_len + last_t + 1 + kChunk - 1) / kChunk, a.ncs);   // chunks the split kernel wrote for this block
+    const int n_tot = min((len - q_len + last_t + 1 + a.chunk - 1) / a.chunk, a.ncs);   // chunks the split kernel wrote for this block
     const int64_t base = ((int64_t(b) * a.n_kv_heads + h) * a.row_blocks + rb) * a.ncs;
 
     float acc[PER];
@@ -837,8 +1061,8 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
             else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
             prof_end(kProfDecodeSplit, s);
         } else {
-            if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64, false>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((decode_split_kernel<128, false>), grid, block, 0, s, a);
+            if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((decode_split_kernel<128>), grid, block, 0, s, a);
         }
         ST_LAUNCH_CHECK("decode_split_kernel");
     }
@@ -908,8 +1132,19 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
     a.n_kv_heads = hkv;
     a.group = n_q_heads / hkv;
     a.rows = 32;
+    // Work unit: 512 tokens of the cache; longer ones when that still leaves a thousand workgroups or more --
+    // a unit's partial result (128 rows x D floats) is written and merged once per unit.  (The workspace is
+    // sized for the smallest unit.)
     a.chunk = kChunk;
-    a.ncs = chunks_of(max_src_len);
+    {
+        const int64_t groups = int64_t(batch) * hkv * ((int64_t(max_new) * (n_q_heads / hkv) + 127) / 128);
+        for (int unit = 8 * kChunk; unit > kChunk; unit /= 2)
+            if (groups * ((max_src_len + unit - 1) / unit) >= 1024) {
+                a.chunk = unit;
+                break;
+            }
+    }
+    a.ncs = (max_src_len + a.chunk - 1) / a.chunk;
     a.ncr = 0;
     a.scale_log2 = scale * kLog2e;
     a.n_new = n_new;
@@ -926,10 +1161,18 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
     const int64_t out_units = int64_t(batch) * max_new * n_q_heads;
     if (units / 4 + 1 > 0x7fffffff || out_units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_source_chunk: grid too large");
     if (units > 0) {
-        const dim3 grid((unsigned)((units + 3) / 4)), block(256);
-        if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((decode_split_kernel<128, true>), grid, block, 0, s, a);
-        ST_LAUNCH_CHECK("decode_split_kernel (chunked)");
+        const int64_t wgs = int64_t(batch) * hkv * ((a.row_blocks + 3) / 4) * a.ncs;
+        auto launch = [&](auto dtag) -> st_status {
+            constexpr int HD = decltype(dtag)::value;
+            constexpr int STAGES = ST_CHUNK_STAGES, TOK = ST_CHUNK_TOK;
+            const size_t smem = sizeof(ChunkSmem<HD, STAGES, TOK>);
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_split_lds_kernel<HD, STAGES, TOK>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            hipLaunchKernelGGL((chunk_split_lds_kernel<HD, STAGES, TOK>), dim3((unsigned)wgs), dim3(256), smem, s, a);
+            return ST_OK;
+        };
+        const st_status lr = d == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});
+        if (lr != ST_OK) return lr;
+        ST_LAUNCH_CHECK("chunk_split_lds_kernel");
     }
     if (d == 64) hipLaunchKernelGGL((chunk_combine_kernel<64>), dim3((unsigned)out_units), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
     else hipLaunchKernelGGL((chunk_combine_kernel<128>), dim3((unsigned)out_units), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
