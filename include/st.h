@@ -469,6 +469,11 @@ typedef struct st_stream_job {
     size_t decode_workspace_bytes;
     void* prefill_stream;          /* hipStream_t */
     void* decode_stream;           /* hipStream_t, different from prefill_stream for ST_SCHED_STREAMING */
+    int32_t decode_graph;          /* != 0: one decoded token (all layers) is recorded into a HIP graph once and
+                                      replayed per token (small batches are bound by launch gaps otherwise); the
+                                      session falls back to plain launches if the recording fails.  Results agree
+                                      with decode_graph = 0 within rounding (the work is cut into units for the
+                                      longest reasoning cache of the session instead of the current one). */
 } st_stream_job;
 
 typedef struct st_stream_report {

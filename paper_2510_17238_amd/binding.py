@@ -43,7 +43,7 @@ class _StreamJobStruct(C.Structure):
                 ("scale", C.c_float), ("theta_base", C.c_double),
                 ("prefill_workspace", C.c_void_p), ("prefill_workspace_bytes", C.c_size_t),
                 ("decode_workspace", C.c_void_p), ("decode_workspace_bytes", C.c_size_t),
-                ("prefill_stream", C.c_void_p), ("decode_stream", C.c_void_p)]
+                ("prefill_stream", C.c_void_p), ("decode_stream", C.c_void_p), ("decode_graph", C.c_int32)]
 
 
 class _StreamReportStruct(C.Structure):
@@ -567,7 +567,7 @@ def st_stream_timeline(mode, arrival_s, prefill_s, n_decode, decode_s):
 
 
 def st_stream_run(mode, layers, n_q_heads, src_tokens, rsn_tokens, src_q, src_k, src_v, rsn_q, rsn_k, rsn_v, theta_base=1.0e6,
-                  arrival_s=None, scale=0.0, prefill_stream=None, decode_stream=None):
+                  arrival_s=None, scale=0.0, prefill_stream=None, decode_stream=None, decode_graph=True):
     """Run one streaming session (Alg. 1) over `layers` (a list of DualCache, all empty).
 
     src_*: flat bf16 device tensors in the sentence-major layout of st.h, rsn_*: [steps, batch, heads, D].
@@ -602,7 +602,7 @@ def st_stream_run(mode, layers, n_q_heads, src_tokens, rsn_tokens, src_q, src_k,
     job = _StreamJobStruct(len(layers), batch, n_q_heads, k, C.addressof(cache_arr), ptr(src_tokens), ptr(rsn_tokens), ptr(arr),
                            dp(src_q), dp(src_k), dp(src_v), dp(src_out), dp(rsn_q), dp(rsn_k), dp(rsn_v), dp(rsn_out),
                            float(scale), float(theta_base), dp(pws), pws.numel(), dp(dws), dws.numel(),
-                           prefill_stream.cuda_stream, decode_stream.cuda_stream)
+                           prefill_stream.cuda_stream, decode_stream.cuda_stream, 1 if decode_graph else 0)
     report = _StreamReportStruct(ptr(rep["prefill_done"]), ptr(rep["first_token"]), ptr(rep["unit_done"]), ptr(flags["waited"]),
                                  ptr(flags["sliced"]), 0.0)
     torch.cuda.synchronize(dev)

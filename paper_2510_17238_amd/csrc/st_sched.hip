@@ -15,6 +15,12 @@
 // activations are given (one set, reused by every layer) and the number of tokens of every reasoning unit
 // is an input, as it is in Alg. 1 (source and target length lists).
 //
+// A decoded token is 4 small launches per layer, and with small batches the step is bound by launch gaps.  With
+// job.decode_graph set, one token (all layers) is recorded ONCE into a HIP graph and replayed for every token:
+// the token's activations reach fixed staging buffers through a kernel that reads the step number from a device
+// word (bumped at the end of the graph), so a replay needs no host-side update at all; the grid is sized for the
+// longest reasoning cache of the session (units past the current length exit at once).
+//
 // st_stream_timeline is the same control logic as a pure host model: event times for given stage durations.
 #include <atomic>
 #include <chrono>
@@ -85,6 +91,41 @@ struct Layout {
         }                                                                          \
     } while (0)
 
+// ---- staging kernels of the graph-replayed decode step ----
+// copy the activations of step *step from the step-major tensors into the staging buffers (16-byte pieces)
+__global__ void stage_in_kernel(u32x4* __restrict__ qs, u32x4* __restrict__ ks, u32x4* __restrict__ vs, const u32x4* __restrict__ q,
+                                const u32x4* __restrict__ k, const u32x4* __restrict__ v, const int32_t* __restrict__ step,
+                                int q_pieces, int kv_pieces) {
+    const int64_t g = *step;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < q_pieces + 2 * kv_pieces; i += gridDim.x * blockDim.x) {
+        if (i < q_pieces) qs[i] = q[g * q_pieces + i];
+        else if (i < q_pieces + kv_pieces) ks[i - q_pieces] = k[g * kv_pieces + (i - q_pieces)];
+        else vs[i - q_pieces - kv_pieces] = v[g * kv_pieces + (i - q_pieces - kv_pieces)];
+    }
+}
+__global__ void stage_out_kernel(u32x4* __restrict__ out, const u32x4* __restrict__ os, const int32_t* __restrict__ step, int q_pieces) {
+    const int64_t g = *step;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < q_pieces; i += gridDim.x * blockDim.x) out[g * q_pieces + i] = os[i];
+}
+__global__ void step_bump_kernel(int32_t* step) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *step += 1;
+}
+__global__ void copy_i32_kernel(int32_t* __restrict__ dst, const int32_t* __restrict__ src, int n) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+struct Staging {                      // device memory of the graph-replayed decode step
+    int32_t* step = nullptr;          // [1] number of the token the next replay decodes
+    int32_t* vis = nullptr;           // [batch] visible source length of the current unit
+    uint16_t *q = nullptr, *k = nullptr, *v = nullptr, *out = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    ~Staging() {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+    }
+};
+
 struct Runner {
     const st_stream_job& job;
     const Layout& lay;
@@ -95,6 +136,7 @@ struct Runner {
     Clock::time_point t0;
     int hkv, d;
     hipStream_t ps, ds;
+    Staging* stg = nullptr;           // null: eager launches for every token
 
     const char* at(const void* base, int64_t rows, int heads) const {
         return static_cast<const char*>(base) + rows * job.batch * heads * d * 2;
@@ -130,9 +172,66 @@ struct Runner {
         SCHED_HIP(sh, hipEventRecord(ev.prefilled[k], s));
     }
 
+    // one token, every layer, from and to the staging buffers: recorded into a graph on stream s
+    st_status enqueue_staged_token(hipStream_t s) {
+        const int q_pieces = job.batch * job.n_q_heads * d / 8, kv_pieces = job.batch * hkv * d / 8;
+        const int blocks = std::min(64, (q_pieces + 2 * kv_pieces + 255) / 256);
+        hipLaunchKernelGGL(stage_in_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<u32x4*>(stg->q), reinterpret_cast<u32x4*>(stg->k),
+                           reinterpret_cast<u32x4*>(stg->v), static_cast<const u32x4*>(job.rsn_q), static_cast<const u32x4*>(job.rsn_k),
+                           static_cast<const u32x4*>(job.rsn_v), stg->step, q_pieces, kv_pieces);
+        st_dual_lens lens;
+        lens.src_visible_len = stg->vis;
+        lens.q_len = 1;
+        lens.max_src_len = int(lay.total_src);
+        lens.max_rsn_len = int(lay.total_steps);
+        for (int l = 0; l < job.n_layers; ++l) {
+            st_status r = st_kv_append_rope(&job.caches[l], ST_REASONING, stg->k, stg->v, nullptr, 1, job.batch, int(lay.total_steps),
+                                            job.theta_base, s);
+            if (r != ST_OK) return r;
+            lens.rsn_len = job.caches[l].reasoning.appended_len;
+            r = st_attn_decode_dual_rope(stg->out, nullptr, stg->q, &job.caches[l], &lens, job.batch, job.n_q_heads, job.scale,
+                                         job.theta_base, job.decode_workspace, job.decode_workspace_bytes, s);
+            if (r != ST_OK) return r;
+        }
+        hipLaunchKernelGGL(stage_out_kernel, dim3(std::min(64, (q_pieces + 255) / 256)), dim3(256), 0, s, static_cast<u32x4*>(job.rsn_out),
+                           reinterpret_cast<const u32x4*>(stg->out), stg->step, q_pieces);
+        hipLaunchKernelGGL(step_bump_kernel, dim3(1), dim3(64), 0, s, stg->step);
+        if (hipGetLastError() != hipSuccess) return fail(ST_ERR_RUNTIME, "st_stream_run: launch of a staging kernel failed");
+        return ST_OK;
+    }
+
+    // Record one token into a graph (nothing runs).  On any failure the session falls back to eager launches.
+    void record_token_graph(hipStream_t s) {
+        if (!stg || lay.total_steps == 0) return;
+        bool ok = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) == hipSuccess;
+        if (ok) {
+            const st_status r = enqueue_staged_token(s);
+            hipGraph_t g = nullptr;
+            const hipError_t e = hipStreamEndCapture(s, &g);
+            stg->graph = g;
+            ok = r == ST_OK && e == hipSuccess && g != nullptr;
+        }
+        if (ok) ok = hipGraphInstantiate(&stg->exec, stg->graph, nullptr, nullptr, 0) == hipSuccess;
+        if (!ok) {
+            (void)hipGetLastError();
+            stg = nullptr;
+        }
+    }
+
     // decoding of unit t on stream s, every layer; vis_unit: which unit's slice of the source cache is visible
     void decode_unit(int t, int vis_unit, hipStream_t s) {
         const int n = job.rsn_tokens[t];
+        if (stg) {
+            // the unit's slice of the source cache, then one replay per token (they find their step number on the device)
+            hipLaunchKernelGGL(copy_i32_kernel, dim3(1), dim3(256), 0, s, stg->vis, vis_dev + int64_t(vis_unit) * job.batch, job.batch);
+            for (int j = 0; j < n; ++j) {
+                SCHED_HIP(sh, hipGraphLaunch(stg->exec, s));
+                if (j == 0) SCHED_HIP(sh, hipEventRecord(ev.first_token[t], s));
+            }
+            if (n == 0) SCHED_HIP(sh, hipEventRecord(ev.first_token[t], s));
+            SCHED_HIP(sh, hipEventRecord(ev.unit_done[t], s));
+            return;
+        }
         for (int j = 0; j < n; ++j) {
             const int64_t g = lay.step0[t] + j;
             st_dual_lens lens;
@@ -178,6 +277,7 @@ struct Runner {
 
     void decode_loop(int32_t* waited, int32_t* sliced) {
         if (hipSetDevice(device) != hipSuccess) return sh.fail_with(ST_ERR_RUNTIME, "hipSetDevice failed in the decoding loop");
+        record_token_graph(ds);
         for (int t = 0; t < job.n_sentences && !sh.abort.load(); ++t) {
             if (t > 0) SCHED_HIP(sh, hipEventSynchronize(ev.unit_done[t - 1]));     // the unit ended (its last token is out)
             const bool here = prefilled_now(t);
@@ -195,6 +295,7 @@ struct Runner {
 
     // one worker: prefill sentence k, decode unit k, next sentence
     void serial_loop(int32_t* waited, int32_t* sliced) {
+        record_token_graph(ds);
         for (int k = 0; k < job.n_sentences && !sh.abort.load(); ++k) {
             sleep_until_arrival(k);
             waited[k] = (k == 0 || hipEventQuery(ev.unit_done[k - 1]) == hipSuccess) ? 1 : 0;   // the worker was idle when it arrived
@@ -209,6 +310,7 @@ struct Runner {
 
     // read everything, prefill everything, then decode with the whole input visible
     void batch_loop(int32_t* waited, int32_t* sliced) {
+        record_token_graph(ds);
         if (job.n_sentences > 0) sleep_until_arrival(job.n_sentences - 1);
         for (int k = 0; k < job.n_sentences && !sh.abort.load(); ++k) prefill_sentence(k, ps);
         if (sh.abort.load() || job.n_sentences == 0) return;
@@ -346,10 +448,29 @@ extern "C" st_status st_stream_run(const st_stream_job* job_in, int32_t mode, st
     std::vector<int32_t> vis_host(size_t(std::max(job.n_sentences, 1)) * job.batch);
     for (int t = 0; t < job.n_sentences; ++t)
         for (int b = 0; b < job.batch; ++b) vis_host[size_t(t) * job.batch + b] = int32_t(lay.src_row0[t] + job.src_tokens[t]);
-    int32_t* vis_dev = nullptr;
-    ST_HIP(hipMalloc(&vis_dev, vis_host.size() * sizeof(int32_t)));
-    struct Free { int32_t* p; ~Free() { (void)hipFree(p); } } free_vis{vis_dev};
+    // one device block: the visibility table, then (graph-replayed decode) the step word, the current unit's slice and
+    // the staging buffers of one token
+    const size_t vis_bytes = (vis_host.size() * sizeof(int32_t) + 255) & ~size_t(255);
+    const size_t q_bytes = (size_t(job.batch) * job.n_q_heads * c0.head_dim * 2 + 255) & ~size_t(255);
+    const size_t kv_bytes = (size_t(job.batch) * c0.n_kv_heads * c0.head_dim * 2 + 255) & ~size_t(255);
+    const size_t vis1_bytes = (size_t(job.batch) * sizeof(int32_t) + 255) & ~size_t(255);
+    const bool use_graph = job.decode_graph != 0 && lay.total_steps > 0;
+    unsigned char* block = nullptr;
+    ST_HIP(hipMalloc(&block, vis_bytes + (use_graph ? 256 + vis1_bytes + 2 * q_bytes + 2 * kv_bytes : 0)));
+    struct Free { void* p; ~Free() { (void)hipFree(p); } } free_block{block};
+    int32_t* vis_dev = reinterpret_cast<int32_t*>(block);
     ST_HIP(hipMemcpy(vis_dev, vis_host.data(), vis_host.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    Staging staging;
+    if (use_graph) {
+        unsigned char* p = block + vis_bytes;
+        staging.step = reinterpret_cast<int32_t*>(p); p += 256;
+        staging.vis = reinterpret_cast<int32_t*>(p); p += vis1_bytes;
+        staging.q = reinterpret_cast<uint16_t*>(p); p += q_bytes;
+        staging.out = reinterpret_cast<uint16_t*>(p); p += q_bytes;
+        staging.k = reinterpret_cast<uint16_t*>(p); p += kv_bytes;
+        staging.v = reinterpret_cast<uint16_t*>(p);
+        ST_HIP(hipMemset(staging.step, 0, 256));
+    }
 
     Events ev;
     ST_HIP(hipEventCreate(&ev.start));
@@ -358,7 +479,7 @@ extern "C" st_status st_stream_run(const st_stream_job* job_in, int32_t mode, st
         for (auto& e : *v) ST_HIP(hipEventCreate(&e));
     }
     Shared sh;
-    Runner run{job, lay, ev, sh, vis_dev, device, Clock::now(), c0.n_kv_heads, c0.head_dim, ps, ds};
+    Runner run{job, lay, ev, sh, vis_dev, device, Clock::now(), c0.n_kv_heads, c0.head_dim, ps, ds, use_graph ? &staging : nullptr};
     for (int k = 0; k < job.n_sentences; ++k) report->waited[k] = report->sliced[k] = 0;
 
     ST_HIP(hipEventRecord(ev.start, ps));

@@ -84,8 +84,10 @@ def _check_report(rep, s, r, arrival=None):
     assert rep["total_s"] >= rep["unit_done"][-1] - 2e-3 if K else True
 
 
-@pytest.mark.parametrize("d,hq,hkv,n_layers", [(128, 4, 2, 2), (64, 8, 2, 1)])
-def test_stream_session_equals_dense_streaming_mask(st, d, hq, hkv, n_layers):
+@pytest.mark.parametrize("d,hq,hkv,n_layers,graph", [(128, 4, 2, 2, True), (64, 8, 2, 1, True), (128, 4, 2, 2, False)])
+def test_stream_session_equals_dense_streaming_mask(st, d, hq, hkv, n_layers, graph):
+    """Every token of a session -- decoded by replays of one recorded graph (graph = True) or by plain launches --
+    against the dense Eq. 2 mask over the equivalent interleaved sequence."""
     rng = np.random.Generator(np.random.PCG64(1300 + d))
     batch, theta = 2, 1.0e6
     s, r = [5, 20, 3, 17], [4, 1, 9, 3]
@@ -94,7 +96,7 @@ def test_stream_session_equals_dense_streaming_mask(st, d, hq, hkv, n_layers):
     for mode in (st.ST_SCHED_STREAMING, st.ST_SCHED_SERIAL):
         layers = _layers(st, rng, n_layers, batch, hkv, d, sum(s), sum(r))
         src_out, rsn_out, rep = st.st_stream_run(mode, layers, hq, s, r, dev["sq"], dev["sk"], dev["sv"], dev["rq"], dev["rk"],
-                                                 dev["rv"], theta)
+                                                 dev["rv"], theta, decode_graph=graph)
         _check_report(rep, s, r)
         for c in layers:
             assert c.source.appended_len.cpu().tolist() == [sum(s)] * batch
