@@ -8,7 +8,8 @@
 // 16-byte loads:
 //   K: [page][head][d / 8][slot][8]      V: [page][head][d][slot]
 // The new length is written by a second, tiny kernel so that every workgroup of the
-// first one sees the old length.
+// first one sees the old length (a single new token per sequence takes one launch: see
+// kv_append_token_kernel).
 //
 // ROPE = true is the fused form: k_new holds UNROTATED keys and each key is rotated on its way
 // into the pool by its position id, which is its index in this cache (Sec. 3.2 numbers the tokens
@@ -103,6 +104,60 @@ __global__ __launch_bounds__(256) void kv_append_kernel(CacheView cache, const u
             if (s < cnt) vdst[d * kPage + slot_lo + s] = s_v[s][d];
         }
     }
+}
+
+// One new token per sequence (the decoding step): one workgroup per sequence, no staging, and -- nobody else reads
+// this sequence's length -- the workgroup writes the new length itself, which saves the second launch per layer and
+// token.  Threads split the token's Hkv x D / 8 pieces of K (rotated on the way in if ROPE) and of V.
+template <int D, bool ROPE>
+__global__ __launch_bounds__(256) void kv_append_token_kernel(CacheView cache, const uint16_t* __restrict__ k_new,
+                                                              const uint16_t* __restrict__ v_new,
+                                                              const int32_t* __restrict__ n_new, RopeFreq freq) {
+    constexpr int KCH = D / 8;
+    const int b = blockIdx.x;
+    const int capacity = cache.max_pages * kPage;
+    const int start = min(max(cache.appended_len[b], 0), capacity);
+    int n = n_new ? min(max(n_new[b], 0), 1) : 1;
+    n = min(n, capacity - start);
+    __syncthreads();                                     // every thread has read the old length
+    if (n == 0) return;
+    const int id = cache.page_table[int64_t(b) * cache.max_pages + start / kPage];
+    if (id >= 0 && id < cache.n_pages) {                 // never write outside the pool
+        const int slot = start % kPage;
+        const int pieces = cache.n_kv_heads * KCH;
+        const uint16_t* krow = k_new + int64_t(b) * cache.n_kv_heads * D;
+        const uint16_t* vrow = v_new + int64_t(b) * cache.n_kv_heads * D;
+        for (int w = threadIdx.x; w < pieces; w += 256) {
+            const int h = w / KCH, c8 = w % KCH;
+            uint16_t* kdst = cache.k_pool + ((int64_t(id) * cache.n_kv_heads + h) * KCH + c8) * (kPage * 8) + slot * 8;
+            if (ROPE) {
+                // piece c8 < KCH / 2 and its partner c8 + KCH / 2: the two halves of eight rotation pairs
+                if (c8 < KCH / 2) {
+                    const Piece lo_in = *reinterpret_cast<const Piece*>(krow + h * D + c8 * 8);
+                    const Piece hi_in = *reinterpret_cast<const Piece*>(krow + h * D + c8 * 8 + D / 2);
+                    Piece lo_out, hi_out;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        float cs, sn;
+                        rope_cos_sin(start, freq.f[c8 * 8 + e], &cs, &sn);      // index in this cache == position id
+                        const float a = bf16_bits_to_f32(lo_in.v[e]), b2 = bf16_bits_to_f32(hi_in.v[e]);
+                        lo_out.v[e] = f32_to_bf16_bits(a * cs - b2 * sn);
+                        hi_out.v[e] = f32_to_bf16_bits(b2 * cs + a * sn);
+                    }
+                    *reinterpret_cast<Piece*>(kdst) = lo_out;
+                    *reinterpret_cast<Piece*>(kdst + (KCH / 2) * (kPage * 8)) = hi_out;
+                }
+            } else {
+                *reinterpret_cast<Piece*>(kdst) = *reinterpret_cast<const Piece*>(krow + h * D + c8 * 8);
+            }
+            // V: the piece's 8 values go to 8 rows d of the page, slot `slot` each
+            const Piece vin = *reinterpret_cast<const Piece*>(vrow + h * D + c8 * 8);
+            uint16_t* vdst = cache.v_pool + (int64_t(id) * cache.n_kv_heads + h) * (D * kPage) + (c8 * 8) * kPage + slot;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vdst[e * kPage] = vin.v[e];
+        }
+    }
+    if (threadIdx.x == 0) cache.appended_len[b] = start + n;
 }
 
 // 8-bit store: every key row and every value row (one token, one KV head) is divided by its own power of
@@ -259,6 +314,19 @@ static st_status kv_append_impl(const char* who, const st_dual_cache* caches, st
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const CacheView cv = cache_view(c);
     const RopeFreq freq = rotate ? make_rope_freq(theta_base, c.head_dim) : RopeFreq{};
+    if (max_new == 1 && !fp8) {
+        // the decoding step: one launch, the workgroup of a sequence writes its new length itself
+        auto token = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, dim3((unsigned)batch), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new, n_new, freq);
+        };
+        if (c.head_dim == 64) {
+            if (rotate) token(kv_append_token_kernel<64, true>); else token(kv_append_token_kernel<64, false>);
+        } else {
+            if (rotate) token(kv_append_token_kernel<128, true>); else token(kv_append_token_kernel<128, false>);
+        }
+        ST_LAUNCH_CHECK("kv_append_token_kernel");
+        return ST_OK;
+    }
     auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new,
                            n_new, max_new, touched, freq);
