@@ -22,6 +22,7 @@
 namespace st {
 
 constexpr int kChunk = 512;                 // tokens per work unit
+constexpr int kSmallDecodeTokens = 1024;    // both caches together: below this one wave per (sequence, KV head) finishes the rows itself
 constexpr int kChunkLong = 1024;            // ... of the one-token decode step when there is plenty of work (64 pages: one id per lane)
 
 struct DecodeArgs {
@@ -228,57 +229,23 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 // whose A operand (V^T) is then one contiguous 16-byte load.  All loads are unconditional (page
 // ids are clamped into the pool); what lies beyond the visible length is removed afterwards by
 // index: scores by select, V by bit mask.
+// One unit (tokens [tok0, tok_end) of one cache) folded into the running state of a query column: the step loop of the
+// one-wave kernels.  State in base-2 exponent units: m_ref is the column's reference exponent (the same in its four
+// lanes); it starts at 0 with has_ref = false and is moved, out of line, only when a step brings an exponent more
+// than kLazyRise above it (or the first finite score): the common step then needs no exchange between lanes and no
+// rescale of the accumulator -- probabilities are bounded by 2^kLazyRise instead of 1, which fp32 and bf16 do not
+// mind, and whoever finishes the row divides by l anyway.
 template <int D>
-__global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
+__device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, int lane, int tok0, int tok_end, int len, int limit,
+                                            int limit_min, float scale_log2, const bf16x8 (&qf)[D / 32], f32x4 (&o_acc)[D / 16],
+                                            float& m_ref, float& l_run, bool& has_ref) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
-    const int lane = threadIdx.x;
-    const int nc = a.ncs + a.ncr;
-    const int c = int(blockIdx.x % unsigned(nc));
-    const unsigned bh = blockIdx.x / unsigned(nc);
-    const int h = int(bh % unsigned(a.n_kv_heads));
-    const int b = int(bh / unsigned(a.n_kv_heads));
-    const bool is_src = c < a.ncs;
-    const CacheView& cv = is_src ? a.src : a.rsn;
-    const int cc = is_src ? c : c - a.ncs;
-    const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
-    const int tok0 = cc * a.chunk;
-    if (tok0 >= len) return;
-    const int tok_end = min(len, tok0 + a.chunk);
-    const int n_steps = (tok_end - tok0 + 31) / 32;
-
+    constexpr float kLazyRise = 8.f;
     const int n = lane & 15, g4 = lane >> 4;
-    const bool valid_row = n < a.rows;
-    const int nr = min(n, a.rows - 1);                  // rows past the end repeat the last one (never stored)
-    const int t_row = nr / a.group;
-    const int hq = h * a.group + nr % a.group;
-    const int limit = is_src ? len : max(len - a.q_len + t_row + 1, 0);
-    const int limit_min = is_src ? len : max(len - a.q_len + 1, 0);     // the smallest limit of any row (row 0's)
+    const int n_steps = (tok_end - tok0 + 31) / 32;
     bf16x2 ones2;
     ones2[0] = (__bf16)1.f;
     ones2[1] = (__bf16)1.f;
-
-    bf16x8 qf[KS];
-    {
-        const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
-    }
-    if (a.rope) {
-        const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
-        rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
-    }
-    f32x4 o_acc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // Softmax state in base-2 exponent units.  m_ref is the row's reference exponent (the same in the four
-    // lanes of a query column); it starts at 0 with has_ref = false and is moved, out of line, only when a
-    // step brings an exponent more than kLazyRise above it (or the first finite score): the common step then
-    // needs no exchange between lanes and no rescale of the accumulator -- probabilities are bounded by
-    // 2^kLazyRise instead of 1, which fp32 and bf16 do not mind, and the merge kernel divides by l anyway.
-    constexpr float kLazyRise = 8.f;
-    float m_ref = 0.f, l_run = 0.f;
-    bool has_ref = false;
-
     // the page ids of the whole unit, one per lane, fetched once: no dependent scalar load per step
     const int last_page = (tok_end - 1) / kPage - tok0 / kPage;      // last page of the chunk that holds visible tokens
     int my_page = cv.page_table[int64_t(b) * cv.max_pages + tok0 / kPage + min(lane, last_page)];
@@ -328,7 +295,7 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
         }
         float t[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = fmaf(e < 4 ? sx[e] : sy[e - 4], a.scale_log2, -m_ref);
+        for (int e = 0; e < 8; ++e) t[e] = fmaf(e < 4 ? sx[e] : sy[e - 4], scale_log2, -m_ref);
         if (tok0 + 32 * s + 32 > limit_min) {           // uniform: a step that reaches some row's limit
 #pragma unroll
             for (int e = 0; e < 8; ++e) t[e] = first + e < limit ? t[e] : -INFINITY;
@@ -375,6 +342,49 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
             o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv[db]), pb, o_acc[db], 0, 0, 0);
     }
 
+}
+
+template <int D>
+__global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
+    constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
+    const int lane = threadIdx.x;
+    const int nc = a.ncs + a.ncr;
+    const int c = int(blockIdx.x % unsigned(nc));
+    const unsigned bh = blockIdx.x / unsigned(nc);
+    const int h = int(bh % unsigned(a.n_kv_heads));
+    const int b = int(bh / unsigned(a.n_kv_heads));
+    const bool is_src = c < a.ncs;
+    const CacheView& cv = is_src ? a.src : a.rsn;
+    const int cc = is_src ? c : c - a.ncs;
+    const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
+    const int tok0 = cc * a.chunk;
+    if (tok0 >= len) return;
+    const int tok_end = min(len, tok0 + a.chunk);
+
+    const int n = lane & 15, g4 = lane >> 4;
+    const bool valid_row = n < a.rows;
+    const int nr = min(n, a.rows - 1);                  // rows past the end repeat the last one (never stored)
+    const int t_row = nr / a.group;
+    const int hq = h * a.group + nr % a.group;
+    const int limit = is_src ? len : max(len - a.q_len + t_row + 1, 0);
+    const int limit_min = is_src ? len : max(len - a.q_len + 1, 0);     // the smallest limit of any row (row 0's)
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
+    }
+    if (a.rope) {
+        const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+        rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
+    }
+    f32x4 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_ref = 0.f, l_run = 0.f;
+    bool has_ref = false;
+    scan_unit16<D>(cv, b, h, lane, tok0, tok_end, len, limit, limit_min, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+
     float l_tot = l_run + __shfl_xor(l_run, 16);
     l_tot += __shfl_xor(l_tot, 32);
     if (!valid_row) return;
@@ -387,6 +397,59 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
         a.part_ml[slot * 2] = has_ref ? m_ref : -INFINITY;
         a.part_ml[slot * 2 + 1] = l_tot;
     }
+}
+
+// Short caches (the streaming session of one listener: a hundred source tokens, a few hundred reasoning tokens): one
+// wave per (sequence, KV head) folds every unit of BOTH caches into one running state and writes the finished rows
+// itself -- no partial results, no merge kernel, one launch per layer and token instead of two.
+template <int D>
+__global__ __launch_bounds__(64, 4) void decode_small16_kernel(DecodeArgs a, uint16_t* __restrict__ out, float* __restrict__ lse) {
+    constexpr int KS = D / 32, DB = D / 16;
+    const int lane = threadIdx.x;
+    const int h = int(blockIdx.x % unsigned(a.n_kv_heads));
+    const int b = int(blockIdx.x / unsigned(a.n_kv_heads));
+    const int n = lane & 15, g4 = lane >> 4;
+    const bool valid_row = n < a.rows;
+    const int nr = min(n, a.rows - 1);
+    const int t_row = nr / a.group;
+    const int hq = h * a.group + nr % a.group;
+    const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
+    const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
+    }
+    if (a.rope) rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
+    f32x4 o_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_ref = 0.f, l_run = 0.f;
+    bool has_ref = false;
+    // the source slice is seen whole; reasoning token j by rows t with j <= len_r - q_len + t
+    for (int tok0 = 0; tok0 < len_s; tok0 += kChunkLong)
+        scan_unit16<D>(a.src, b, h, lane, tok0, min(len_s, tok0 + kChunkLong), len_s, len_s, len_s, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+    const int limit = max(len_r - a.q_len + t_row + 1, 0), limit_min = max(len_r - a.q_len + 1, 0);
+    for (int tok0 = 0; tok0 < len_r; tok0 += kChunkLong)
+        scan_unit16<D>(a.rsn, b, h, lane, tok0, min(len_r, tok0 + kChunkLong), len_r, limit, limit_min, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (!valid_row) return;
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;              // a row that sees nothing: out = 0, lse = -inf
+    uint16_t* op = out + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D;
+    // lane (n, g4), block db, register i  <->  d = 16 db + 4 g4 + i
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        bf16x4 o4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(o_acc[db][i] * inv);
+        *reinterpret_cast<bf16x4*>(op + 16 * db + 4 * g4) = o4;
+    }
+    if (lse && g4 == 0)
+        lse[(int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
 }
 
 // The one-wave kernel over 8-bit caches (E4M3 codes, one power-of-two fp32 scale per key row and per value
@@ -1046,6 +1109,14 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // Short caches: one wave per (sequence, KV head) does everything (no partials, no merge launch) -- when the
+    // serial walk of both caches is short and there are too few sequences for the split to pay anyway.
+    if (!fp8 && a.rows <= 16 && lens->max_src_len + lens->max_rsn_len <= kSmallDecodeTokens && int64_t(batch) * hkv <= 0x7fffffff) {
+        if (d == 64) hipLaunchKernelGGL((decode_small16_kernel<64>), dim3((unsigned)(batch * hkv)), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
+        else hipLaunchKernelGGL((decode_small16_kernel<128>), dim3((unsigned)(batch * hkv)), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
+        ST_LAUNCH_CHECK("decode_small16_kernel");
+        return ST_OK;
+    }
     const int64_t units = int64_t(batch) * hkv * (a.ncs + a.ncr);
     const int64_t out_units = int64_t(batch) * a.q_len * n_q_heads;
     if (units / 4 + 1 > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
