@@ -48,6 +48,8 @@ static WsLayout ws_layout(int32_t batch, int64_t n_tokens) {
 }
 
 constexpr int kPlanThreads = 1024;
+constexpr int kSegLds = 8192;            // source tokens of a sequence whose segment ids are searched in LDS
+constexpr int kSortedMax = 4096;          // work items up to which one workgroup builds and orders them
 constexpr int kTablesMaxBatch = 64;      // up to this batch the three host tables travel as kernel arguments
 
 struct HostTables {                      // cu_seqlens | item slot bases | packed tile bases, batch + 1 entries each
@@ -96,6 +98,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32
     __shared__ int s_wave[kPlanThreads / 64];
     __shared__ int s_total;
     __shared__ unsigned long long s_pairs[kPlanThreads / 64];
+    __shared__ int s_seg[kSegLds];            // segment ids of the source stream: the bisection below stays in LDS
     const int b = blockIdx.x;
     const int t0 = cu[b], t1 = cu[b + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -144,6 +147,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32
 
     // pass 3: visible source count per compact row, pair count, validation
     const int n = t1 - t0;
+    const bool seg_in_lds = S <= kSegLds;      // (a dozen dependent loads per row otherwise go to global memory)
+    if (seg_in_lds) {
+        for (int i = threadIdx.x; i < S; i += kPlanThreads) s_seg[i] = seg_c[t0 + i];
+        __syncthreads();
+    }
     unsigned long long mine = 0ull;
     for (int r = threadIdx.x; r < n; r += kPlanThreads) {
         const int c = t0 + r;
@@ -156,7 +164,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32
             int lo = 0, hi = S;  // first source index whose segment id is > g
             while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
-                if (seg_c[t0 + mid] <= g) lo = mid + 1; else hi = mid;
+                if ((seg_in_lds ? s_seg[mid] : seg_c[t0 + mid]) <= g) lo = mid + 1; else hi = mid;
             }
             v = lo;
             mine += (unsigned long long)v + (unsigned long long)(r - S + 1);
@@ -233,18 +241,20 @@ __global__ __launch_bounds__(kPlanThreads) void plan_items_sorted_kernel(const i
                                                                          const int32_t* __restrict__ vis,
                                                                          WorkItem* __restrict__ items, int32_t* __restrict__ cost,
                                                                          WorkItem* __restrict__ sorted) {
+    __shared__ int s_cost[kSortedMax];
     for (int slot = threadIdx.x; slot < m_max; slot += kPlanThreads) {
         int c;
         items[slot] = make_item(slot, cu, slot_base, pack_base, batch, n_src, n_rsn, vis, &c);
         cost[slot] = c;
+        s_cost[slot] = c;
     }
     __threadfence_block();
     __syncthreads();
     for (int i = threadIdx.x; i < m_max; i += kPlanThreads) {
-        const int ci = cost[i];
+        const int ci = s_cost[i];
         int rank = 0;
         for (int j = 0; j < m_max; ++j) {
-            const int cj = cost[j];
+            const int cj = s_cost[j];
             rank += (cj > ci) || (cj == ci && j < i);
         }
         sorted[rank] = items[i];
@@ -389,7 +399,7 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
     }
     hipLaunchKernelGGL(plan_sequence_kernel, dim3(batch), dim3(kPlanThreads), 0, s, stream_ids, segment_ids, positions, p->cu,
                        p->n_src, p->n_rsn, p->perm, p->seg_c, p->vis, p->pairs, p->flag, validate ? 1 : 0);
-    if (p->m_max <= 4096) {
+    if (p->m_max <= kSortedMax) {
         hipLaunchKernelGGL(plan_items_sorted_kernel, dim3(1), dim3(kPlanThreads), 0, s, p->cu, p->slot_base, p->pack_base, batch,
                            p->m_max, p->n_src, p->n_rsn, p->vis, p->items, p->cost, p->sorted);
     } else {
