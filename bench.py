@@ -11,6 +11,11 @@ of the metric is measured in the same run on the Qwen3-1.7B-shaped decode worklo
 batch 32, source cache 2K + reasoning cache 1-6K, concurrent 64-token source append) and reported
 in the "decode" object as GB/s of algorithmic cache bytes.
 
+Further objects of the same line (all by default; --no-extras leaves them out, naming some runs only those):
+"source_chunk" (Alg. 1's prefill loop on the streaming shape), "prefill_long" (16K-token sequences), "decode_fp8"
+(8-bit caches), "prefill_backward" (gradients), "stream_session" (Alg. 1 end to end), "probes" (what the machine
+sustains for the two kernels' access pattern / instruction).
+
 Prints ONE JSON line.  All inputs are seeded, synthetic and resident in HBM before timing starts.
 """
 import argparse
@@ -478,6 +483,9 @@ def main():
     ap.add_argument("--stream-session", action="store_true",
                     help="also run one Alg. 1 session (streaming / alternating / batch schedules) and report it under 'stream_session'")
     ap.add_argument("--stream-time-scale", type=float, default=0.01, help="compression of the arrival times of --stream-session")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the prefill step, the decode workload and the source chunk.  Without this flag, and when none of "
+                         "--long-prefill / --probes / --fp8-cache / --backward / --stream-session is given, ALL of them run")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -547,6 +555,10 @@ def main():
             "pct_of_bf16_peak": round(100.0 * sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
             "note": "append + attention; the 128 (token, head) rows of a sequence and KV head are one workgroup (4 waves x 32 rows) "
                     "that shares the cache pages through LDS"}
+    # the additional legs: those asked for, or all of them when none is named
+    named = args.long_prefill or args.probes or args.fp8_cache or args.backward or args.stream_session
+    if not named and not args.no_extras:
+        args.long_prefill = args.probes = args.fp8_cache = args.backward = args.stream_session = True
     if args.probes:
         line["probes"] = bench_probes(st, torch)
     if args.fp8_cache and not args.no_decode:
