@@ -180,16 +180,19 @@ __global__ __launch_bounds__(kTileM) void bwd_dkv_kernel(T* __restrict__ dkv, co
 //   S^T  = K  Q^T     (K row tile from LDS, Q^T in registers)        -> P^T = exp2(S^T scale - lse)
 //   dP^T = V  dO^T    (V row tile from LDS, dO^T in registers)       -> dS^T = P^T (dP^T - delta)
 //   dQ^T += K^T dS^T  (K^T tile from LDS, dS^T from the accumulators, rounded to bf16)
-// Two buffers per tile kind (96 KB), one barrier per key tile, copies one tile ahead.
+// The kernel fits 256 registers, so TWO workgroups share a CU (two waves per SIMD fill each other's gaps between
+// matrix and vector work) if each stays within 80 KB of LDS: the K and V row tiles are double-buffered and copied
+// one tile ahead, K^T -- needed only by the last product -- has ONE buffer, filled at the top of its own
+// iteration and awaited (second barrier) before that product.
 template <int D>
 struct BwdDqSmem {
     uint16_t k[2][kTileN * D];        // K rows
     uint16_t v[2][kTileN * D];        // V rows
-    uint16_t kt[2][D * kTileN];       // K^T
+    uint16_t kt[1][D * kTileN];       // K^T
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restrict__ dq, const uint16_t* __restrict__ d_out,
+__global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restrict__ dq, const uint16_t* __restrict__ d_out,
                                                              const uint16_t* __restrict__ q, const uint16_t* __restrict__ krows,
                                                              const uint16_t* __restrict__ vrows, const uint16_t* __restrict__ ktr,
                                                              const float* __restrict__ lse, const float* __restrict__ delta,
@@ -220,16 +223,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
     const uint32_t wave_off = uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
     const uint32_t lds_k = uint32_t(uintptr_t(&sm.k[0][0])) + wave_off, lds_v = uint32_t(uintptr_t(&sm.v[0][0])) + wave_off,
                    lds_kt = uint32_t(uintptr_t(&sm.kt[0][0])) + wave_off;
-    auto issue = [&](int ti, int buf) {
+    auto issue_rows = [&](int ti, int buf) {
         const size_t off = head_off + size_t(tile_of(ti)) * TILE;
 #pragma unroll
         for (int u = 0; u < NL; ++u) async_copy16(krows + off + u * 512, lds_k + buf * (TILE * 2) + u * 1024);
 #pragma unroll
         for (int u = 0; u < NL; ++u) async_copy16(vrows + off + u * 512, lds_v + buf * (TILE * 2) + u * 1024);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(ktr + off + u * 512, lds_kt + buf * (TILE * 2) + u * 1024);
     };
-    issue(0, 0);
+    auto issue_kt = [&](int ti) {
+        const size_t off = head_off + size_t(tile_of(ti)) * TILE;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) async_copy16(ktr + off + u * 512, lds_kt + u * 1024);
+    };
+    issue_rows(0, 0);
 
     const int row_in_tile = wave * 32 + n;
     const bool active = row_in_tile < it.n_rows;
@@ -264,9 +270,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
 
     for (int ti = 0; ti < n_tiles; ++ti) {
         const int buf = ti & 1;
-        wait_vmcnt<0>();                 // tile ti has landed; everybody is done with tile ti - 1
+        wait_vmcnt<0>();                 // the row tiles of ti have landed; everybody is done with tile ti - 1
         __syncthreads();
-        if (ti + 1 < n_tiles) issue(ti + 1, buf ^ 1);
+        issue_kt(ti);                    // (always the same number of copies per iteration: the wait below counts them)
+        issue_rows(ti + 1, buf ^ 1);     // (past the end: the last tile again, never used)
 
         const bool in_a = ti < it.a_total;
         const int kt = in_a ? ti : ti - it.a_total;
@@ -278,7 +285,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
         f32x16 s_acc[SB], dp_acc[SB];
         const uint16_t* kb = &sm.k[buf][0];
         const uint16_t* vb = &sm.v[buf][0];
-        const uint16_t* tb = &sm.kt[buf][0];
+        const uint16_t* tb = &sm.kt[0][0];
         constexpr int G = 4, NG1 = SB * KS / G, NG2 = DB * SB * 2 / (2 * G);
         bf16x8 fk[2][G], fv[2][G];
         auto load1 = [&](int g, int slot) {
@@ -301,7 +308,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
 #pragma unroll
         for (int g = 0; g < NG1; ++g) {
             if (g + 1 < NG1) load1(g + 1, (g + 1) & 1);
-            else load2(0, NG1 & 1);
 #pragma unroll
             for (int u = 0; u < G; ++u) {
                 const int f = g * G + u, sb = f % SB, j = f / SB;
@@ -324,6 +330,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_mfma_kernel(uint16_t* __restric
                 }
                 dsb[sb][i >> 3][i & 7] = (__bf16)(p * (dp_acc[sb][i] - my_delta));
             }
+        wait_vmcnt<2 * NL>();            // K^T of this tile has landed (the next row tiles may still fly) ...
+        __syncthreads();                 // ... for every wave
+        load2(0, NG1 & 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < NG2; ++g) {
