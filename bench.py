@@ -555,6 +555,12 @@ def main():
             "pct_of_bf16_peak": round(100.0 * sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
             "note": "append + attention; the 128 (token, head) rows of a sequence and KV head are one workgroup (4 waves x 32 rows) "
                     "that shares the cache pages through LDS"}
+    # the paper's own latency figures for context (Table 4, "Efficiency evaluation on Qwen3-4B": whole model, 100
+    # GSM-Symbolic samples, input read at 150 words per minute); its text names no GPU
+    line["paper_reference"] = {
+        "source": "Table 4 (Qwen3-4B, whole model, another machine: context, not a target)", "hardware": "not stated in the paper",
+        "prefill_s_per_sentence": {"streaming": 0.041, "batch": 0.052}, "decode_s_per_token": {"streaming": 0.037, "batch": 0.039},
+        "decoded_tokens": {"streaming": 439, "batch": 436}, "first_token_latency_s": {"streaming": 6.231, "batch": 28.003}}
     # the additional legs: those asked for, or all of them when none is named
     named = args.long_prefill or args.probes or args.fp8_cache or args.backward or args.stream_session
     if not named and not args.no_extras:
