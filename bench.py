@@ -188,8 +188,19 @@ def bench_prefill_long(st, torch, W, reps):
     torch.cuda.synchronize()
     st.st_profile_enable(False)
     ms, cnt = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    # the same launches on all-zero inputs: the same instruction stream with no bits toggling in the operands --
+    # how much of the time is the power limit and not the schedule
+    q.zero_(); k.zero_(); v.zero_()
+    st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    st.st_profile_enable(True)
+    for _ in range(reps):
+        st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    st.st_profile_enable(False)
+    zero_ms, _ = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
     plan.destroy()
-    return {"kernel_ms": ms, "flops": flops, "n_tokens": n, "launches": cnt}
+    return {"kernel_ms": ms, "flops": flops, "n_tokens": n, "launches": cnt, "zero_input_kernel_ms": zero_ms}
 
 
 def bench_stream_session(st, torch, W, time_scale):
@@ -606,6 +617,9 @@ def main():
             "workload": "configs[3]: Qwen3-4B-shaped long-context prefill layer, 8 sequences x 16,384 tokens, 32 q / 8 kv heads, "
                         "head_dim 128, bf16; attention kernel only (two query heads per workgroup)",
             "avg_kernel_ms": round(lp["kernel_ms"], 3), "effective_flops": lp["flops"],
+            "same_launch_on_all_zero_inputs": {"avg_kernel_ms": round(lp["zero_input_kernel_ms"], 3),
+                                               "tflops": round(lp["flops"] / (lp["zero_input_kernel_ms"] * 1e-3) / 1e12, 1),
+                                               "note": "same instruction stream, no operand bits toggling: the difference is the power limit"},
             "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 2>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
     if not args.no_cpu_baseline:
