@@ -319,6 +319,45 @@ def test_prefill_bwd_is_deterministic_and_checks_arguments(st):
     assert e.value.status == 4
 
 
+# ------------------------------------------------- many random structures --
+def test_forward_and_backward_over_many_random_structures(st):
+    """Thirty seeded structures -- segment counts, empty and one-token segments, both layouts, both head sizes, grouped
+    heads, tile multiples by chance -- through the bf16 forward (both kernels) and backward, and a few in fp32."""
+    rng = np.random.Generator(np.random.PCG64(9000))
+    prev = st.st_prefill_variant_set(st.ST_PREFILL_AUTO)
+    try:
+        for trial in range(30):
+            d = int(rng.choice([64, 128])); hkv = int(rng.choice([1, 2])); hq = hkv * int(rng.choice([1, 2, 4]))
+            layout = "interleaved" if trial % 2 else "grouped"
+            hi_s, hi_r = int(rng.choice([3, 40, 130])), int(rng.choice([3, 50, 150]))
+            cfg = W.random_prefill(9100 + trial, int(rng.integers(1, 4)), int(rng.integers(1, 7)), (0, hi_s), (0, hi_r), hq, hkv, d,
+                                   "f32" if trial % 10 == 9 else "bf16", layout)
+            if cfg.n_tokens == 0:
+                continue
+            st.st_prefill_variant_set(st.ST_PREFILL_TWO_HEADS if trial % 3 == 0 else st.ST_PREFILL_ONE_HEAD)
+            _run_prefill(st, cfg)
+            _run_prefill_bwd(st, cfg)
+    finally:
+        st.st_prefill_variant_set(prev)
+
+
+def test_decode_over_many_random_lengths(st):
+    """Random cache lengths around page, step and unit boundaries, visible source prefixes from 0 to everything, one to
+    eight query tokens, bf16 and 8-bit caches, short (fused single launch) and long (split + merge) caches."""
+    rng = np.random.Generator(np.random.PCG64(9001))
+    marks = np.array([0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 511, 512, 513, 1023, 1024, 1025, 1300])
+    for trial in range(14):
+        batch = int(rng.integers(1, 5)); d = int(rng.choice([64, 128])); hkv = int(rng.choice([1, 2])); group = int(rng.choice([1, 2, 4]))
+        q_len = int(rng.choice([1, 1, 2, 4]))
+        if q_len * group > 16:
+            q_len = 16 // group
+        short = trial % 2 == 0
+        pool = marks[marks <= (400 if short else 1300)]
+        src_lens = rng.choice(pool, batch); rsn_lens = np.maximum(rng.choice(pool, batch), q_len)
+        src_vis = np.array([int(rng.integers(0, s + 1)) for s in src_lens])
+        _check_decode(st, rng, batch, hkv * group, hkv, d, src_lens, rsn_lens, src_vis, q_len=q_len, fp8=(trial % 4 == 3))
+
+
 # ------------------------------------------------------- append / decode --
 def _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, chunks=(1, 15, 17, 64, 3), rope_theta=None, fp8=False,
                row_exponents=None):
