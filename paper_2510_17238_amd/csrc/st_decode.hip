@@ -459,8 +459,8 @@ __global__ __launch_bounds__(64, 4) void decode_small16_kernel(DecodeArgs a, uin
 // Pool layouts [page][head][D/16][slot][16] and [page][head][D][slot] bytes keep the loads contiguous:
 //   K: lane (m, g4) reads the 16 bytes d = 64 jj + 16 g4 .. + 15 of key row m: two k-steps' worth (the query
 //      fragments use the same assignment of head dims to k-steps)
-//   V: lane (m, g4) reads the 8 bytes slots 8 (g4 % 2) .. + 7 of row d = 16 db + m in page g4 / 2
-//   scales: the 8 + 8 floats of those same slots.
+//   V: lane (m, g4) reads the 16 bytes (all slots) of row d = 16 db + m in page g4: two k-steps' worth
+//   scales: the 16 + 16 floats of page g4.
 __device__ __forceinline__ bf16x8 e4m3x8_to_bf16(uint32_t lo, uint32_t hi) {
     const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.f, false), b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.f, true);
     const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.f, false), d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.f, true);
@@ -471,7 +471,7 @@ __device__ __forceinline__ bf16x8 e4m3x8_to_bf16(uint32_t lo, uint32_t hi) {
 }
 
 template <int D>
-__global__ __launch_bounds__(64, 4) void decode_split16_fp8_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64, 3) void decode_split16_fp8_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, KP = D / 64, DB = D / 16, C16 = D / 16;
     const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr;
@@ -486,7 +486,9 @@ __global__ __launch_bounds__(64, 4) void decode_split16_fp8_kernel(DecodeArgs a)
     const int tok0 = cc * a.chunk;
     if (tok0 >= len) return;
     const int tok_end = min(len, tok0 + a.chunk);
-    const int n_steps = (tok_end - tok0 + 31) / 32;
+    // With half the bytes per token, a wave takes 64 tokens (four pages) per step to keep as many bytes in flight
+    // as the bf16 kernel does with 32.
+    const int n_steps = (tok_end - tok0 + 63) / 64;
 
     const int n = lane & 15, g4 = lane >> 4;
     const bool valid_row = n < a.rows;
@@ -536,12 +538,15 @@ __global__ __launch_bounds__(64, 4) void decode_split16_fp8_kernel(DecodeArgs a)
     const int64_t page_k = int64_t(cv.n_kv_heads) * C16 * (kPage * 16);      // bytes
     const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
     const int64_t page_s = int64_t(cv.n_kv_heads) * kPage;                   // floats
-    const bool k_second_page = (n >> 3) != 0;
-    const uint8_t* k_lane = reinterpret_cast<const uint8_t*>(cv.k_pool) + int64_t(h) * C16 * (kPage * 16) + g4 * (kPage * 16) +
-                            (8 * ((n >> 2) & 1) + (n & 3)) * 16;
-    const bool v_second_page = (g4 >> 1) != 0;
-    const uint8_t* v_lane = reinterpret_cast<const uint8_t*>(cv.v_pool) + int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
-    const int s_lane = h * kPage + 8 * (g4 & 1);
+    // K: four 16-key sets per step; in set s, key row m = 4 gq + i is slot 4 s + i of page gq, so that afterwards
+    //    lane group g4 holds all 16 slots of page g4 (set s, register i -> slot 4 s + i).  Lane (m = n, g4) reads
+    //    the 16 bytes d = 64 jj + 16 g4 .. + 15 of its row.
+    const int k_page_sel = n >> 2;
+    const uint8_t* k_lane = reinterpret_cast<const uint8_t*>(cv.k_pool) + int64_t(h) * C16 * (kPage * 16) + g4 * (kPage * 16) + (n & 3) * 16;
+    // V: lane (m = n, g4) reads the whole 16-slot row d = 16 db + m of page g4: slots 0..7 feed the first, 8..15 the
+    //    second matrix instruction of the block
+    const uint8_t* v_lane = reinterpret_cast<const uint8_t*>(cv.v_pool) + int64_t(h) * D * kPage + n * kPage;
+    const int s_lane = h * kPage;
 
     auto column_max = [&](float x) {
         float a1 = x, b1 = x;
@@ -552,60 +557,64 @@ __global__ __launch_bounds__(64, 4) void decode_split16_fp8_kernel(DecodeArgs a)
     };
 
     for (int s = 0; s < n_steps; ++s) {
-        const int id0 = __builtin_amdgcn_readlane(my_page, min(2 * s, last_page));
-        const int id1 = __builtin_amdgcn_readlane(my_page, min(2 * s + 1, last_page));
-        const uint8_t* kp = k_lane + int64_t(k_second_page ? id1 : id0) * page_k;
-        const uint8_t* vp = v_lane + int64_t(v_second_page ? id1 : id0) * page_v;
-        const int64_t sp = int64_t(v_second_page ? id1 : id0) * page_s + s_lane;
-        u32x4 kx[KP], ky[KP];
-        u32x2 vv8[DB];
+        int id[4];
 #pragma unroll
-        for (int jj = 0; jj < KP; ++jj) {
-            kx[jj] = *reinterpret_cast<const u32x4*>(kp + 4 * jj * (kPage * 16));
-            ky[jj] = *reinterpret_cast<const u32x4*>(kp + 4 * jj * (kPage * 16) + 4 * 16);
-        }
+        for (int u = 0; u < 4; ++u) id[u] = __builtin_amdgcn_readlane(my_page, min(4 * s + u, last_page));
+        const int id_k = k_page_sel == 0 ? id[0] : k_page_sel == 1 ? id[1] : k_page_sel == 2 ? id[2] : id[3];
+        const int id_g = g4 == 0 ? id[0] : g4 == 1 ? id[1] : g4 == 2 ? id[2] : id[3];
+        const uint8_t* kp = k_lane + int64_t(id_k) * page_k;
+        const uint8_t* vp = v_lane + int64_t(id_g) * page_v;
+        const int64_t sp = int64_t(id_g) * page_s + s_lane;
+        u32x4 k8[4][KP], v8[DB];
 #pragma unroll
-        for (int db = 0; db < DB; ++db) vv8[db] = *reinterpret_cast<const u32x2*>(vp + db * 16 * kPage);
-        f32x4 ks[2], vs[2];
+        for (int st = 0; st < 4; ++st)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+            for (int jj = 0; jj < KP; ++jj) k8[st][jj] = *reinterpret_cast<const u32x4*>(kp + 4 * jj * (kPage * 16) + 4 * st * 16);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) v8[db] = *reinterpret_cast<const u32x4*>(vp + db * 16 * kPage);
+        f32x4 ks[4], vs[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
             ks[u] = *reinterpret_cast<const f32x4*>(cv.k_scale + sp + 4 * u);
             vs[u] = *reinterpret_cast<const f32x4*>(cv.v_scale + sp + 4 * u);
         }
 
-        const int first = tok0 + 32 * s + 8 * g4;
-        f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
+        const int first = tok0 + 64 * s + 16 * g4;      // token of this lane's slot 0
+        f32x4 sc[4];
 #pragma unroll
-        for (int j = 0; j < KS; ++j) {
-            const int jj = j >> 1, u = j & 1;
-            sx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(kx[jj][2 * u], kx[jj][2 * u + 1]), qf[j], sx, 0, 0, 0);
-            sy = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(ky[jj][2 * u], ky[jj][2 * u + 1]), qf[j], sy, 0, 0, 0);
+        for (int st = 0; st < 4; ++st) {
+            sc[st] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                const int jj = j >> 1, u = j & 1;
+                sc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(k8[st][jj][2 * u], k8[st][jj][2 * u + 1]), qf[j], sc[st], 0, 0, 0);
+            }
         }
-        const bool reaches_limit = tok0 + 32 * s + 32 > limit_min;      // uniform
-        float t[8], vsc[8];
+        const bool reaches_limit = tok0 + 64 * s + 64 > limit_min;      // uniform
+        float t[16], vsc[16];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            t[e] = fmaf(e < 4 ? sx[e] : sy[e - 4], ks[e >> 2][e & 3] * a.scale_log2, -m_ref);
+        for (int e = 0; e < 16; ++e) {                  // slot e = 4 set + register
+            t[e] = fmaf(sc[e >> 2][e & 3], ks[e >> 2][e & 3] * a.scale_log2, -m_ref);
             vsc[e] = vs[e >> 2][e & 3];
         }
         if (reaches_limit) {
             // slots past the visible length hold anything (scales included): remove them by index
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < 16; ++e) {
                 t[e] = first + e < limit ? t[e] : -INFINITY;
                 vsc[e] = first + e < len ? vsc[e] : 0.f;
             }
         }
         float mx = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) mx = fmaxf(mx, t[e]);
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t[e]);
         if (__any(mx > kLazyRise || (!has_ref && mx > -INFINITY))) {
             const float rise = column_max(mx);
             const bool move = has_ref ? rise > 0.f : rise > -INFINITY;
             const float shift = move ? rise : 0.f;
             const float alpha = has_ref ? __builtin_amdgcn_exp2f(-shift) : 1.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] -= shift;
+            for (int e = 0; e < 16; ++e) t[e] -= shift;
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -614,28 +623,33 @@ __global__ __launch_bounds__(64, 4) void decode_split16_fp8_kernel(DecodeArgs a)
             m_ref += shift;
             has_ref = has_ref || move;
         }
-        bf16x8 pb;
+        bf16x8 pb[2];
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) {
+        for (int e = 0; e < 16; e += 2) {
             const float p0 = __builtin_amdgcn_exp2f(t[e]), p1 = __builtin_amdgcn_exp2f(t[e + 1]);
             bf16x2 p2;
             p2[0] = (__bf16)p0;
             p2[1] = (__bf16)p1;
             l_run = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, l_run, false);
-            pb[e] = (__bf16)(p0 * vsc[e]);
-            pb[e + 1] = (__bf16)(p1 * vsc[e + 1]);
+            pb[e >> 3][e & 7] = (__bf16)(p0 * vsc[e]);
+            pb[e >> 3][(e & 7) + 1] = (__bf16)(p1 * vsc[e + 1]);
         }
-        u32x4 keep = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
-        if (tok0 + 32 * s + 32 > len) {
+        u32x4 keep[2];
+        keep[0] = keep[1] = u32x4{0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+        if (tok0 + 64 * s + 64 > len) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                keep[e] = (first + 2 * e < len ? 0x0000ffffu : 0u) | (first + 2 * e + 1 < len ? 0xffff0000u : 0u);
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    keep[hf][e] = (first + 8 * hf + 2 * e < len ? 0x0000ffffu : 0u) | (first + 8 * hf + 2 * e + 1 < len ? 0xffff0000u : 0u);
         }
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const u32x4 vb = __builtin_bit_cast(u32x4, e4m3x8_to_bf16(vv8[db][0], vv8[db][1])) & keep;
-            o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vb), pb, o_acc[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const u32x4 vb = __builtin_bit_cast(u32x4, e4m3x8_to_bf16(v8[db][2 * hf], v8[db][2 * hf + 1])) & keep[hf];
+                o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vb), pb[hf], o_acc[db], 0, 0, 0);
+            }
     }
 
     float l_tot = l_run + __shfl_xor(l_run, 16);
