@@ -98,7 +98,7 @@ def test_metadata_edge_structures(st):
 def test_many_short_sequences_take_the_large_plan_paths(st):
     """2,800 sequences of a few tokens each: more than 64 sequences (segment tables copied to the device instead of
     passed by value) and more than 4,096 work items (items and their longest-first order built by the multi-workgroup
-    kernels).  Metadata bit-exact, attention against the oracle for both dtypes."""
+    kernels).  Metadata bit-exact, attention and its gradients against the oracle for both dtypes."""
     rng = np.random.Generator(np.random.PCG64(250))
     lists = [W.draw_pairs(rng, int(rng.integers(1, 2, endpoint=True)), (0, 3), (0, 3)) for _ in range(2800)]
     lists[7] = (np.array([150]), np.array([140]))            # one sequence with several tiles among them
@@ -110,6 +110,7 @@ def test_many_short_sequences_take_the_large_plan_paths(st):
         if dtype == "f32":
             _check_metadata(st, cfg)
         _run_prefill(st, cfg)
+        _run_prefill_bwd(st, cfg)          # the backward walks the same tables (2,800 sequences, > 4,096 items)
 
 
 def test_plan_validation_rejects_bad_metadata(st):
