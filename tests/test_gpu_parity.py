@@ -711,6 +711,62 @@ def test_decode_workspace_reuse(st):
             assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2, b
 
 
+def test_whole_step_replays_from_a_hip_graph(st):
+    """Nothing on the path allocates or waits: plan build, rotation, prefill, appends, decode and the source chunk are
+    recorded into one HIP graph; every replay -- with eager work of the same kind in between -- reproduces the eager
+    step bit for bit."""
+    rng = np.random.Generator(np.random.PCG64(431))
+    cfg = W.random_prefill(432, 2, 5, (10, 70), (10, 90), 4, 2, 128, "bf16")
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    q0, k0, tv = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+    tq, tk = torch.empty_like(q0), torch.empty_like(k0)
+    n, hq, hkv, d, batch = cfg.n_tokens, 4, 2, 128, 2
+    plan_ws = torch.empty(st.st_plan_workspace_bytes(cfg.batch, n), dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(q0); lse = torch.empty((n, hq), dtype=torch.float32, device=DEV)
+    src_lens = np.array([300, 37]); rsn_lens = np.array([129, 560])
+    caches, _, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=64)
+    base_s, base_r = caches.source.appended_len.clone(), caches.reasoning.appended_len.clone()
+    k_tok = to_dev(W.normal(rng, (batch, 1, hkv, d), "bf16"), "bf16"); v_tok = to_dev(W.normal(rng, (batch, 1, hkv, d), "bf16"), "bf16")
+    q_tok = to_dev(W.normal(rng, (batch, 1, hq, d), "bf16"), "bf16")
+    k_src = to_dev(W.normal(rng, (batch, 20, hkv, d), "bf16"), "bf16"); q_src = to_dev(W.normal(rng, (batch, 20, hq, d), "bf16"), "bf16")
+    vis = torch.from_numpy(src_lens.astype(np.int32)).to(DEV); rl = torch.from_numpy((rsn_lens + 1).astype(np.int32)).to(DEV)
+    sl = torch.from_numpy((src_lens + 20).astype(np.int32)).to(DEV)
+    o_dec = torch.empty_like(q_tok); o_src = torch.empty_like(q_src)
+    dws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, 320, 561), dtype=torch.uint8, device=DEV)
+    cws = torch.empty(st.st_source_chunk_workspace_bytes(batch, hq, hkv, d, 20, 320), dtype=torch.uint8, device=DEV)
+    plan0 = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+    pws = torch.empty(st.st_prefill_workspace_bytes(plan0, hkv, d, st.ST_BF16), dtype=torch.uint8, device=DEV)
+    plan0.destroy()
+    plans = []
+
+    def step():
+        caches.source.appended_len.copy_(base_s); caches.reasoning.appended_len.copy_(base_r)
+        plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+        plans.append(plan)
+        st.st_rope_apply(q0, pos, cfg.theta, out=tq); st.st_rope_apply(k0, pos, cfg.theta, out=tk)
+        st.st_attn_prefill(tq, tk, tv, plan, out=out, lse=lse, workspace=pws)
+        # (a bound on the lengths from the host: no read-back of the device counters, which a capture forbids)
+        st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, rope_theta=cfg.theta, host_len_upper_bound=561)
+        st.st_attn_decode_dual(q_tok, caches, vis, rl, 320, 561, out=o_dec, workspace=dws, rope_theta=cfg.theta)
+        st.st_kv_append(caches, st.ST_SOURCE, k_src, k_src, rope_theta=cfg.theta, host_len_upper_bound=320)
+        st.st_attn_source_chunk(q_src, caches, sl, 320, out=o_src, workspace=cws, rope_theta=cfg.theta)
+
+    step(); torch.cuda.synchronize()
+    want = [t.clone() for t in (out, lse, o_dec, o_src)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for t in (out, lse, o_dec, o_src):
+            t.fill_(float("nan"))
+        graph.replay(); torch.cuda.synchronize()
+        for got, ref in zip((out, lse, o_dec, o_src), want):
+            assert torch.equal(got, ref)
+        step(); torch.cuda.synchronize()                  # eager work between the replays
+
+
 # ------------------------------------------------- source-chunk prefill --
 def _check_source_chunk(st, rng, batch, hq, hkv, d, src_before, n_new, max_new, rope_theta=None):
     """Append a ragged chunk to the source cache, then let its tokens attend over the cache.
