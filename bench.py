@@ -94,6 +94,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
     max_s, max_r = int(S.max()), int(R.max()) + 1
     dec_ws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream()
+    plan_stream = torch.cuda.Stream()
     main = torch.cuda.current_stream()
 
     def step(i_timed):
@@ -101,9 +102,14 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
         side.wait_stream(main)
         with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
             st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk, stream=side)
-        p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+        # the plan needs only the metadata, the rotations only the activations: the plan's three short, latency-bound
+        # kernels run beside the two memory-bound rotations and join before the attention
+        plan_stream.wait_stream(main)
+        with torch.cuda.stream(plan_stream):
+            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, stream=plan_stream)
         st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
         st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
+        main.wait_stream(plan_stream)
         st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
         # kernel, both by the token's index in the reasoning stream (its position id)
@@ -126,7 +132,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
     kern_ms, n_rec = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
     st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
     assert n_rec == n_prof
-    # the timed steps: the whole step (13 kernels on two streams) recorded once into a HIP graph and replayed;
+    # the timed steps: the whole step (13 kernels on three streams) recorded once into a HIP graph and replayed;
     # every replay is first checked against the eager step, and eager launches are timed if capture is unavailable
     mode, graph = "eager", None
     if use_graph:

@@ -352,6 +352,15 @@ typedef struct st_dual_lens {
     int32_t max_rsn_len;
 } st_dual_lens;
 
+/* Tokens per work unit of the decode step with q_len * (n_q_heads / n_kv_heads) <= 16: 0 (default)
+ * chooses by launch size -- 1024 for large batches down to 128 for a few sequences, whose step is
+ * bound by a wave's serial walk over its unit; 128, 256, 512 or 1024 pins it (for tests and
+ * tuning).  Results agree within rounding.  Process-wide.  Returns the previous setting; other
+ * values leave it unchanged.  st_decode_workspace_bytes follows the setting: size the workspace
+ * after changing it.  A workspace sized for other length bounds is accepted as long as it holds
+ * 512-token units; the call then uses the smallest unit the workspace has room for. */
+int32_t st_decode_unit_set(int32_t tokens);
+
 size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
                                  int32_t head_dim, int32_t q_len,
                                  int32_t max_src_len, int32_t max_rsn_len);

@@ -122,6 +122,8 @@ def load_library():
     lib.st_attn_decode_dual_rope.restype = i32
     lib.st_attn_decode_dual_rope.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
                                              f32, C.c_double, vp, sz, vp]
+    lib.st_decode_unit_set.restype = i32
+    lib.st_decode_unit_set.argtypes = [i32]
     lib.st_decode_workspace_bytes.restype = sz
     lib.st_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
     lib.st_attn_decode_dual.restype = i32
@@ -473,6 +475,11 @@ def st_kv_append(caches, which, k_new, v_new, n_new=None, host_len_upper_bound=N
 def st_kv_append_rope(caches, which, k_new, v_new, theta_base, n_new=None, host_len_upper_bound=None, stream=None):
     """st_kv_append for UNROTATED keys: each key is rotated by its index in the cache on the way in."""
     st_kv_append(caches, which, k_new, v_new, n_new, host_len_upper_bound, stream, rope_theta=theta_base)
+
+
+def st_decode_unit_set(tokens):
+    """Pin the decode work unit (128 / 256 / 512 / 1024 tokens; 0 = by launch size); returns the previous setting."""
+    return int(load_library().st_decode_unit_set(int(tokens)))
 
 
 def st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len):

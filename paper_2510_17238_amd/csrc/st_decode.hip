@@ -17,12 +17,15 @@
 #include <type_traits>
 
 #include "st_cache.h"
+#include <atomic>
+
 #include "st_tiles.h"
 
 namespace st {
 
 constexpr int kChunk = 512;                 // tokens per work unit
 constexpr int kSmallDecodeTokens = 1024;    // both caches together: below this one wave per (sequence, KV head) finishes the rows itself
+constexpr int kChunkMin = 128;              // ... of the one-token decode step of a few sequences
 constexpr int kChunkLong = 1024;            // ... of the one-token decode step when there is plenty of work (64 pages: one id per lane)
 
 struct DecodeArgs {
@@ -34,7 +37,7 @@ struct DecodeArgs {
     float* part_ml;    // [B][Hkv][nc][rows][2]
     int batch, q_len, n_q_heads, n_kv_heads, group, rows;
     int ncs, ncr;      // chunk slots per (sequence, head) for the two caches
-    int chunk;         // tokens per work unit (kChunk, or kChunkLong for the one-wave decode kernel)
+    int chunk;         // tokens per work unit (kChunk; kChunkMin .. kChunkLong for the one-wave decode kernels)
     float scale_log2;
     // source-chunk prefill only: ragged query counts and 32-row blocks
     const int32_t* n_new;   // [B] query tokens per sequence, or null for max_new everywhere
@@ -1045,18 +1048,47 @@ __global__ __launch_bounds__(64) void chunk_combine_kernel(DecodeArgs a, uint16_
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 static inline int chunks_of(int len) { return (len + kChunk - 1) / kChunk; }
 
+// Partial results of a decode step cut into `unit`-token work units.
+static inline size_t decode_partial_bytes(int unit, int64_t batch, int hkv, int rows, int d, int max_src, int max_rsn) {
+    const size_t nc = size_t((max_src + unit - 1) / unit) + size_t((max_rsn + unit - 1) / unit);
+    const size_t slots = size_t(batch) * hkv * nc * rows;
+    return align256(slots * d * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
+}
+static std::atomic<int> g_decode_unit{0};     // 0: by the rule below; else the pinned unit (st_decode_unit_set)
+// Tokens per work unit of the one-wave decode kernels (<= 16 query rows): a wave walks its unit serially, one
+// memory round trip per 32 tokens, so the unit is as long as still leaves about a thousand units (four per
+// compute unit) -- 1024 tokens for a large batch (fewest partial results), down to 128 for a few sequences,
+// where the step is bound by that serial walk and not by bandwidth.
+static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_src, int max_rsn) {
+    if (rows > 16) return kChunk;
+    const int pinned = g_decode_unit.load(std::memory_order_relaxed);
+    if (pinned) return pinned;
+    int unit = kChunkLong;
+    while (unit > kChunkMin && batch * hkv * ((max_src + unit - 1) / unit + (max_rsn + unit - 1) / unit) < 1024) unit /= 2;
+    return unit;
+}
+
 }  // namespace st
 
 using namespace st;
+
+extern "C" int32_t st_decode_unit_set(int32_t tokens) {
+    const int prev = g_decode_unit.load(std::memory_order_relaxed);
+    if (tokens == 0 || tokens == 128 || tokens == 256 || tokens == 512 || tokens == 1024)
+        g_decode_unit.store(tokens, std::memory_order_relaxed);
+    return prev;
+}
 
 extern "C" size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                             int32_t q_len, int32_t max_src_len, int32_t max_rsn_len) {
     if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || q_len <= 0 || head_dim <= 0 || max_src_len < 0 || max_rsn_len < 0)
         return 0;
-    const size_t nc = size_t(chunks_of(max_src_len)) + size_t(chunks_of(max_rsn_len));
-    const size_t rows = size_t(q_len) * (n_q_heads / n_kv_heads);
-    const size_t slots = size_t(batch) * n_kv_heads * nc * rows;
-    return align256(slots * head_dim * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
+    const int rows = q_len * (n_q_heads / n_kv_heads);
+    // enough for 512-token units whatever the bounds of a later call, and for the unit this very call would use
+    const size_t base = decode_partial_bytes(kChunk, batch, n_kv_heads, rows, head_dim, max_src_len, max_rsn_len);
+    const int unit = decode_unit_tokens(batch, n_kv_heads, rows, max_src_len, max_rsn_len);
+    const size_t own = decode_partial_bytes(unit, batch, n_kv_heads, rows, head_dim, max_src_len, max_rsn_len);
+    return base > own ? base : own;
 }
 
 static st_status decode_dual_impl(void* out, float* lse, const void* q, const st_dual_cache* caches,
@@ -1086,7 +1118,7 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     if (lens->max_src_len < 0 || lens->max_rsn_len < 0) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: negative length bound");
     if (int64_t(lens->max_src_len) > int64_t(cs.max_pages_per_seq) * kPage || int64_t(lens->max_rsn_len) > int64_t(cr.max_pages_per_seq) * kPage)
         return fail(ST_ERR_CAPACITY, "st_attn_decode_dual: length bound exceeds the page table");
-    const size_t need = st_decode_workspace_bytes(batch, n_q_heads, hkv, d, lens->q_len, lens->max_src_len, lens->max_rsn_len);
+    const size_t need = decode_partial_bytes(kChunk, batch, hkv, lens->q_len * group, d, lens->max_src_len, lens->max_rsn_len);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: workspace must be non-null and 256-byte aligned");
     if (workspace_bytes < need) return fail(ST_ERR_CAPACITY, "st_attn_decode_dual: workspace has %zu bytes, needs %zu", workspace_bytes, need);
@@ -1104,12 +1136,10 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.n_kv_heads = hkv;
     a.group = group;
     a.rows = lens->q_len * group;
-    // Work unit: 512 tokens of one cache; 1024 for the one-wave kernel when that still leaves a thousand
-    // units or more -- its duration does not depend on the unit size, and half as many partial results
-    // have to be written and merged.  (The workspace is sized for the smaller unit.)
-    a.chunk = kChunk;
-    if (a.rows <= 16 && int64_t(batch) * hkv * ((lens->max_src_len + kChunkLong - 1) / kChunkLong + (lens->max_rsn_len + kChunkLong - 1) / kChunkLong) >= 1024)
-        a.chunk = kChunkLong;
+    // Work unit: see decode_unit_tokens; a workspace sized for other length bounds may only hold longer units.
+    a.chunk = decode_unit_tokens(batch, hkv, a.rows, lens->max_src_len, lens->max_rsn_len);
+    while (a.chunk < kChunk && decode_partial_bytes(a.chunk, batch, hkv, a.rows, d, lens->max_src_len, lens->max_rsn_len) > workspace_bytes)
+        a.chunk *= 2;
     a.ncs = (lens->max_src_len + a.chunk - 1) / a.chunk;
     a.ncr = (lens->max_rsn_len + a.chunk - 1) / a.chunk;
     a.scale_log2 = scale * kLog2e;

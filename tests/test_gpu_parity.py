@@ -496,6 +496,22 @@ def test_decode_q_len_8(st):
     _check_decode(st, rng, 3, 8, 2, 128, np.array([64, 10, 290]), np.array([8, 300, 40]), np.array([64, 0, 290]), q_len=8)
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+@pytest.mark.parametrize("unit", [128, 256, 512, 1024])
+def test_decode_every_unit_size(st, unit, fp8):
+    """The work unit is chosen by launch size (small launches take short units); every size the rule can pick is
+    pinned here on caches that span several units with ragged ends, and gives the same rows."""
+    rng = np.random.Generator(np.random.PCG64(413))
+    src_lens = np.array([1100, 129, 640]); rsn_lens = np.array([700, 1500, 127]); src_vis = np.array([1025, 128, 0])
+    prev = st.st_decode_unit_set(unit)
+    try:
+        assert st.st_decode_unit_set(unit) == unit
+        assert st.st_decode_unit_set(100) == unit                 # not a unit size: nothing changes
+        _check_decode(st, rng, 3, 4, 2, 128, src_lens, rsn_lens, src_vis, fp8=fp8)
+    finally:
+        st.st_decode_unit_set(prev)
+
+
 # ------------------------------------------------------- 8-bit caches --
 def test_kv_append_fp8_codes_and_scales_are_the_oracles(st):
     """Bytes and scales in the pools == the oracle's E4M3 codes and powers of two, bit for bit; untouched slots keep the fill."""
