@@ -403,12 +403,28 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
 }
 
 // Short caches (the streaming session of one listener: a hundred source tokens, a few hundred reasoning tokens): one
-// wave per (sequence, KV head) folds every unit of BOTH caches into one running state and writes the finished rows
-// itself -- no partial results, no merge kernel, one launch per layer and token instead of two.
+// workgroup per (sequence, KV head) does everything -- no partial results in memory, no merge kernel, one launch per
+// layer and token instead of two.  Such a step is bound by the chain of memory round trips a wave makes walking its
+// tokens, so the tokens of BOTH caches are dealt out in short units to the waves of the workgroup (wave w folds
+// units w, w + W, ... into one running state), and the waves' states meet in LDS, where all threads merge them
+// (log-sum-exp, fixed order) and write the finished rows.
+#ifndef ST_SMALL_WAVES
+#define ST_SMALL_WAVES 8
+#endif
+#ifndef ST_SMALL_UNIT
+#define ST_SMALL_UNIT 64
+#endif
+constexpr int kSmallWaves = ST_SMALL_WAVES, kSmallUnit = ST_SMALL_UNIT;
 template <int D>
-__global__ __launch_bounds__(64, 4) void decode_small16_kernel(DecodeArgs a, uint16_t* __restrict__ out, float* __restrict__ lse) {
+__global__ __launch_bounds__(64 * kSmallWaves) void decode_small16_kernel(DecodeArgs a, uint16_t* __restrict__ out, float* __restrict__ lse) {
     constexpr int KS = D / 32, DB = D / 16;
-    const int lane = threadIdx.x;
+    constexpr int W = kSmallWaves, UNIT = kSmallUnit;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    // [W][rows][D] partial outputs, then [W][rows] reference exponents, then [W][rows] sums
+    float* sm_o = reinterpret_cast<float*>(smem_raw);
+    float* sm_m = sm_o + W * a.rows * D;
+    float* sm_l = sm_m + W * a.rows;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int h = int(blockIdx.x % unsigned(a.n_kv_heads));
     const int b = int(blockIdx.x / unsigned(a.n_kv_heads));
     const int n = lane & 15, g4 = lane >> 4;
@@ -418,41 +434,76 @@ __global__ __launch_bounds__(64, 4) void decode_small16_kernel(DecodeArgs a, uin
     const int hq = h * a.group + nr % a.group;
     const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
     const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+    const int units_s = (len_s + UNIT - 1) / UNIT, units = units_s + (len_r + UNIT - 1) / UNIT;
 
-    bf16x8 qf[KS];
-    {
-        const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
-    }
-    if (a.rope) rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
     f32x4 o_acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_ref = 0.f, l_run = 0.f;
     bool has_ref = false;
-    // the source slice is seen whole; reasoning token j by rows t with j <= len_r - q_len + t
-    for (int tok0 = 0; tok0 < len_s; tok0 += kChunkLong)
-        scan_unit16<D>(a.src, b, h, lane, tok0, min(len_s, tok0 + kChunkLong), len_s, len_s, len_s, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
-    const int limit = max(len_r - a.q_len + t_row + 1, 0), limit_min = max(len_r - a.q_len + 1, 0);
-    for (int tok0 = 0; tok0 < len_r; tok0 += kChunkLong)
-        scan_unit16<D>(a.rsn, b, h, lane, tok0, min(len_r, tok0 + kChunkLong), len_r, limit, limit_min, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
-
+    if (wave < units) {                               // (uniform per wave)
+        bf16x8 qf[KS];
+        {
+            const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
+        }
+        if (a.rope) rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
+        // the source slice is seen whole; reasoning token j by rows t with j <= len_r - q_len + t
+        const int limit = max(len_r - a.q_len + t_row + 1, 0), limit_min = max(len_r - a.q_len + 1, 0);
+        for (int u = wave; u < units; u += W) {
+            if (u < units_s) {
+                const int tok0 = u * UNIT;
+                scan_unit16<D>(a.src, b, h, lane, tok0, min(len_s, tok0 + UNIT), len_s, len_s, len_s, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+            } else {
+                const int tok0 = (u - units_s) * UNIT;
+                scan_unit16<D>(a.rsn, b, h, lane, tok0, min(len_r, tok0 + UNIT), len_r, limit, limit_min, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+            }
+        }
+    }
     float l_tot = l_run + __shfl_xor(l_run, 16);
     l_tot += __shfl_xor(l_tot, 32);
-    if (!valid_row) return;
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;              // a row that sees nothing: out = 0, lse = -inf
-    uint16_t* op = out + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D;
-    // lane (n, g4), block db, register i  <->  d = 16 db + 4 g4 + i
+    if (valid_row) {
+        // lane (n, g4), block db, register i  <->  d = 16 db + 4 g4 + i
+        float* po = sm_o + (wave * a.rows + n) * D;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
+        for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db + 4 * g4) = o_acc[db];
+        if (g4 == 0) {
+            sm_m[wave * a.rows + n] = has_ref ? m_ref : -INFINITY;
+            sm_l[wave * a.rows + n] = l_tot;
+        }
+    }
+    __syncthreads();
+    // merge: thread -> (row, 4 head dims); rows * D / 4 of the threads have work
+    const int e0 = int(threadIdx.x) * 4;
+    for (int e = e0; e < a.rows * D; e += 64 * W * 4) {
+        const int row = e / D, d0 = e % D;
+        float m_all = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < W; ++w) m_all = fmaxf(m_all, sm_m[w * a.rows + row]);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+        if (m_all != -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                const float mw = sm_m[w * a.rows + row];
+                if (mw == -INFINITY) continue;                        // a wave that saw nothing for this row
+                const float wt = __builtin_amdgcn_exp2f(mw - m_all);
+                den = fmaf(wt, sm_l[w * a.rows + row], den);
+                const f32x4 o = *reinterpret_cast<const f32x4*>(sm_o + (w * a.rows + row) * D + d0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fmaf(wt, o[i], acc[i]);
+            }
+        }
+        const float inv = den > 0.f ? 1.f / den : 0.f;               // a row that sees nothing: out = 0, lse = -inf
+        const int t = row / a.group, hq_row = h * a.group + row % a.group;
         bf16x4 o4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(o_acc[db][i] * inv);
-        *reinterpret_cast<bf16x4*>(op + 16 * db + 4 * g4) = o4;
+        for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(acc[i] * inv);
+        *reinterpret_cast<bf16x4*>(out + ((int64_t(b) * a.q_len + t) * a.n_q_heads + hq_row) * D + d0) = o4;
+        if (lse && d0 == 0)
+            lse[(int64_t(b) * a.q_len + t) * a.n_q_heads + hq_row] = den > 0.f ? (m_all + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
     }
-    if (lse && g4 == 0)
-        lse[(int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
 }
 
 // The one-wave kernel over 8-bit caches (E4M3 codes, one power-of-two fp32 scale per key row and per value
@@ -1156,8 +1207,13 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     // Short caches: one wave per (sequence, KV head) does everything (no partials, no merge launch) -- when the
     // serial walk of both caches is short and there are too few sequences for the split to pay anyway.
     if (!fp8 && a.rows <= 16 && lens->max_src_len + lens->max_rsn_len <= kSmallDecodeTokens && int64_t(batch) * hkv <= 0x7fffffff) {
-        if (d == 64) hipLaunchKernelGGL((decode_small16_kernel<64>), dim3((unsigned)(batch * hkv)), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
-        else hipLaunchKernelGGL((decode_small16_kernel<128>), dim3((unsigned)(batch * hkv)), dim3(64), 0, s, a, static_cast<uint16_t*>(out), lse);
+        const size_t smem = size_t(kSmallWaves) * a.rows * (d + 2) * sizeof(float);
+        if (smem > 64 * 1024) {                         // beyond the default limit (16 rows of 128 dims only)
+            const void* fn = d == 64 ? reinterpret_cast<const void*>(&decode_small16_kernel<64>) : reinterpret_cast<const void*>(&decode_small16_kernel<128>);
+            ST_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+        }
+        if (d == 64) hipLaunchKernelGGL((decode_small16_kernel<64>), dim3((unsigned)(batch * hkv)), dim3(64 * kSmallWaves), smem, s, a, static_cast<uint16_t*>(out), lse);
+        else hipLaunchKernelGGL((decode_small16_kernel<128>), dim3((unsigned)(batch * hkv)), dim3(64 * kSmallWaves), smem, s, a, static_cast<uint16_t*>(out), lse);
         ST_LAUNCH_CHECK("decode_small16_kernel");
         return ST_OK;
     }

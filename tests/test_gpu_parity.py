@@ -491,6 +491,17 @@ def test_decode_head_dim_64_and_group_4(st):
     _check_decode(st, rng, 2, 8, 2, 64, np.array([100, 513]), np.array([700, 31]), np.array([100, 500]))
 
 
+@pytest.mark.parametrize("q_len,hq,hkv,d,rope", [(1, 4, 2, 128, None), (4, 8, 2, 128, 1.0e6), (2, 16, 2, 64, None), (3, 4, 1, 64, 1.0e6)])
+def test_decode_short_caches_one_workgroup_per_head(st, q_len, hq, hkv, d, rope):
+    """Both caches together at most 1,024 tokens: one launch, the units dealt out to the waves of a workgroup and
+    merged in LDS -- lengths with fewer units than waves, more units than waves, ragged ends, empty caches; up to 16
+    rows (the largest LDS footprint)."""
+    rng = np.random.Generator(np.random.PCG64(414 + q_len))
+    src_lens = np.array([98, 0, 500, 64, 1, 130, 16]); rsn_lens = np.array([439, 5, 524, 3, 4, 890, 700])
+    src_vis = np.array([98, 0, 449, 63, 0, 130, 16])
+    _check_decode(st, rng, 7, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=q_len, rope_theta=rope)
+
+
 def test_decode_q_len_8(st):
     rng = np.random.Generator(np.random.PCG64(412))
     _check_decode(st, rng, 3, 8, 2, 128, np.array([64, 10, 290]), np.array([8, 300, 40]), np.array([64, 0, 290]), q_len=8)
