@@ -380,6 +380,29 @@ st_status st_attn_decode_dual_rope(void* out, float* lse, const void* q,
                                    int32_t batch, int32_t n_q_heads, float scale, double theta_base,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* One decoding step in one call (Alg. 1, decoding loop: the new token's key and value are stored
+ * in the reasoning cache, then the token attends over both caches): the same result as
+ *   st_kv_append[_rope](caches, ST_REASONING, k_new, v_new, NULL, 1, ...) followed by
+ *   st_attn_decode_dual[_rope](out, lse, q, caches, lens, ...)
+ * for q_len = 1, within rounding.  lens->rsn_len[b] is the length of sequence b's reasoning stream
+ * INCLUDING the new token, as for st_attn_decode_dual: the token is stored at index
+ * rsn_len[b] - 1 and reasoning.appended_len[b] becomes rsn_len[b] (the caller's lengths are
+ * authoritative here; with rsn_len[b] = 0 nothing is stored for sequence b and its length stays).
+ *   q            : [batch, 1, n_q_heads, head_dim] bf16 device
+ *   k_new, v_new : [batch, 1, n_kv_heads, head_dim] bf16 device, 16-byte aligned
+ *   theta_base   : > 0: q and k_new are UNROTATED and are rotated by the token's position id
+ *                  rsn_len[b] - 1 (Sec. 3.2); 0: both are already rotated
+ * When both caches are short (max_src_len + max_rsn_len <= 1024) the step is ONE kernel launch:
+ * the workgroup that attends for a KV head also stores that head's key and value, and takes the
+ * new token from registers.  Longer caches take two launches, as the separate calls do.
+ * lens->q_len other than 1 and 8-bit caches give ST_ERR_UNSUPPORTED.  Everything else (workspace,
+ * bounds, errors) as for st_attn_decode_dual. */
+st_status st_attn_decode_dual_append(void* out, float* lse, const void* q, const void* k_new,
+                                     const void* v_new, const st_dual_cache* caches,
+                                     const st_dual_lens* lens, int32_t batch, int32_t n_q_heads,
+                                     float scale, double theta_base, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------
  * st_attn_source_chunk -- attention of an arriving source chunk over the paged source
  * cache.  Alg. 1, prefill loop ("read the input sentence and save hidden state to the
@@ -434,7 +457,7 @@ st_status st_attn_source_chunk_rope(void* out, float* lse, const void* q, const 
  *   ST_SCHED_BATCH      the batch paradigm: wait for the last sentence, prefill everything,
  *                       then decode every unit with the WHOLE input visible.
  * The keys and queries are given unrotated and are rotated inside the kernels by their index in
- * their stream (st_kv_append_rope, st_attn_source_chunk_rope, st_attn_decode_dual_rope).
+ * their stream (st_kv_append_rope, st_attn_source_chunk_rope, st_attn_decode_dual_append).
  * Every layer is fed the same activations (projections and MLP need weights and are outside this
  * path); outputs are those of the last layer.  All caches must be empty at the start.
  *

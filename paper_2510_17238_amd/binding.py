@@ -122,6 +122,9 @@ def load_library():
     lib.st_attn_decode_dual_rope.restype = i32
     lib.st_attn_decode_dual_rope.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
                                              f32, C.c_double, vp, sz, vp]
+    lib.st_attn_decode_dual_append.restype = i32
+    lib.st_attn_decode_dual_append.argtypes = [vp, vp, vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
+                                               f32, f64, vp, sz, vp]
     lib.st_decode_unit_set.restype = i32
     lib.st_decode_unit_set.argtypes = [i32]
     lib.st_decode_workspace_bytes.restype = sz
@@ -514,6 +517,30 @@ def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rs
 def st_attn_decode_dual_rope(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, theta_base, **kw):
     """st_attn_decode_dual for UNROTATED queries (rotated in the kernel by their index in the reasoning stream)."""
     return st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, rope_theta=theta_base, **kw)
+
+
+def st_attn_decode_dual_append(q, k_new, v_new, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, theta_base=0.0, scale=0.0,
+                               out=None, lse=None, workspace=None, stream=None):
+    """One decoding step: k_new / v_new [batch, 1, Hkv, D] go into the reasoning cache at index rsn_len - 1 and
+    q [batch, 1, Hq, D] attends over both caches.  theta_base > 0: q and k_new are unrotated; 0: already rotated."""
+    lib = load_library()
+    assert q.is_cuda and q.is_contiguous() and q.dtype == torch.bfloat16 and q.dim() == 4
+    batch, q_len, hq, d = q.shape
+    hkv = caches.source.n_kv_heads
+    for t in (k_new, v_new):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16 and tuple(t.shape) == (batch, 1, hkv, d)
+    _dev_i32(src_visible_len, "src_visible_len"); _dev_i32(rsn_len, "rsn_len")
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = st_decode_workspace_bytes(batch, hq, hkv, d, q_len, max_src_len, max_rsn_len)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    st = caches.struct()
+    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
+    _check(lib.st_attn_decode_dual_append(_ptr(out), _ptr(lse), _ptr(q), _ptr(k_new), _ptr(v_new), C.byref(st), C.byref(lens), batch, hq,
+                                          float(scale), float(theta_base), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                          _stream(stream)))
+    return out
 
 
 def st_source_chunk_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, max_new, max_src_len):

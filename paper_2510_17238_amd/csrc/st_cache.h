@@ -20,5 +20,8 @@ struct CacheView {
 
 st_status check_cache(const st_kv_cache& c, const char* who, const char* which, bool allow_fp8 = false);
 CacheView cache_view(const st_kv_cache& c);
+// One token per sequence into a (checked, bf16) cache at index len_after[b] - 1; the length becomes len_after[b].
+st_status append_token_at(const st_kv_cache& c, const void* k_new, const void* v_new, const int32_t* len_after, int batch,
+                          bool rotate, double theta_base, hipStream_t s);
 
 }  // namespace st

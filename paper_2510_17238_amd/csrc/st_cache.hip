@@ -112,12 +112,16 @@ __global__ __launch_bounds__(256) void kv_append_kernel(CacheView cache, const u
 template <int D, bool ROPE>
 __global__ __launch_bounds__(256) void kv_append_token_kernel(CacheView cache, const uint16_t* __restrict__ k_new,
                                                               const uint16_t* __restrict__ v_new,
-                                                              const int32_t* __restrict__ n_new, RopeFreq freq) {
+                                                              const int32_t* __restrict__ n_new,
+                                                              const int32_t* __restrict__ len_after, RopeFreq freq) {
     constexpr int KCH = D / 8;
     const int b = blockIdx.x;
     const int capacity = cache.max_pages * kPage;
-    const int start = min(max(cache.appended_len[b], 0), capacity);
-    int n = n_new ? min(max(n_new[b], 0), 1) : 1;
+    // the token's index: the cache's own length, or -- len_after given -- the caller's length INCLUDING the token
+    // minus one (a length of 0 there: nothing to store for this sequence)
+    const int given = len_after ? min(max(len_after[b], 0), capacity) : 0;
+    const int start = len_after ? max(given - 1, 0) : min(max(cache.appended_len[b], 0), capacity);
+    int n = len_after ? (given > 0 ? 1 : 0) : (n_new ? min(max(n_new[b], 0), 1) : 1);
     n = min(n, capacity - start);
     __syncthreads();                                     // every thread has read the old length
     if (n == 0) return;
@@ -286,6 +290,23 @@ CacheView cache_view(const st_kv_cache& c) {
     return v;
 }
 
+st_status append_token_at(const st_kv_cache& c, const void* k_new, const void* v_new, const int32_t* len_after, int batch,
+                          bool rotate, double theta_base, hipStream_t s) {
+    const CacheView cv = cache_view(c);
+    const RopeFreq freq = rotate ? make_rope_freq(theta_base, c.head_dim) : RopeFreq{};
+    auto token = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3((unsigned)batch), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new,
+                           (const int32_t*)nullptr, len_after, freq);
+    };
+    if (c.head_dim == 64) {
+        if (rotate) token(kv_append_token_kernel<64, true>); else token(kv_append_token_kernel<64, false>);
+    } else {
+        if (rotate) token(kv_append_token_kernel<128, true>); else token(kv_append_token_kernel<128, false>);
+    }
+    ST_LAUNCH_CHECK("kv_append_token_kernel");
+    return ST_OK;
+}
+
 }  // namespace st
 
 using namespace st;
@@ -317,7 +338,8 @@ static st_status kv_append_impl(const char* who, const st_dual_cache* caches, st
     if (max_new == 1 && !fp8) {
         // the decoding step: one launch, the workgroup of a sequence writes its new length itself
         auto token = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, dim3((unsigned)batch), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new, n_new, freq);
+            hipLaunchKernelGGL(kernel, dim3((unsigned)batch), dim3(256), 0, s, cv, (const uint16_t*)k_new, (const uint16_t*)v_new, n_new,
+                               (const int32_t*)nullptr, freq);
         };
         if (c.head_dim == 64) {
             if (rotate) token(kv_append_token_kernel<64, true>); else token(kv_append_token_kernel<64, false>);

@@ -415,15 +415,40 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
 #define ST_SMALL_UNIT 64
 #endif
 constexpr int kSmallWaves = ST_SMALL_WAVES, kSmallUnit = ST_SMALL_UNIT;
-template <int D>
-__global__ __launch_bounds__(64 * kSmallWaves) void decode_small16_kernel(DecodeArgs a, uint16_t* __restrict__ out, float* __restrict__ lse) {
-    constexpr int KS = D / 32, DB = D / 16;
+
+// Rotation of a fragment set (layout of rotate_query<KS, 32>) by cos / sin values parked in LDS: entry i belongs
+// to head dims i and D/2 + i.
+template <int KS>
+__device__ __forceinline__ void rotate_fragments(bf16x8 (&f)[KS], int off, const float* cs, const float* sn) {
+#pragma unroll
+    for (int j = 0; j < KS / 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float c = cs[32 * j + off + e], s_ = sn[32 * j + off + e];
+            const float x = float(f[j][e]), y = float(f[j + KS / 2][e]);
+            f[j][e] = (__bf16)(x * c - y * s_);
+            f[j + KS / 2][e] = (__bf16)(y * c + x * s_);
+        }
+}
+
+// APPEND (one new token per sequence, q_len = 1): k_new / v_new [batch][Hkv][D] is the token at index
+// rsn_len[b] - 1 of the reasoning stream.  The workgroup of (sequence, KV head) stores its head's key (rotated by
+// that index if a.rope) and value in the reasoning cache, folds the token in from registers -- score in fp32 from
+// the bf16 operands, as the matrix instruction would -- and walks the cache only up to the token before it; the
+// workgroup of head 0 writes the new length.  Nobody in this launch reads what it writes.
+template <int D, bool APPEND>
+__global__ __launch_bounds__(64 * kSmallWaves) void decode_small16_kernel(DecodeArgs a, uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                                          const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new) {
+    constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
     constexpr int W = kSmallWaves, UNIT = kSmallUnit;
+    constexpr int WP = APPEND ? W + 1 : W;            // states to merge: the waves' and the new token's
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    // [W][rows][D] partial outputs, then [W][rows] reference exponents, then [W][rows] sums
+    // [WP][rows][D] partial outputs, [WP][rows] reference exponents, [WP][rows] sums, [D/2] cos, [D/2] sin
     float* sm_o = reinterpret_cast<float*>(smem_raw);
-    float* sm_m = sm_o + W * a.rows * D;
-    float* sm_l = sm_m + W * a.rows;
+    float* sm_m = sm_o + WP * a.rows * D;
+    float* sm_l = sm_m + WP * a.rows;
+    float* sm_cs = sm_l + WP * a.rows;
+    float* sm_sn = sm_cs + D / 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int h = int(blockIdx.x % unsigned(a.n_kv_heads));
     const int b = int(blockIdx.x / unsigned(a.n_kv_heads));
@@ -433,24 +458,71 @@ __global__ __launch_bounds__(64 * kSmallWaves) void decode_small16_kernel(Decode
     const int t_row = nr / a.group;
     const int hq = h * a.group + nr % a.group;
     const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
-    const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+    const int len_all = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+    const bool add = APPEND && len_all > 0;          // (rsn_len 0: an idle sequence, nothing to store)
+    const int len_r = add ? len_all - 1 : len_all;   // cached reasoning tokens to walk
     const int units_s = (len_s + UNIT - 1) / UNIT, units = units_s + (len_r + UNIT - 1) / UNIT;
 
+    if (a.rope) {
+        // q_len rows at consecutive positions: the workgroup evaluates the D/2 (cos, sin) pairs of the LAST row's
+        // position once; other rows (q_len > 1 only) rotate by their own position the slow way
+        if (threadIdx.x < D / 2) rope_cos_sin(max(len_all - 1, 0), a.freq.f[threadIdx.x], &sm_cs[threadIdx.x], &sm_sn[threadIdx.x]);
+        __syncthreads();
+    }
     f32x4 o_acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_ref = 0.f, l_run = 0.f;
     bool has_ref = false;
-    if (wave < units) {                               // (uniform per wave)
+    if (wave < units || (APPEND && wave == W - 1)) {      // (uniform per wave)
         bf16x8 qf[KS];
         {
             const uint16_t* qp = a.q + ((int64_t(b) * a.q_len + t_row) * a.n_q_heads + hq) * D + 8 * g4;
 #pragma unroll
             for (int j = 0; j < KS; ++j) qf[j] = *reinterpret_cast<const bf16x8*>(qp + 32 * j);
         }
-        if (a.rope) rotate_query<KS, 32>(qf, 8 * g4, max(len_r - a.q_len + t_row, 0), a.freq);
-        // the source slice is seen whole; reasoning token j by rows t with j <= len_r - q_len + t
-        const int limit = max(len_r - a.q_len + t_row + 1, 0), limit_min = max(len_r - a.q_len + 1, 0);
+        if (a.rope) {
+            if (a.q_len == 1) rotate_fragments<KS>(qf, 8 * g4, sm_cs, sm_sn);
+            else rotate_query<KS, 32>(qf, 8 * g4, max(len_all - a.q_len + t_row, 0), a.freq);
+        }
+        if (APPEND && wave == W - 1 && add) {
+            // the new token: key fragments in the query's layout (piece 4 j + g4 of the row), the same for every row
+            bf16x8 kf[KS];
+            const uint16_t* kp = k_new + (int64_t(b) * a.n_kv_heads + h) * D + 8 * g4;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) kf[j] = *reinterpret_cast<const bf16x8*>(kp + 32 * j);
+            if (a.rope) rotate_fragments<KS>(kf, 8 * g4, sm_cs, sm_sn);
+            float dot = 0.f;
+#pragma unroll
+            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = fmaf(float(qf[j][e]), float(kf[j][e]), dot);
+            dot += __shfl_xor(dot, 16);
+            dot += __shfl_xor(dot, 32);
+            if (valid_row && g4 == 0) {
+                sm_m[W * a.rows + n] = dot * a.scale_log2;
+                sm_l[W * a.rows + n] = 1.f;
+            }
+            // into the cache: page of index len_all - 1, this head
+            const int idx = len_all - 1;
+            const int id = a.rsn.page_table[int64_t(b) * a.rsn.max_pages + idx / kPage];
+            const int slot = idx % kPage;
+            const uint16_t* vp = v_new + (int64_t(b) * a.n_kv_heads + h) * D;
+            if (id >= 0 && id < a.rsn.n_pages) {             // never write outside the pool
+                if (n == 0) {
+                    uint16_t* kdst = a.rsn.k_pool + (int64_t(id) * a.n_kv_heads + h) * KCH * (kPage * 8) + slot * 8;
+#pragma unroll
+                    for (int j = 0; j < KS; ++j) *reinterpret_cast<bf16x8*>(kdst + (4 * j + g4) * (kPage * 8)) = kf[j];
+                }
+                uint16_t* vdst = a.rsn.v_pool + (int64_t(id) * a.n_kv_heads + h) * (D * kPage) + slot;
+                for (int d0 = lane; d0 < D; d0 += 64) vdst[d0 * kPage] = vp[d0];
+            }
+            // the token's value row is its partial output, the same for every row
+            for (int e = lane; e < a.rows * D; e += 64) sm_o[W * a.rows * D + e] = bf16_bits_to_f32(vp[e % D]);
+            if (h == 0 && lane == 0) a.rsn.appended_len[b] = len_all;
+        }
+        // the source slice is seen whole; reasoning token j by rows t with j <= len_all - q_len + t
+        const int limit = min(max(len_all - a.q_len + t_row + 1, 0), len_r), limit_min = min(max(len_all - a.q_len + 1, 0), len_r);
         for (int u = wave; u < units; u += W) {
             if (u < units_s) {
                 const int tok0 = u * UNIT;
@@ -461,6 +533,7 @@ __global__ __launch_bounds__(64 * kSmallWaves) void decode_small16_kernel(Decode
             }
         }
     }
+    if (APPEND && !add && wave == W - 1 && lane < a.rows) sm_m[W * a.rows + lane] = -INFINITY;
     float l_tot = l_run + __shfl_xor(l_run, 16);
     l_tot += __shfl_xor(l_tot, 32);
     if (valid_row) {
@@ -480,14 +553,14 @@ __global__ __launch_bounds__(64 * kSmallWaves) void decode_small16_kernel(Decode
         const int row = e / D, d0 = e % D;
         float m_all = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < W; ++w) m_all = fmaxf(m_all, sm_m[w * a.rows + row]);
+        for (int w = 0; w < WP; ++w) m_all = fmaxf(m_all, sm_m[w * a.rows + row]);
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
         if (m_all != -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < W; ++w) {
+            for (int w = 0; w < WP; ++w) {
                 const float mw = sm_m[w * a.rows + row];
-                if (mw == -INFINITY) continue;                        // a wave that saw nothing for this row
+                if (mw == -INFINITY) continue;                        // a state that holds nothing for this row
                 const float wt = __builtin_amdgcn_exp2f(mw - m_all);
                 den = fmaf(wt, sm_l[w * a.rows + row], den);
                 const f32x4 o = *reinterpret_cast<const f32x4*>(sm_o + (w * a.rows + row) * D + d0);
@@ -1144,8 +1217,17 @@ extern "C" size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, in
 
 static st_status decode_dual_impl(void* out, float* lse, const void* q, const st_dual_cache* caches,
                                   const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale, bool rotate,
-                                  double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                  double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                  const void* k_new = nullptr, const void* v_new = nullptr, bool append = false) {
     if (!out || !q || !caches || !lens) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null pointer");
+    if (append) {
+        if (!k_new || !v_new) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_append: null pointer");
+        if (!aligned16(k_new) || !aligned16(v_new)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_append: k_new / v_new must be 16-byte aligned");
+        if (lens->q_len != 1) return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual_append: one token per step (q_len %d)", lens->q_len);
+        if (caches->source.dtype != ST_BF16 || caches->reasoning.dtype != ST_BF16)
+            return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual_append: bf16 caches only");
+        if (!caches->reasoning.appended_len) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_append: appended_len is null");
+    }
     if (!lens->src_visible_len || !lens->rsn_len) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null length vector");
     if (!aligned16(out) || !aligned16(q)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: q / out must be 16-byte aligned");
     st_status r = check_cache(caches->source, "st_attn_decode_dual", "source", true);
@@ -1207,15 +1289,24 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     // Short caches: one wave per (sequence, KV head) does everything (no partials, no merge launch) -- when the
     // serial walk of both caches is short and there are too few sequences for the split to pay anyway.
     if (!fp8 && a.rows <= 16 && lens->max_src_len + lens->max_rsn_len <= kSmallDecodeTokens && int64_t(batch) * hkv <= 0x7fffffff) {
-        const size_t smem = size_t(kSmallWaves) * a.rows * (d + 2) * sizeof(float);
-        if (smem > 64 * 1024) {                         // beyond the default limit (16 rows of 128 dims only)
-            const void* fn = d == 64 ? reinterpret_cast<const void*>(&decode_small16_kernel<64>) : reinterpret_cast<const void*>(&decode_small16_kernel<128>);
-            ST_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
-        }
-        if (d == 64) hipLaunchKernelGGL((decode_small16_kernel<64>), dim3((unsigned)(batch * hkv)), dim3(64 * kSmallWaves), smem, s, a, static_cast<uint16_t*>(out), lse);
-        else hipLaunchKernelGGL((decode_small16_kernel<128>), dim3((unsigned)(batch * hkv)), dim3(64 * kSmallWaves), smem, s, a, static_cast<uint16_t*>(out), lse);
+        const size_t smem = (size_t(kSmallWaves + (append ? 1 : 0)) * a.rows * (d + 2) + d) * sizeof(float);
+        auto launch = [&](auto kernel) -> st_status {
+            if (smem > 64 * 1024)                       // beyond the default limit (16 rows of 128 dims only)
+                ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            hipLaunchKernelGGL(kernel, dim3((unsigned)(batch * hkv)), dim3(64 * kSmallWaves), smem, s, a, static_cast<uint16_t*>(out), lse,
+                               static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new));
+            return ST_OK;
+        };
+        const st_status lr = d == 64 ? (append ? launch(decode_small16_kernel<64, true>) : launch(decode_small16_kernel<64, false>))
+                                     : (append ? launch(decode_small16_kernel<128, true>) : launch(decode_small16_kernel<128, false>));
+        if (lr != ST_OK) return lr;
         ST_LAUNCH_CHECK("decode_small16_kernel");
         return ST_OK;
+    }
+    if (append) {
+        // longer caches: the token goes in with a launch of its own, then the step below reads it like any other
+        const st_status ar = append_token_at(cr, k_new, v_new, lens->rsn_len, batch, rotate, theta_base, s);
+        if (ar != ST_OK) return ar;
     }
     const int64_t units = int64_t(batch) * hkv * (a.ncs + a.ncr);
     const int64_t out_units = int64_t(batch) * a.q_len * n_q_heads;
@@ -1260,6 +1351,15 @@ extern "C" st_status st_attn_decode_dual_rope(void* out, float* lse, const void*
     if (!(theta_base > 0.0)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_rope: theta_base must be positive");
     return decode_dual_impl(out, lse, q, caches, lens, batch, n_q_heads, scale, true, theta_base, workspace, workspace_bytes,
                             hip_stream);
+}
+
+extern "C" st_status st_attn_decode_dual_append(void* out, float* lse, const void* q, const void* k_new, const void* v_new,
+                                                const st_dual_cache* caches, const st_dual_lens* lens, int32_t batch,
+                                                int32_t n_q_heads, float scale, double theta_base, void* workspace,
+                                                size_t workspace_bytes, void* hip_stream) {
+    if (theta_base < 0.0 || theta_base != theta_base) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_append: theta_base must be positive, or 0 for rotated inputs");
+    return decode_dual_impl(out, lse, q, caches, lens, batch, n_q_heads, scale, theta_base > 0.0, theta_base, workspace, workspace_bytes,
+                            hip_stream, k_new, v_new, true);
 }
 
 extern "C" size_t st_source_chunk_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,

@@ -9,13 +9,13 @@
 //                    (N_EOS >= N_EOT + 1).  If the prefill is not there yet the loop waits for its event;
 //                    if later sentences are already cached it selects the slice of the source cache that
 //                    ends with sentence t (src_visible_len).  Each token is appended to the reasoning
-//                    cache and attends over both caches (st_kv_append_rope + st_attn_decode_dual_rope).
+//                    cache and attends over both caches (st_attn_decode_dual_append: one launch per layer while the caches are short).
 // The paper's merge / split of the caches around every sentence does not exist here: the two caches are
 // attended in place.  Projections, MLP and sampling need weights and are outside this path, so the
 // activations are given (one set, reused by every layer) and the number of tokens of every reasoning unit
 // is an input, as it is in Alg. 1 (source and target length lists).
 //
-// A decoded token is 4 small launches per layer, and with small batches the step is bound by launch gaps.  With
+// A decoded token is one or two small launches per layer, a chain of dependent kernels for the host to feed.  With
 // job.decode_graph set, one token (all layers) is recorded ONCE into a HIP graph and replayed for every token:
 // the token's activations reach fixed staging buffers through a kernel that reads the step number from a device
 // word (bumped at the end of the graph), so a replay needs no host-side update at all; the grid is sized for the
@@ -95,8 +95,11 @@ struct Layout {
 // copy the activations of step *step from the step-major tensors into the staging buffers (16-byte pieces)
 __global__ void stage_in_kernel(u32x4* __restrict__ qs, u32x4* __restrict__ ks, u32x4* __restrict__ vs, const u32x4* __restrict__ q,
                                 const u32x4* __restrict__ k, const u32x4* __restrict__ v, const int32_t* __restrict__ step,
-                                int q_pieces, int kv_pieces) {
+                                int32_t* __restrict__ rsn_len, int batch, int q_pieces, int kv_pieces) {
     const int64_t g = *step;
+    // token g is the (g + 1)-th of every sequence's reasoning stream
+    if (blockIdx.x == 0)
+        for (int b = threadIdx.x; b < batch; b += blockDim.x) rsn_len[b] = int32_t(g + 1);
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < q_pieces + 2 * kv_pieces; i += gridDim.x * blockDim.x) {
         if (i < q_pieces) qs[i] = q[g * q_pieces + i];
         else if (i < q_pieces + kv_pieces) ks[i - q_pieces] = k[g * kv_pieces + (i - q_pieces)];
@@ -117,6 +120,7 @@ __global__ void copy_i32_kernel(int32_t* __restrict__ dst, const int32_t* __rest
 struct Staging {                      // device memory of the graph-replayed decode step
     int32_t* step = nullptr;          // [1] number of the token the next replay decodes
     int32_t* vis = nullptr;           // [batch] visible source length of the current unit
+    int32_t* len = nullptr;           // [batch] reasoning length including the token being decoded
     uint16_t *q = nullptr, *k = nullptr, *v = nullptr, *out = nullptr;
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
@@ -132,6 +136,7 @@ struct Runner {
     Events& ev;
     Shared& sh;
     const int32_t* vis_dev;           // [n_sentences][batch] visible source length of unit t
+    const int32_t* len_dev;           // [total_steps][batch] reasoning length including token g: g + 1
     int device;
     Clock::time_point t0;
     int hkv, d;
@@ -178,19 +183,17 @@ struct Runner {
         const int blocks = std::min(64, (q_pieces + 2 * kv_pieces + 255) / 256);
         hipLaunchKernelGGL(stage_in_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<u32x4*>(stg->q), reinterpret_cast<u32x4*>(stg->k),
                            reinterpret_cast<u32x4*>(stg->v), static_cast<const u32x4*>(job.rsn_q), static_cast<const u32x4*>(job.rsn_k),
-                           static_cast<const u32x4*>(job.rsn_v), stg->step, q_pieces, kv_pieces);
+                           static_cast<const u32x4*>(job.rsn_v), stg->step, stg->len, job.batch, q_pieces, kv_pieces);
         st_dual_lens lens;
         lens.src_visible_len = stg->vis;
+        lens.rsn_len = stg->len;
         lens.q_len = 1;
         lens.max_src_len = int(lay.total_src);
         lens.max_rsn_len = int(lay.total_steps);
         for (int l = 0; l < job.n_layers; ++l) {
-            st_status r = st_kv_append_rope(&job.caches[l], ST_REASONING, stg->k, stg->v, nullptr, 1, job.batch, int(lay.total_steps),
-                                            job.theta_base, s);
-            if (r != ST_OK) return r;
-            lens.rsn_len = job.caches[l].reasoning.appended_len;
-            r = st_attn_decode_dual_rope(stg->out, nullptr, stg->q, &job.caches[l], &lens, job.batch, job.n_q_heads, job.scale,
-                                         job.theta_base, job.decode_workspace, job.decode_workspace_bytes, s);
+            const st_status r = st_attn_decode_dual_append(stg->out, nullptr, stg->q, stg->k, stg->v, &job.caches[l], &lens, job.batch,
+                                                           job.n_q_heads, job.scale, job.theta_base, job.decode_workspace,
+                                                           job.decode_workspace_bytes, s);
             if (r != ST_OK) return r;
         }
         hipLaunchKernelGGL(stage_out_kernel, dim3(std::min(64, (q_pieces + 255) / 256)), dim3(256), 0, s, static_cast<u32x4*>(job.rsn_out),
@@ -236,17 +239,15 @@ struct Runner {
             const int64_t g = lay.step0[t] + j;
             st_dual_lens lens;
             lens.src_visible_len = vis_dev + int64_t(vis_unit) * job.batch;
+            lens.rsn_len = len_dev + g * job.batch;
             lens.q_len = 1;
             lens.max_src_len = int(lay.total_src);
             lens.max_rsn_len = int(g + 1);
-            for (int l = 0; l < job.n_layers; ++l) {
-                SCHED_CALL(sh, st_kv_append_rope(&job.caches[l], ST_REASONING, at(job.rsn_k, g, hkv), at(job.rsn_v, g, hkv), nullptr, 1,
-                                                 job.batch, int(g + 1), job.theta_base, s));
-                lens.rsn_len = job.caches[l].reasoning.appended_len;
-                SCHED_CALL(sh, st_attn_decode_dual_rope(at(job.rsn_out, g, job.n_q_heads), nullptr, at(job.rsn_q, g, job.n_q_heads),
-                                                        &job.caches[l], &lens, job.batch, job.n_q_heads, job.scale, job.theta_base,
-                                                        job.decode_workspace, job.decode_workspace_bytes, s));
-            }
+            for (int l = 0; l < job.n_layers; ++l)
+                SCHED_CALL(sh, st_attn_decode_dual_append(at(job.rsn_out, g, job.n_q_heads), nullptr, at(job.rsn_q, g, job.n_q_heads),
+                                                          at(job.rsn_k, g, hkv), at(job.rsn_v, g, hkv), &job.caches[l], &lens, job.batch,
+                                                          job.n_q_heads, job.scale, job.theta_base, job.decode_workspace,
+                                                          job.decode_workspace_bytes, s));
             if (j == 0) SCHED_HIP(sh, hipEventRecord(ev.first_token[t], s));
         }
         if (n == 0) SCHED_HIP(sh, hipEventRecord(ev.first_token[t], s));
@@ -448,23 +449,31 @@ extern "C" st_status st_stream_run(const st_stream_job* job_in, int32_t mode, st
     std::vector<int32_t> vis_host(size_t(std::max(job.n_sentences, 1)) * job.batch);
     for (int t = 0; t < job.n_sentences; ++t)
         for (int b = 0; b < job.batch; ++b) vis_host[size_t(t) * job.batch + b] = int32_t(lay.src_row0[t] + job.src_tokens[t]);
-    // one device block: the visibility table, then (graph-replayed decode) the step word, the current unit's slice and
-    // the staging buffers of one token
+    // reasoning length of every sequence while token g is decoded (the token included)
+    std::vector<int32_t> len_host(size_t(std::max<int64_t>(lay.total_steps, 1)) * job.batch);
+    for (int64_t g = 0; g < lay.total_steps; ++g)
+        for (int b = 0; b < job.batch; ++b) len_host[size_t(g) * job.batch + b] = int32_t(g + 1);
+    // one device block: the visibility table, the length table, then (graph-replayed decode) the step word, the current
+    // unit's slice, the current lengths and the staging buffers of one token
     const size_t vis_bytes = (vis_host.size() * sizeof(int32_t) + 255) & ~size_t(255);
+    const size_t len_bytes = (len_host.size() * sizeof(int32_t) + 255) & ~size_t(255);
     const size_t q_bytes = (size_t(job.batch) * job.n_q_heads * c0.head_dim * 2 + 255) & ~size_t(255);
     const size_t kv_bytes = (size_t(job.batch) * c0.n_kv_heads * c0.head_dim * 2 + 255) & ~size_t(255);
     const size_t vis1_bytes = (size_t(job.batch) * sizeof(int32_t) + 255) & ~size_t(255);
     const bool use_graph = job.decode_graph != 0 && lay.total_steps > 0;
     unsigned char* block = nullptr;
-    ST_HIP(hipMalloc(&block, vis_bytes + (use_graph ? 256 + vis1_bytes + 2 * q_bytes + 2 * kv_bytes : 0)));
+    ST_HIP(hipMalloc(&block, vis_bytes + len_bytes + (use_graph ? 256 + 2 * vis1_bytes + 2 * q_bytes + 2 * kv_bytes : 0)));
     struct Free { void* p; ~Free() { (void)hipFree(p); } } free_block{block};
     int32_t* vis_dev = reinterpret_cast<int32_t*>(block);
     ST_HIP(hipMemcpy(vis_dev, vis_host.data(), vis_host.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    int32_t* len_dev = reinterpret_cast<int32_t*>(block + vis_bytes);
+    ST_HIP(hipMemcpy(len_dev, len_host.data(), len_host.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     Staging staging;
     if (use_graph) {
-        unsigned char* p = block + vis_bytes;
+        unsigned char* p = block + vis_bytes + len_bytes;
         staging.step = reinterpret_cast<int32_t*>(p); p += 256;
         staging.vis = reinterpret_cast<int32_t*>(p); p += vis1_bytes;
+        staging.len = reinterpret_cast<int32_t*>(p); p += vis1_bytes;
         staging.q = reinterpret_cast<uint16_t*>(p); p += q_bytes;
         staging.out = reinterpret_cast<uint16_t*>(p); p += q_bytes;
         staging.k = reinterpret_cast<uint16_t*>(p); p += kv_bytes;
@@ -479,7 +488,7 @@ extern "C" st_status st_stream_run(const st_stream_job* job_in, int32_t mode, st
         for (auto& e : *v) ST_HIP(hipEventCreate(&e));
     }
     Shared sh;
-    Runner run{job, lay, ev, sh, vis_dev, device, Clock::now(), c0.n_kv_heads, c0.head_dim, ps, ds, use_graph ? &staging : nullptr};
+    Runner run{job, lay, ev, sh, vis_dev, len_dev, device, Clock::now(), c0.n_kv_heads, c0.head_dim, ps, ds, use_graph ? &staging : nullptr};
     for (int k = 0; k < job.n_sentences; ++k) report->waited[k] = report->sliced[k] = 0;
 
     ST_HIP(hipEventRecord(ev.start, ps));

@@ -652,6 +652,63 @@ def test_decode_rope_fused(st, q_len, hq, hkv, d):
     _check_decode(st, rng, 4, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=q_len, rope_theta=1.0e6)
 
 
+@pytest.mark.parametrize("hq,hkv,d,theta,long", [(4, 2, 128, 1.0e6, False), (8, 2, 64, 1.0e6, False), (32, 8, 128, None, False),
+                                                  (16, 1, 128, 1.0e6, False), (4, 2, 128, 1.0e6, True), (8, 2, 64, None, True)])
+def test_decode_append_in_one_call(st, hq, hkv, d, theta, long):
+    """st_attn_decode_dual_append against the oracle (store the rotated key and the value at index rsn_len - 1, then
+    attend), and against the two separate calls on a twin pair of caches: same pool bits, same lengths, rows that
+    agree within rounding.  Short caches take the single fused launch, long ones the two-launch path; one sequence
+    starts with an empty reasoning cache, one is idle (rsn_len 0: nothing stored, source only)."""
+    src_lens = np.array([98, 0, 500, 64, 1, 31]); rsn_lens = np.array([439, 7, 500, 3, 15, 0]); src_vis = np.array([98, 0, 449, 63, 0, 31])
+    if long:
+        src_lens = np.array([1198, 0, 500, 764, 1, 31]); rsn_lens = np.array([439, 1507, 1100, 3, 15, 0]); src_vis = np.array([1198, 0, 449, 700, 0, 31])
+    batch, idle = len(src_lens), 3
+    twins = []
+    for _ in range(2):
+        rng = np.random.Generator(np.random.PCG64(440 + d))
+        twins.append(_fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra=0, rope_theta=theta))
+    (ca, ref, _), (cb, _, _) = twins
+    assert torch.equal(ca.reasoning.k_pool.view(torch.int16), cb.reasoning.k_pool.view(torch.int16))
+    assert torch.equal(ca.reasoning.page_table, cb.reasoning.page_table)
+    q = W.normal(rng, (batch, 1, hq, d), "bf16"); k_tok = W.normal(rng, (batch, 1, hkv, d), "bf16"); v_tok = W.normal(rng, (batch, 1, hkv, d), "bf16")
+    tq, tk, tv = to_dev(q, "bf16"), to_dev(k_tok, "bf16"), to_dev(v_tok, "bf16")
+    new_len = rsn_lens + 1; new_len[idle] = 0
+    n_new = np.ones(batch, np.int32); n_new[idle] = 0
+    vis_t = torch.from_numpy(src_vis.astype(np.int32)).to(DEV); rl_t = torch.from_numpy(new_len.astype(np.int32)).to(DEV)
+    max_s, max_r = int(src_lens.max()), int(new_len.max())
+    lse_f = torch.empty((batch, 1, hq), dtype=torch.float32, device=DEV)
+    out_f = st.st_attn_decode_dual_append(tq, tk, tv, ca, vis_t, rl_t, max_s, max_r, theta_base=theta or 0.0, lse=lse_f)
+    st.st_kv_append(cb, st.ST_REASONING, tk, tv, torch.from_numpy(n_new).to(DEV), rope_theta=theta)
+    out_u = st.st_attn_decode_dual(tq, cb, vis_t, rl_t, max_s, max_r, rope_theta=theta)
+    torch.cuda.synchronize()
+    want_len = rsn_lens + n_new
+    assert ca.reasoning.appended_len.cpu().tolist() == want_len.tolist() == cb.reasoning.appended_len.cpu().tolist()
+    # only slots below the lengths are defined (the rest keeps its NaN fill in both)
+    for name in ("k_pool", "v_pool"):
+        a, b_ = getattr(ca.reasoning, name), getattr(cb.reasoning, name)
+        assert torch.equal(a.view(torch.int16), b_.view(torch.int16)), name
+    assert np.abs(to_f64(out_f) - to_f64(out_u)).max() <= 1e-2
+    for b in range(batch):
+        L = int(rsn_lens[b])
+        if b == idle:
+            if theta is not None:
+                continue                                  # no reasoning token: the query has no position id
+            o_ref, l_ref = O.decode_dual_concat(q[b].astype(np.float64), ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b],
+                                                ref[st.ST_REASONING][0][b], ref[st.ST_REASONING][1][b], int(src_vis[b]), 0)
+        else:
+            k_row = k_tok[b].astype(np.float64)
+            if theta is not None:
+                k_row = O.rope(k_row, np.array([L]), theta)
+            kr = np.concatenate([ref[st.ST_REASONING][0][b][:L], k_row]); vr = np.concatenate([ref[st.ST_REASONING][1][b][:L], v_tok[b]])
+            args = (q[b].astype(np.float64), ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], kr, vr, int(src_vis[b]), L + 1)
+            o_ref, l_ref = O.decode_dual_rotated(*args, theta) if theta is not None else O.decode_dual_concat(*args)
+        assert np.abs(to_f64(out_f[b]) - o_ref).max() <= 2e-2, b
+        assert np.abs(to_f64(lse_f[b]) - l_ref).max() <= 2e-2, b
+    with pytest.raises(st.StError) as e:                  # one token per step
+        st.st_attn_decode_dual_append(torch.cat([tq, tq], 1), tk, tv, ca, vis_t, rl_t, max_s, max_r)
+    assert e.value.status == 5
+
+
 def test_decode_empty_row(st):
     """Both lengths zero: out = 0, lse = -inf."""
     rng = np.random.Generator(np.random.PCG64(413))
