@@ -94,10 +94,19 @@ def test_cache_argument_checks(lib):
     assert lib.st_attn_decode_dual_rope(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 1.0e6, fp, 1 << 20, None) == 2
     assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 64, 1, 8, 0.0, 0.0, fp, 1 << 20, None) == 1
     assert lib.st_attn_source_chunk_rope(fp, None, fp, C.byref(good), fp, None, 8, 65, 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 4
+    # the whole decoding step in one call: one token, bf16 caches, a rotation base that is positive or 0
+    ap = lib.st_attn_decode_dual_append
+    assert ap(fp, None, fp, fp, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, -1.0, fp, 1 << 20, None) == 1
+    assert ap(fp, None, fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 1
+    assert b"st_attn_decode_dual_append" in lib.st_last_error()
+    assert ap(fp, None, fp, fp, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 0.0, fp, 1 << 20, None) == 2
+    two = B._DualLensStruct(fake, fake, 2, 64, 64)
+    assert ap(fp, None, fp, fp, fp, C.byref(good), C.byref(two), 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 5
     # 8-bit caches: need their scale arrays; append (unfused) and decode up to 16 rows take them, nothing else does
     c8 = lambda **kw: cache(dtype=B.ST_FP8_E4M3, k_scale=fake, v_scale=fake, **kw)
     eight = B._DualCacheStruct(c8(), c8())
     assert lib.st_kv_append(C.byref(eight), B.ST_SOURCE, fp, fp, None, 8, 1, 65, None) == 4          # passes the dtype check
+    assert ap(fp, None, fp, fp, fp, C.byref(eight), C.byref(lens), 1, 8, 0.0, 0.0, fp, 1 << 20, None) == 5
     assert lib.st_kv_append(C.byref(B._DualCacheStruct(cache(dtype=B.ST_FP8_E4M3), c8())), B.ST_SOURCE, fp, fp, None, 8, 1, 64, None) == 1
     assert b"scale" in lib.st_last_error()
     assert lib.st_kv_append_rope(C.byref(eight), B.ST_SOURCE, fp, fp, None, 8, 1, 64, 1.0e6, None) == 5
