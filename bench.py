@@ -103,11 +103,11 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
         with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
             st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk, stream=side)
         # the plan needs only the metadata, the rotations only the activations: the plan's three short, latency-bound
-        # kernels run beside the two memory-bound rotations and join before the attention
+        # kernels and the query rotation run beside the key rotation and join before the attention
         plan_stream.wait_stream(main)
         with torch.cuda.stream(plan_stream):
             p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, stream=plan_stream)
-        st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
+            st.st_rope_apply(q, pos, cfg.theta, out=q_rot, stream=plan_stream)
         st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
         main.wait_stream(plan_stream)
         st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
