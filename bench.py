@@ -42,7 +42,7 @@ def _median(xs):
     return float(np.median(np.asarray(xs, dtype=np.float64)))
 
 
-def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
+def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=False):
     dev = "cuda"
     cfg = W.config2()
     hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -102,15 +102,20 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True):
         side.wait_stream(main)
         with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
             st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk, stream=side)
-        # the plan needs only the metadata, the rotations only the activations: the plan's three short, latency-bound
-        # kernels and the query rotation run beside the key rotation and join before the attention
-        plan_stream.wait_stream(main)
-        with torch.cuda.stream(plan_stream):
-            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, stream=plan_stream)
-            st.st_rope_apply(q, pos, cfg.theta, out=q_rot, stream=plan_stream)
-        st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
-        main.wait_stream(plan_stream)
-        st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
+        if fused_rope:
+            # rotation inside the attention call: keys on their way into the key tiles, queries as they are loaded
+            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+            st.st_attn_prefill_rope(q, k, v, pos, cfg.theta, p, out=out, workspace=pre_ws)
+        else:
+            # the plan needs only the metadata, the rotations only the activations: the plan's three short,
+            # latency-bound kernels and the query rotation run beside the key rotation and join before the attention
+            plan_stream.wait_stream(main)
+            with torch.cuda.stream(plan_stream):
+                p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, stream=plan_stream)
+                st.st_rope_apply(q, pos, cfg.theta, out=q_rot, stream=plan_stream)
+            st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
+            main.wait_stream(plan_stream)
+            st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
         # kernel, both by the token's index in the reasoning stream (its position id)
         st.st_kv_append_rope(caches, st.ST_REASONING, k_tok, v_tok, cfg.theta, host_len_upper_bound=max_r)
@@ -487,6 +492,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays of the steps")
+    ap.add_argument("--fused-rope", action="store_true",
+                    help="prefill step: st_attn_prefill_rope on unrotated q, k instead of st_rope_apply (beside the plan build) + "
+                         "st_attn_prefill; measured slower in this step, where the rotations hide behind the plan build")
     ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
     ap.add_argument("--long-prefill", action="store_true",
                     help="also time the attention kernel on configs[3] (8 x 16,384 tokens) and report it under 'prefill_long'")
@@ -525,7 +533,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": a.numel() * 2, "bytes_written_per_copy": a.numel() * 2, "copies": 5}))
         return
-    pre = bench_prefill_step(st, torch, W, args.steps, args.warmup, not args.no_graph)
+    pre = bench_prefill_step(st, torch, W, args.steps, args.warmup, not args.no_graph, args.fused_rope)
     cfg = pre["cfg"]
     tflops_step = pre["flops"] / pre["sec_per_step"] / 1e12
     tflops_kernel = pre["flops"] / (pre["prefill_kernel_ms"] * 1e-3) / 1e12
@@ -536,7 +544,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": pre["mode"],
         "config": {"workload": "configs[1]: Qwen3-0.6B-shaped layer, batch 4, 16 q / 8 kv heads, head_dim 128, bf16, "
                                "32 source (24-64 tok) + 32 reasoning (32-128 tok) segments per sequence, interleaved; "
-                               "step = plan + RoPE + streaming-mask prefill + paged append (64-token source chunk, 1 reasoning "
+                               "step = plan + RoPE (" + ("inside st_attn_prefill_rope" if args.fused_rope else "st_rope_apply on q and k") +
+                               ") + streaming-mask prefill + paged append (64-token source chunk, 1 reasoning "
                                "token) + dual-cache decode of one token",
                    "n_tokens": pre["n_tokens"], "effective_flops_per_step": pre["flops"]},
         "prefill_pct_of_peak": round(100.0 * tflops_kernel / PEAK_BF16_TFLOPS, 2),

@@ -196,7 +196,8 @@ st_status st_plan_tile_classes(const st_plan* plan, int32_t seq, int32_t block,
  *
  * workspace (bf16 only): at least st_prefill_workspace_bytes(...) bytes, 256-byte
  * aligned; holds K and V^T regrouped into contiguous key tiles for the duration of
- * the call (about the size of k plus v).  Not needed for f32 (may be NULL).
+ * the call (about the size of k plus v), and room for the rotation table of
+ * st_attn_prefill_rope (head_dim * 4 bytes per token).  Not needed for f32 (may be NULL).
  * ---------------------------------------------------------------------- */
 size_t st_prefill_workspace_bytes(const st_plan* plan, int32_t n_kv_heads, int32_t head_dim, st_dtype dt);
 
@@ -204,6 +205,19 @@ st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, c
                           const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads,
                           int32_t head_dim, float scale, st_dtype dt,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* st_attn_prefill with the rotation of Sec. 3.2 fused in: q and k are UNROTATED and are rotated by
+ * positions[token] (device int32 [n_tokens], the stream-local position ids the plan was built
+ * from) with base theta_base, as st_rope_apply would -- k on its way into the key tiles, q as the
+ * attention kernel loads it -- so neither tensor makes the extra trip through memory.  The angle
+ * is reduced in fp64, cos / sin are fp32 (st_rope_apply evaluates them in fp64): a rotated
+ * element may differ from st_rope_apply's in its last bf16 bit.  bf16 only (ST_ERR_UNSUPPORTED
+ * for f32: rotate with st_rope_apply); theta_base <= 0 or positions == NULL give
+ * ST_ERR_INVALID_ARG.  Everything else as for st_attn_prefill, same workspace. */
+st_status st_attn_prefill_rope(void* out, float* lse, const void* q, const void* k, const void* v,
+                               const int32_t* positions, double theta_base, const st_plan* plan,
+                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float scale,
+                               st_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Same, taking the token metadata directly: builds a plan, runs the attention,
  * WAITS for it and frees the plan (and a workspace it allocates itself).  For one-off

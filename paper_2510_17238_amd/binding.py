@@ -107,6 +107,8 @@ def load_library():
     lib.st_plan_tile_classes.argtypes = [vp, i32, i32, vp, C.POINTER(i32), C.POINTER(i32)]
     lib.st_attn_prefill.restype = i32
     lib.st_attn_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, i32, vp, sz, vp]
+    lib.st_attn_prefill_rope.restype = i32
+    lib.st_attn_prefill_rope.argtypes = [vp, vp, vp, vp, vp, vp, f64, vp, i32, i32, i32, f32, i32, vp, sz, vp]
     lib.st_prefill_workspace_bytes.restype = sz
     lib.st_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.st_attn_prefill_ids.restype = i32
@@ -315,8 +317,9 @@ def st_prefill_workspace_bytes(plan, n_kv_heads, head_dim, dtype_code):
     return int(load_library().st_prefill_workspace_bytes(plan.handle, n_kv_heads, head_dim, dtype_code))
 
 
-def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, workspace=None, stream=None):
-    """q[N, Hq, D], k, v[N, Hkv, D] -> out[N, Hq, D]; lse: fp32 [N, Hq] tensor to fill, or None."""
+def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, workspace=None, stream=None, positions=None, rope_theta=None):
+    """q[N, Hq, D], k, v[N, Hkv, D] -> out[N, Hq, D]; lse: fp32 [N, Hq] tensor to fill, or None.
+    rope_theta: None for st_attn_prefill (rotated q, k); a base (with positions) for st_attn_prefill_rope."""
     lib = load_library()
     assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
     assert q.dtype == k.dtype == v.dtype
@@ -334,9 +337,20 @@ def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, workspace=None
             workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
-    _check(lib.st_attn_prefill(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), plan.handle, hq, hkv, d, float(scale),
-                               _dtype_code(q), _ptr(workspace), ws_bytes, _stream(stream)))
+    if rope_theta is None:
+        _check(lib.st_attn_prefill(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), plan.handle, hq, hkv, d, float(scale),
+                                   _dtype_code(q), _ptr(workspace), ws_bytes, _stream(stream)))
+    else:
+        _dev_i32(positions, "positions")
+        assert positions.numel() == n
+        _check(lib.st_attn_prefill_rope(_ptr(out), _ptr(lse), _ptr(q), _ptr(k), _ptr(v), _ptr(positions), float(rope_theta), plan.handle,
+                                        hq, hkv, d, float(scale), _dtype_code(q), _ptr(workspace), ws_bytes, _stream(stream)))
     return out
+
+
+def st_attn_prefill_rope(q, k, v, positions, theta_base, plan, **kw):
+    """st_attn_prefill for UNROTATED q, k (rotated inside by positions[token], base theta_base); bf16 only."""
+    return st_attn_prefill(q, k, v, plan, positions=positions, rope_theta=theta_base, **kw)
 
 
 def st_attn_prefill_bwd(d_out, q, k, v, out, lse, plan, scale=0.0, workspace=None, stream=None):

@@ -14,7 +14,7 @@
 //                         64-row key tile (stream-compact order) into contiguous 16 KB blocks, so
 //                         that the attention kernel streams tiles with plain linear loads and needs
 //                         no per-row token lookup and no transpose in its inner loop.
-//   prefill_mfma_pipe_kernel<D, NH>
+//   prefill_mfma_pipe_kernel<D, NH, ROPE>
 //                         bf16, 4 waves x 32 query rows x NH query heads (1 or 2) of one KV head; K and V^T
 //                         tiles copied asynchronously into swizzled LDS buffers; QK^T and PV on
 //                         v_mfma_f32_32x32x16_bf16, fp32 softmax state.  Both products are computed
@@ -22,6 +22,9 @@
 //                         row max / row sum are in-register reductions plus one exchange with lane^32,
 //                         and the S^T accumulators are already laid out as the B operand of the second
 //                         product.  The loop is software-pipelined by hand (see the kernel).
+//   rope_table_kernel, tile_pack_rope_kernel
+//                         the fused rotation of st_attn_prefill_rope: (cos, sin) of every token once, keys rotated
+//                         on their way into the key tiles; the attention kernel's ROPE form rotates its query rows.
 //   prefill_simple_kernel any dtype, one thread per query row, plain fp32 arithmetic.  It is
 //                         the fp32 path (tolerance 1e-4) and walks the same work items.
 #include <stdlib.h>
@@ -163,17 +166,122 @@ __global__ __launch_bounds__(kTileM) void prefill_simple_kernel(T* __restrict__ 
 // 2^kLazyMax instead of 1, which neither fp32 nor bf16 minds, the final division by l is unchanged, and
 // the rescale of l and of the output accumulator (an out-of-line block) becomes a rare event instead of a
 // per-tile one.
+// Fused rotation (Sec. 3.2), step 1: the (cos, sin) pairs of every packed row -- `tab` [packed tile][64 rows][D/2]
+// float2, row r of a stream's tile t at (tile t) * 64 + r -- evaluated ONCE per token (not once per head): the key
+// pack below and the attention kernel's query load both rotate with them.  The angle position * theta^(-2i/D) is
+// reduced in fp64, cos / sin are fp32 (rope_cos_sin).  One workgroup per packed tile.
+template <int D>
+__global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ tab, const int32_t* __restrict__ positions, PlanView pv,
+                                                         RopeFreq freq) {
+    constexpr int HALF = D / 2;
+    const int tile = blockIdx.x;
+    const int b = find_seq(pv.pack_base, pv.batch, tile);
+    const int lt = tile - pv.pack_base[b];
+    const int t0 = pv.cu[b], S = pv.n_src[b], R = pv.cu[b + 1] - t0 - S;
+    const int ts = (S + kTileN - 1) / kTileN, tr = (R + kTileN - 1) / kTileN;
+    if (lt >= ts + tr) return;                      // spare tile of this sequence: never read
+    const bool src = lt < ts;
+    const int kt = src ? lt : lt - ts;
+    const int base = t0 + (src ? 0 : S) + kt * kTileN;
+    const int valid = min(kTileN, (src ? S : R) - kt * kTileN);
+    for (int w = threadIdx.x; w < valid * HALF; w += 256) {
+        const int row = w / HALF, i = w % HALF;
+        float cs, sn;
+        rope_cos_sin(positions[pv.perm[base + row]], freq.f[i], &cs, &sn);
+        tab[(size_t(tile) * kTileN + row) * HALF + i] = float2{cs, sn};
+    }
+}
+
+// Step 2: tile_pack_kernel for UNROTATED keys -- every key row is rotated with its table row on its way into the row
+// tile.  A thread owns two rows x one pair of 8-dim pieces (dims 8 cp .. + 7 and D/2 + the same).
+template <int D>
+__global__ __launch_bounds__(256) void tile_pack_rope_kernel(uint16_t* __restrict__ kc, uint16_t* __restrict__ vc,
+                                                            const float2* __restrict__ tab, const uint16_t* __restrict__ k,
+                                                            const uint16_t* __restrict__ v, PlanView pv, int n_kv_heads) {
+    constexpr int KCH = D / 8, CP = KCH / 2;
+    constexpr int PER_THREAD = kTileN * CP / 256;
+    constexpr int VQ = D / 4;
+    const int tile = blockIdx.x / n_kv_heads;
+    const int h = blockIdx.x % n_kv_heads;
+    const int b = find_seq(pv.pack_base, pv.batch, tile);
+    const int lt = tile - pv.pack_base[b];
+    const int t0 = pv.cu[b], S = pv.n_src[b], R = pv.cu[b + 1] - t0 - S;
+    const int ts = (S + kTileN - 1) / kTileN, tr = (R + kTileN - 1) / kTileN;
+    if (lt >= ts + tr) return;                      // spare tile of this sequence: never read
+    const bool src = lt < ts;
+    const int kt = src ? lt : lt - ts;
+    const int base = t0 + (src ? 0 : S) + kt * kTileN;
+    const int valid = min(kTileN, (src ? S : R) - kt * kTileN);
+    const int tid = threadIdx.x;
+    const uint32_t row_stride = uint32_t(n_kv_heads) * D;
+    uint16_t* kdst = kc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
+    uint16_t* vdst = vc + (size_t(h) * pv.pack_tiles + tile) * (kTileN * D);
+#pragma unroll
+    for (int u = 0; u < PER_THREAD; ++u) {
+        const int c = tid + 256 * u;
+        const int row = c / CP, cp = c % CP;
+        u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};
+        if (row < valid) {
+            const uint16_t* kr = k + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + cp * 8);
+            const u32x4 lo_in = *reinterpret_cast<const u32x4*>(kr), hi_in = *reinterpret_cast<const u32x4*>(kr + D / 2);
+            const f32x4* trow = reinterpret_cast<const f32x4*>(tab + (size_t(tile) * kTileN + row) * (D / 2) + cp * 8);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const f32x4 t = trow[w];                                  // (cos, sin) of pairs 2 w and 2 w + 1
+                uint32_t out_lo = 0, out_hi = 0;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const float cs = t[2 * half], sn = t[2 * half + 1];
+                    const float x = bf16_bits_to_f32(uint16_t(lo_in[w] >> (16 * half))), y = bf16_bits_to_f32(uint16_t(hi_in[w] >> (16 * half)));
+                    out_lo |= uint32_t(f32_to_bf16_bits(x * cs - y * sn)) << (16 * half);
+                    out_hi |= uint32_t(f32_to_bf16_bits(y * cs + x * sn)) << (16 * half);
+                }
+                lo[w] = out_lo;
+                hi[w] = out_hi;
+            }
+        }
+        const int lr = swap23(row);                                    // row position in the tile
+        *reinterpret_cast<u32x4*>(kdst + lr * D + (cp ^ swizzle_key<2 * D>(lr)) * 8) = lo;
+        *reinterpret_cast<u32x4*>(kdst + lr * D + ((cp + CP) ^ swizzle_key<2 * D>(lr)) * 8) = hi;
+    }
+    // V: as in tile_pack_kernel -- 8 keys x 4 d per thread, transposed in registers to 4 d x 8 keys
+    const int kvb = tid & 7, dq = tid >> 3;
+    if (dq < VQ) {
+        u32x2 vreg[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int row = kvb * 8 + r;
+            vreg[r] = u32x2{0u, 0u};
+            if (row < valid) vreg[r] = *reinterpret_cast<const u32x2*>(v + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + dq * 4));
+        }
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            u32x4 even, odd;
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                const uint32_t a = vreg[2 * pr][w], bb = vreg[2 * pr + 1][w];
+                even[pr] = __builtin_amdgcn_perm(bb, a, 0x05040100u);   // low halves
+                odd[pr] = __builtin_amdgcn_perm(bb, a, 0x07060302u);    // high halves
+            }
+            const int d0 = dq * 4 + 2 * w;
+            *reinterpret_cast<u32x4*>(vdst + d0 * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0)) * 8) = even;
+            *reinterpret_cast<u32x4*>(vdst + (d0 + 1) * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0 + 1)) * 8) = odd;
+        }
+    }
+}
+
 template <int D, int STAGES>
 struct PipeSmem {
     uint16_t k[STAGES][kTileN * D];
     uint16_t vt[STAGES][D * kTileN];
 };
-template <int D, int NH>
+template <int D, int NH, bool ROPE>
 __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_mfma_pipe_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
                                                                    const uint16_t* __restrict__ q,
                                                                    const uint16_t* __restrict__ kc,
                                                                    const uint16_t* __restrict__ vc, PlanView pv,
-                                                                   int n_q_heads, int n_kv_heads, float scale_log2) {
+                                                                   int n_q_heads, int n_kv_heads, float scale_log2,
+                                                                   const float2* __restrict__ rope_tab) {
     constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
     constexpr int TILE = kTileN * D;              // elements of one K or V^T tile
     constexpr int STAGES = NH == 2 ? 3 : 2;       // K / V^T buffers: the one-head form must fit two workgroups per CU
@@ -239,6 +347,27 @@ __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_mfma_pipe_kernel
         for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int j = 0; j < KS; ++j) qf[h][j] = *reinterpret_cast<const bf16x8*>(qp + h * D + 16 * j);
+    }
+    if (ROPE) {
+        // UNROTATED queries: the row's (cos, sin) pairs were left by rope_table_kernel at the row's place among
+        // the packed tiles of its own stream; fragments j and j + KS/2 hold the two halves of eight rotation pairs
+        const float2* trow = rope_tab + (size_t(it.tile_a0) * kTileN + my_row) * (D / 2) + 8 * hg;
+#pragma unroll
+        for (int j = 0; j < KS / 2; ++j) {
+            f32x4 cs4[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) cs4[w] = *reinterpret_cast<const f32x4*>(trow + 16 * j + 2 * w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float cs = cs4[e / 2][2 * (e % 2)], sn = cs4[e / 2][2 * (e % 2) + 1];
+#pragma unroll
+                for (int h = 0; h < NH; ++h) {
+                    const float x = float(qf[h][j][e]), y = float(qf[h][j + KS / 2][e]);
+                    qf[h][j][e] = (__bf16)(x * cs - y * sn);
+                    qf[h][j + KS / 2][e] = (__bf16)(y * cs + x * sn);
+                }
+            }
+        }
     }
 
     f32x16 o_acc[NH][DB];
@@ -556,9 +685,13 @@ extern "C" int32_t st_prefill_variant_set(int32_t variant) {
     return prev;
 }
 
+// packed K and V^T tiles, then the (cos, sin) table of the fused rotation (one float2 per packed row and pair)
+static size_t prefill_tile_bytes(const st_plan* plan, int n_kv_heads, int head_dim) {
+    return 2 * size_t(n_kv_heads) * size_t(plan->pack_tiles) * kTileN * size_t(head_dim) * sizeof(uint16_t);
+}
 static size_t prefill_ws_bytes(const st_plan* plan, int n_kv_heads, int head_dim, st_dtype dt) {
     if (dt != ST_BF16) return 0;                     // the fp32 path reads q / k / v in place
-    return 2 * size_t(n_kv_heads) * size_t(plan->pack_tiles) * kTileN * size_t(head_dim) * sizeof(uint16_t);
+    return prefill_tile_bytes(plan, n_kv_heads, head_dim) + size_t(plan->pack_tiles) * kTileN * size_t(head_dim / 2) * sizeof(float2);
 }
 
 extern "C" size_t st_prefill_workspace_bytes(const st_plan* plan, int32_t n_kv_heads, int32_t head_dim, st_dtype dt) {
@@ -566,10 +699,10 @@ extern "C" size_t st_prefill_workspace_bytes(const st_plan* plan, int32_t n_kv_h
     return prefill_ws_bytes(plan, n_kv_heads, head_dim, dt);
 }
 
-extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, const void* v,
-                                     const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                     float scale, st_dtype dt, void* workspace, size_t workspace_bytes,
-                                     void* hip_stream) {
+// positions == nullptr: rotated q / k (st_attn_prefill); otherwise unrotated, rotated here (st_attn_prefill_rope)
+static st_status prefill_impl(void* out, float* lse, const void* q, const void* k, const void* v, const int32_t* positions,
+                              double theta_base, const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                              float scale, st_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!out || !q || !k || !v || !plan) return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: null pointer");
     if (!aligned16(out) || !aligned16(q) || !aligned16(k) || !aligned16(v))
         return fail(ST_ERR_INVALID_ARG, "st_attn_prefill: tensors must be 16-byte aligned");
@@ -609,8 +742,12 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
         ST_LAUNCH_CHECK("prefill_simple_kernel");
         return ST_OK;
     }
+    const size_t tile_bytes = prefill_tile_bytes(plan, n_kv_heads, head_dim);
     uint16_t* kc = static_cast<uint16_t*>(workspace);
-    uint16_t* vc = kc + need / (2 * sizeof(uint16_t));
+    uint16_t* vc = kc + tile_bytes / (2 * sizeof(uint16_t));
+    float2* tab = reinterpret_cast<float2*>(static_cast<char*>(workspace) + tile_bytes);
+    const bool rope = positions != nullptr;
+    const RopeFreq freq = rope ? make_rope_freq(theta_base, head_dim) : RopeFreq{};
     const float scale_log2 = scale * kLog2e;
     // Two query heads per workgroup when heads come in pairs over a KV head and the batch is large
     // enough to keep every compute unit busy for several rounds of such (one per CU) workgroups;
@@ -619,27 +756,53 @@ extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const
     const bool pair = ((n_q_heads / n_kv_heads) % 2 == 0) && (variant == ST_PREFILL_TWO_HEADS || (variant == ST_PREFILL_AUTO && blocks / 2 >= 2048));
     auto launch = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
-        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
-                           (const uint16_t*)v, pv, n_kv_heads);
-        auto run = [&](auto nh_tag) -> st_status {
+        if (rope) {
+            hipLaunchKernelGGL((rope_table_kernel<HD>), dim3((unsigned)plan->pack_tiles), dim3(256), 0, s, tab, positions, pv, freq);
+            hipLaunchKernelGGL((tile_pack_rope_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const float2*)tab,
+                               (const uint16_t*)k, (const uint16_t*)v, pv, n_kv_heads);
+        } else
+            hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
+                               (const uint16_t*)v, pv, n_kv_heads);
+        auto run = [&](auto nh_tag, auto rope_tag) -> st_status {
             constexpr int NH = decltype(nh_tag)::value;
+            constexpr bool ROPE = decltype(rope_tag)::value;
             const size_t smem = sizeof(PipeSmem<HD, NH == 2 ? 3 : 2>);
-            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_pipe_kernel<HD, NH>),
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_pipe_kernel<HD, NH, ROPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfPrefillAttn, s);
-            hipLaunchKernelGGL((prefill_mfma_pipe_kernel<HD, NH>), dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
-                               lse, (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2);
+            hipLaunchKernelGGL((prefill_mfma_pipe_kernel<HD, NH, ROPE>), dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
+                               lse, (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2, (const float2*)tab);
             prof_end(kProfPrefillAttn, s);
             return ST_OK;
         };
-        const st_status rr = pair ? run(std::integral_constant<int, 2>{}) : run(std::integral_constant<int, 1>{});
-        if (rr != ST_OK) return rr;
-        return ST_OK;
+        using One = std::integral_constant<int, 1>;
+        using Two = std::integral_constant<int, 2>;
+        return rope ? (pair ? run(Two{}, std::true_type{}) : run(One{}, std::true_type{}))
+                    : (pair ? run(Two{}, std::false_type{}) : run(One{}, std::false_type{}));
     };
     const st_status lr = head_dim == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});
     if (lr != ST_OK) return lr;
     ST_LAUNCH_CHECK("tile_pack_kernel / prefill_mfma_pipe_kernel");
     return ST_OK;
+}
+
+extern "C" st_status st_attn_prefill(void* out, float* lse, const void* q, const void* k, const void* v,
+                                     const st_plan* plan, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     float scale, st_dtype dt, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+    return prefill_impl(out, lse, q, k, v, nullptr, 0.0, plan, n_q_heads, n_kv_heads, head_dim, scale, dt, workspace, workspace_bytes,
+                        hip_stream);
+}
+
+extern "C" st_status st_attn_prefill_rope(void* out, float* lse, const void* q, const void* k, const void* v,
+                                          const int32_t* positions, double theta_base, const st_plan* plan, int32_t n_q_heads,
+                                          int32_t n_kv_heads, int32_t head_dim, float scale, st_dtype dt, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream) {
+    if (!positions) return fail(ST_ERR_INVALID_ARG, "st_attn_prefill_rope: positions is null");
+    if (!(theta_base > 0.0)) return fail(ST_ERR_INVALID_ARG, "st_attn_prefill_rope: theta_base must be positive");
+    if (dt != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "st_attn_prefill_rope: bf16 only (dtype %d); rotate fp32 inputs with st_rope_apply", int(dt));
+    return prefill_impl(out, lse, q, k, v, positions, theta_base, plan, n_q_heads, n_kv_heads, head_dim, scale, dt, workspace,
+                        workspace_bytes, hip_stream);
 }
 
 extern "C" st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* k, const void* v,

@@ -221,6 +221,45 @@ def test_prefill_each_bf16_kernel(st, variant):
     assert st.st_prefill_variant_set(prev) == prev
 
 
+@pytest.mark.parametrize("variant", ["ST_PREFILL_ONE_HEAD", "ST_PREFILL_TWO_HEADS"])
+def test_prefill_rope_fused(st, variant):
+    """UNROTATED q, k through st_attn_prefill_rope (keys rotated on their way into the key tiles, queries as the
+    attention kernel loads them) against the oracle's rotate-then-attend on the same bf16 inputs, and against the
+    unfused path (st_rope_apply twice, then st_attn_prefill), with both attention kernels."""
+    prev = st.st_prefill_variant_set(getattr(st, variant))
+    try:
+        lists = [(np.array([5, 130]), np.array([0, 0])), (np.array([0]), np.array([200])), (np.array([], int), np.array([], int)),
+                 (np.array([1]), np.array([1])), (np.array([64, 64]), np.array([128, 1]))]
+        for cfg in (W.random_prefill(321, 3, 8, (0, 90), (0, 120), 4, 2, 64, "bf16"), W.random_prefill(322, 3, 8, (0, 90), (0, 120), 4, 2, 128, "bf16"),
+                    W._assemble("edges", "bf16", 4, 2, 128, lists, "interleaved", 7), W.config2()):
+            q, k, v = cfg.tensors()
+            seg, strm, pos = ids_to_dev(cfg)
+            tq, tk, tv = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+            plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+            lse = torch.empty((cfg.n_tokens, cfg.n_q_heads), dtype=torch.float32, device=DEV)
+            out_f = st.st_attn_prefill_rope(tq, tk, tv, pos, cfg.theta, plan, lse=lse)
+            rq, rk = st.st_rope_apply(tq, pos, cfg.theta, out=torch.empty_like(tq)), st.st_rope_apply(tk, pos, cfg.theta, out=torch.empty_like(tk))
+            out_u = st.st_attn_prefill(rq, rk, tv, plan)
+            torch.cuda.synchronize()
+            ref, ref_lse = O.attention_varlen(O.rope(to_f64(tq), cfg.positions, cfg.theta), O.rope(to_f64(tk), cfg.positions, cfg.theta),
+                                              to_f64(tv), cfg.stream_ids, cfg.segment_ids, cfg.positions, cfg.cu_seqlens)
+            assert np.abs(to_f64(out_f) - ref).max() <= 2e-2, cfg.name
+            assert np.abs(to_f64(lse) - ref_lse).max() <= 2e-2, cfg.name
+            assert (out_f.float() - out_u.float()).abs().max().item() <= 2e-2, cfg.name
+        cfg = W.config1()
+        q, k, v = cfg.tensors()
+        seg, strm, pos = ids_to_dev(cfg)
+        plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+        with pytest.raises(st.StError) as e:                      # fp32 inputs keep the separate, fp64-accurate rotation
+            st.st_attn_prefill_rope(to_dev(q, "f32"), to_dev(k, "f32"), to_dev(v, "f32"), pos, cfg.theta, plan)
+        assert e.value.status == 5
+        with pytest.raises(st.StError) as e:
+            st.st_attn_prefill_rope(to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16"), pos, 0.0, plan)
+        assert e.value.status == 1
+    finally:
+        st.st_prefill_variant_set(prev)
+
+
 def test_prefill_mfma_agrees_with_plain_kernel(st):
     """bf16 inputs through the MFMA kernel vs the same values through the fp32 kernel."""
     cfg = W.random_prefill(311, 2, 10, (10, 80), (10, 100), 4, 2, 128, "bf16")
