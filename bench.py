@@ -272,8 +272,8 @@ def bench_stream_session(st, torch, W, time_scale):
 def bench_probes(st, torch):
     """What this GPU sustains for the decode kernel's access pattern and for the prefill kernel's MFMA instruction."""
     dev = "cuda"
-    pool = torch.empty(1 << 31, dtype=torch.uint8, device=dev)
-    pool.random_(0, 256)
+    pool = torch.empty(1 << 34, dtype=torch.uint8, device=dev)       # 16 GiB: 64 times the memory-side cache
+    pool.view(torch.int64).random_()
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
     fsink = torch.zeros(4, dtype=torch.float32, device=dev)
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)

@@ -85,7 +85,8 @@ st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
  * st_probe_paged_read: n_waves one-wave workgroups each read steps_per_wave x 16 KiB from `pool`
  *   (device memory, pool_bytes a power of two >= 4 KiB, 16-byte aligned) as the decode kernel
  *   reads a paged bf16 cache with head_dim 128: four pseudo-random 4 KiB pages per step, 16 loads
- *   of 16 bytes per lane with its per-lane addressing.  Bytes read per launch =
+ *   of 16 bytes per lane with its per-lane addressing; every call picks other pages than the one
+ *   before, so with a pool much larger than the caches nothing is found cached.  Bytes read per launch =
  *   n_waves * steps_per_wave * 16384.  sink: device uint32 (practically never written).
  * st_probe_mfma_bf16: n_workgroups x 4 waves each issue iterations x 8 v_mfma_f32_32x32x16_bf16
  *   on register operands with random mantissas; flop per launch =

@@ -28,6 +28,13 @@ constexpr int kSmallDecodeTokens = 1024;    // both caches together: below this 
 constexpr int kChunkMin = 128;              // ... of the one-token decode step of a few sequences
 constexpr int kChunkLong = 1024;            // ... of the one-token decode step when there is plenty of work (64 pages: one id per lane)
 
+// 16 bytes of a VALUE pool: read once and never again by this launch, whole 128-byte lines per instruction, so the
+// load carries the non-temporal hint -- measured on the decode step of 28 layers: 3 to 4 % faster.  (The same hint on
+// the KEY loads, whose instructions each take half of every line they touch, costs 7 %; a pure read with the key
+// loads' pattern gains from it, so the cause is not the pattern alone -- left as measured.)
+template <typename T>
+__device__ __forceinline__ u32x4 stream_load(const T* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+
 struct DecodeArgs {
     CacheView src, rsn;
     const int32_t* src_len;
@@ -287,7 +294,7 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
             ky[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8) + 4 * 8);
         }
 #pragma unroll
-        for (int db = 0; db < DB; ++db) vv[db] = *reinterpret_cast<const u32x4*>(vp + db * 16 * kPage);
+        for (int db = 0; db < DB; ++db) vv[db] = stream_load(vp + db * 16 * kPage);
 
         const int first = tok0 + 32 * s + 8 * g4;       // token of this lane's first slot
         f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
@@ -698,7 +705,7 @@ __global__ __launch_bounds__(64, 3) void decode_split16_fp8_kernel(DecodeArgs a)
 #pragma unroll
             for (int jj = 0; jj < KP; ++jj) k8[st][jj] = *reinterpret_cast<const u32x4*>(kp + 4 * jj * (kPage * 16) + 4 * st * 16);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) v8[db] = *reinterpret_cast<const u32x4*>(vp + db * 16 * kPage);
+        for (int db = 0; db < DB; ++db) v8[db] = stream_load(vp + db * 16 * kPage);
         f32x4 ks[4], vs[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

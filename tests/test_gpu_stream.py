@@ -118,7 +118,7 @@ def test_stream_session_with_arrival_times(st):
     rng = np.random.Generator(np.random.PCG64(1310))
     batch, hq, hkv, d, theta = 1, 4, 2, 128, 1.0e6
     s, r = [6, 9, 2], [3, 5, 2]
-    arrival = [0.0, 0.06, 0.12]
+    arrival = [0.0, 0.15, 0.30]
     act, dev = _session(rng, batch, hq, hkv, d, s, r)
     layers = _layers(st, rng, 1, batch, hkv, d, sum(s), sum(r))
     src_out, rsn_out, rep = st.st_stream_run(st.ST_SCHED_STREAMING, layers, hq, s, r, dev["sq"], dev["sk"], dev["sv"], dev["rq"],
