@@ -19,6 +19,10 @@ constexpr float kLn2 = 0.6931471805599453f;
 __device__ __forceinline__ void async_copy16(const void* g, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_off) : "memory", "m0");
 }
+// the same with the non-temporal hint: for bytes that are read once
+__device__ __forceinline__ void async_copy16_nt(const void* g, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(g), "s"(lds_off) : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
