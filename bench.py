@@ -13,7 +13,7 @@ in the "decode" object as GB/s of algorithmic cache bytes.
 
 Further objects of the same line (all by default; --no-extras leaves them out, naming some runs only those):
 "source_chunk" (Alg. 1's prefill loop on the streaming shape), "prefill_long" (16K-token sequences), "decode_fp8"
-(8-bit caches), "prefill_backward" (gradients), "stream_session" (Alg. 1 end to end), "probes" (what the machine
+(8-bit caches), "prefill_backward" (gradients), "stream_session" (Alg. 1 end to end), "stream_step" (the configs[4] streaming step), "probes" (what the machine
 sustains for the two kernels' access pattern / instruction).
 
 Prints ONE JSON line.  All inputs are seeded, synthetic and resident in HBM before timing starts.
@@ -40,6 +40,22 @@ MEASURED_TRAFFIC = {"prefill_mfma_pipe_kernel<128, 1>": 261.9e6 + 65.7e6, "decod
 
 def _median(xs):
     return float(np.median(np.asarray(xs, dtype=np.float64)))
+
+
+def _time_launch_modes(torch, steps, graph, eager_step):
+    """Wall time per step of `steps` graph replays (if a verified graph is given) and of `steps` plain launches of the
+    same step; returns ({launch mode: seconds per step}, the faster mode)."""
+    times = {}
+    for mode, run in (("hip-graph", graph.replay if graph is not None else None), ("eager", eager_step)):
+        if run is None:
+            continue
+        run(); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        times[mode] = (time.perf_counter() - t0) / steps
+    return times, min(times, key=times.get)
 
 
 def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=False):
@@ -94,10 +110,11 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
     max_s, max_r = int(S.max()), int(R.max()) + 1
     dec_ws = torch.empty(st.st_decode_workspace_bytes(batch, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream()
-    plan_stream = torch.cuda.Stream()
-    main = torch.cuda.current_stream()
 
     def step(i_timed):
+        # (the stream the step is issued on: torch's current stream now -- under graph capture that is the capturing
+        # stream, and only streams that wait on IT become part of the graph)
+        main = torch.cuda.current_stream()
         cs.appended_len.copy_(len_s0); cr.appended_len.copy_(len_r0)      # same state every step
         side.wait_stream(main)
         with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
@@ -107,14 +124,9 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
             p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
             st.st_attn_prefill_rope(q, k, v, pos, cfg.theta, p, out=out, workspace=pre_ws)
         else:
-            # the plan needs only the metadata, the rotations only the activations: the plan's three short,
-            # latency-bound kernels and the query rotation run beside the key rotation and join before the attention
-            plan_stream.wait_stream(main)
-            with torch.cuda.stream(plan_stream):
-                p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, stream=plan_stream)
-                st.st_rope_apply(q, pos, cfg.theta, out=q_rot, stream=plan_stream)
+            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+            st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
             st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
-            main.wait_stream(plan_stream)
             st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
         # kernel, both by the token's index in the reasoning stream (its position id)
@@ -137,8 +149,9 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
     kern_ms, n_rec = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
     st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
     assert n_rec == n_prof
-    # the timed steps: the whole step (13 kernels on three streams) recorded once into a HIP graph and replayed;
-    # every replay is first checked against the eager step, and eager launches are timed if capture is unavailable
+    # the timed steps, two ways: the whole step (two streams) recorded once into a HIP graph and replayed -- every
+    # replay first checked against the eager step, side stream included -- and as plain launches; the faster one is
+    # the step time, both are reported (graphs with a second branch replay slowly on this ROCm)
     mode, graph = "eager", None
     if use_graph:
         try:
@@ -152,23 +165,19 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
                 torch.cuda.synchronize()
                 if not (torch.equal(ref_out, out) and torch.equal(ref_tok, out_tok)):
                     raise RuntimeError("graph replay differs from the eager step")
+                if not torch.equal(cs.appended_len, len_s0 + chunk):       # the side stream's append is part of the replay
+                    raise RuntimeError("graph replay did not run the source append")
                 plans.append(step(None))
                 torch.cuda.synchronize()
             mode = "hip-graph"
         except Exception as exc:                           # noqa: BLE001
             print(f"bench.py: HIP graph capture not used ({exc}); timing eager launches", file=sys.stderr)
             graph = None
-    run = graph.replay if graph is not None else (lambda: plans.append(step(None)))
-    run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    times, mode = _time_launch_modes(torch, steps, graph, lambda: plans.append(step(None)))
     for p in plans:
         p.destroy()
-    return {"cfg": cfg, "flops": flops, "sec_per_step": dt / steps, "prefill_kernel_ms": kern_ms, "n_tokens": n, "mode": mode}
+    return {"cfg": cfg, "flops": flops, "sec_per_step": times[mode], "prefill_kernel_ms": kern_ms, "n_tokens": n, "mode": mode,
+            "sec_per_step_by_launch": times}
 
 
 def bench_prefill_long(st, torch, W, reps):
@@ -328,6 +337,110 @@ def bench_prefill_backward(st, torch, W, reps):
     return {"ms": e0.elapsed_time(e1) / reps, "flops": 2.5 * flops_fwd, "dq_ms": dq_ms, "dkv_ms": dkv_ms, "flops_fwd": flops_fwd}
 
 
+def _compact_page_table(rng, need_pages, max_pages):
+    """[batch, max_pages] page ids: sequence b owns need_pages[b] distinct pages (shuffled over the pool); entries
+    past them are never used by a step that stays within those pages and point at page 0.  Returns (table, n_pages)."""
+    total = int(need_pages.sum())
+    ids = rng.permutation(total).astype(np.int32)
+    table = np.zeros((len(need_pages), max_pages), np.int32)
+    off = 0
+    for b, n in enumerate(need_pages):
+        table[b, :n] = ids[off:off + n]; off += int(n)
+    return table, total
+
+
+def bench_stream_step(st, torch, W, steps, warmup, distinct_layers=None, use_graph=True):
+    """configs[4], the end-to-end streaming step: 36 layers, 64 streams; per step every layer appends a 32-token source
+    chunk (second stream) while 8 reasoning tokens are decoded one after the other, each through all layers (store the
+    token, attend over the source cache and the reasoning cache).  Pools hold exactly the pages the drawn lengths need
+    (about 3.6 GB per layer)."""
+    dev = "cuda"
+    shp = W.config5()
+    B, L, hq, hkv, d = shp.batch, shp.n_layers, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
+    n_tok = 8
+    rng = np.random.Generator(np.random.PCG64(shp.seed))
+    src0 = shp.src_visible_len.astype(np.int64); rsn0 = shp.rsn_len.astype(np.int64) - 1      # cached before the step
+    need_s = (src0 + shp.src_append + 15) // 16; need_r = (rsn0 + n_tok + 15) // 16
+    pages_s = int(need_s.max()); pages_r = int(need_r.max())
+    tab_s_np, n_pages_s = _compact_page_table(rng, need_s, pages_s)
+    tab_r_np, n_pages_r = _compact_page_table(rng, need_r, pages_r)
+    tab_s = torch.from_numpy(tab_s_np).to(dev); tab_r = torch.from_numpy(tab_r_np).to(dev)
+    g = torch.Generator(device=dev); g.manual_seed(shp.seed)
+    per_layer = (n_pages_s + n_pages_r) * 16 * hkv * d * 2 * 2
+    free, _ = torch.cuda.mem_get_info()
+    n_phys = L if distinct_layers is None else int(distinct_layers)
+    n_phys = max(1, min(n_phys, L, int(free * 0.85) // per_layer))
+    layers = []
+    len_s_all = torch.zeros((n_phys, B), dtype=torch.int32, device=dev)
+    for li in range(n_phys):
+        cs = st.KVCache(n_pages_s, B, pages_s, hkv, d, tab_s); cr = st.KVCache(n_pages_r, B, pages_r, hkv, d, tab_r)
+        cs.appended_len = len_s_all[li]
+        for c in (cs, cr):
+            c.k_pool.normal_(generator=g); c.v_pool.normal_(generator=g)
+        layers.append(st.DualCache(cs, cr))
+    src_vis = torch.from_numpy(shp.src_visible_len).to(dev)
+    # reasoning length of every sequence while token t of the step is decoded, the token included
+    rsn_len_t = [torch.from_numpy((rsn0 + t + 1).astype(np.int32)).to(dev) for t in range(n_tok)]
+    q = torch.randn((n_tok, B, 1, hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k_tok = torch.randn((n_tok, B, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_tok = torch.randn((n_tok, B, 1, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k_src = torch.randn((B, shp.src_append, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_src = torch.randn((B, shp.src_append, hkv, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    max_s, max_r = int(src0.max()), int(rsn0.max()) + n_tok
+    ws = torch.empty(st.st_decode_workspace_bytes(B, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+
+    def step():
+        main = torch.cuda.current_stream()                              # (under capture: the capturing stream)
+        len_s_all.copy_(src_vis.expand(n_phys, B))                      # the source caches as they were before the step
+        side.wait_stream(main)
+        with torch.cuda.stream(side):                                   # prefill loop: the arriving chunk, every layer
+            for li in range(L):
+                if li < n_phys:                                         # (a cache standing for several layers takes it once)
+                    st.st_kv_append_rope(layers[li], st.ST_SOURCE, k_src, v_src, 1.0e6, host_len_upper_bound=max_s + shp.src_append, stream=side)
+        for t in range(n_tok):                                          # decoding loop: token after token, layer after layer
+            for li in range(L):
+                st.st_attn_decode_dual_append(q[t], k_tok[t], v_tok[t], layers[li % n_phys], src_vis, rsn_len_t[t], max_s, max_r,
+                                              theta_base=1.0e6, out=out[t], workspace=ws)
+        main.wait_stream(side)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    mode, graph = "eager", None
+    ref = out.clone()
+    step(); torch.cuda.synchronize()
+    if not torch.equal(ref.view(torch.int16), out.view(torch.int16)):
+        raise RuntimeError("stream step: two eager runs of the same step differ")
+    if use_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            for _ in range(2):
+                out.zero_()
+                graph.replay(); torch.cuda.synchronize()
+                if not torch.equal(ref.view(torch.int16), out.view(torch.int16)):
+                    dd = (ref.float() - out.float()).abs()
+                    raise RuntimeError(f"graph replay differs from the eager step (max abs difference {float(dd.max())})")
+                if not torch.equal(len_s_all, (src_vis + shp.src_append).expand(n_phys, B)):
+                    raise RuntimeError("graph replay did not run the source appends")
+                step(); torch.cuda.synchronize()
+            mode = "hip-graph"
+        except Exception as exc:                           # noqa: BLE001
+            print(f"bench.py: HIP graph capture not used ({exc}); timing eager launches", file=sys.stderr)
+            graph = None
+    times, mode = _time_launch_modes(torch, steps, graph, step)
+    dt = times[mode]
+    tokens_read = float(sum((src0 + rsn0 + t + 1).sum() for t in range(n_tok)))
+    read_bytes = tokens_read * hkv * d * 2 * 2 * L
+    append_bytes = float(B * (shp.src_append + n_tok) * hkv * d * 2 * 2 * 2 * L)
+    del layers
+    return {"sec_per_step": dt, "read_bytes": read_bytes, "append_bytes": append_bytes, "mode": mode, "distinct_layers": n_phys,
+            "resident_gb": per_layer * n_phys / 1e9, "n_tok": n_tok, "sec_per_step_by_launch": times}
+
+
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8=False):
     dev = "cuda"
     shp = W.config3() if n_layers is None else W.config3(n_layers=n_layers)
@@ -360,9 +473,10 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
     out = torch.empty_like(q)
     max_s, max_r = int(shp.src_visible_len.max()), int(shp.rsn_len.max())
     ws = torch.empty(st.st_decode_workspace_bytes(B, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
-    side = torch.cuda.Stream(); main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
 
     def step(i_timed):
+        main = torch.cuda.current_stream()                              # (under capture: the capturing stream)
         len_s_all.copy_(src_vis.expand(L, B)); len_r_all.copy_(rsn_before.expand(L, B))
         side.wait_stream(main)
         for li, dc in enumerate(layers):
@@ -383,8 +497,8 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
     st.st_profile_enable(False)
     layer_ms, n_rec = st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
     assert n_rec == min(steps, 3) * L
-    # the timed steps: the whole 28-layer step (both streams) recorded once into a HIP graph and replayed,
-    # which removes the per-launch gaps of this launch-bound loop; eager launches if capture is unavailable
+    # the timed steps, two ways: the whole 28-layer step (both streams) as replays of one HIP graph (checked against the
+    # eager step, second stream included) and as plain launches; the faster one is the step time, both are reported
     mode = "hip-graph"
     graph = None
     if use_graph:
@@ -401,27 +515,21 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
                 torch.cuda.synchronize()
                 if not torch.equal(ref, out):
                     raise RuntimeError("graph replay differs from the eager step")
+                if not torch.equal(len_s_all, (src_vis + shp.src_append).expand(L, B)):   # the second stream's appends ran in the replay
+                    raise RuntimeError("graph replay did not run the source appends")
                 step(None)
                 torch.cuda.synchronize()
         except Exception as exc:                           # noqa: BLE001
             print(f"bench.py: HIP graph capture not used ({exc}); timing eager launches", file=sys.stderr)
             graph = None
-    if graph is None:
-        mode = "eager"
-    run = graph.replay if graph is not None else (lambda: step(None))
-    run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    times, mode = _time_launch_modes(torch, steps, graph, lambda: step(None))
+    dt = times[mode] * steps
     tokens = float((shp.src_visible_len.astype(np.int64) + shp.rsn_len).sum())
     # bytes per cached token and KV head: K and V rows of D elements; 8-bit rows carry an fp32 scale each
     per_layer = tokens * hkv * ((2 * d + 8) if fp8 else 2 * d * 2)
     append_bytes = float(B * (shp.src_append + 1)) * hkv * (2 * d * 2 + ((2 * d + 8) if fp8 else 2 * d * 2)) * L
     return {"shape": shp, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
-            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode}
+            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode, "sec_per_step_by_launch": times}
 
 
 def bench_source_chunk(st, torch, W, steps, warmup):
@@ -507,10 +615,15 @@ def main():
                     help="also time st_attn_prefill_bwd on configs[1] and report it under 'prefill_backward'")
     ap.add_argument("--stream-session", action="store_true",
                     help="also run one Alg. 1 session (streaming / alternating / batch schedules) and report it under 'stream_session'")
+    ap.add_argument("--stream-step", action="store_true",
+                    help="also run the configs[4] streaming step (36 layers, 64 streams: a 32-token source chunk appended per layer "
+                         "beside 8 decoded tokens) and report it under 'stream_step'; allocates the caches it needs (about 130 GB)")
+    ap.add_argument("--stream-step-layers", type=int, default=None,
+                    help="distinct per-layer caches of --stream-step (default: all 36 if memory allows; fewer are cycled)")
     ap.add_argument("--stream-time-scale", type=float, default=0.01, help="compression of the arrival times of --stream-session")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the prefill step, the decode workload and the source chunk.  Without this flag, and when none of "
-                         "--long-prefill / --probes / --fp8-cache / --backward / --stream-session is given, ALL of them run")
+                         "--long-prefill / --probes / --fp8-cache / --backward / --stream-session / --stream-step is given, ALL of them run")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -541,7 +654,7 @@ def main():
         "metric": "streaming-mask prefill TFLOP/s + dual-cache decode GB/s, % of MI355X peak",
         "value": round(tflops_step, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(pre["sec_per_step"] * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": pre["mode"],
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": pre["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in pre["sec_per_step_by_launch"].items()},
         "config": {"workload": "configs[1]: Qwen3-0.6B-shaped layer, batch 4, 16 q / 8 kv heads, head_dim 128, bf16, "
                                "32 source (24-64 tok) + 32 reasoning (32-128 tok) segments per sequence, interleaved; "
                                "step = plan + RoPE (" + ("inside st_attn_prefill_rope" if args.fused_rope else "st_rope_apply on q and k") +
@@ -563,7 +676,7 @@ def main():
             "workload": "configs[2]: Qwen3-1.7B-shaped decode, 28 layers, batch 32, 16 q / 8 kv heads, head_dim 128, bf16, "
                         "source cache 2048 + reasoning cache U[1024,6144], 16-token pages (shuffled), one token per step, "
                         "concurrent 64-token source append per layer on a second stream",
-            "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "launch": dec["mode"], "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
+            "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "launch": dec["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in dec["sec_per_step_by_launch"].items()}, "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
             "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
             "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
             "roofline": {"kernel": "decode_split16_kernel<128> (one layer)", "bound": "hbm",
@@ -588,9 +701,9 @@ def main():
         "prefill_s_per_sentence": {"streaming": 0.041, "batch": 0.052}, "decode_s_per_token": {"streaming": 0.037, "batch": 0.039},
         "decoded_tokens": {"streaming": 439, "batch": 436}, "first_token_latency_s": {"streaming": 6.231, "batch": 28.003}}
     # the additional legs: those asked for, or all of them when none is named
-    named = args.long_prefill or args.probes or args.fp8_cache or args.backward or args.stream_session
+    named = args.long_prefill or args.probes or args.fp8_cache or args.backward or args.stream_session or args.stream_step
     if not named and not args.no_extras:
-        args.long_prefill = args.probes = args.fp8_cache = args.backward = args.stream_session = True
+        args.long_prefill = args.probes = args.fp8_cache = args.backward = args.stream_session = args.stream_step = True
     if args.probes:
         line["probes"] = bench_probes(st, torch)
     if args.fp8_cache and not args.no_decode:
@@ -600,7 +713,7 @@ def main():
         line["decode_fp8"] = {
             "workload": "configs[2] with both caches stored in 8 bits (E4M3 codes + one fp32 power-of-two scale per key row and per "
                         "value row: 264 B instead of 512 B per cached token and KV head); same step as 'decode'",
-            "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"],
+            "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in d8["sec_per_step_by_launch"].items()},
             "ms_per_step": round(d8["sec_per_step"] * 1e3, 4), "algorithmic_bytes_per_step": d8["bytes_per_step"],
             "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3),
             "roofline": {"kernel": "decode_split16_fp8_kernel<128> (one layer)", "bound": "hbm", "achieved": round(g8_kernel, 1),
@@ -625,6 +738,19 @@ def main():
                                  "kernels execute 7 (scores and dP are recomputed on the key side); executed_tflops counts those"}}
     if args.stream_session:
         line["stream_session"] = bench_stream_session(st, torch, W, args.stream_time_scale)
+    if args.stream_step:
+        ss = bench_stream_step(st, torch, W, 3, 1, args.stream_step_layers, not args.no_graph)
+        gbps = ss["read_bytes"] / ss["sec_per_step"] / 1e9
+        line["stream_step"] = {
+            "workload": "configs[4]: Qwen3-8B-shaped end-to-end streaming step, 36 layers, 64 streams, 32 q / 8 kv heads, head_dim 128, "
+                        "bf16, source caches U[1024,8192] and reasoning caches U[2048,16384] tokens in 16-token pages (shuffled); per "
+                        "step every layer appends a 32-token source chunk on a second stream while 8 reasoning tokens are decoded one "
+                        "after the other through all layers (st_attn_decode_dual_append: store the token, attend over both caches)",
+            "ms_per_step": round(ss["sec_per_step"] * 1e3, 2), "ms_per_token": round(ss["sec_per_step"] * 1e3 / ss["n_tok"], 2),
+            "value": round(gbps, 1), "unit": "GB/s", "pct_of_peak": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
+            "algorithmic_read_bytes_per_step": ss["read_bytes"], "append_bytes_per_step": ss["append_bytes"], "launch": ss["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ss["sec_per_step_by_launch"].items()},
+            "distinct_layer_caches": ss["distinct_layers"], "resident_cache_gb": round(ss["resident_gb"], 1),
+            "tokens_per_s": round(64 * ss["n_tok"] / ss["sec_per_step"], 1)}
     if args.long_prefill:
         lp = bench_prefill_long(st, torch, W, 5)
         tf = lp["flops"] / (lp["kernel_ms"] * 1e-3) / 1e12
