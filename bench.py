@@ -130,8 +130,8 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
             st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
         # kernel, both by the token's index in the reasoning stream (its position id)
-        st.st_kv_append_rope(caches, st.ST_REASONING, k_tok, v_tok, cfg.theta, host_len_upper_bound=max_r)
-        st.st_attn_decode_dual_rope(q_tok, caches, src_vis, rsn_len, max_s, max_r, cfg.theta, out=out_tok, workspace=dec_ws)
+        st.st_attn_decode_dual_append(q_tok, k_tok, v_tok, caches, src_vis, rsn_len, max_s, max_r, theta_base=cfg.theta, out=out_tok,
+                                      workspace=dec_ws)
         main.wait_stream(side)
         return p
 
@@ -482,8 +482,11 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
         for li, dc in enumerate(layers):
             with torch.cuda.stream(side):
                 st.st_kv_append(dc, st.ST_SOURCE, k_src, v_src, host_len_upper_bound=shp.max_src_len, stream=side)
-            st.st_kv_append(dc, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
-            st.st_attn_decode_dual(q, dc, src_vis, rsn_len, max_s, max_r, out=out, workspace=ws)
+            if fp8:
+                st.st_kv_append(dc, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
+                st.st_attn_decode_dual(q, dc, src_vis, rsn_len, max_s, max_r, out=out, workspace=ws)
+            else:                                          # store the token and attend, one call
+                st.st_attn_decode_dual_append(q, k_tok, v_tok, dc, src_vis, rsn_len, max_s, max_r, out=out, workspace=ws)
         main.wait_stream(side)
 
     for _ in range(warmup):

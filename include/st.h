@@ -409,7 +409,9 @@ st_status st_attn_decode_dual_rope(void* out, float* lse, const void* q,
  *                  rsn_len[b] - 1 (Sec. 3.2); 0: both are already rotated
  * When both caches are short (max_src_len + max_rsn_len <= 1024) the step is ONE kernel launch:
  * the workgroup that attends for a KV head also stores that head's key and value, and takes the
- * new token from registers.  Longer caches take two launches, as the separate calls do.
+ * new token from registers.  Longer caches take two launches (the split kernel stores the token
+ * through one more work unit per sequence and KV head and merges it as one more partial state;
+ * with more than 16 query heads per KV head the token goes in with a launch of its own).
  * lens->q_len other than 1 and 8-bit caches give ST_ERR_UNSUPPORTED.  Everything else (workspace,
  * bounds, errors) as for st_attn_decode_dual. */
 st_status st_attn_decode_dual_append(void* out, float* lse, const void* q, const void* k_new,

@@ -54,6 +54,12 @@ struct DecodeArgs {
     // stream (reasoning for a decode step, source for a source chunk), which is its position id
     int rope;
     RopeFreq freq;
+    // one decoding step in one call (bf16, q_len = 1, <= 16 rows): the token k_new / v_new [batch][Hkv][D] is the one at
+    // index rsn_len[b] - 1 of the reasoning stream and is NOT in the cache yet -- the launch stores it, attends over
+    // the cached tokens before it, and takes the token itself from registers as one more partial state
+    int append;
+    const uint16_t* k_new;
+    const uint16_t* v_new;
 };
 
 // Fused query rotation (Sec. 3.2, stream-local position ids): fragments j and j + KS/2 of a lane hold the
@@ -358,17 +364,19 @@ template <int D>
 __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
     const int lane = threadIdx.x;
-    const int nc = a.ncs + a.ncr;
+    const int nc = a.ncs + a.ncr + a.append;             // (append: one more slot per sequence and head, the new token's)
     const int c = int(blockIdx.x % unsigned(nc));
     const unsigned bh = blockIdx.x / unsigned(nc);
     const int h = int(bh % unsigned(a.n_kv_heads));
     const int b = int(bh / unsigned(a.n_kv_heads));
     const bool is_src = c < a.ncs;
+    const bool is_tok = c == a.ncs + a.ncr;
     const CacheView& cv = is_src ? a.src : a.rsn;
     const int cc = is_src ? c : c - a.ncs;
-    const int len = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
-    const int tok0 = cc * a.chunk;
-    if (tok0 >= len) return;
+    const int len_all = min(max(is_src ? a.src_len[b] : a.rsn_len[b], 0), cv.max_pages * kPage);
+    const int len = (a.append && !is_src && len_all > 0) ? len_all - 1 : len_all;     // cached tokens to walk
+    const int tok0 = is_tok ? 0 : cc * a.chunk;
+    if (is_tok ? len_all == 0 : tok0 >= len) return;
     const int tok_end = min(len, tok0 + a.chunk);
 
     const int n = lane & 15, g4 = lane >> 4;
@@ -393,7 +401,45 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
     for (int db = 0; db < DB; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_ref = 0.f, l_run = 0.f;
     bool has_ref = false;
-    scan_unit16<D>(cv, b, h, lane, tok0, tok_end, len, limit, limit_min, a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+    if (is_tok) {
+        // the new token: key fragments in the query's layout (piece 4 j + g4 of the row), rotated by the token's index
+        const int idx = len_all - 1;
+        bf16x8 kf[KS];
+        const uint16_t* kp = a.k_new + (int64_t(b) * a.n_kv_heads + h) * D + 8 * g4;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) kf[j] = *reinterpret_cast<const bf16x8*>(kp + 32 * j);
+        if (a.rope) rotate_query<KS, 32>(kf, 8 * g4, idx, a.freq);
+        float dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < KS; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(float(qf[j][e]), float(kf[j][e]), dot);
+        dot += __shfl_xor(dot, 16);
+        dot += __shfl_xor(dot, 32);
+        m_ref = dot * a.scale_log2;
+        has_ref = true;
+        l_run = g4 == 0 ? 1.f : 0.f;                                  // (summed over the four lanes of a row below)
+        const uint16_t* vp = a.v_new + (int64_t(b) * a.n_kv_heads + h) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o_acc[db][i] = bf16_bits_to_f32(vp[16 * db + 4 * g4 + i]);
+        // into the cache: this head's key and value at index idx; the workgroup of head 0 writes the new length
+        const int id = a.rsn.page_table[int64_t(b) * a.rsn.max_pages + idx / kPage];
+        const int slot_in_page = idx % kPage;
+        if (id >= 0 && id < a.rsn.n_pages) {                          // never write outside the pool
+            if (n == 0) {
+                uint16_t* kdst = a.rsn.k_pool + (int64_t(id) * a.n_kv_heads + h) * KCH * (kPage * 8) + slot_in_page * 8;
+#pragma unroll
+                for (int j = 0; j < KS; ++j) *reinterpret_cast<bf16x8*>(kdst + (4 * j + g4) * (kPage * 8)) = kf[j];
+            }
+            uint16_t* vdst = a.rsn.v_pool + (int64_t(id) * a.n_kv_heads + h) * (D * kPage) + slot_in_page;
+            for (int d0 = lane; d0 < D; d0 += 64) vdst[d0 * kPage] = vp[d0];
+        }
+        if (h == 0 && lane == 0) a.rsn.appended_len[b] = len_all;
+    } else {
+        scan_unit16<D>(cv, b, h, lane, tok0, tok_end, len, min(limit, len), min(limit_min, len), a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+    }
 
     float l_tot = l_run + __shfl_xor(l_run, 16);
     l_tot += __shfl_xor(l_tot, 32);
@@ -813,12 +859,16 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
     const int t = int((blockIdx.x / unsigned(a.n_q_heads)) % unsigned(a.q_len));
     const int b = int(blockIdx.x / unsigned(a.n_q_heads * a.q_len));
     const int h = hq / a.group, n = t * a.group + hq % a.group;
-    const int nc = a.ncs + a.ncr;
+    const int nc = a.ncs + a.ncr + a.append;
     const int len_s = min(max(a.src_len[b], 0), a.src.max_pages * kPage);
-    const int len_r = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+    const int len_all = min(max(a.rsn_len[b], 0), a.rsn.max_pages * kPage);
+    const int n_tok = (a.append && len_all > 0) ? 1 : 0;            // the new token's own partial (slot ncs + ncr)
+    const int len_r = len_all - n_tok;                               // what the split kernel walked
     const int n_s = min((len_s + a.chunk - 1) / a.chunk, a.ncs), n_r = min((len_r + a.chunk - 1) / a.chunk, a.ncr);
-    const int n_tot = n_s + n_r;
+    const int n_tot = n_s + n_r + n_tok;
     const int64_t base = (int64_t(b) * a.n_kv_heads + h) * nc;
+    // partial i of the row -> slot: source units, reasoning units, then the token
+    auto slot_of = [&](int i) { return i < n_s ? i : i < n_s + n_r ? a.ncs + (i - n_s) : a.ncs + a.ncr; };
 
     float acc[PER];
 #pragma unroll
@@ -830,7 +880,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
         float m_mine = -INFINITY, l_mine = 0.f;
         if (lane < cnt) {
             const int i = i0 + lane;
-            const int c = i < n_s ? i : a.ncs + (i - n_s);
+            const int c = slot_of(i);
             const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + ((base + c) * a.rows + n) * 2);
             m_mine = ml[0];
             l_mine = ml[1];
@@ -839,7 +889,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int i = i0 + min(u, cnt - 1);          // rows past the end repeat the last one, with weight 0
-            const int c = i < n_s ? i : a.ncs + (i - n_s);
+            const int c = slot_of(i);
             const float* po = a.part_o + ((base + c) * a.rows + n) * D + lane * PER;
 #pragma unroll
             for (int e = 0; e < PER; ++e) rows[u][e] = po[e];
@@ -1181,7 +1231,7 @@ static inline int chunks_of(int len) { return (len + kChunk - 1) / kChunk; }
 
 // Partial results of a decode step cut into `unit`-token work units.
 static inline size_t decode_partial_bytes(int unit, int64_t batch, int hkv, int rows, int d, int max_src, int max_rsn) {
-    const size_t nc = size_t((max_src + unit - 1) / unit) + size_t((max_rsn + unit - 1) / unit);
+    const size_t nc = size_t((max_src + unit - 1) / unit) + size_t((max_rsn + unit - 1) / unit) + 1;   // + the appended token's slot
     const size_t slots = size_t(batch) * hkv * nc * rows;
     return align256(slots * d * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
 }
@@ -1288,7 +1338,13 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.row_blocks = 1;
     a.rope = rotate ? 1 : 0;
     a.freq = rotate ? make_rope_freq(theta_base, d) : RopeFreq{};
-    const size_t slots = size_t(batch) * hkv * size_t(a.ncs + a.ncr) * a.rows;
+    // long caches: the one-wave split kernel stores the token itself (one more slot per sequence and head); the
+    // 32-row kernel does not, the token then goes in with a launch of its own
+    const bool fuse_token = append && !fp8 && a.rows <= 16;
+    a.append = fuse_token ? 1 : 0;
+    a.k_new = static_cast<const uint16_t*>(k_new);
+    a.v_new = static_cast<const uint16_t*>(v_new);
+    const size_t slots = size_t(batch) * hkv * size_t(a.ncs + a.ncr + a.append) * a.rows;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
 
@@ -1310,12 +1366,12 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
         ST_LAUNCH_CHECK("decode_small16_kernel");
         return ST_OK;
     }
-    if (append) {
-        // longer caches: the token goes in with a launch of its own, then the step below reads it like any other
+    if (append && !fuse_token) {
+        // the token goes in with a launch of its own, then the step below reads it like any other
         const st_status ar = append_token_at(cr, k_new, v_new, lens->rsn_len, batch, rotate, theta_base, s);
         if (ar != ST_OK) return ar;
     }
-    const int64_t units = int64_t(batch) * hkv * (a.ncs + a.ncr);
+    const int64_t units = int64_t(batch) * hkv * (a.ncs + a.ncr + a.append);
     const int64_t out_units = int64_t(batch) * a.q_len * n_q_heads;
     if (units / 4 + 1 > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
     if (units > 0) {
@@ -1424,6 +1480,8 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
     }
     a.ncs = (max_src_len + a.chunk - 1) / a.chunk;
     a.ncr = 0;
+    a.append = 0;
+    a.k_new = a.v_new = nullptr;
     a.scale_log2 = scale * kLog2e;
     a.n_new = n_new;
     a.max_new = max_new;

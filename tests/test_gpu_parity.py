@@ -692,12 +692,14 @@ def test_decode_rope_fused(st, q_len, hq, hkv, d):
 
 
 @pytest.mark.parametrize("hq,hkv,d,theta,long", [(4, 2, 128, 1.0e6, False), (8, 2, 64, 1.0e6, False), (32, 8, 128, None, False),
-                                                  (16, 1, 128, 1.0e6, False), (4, 2, 128, 1.0e6, True), (8, 2, 64, None, True)])
+                                                  (16, 1, 128, 1.0e6, False), (4, 2, 128, 1.0e6, True), (8, 2, 64, None, True),
+                                                  (32, 1, 64, 1.0e6, True), (32, 8, 128, 1.0e6, True)])
 def test_decode_append_in_one_call(st, hq, hkv, d, theta, long):
     """st_attn_decode_dual_append against the oracle (store the rotated key and the value at index rsn_len - 1, then
     attend), and against the two separate calls on a twin pair of caches: same pool bits, same lengths, rows that
-    agree within rounding.  Short caches take the single fused launch, long ones the two-launch path; one sequence
-    starts with an empty reasoning cache, one is idle (rsn_len 0: nothing stored, source only)."""
+    agree within rounding.  Short caches take the single fused launch; long ones the split kernel with one more slot
+    for the token (up to 16 rows) or a token launch of its own (32 rows); one sequence starts with an empty reasoning
+    cache, one is idle (rsn_len 0: nothing stored, source only)."""
     src_lens = np.array([98, 0, 500, 64, 1, 31]); rsn_lens = np.array([439, 7, 500, 3, 15, 0]); src_vis = np.array([98, 0, 449, 63, 0, 31])
     if long:
         src_lens = np.array([1198, 0, 500, 764, 1, 31]); rsn_lens = np.array([439, 1507, 1100, 3, 15, 0]); src_vis = np.array([1198, 0, 449, 700, 0, 31])
