@@ -251,7 +251,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 // than kLazyRise above it (or the first finite score): the common step then needs no exchange between lanes and no
 // rescale of the accumulator -- probabilities are bounded by 2^kLazyRise instead of 1, which fp32 and bf16 do not
 // mind, and whoever finishes the row divides by l anyway.
-template <int D>
+template <int D, bool PREFETCH = false>
 __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, int lane, int tok0, int tok_end, int len, int limit,
                                             int limit_min, float scale_log2, const bf16x8 (&qf)[D / 32], f32x4 (&o_acc)[D / 16],
                                             float& m_ref, float& l_run, bool& has_ref) {
@@ -287,13 +287,13 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
         return fmaxf(a2, b2);
     };
 
-    for (int s = 0; s < n_steps; ++s) {
+    // one step = 32 tokens (two pages): 8 key loads and 8 value loads of 16 bytes per lane
+    auto load = [&](int s, u32x4 (&kx)[KS], u32x4 (&ky)[KS], u32x4 (&vv)[DB]) {
         // page ids of this step (uniform); pages past the visible length fall back to the last visible one
         const int id0 = __builtin_amdgcn_readlane(my_page, min(2 * s, last_page));
         const int id1 = __builtin_amdgcn_readlane(my_page, min(2 * s + 1, last_page));
         const uint16_t* kp = k_lane + int64_t(k_second_page ? id1 : id0) * page_k;
         const uint16_t* vp = v_lane + int64_t(v_second_page ? id1 : id0) * page_v;
-        u32x4 kx[KS], ky[KS], vv[DB];
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
             kx[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8));
@@ -301,7 +301,8 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) vv[db] = stream_load(vp + db * 16 * kPage);
-
+    };
+    auto compute = [&](int s, const u32x4 (&kx)[KS], const u32x4 (&ky)[KS], u32x4 (&vv)[DB]) {
         const int first = tok0 + 32 * s + 8 * g4;       // token of this lane's first slot
         f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -356,12 +357,36 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
 #pragma unroll
         for (int db = 0; db < DB; ++db)
             o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv[db]), pb, o_acc[db], 0, 0, 0);
+    };
+    if (PREFETCH) {
+        // The loads of step s + 1 are issued before step s is computed (two register sets, used in turn): a wave
+        // has up to two steps' worth of bytes in flight, and a load's latency is covered by the step before it.
+        u32x4 kxa[KS], kya[KS], vva[DB], kxb[KS], kyb[KS], vvb[DB];
+        if (n_steps > 0) load(0, kxa, kya, vva);
+        for (int s = 0; s < n_steps; s += 2) {
+            if (s + 1 < n_steps) load(s + 1, kxb, kyb, vvb);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(s, kxa, kya, vva);
+            if (s + 1 < n_steps) {
+                if (s + 2 < n_steps) load(s + 2, kxa, kya, vva);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(s + 1, kxb, kyb, vvb);
+            }
+        }
+    } else {
+        for (int s = 0; s < n_steps; ++s) {
+            u32x4 kx[KS], ky[KS], vv[DB];
+            load(s, kx, ky, vv);
+            compute(s, kx, ky, vv);
+        }
     }
-
 }
 
+#ifndef ST_DECODE_PREFETCH
+#define ST_DECODE_PREFETCH 1
+#endif
 template <int D>
-__global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64, ST_DECODE_PREFETCH ? 2 : 4) void decode_split16_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
     const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr + a.append;             // (append: one more slot per sequence and head, the new token's)
@@ -438,7 +463,8 @@ __global__ __launch_bounds__(64, 4) void decode_split16_kernel(DecodeArgs a) {
         }
         if (h == 0 && lane == 0) a.rsn.appended_len[b] = len_all;
     } else {
-        scan_unit16<D>(cv, b, h, lane, tok0, tok_end, len, min(limit, len), min(limit_min, len), a.scale_log2, qf, o_acc, m_ref, l_run, has_ref);
+        scan_unit16<D, ST_DECODE_PREFETCH != 0>(cv, b, h, lane, tok0, tok_end, len, min(limit, len), min(limit_min, len), a.scale_log2, qf, o_acc, m_ref, l_run,
+                                                has_ref);
     }
 
     float l_tot = l_run + __shfl_xor(l_run, 16);
@@ -1237,15 +1263,18 @@ static inline size_t decode_partial_bytes(int unit, int64_t batch, int hkv, int 
 }
 static std::atomic<int> g_decode_unit{0};     // 0: by the rule below; else the pinned unit (st_decode_unit_set)
 // Tokens per work unit of the one-wave decode kernels (<= 16 query rows): a wave walks its unit serially, one
-// memory round trip per 32 tokens, so the unit is as long as still leaves about a thousand units (four per
-// compute unit) -- 1024 tokens for a large batch (fewest partial results), down to 128 for a few sequences,
-// where the step is bound by that serial walk and not by bandwidth.
+// memory round trip per 32 tokens, so the unit is as long as still leaves enough units -- 1024 tokens when that
+// gives four thousand (fewest partial results; measured best on 64 streams of 36 layers), else 512 if that gives a
+// thousand (measured best on configs[2]: 32 streams), down to 128 for a few sequences, where the step is bound by
+// that serial walk and not by bandwidth.
 static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_src, int max_rsn) {
     if (rows > 16) return kChunk;
     const int pinned = g_decode_unit.load(std::memory_order_relaxed);
     if (pinned) return pinned;
-    int unit = kChunkLong;
-    while (unit > kChunkMin && batch * hkv * ((max_src + unit - 1) / unit + (max_rsn + unit - 1) / unit) < 1024) unit /= 2;
+    auto units = [&](int unit) { return batch * hkv * ((max_src + unit - 1) / unit + (max_rsn + unit - 1) / unit); };
+    if (units(kChunkLong) >= 4096) return kChunkLong;       // (counted with the length BOUNDS: about half are real)
+    int unit = kChunk;
+    while (unit > kChunkMin && units(unit) < 1024) unit /= 2;
     return unit;
 }
 
