@@ -19,6 +19,8 @@ sustains for the two kernels' access pattern / instruction).
 Prints ONE JSON line.  All inputs are seeded, synthetic and resident in HBM before timing starts.
 """
 import argparse
+import contextlib
+import gc
 import json
 import os
 import sys
@@ -40,6 +42,20 @@ MEASURED_TRAFFIC = {"prefill_mfma_pipe_kernel<128, 1>": 261.7e6 + 65.7e6, "decod
 
 def _median(xs):
     return float(np.median(np.asarray(xs, dtype=np.float64)))
+
+
+@contextlib.contextmanager
+def _no_gc():
+    """Around a graph capture: Python must not collect, inside it, an object whose destructor frees device memory
+    (a plan that owns its workspace does) -- that would invalidate the capture."""
+    gc.collect()
+    was = gc.isenabled()
+    gc.disable()
+    try:
+        yield
+    finally:
+        if was:
+            gc.enable()
 
 
 def _time_launch_modes(torch, steps, graph, eager_step):
@@ -125,8 +141,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
             st.st_attn_prefill_rope(q, k, v, pos, cfg.theta, p, out=out, workspace=pre_ws)
         else:
             p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
-            st.st_rope_apply(q, pos, cfg.theta, out=q_rot)
-            st.st_rope_apply(k, pos, cfg.theta, out=k_rot)
+            st.st_rope_apply_qk(q, k, pos, cfg.theta, q_out=q_rot, k_out=k_rot)      # queries and keys in one launch
             st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
         # kernel, both by the token's index in the reasoning stream (its position id)
@@ -157,7 +172,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
         try:
             ref_out, ref_tok = out.clone(), out_tok.clone()
             graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
+            with _no_gc(), torch.cuda.graph(graph):
                 plans.append(step(None))
             for _ in range(3):
                 out.zero_(); out_tok.zero_()
@@ -416,7 +431,7 @@ def bench_stream_step(st, torch, W, steps, warmup, distinct_layers=None, use_gra
     if use_graph:
         try:
             graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
+            with _no_gc(), torch.cuda.graph(graph):
                 step()
             for _ in range(2):
                 out.zero_()
@@ -507,7 +522,7 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
     if use_graph:
         try:
             graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
+            with _no_gc(), torch.cuda.graph(graph):
                 step(None)
             step(None)                                     # eager result of the same step
             torch.cuda.synchronize()

@@ -111,6 +111,13 @@ st_status st_rope_apply(void* out, const void* x, const int32_t* positions,
                         int64_t n_tokens, int32_t n_heads, int32_t head_dim,
                         double theta_base, st_dtype dt, void* hip_stream);
 
+/* The queries and the keys of the same tokens in ONE launch: q [n_tokens, n_q_heads, head_dim] and
+ * k [n_tokens, n_kv_heads, head_dim] are rotated with the same cos / sin values, evaluated once --
+ * the same bits as two st_rope_apply calls.  q_out / k_out may equal q / k. */
+st_status st_rope_apply_qk(void* q_out, const void* q, int32_t n_q_heads, void* k_out, const void* k,
+                           int32_t n_kv_heads, const int32_t* positions, int64_t n_tokens,
+                           int32_t head_dim, double theta_base, st_dtype dt, void* hip_stream);
+
 /* ------------------------------------------------------------------------
  * st_plan -- segment tables of one packed batch, replacing the dense additive
  * mask of Eq. 2.  The mask depends only on the training / prefill instance
@@ -155,7 +162,9 @@ st_status st_plan_create(st_plan** plan,
                          int32_t validate, void* hip_stream);
 
 /* Frees the plan (and its own workspace, if it allocated one).  The caller must
- * make sure no kernel that uses the plan is still running.  NULL is ignored. */
+ * make sure no kernel that uses the plan is still running.  NULL is ignored.
+ * A plan that owns its workspace frees device memory here: not while a stream of
+ * the process is being captured into a graph (that would invalidate the capture). */
 void st_plan_destroy(st_plan* plan);
 
 /* Query tile size (rows of a query tile, columns of a key tile). */

@@ -90,6 +90,8 @@ def load_library():
     lib.st_profile_read.argtypes = [i32, C.POINTER(f64), C.POINTER(i32)]
     lib.st_rope_apply.restype = i32
     lib.st_rope_apply.argtypes = [vp, vp, vp, i64, i32, i32, f64, i32, vp]
+    lib.st_rope_apply_qk.restype = i32
+    lib.st_rope_apply_qk.argtypes = [vp, vp, i32, vp, vp, i32, vp, i64, i32, f64, i32, vp]
     lib.st_plan_workspace_bytes.restype = sz
     lib.st_plan_workspace_bytes.argtypes = [i32, i64]
     lib.st_plan_create.restype = i32
@@ -230,6 +232,22 @@ def st_rope_apply(x, positions, theta_base=1.0e6, out=None, stream=None):
     n, h, d = x.shape
     _check(lib.st_rope_apply(_ptr(out), _ptr(x), _ptr(positions), n, h, d, float(theta_base), _dtype_code(x), _stream(stream)))
     return out
+
+
+def st_rope_apply_qk(q, k, positions, theta_base=1.0e6, q_out=None, k_out=None, stream=None):
+    """q[n_tokens, Hq, D] and k[n_tokens, Hkv, D] rotated by positions[n_tokens] in one launch; outs default to in place."""
+    lib = load_library()
+    assert q.is_cuda and q.is_contiguous() and q.dim() == 3 and k.is_contiguous() and k.dim() == 3 and k.dtype == q.dtype
+    _dev_i32(positions, "positions")
+    q_out = q if q_out is None else q_out
+    k_out = k if k_out is None else k_out
+    assert q_out.shape == q.shape and q_out.dtype == q.dtype and q_out.is_contiguous()
+    assert k_out.shape == k.shape and k_out.dtype == k.dtype and k_out.is_contiguous()
+    n, hq, d = q.shape
+    assert k.shape[0] == n and k.shape[2] == d
+    _check(lib.st_rope_apply_qk(_ptr(q_out), _ptr(q), hq, _ptr(k_out), _ptr(k), k.shape[1], _ptr(positions), n, d, float(theta_base),
+                                _dtype_code(q), _stream(stream)))
+    return q_out, k_out
 
 
 # ------------------------------------------------------------------ plan --

@@ -53,6 +53,9 @@ def test_host_side_argument_checks(lib):
     cu = np.array([1, 5], np.int32)
     assert lib.st_plan_create(C.byref(handle), fake, fake, fake, cu.ctypes.data, 1, None, 0, 0, None) == 3
     assert lib.st_plan_workspace_bytes(4, 16000) > 3 * 4 * 16000
+    assert lib.st_rope_apply_qk(fake, fake, 4, None, fake, 2, fake, 10, 64, 1.0e6, B.ST_BF16, None) == 1
+    assert b"st_rope_apply_qk" in lib.st_last_error()
+    assert lib.st_rope_apply_qk(fake, fake, 4, fake, fake, 2, fake, 10, 96, 1.0e6, B.ST_BF16, None) == 5
     assert lib.st_attn_prefill(fake, None, fake, fake, fake, None, 4, 2, 64, 0.0, B.ST_BF16, None, 0, None) == 1
     # the fused-rotation form: positions and a positive base are required, bf16 only
     assert lib.st_attn_prefill_rope(fake, None, fake, fake, fake, None, 1.0e6, None, 4, 2, 64, 0.0, B.ST_BF16, None, 0, None) == 1

@@ -1,6 +1,8 @@
 """GPU parity: every call goes through the C-ABI library and is compared with the fp64
 oracle on the same seeded inputs.  Tolerances (max-abs): 1e-4 for fp32 inputs, 2e-2 for
 bf16 inputs with fp32 accumulation; integer metadata bit-exact."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -148,6 +150,21 @@ def _run_prefill(st, cfg, rope=True, check_lse=True):
     if check_lse:
         assert np.abs(to_f64(lse) - ref_lse).max() <= TOL[cfg.dtype]
     return tq, tk, tv, out, plan
+
+
+def test_rope_queries_and_keys_in_one_launch(st):
+    """st_rope_apply_qk gives the bits of two st_rope_apply calls (fp32 and bf16, both head dims, in place and not)."""
+    rng = np.random.Generator(np.random.PCG64(140))
+    for dt, d, hq, hkv, n in (("f32", 64, 2, 1, 131), ("bf16", 128, 16, 8, 1000), ("bf16", 64, 4, 4, 7), ("f32", 128, 3, 2, 257)):
+        q = to_dev(W.normal(rng, (n, hq, d), dt), dt); k = to_dev(W.normal(rng, (n, hkv, d), dt), dt)
+        pos = torch.from_numpy(rng.integers(0, 40000, n).astype(np.int32)).to(DEV)
+        rq = st.st_rope_apply(q, pos, 1.0e6, out=torch.empty_like(q)); rk = st.st_rope_apply(k, pos, 1.0e6, out=torch.empty_like(k))
+        oq, ok = st.st_rope_apply_qk(q, k, pos, 1.0e6, q_out=torch.empty_like(q), k_out=torch.empty_like(k))
+        assert torch.equal(rq, oq) and torch.equal(rk, ok)
+        q2, k2 = q.clone(), k.clone()
+        st.st_rope_apply_qk(q2, k2, pos, 1.0e6)
+        torch.cuda.synchronize()
+        assert torch.equal(rq, q2) and torch.equal(rk, k2)
 
 
 def test_prefill_config1_fp32(st):
@@ -879,9 +896,15 @@ def test_whole_step_replays_from_a_hip_graph(st):
 
     step(); torch.cuda.synchronize()
     want = [t.clone() for t in (out, lse, o_dec, o_src)]
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        step()
+    # (plans of earlier tests that own device memory free it when Python collects them: not during the capture)
+    gc.collect()
+    gc.disable()
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+    finally:
+        gc.enable()
     torch.cuda.synchronize()
     for _ in range(3):
         for t in (out, lse, o_dec, o_src):
