@@ -112,6 +112,26 @@ def test_stream_session_equals_dense_streaming_mask(st, d, hq, hkv, n_layers, gr
     assert torch.equal(results[st.ST_SCHED_STREAMING][1], results[st.ST_SCHED_SERIAL][1])
 
 
+@pytest.mark.parametrize("graph", [True, False])
+def test_stream_session_growing_past_the_short_cache_path(st, graph):
+    """A session whose caches grow from a few hundred to 1,400 tokens: with plain launches the decoding step changes
+    over, mid-session, from the single-launch kernel for short caches to the split kernel that stores the token through
+    an extra work unit; the recorded graph takes the split kernel from the first token.  Every row against the dense
+    Eq. 2 mask."""
+    rng = np.random.Generator(np.random.PCG64(1340))
+    batch, hq, hkv, d, theta = 1, 4, 2, 64, 1.0e6
+    s, r = [600, 300], [300, 200]
+    act, dev = _session(rng, batch, hq, hkv, d, s, r)
+    layers = _layers(st, rng, 1, batch, hkv, d, sum(s), sum(r))
+    src_out, rsn_out, rep = st.st_stream_run(st.ST_SCHED_SERIAL, layers, hq, s, r, dev["sq"], dev["sk"], dev["sv"], dev["rq"], dev["rk"],
+                                             dev["rv"], theta, decode_graph=graph)
+    _check_report(rep, s, r)
+    assert layers[0].reasoning.appended_len.cpu().tolist() == [sum(r)] and layers[0].source.appended_len.cpu().tolist() == [sum(s)]
+    o_src, o_rsn = _oracle_rows(act, 0, s, r, theta)
+    assert np.abs(to_f64(_unpack_src(src_out, batch, s, hq, d)[0]) - o_src).max() <= 2e-2
+    assert np.abs(to_f64(rsn_out[:, 0]) - o_rsn).max() <= 2e-2
+
+
 def test_stream_session_with_arrival_times(st):
     """Sentences arriving slower than they are reasoned about: every unit waits for its prefill (Alg. 1, second
     branch), nothing happens before its sentence has arrived, results unchanged."""
