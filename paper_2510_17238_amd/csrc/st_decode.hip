@@ -1267,12 +1267,14 @@ static std::atomic<int> g_decode_unit{0};     // 0: by the rule below; else the 
 // gives four thousand (fewest partial results; measured best on 64 streams of 36 layers), else 512 if that gives a
 // thousand (measured best on configs[2]: 32 streams), down to 128 for a few sequences, where the step is bound by
 // that serial walk and not by bandwidth.
-static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_src, int max_rsn) {
+static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_src, int max_rsn, bool fp8 = false) {
     if (rows > 16) return kChunk;
     const int pinned = g_decode_unit.load(std::memory_order_relaxed);
     if (pinned) return pinned;
     auto units = [&](int unit) { return batch * hkv * ((max_src + unit - 1) / unit + (max_rsn + unit - 1) / unit); };
-    if (units(kChunkLong) >= 4096) return kChunkLong;       // (counted with the length BOUNDS: about half are real)
+    // (counted with the length BOUNDS: about half are real; the 8-bit kernel, which walks 64 tokens per step and
+    // keeps four waves per SIMD, is best with the long unit from a thousand on)
+    if (units(kChunkLong) >= (fp8 ? 1024 : 4096)) return kChunkLong;
     int unit = kChunk;
     while (unit > kChunkMin && units(unit) < 1024) unit /= 2;
     return unit;
@@ -1356,7 +1358,7 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.group = group;
     a.rows = lens->q_len * group;
     // Work unit: see decode_unit_tokens; a workspace sized for other length bounds may only hold longer units.
-    a.chunk = decode_unit_tokens(batch, hkv, a.rows, lens->max_src_len, lens->max_rsn_len);
+    a.chunk = decode_unit_tokens(batch, hkv, a.rows, lens->max_src_len, lens->max_rsn_len, fp8);
     while (a.chunk < kChunk && decode_partial_bytes(a.chunk, batch, hkv, a.rows, d, lens->max_src_len, lens->max_rsn_len) > workspace_bytes)
         a.chunk *= 2;
     a.ncs = (lens->max_src_len + a.chunk - 1) / a.chunk;
