@@ -95,6 +95,20 @@ def test_cache_argument_checks(lib):
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, fp, 1 << 20, None) == 2
     need = lib.st_decode_workspace_bytes(1, 8, 2, 128, 1, 64, 64)
     assert need >= 2 * 4 * (128 + 2) * 4
+    # the work unit of the decode step: pinned sizes change the workspace (more, shorter units need more slots), other
+    # values are ignored, and the size by launch shrinks the unit for small launches
+    prev = lib.st_decode_unit_set(128)
+    try:
+        w128 = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144)
+        assert lib.st_decode_unit_set(1024) == 128
+        w1024 = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144)
+        assert lib.st_decode_unit_set(100) == 1024 and lib.st_decode_unit_set(0) == 1024
+        auto_big = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144)
+        auto_small = lib.st_decode_workspace_bytes(1, 16, 8, 128, 1, 2048, 6144)
+        # 512-token units are always provided for; 128-token units need about four times the slots
+        assert w128 > 3 * w1024 and auto_big == w1024 and auto_small * 32 > 3 * auto_big
+    finally:
+        lib.st_decode_unit_set(prev)
     # the fused forms take the same checks, plus the rotation base
     assert lib.st_kv_append_rope(C.byref(good), B.ST_SOURCE, fp, fp, None, 8, 1, 65, 1.0e6, None) == 4
     assert lib.st_kv_append_rope(C.byref(good), B.ST_SOURCE, fp, fp, None, 8, 1, 64, 0.0, None) == 1
