@@ -58,6 +58,17 @@ def _no_gc():
             gc.enable()
 
 
+@contextlib.contextmanager
+def _leg(line, name, torch):
+    """An additional leg must not cost the line its main figures: a failure is reported in the leg's place."""
+    try:
+        yield
+    except Exception as exc:                               # noqa: BLE001
+        line[name] = {"error": f"{type(exc).__name__}: {exc}"}
+        print(f"bench.py: leg '{name}' failed: {type(exc).__name__}: {exc}", file=sys.stderr)
+        torch.cuda.empty_cache()
+
+
 def _time_launch_modes(torch, steps, graph, eager_step):
     """Wall time per step of `steps` graph replays (if a verified graph is given) and of `steps` plain launches of the
     same step; returns ({launch mode: seconds per step}, the faster mode)."""
@@ -723,64 +734,70 @@ def main():
     if not named and not args.no_extras:
         args.long_prefill = args.probes = args.fp8_cache = args.backward = args.stream_session = args.stream_step = True
     if args.probes:
-        line["probes"] = bench_probes(st, torch)
+        with _leg(line, "probes", torch):
+            line["probes"] = bench_probes(st, torch)
     if args.fp8_cache and not args.no_decode:
-        d8 = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph, fp8=True)
-        g8_step = d8["bytes_per_step"] / d8["sec_per_step"] / 1e9
-        g8_kernel = d8["bytes_per_layer"] / (d8["layer_decode_ms"] * 1e-3) / 1e9
-        line["decode_fp8"] = {
-            "workload": "configs[2] with both caches stored in 8 bits (E4M3 codes + one fp32 power-of-two scale per key row and per "
-                        "value row: 264 B instead of 512 B per cached token and KV head); same step as 'decode'",
-            "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in d8["sec_per_step_by_launch"].items()},
-            "ms_per_step": round(d8["sec_per_step"] * 1e3, 4), "algorithmic_bytes_per_step": d8["bytes_per_step"],
-            "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3),
-            "roofline": {"kernel": "decode_split16_fp8_kernel<128> (one layer)", "bound": "hbm", "achieved": round(g8_kernel, 1),
-                         "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g8_kernel / PEAK_HBM_GBPS, 4), "traffic": None,
-                         "avg_kernel_ms": round(d8["layer_decode_ms"], 4)}}
+        with _leg(line, "decode_fp8", torch):
+            d8 = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph, fp8=True)
+            g8_step = d8["bytes_per_step"] / d8["sec_per_step"] / 1e9
+            g8_kernel = d8["bytes_per_layer"] / (d8["layer_decode_ms"] * 1e-3) / 1e9
+            line["decode_fp8"] = {
+                "workload": "configs[2] with both caches stored in 8 bits (E4M3 codes + one fp32 power-of-two scale per key row and per "
+                            "value row: 264 B instead of 512 B per cached token and KV head); same step as 'decode'",
+                "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in d8["sec_per_step_by_launch"].items()},
+                "ms_per_step": round(d8["sec_per_step"] * 1e3, 4), "algorithmic_bytes_per_step": d8["bytes_per_step"],
+                "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3),
+                "roofline": {"kernel": "decode_split16_fp8_kernel<128> (one layer)", "bound": "hbm", "achieved": round(g8_kernel, 1),
+                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g8_kernel / PEAK_HBM_GBPS, 4), "traffic": None,
+                             "avg_kernel_ms": round(d8["layer_decode_ms"], 4)}}
     if args.backward:
-        bw = bench_prefill_backward(st, torch, W, 10)
-        tf = bw["flops"] / (bw["ms"] * 1e-3) / 1e12
-        tf_dq = 1.5 * bw["flops_fwd"] / (bw["dq_ms"] * 1e-3) / 1e12
-        tf_dkv = 2.0 * bw["flops_fwd"] / (bw["dkv_ms"] * 1e-3) / 1e12
-        line["prefill_backward"] = {
-            "workload": "configs[1], gradients dq / dk / dv of the attention stage, bf16 (tile gathering, row statistics and "
-                        "both matrix-core kernels)",
-            "ms": round(bw["ms"], 3), "algorithmic_flops": bw["flops"], "tflops": round(tf, 1),
-            "kernels": {"bwd_dq_mfma_kernel<128>": {"avg_ms": round(bw["dq_ms"], 4), "executed_tflops": round(tf_dq, 1)},
-                        "bwd_dkv_mfma_kernel<128>": {"avg_ms": round(bw["dkv_ms"], 4), "executed_tflops": round(tf_dkv, 1)}},
-            "roofline": {"kernel": "bwd_dq_mfma_kernel<128> + bwd_dkv_mfma_kernel<128>", "bound": "mfma",
-                         "achieved": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12, 1), "peak": PEAK_BF16_TFLOPS,
-                         "unit": "TFLOP/s", "frac": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                         "traffic": None,
-                         "note": "algorithmic = 5 products of 2 D flop per visible (query, key, head) triple (2.5x the forward); the two "
-                                 "kernels execute 7 (scores and dP are recomputed on the key side); executed_tflops counts those"}}
+        with _leg(line, "prefill_backward", torch):
+            bw = bench_prefill_backward(st, torch, W, 10)
+            tf = bw["flops"] / (bw["ms"] * 1e-3) / 1e12
+            tf_dq = 1.5 * bw["flops_fwd"] / (bw["dq_ms"] * 1e-3) / 1e12
+            tf_dkv = 2.0 * bw["flops_fwd"] / (bw["dkv_ms"] * 1e-3) / 1e12
+            line["prefill_backward"] = {
+                "workload": "configs[1], gradients dq / dk / dv of the attention stage, bf16 (tile gathering, row statistics and "
+                            "both matrix-core kernels)",
+                "ms": round(bw["ms"], 3), "algorithmic_flops": bw["flops"], "tflops": round(tf, 1),
+                "kernels": {"bwd_dq_mfma_kernel<128>": {"avg_ms": round(bw["dq_ms"], 4), "executed_tflops": round(tf_dq, 1)},
+                            "bwd_dkv_mfma_kernel<128>": {"avg_ms": round(bw["dkv_ms"], 4), "executed_tflops": round(tf_dkv, 1)}},
+                "roofline": {"kernel": "bwd_dq_mfma_kernel<128> + bwd_dkv_mfma_kernel<128>", "bound": "mfma",
+                             "achieved": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12, 1), "peak": PEAK_BF16_TFLOPS,
+                             "unit": "TFLOP/s", "frac": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                             "traffic": None,
+                             "note": "algorithmic = 5 products of 2 D flop per visible (query, key, head) triple (2.5x the forward); the two "
+                                     "kernels execute 7 (scores and dP are recomputed on the key side); executed_tflops counts those"}}
     if args.stream_session:
-        line["stream_session"] = bench_stream_session(st, torch, W, args.stream_time_scale)
+        with _leg(line, "stream_session", torch):
+            line["stream_session"] = bench_stream_session(st, torch, W, args.stream_time_scale)
     if args.stream_step:
-        ss = bench_stream_step(st, torch, W, 3, 1, args.stream_step_layers, not args.no_graph)
-        gbps = ss["read_bytes"] / ss["sec_per_step"] / 1e9
-        line["stream_step"] = {
-            "workload": "configs[4]: Qwen3-8B-shaped end-to-end streaming step, 36 layers, 64 streams, 32 q / 8 kv heads, head_dim 128, "
-                        "bf16, source caches U[1024,8192] and reasoning caches U[2048,16384] tokens in 16-token pages (shuffled); per "
-                        "step every layer appends a 32-token source chunk on a second stream while 8 reasoning tokens are decoded one "
-                        "after the other through all layers (st_attn_decode_dual_append: store the token, attend over both caches)",
-            "ms_per_step": round(ss["sec_per_step"] * 1e3, 2), "ms_per_token": round(ss["sec_per_step"] * 1e3 / ss["n_tok"], 2),
-            "value": round(gbps, 1), "unit": "GB/s", "pct_of_peak": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
-            "algorithmic_read_bytes_per_step": ss["read_bytes"], "append_bytes_per_step": ss["append_bytes"], "launch": ss["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ss["sec_per_step_by_launch"].items()},
-            "distinct_layer_caches": ss["distinct_layers"], "resident_cache_gb": round(ss["resident_gb"], 1),
-            "tokens_per_s": round(64 * ss["n_tok"] / ss["sec_per_step"], 1)}
+        with _leg(line, "stream_step", torch):
+            ss = bench_stream_step(st, torch, W, 3, 1, args.stream_step_layers, not args.no_graph)
+            gbps = ss["read_bytes"] / ss["sec_per_step"] / 1e9
+            line["stream_step"] = {
+                "workload": "configs[4]: Qwen3-8B-shaped end-to-end streaming step, 36 layers, 64 streams, 32 q / 8 kv heads, head_dim 128, "
+                            "bf16, source caches U[1024,8192] and reasoning caches U[2048,16384] tokens in 16-token pages (shuffled); per "
+                            "step every layer appends a 32-token source chunk on a second stream while 8 reasoning tokens are decoded one "
+                            "after the other through all layers (st_attn_decode_dual_append: store the token, attend over both caches)",
+                "ms_per_step": round(ss["sec_per_step"] * 1e3, 2), "ms_per_token": round(ss["sec_per_step"] * 1e3 / ss["n_tok"], 2),
+                "value": round(gbps, 1), "unit": "GB/s", "pct_of_peak": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
+                "algorithmic_read_bytes_per_step": ss["read_bytes"], "append_bytes_per_step": ss["append_bytes"], "launch": ss["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ss["sec_per_step_by_launch"].items()},
+                "distinct_layer_caches": ss["distinct_layers"], "resident_cache_gb": round(ss["resident_gb"], 1),
+                "tokens_per_s": round(64 * ss["n_tok"] / ss["sec_per_step"], 1)}
     if args.long_prefill:
-        lp = bench_prefill_long(st, torch, W, 5)
-        tf = lp["flops"] / (lp["kernel_ms"] * 1e-3) / 1e12
-        line["prefill_long"] = {
-            "workload": "configs[3]: Qwen3-4B-shaped long-context prefill layer, 8 sequences x 16,384 tokens, 32 q / 8 kv heads, "
-                        "head_dim 128, bf16; attention kernel only (two query heads per workgroup)",
-            "avg_kernel_ms": round(lp["kernel_ms"], 3), "effective_flops": lp["flops"],
-            "same_launch_on_all_zero_inputs": {"avg_kernel_ms": round(lp["zero_input_kernel_ms"], 3),
-                                               "tflops": round(lp["flops"] / (lp["zero_input_kernel_ms"] * 1e-3) / 1e12, 1),
-                                               "note": "same instruction stream, no operand bits toggling: the difference is the power limit"},
-            "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 2>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
-                         "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
+        with _leg(line, "prefill_long", torch):
+            lp = bench_prefill_long(st, torch, W, 5)
+            tf = lp["flops"] / (lp["kernel_ms"] * 1e-3) / 1e12
+            line["prefill_long"] = {
+                "workload": "configs[3]: Qwen3-4B-shaped long-context prefill layer, 8 sequences x 16,384 tokens, 32 q / 8 kv heads, "
+                            "head_dim 128, bf16; attention kernel only (two query heads per workgroup)",
+                "avg_kernel_ms": round(lp["kernel_ms"], 3), "effective_flops": lp["flops"],
+                "same_launch_on_all_zero_inputs": {"avg_kernel_ms": round(lp["zero_input_kernel_ms"], 3),
+                                                   "tflops": round(lp["flops"] / (lp["zero_input_kernel_ms"] * 1e-3) / 1e12, 1),
+                                                   "note": "same instruction stream, no operand bits toggling: the difference is the power limit"},
+                "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 2>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
+                             "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
     if not args.no_cpu_baseline:
         from oracle import streaming_attention as O
         line["cpu_baseline"] = cpu_baseline(W, O, 4.0 * cfg.head_dim)
