@@ -767,6 +767,43 @@ def test_decode_append_in_one_call(st, hq, hkv, d, theta, long):
     assert e.value.status == 5
 
 
+def test_decode_append_in_one_call_random_lengths(st):
+    """Twenty random shapes and length vectors around the page, unit and short-cache boundaries: the one-call step
+    leaves the same pool bits and lengths as st_kv_append_rope + st_attn_decode_dual_rope on a twin pair of caches,
+    and its rows agree with theirs within rounding (those calls are checked against the oracle elsewhere)."""
+    rng = np.random.Generator(np.random.PCG64(450))
+    specials = np.array([0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 511, 512, 513, 1023, 1024, 1025])
+    for trial in range(20):
+        hkv = int(rng.choice([1, 2])); group = int(rng.choice([1, 2, 4, 8, 16])); d = int(rng.choice([64, 128]))
+        hq, batch = hkv * group, 4
+        top = int(rng.choice([200, 900, 1500]))
+        pick = lambda: np.where(rng.random(batch) < 0.5, rng.choice(specials[specials <= top], batch), rng.integers(0, top + 1, batch))
+        src_lens, rsn_lens = pick(), pick()
+        src_vis = np.minimum(src_lens, pick())
+        theta = 1.0e6 if trial % 3 else None
+        twins = []
+        for _ in range(2):
+            r2 = np.random.Generator(np.random.PCG64(4500 + trial))
+            twins.append(_fill_dual(st, r2, batch, hkv, d, src_lens, rsn_lens, rope_theta=theta)[0])
+        ca, cb = twins
+        q = to_dev(W.normal(rng, (batch, 1, hq, d), "bf16"), "bf16")
+        tk = to_dev(W.normal(rng, (batch, 1, hkv, d), "bf16"), "bf16"); tv = to_dev(W.normal(rng, (batch, 1, hkv, d), "bf16"), "bf16")
+        new_len = rsn_lens + 1
+        vis_t = torch.from_numpy(src_vis.astype(np.int32)).to(DEV); rl_t = torch.from_numpy(new_len.astype(np.int32)).to(DEV)
+        max_s, max_r = int(src_lens.max()), int(new_len.max())
+        lse_f = torch.empty((batch, 1, hq), dtype=torch.float32, device=DEV); lse_u = torch.empty_like(lse_f)
+        out_f = st.st_attn_decode_dual_append(q, tk, tv, ca, vis_t, rl_t, max_s, max_r, theta_base=theta or 0.0, lse=lse_f)
+        st.st_kv_append(cb, st.ST_REASONING, tk, tv, rope_theta=theta)
+        out_u = st.st_attn_decode_dual(q, cb, vis_t, rl_t, max_s, max_r, rope_theta=theta, lse=lse_u)
+        torch.cuda.synchronize()
+        tag = (trial, hq, hkv, d, src_lens.tolist(), rsn_lens.tolist())
+        assert ca.reasoning.appended_len.cpu().tolist() == new_len.tolist() == cb.reasoning.appended_len.cpu().tolist(), tag
+        for name in ("k_pool", "v_pool"):
+            assert torch.equal(getattr(ca.reasoning, name).view(torch.int16), getattr(cb.reasoning, name).view(torch.int16)), (name, tag)
+        assert (out_f.float() - out_u.float()).abs().max().item() <= 1e-2, tag
+        assert (lse_f - lse_u).abs().max().item() <= 1e-2, tag
+
+
 def test_decode_empty_row(st):
     """Both lengths zero: out = 0, lse = -inf."""
     rng = np.random.Generator(np.random.PCG64(413))
