@@ -658,7 +658,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU; there is no multi-GPU mode (sequences and KV heads shard "
-              "without communication, see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "without communication; sharding one sequence's caches by token range needs one exchange of partial results). "
+              "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2510_17238_amd as st
