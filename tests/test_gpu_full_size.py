@@ -104,7 +104,7 @@ def test_config4b_prefill_128_pairs(st):
     _prefill_full(st, W.config4b(), meta_seqs=(3,), n_extra=12)
 
 
-def _decode_full(st, shp, q_len, check_seqs, seed, fp8=False):
+def _decode_full(st, shp, q_len, check_seqs, seed, fp8=False, one_call=False):
     B, hq, hkv, d = shp.batch, shp.n_q_heads, shp.n_kv_heads, shp.head_dim
     rng = np.random.Generator(np.random.PCG64(seed))
     pages_s = (shp.max_src_len + 15) // 16; pages_r = (shp.max_rsn_len + 15) // 16
@@ -128,7 +128,8 @@ def _decode_full(st, shp, q_len, check_seqs, seed, fp8=False):
     cs.appended_len.copy_(torch.from_numpy(shp.src_visible_len)); cr.appended_len.copy_(torch.from_numpy(rsn_before))
     k_tok = _device_normal((B, q_len, hkv, d), seed + 1); v_tok = _device_normal((B, q_len, hkv, d), seed + 2)
     q = _device_normal((B, q_len, hq, d), seed + 3)
-    st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=int(shp.rsn_len.max()))
+    if not one_call:
+        st.st_kv_append(caches, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=int(shp.rsn_len.max()))
     # a source chunk arriving on a second stream while the decode runs (not yet visible)
     k_src = _device_normal((B, shp.src_append, hkv, d), seed + 4)
     side = torch.cuda.Stream(); side.wait_stream(torch.cuda.current_stream())
@@ -136,7 +137,10 @@ def _decode_full(st, shp, q_len, check_seqs, seed, fp8=False):
         st.st_kv_append(caches, st.ST_SOURCE, k_src, k_src, host_len_upper_bound=shp.max_src_len, stream=side)
     vis = torch.from_numpy(shp.src_visible_len).to(DEV); rl = torch.from_numpy(shp.rsn_len).to(DEV)
     lse = torch.empty((B, q_len, hq), dtype=torch.float32, device=DEV)
-    out = st.st_attn_decode_dual(q, caches, vis, rl, int(shp.src_visible_len.max()), int(shp.rsn_len.max()), lse=lse)
+    if one_call:     # the form bench.py times: store the token and attend in one call (rotated inputs: theta_base 0)
+        out = st.st_attn_decode_dual_append(q, k_tok, v_tok, caches, vis, rl, int(shp.src_visible_len.max()), int(shp.rsn_len.max()), lse=lse)
+    else:
+        out = st.st_attn_decode_dual(q, caches, vis, rl, int(shp.src_visible_len.max()), int(shp.rsn_len.max()), lse=lse)
     torch.cuda.synchronize()
     assert cr.appended_len.cpu().tolist() == shp.rsn_len.tolist()
     assert cs.appended_len.cpu().tolist() == (shp.src_visible_len + shp.src_append).tolist()
@@ -174,6 +178,22 @@ def test_config3_decode_one_layer(st):
     shp = W.config3()
     longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
     _decode_full(st, shp, 1, sorted({0, 7, longest, shortest}), seed=31)
+
+
+def test_config3_decode_one_layer_in_one_call(st):
+    """The same step the way bench.py issues it: st_attn_decode_dual_append stores the token and attends (512-token
+    units chosen by launch size, the token through the split kernel's extra work unit)."""
+    shp = W.config3()
+    longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
+    _decode_full(st, shp, 1, sorted({1, 9, longest, shortest}), seed=33, one_call=True)
+
+
+def test_config5_decode_token_in_one_call(st):
+    """One token of the Qwen3-8B-shaped streaming step (64 streams, caches up to 8K + 16K tokens: 1024-token units), one
+    layer, issued as bench.py's streaming-step leg issues it."""
+    shp = W.config5()
+    longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
+    _decode_full(st, shp, 1, sorted({2, longest, shortest}), seed=34, one_call=True)
 
 
 def test_config3_decode_one_layer_8bit_caches(st):
