@@ -37,7 +37,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # HBM bytes per launch of the two dominant kernels on the default workloads, from the FETCH_SIZE and
 # WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB copy (x2.000 and x1.000);
 # see profiles/hbm_traffic_prefill_cfg2_decode_cfg3.txt for the runs.
-MEASURED_TRAFFIC = {"prefill_mfma_pipe_kernel<128, 1>": 261.7e6 + 65.7e6, "decode_split16_kernel<128>": 701.8e6 + 3.0e6}
+MEASURED_TRAFFIC = {"prefill_mfma_pipe_kernel<128, 1>": 261.7e6 + 65.7e6, "decode_split16_kernel<128>": 702.5e6 + 4.4e6}
 
 
 def _median(xs):
