@@ -96,16 +96,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32
                                                                      unsigned long long* __restrict__ pairs,
                                                                      int32_t* __restrict__ flag, int validate) {
     __shared__ int s_wave[kPlanThreads / 64];
-    __shared__ int s_total;
     __shared__ unsigned long long s_pairs[kPlanThreads / 64];
     __shared__ int s_seg[kSegLds];            // segment ids of the source stream: the bisection below stays in LDS
     const int b = blockIdx.x;
     const int t0 = cu[b], t1 = cu[b + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
+    // The ids of the first kPre chunks (8,192 tokens) are fetched once, up front, and serve both passes below, so
+    // that the iterations of the rank pass do not each wait for memory.
+    constexpr int kPre = 8;
+    int pre_stream[kPre], pre_seg[kPre];
+#pragma unroll
+    for (int j = 0; j < kPre; ++j) {
+        const int t = t0 + j * kPlanThreads + threadIdx.x;
+        pre_stream[j] = t < t1 ? stream_ids[t] : -1;
+        pre_seg[j] = t < t1 ? segment_ids[t] : 0;
+    }
+
     // pass 1: number of source tokens
     int cnt = 0;
-    for (int t = t0 + threadIdx.x; t < t1; t += kPlanThreads) {
+#pragma unroll
+    for (int j = 0; j < kPre; ++j) {
+        const int t = t0 + j * kPlanThreads + threadIdx.x;
+        if (t < t1) {
+            if (pre_stream[j] != ST_SOURCE && pre_stream[j] != ST_REASONING) atomicOr(flag, 1);
+            cnt += (pre_stream[j] == ST_SOURCE);
+        }
+    }
+    for (int t = t0 + kPre * kPlanThreads + threadIdx.x; t < t1; t += kPlanThreads) {
         const int s = stream_ids[t];
         if (s != ST_SOURCE && s != ST_REASONING) atomicOr(flag, 1);
         cnt += (s == ST_SOURCE);
@@ -114,33 +132,42 @@ __global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32
     if (threadIdx.x == 0) {
         n_src[b] = S;
         n_rsn[b] = (t1 - t0) - S;
-        s_total = 0;
     }
     __syncthreads();
 
-    // pass 2: running rank of source tokens; reasoning rank = index - source rank
-    for (int base = t0; base < t1; base += kPlanThreads) {
-        const int t = base + threadIdx.x;
+    // pass 2: running rank of source tokens; reasoning rank = index - source rank.  One barrier per chunk: the wave
+    // counts go to two buffers used in turn, and every thread keeps the running total itself.
+    __shared__ int s_cnt[2][kPlanThreads / 64];
+    int total_before = 0;                                    // sources in the chunks already done (same in every thread)
+    auto rank_chunk = [&](int parity, int t, int sid, int seg) {
         const bool in = t < t1;
-        const bool is_src = in && stream_ids[t] == ST_SOURCE;
+        const bool is_src = in && sid == ST_SOURCE;
         const unsigned long long mask = __ballot(is_src);
         const int before_in_wave = __popcll(mask & ((1ull << lane) - 1ull));
-        if (lane == 0) s_wave[wave] = __popcll(mask);
+        if (lane == 0) s_cnt[parity][wave] = __popcll(mask);
         __syncthreads();
-        int before = s_total, all = 0;
+        int before = total_before, all = 0;
         for (int w = 0; w < kPlanThreads / 64; ++w) {
-            before += w < wave ? s_wave[w] : 0;
-            all += s_wave[w];
+            const int c = s_cnt[parity][w];
+            before += w < wave ? c : 0;
+            all += c;
         }
         const int src_rank = before + before_in_wave;          // sources strictly before t
         if (in) {
             const int r = is_src ? src_rank : S + ((t - t0) - src_rank);
             perm[t0 + r] = t;
-            seg_c[t0 + r] = segment_ids[t];
+            seg_c[t0 + r] = seg;
         }
-        __syncthreads();
-        if (threadIdx.x == 0) s_total += all;
-        __syncthreads();
+        total_before += all;
+    };
+#pragma unroll
+    for (int j = 0; j < kPre; ++j) {
+        if (t0 + j * kPlanThreads < t1)                        // (uniform)
+            rank_chunk(j & 1, t0 + j * kPlanThreads + threadIdx.x, pre_stream[j], pre_seg[j]);
+    }
+    for (int base = t0 + kPre * kPlanThreads, j = kPre; base < t1; base += kPlanThreads, ++j) {
+        const int t = base + threadIdx.x;
+        rank_chunk(j & 1, t, t < t1 ? stream_ids[t] : -1, t < t1 ? segment_ids[t] : 0);
     }
     __threadfence_block();      // perm / seg_c of this sequence are read back below by other threads
     __syncthreads();
