@@ -56,17 +56,7 @@ struct HostTables {                      // cu_seqlens | item slot bases | packe
     int32_t v[3 * (kTablesMaxBatch + 1)];
 };
 
-// ---- kernel 0: publish the host tables (passed by value, no copy engine involved) and clear the
-// validation flag; a fill kernel, so that the whole build can be recorded into a HIP graph ----------
-__global__ void plan_init_kernel(HostTables t, int batch, int32_t* __restrict__ cu, int32_t* __restrict__ slot_base,
-                                 int32_t* __restrict__ pack_base, int32_t* __restrict__ flag) {
-    for (int i = threadIdx.x; i <= batch; i += blockDim.x) {
-        cu[i] = t.v[i];
-        slot_base[i] = t.v[(batch + 1) + i];
-        pack_base[i] = t.v[2 * (batch + 1) + i];
-    }
-    if (threadIdx.x == 0) *flag = 0;
-}
+// ---- fill kernel that clears the validation flag (a kernel, so that the build can be recorded into a HIP graph) ----
 __global__ void plan_clear_kernel(int32_t* flag) {
     if (threadIdx.x == 0) *flag = 0;
 }
@@ -94,12 +84,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_sequence_kernel(const int32
                                                                      int32_t* __restrict__ perm, int32_t* __restrict__ seg_c,
                                                                      int32_t* __restrict__ vis,
                                                                      unsigned long long* __restrict__ pairs,
-                                                                     int32_t* __restrict__ flag, int validate) {
+                                                                     int32_t* __restrict__ flag, int validate, HostTables tables,
+                                                                     int batch, int32_t* __restrict__ cu_out,
+                                                                     int32_t* __restrict__ slot_base_out,
+                                                                     int32_t* __restrict__ pack_base_out) {
     __shared__ int s_wave[kPlanThreads / 64];
     __shared__ unsigned long long s_pairs[kPlanThreads / 64];
     __shared__ int s_seg[kSegLds];            // segment ids of the source stream: the bisection below stays in LDS
     const int b = blockIdx.x;
-    const int t0 = cu[b], t1 = cu[b + 1];
+    // batch > 0: the host tables travel as a kernel argument (no separate launch to publish them): this kernel reads
+    // its offsets from there, and workgroup 0 writes the device copies that every later kernel uses.  batch = 0: the
+    // tables were copied to `cu` beforehand.
+    const int t0 = batch > 0 ? tables.v[b] : cu[b], t1 = batch > 0 ? tables.v[b + 1] : cu[b + 1];
+    if (batch > 0 && b == 0)
+        for (int i = threadIdx.x; i <= batch; i += kPlanThreads) {
+            cu_out[i] = tables.v[i];
+            slot_base_out[i] = tables.v[(batch + 1) + i];
+            pack_base_out[i] = tables.v[2 * (batch + 1) + i];
+        }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // The ids of the first kPre chunks (8,192 tokens) are fetched once, up front, and serve both passes below, so
@@ -406,14 +408,17 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
         return r;
     };
     hipError_t e;
-    if (batch <= kTablesMaxBatch) {
-        HostTables t;
+    HostTables t = {};
+    const bool by_value = batch <= kTablesMaxBatch;
+    if (by_value) {
         for (int i = 0; i <= batch; ++i) {
             t.v[i] = p->cu_host[i];
             t.v[(batch + 1) + i] = p->slot_base_host[i];
             t.v[2 * (batch + 1) + i] = p->pack_base_host[i];
         }
-        hipLaunchKernelGGL(plan_init_kernel, dim3(1), dim3(256), 0, s, t, batch, p->cu, p->slot_base, p->pack_base, p->flag);
+        // (the validation flag is only read back when validation is asked for: cleared then, by a fill kernel, so
+        // that the build can be recorded into a HIP graph)
+        if (validate) hipLaunchKernelGGL(plan_clear_kernel, dim3(1), dim3(64), 0, s, p->flag);
     } else {
         // the host vectors live as long as the plan, so the asynchronous copies may read them later
         if ((e = hipMemcpyAsync(p->cu, p->cu_host.data(), sizeof(int32_t) * (batch + 1), hipMemcpyHostToDevice, s)) != hipSuccess)
@@ -425,7 +430,8 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
         hipLaunchKernelGGL(plan_clear_kernel, dim3(1), dim3(64), 0, s, p->flag);
     }
     hipLaunchKernelGGL(plan_sequence_kernel, dim3(batch), dim3(kPlanThreads), 0, s, stream_ids, segment_ids, positions, p->cu,
-                       p->n_src, p->n_rsn, p->perm, p->seg_c, p->vis, p->pairs, p->flag, validate ? 1 : 0);
+                       p->n_src, p->n_rsn, p->perm, p->seg_c, p->vis, p->pairs, p->flag, validate ? 1 : 0, t, by_value ? batch : 0, p->cu,
+                       p->slot_base, p->pack_base);
     if (p->m_max <= kSortedMax) {
         hipLaunchKernelGGL(plan_items_sorted_kernel, dim3(1), dim3(kPlanThreads), 0, s, p->cu, p->slot_base, p->pack_base, batch,
                            p->m_max, p->n_src, p->n_rsn, p->vis, p->items, p->cost, p->sorted);
