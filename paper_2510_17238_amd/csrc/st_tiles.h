@@ -48,7 +48,6 @@ __global__ __launch_bounds__(256) void tile_pack_kernel(uint16_t* __restrict__ k
                                                            int n_kv_heads) {
     constexpr int KCH = D / 8;
     constexpr int K_PER_THREAD = kTileN * KCH / 256;
-    constexpr int VQ = D / 4;
     const int tile = blockIdx.x / n_kv_heads;
     const int h = blockIdx.x % n_kv_heads;
     const int b = find_seq(pv.pack_base, pv.batch, tile);
@@ -77,18 +76,18 @@ __global__ __launch_bounds__(256) void tile_pack_kernel(uint16_t* __restrict__ k
         const int lr = swap23(row);                                    // row position in the tile
         *reinterpret_cast<u32x4*>(kdst + lr * D + (ch ^ swizzle_key<2 * D>(lr)) * 8) = val;
     }
-    // V: 8 keys x 4 d per thread, transposed in registers to 4 d x 8 keys
+    // V: 8 keys x 8 d per thread (16-byte loads), transposed in registers to 8 d x 8 keys (16-byte stores)
     const int kvb = tid & 7, dq = tid >> 3;
-    if (vc != nullptr && dq < VQ) {
-        u32x2 vreg[8];
+    if (vc != nullptr && dq < D / 8) {
+        u32x4 vreg[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int row = kvb * 8 + r;
-            vreg[r] = u32x2{0u, 0u};
-            if (row < valid) vreg[r] = *reinterpret_cast<const u32x2*>(v + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + dq * 4));
+            vreg[r] = u32x4{0u, 0u, 0u, 0u};
+            if (row < valid) vreg[r] = *reinterpret_cast<const u32x4*>(v + (uint32_t(pv.perm[base + row]) * row_stride + uint32_t(h) * D + dq * 8));
         }
 #pragma unroll
-        for (int w = 0; w < 2; ++w) {
+        for (int w = 0; w < 4; ++w) {                 // word w of every row holds d = 2 w and 2 w + 1
             u32x4 even, odd;
 #pragma unroll
             for (int pr = 0; pr < 4; ++pr) {
@@ -96,7 +95,7 @@ __global__ __launch_bounds__(256) void tile_pack_kernel(uint16_t* __restrict__ k
                 even[pr] = __builtin_amdgcn_perm(bb, a, 0x05040100u);   // low halves
                 odd[pr] = __builtin_amdgcn_perm(bb, a, 0x07060302u);    // high halves
             }
-            const int d0 = dq * 4 + 2 * w;
+            const int d0 = dq * 8 + 2 * w;
             *reinterpret_cast<u32x4*>(vdst + d0 * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0)) * 8) = even;
             *reinterpret_cast<u32x4*>(vdst + (d0 + 1) * kTileN + (kvb ^ swizzle_key<2 * kTileN>(d0 + 1)) * 8) = odd;
         }
