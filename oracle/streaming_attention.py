@@ -26,7 +26,9 @@ decode == last prefill row, paged gather == contiguous, rotate-on-append / rotat
 the unfused pipeline, Alg. 1 timeline == hand-worked schedules and the paper's Table 4 latencies,
 backward == central differences of the forward and == library autograd of a dense-mask softmax,
 E4M3 rounding / bytes == a library's cast over all codes, midpoints and random values, row scales == their
-defining inequality, 8-bit store idempotent and within half a grid step.
+defining inequality, 8-bit store idempotent and within half a grid step, the row-subset mask / attention ==
+the scalar rule pair by pair, the hand-listed sets, Eq. 2 as printed and the rows of the full result, the
+packed-batch forward / backward == brute force per sequence and central differences of the packed forward.
 No function here is "parity unpinned".
 """
 import numpy as np

@@ -592,3 +592,136 @@ def test_bf16_rounding_helper_roundtrip():
     t = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(r, t)
     assert np.array_equal(W.bf16_from_bits(W.bf16_bits(r)), r)
+
+
+# ---- P14: the row-subset and packed-batch forms are the same definitions (Eq. 1, Eq. 2, Sec. 3.2)
+def _ragged_structures():
+    """configs[0] in both layouts, plus random ragged structures with empty and 1-token segments."""
+    cases = []
+    for layout in ("interleaved", "grouped"):
+        c = W.config1(layout)
+        cases.append((f"cfg1-{layout}", c.stream_ids, c.segment_ids, c.positions))
+        for seed in (1401, 1402, 1403):
+            rng = np.random.Generator(np.random.PCG64(seed))
+            s, r = W.draw_pairs(rng, 6, (0, 4), (0, 5))
+            s[1] = 0; r[2] = 0; s[3] = 1; r[4] = 1            # empty and 1-token segments on both streams
+            st, sg, ps = W.tokens_from_segments(s, r, layout)
+            cases.append((f"rand{seed}-{layout}", st, sg, ps))
+    return cases
+
+
+@pytest.mark.parametrize("name,stream,seg,pos", _ragged_structures(), ids=lambda x: x if isinstance(x, str) else "")
+def test_p14_mask_rows_is_eq1_row_by_row(name, stream, seg, pos):
+    """mask_rows against the scalar rule of Eq. 1 (visible(), pinned by the hand-listed sets and by Eq. 2 as
+    printed) pair by pair, and against the rows of the dense mask, for row lists in any order with repeats."""
+    n = len(stream)
+    rng = np.random.Generator(np.random.PCG64(1410))
+    for rows in (np.arange(n), np.arange(n)[::-1], rng.integers(0, n, size=2 * n), np.array([n - 1, 0, n - 1]), np.zeros(0, np.int64)):
+        got = O.mask_rows(stream, seg, pos, rows)
+        assert got.shape == (len(rows), n) and got.dtype == bool
+        assert (got == O.dense_mask(stream, seg, pos)[rows]).all()
+        for a, i in enumerate(rows):
+            for j in range(n):
+                assert got[a, j] == O.visible(stream[i], seg[i], pos[i], stream[j], seg[j], pos[j]), (name, i, j)
+
+
+def test_p14_mask_rows_hand_listed_sets_and_eq2_print():
+    """The same hand-written conditioning sets and the same printed Eq. 2 matrix that pin dense_mask."""
+    stream, seg, pos = W.tokens_from_segments([2, 3, 1], [2, 1, 3], "interleaved")
+    # physical order: S1(0,1) R1(2,3) S2(4,5,6) R2(7) S3(8) R3(9,10,11)
+    expect = {7: [0, 1, 4, 5, 6, 2, 3, 7], 8: [0, 1, 4, 5, 6, 8], 2: [0, 1, 2], 11: [0, 1, 4, 5, 6, 8, 2, 3, 7, 9, 10, 11], 4: [0, 1, 4]}
+    rows = list(expect)
+    got = O.mask_rows(stream, seg, pos, rows)
+    for a, i in enumerate(rows):
+        assert sorted(np.nonzero(got[a])[0].tolist()) == sorted(expect[i]), i
+    T, L = 6, 4
+    lines = [l.split() for l in open(os.path.join(GOLDEN, "eq2_mask_T6_L4.txt")) if l.strip() and not l.startswith("#")]
+    printed = np.array(lines, dtype=int).astype(bool)
+    stream = np.array([O.SRC] * T + [O.RSN] * L)
+    seg = np.array(list(range(1, T + 1)) + [r + 1 for r in range(1, L + 1)])
+    pos = np.array(list(range(T)) + list(range(L)))
+    rows = np.array([9, 6, 0, 7, 8, 5])
+    cols = np.arange(T + L) != (T - 1)
+    assert (O.mask_rows(stream, seg, pos, rows)[:, cols] == printed[rows][:, cols]).all()
+
+
+@pytest.mark.parametrize("name,stream,seg,pos", _ragged_structures(), ids=lambda x: x if isinstance(x, str) else "")
+def test_p14_attention_rows_equals_rows_of_attention(name, stream, seg, pos):
+    """attention_dense(rows=r) == attention_dense()[r], exactly (same products, same sums per row), and == the
+    brute force over the gathered visible sets on the tiny cases."""
+    n = len(stream)
+    rng = np.random.Generator(np.random.PCG64(1420))
+    hq, hkv, d = 4, 2, 8
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    o_all, l_all = O.attention_dense(q, k, v, stream, seg, pos)
+    for rows in (rng.permutation(n)[: max(1, n // 3)], np.array([n - 1, 0]), np.arange(n)):
+        o_r, l_r = O.attention_dense(q, k, v, stream, seg, pos, rows=rows)
+        assert o_r.shape == (len(rows), hq, d) and l_r.shape == (len(rows), hq)
+        assert np.abs(o_r - o_all[rows]).max() < 1e-14 and np.abs(l_r - l_all[rows]).max() < 1e-14
+    if n <= 40:
+        o_b, l_b = O.attention_bruteforce(q, k, v, stream, seg, pos)
+        rows = rng.permutation(n)[:5]
+        o_r, l_r = O.attention_dense(q, k, v, stream, seg, pos, rows=rows)
+        assert np.abs(o_r - o_b[rows]).max() < 1e-12 and np.abs(l_r - l_b[rows]).max() < 1e-12
+
+
+def _packed_batch(seed, hq, hkv, d):
+    """Three sequences packed one after the other, the middle one EMPTY, ids restarting in every sequence."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    metas = [W.tokens_from_segments([3, 0, 2], [2, 4, 1], "interleaved"),
+             (np.zeros(0, np.int32),) * 3,
+             W.tokens_from_segments([1, 5], [6, 0], "grouped"),
+             W.tokens_from_segments([4], [3], "interleaved")]
+    cu = np.cumsum([0] + [len(m[0]) for m in metas]).astype(np.int32)
+    stream, seg, pos = (np.concatenate([m[i] for m in metas]) for i in range(3))
+    n = int(cu[-1])
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    g = rng.standard_normal((n, hq, d))
+    return cu, stream, seg, pos, q, k, v, g
+
+
+def test_p14_varlen_forward_is_per_sequence_attention():
+    cu, stream, seg, pos, q, k, v, g = _packed_batch(1430, 4, 2, 8)
+    out, lse = O.attention_varlen(q, k, v, stream, seg, pos, cu)
+    for b in range(len(cu) - 1):
+        s, e = int(cu[b]), int(cu[b + 1])
+        if e == s:
+            continue
+        # an independent route per sequence: the brute force over the visible sets of Eq. 1
+        o_b, l_b = O.attention_bruteforce(q[s:e], k[s:e], v[s:e], stream[s:e], seg[s:e], pos[s:e])
+        assert np.abs(out[s:e] - o_b).max() < 1e-12 and np.abs(lse[s:e] - l_b).max() < 1e-12
+    # no token sees another sequence: changing sequence 0's keys / values leaves the others' rows bit-identical
+    k2 = k.copy(); v2 = v.copy(); k2[: cu[1]] += 3.0; v2[: cu[1]] -= 2.0
+    out2, lse2 = O.attention_varlen(q, k2, v2, stream, seg, pos, cu)
+    assert (out2[cu[1]:] == out[cu[1]:]).all() and (lse2[cu[1]:] == lse[cu[1]:]).all()
+    assert np.abs(out2[: cu[1]] - out[: cu[1]]).max() > 1e-3
+    # a scale passed through reaches every sequence
+    o_s, _ = O.attention_varlen(q, k, v, stream, seg, pos, cu, scale=0.3)
+    s, e = int(cu[2]), int(cu[3])
+    assert np.abs(o_s[s:e] - O.attention_dense(q[s:e], k[s:e], v[s:e], stream[s:e], seg[s:e], pos[s:e], 0.3)[0]).max() < 1e-14
+
+
+def test_p14_varlen_backward_is_per_sequence_and_stays_inside_sequences():
+    cu, stream, seg, pos, q, k, v, g = _packed_batch(1440, 4, 2, 6)
+    dq, dk, dv = O.attention_varlen_backward(q, k, v, g, stream, seg, pos, cu)
+    for b in range(len(cu) - 1):
+        s, e = int(cu[b]), int(cu[b + 1])
+        dq_b, dk_b, dv_b = O.attention_dense_backward(q[s:e], k[s:e], v[s:e], g[s:e], stream[s:e], seg[s:e], pos[s:e])
+        assert (dq[s:e] == dq_b).all() and (dk[s:e] == dk_b).all() and (dv[s:e] == dv_b).all()
+    # independent of the per-sequence routine: central differences of the PACKED forward
+    loss = lambda q_, k_, v_: float((g * O.attention_varlen(q_, k_, v_, stream, seg, pos, cu)[0]).sum())
+    rng = np.random.Generator(np.random.PCG64(1441))
+    eps = 1e-6
+    for name, x, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        for _ in range(20):
+            i = tuple(int(rng.integers(0, s)) for s in x.shape)
+            xp = x.copy(); xm = x.copy(); xp[i] += eps; xm[i] -= eps
+            args_p = {"q": (xp, k, v), "k": (q, xp, v), "v": (q, k, xp)}[name]
+            args_m = {"q": (xm, k, v), "k": (q, xm, v), "v": (q, k, xm)}[name]
+            num = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(num - grad[i]) < 1e-7, (name, i, num, grad[i])
+    # gradient flowing only into the LAST sequence's outputs leaves dk / dv of the other sequences exactly zero
+    g_last = np.zeros_like(g); g_last[cu[-2]:] = g[cu[-2]:]
+    dq1, dk1, dv1 = O.attention_varlen_backward(q, k, v, g_last, stream, seg, pos, cu)
+    assert np.all(dk1[: cu[-2]] == 0) and np.all(dv1[: cu[-2]] == 0) and np.all(dq1[: cu[-2]] == 0)
+    assert np.abs(dk1[cu[-2]:]).max() > 0 and np.abs(dv1[cu[-2]:]).max() > 0
