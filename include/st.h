@@ -394,6 +394,22 @@ st_status st_attn_decode_dual(void* out, float* lse, const void* q,
                               int32_t batch, int32_t n_q_heads, float scale,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* st_attn_decode_dual for callers that cannot allocate device memory or hand over a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * partial results live in a device array that is part of the library's code object
+ * (st_decode_static_scratch_bytes() bytes -- 64 MiB -- on every GPU the library is used on, held
+ * until the process ends); the call itself allocates nothing and frees nothing.  Same arguments,
+ * kernels and results as st_attn_decode_dual.  A step whose partial results (for 512-token work
+ * units: what st_attn_decode_dual demands of its workspace) do not fit the array gives
+ * ST_ERR_CAPACITY and launches nothing.  All calls on one GPU share that GPU's array: two such
+ * calls that overlap in time on one GPU (different streams or threads) race; calls on one stream
+ * are ordered.  Nothing in the array needs clearing between calls. */
+size_t st_decode_static_scratch_bytes(void);
+
+st_status st_attn_decode_dual_static(void* out, float* lse, const void* q,
+                                     const st_dual_cache* caches, const st_dual_lens* lens,
+                                     int32_t batch, int32_t n_q_heads, float scale, void* hip_stream);
+
 /* st_attn_decode_dual with the query rotation fused in (Sec. 3.2): q holds UNROTATED
  * queries; row t of sequence b is the reasoning token at index rsn_len[b] - q_len + t of
  * its stream (already appended, Alg. 1), and is rotated by that position id with base

@@ -136,6 +136,10 @@ def load_library():
     lib.st_attn_decode_dual.restype = i32
     lib.st_attn_decode_dual.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
                                         f32, vp, sz, vp]
+    lib.st_decode_static_scratch_bytes.restype = sz
+    lib.st_decode_static_scratch_bytes.argtypes = []
+    lib.st_attn_decode_dual_static.restype = i32
+    lib.st_attn_decode_dual_static.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32, f32, vp]
     lib.st_source_chunk_workspace_bytes.restype = sz
     lib.st_source_chunk_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
     lib.st_attn_source_chunk.restype = i32
@@ -543,6 +547,24 @@ def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rs
         _check(lib.st_attn_decode_dual_rope(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
                                             float(rope_theta), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream(stream)))
+    return out
+
+
+def st_decode_static_scratch_bytes():
+    return int(load_library().st_decode_static_scratch_bytes())
+
+
+def st_attn_decode_dual_static(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, out, lse=None, scale=0.0, stream=None):
+    """st_attn_decode_dual without a workspace (the library's own device array); `out` is the caller's: nothing is
+    allocated here either."""
+    assert q.is_cuda and q.is_contiguous() and q.dtype == torch.bfloat16 and q.dim() == 4
+    assert out.shape == q.shape and out.dtype == q.dtype and out.is_contiguous()
+    batch, q_len, hq, d = q.shape
+    _dev_i32(src_visible_len, "src_visible_len"); _dev_i32(rsn_len, "rsn_len")
+    st = caches.struct()
+    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
+    _check(load_library().st_attn_decode_dual_static(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
+                                                     _stream(stream)))
     return out
 
 

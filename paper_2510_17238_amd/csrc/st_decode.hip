@@ -18,6 +18,7 @@
 
 #include "st_cache.h"
 #include <atomic>
+#include <mutex>
 
 #include "st_tiles.h"
 
@@ -1303,10 +1304,38 @@ extern "C" size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, in
     return base > own ? base : own;
 }
 
+// ---- the decode step for callers that cannot allocate: partial results in a device array of the library ----
+// One copy of `scratch` exists on every GPU the library's code object is loaded on, at an address of its own; in host
+// code the array's NAME is only a stand-in for it, so its device address is looked up once per device
+// (hipGetSymbolAddress, with that device current) and only that pointer is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = size_t(64) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+// Device address of `scratch` on the CURRENT device (looked up at the first call on that device).
+static st_status static_scratch(void** ptr) {
+    int dev = -1;
+    ST_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual_static: device index %d (0 .. %d)", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        ST_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return fail(ST_ERR_RUNTIME, "st_attn_decode_dual_static: bad address of the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return ST_OK;
+}
+
 static st_status decode_dual_impl(void* out, float* lse, const void* q, const st_dual_cache* caches,
                                   const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale, bool rotate,
                                   double theta_base, void* workspace, size_t workspace_bytes, void* hip_stream,
-                                  const void* k_new = nullptr, const void* v_new = nullptr, bool append = false) {
+                                  const void* k_new = nullptr, const void* v_new = nullptr, bool append = false, bool no_alloc = false) {
     if (!out || !q || !caches || !lens) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: null pointer");
     if (append) {
         if (!k_new || !v_new) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_append: null pointer");
@@ -1409,13 +1438,13 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
         const dim3 grid((unsigned)((units + 3) / 4)), block(256);
         if (a.rows <= 16) {
             if (units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
-            prof_begin(kProfDecodeSplit, s);
+            if (!no_alloc) prof_begin(kProfDecodeSplit, s);      // (the timing hooks create events)
             if (fp8) {
                 if (d == 64) hipLaunchKernelGGL((decode_split16_fp8_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
                 else hipLaunchKernelGGL((decode_split16_fp8_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
             } else if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
             else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
-            prof_end(kProfDecodeSplit, s);
+            if (!no_alloc) prof_end(kProfDecodeSplit, s);
         } else {
             if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
             else hipLaunchKernelGGL((decode_split_kernel<128>), grid, block, 0, s, a);
@@ -1437,6 +1466,28 @@ extern "C" st_status st_attn_decode_dual(void* out, float* lse, const void* q, c
                                          const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale,
                                          void* workspace, size_t workspace_bytes, void* hip_stream) {
     return decode_dual_impl(out, lse, q, caches, lens, batch, n_q_heads, scale, false, 0.0, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t st_decode_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" st_status st_attn_decode_dual_static(void* out, float* lse, const void* q, const st_dual_cache* caches,
+                                                const st_dual_lens* lens, int32_t batch, int32_t n_q_heads, float scale,
+                                                void* hip_stream) {
+    if (!caches || !lens) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual_static: null pointer");
+    const int hkv = caches->source.n_kv_heads, d = caches->source.head_dim;
+    if (batch <= 0 || n_q_heads <= 0 || hkv <= 0 || d <= 0 || n_q_heads % hkv != 0 || lens->q_len <= 0 || lens->max_src_len < 0 || lens->max_rsn_len < 0)
+        return fail(ST_ERR_SHAPE, "st_attn_decode_dual_static: bad sizes");
+    // what st_attn_decode_dual asks of a workspace for these bounds (partials of 512-token units) must fit the array
+    const size_t need = decode_partial_bytes(kChunk, batch, hkv, lens->q_len * (n_q_heads / hkv), d, lens->max_src_len, lens->max_rsn_len);
+    if (need > kStaticScratchBytes)
+        return fail(ST_ERR_CAPACITY, "st_attn_decode_dual_static: the step needs %zu bytes of partial results, the library's array holds %zu; use st_attn_decode_dual with a workspace", need, kStaticScratchBytes);
+    void* ws = nullptr;
+    const st_status r = static_scratch(&ws);
+    if (r != ST_OK) return r;
+    // Nothing in the array has to start at zero: the split kernel writes every partial the merge kernel reads in the
+    // same call (both walk the same units of the same lengths), so what an earlier call left is never looked at.
+    return decode_dual_impl(out, lse, q, caches, lens, batch, n_q_heads, scale, false, 0.0, ws, kStaticScratchBytes, hip_stream,
+                            nullptr, nullptr, false, /*no_alloc=*/true);
 }
 
 extern "C" st_status st_attn_decode_dual_rope(void* out, float* lse, const void* q, const st_dual_cache* caches,
