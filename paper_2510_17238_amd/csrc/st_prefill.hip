@@ -662,6 +662,489 @@ __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_mfma_pipe_kernel
     }
 }
 
+
+// --------------------------------------------------------------------------
+// The attention kernel, second form.  Same tiles, same transposed products and the same two phases per key tile as
+// prefill_mfma_pipe_kernel above, with the instructions per matrix instruction cut down: one wave issues at most
+// one instruction every few cycles, and beside a v_mfma_f32_32x32x16_bf16 (32 cycles of the matrix pipe) about 3.5
+// plain vector instructions are free, every further one costs about 5 cycles, a ds_read_b128 about 4 and a
+// v_dot2_f32_bf16 about 18 -- it shares the matrix pipe (measured on this chip, one wave per SIMD).
+//   * The queries are multiplied by scale * log2(e) once, when they are loaded (and rounded to bf16 again), and
+//     the first matrix instruction of a score block starts from -m_ref instead of 0 (a block of 16 registers per
+//     head that holds -m_ref in every register): a score leaves the matrix pipe as the base-2 exponent of its
+//     probability relative to the row's reference exponent m_ref -- no multiply-add per element.
+//   * No running maximum.  m_ref is the row maximum of the FIRST tile (every row sees column 0 of its own stream,
+//     so it is finite); bf16 and fp32 have the same exponent range, so probabilities may grow far beyond 1 without
+//     any loss.  Only when a tile's row sum exceeds 2^kRiseLog2 (or is not finite) -- seen right after the
+//     probabilities of that tile were formed, before they are used -- the reference is moved, out of line: the
+//     tile's probabilities are formed again, the sum and the output accumulator are rescaled.
+//   * The first operand fragments of a phase are read from LDS in the slots of the phase before that need no
+//     fragment of their own any more (with three buffers the K tile is known to have landed one tile early), and
+//     the copies of the next tiles are issued behind the first matrix instructions instead of in front of them.
+//   * The score block that the other kernel computes past the last tile is not computed.
+// --------------------------------------------------------------------------
+constexpr float kRiseLog2 = 40.f;
+
+// NL wave-wide 16-byte copies global -> LDS, 1 KB apart on both sides: the instruction's immediate offset moves
+// the global address and the LDS address alike, so the LDS base goes into m0 once.
+template <int NL>
+__device__ __forceinline__ void async_copy_rows(const void* base, uint32_t lane_off, uint32_t lds_off) {
+    static_assert(NL == 2 || NL == 4, "tile sizes of head_dim 64 and 128");
+    if constexpr (NL == 4)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %0, %1 offset:2048\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072"
+                     ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024"
+                     ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory", "m0");
+}
+
+template <int D, int NH, bool ROPE>
+__global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_attn_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
+                                                                   const uint16_t* __restrict__ q,
+                                                                   const uint16_t* __restrict__ kc,
+                                                                   const uint16_t* __restrict__ vc, PlanView pv,
+                                                                   int n_q_heads, int n_kv_heads, float scale_log2,
+                                                                   const float2* __restrict__ rope_tab) {
+    constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
+    constexpr int TILE = kTileN * D;
+    constexpr int STAGES = NH == 2 ? 3 : 2;
+    constexpr bool EARLY_K = STAGES == 3;          // K(t + 2) has landed when tile t starts: its first fragments may be read a phase early
+    constexpr int PER = 16 / KS;                   // score elements of vector work per matrix instruction (both phases)
+    constexpr int kPF = 3;                         // operand fragments read ahead
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    PipeSmem<D, STAGES>& sm = *reinterpret_cast<PipeSmem<D, STAGES>*>(smem_raw);
+
+    const int n_sets = n_q_heads / NH;
+    const int rank = blockIdx.x / n_sets;
+    const int hh0 = blockIdx.x % n_sets;
+    const int group = n_q_heads / n_kv_heads;
+    const int hk = hh0 % n_kv_heads;                // consecutive workgroups -> consecutive KV heads
+    const int hq0 = hk * group + NH * (hh0 / n_kv_heads);
+    const WorkItem it = pv.sorted[rank];
+    if (it.n_rows == 0) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, hg = lane >> 5;
+    const int n_tiles = it.a_total + it.b_total;
+
+    constexpr int NL = TILE * 2 / 1024 / 4;         // 1 KB copies per wave per tile
+    // a copy instruction takes the tile's address from scalar registers and one 32-bit byte offset per lane
+    const uint16_t* kc_head = kc + size_t(hk) * pv.pack_tiles * TILE;
+    const uint16_t* vc_head = vc + size_t(hk) * pv.pack_tiles * TILE;
+    const uint32_t lane_off = uint32_t(wave) * (NL * 1024) + uint32_t(lane) * 16;
+    auto tile_of = [&](int ti) {
+        ti = min(ti, n_tiles - 1);                   // past the end: fetch the last tile again (never used)
+        return ti < it.a_total ? it.tile_a0 + ti : it.tile_b0 + (ti - it.a_total);
+    };
+    const uint32_t lds_k0 = uint32_t(uintptr_t(&sm.k[0][0])) + uint32_t(wave) * (NL * 1024);
+    const uint32_t lds_v0 = uint32_t(uintptr_t(&sm.vt[0][0])) + uint32_t(wave) * (NL * 1024);
+    auto issue_k = [&](int ti, int stage) { async_copy_rows<NL>(kc_head + size_t(tile_of(ti)) * TILE, lane_off, lds_k0 + stage * (TILE * 2)); };
+    auto issue_v = [&](int ti, int stage) { async_copy_rows<NL>(vc_head + size_t(tile_of(ti)) * TILE, lane_off, lds_v0 + stage * (TILE * 2)); };
+    // copy order (tile x lives in buffer x % STAGES):
+    //   three buffers: K0 V0 K1 K2 V1 | K3 V2 | K4 V3 | ...   K two tiles ahead, V^T one
+    //   two buffers:   K0 V0 K1       | V1 K2 | V2 K3 | ...   one tile ahead
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
+    if (STAGES == 3) {
+        issue_k(2, 2);
+        issue_v(1, 1);
+    }
+
+    const int row_in_tile = wave * 32 + n;
+    const bool active = row_in_tile < it.n_rows;
+    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
+    const int tok_q = pv.perm[it.a_base + my_row];
+    const int my_vis = pv.vis[it.a_base + my_row];
+
+    bf16x8 qf[NH][KS];
+    {
+        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq0) * D + 8 * hg;
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int j = 0; j < KS; ++j) qf[h][j] = *reinterpret_cast<const bf16x8*>(qp + h * D + 16 * j);
+    }
+    if (ROPE) {
+        const float2* trow = rope_tab + (size_t(it.tile_a0) * kTileN + my_row) * (D / 2) + 8 * hg;
+#pragma unroll
+        for (int j = 0; j < KS / 2; ++j) {
+            f32x4 cs4[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) cs4[w] = *reinterpret_cast<const f32x4*>(trow + 16 * j + 2 * w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float cs = cs4[e / 2][2 * (e % 2)], sn = cs4[e / 2][2 * (e % 2) + 1];
+#pragma unroll
+                for (int h = 0; h < NH; ++h) {
+                    const float x = float(qf[h][j][e]), y = float(qf[h][j + KS / 2][e]);
+                    qf[h][j][e] = (__bf16)(x * cs - y * sn);
+                    qf[h][j + KS / 2][e] = (__bf16)(y * cs + x * sn);
+                }
+            }
+        }
+    }
+    // scores in base-2 exponent units straight out of the matrix pipe
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int j = 0; j < KS; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[h][j][e] = (__bf16)(float(qf[h][j][e]) * scale_log2);
+
+    f32x16 o_acc[NH][DB];
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[h][db][i] = 0.f;
+    // Softmax state of a row, per head, in base-2 exponent units: m_ref is the reference exponent, l_run the sum of
+    // the probabilities 2^(s - m_ref) so far (this lane's half of the row).
+    float l_run[NH], m_ref[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        l_run[h] = 0.f;
+        m_ref[h] = 0.f;
+    }
+
+    int koff[KS], voff[4];
+    {
+        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
+    }
+    {
+        int t0 = my_vis, t1 = tok_q;
+        asm volatile("" : "+v"(t0), "+v"(t1));
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            u32x4 t = __builtin_bit_cast(u32x4, qf[h][j]);
+            asm volatile("" : "+v"(t));
+            qf[h][j] = __builtin_bit_cast(bf16x8, t);
+        }
+
+    // K fragment f of a tile: key block f % SB, k-step f / SB; V^T fragment f: d block f % DB, 16-key step f / DB
+    auto ld_k = [&](const uint16_t* kb, int f) { return *reinterpret_cast<const bf16x8*>(kb + 32 * (f % SB) * D + koff[f / SB]); };
+    auto ld_v = [&](const uint16_t* vb, int f) { return *reinterpret_cast<const bf16x8*>(vb + 32 * (f % DB) * kTileN + voff[f / DB]); };
+
+    struct TileInfo { bool partial; int limit; int c0; };
+    auto tile_info = [&](int ti) {
+        const bool in_a = ti < it.a_total;
+        const int kt = in_a ? ti : ti - it.a_total;
+        const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? it.n_stream : it.n_src);
+        return TileInfo{partial, in_a ? my_row + 1 : my_vis, kt * kTileN + 8 * hg};
+    };
+    auto max_with_partner = [&](float x) {
+        float a = x, b = x;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+        return fmaxf(a, b);
+    };
+    auto rescale_acc = [&](int h, float alpha) {
+        if constexpr (NH == 2) {
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float x = o_acc[h][db][i], tmp;
+                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                                 : "+a"(x), "=&v"(tmp) : "v"(alpha));
+                    o_acc[h][db][i] = x;
+                }
+            asm volatile("s_nop 7" ::: "memory");
+        } else {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o_acc[h][db][i] *= alpha;
+        }
+    };
+    // the columns of a partial tile that a row may not see: exponent -inf, probability 0
+    // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
+    auto mask_tile = [&](f32x16 (&sv)[NH][SB], const TileInfo& ti) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int col = ti.c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
+                    sv[h][sb][i] = col < ti.limit ? sv[h][sb][i] : -INFINITY;
+                }
+    };
+    // row maximum (both lanes of the row) of a tile's exponents
+    auto row_max = [&](const f32x16 (&blk)[SB]) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, blk[sb][i]);
+        return max_with_partner(mx);
+    };
+
+    // ---- prologue: tile 0 gives every row its reference exponent ----
+    // sv: the exponents of the tile whose probabilities are formed next (vector registers); s_next: the score blocks
+    // the matrix pipe is filling.  Between two tiles the LAST block of s_next holds -m_ref in all its 16 registers:
+    // the first matrix instruction of every score block starts from it (the last block in place), so a score leaves
+    // the pipe as s - m_ref.
+    f32x16 sv[NH][SB], s_next[NH][SB];
+    wait_vmcnt<(STAGES == 3 ? 4 : 2) * NL>();            // K0 has landed
+    __syncthreads();
+    {
+        const uint16_t* kb = &sm.k[0][0];
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int f = 0; f < SB * KS; ++f) {
+            const bf16x8 a = ld_k(kb, f);
+#pragma unroll
+            for (int h = 0; h < NH; ++h)
+                sv[h][f % SB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[h][f / SB], f / SB == 0 ? zero16 : sv[h][f % SB], 0, 0, 0);
+        }
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float x = sv[h][sb][i];
+                    asm volatile("" : "+v"(x));                   // in vector registers from here on
+                    sv[h][sb][i] = x;
+                }
+        const TileInfo t0 = tile_info(0);
+        if (t0.partial) mask_tile(sv, t0);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            m_ref[h] = row_max(sv[h]);                            // finite: column 0 is visible to every row
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sv[h][sb][i] -= m_ref[h];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s_next[h][SB - 1][i] = -m_ref[h];
+        }
+    }
+
+    bf16x8 pb[NH][SB][2];                                // probabilities of the current tile, as the second product's operand
+    float psum[NH];
+    // slot m of NH SB KS: PER elements of the probabilities of the tile in sv, in the order (head, block, register)
+    auto exp_slot = [&](int m) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int e = m * PER + u;
+            const int hh = e / (SB * 16), sb2 = (e / 16) % SB, i = e % 16;
+            const float pr = __builtin_amdgcn_exp2f(sv[hh][sb2][i]);
+            psum[hh] += pr;
+            pb[hh][sb2][i >> 3][i & 7] = (__bf16)pr;
+        }
+    };
+    // A row sum beyond 2^kRiseLog2 (or not finite) means the tile's exponents outgrew the reference: move it to the
+    // tile's row maximum, form the tile's probabilities again, rescale what has been accumulated.  Scores already in
+    // flight relative to the old reference still have `late` to lose when they arrive.
+    float late[NH];
+    auto check_rise = [&]() {
+        bool trig = false;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            asm volatile("" : "+v"(psum[h]));
+            late[h] = 0.f;
+            trig = trig || !(psum[h] <= __builtin_exp2f(kRiseLog2));
+        }
+        const bool any = __any(trig);
+        if (any) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const float rise = row_max(sv[h]);
+                const float shift = rise > 0.f ? rise : 0.f;           // (-inf: the row sees nothing in this tile)
+                const float alpha = __builtin_amdgcn_exp2f(-shift);
+                late[h] = shift;
+                psum[h] = 0.f;
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float pr = __builtin_amdgcn_exp2f(sv[h][sb][i] - shift);
+                        psum[h] += pr;
+                        pb[h][sb][i >> 3][i & 7] = (__bf16)pr;
+                    }
+                l_run[h] *= alpha;
+                rescale_acc(h, alpha);
+                m_ref[h] += shift;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < NH; ++h) l_run[h] += psum[h];
+        return any;
+    };
+
+    int stage = 0;                                       // buffer of tile ti
+    bf16x8 kpre[kPF], vpre[kPF];                         // first fragments of a phase, read during the phase before
+    // every tile but the last: the loop body has no branch around its matrix instructions
+    for (int ti = 0; ti + 1 < n_tiles; ++ti) {
+        // three buffers: K(ti+2) and V^T(ti) have landed (V^T(ti+1) is in flight behind them); two: K(ti+1), V^T(ti);
+        // everybody is done with K(ti) and V^T(ti-1), whose buffers the next copies go to
+        wait_vmcnt<(STAGES == 3 ? 1 : 0) * NL>();
+        __syncthreads();
+        const int stage1 = stage == STAGES - 1 ? 0 : stage + 1;
+        const int stage2 = stage1 == STAGES - 1 ? 0 : stage1 + 1;
+        const uint16_t* copy_k = kc_head + size_t(tile_of(ti + (STAGES == 3 ? 3 : 2))) * TILE;
+        const uint16_t* copy_v = vc_head + size_t(tile_of(ti + (STAGES == 3 ? 2 : 1))) * TILE;
+        const uint32_t copy_k_lds = lds_k0 + stage * (TILE * 2);
+        const uint32_t copy_v_lds = lds_v0 + (STAGES == 3 ? (stage == 0 ? 2 : stage - 1) : stage1) * (TILE * 2);
+        const uint16_t* kb = &sm.k[0][0] + stage1 * TILE;
+        const uint16_t* vb = &sm.vt[0][0] + stage * TILE;
+        const uint16_t* kb2 = &sm.k[0][0] + stage2 * TILE;        // K(ti+2): the tile of the next round's phase X
+        if (!EARLY_K || ti == 0) {
+#pragma unroll
+            for (int f = 0; f < kPF; ++f) kpre[f] = ld_k(kb, f);
+        }
+
+        // ---- phase X: scores of tile ti+1  |  probabilities of tile ti ----
+#pragma unroll
+        for (int h = 0; h < NH; ++h) psum[h] = 0.f;
+        {
+            constexpr int NF = SB * KS;
+            bf16x8 a[NF];
+#pragma unroll
+            for (int f = 0; f < kPF; ++f) a[f] = kpre[f];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                if (f + kPF < NF) a[f + kPF] = ld_k(kb, f + kPF);
+                else vpre[f + kPF - NF] = ld_v(vb, f + kPF - NF);     // the first V^T fragments of phase Y
+                const int sb = f % SB, j = f / SB;
+#pragma unroll
+                for (int h = 0; h < NH; ++h) {
+                    // k-step 0 starts from -m_ref, parked in the last block (which starts in place)
+                    s_next[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[h][j], j == 0 ? s_next[h][SB - 1] : s_next[h][sb], 0, 0, 0);
+                    // the copies of this round go out behind the first matrix instructions
+                    if (f * NH + h == 0) {
+                        if (STAGES == 3) async_copy_rows<NL>(copy_k, lane_off, copy_k_lds);
+                        else async_copy_rows<NL>(copy_v, lane_off, copy_v_lds);
+                    }
+                    if (f * NH + h == 1) {
+                        if (STAGES == 3) async_copy_rows<NL>(copy_v, lane_off, copy_v_lds);
+                        else async_copy_rows<NL>(copy_k, lane_off, copy_k_lds);
+                    }
+                    exp_slot(f * NH + h);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        const bool moved = check_rise();
+
+        // ---- phase Y: O^T += V^T P^T of tile ti  |  the exponents of tile ti+1 leave the accumulation registers ----
+        // slot m of NH DB SB 2: PER fresh exponents, in the order (block, head, register); the last block is left
+        // holding -m_ref for the next round
+        float neg[NH];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) neg[h] = -m_ref[h];
+        auto move_slot = [&](int m) {
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int e = m * PER + u;
+                const int sb2 = e / (NH * 16), hh = (e / 16) % NH, i = e % 16;
+                // ONE move out of the accumulation registers, HERE (a plain copy would be sunk to its use, into
+                // the crowded phase X); the producing matrix instruction retired at least three of them ago
+                float x;
+                if constexpr (NH == 2) {
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(s_next[hh][sb2][i]));
+                } else {
+                    x = s_next[hh][sb2][i];
+                    asm volatile("" : "+v"(x));
+                }
+                sv[hh][sb2][i] = x;
+                if (sb2 == SB - 1) {
+                    if constexpr (NH == 2) {
+                        float t;
+                        asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(t) : "v"(neg[hh]));
+                        s_next[hh][sb2][i] = t;
+                    } else {
+                        s_next[hh][sb2][i] = neg[hh];
+                    }
+                }
+            }
+        };
+        {
+            constexpr int NF = DB * SB * 2;
+            bf16x8 a[NF];
+#pragma unroll
+            for (int f = 0; f < kPF; ++f) a[f] = vpre[f];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                if (f + kPF < NF) a[f + kPF] = ld_v(vb, f + kPF);
+                else if (EARLY_K) kpre[f + kPF - NF] = ld_k(kb2, f + kPF - NF);   // the first K fragments of the next round
+                const int db = f % DB, st = f / DB;              // keys 16 st .. 16 st + 15
+#pragma unroll
+                for (int h = 0; h < NH; ++h) {
+                    o_acc[h][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[h][st >> 1][st & 1], o_acc[h][db], 0, 0, 0);
+                    move_slot(f * NH + h);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        if (moved) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h)
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sv[h][sb][i] -= late[h];
+        }
+        const TileInfo fresh = tile_info(ti + 1);
+        if (fresh.partial) mask_tile(sv, fresh);
+        stage = stage1;
+    }
+    // ---- the last tile: its probabilities and the second product, no scores behind it ----
+    {
+        wait_vmcnt<0>();                                 // (also: no copy into LDS may outlive the workgroup)
+        __syncthreads();
+        const uint16_t* vb = &sm.vt[0][0] + stage * TILE;
+        constexpr int NF = DB * SB * 2;
+        bf16x8 a[NF];
+#pragma unroll
+        for (int f = 0; f < kPF; ++f) a[f] = ld_v(vb, f);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) psum[h] = 0.f;
+#pragma unroll
+        for (int m = 0; m < NH * SB * KS; ++m) exp_slot(m);
+        check_rise();
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            if (f + kPF < NF) a[f + kPF] = ld_v(vb, f + kPF);
+            const int db = f % DB, st = f / DB;
+#pragma unroll
+            for (int h = 0; h < NH; ++h)
+                o_acc[h][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[h][st >> 1][st & 1], o_acc[h][db], 0, 0, 0);
+        }
+    }
+
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        const float l_tot = l_run[h] + __shfl_xor(l_run[h], 32);   // wave-wide exchange: inactive rows take part
+        if (!active) continue;
+        const float inv = 1.f / l_tot;
+        uint16_t* op = out + (int64_t(tok_q) * n_q_heads + hq0 + h) * D;
+        // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o4[c] = (__bf16)(o_acc[h][db][4 * q4 + c] * inv);
+                *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * hg) = o4;
+            }
+        if (lse && hg == 0) lse[int64_t(tok_q) * n_q_heads + hq0 + h] = (m_ref[h] + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    }
+}
+
 }  // namespace st
 
 using namespace st;
@@ -766,10 +1249,11 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
             constexpr int NH = decltype(nh_tag)::value;
             constexpr bool ROPE = decltype(rope_tag)::value;
             const size_t smem = sizeof(PipeSmem<HD, NH == 2 ? 3 : 2>);
-            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_pipe_kernel<HD, NH, ROPE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            static const bool old_kernel = getenv("ST_PREFILL_OLD") != nullptr;
+            auto* kern = old_kernel ? &prefill_mfma_pipe_kernel<HD, NH, ROPE> : &prefill_attn_kernel<HD, NH, ROPE>;
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfPrefillAttn, s);
-            hipLaunchKernelGGL((prefill_mfma_pipe_kernel<HD, NH, ROPE>), dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
+            hipLaunchKernelGGL(kern, dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
                                lse, (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2, (const float2*)tab);
             prof_end(kProfPrefillAttn, s);
             return ST_OK;

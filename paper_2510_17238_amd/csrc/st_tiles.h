@@ -23,6 +23,10 @@ __device__ __forceinline__ void async_copy16(const void* g, uint32_t lds_off) {
 __device__ __forceinline__ void async_copy16_nt(const void* g, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(g), "s"(lds_off) : "memory", "m0");
 }
+// the same with the address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit byte offset per lane
+__device__ __forceinline__ void async_copy16_s(const void* base, uint32_t lane_off, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
