@@ -62,15 +62,6 @@ const char* st_last_error(void);
 /* Library version (major * 100 + minor). */
 int32_t st_version(void);
 
-/* Which bf16 attention kernel st_attn_prefill launches: ST_PREFILL_AUTO (default) chooses by problem
- * size, ST_PREFILL_ONE_HEAD keeps one query head per workgroup, ST_PREFILL_TWO_HEADS serves two
- * query heads of one KV head per workgroup wherever n_q_heads / n_kv_heads is even (otherwise it
- * falls back to one head).  Results agree within rounding.  Process-wide; the environment variable
- * ST_PREFILL_VARIANT (1 or 2) sets the initial value.  Returns the previous setting; values other
- * than the three below leave the setting unchanged. */
-enum { ST_PREFILL_AUTO = 0, ST_PREFILL_ONE_HEAD = 1, ST_PREFILL_TWO_HEADS = 2 };
-int32_t st_prefill_variant_set(int32_t variant);
-
 /* Optional kernel timing for benchmarks.  While enabled, st_attn_prefill brackets its attention
  * kernel (ST_PROF_PREFILL_ATTN), st_attn_decode_dual its split kernel (ST_PROF_DECODE_SPLIT) and
  * the bf16 st_attn_prefill_bwd its two attention kernels (ST_PROF_BWD_DQ, ST_PROF_BWD_DKV)
@@ -167,6 +158,14 @@ st_status st_plan_create(st_plan** plan,
  * the process is being captured into a graph (that would invalidate the capture). */
 void st_plan_destroy(st_plan* plan);
 
+/* How many query heads of one KV head a workgroup of the bf16 attention kernel serves when
+ * st_attn_prefill / st_attn_prefill_rope run with this plan (the backward is not affected):
+ * 0 (default) chooses by problem size -- two for sequences of 8K tokens and more on average, else
+ * one --, 1 keeps one head per workgroup, 2 serves two wherever n_q_heads / n_kv_heads is even
+ * (otherwise one).  Results agree within rounding.  A property of the plan object: set it before
+ * the calls that use the plan; other values give ST_ERR_INVALID_ARG. */
+st_status st_plan_heads_per_workgroup(st_plan* plan, int32_t heads);
+
 /* Query tile size (rows of a query tile, columns of a key tile). */
 st_status st_plan_tile_shape(const st_plan* plan, int32_t* tile_m, int32_t* tile_n);
 
@@ -201,8 +200,11 @@ st_status st_plan_tile_classes(const st_plan* plan, int32_t seq, int32_t block,
  *   k, v   : [n_tokens, n_kv_heads, head_dim]
  *   lse    : fp32 [n_tokens, n_q_heads] natural-log softmax denominator, or NULL
  * Key tiles that the plan marks SKIP are never read.  bf16: MFMA products with
- * fp32 accumulation and fp32 softmax state, probabilities rounded to bf16 before
- * the second product.  f32: plain fp32 arithmetic.
+ * fp32 accumulation and fp32 softmax state; the queries carry the softmax scale
+ * (q * scale * log2(e), rounded to bf16 once more: a perturbation of q of at most
+ * half a bf16 unit in the last place, the size of its own quantisation), the
+ * probabilities are rounded to bf16 before the second product.  f32: plain fp32
+ * arithmetic.
  *
  * workspace (bf16 only): at least st_prefill_workspace_bytes(...) bytes, 256-byte
  * aligned; holds K and V^T regrouped into contiguous key tiles for the duration of

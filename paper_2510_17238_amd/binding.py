@@ -78,8 +78,8 @@ def load_library():
     lib.st_last_error.argtypes = []
     lib.st_version.restype = i32
     lib.st_version.argtypes = []
-    lib.st_prefill_variant_set.restype = i32
-    lib.st_prefill_variant_set.argtypes = [i32]
+    lib.st_plan_heads_per_workgroup.restype = i32
+    lib.st_plan_heads_per_workgroup.argtypes = [vp, i32]
     lib.st_probe_paged_read.restype = i32
     lib.st_probe_paged_read.argtypes = [vp, sz, i32, i32, vp, vp]
     lib.st_probe_mfma_bf16.restype = i32
@@ -195,14 +195,6 @@ def st_last_error():
 ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT, ST_PROF_BWD_DQ, ST_PROF_BWD_DKV = 0, 1, 2, 3
 
 
-ST_PREFILL_AUTO, ST_PREFILL_ONE_HEAD, ST_PREFILL_TWO_HEADS = 0, 1, 2
-
-
-def st_prefill_variant_set(variant):
-    """Select the bf16 prefill attention kernel; returns the previous setting."""
-    return int(load_library().st_prefill_variant_set(int(variant)))
-
-
 def st_probe_paged_read(pool, n_waves, steps_per_wave, sink, stream=None):
     """pool: uint8 device tensor whose size is a power of two; sink: uint32-sized device tensor."""
     _check(load_library().st_probe_paged_read(_ptr(pool), pool.numel() * pool.element_size(), int(n_waves), int(steps_per_wave),
@@ -279,6 +271,11 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+    def heads_per_workgroup(self, heads):
+        """0 = by problem size, 1 or 2 query heads of a KV head per workgroup of the bf16 attention kernel."""
+        _check(load_library().st_plan_heads_per_workgroup(self.handle, int(heads)))
+        return self
 
     def tile_shape(self):
         m, n = C.c_int32(), C.c_int32()

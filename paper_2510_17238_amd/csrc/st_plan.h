@@ -59,6 +59,7 @@ struct st_plan {
     int32_t batch = 0;
     int64_t n_tokens = 0;
     int32_t m_max = 0;
+    int32_t heads_per_workgroup = 0;   // bf16 attention kernel: 0 = chosen by problem size, 1, 2 (st_plan_heads_per_workgroup)
     std::vector<int32_t> cu_host, slot_base_host, pack_base_host;
     int32_t pack_tiles = 0;
     void* ws = nullptr;

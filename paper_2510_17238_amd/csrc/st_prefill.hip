@@ -14,29 +14,24 @@
 //                         64-row key tile (stream-compact order) into contiguous 16 KB blocks, so
 //                         that the attention kernel streams tiles with plain linear loads and needs
 //                         no per-row token lookup and no transpose in its inner loop.
-//   prefill_mfma_pipe_kernel<D, NH, ROPE>
+//   prefill_attn_kernel<D, NH, ROPE>
 //                         bf16, 4 waves x 32 query rows x NH query heads (1 or 2) of one KV head; K and V^T
 //                         tiles copied asynchronously into swizzled LDS buffers; QK^T and PV on
 //                         v_mfma_f32_32x32x16_bf16, fp32 softmax state.  Both products are computed
-//                         TRANSPOSED (S^T = K Q^T, O^T = V^T P^T): a lane then owns one query row, so the
-//                         row max / row sum are in-register reductions plus one exchange with lane^32,
-//                         and the S^T accumulators are already laid out as the B operand of the second
-//                         product.  The loop is software-pipelined by hand (see the kernel).
+//                         TRANSPOSED (S^T = K Q^T, O^T = V^T P^T): a lane then owns one query row, so a
+//                         row sum is an in-register reduction plus one exchange with lane^32, and the S^T
+//                         accumulators are already laid out as the B operand of the second product.  The
+//                         loop is software-pipelined by hand (see the kernel).
 //   rope_table_kernel, tile_pack_rope_kernel
 //                         the fused rotation of st_attn_prefill_rope: (cos, sin) of every token once, keys rotated
 //                         on their way into the key tiles; the attention kernel's ROPE form rotates its query rows.
 //   prefill_simple_kernel any dtype, one thread per query row, plain fp32 arithmetic.  It is
 //                         the fp32 path (tolerance 1e-4) and walks the same work items.
-#include <stdlib.h>
-
-#include <atomic>
 #include <type_traits>
 
 #include "st_tiles.h"
 
 namespace st {
-
-constexpr float kLazyMax = 8.f;                   // exponent units a tile maximum may exceed the running one
 
 struct ItemGeom {
     int S;           // source tokens
@@ -274,405 +269,29 @@ struct PipeSmem {
     uint16_t k[STAGES][kTileN * D];
     uint16_t vt[STAGES][D * kTileN];
 };
-template <int D, int NH, bool ROPE>
-__global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_mfma_pipe_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
-                                                                   const uint16_t* __restrict__ q,
-                                                                   const uint16_t* __restrict__ kc,
-                                                                   const uint16_t* __restrict__ vc, PlanView pv,
-                                                                   int n_q_heads, int n_kv_heads, float scale_log2,
-                                                                   const float2* __restrict__ rope_tab) {
-    constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
-    constexpr int TILE = kTileN * D;              // elements of one K or V^T tile
-    constexpr int STAGES = NH == 2 ? 3 : 2;       // K / V^T buffers: the one-head form must fit two workgroups per CU
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    PipeSmem<D, STAGES>& sm = *reinterpret_cast<PipeSmem<D, STAGES>*>(smem_raw);
-
-    const int n_sets = n_q_heads / NH;
-    const int rank = blockIdx.x / n_sets;
-    const int hh = blockIdx.x % n_sets;
-    const int group = n_q_heads / n_kv_heads;
-    const int hk = hh % n_kv_heads;                 // consecutive workgroups -> consecutive KV heads
-    const int hq0 = hk * group + NH * (hh / n_kv_heads);
-    const WorkItem it = pv.sorted[rank];
-    if (it.n_rows == 0) return;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int n = lane & 31, hg = lane >> 5;
-    const int n_tiles = it.a_total + it.b_total;
-
-    constexpr int NL = TILE * 2 / 1024 / 4;         // 1 KB copies per wave per tile
-    const int tile_a0 = it.tile_a0, tile_b0 = it.tile_b0;
-    const size_t head_off = size_t(hk) * pv.pack_tiles * TILE + (wave * NL) * 512 + lane * 8;
-    const uint16_t* kc_lane = kc + head_off;
-    const uint16_t* vc_lane = vc + head_off;
-    auto tile_of = [&](int ti) {
-        ti = min(ti, n_tiles - 1);                   // past the end: fetch the last tile again (never used)
-        return ti < it.a_total ? tile_a0 + ti : tile_b0 + (ti - it.a_total);
-    };
-    const uint32_t lds_k0 = uint32_t(uintptr_t(&sm.k[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
-    const uint32_t lds_v0 = uint32_t(uintptr_t(&sm.vt[0][0])) + uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
-    auto issue_k = [&](int ti, int stage) {
-        const uint16_t* src = kc_lane + size_t(tile_of(ti)) * TILE;
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_k0 + stage * (TILE * 2) + u * 1024);
-    };
-    auto issue_v = [&](int ti, int stage) {
-        const uint16_t* src = vc_lane + size_t(tile_of(ti)) * TILE;
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(src + u * 512, lds_v0 + stage * (TILE * 2) + u * 1024);
-    };
-    // copy order (tile x lives in buffer x % STAGES):
-    //   three buffers: K0 V0 K1 V1 K2 | V2 K3 | V3 K4 | ...  two tiles ahead
-    //   two buffers:   K0 V0 K1       | V1 K2 | V2 K3 | ...  one tile ahead
-    issue_k(0, 0);
-    issue_v(0, 0);
-    issue_k(1, 1);
-    if (STAGES == 3) {
-        issue_v(1, 1);
-        issue_k(2, 2);
-    }
-
-    const int row_in_tile = wave * 32 + n;
-    const bool active = row_in_tile < it.n_rows;
-    const int my_row = it.row0 + min(row_in_tile, it.n_rows - 1);
-    const int tok_q = pv.perm[it.a_base + my_row];
-    const int my_vis = pv.vis[it.a_base + my_row];
-
-    bf16x8 qf[NH][KS];
-    {
-        const uint16_t* qp = q + (int64_t(tok_q) * n_q_heads + hq0) * D + 8 * hg;
-#pragma unroll
-        for (int h = 0; h < NH; ++h)
-#pragma unroll
-            for (int j = 0; j < KS; ++j) qf[h][j] = *reinterpret_cast<const bf16x8*>(qp + h * D + 16 * j);
-    }
-    if (ROPE) {
-        // UNROTATED queries: the row's (cos, sin) pairs were left by rope_table_kernel at the row's place among
-        // the packed tiles of its own stream; fragments j and j + KS/2 hold the two halves of eight rotation pairs
-        const float2* trow = rope_tab + (size_t(it.tile_a0) * kTileN + my_row) * (D / 2) + 8 * hg;
-#pragma unroll
-        for (int j = 0; j < KS / 2; ++j) {
-            f32x4 cs4[4];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) cs4[w] = *reinterpret_cast<const f32x4*>(trow + 16 * j + 2 * w);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float cs = cs4[e / 2][2 * (e % 2)], sn = cs4[e / 2][2 * (e % 2) + 1];
-#pragma unroll
-                for (int h = 0; h < NH; ++h) {
-                    const float x = float(qf[h][j][e]), y = float(qf[h][j + KS / 2][e]);
-                    qf[h][j][e] = (__bf16)(x * cs - y * sn);
-                    qf[h][j + KS / 2][e] = (__bf16)(y * cs + x * sn);
-                }
-            }
-        }
-    }
-
-    f32x16 o_acc[NH][DB];
-#pragma unroll
-    for (int h = 0; h < NH; ++h)
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o_acc[h][db][i] = 0.f;
-    float m_run[NH], l_run[NH], m_ref[NH];
-#pragma unroll
-    for (int h = 0; h < NH; ++h) {
-        m_run[h] = -INFINITY;
-        l_run[h] = 0.f;
-        m_ref[h] = 0.f;
-    }
-
-    int koff[KS], voff[4];
-    {
-        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
-    }
-    {
-        int t0 = my_vis, t1 = tok_q;
-        asm volatile("" : "+v"(t0), "+v"(t1));
-    }
-#pragma unroll
-    for (int h = 0; h < NH; ++h)
-#pragma unroll
-        for (int j = 0; j < KS; ++j) {
-            u32x4 t = __builtin_bit_cast(u32x4, qf[h][j]);
-            asm volatile("" : "+v"(t));
-            qf[h][j] = __builtin_bit_cast(bf16x8, t);
-        }
-
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-    // scores of the tile in buffer `stage`, both heads: every K fragment feeds two MFMAs
-    auto scores = [&](f32x16 (&s)[NH][SB], int stage) {
-        const uint16_t* kb = &sm.k[0][0] + stage * TILE;
-#pragma unroll
-        for (int f = 0; f < SB * KS; ++f) {
-            const int sb = f % SB, j = f / SB;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(kb + 32 * sb * D + koff[j]);
-#pragma unroll
-            for (int h = 0; h < NH; ++h)
-                s[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[h][j], j == 0 ? zero16 : s[h][sb], 0, 0, 0);
-        }
-    };
-    // tile parameters
-    struct TileInfo { bool partial; int limit; int c0; };
-    auto tile_info = [&](int ti) {
-        ti = min(ti, n_tiles - 1);
-        const bool in_a = ti < it.a_total;
-        const int kt = in_a ? ti : ti - it.a_total;
-        const bool partial = kt >= (in_a ? it.a_full : it.b_full) || (kt + 1) * kTileN > (in_a ? it.n_stream : it.n_src);
-        return TileInfo{partial, in_a ? my_row + 1 : my_vis, kt * kTileN + 8 * hg};
-    };
-    // Softmax state of a row, per head, in base-2 exponent units: m_run is the reference maximum
-    // (-inf until the row has seen a finite score), m_ref the finite value actually subtracted
-    // (0 while m_run is -inf).  Scores are turned into exponents t = s * scale - m_ref the moment
-    // they leave the accumulation registers, i.e. BEFORE the maximum of their tile is known; in the
-    // common case the tile maximum stays within kLazyMax of the reference and t is final.
-    // Otherwise (first tile of a row, or a real jump of the maximum) settle() moves the reference
-    // and repairs t, l and the output accumulator, out of line.
-    // value of lane ^ 32 (v_permlane32_swap exchanges the upper half of its first operand with the
-    // lower half of its second one; with both set to x, each lane finds its partner's x in one of them)
-    auto max_with_partner = [&](float x) {
-        float a = x, b = x;
-        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-        return fmaxf(a, b);
-    };
-    auto rescale_acc = [&](int h, float alpha) {
-        // The accumulators live in accumulation registers, which the vector ALU cannot multiply in
-        // place: each element goes through a temporary by hand, so that nothing here asks for the
-        // accumulators in ordinary vector registers (the register allocator would then shuttle all
-        // 128 of them back and forth in every iteration).  The idle cycles in front let the last
-        // matrix instructions retire before their results are read, the ones behind separate the
-        // last write from the next matrix instruction.
-        // (The one-head form fits the ordinary vector registers and multiplies there.)
-        if constexpr (NH == 2) {
-            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float x = o_acc[h][db][i], tmp;
-                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
-                                 : "+a"(x), "=&v"(tmp) : "v"(alpha));
-                    o_acc[h][db][i] = x;
-                }
-            asm volatile("s_nop 7" ::: "memory");
-        } else {
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o_acc[h][db][i] *= alpha;
-        }
-    };
-    // sv holds the exponents of a fresh tile relative to m_ref, mx their per-lane maximum
-    auto settle = [&](f32x16 (&sv)[NH][SB], float (&mx)[NH], const TileInfo& ti) {
-        if (ti.partial) {
-            // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
-#pragma unroll
-            for (int h = 0; h < NH; ++h) {
-                mx[h] = -INFINITY;
-#pragma unroll
-                for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int col = ti.c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
-                        sv[h][sb][i] = col < ti.limit ? sv[h][sb][i] : -INFINITY;
-                        mx[h] = fmaxf(mx[h], sv[h][sb][i]);
-                    }
-            }
-        }
-        float rise[NH];
-        bool g[NH], any_g = false;
-#pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            rise[h] = max_with_partner(mx[h]);                   // tile maximum of the row, relative to m_ref
-            g[h] = m_run[h] == -INFINITY ? rise[h] > -INFINITY : rise[h] > kLazyMax;
-            any_g = any_g || g[h];
-        }
-        if (__any(any_g)) {
-#pragma unroll
-            for (int h = 0; h < NH; ++h) {
-                const float shift = g[h] ? rise[h] : 0.f;        // rows that stay put: shift 0, alpha 1
-                const float m_new = m_ref[h] + shift;
-                const float alpha = g[h] ? __builtin_amdgcn_exp2f(m_run[h] - m_new) : 1.f;
-#pragma unroll
-                for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sv[h][sb][i] -= shift;
-                l_run[h] *= alpha;
-                rescale_acc(h, alpha);
-                m_run[h] = g[h] ? m_new : m_run[h];
-                m_ref[h] = g[h] ? m_new : m_ref[h];
-            }
-        }
-    };
-
-    // ---- prologue: exponents and row maximum of tile 0 ----
-    f32x16 sv[NH][SB];
-    wait_vmcnt<(STAGES == 3 ? 4 : 2) * NL>();            // K0 has landed
-    __syncthreads();
-    scores(sv, 0);
-    {
-        float mx[NH];
-#pragma unroll
-        for (int h = 0; h < NH; ++h) mx[h] = -INFINITY;
-#pragma unroll
-        for (int h = 0; h < NH; ++h)
-#pragma unroll
-            for (int sb = 0; sb < SB; ++sb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float x = sv[h][sb][i];
-                    asm volatile("" : "+v"(x));                   // in vector registers from here on
-                    x *= scale_log2;
-                    sv[h][sb][i] = x;
-                    mx[h] = fmaxf(mx[h], x);
-                }
-        settle(sv, mx, tile_info(0));
-    }
-
-    int stage = 0;                                       // buffer of tile ti
-    for (int ti = 0; ti < n_tiles; ++ti) {
-        // K(ti+1) and V^T(ti) have landed (with three buffers V^T(ti+1), K(ti+2) are in flight behind them);
-        // everybody is done with K(ti) and V^T(ti-1), whose buffers the next two copies go to
-        wait_vmcnt<(STAGES == 3 ? 2 : 0) * NL>();
-        __syncthreads();
-        const int stage1 = stage == STAGES - 1 ? 0 : stage + 1;
-        if (STAGES == 3) {
-            issue_v(ti + 2, stage == 0 ? 2 : stage - 1);
-            issue_k(ti + 3, stage);
-        } else {
-            issue_v(ti + 1, stage1);
-            issue_k(ti + 2, stage);
-        }
-
-        // The two phases below are written in the exact instruction order wanted -- per matrix
-        // instruction one small piece of vector work, LDS operand reads kPF fragments ahead -- and
-        // every piece ends in a scheduling barrier so that the compiler keeps that order.
-        // ---- phase X: scores of tile ti+1  |  probabilities of tile ti ----
-        constexpr int kPF = 3;
-        f32x16 s_next[NH][SB];
-        bf16x8 pb[NH][SB][2];
-        float psum[NH];
-#pragma unroll
-        for (int h = 0; h < NH; ++h) psum[h] = 0.f;
-        {
-            constexpr int NF = SB * KS;                          // fragment f: key block f % SB, k-step f / SB
-            const uint16_t* kb = &sm.k[0][0] + stage1 * TILE;
-            bf16x8 a[NF];
-#pragma unroll
-            for (int f = 0; f < kPF; ++f) a[f] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f % SB) * D + koff[f / SB]);
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                if (f + kPF < NF) {
-                    const int f2 = f + kPF;
-                    a[f2] = *reinterpret_cast<const bf16x8*>(kb + 32 * (f2 % SB) * D + koff[f2 / SB]);
-                }
-                const int sb = f % SB, j = f / SB;
-#pragma unroll
-                for (int h = 0; h < NH; ++h) {
-                    s_next[h][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], qf[h][j], j == 0 ? zero16 : s_next[h][sb], 0, 0, 0);
-                    // slot NH f + h of NH NF: its share of the probabilities of tile ti
-                    constexpr int PER = 16 * SB / NF;            // elements per slot (one head has 16 SB of them, in NF slots)
-                    const int slot = NH * f + h;
-                    const int hh = slot / NF, e0 = (slot % NF) * PER;
-#pragma unroll
-                    for (int e = e0; e < e0 + PER; ++e) {
-                        const int sb2 = e / 16, i = e % 16;
-                        const float pr = __builtin_amdgcn_exp2f(sv[hh][sb2][i]);
-                        psum[hh] += pr;
-                        pb[hh][sb2][i >> 3][i & 7] = (__bf16)pr;
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
-        // (the sums are wanted HERE: left alone, the optimiser defers them past the second phase and
-        //  recomputes the exponentials they are made of)
-#pragma unroll
-        for (int h = 0; h < NH; ++h) asm volatile("" : "+v"(psum[h]));
-#pragma unroll
-        for (int h = 0; h < NH; ++h) l_run[h] += psum[h];
-
-        // ---- phase Y: O^T += V^T P^T of tile ti  |  row maximum of tile ti+1 ----
-        float mx[NH];
-#pragma unroll
-        for (int h = 0; h < NH; ++h) mx[h] = -INFINITY;
-        {
-            constexpr int NF = DB * SB * 2;                      // fragment f: d block f % DB, 16-key step f / DB
-            const uint16_t* vb = &sm.vt[0][0] + stage * TILE;
-            bf16x8 a[NF];
-#pragma unroll
-            for (int f = 0; f < kPF; ++f) a[f] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f % DB) * kTileN + voff[f / DB]);
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                if (f + kPF < NF) {
-                    const int f2 = f + kPF;
-                    a[f2] = *reinterpret_cast<const bf16x8*>(vb + 32 * (f2 % DB) * kTileN + voff[f2 / DB]);
-                }
-                const int db = f % DB, st = f / DB;              // keys 16 st .. 16 st + 15
-#pragma unroll
-                for (int h = 0; h < NH; ++h) {
-                    o_acc[h][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], pb[h][st >> 1][st & 1], o_acc[h][db], 0, 0, 0);
-                    constexpr int PER = 16 * SB / NF;
-                    const int slot = NH * f + h;
-                    const int hh = slot / NF, e0 = (slot % NF) * PER;
-#pragma unroll
-                    for (int e = e0; e < e0 + PER; ++e) {
-                        const int sb2 = e / 16, i = e % 16;
-                        float x = s_next[hh][sb2][i];
-                        asm volatile("" : "+v"(x));               // ONE move out of the accumulation registers
-                        x = fmaf(x, scale_log2, -m_ref[hh]);
-                        sv[hh][sb2][i] = x;
-                        mx[hh] = fmaxf(mx[hh], x);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
-#pragma unroll
-        for (int h = 0; h < NH; ++h) asm volatile("" : "+v"(mx[h]));   // computed above, not in a later block
-        settle(sv, mx, tile_info(ti + 1));
-        stage = stage1;
-    }
-    wait_vmcnt<0>();                                     // no copy into LDS may outlive the workgroup
-
-#pragma unroll
-    for (int h = 0; h < NH; ++h) {
-        const float l_tot = l_run[h] + __shfl_xor(l_run[h], 32);   // wave-wide exchange: inactive rows take part
-        if (!active) continue;
-        const float inv = 1.f / l_tot;
-        uint16_t* op = out + (int64_t(tok_q) * n_q_heads + hq0 + h) * D;
-        // lane (n, hg), block db, register i  <->  d = 32 db + 8 (i/4) + 4 hg + i%4
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                bf16x4 o4;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) o4[c] = (__bf16)(o_acc[h][db][4 * q4 + c] * inv);
-                *reinterpret_cast<bf16x4*>(op + 32 * db + 8 * q4 + 4 * hg) = o4;
-            }
-        if (lse && hg == 0) lse[int64_t(tok_q) * n_q_heads + hq0 + h] = (m_run[h] + __builtin_amdgcn_logf(l_tot)) * kLn2;
-    }
-}
-
-
 // --------------------------------------------------------------------------
-// The attention kernel, second form.  Same tiles, same transposed products and the same two phases per key tile as
-// prefill_mfma_pipe_kernel above, with the instructions per matrix instruction cut down: one wave issues at most
-// one instruction every few cycles, and beside a v_mfma_f32_32x32x16_bf16 (32 cycles of the matrix pipe) about 3.5
-// plain vector instructions are free, every further one costs about 5 cycles, a ds_read_b128 about 4 and a
-// v_dot2_f32_bf16 about 18 -- it shares the matrix pipe (measured on this chip, one wave per SIMD).
+// The attention kernel (bf16): NH = 1 or 2 query heads of one KV head per workgroup.
+// Every wave owns 32 query rows of a work item for NH query heads that share a KV head.
+//   NH = 2  A K (or V^T) operand fragment read from LDS feeds two matrix instructions and one tile copied into
+//           LDS serves twice the arithmetic: LDS read traffic and L2 -> LDS copy traffic per flop are both halved.
+//           The price is registers (two output accumulators, two score blocks, two Q operands: about 430 per lane,
+//           the accumulators in accumulation registers), so one wave per SIMD; three K and three V^T buffers
+//           (96 KB), K copied two tiles ahead.
+//   NH = 1  fits the ordinary vector registers twice per SIMD: two workgroups per CU, two buffers each (64 KB),
+//           copies one tile ahead.
+// Either way a wave cannot count on other waves to fill the matrix pipe while it does its softmax, so the loop
+// is software-pipelined by hand, in the exact instruction order wanted:
+//   phase X of tile t:  scores of tile t+1   beside  exp2 / bf16 P / row sum of tile t
+//   phase Y of tile t:  O^T += V^T P^T        beside  the exponents of tile t+1 leaving the accumulation registers
+// with ONE barrier per key tile, and the vector work per matrix instruction cut to what one wave can issue beside
+// its own matrix instructions: it issues at most one instruction every few cycles; beside a
+// v_mfma_f32_32x32x16_bf16 (32 cycles of the matrix pipe) about 3.5 plain vector instructions are free, every
+// further one costs about 5 cycles, a ds_read_b128 about 4 and a v_dot2_f32_bf16 about 18 -- it shares the matrix
+// pipe (measured on this chip, one wave per SIMD).
 //   * The queries are multiplied by scale * log2(e) once, when they are loaded (and rounded to bf16 again), and
-//     the first matrix instruction of a score block starts from -m_ref instead of 0 (a block of 16 registers per
-//     head that holds -m_ref in every register): a score leaves the matrix pipe as the base-2 exponent of its
-//     probability relative to the row's reference exponent m_ref -- no multiply-add per element.
+//     the first matrix instruction of a score block starts from -m_ref instead of 0: a score leaves the matrix
+//     pipe as the base-2 exponent of its probability relative to the row's reference exponent m_ref -- no
+//     multiply-add per element.  Between two tiles the -m_ref values are parked in the last score block.
 //   * No running maximum.  m_ref is the row maximum of the FIRST tile (every row sees column 0 of its own stream,
 //     so it is finite); bf16 and fp32 have the same exponent range, so probabilities may grow far beyond 1 without
 //     any loss.  Only when a tile's row sum exceeds 2^kRiseLog2 (or is not finite) -- seen right after the
@@ -681,9 +300,18 @@ __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_mfma_pipe_kernel
 //   * The first operand fragments of a phase are read from LDS in the slots of the phase before that need no
 //     fragment of their own any more (with three buffers the K tile is known to have landed one tile early), and
 //     the copies of the next tiles are issued behind the first matrix instructions instead of in front of them.
-//   * The score block that the other kernel computes past the last tile is not computed.
+//   * The last tile of an item has no scores behind it: it is peeled out of the loop, whose body has no branch
+//     around its matrix instructions.
+// What was tried on top and did not pay: the first product's matrix instructions placed by hand with their results
+// in ordinary vector registers (no move out of the accumulation registers, a third of the vector instructions
+// gone): as fast, not faster -- the vector instructions co-execute less often with matrix instructions that use the
+// same register file (SQ_VALU_MFMA_COEXEC_CYCLES fell by a quarter); longer LDS rings (tiles requested three or four
+// tiles ahead): no change, the copies are not waited for.  Removing the tile copies altogether (wrong results, same
+// instruction stream otherwise) makes the kernel 15 % faster through the CLOCK, not through cycles: the chip is
+// power-limited under this kernel and the L2 -> LDS traffic is part of the bill; what can be saved of it is saved
+// by the order of the work items (see st_plan.hip).
 // --------------------------------------------------------------------------
-constexpr float kRiseLog2 = 40.f;
+constexpr float kRiseLog2 = 24.f;
 
 // NL wave-wide 16-byte copies global -> LDS, 1 KB apart on both sides: the instruction's immediate offset moves
 // the global address and the LDS address alike, so the LDS base goes into m0 once.
@@ -1145,27 +773,10 @@ __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_attn_kernel(uint
     }
 }
 
+
 }  // namespace st
 
 using namespace st;
-
-// Kernel choice of the bf16 path: ST_PREFILL_AUTO / ONE_HEAD / TWO_HEADS, initialised from the
-// environment variable ST_PREFILL_VARIANT (1 or 2), changed by st_prefill_variant_set.
-static std::atomic<int>& prefill_variant_ref() {
-    static std::atomic<int> v{[] {
-        const char* e = getenv("ST_PREFILL_VARIANT");
-        return (e && (e[0] == '1' || e[0] == '2') && e[1] == 0) ? e[0] - '0' : int(ST_PREFILL_AUTO);
-    }()};
-    return v;
-}
-static int prefill_variant() { return prefill_variant_ref().load(std::memory_order_relaxed); }
-
-extern "C" int32_t st_prefill_variant_set(int32_t variant) {
-    const int prev = prefill_variant();
-    if (variant == ST_PREFILL_AUTO || variant == ST_PREFILL_ONE_HEAD || variant == ST_PREFILL_TWO_HEADS)
-        prefill_variant_ref().store(variant, std::memory_order_relaxed);
-    return prev;
-}
 
 // packed K and V^T tiles, then the (cos, sin) table of the fused rotation (one float2 per packed row and pair)
 static size_t prefill_tile_bytes(const st_plan* plan, int n_kv_heads, int head_dim) {
@@ -1231,11 +842,12 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
     const bool rope = positions != nullptr;
     const RopeFreq freq = rope ? make_rope_freq(theta_base, head_dim) : RopeFreq{};
     const float scale_log2 = scale * kLog2e;
-    // Two query heads per workgroup when heads come in pairs over a KV head and the batch is large
-    // enough to keep every compute unit busy for several rounds of such (one per CU) workgroups;
-    // small batches finish sooner with twice as many, lighter workgroups.
-    const int variant = prefill_variant();
-    const bool pair = ((n_q_heads / n_kv_heads) % 2 == 0) && (variant == ST_PREFILL_TWO_HEADS || (variant == ST_PREFILL_AUTO && blocks / 2 >= 2048));
+    // Two query heads per workgroup when heads come in pairs over a KV head and the sequences are long (an item then
+    // walks a hundred key tiles and more, and the halved LDS / L2 traffic per flop pays); short sequences finish
+    // sooner with twice as many, lighter workgroups, two per compute unit.
+    const int heads_wanted = plan->heads_per_workgroup;
+    const bool can_pair = (n_q_heads / n_kv_heads) % 2 == 0;
+    const bool pair = can_pair && (heads_wanted == 2 || (heads_wanted == 0 && plan->n_tokens / plan->batch >= 8192));
     auto launch = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
         if (rope) {
@@ -1249,8 +861,7 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
             constexpr int NH = decltype(nh_tag)::value;
             constexpr bool ROPE = decltype(rope_tag)::value;
             const size_t smem = sizeof(PipeSmem<HD, NH == 2 ? 3 : 2>);
-            static const bool old_kernel = getenv("ST_PREFILL_OLD") != nullptr;
-            auto* kern = old_kernel ? &prefill_mfma_pipe_kernel<HD, NH, ROPE> : &prefill_attn_kernel<HD, NH, ROPE>;
+            auto* kern = &prefill_attn_kernel<HD, NH, ROPE>;
             ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfPrefillAttn, s);
             hipLaunchKernelGGL(kern, dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
@@ -1265,7 +876,7 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
     };
     const st_status lr = head_dim == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});
     if (lr != ST_OK) return lr;
-    ST_LAUNCH_CHECK("tile_pack_kernel / prefill_mfma_pipe_kernel");
+    ST_LAUNCH_CHECK("tile_pack_kernel / prefill_attn_kernel");
     return ST_OK;
 }
 

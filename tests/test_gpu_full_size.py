@@ -46,12 +46,12 @@ def _sample_rows(cfg, b, tile_m, n_extra, rng):
     return np.array(sorted(r for r in rows if 0 <= r < n))
 
 
-def _prefill_full(st, cfg, meta_seqs, n_extra=24):
+def _prefill_full(st, cfg, meta_seqs, n_extra=24, heads=0):
     hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
     q = _device_normal((n, hq, d), cfg.seed); k = _device_normal((n, hkv, d), cfg.seed + 1); v = _device_normal((n, hkv, d), cfg.seed + 2)
     seg, strm, pos = ids_to_dev(cfg)
     st.st_rope_apply(q, pos, cfg.theta); st.st_rope_apply(k, pos, cfg.theta)
-    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, validate=True)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, validate=True).heads_per_workgroup(heads)
     lse = torch.empty((n, hq), dtype=torch.float32, device=DEV)
     out = st.st_attn_prefill(q, k, v, plan, lse=lse)
     torch.cuda.synchronize()
@@ -92,11 +92,7 @@ def test_config4a_prefill_16k(st):
 
 def test_config4a_prefill_16k_one_head_kernel(st):
     """The same batch through the kernel the automatic choice does NOT take at this size."""
-    prev = st.st_prefill_variant_set(st.ST_PREFILL_ONE_HEAD)
-    try:
-        _prefill_full(st, W.config4a(), meta_seqs=())
-    finally:
-        st.st_prefill_variant_set(prev)
+    _prefill_full(st, W.config4a(), meta_seqs=(), heads=1)
 
 
 def test_config4b_prefill_128_pairs(st):
