@@ -62,30 +62,19 @@ const char* st_last_error(void);
 /* Library version (major * 100 + minor). */
 int32_t st_version(void);
 
-/* Optional kernel timing for benchmarks.  While enabled, st_attn_prefill brackets its attention
- * kernel (ST_PROF_PREFILL_ATTN), st_attn_decode_dual its split kernel (ST_PROF_DECODE_SPLIT) and
- * the bf16 st_attn_prefill_bwd its two attention kernels (ST_PROF_BWD_DQ, ST_PROF_BWD_DKV)
- * with HIP events on the launch stream.  st_profile_read WAITS for the recorded launches, returns
- * their mean duration in milliseconds and their number in host variables, and forgets them. */
-enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1, ST_PROF_BWD_DQ = 2, ST_PROF_BWD_DKV = 3 };
+/* Optional kernel timing for benchmarks, a property of the CALLING THREAD (like the error text):
+ * while the thread has it enabled, its calls bracket these kernels with HIP events on the launch
+ * stream -- st_attn_prefill(_rope) the tile packing (ST_PROF_TILE_PACK: the packing kernel, with
+ * fused rotation also the table kernel) and the attention kernel (ST_PROF_PREFILL_ATTN),
+ * st_attn_decode_dual(_rope, _append) the split kernel (ST_PROF_DECODE_SPLIT), the bf16
+ * st_attn_prefill_bwd its two attention kernels (ST_PROF_BWD_DQ, ST_PROF_BWD_DKV),
+ * st_attn_source_chunk(_rope) its attention kernel (ST_PROF_SOURCE_CHUNK).  st_profile_read WAITS
+ * for the launches the thread recorded, returns their mean duration in milliseconds and their
+ * number in host variables, and forgets them.  (Creating events allocates: not under graph capture.) */
+enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1, ST_PROF_BWD_DQ = 2, ST_PROF_BWD_DKV = 3,
+       ST_PROF_TILE_PACK = 4, ST_PROF_SOURCE_CHUNK = 5 };
 void st_profile_enable(int32_t on);
 st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
-
-/* Machine probes for benchmarks (they compute nothing of the method; callers that only use the
- * operators never need them).
- * st_probe_paged_read: n_waves one-wave workgroups each read steps_per_wave x 16 KiB from `pool`
- *   (device memory, pool_bytes a power of two >= 4 KiB, 16-byte aligned) as the decode kernel
- *   reads a paged bf16 cache with head_dim 128: four pseudo-random 4 KiB pages per step, 16 loads
- *   of 16 bytes per lane with its per-lane addressing; every call picks other pages than the one
- *   before, so with a pool much larger than the caches nothing is found cached.  Bytes read per launch =
- *   n_waves * steps_per_wave * 16384.  sink: device uint32 (practically never written).
- * st_probe_mfma_bf16: n_workgroups x 4 waves each issue iterations x 8 v_mfma_f32_32x32x16_bf16
- *   on register operands with random mantissas; flop per launch =
- *   n_workgroups * 4 * iterations * 8 * 32768.  sink: device float.
- * Both enqueue one kernel on hip_stream and return; ST_ERR_INVALID_ARG on bad arguments. */
-st_status st_probe_paged_read(const void* pool, size_t pool_bytes, int32_t n_waves,
-                              int32_t steps_per_wave, uint32_t* sink, void* hip_stream);
-st_status st_probe_mfma_bf16(int32_t n_workgroups, int32_t iterations, float* sink, void* hip_stream);
 
 /* ------------------------------------------------------------------------
  * st_rope_apply -- rotary position encoding with caller-supplied (stream-local)
@@ -134,7 +123,8 @@ st_status st_rope_apply_qk(void* q_out, const void* q, int32_t n_q_heads, void* 
  *   reasoning row may see, the per-tile SKIP / FULL / PARTIAL extents of the three
  *   mask blocks SS, RS, RR, a longest-first work list, and the visible-pair count.
  * All of it is built by device kernels on hip_stream; st_plan_create itself does
- * not wait for them.
+ * not wait for them.  Calls that take the plan on ANOTHER stream are ordered behind
+ * the build by the library (an event recorded here, waited for there).
  *
  * workspace: device memory of at least st_plan_workspace_bytes(batch, n_tokens)
  * bytes, 256-byte aligned, which must outlive the plan; or NULL, in which case the
@@ -376,20 +366,20 @@ typedef struct st_dual_lens {
     int32_t q_len;
     int32_t max_src_len;
     int32_t max_rsn_len;
+    int32_t unit_tokens;            /* tokens per work unit of the step, see below; 0 = chosen by launch size */
 } st_dual_lens;
 
-/* Tokens per work unit of the decode step with q_len * (n_q_heads / n_kv_heads) <= 16: 0 (default)
- * chooses by launch size -- 1024 for large batches down to 128 for a few sequences, whose step is
- * bound by a wave's serial walk over its unit; 128, 256, 512 or 1024 pins it (for tests and
- * tuning).  Results agree within rounding.  Process-wide.  Returns the previous setting; other
- * values leave it unchanged.  st_decode_workspace_bytes follows the setting: size the workspace
- * after changing it.  A workspace sized for other length bounds is accepted as long as it holds
- * 512-token units; the call then uses the smallest unit the workspace has room for. */
-int32_t st_decode_unit_set(int32_t tokens);
-
+/* Work units.  A step with q_len * (n_q_heads / n_kv_heads) <= 16 cuts each cache into units of
+ * lens->unit_tokens tokens, one wave each: 0 chooses by launch size -- 1024 for large batches down
+ * to 128 for a few sequences, whose step is bound by a wave's serial walk over its unit --, 128,
+ * 256, 512 or 1024 pins it (tests, tuning); other values give ST_ERR_INVALID_ARG.  Results agree
+ * within rounding.  st_decode_workspace_bytes takes the same value and answers for it (and always
+ * provides for 512-token units).  A workspace sized for other length bounds or another unit is
+ * accepted as long as it holds 512-token units; the call then uses the smallest unit not below the
+ * wanted one that the workspace has room for.  0 bytes are returned for arguments that make no sense. */
 size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
                                  int32_t head_dim, int32_t q_len,
-                                 int32_t max_src_len, int32_t max_rsn_len);
+                                 int32_t max_src_len, int32_t max_rsn_len, int32_t unit_tokens);
 
 st_status st_attn_decode_dual(void* out, float* lse, const void* q,
                               const st_dual_cache* caches, const st_dual_lens* lens,
@@ -449,9 +439,9 @@ st_status st_attn_decode_dual_append(void* out, float* lse, const void* q, const
 
 /* ------------------------------------------------------------------------
  * st_attn_source_chunk -- attention of an arriving source chunk over the paged source
- * cache.  Alg. 1, prefill loop ("read the input sentence and save hidden state to the
- * input KV cache"; Sec. 3.3: the model "performs prefill in arrival order"): the tokens of
- * the new sentence attend causally to the source stream only, never to reasoning.
+ * cache.  Alg. 1, prefill loop; Sec. 3.3 "Parallel KV caches": every arriving input sentence is
+ * run through the model in arrival order and its keys / values go to the source cache; its
+ * tokens attend causally to the source stream only, never to reasoning.
  *
  * Call order: st_kv_append(ST_SOURCE, chunk) first, then this call with
  *   src_len[b]  : device int32 [batch], source tokens in the cache INCLUDING the chunk

@@ -53,7 +53,7 @@ class _StreamReportStruct(C.Structure):
 
 class _DualLensStruct(C.Structure):
     _fields_ = [("src_visible_len", C.c_void_p), ("rsn_len", C.c_void_p), ("q_len", C.c_int32),
-                ("max_src_len", C.c_int32), ("max_rsn_len", C.c_int32)]
+                ("max_src_len", C.c_int32), ("max_rsn_len", C.c_int32), ("unit_tokens", C.c_int32)]
 
 
 _lib = None
@@ -80,10 +80,6 @@ def load_library():
     lib.st_version.argtypes = []
     lib.st_plan_heads_per_workgroup.restype = i32
     lib.st_plan_heads_per_workgroup.argtypes = [vp, i32]
-    lib.st_probe_paged_read.restype = i32
-    lib.st_probe_paged_read.argtypes = [vp, sz, i32, i32, vp, vp]
-    lib.st_probe_mfma_bf16.restype = i32
-    lib.st_probe_mfma_bf16.argtypes = [i32, i32, vp, vp]
     lib.st_profile_enable.restype = None
     lib.st_profile_enable.argtypes = [i32]
     lib.st_profile_read.restype = i32
@@ -129,10 +125,8 @@ def load_library():
     lib.st_attn_decode_dual_append.restype = i32
     lib.st_attn_decode_dual_append.argtypes = [vp, vp, vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
                                                f32, f64, vp, sz, vp]
-    lib.st_decode_unit_set.restype = i32
-    lib.st_decode_unit_set.argtypes = [i32]
     lib.st_decode_workspace_bytes.restype = sz
-    lib.st_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32]
+    lib.st_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32, i32]
     lib.st_attn_decode_dual.restype = i32
     lib.st_attn_decode_dual.argtypes = [vp, vp, vp, C.POINTER(_DualCacheStruct), C.POINTER(_DualLensStruct), i32, i32,
                                         f32, vp, sz, vp]
@@ -178,6 +172,15 @@ def _stream(stream):
     return C.c_void_p(stream.cuda_stream)
 
 
+def _temp_workspace(n_bytes, device, stream):
+    """A workspace that lives only for one call: allocated ON the stream the kernels are launched on, so that the
+    caching allocator does not hand the block to somebody else while they still run."""
+    if stream is None or stream == torch.cuda.current_stream():
+        return torch.empty(max(int(n_bytes), 256), dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(max(int(n_bytes), 256), dtype=torch.uint8, device=device)
+
+
 def _dev_i32(t, name):
     if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
         raise TypeError(f"{name} must be a contiguous int32 device tensor")
@@ -192,17 +195,40 @@ def st_last_error():
     return load_library().st_last_error().decode()
 
 
-ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT, ST_PROF_BWD_DQ, ST_PROF_BWD_DKV = 0, 1, 2, 3
+ST_PROF_PREFILL_ATTN, ST_PROF_DECODE_SPLIT, ST_PROF_BWD_DQ, ST_PROF_BWD_DKV, ST_PROF_TILE_PACK, ST_PROF_SOURCE_CHUNK = 0, 1, 2, 3, 4, 5
 
 
-def st_probe_paged_read(pool, n_waves, steps_per_wave, sink, stream=None):
+_probe_lib = None
+
+
+def load_probe_library():
+    """libst_probe.so: the benchmark's machine probes (include/st_probe.h), not part of the path."""
+    global _probe_lib
+    if _probe_lib is None:
+        path = os.path.join(HERE, "libst_probe.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2510_17238_amd.build`")
+        lib = C.CDLL(path)
+        lib.st_probe_paged_read.restype = C.c_int32
+        lib.st_probe_paged_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p]
+        lib.st_probe_mfma_bf16.restype = C.c_int32
+        lib.st_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        _probe_lib = lib
+    return _probe_lib
+
+
+def st_probe_paged_read(pool, n_waves, steps_per_wave, salt, sink, stream=None):
     """pool: uint8 device tensor whose size is a power of two; sink: uint32-sized device tensor."""
-    _check(load_library().st_probe_paged_read(_ptr(pool), pool.numel() * pool.element_size(), int(n_waves), int(steps_per_wave),
-                                              _ptr(sink), _stream(stream)))
+    rc = load_probe_library().st_probe_paged_read(_ptr(pool), pool.numel() * pool.element_size(), int(n_waves), int(steps_per_wave),
+                                                  int(salt) & 0xFFFFFFFF, _ptr(sink), _stream(stream))
+    if rc != ST_OK:
+        raise StError(rc, "st_probe_paged_read")
 
 
 def st_probe_mfma_bf16(n_workgroups, iterations, sink, stream=None):
-    _check(load_library().st_probe_mfma_bf16(int(n_workgroups), int(iterations), _ptr(sink), _stream(stream)))
+    rc = load_probe_library().st_probe_mfma_bf16(int(n_workgroups), int(iterations), _ptr(sink), _stream(stream))
+    if rc != ST_OK:
+        raise StError(rc, "st_probe_mfma_bf16")
 
 
 def st_profile_enable(on):
@@ -353,7 +379,7 @@ def st_attn_prefill(q, k, v, plan, scale=0.0, out=None, lse=None, workspace=None
     if workspace is None:
         need = st_prefill_workspace_bytes(plan, hkv, d, _dtype_code(q))
         if need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+            workspace = _temp_workspace(need, q.device, stream)
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     if rope_theta is None:
@@ -383,7 +409,7 @@ def st_attn_prefill_bwd(d_out, q, k, v, out, lse, plan, scale=0.0, workspace=Non
     assert d_out.shape == q.shape == out.shape and k.shape == v.shape and tuple(lse.shape) == (n, hq)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     if workspace is None:
-        workspace = torch.empty(max(256, int(lib.st_prefill_bwd_workspace_bytes(plan.handle, hq, hkv, d, _dtype_code(q)))), dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(int(lib.st_prefill_bwd_workspace_bytes(plan.handle, hq, hkv, d, _dtype_code(q))), q.device, stream)
     _check(lib.st_attn_prefill_bwd(_ptr(dq), _ptr(dk), _ptr(dv), _ptr(d_out), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                    plan.handle, hq, hkv, d, float(scale), _dtype_code(q), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -513,17 +539,13 @@ def st_kv_append_rope(caches, which, k_new, v_new, theta_base, n_new=None, host_
     st_kv_append(caches, which, k_new, v_new, n_new, host_len_upper_bound, stream, rope_theta=theta_base)
 
 
-def st_decode_unit_set(tokens):
-    """Pin the decode work unit (128 / 256 / 512 / 1024 tokens; 0 = by launch size); returns the previous setting."""
-    return int(load_library().st_decode_unit_set(int(tokens)))
-
-
-def st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len):
-    return int(load_library().st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len))
+def st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len, unit_tokens=0):
+    return int(load_library().st_decode_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, q_len, max_src_len, max_rsn_len,
+                                                        int(unit_tokens)))
 
 
 def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, scale=0.0, out=None, lse=None,
-                        workspace=None, stream=None, rope_theta=None):
+                        workspace=None, stream=None, rope_theta=None, unit_tokens=0):
     """q[batch, q_len, Hq, D] bf16 -> out of the same shape; lengths are int32 device tensors.
     rope_theta: None for st_attn_decode_dual (rotated queries), a base for st_attn_decode_dual_rope."""
     lib = load_library()
@@ -533,10 +555,10 @@ def st_attn_decode_dual(q, caches, src_visible_len, rsn_len, max_src_len, max_rs
     if out is None:
         out = torch.empty_like(q)
     if workspace is None:
-        need = st_decode_workspace_bytes(batch, hq, caches.source.n_kv_heads, d, q_len, max_src_len, max_rsn_len)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        need = st_decode_workspace_bytes(batch, hq, caches.source.n_kv_heads, d, q_len, max_src_len, max_rsn_len, unit_tokens)
+        workspace = _temp_workspace(need, q.device, stream)
     st = caches.struct()
-    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
+    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len), int(unit_tokens))
     if rope_theta is None:
         _check(lib.st_attn_decode_dual(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
                                        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
@@ -559,7 +581,7 @@ def st_attn_decode_dual_static(q, caches, src_visible_len, rsn_len, max_src_len,
     batch, q_len, hq, d = q.shape
     _dev_i32(src_visible_len, "src_visible_len"); _dev_i32(rsn_len, "rsn_len")
     st = caches.struct()
-    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
+    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len), 0)
     _check(load_library().st_attn_decode_dual_static(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), C.byref(lens), batch, hq, float(scale),
                                                      _stream(stream)))
     return out
@@ -571,7 +593,7 @@ def st_attn_decode_dual_rope(q, caches, src_visible_len, rsn_len, max_src_len, m
 
 
 def st_attn_decode_dual_append(q, k_new, v_new, caches, src_visible_len, rsn_len, max_src_len, max_rsn_len, theta_base=0.0, scale=0.0,
-                               out=None, lse=None, workspace=None, stream=None):
+                               out=None, lse=None, workspace=None, stream=None, unit_tokens=0):
     """One decoding step: k_new / v_new [batch, 1, Hkv, D] go into the reasoning cache at index rsn_len - 1 and
     q [batch, 1, Hq, D] attends over both caches.  theta_base > 0: q and k_new are unrotated; 0: already rotated."""
     lib = load_library()
@@ -584,10 +606,10 @@ def st_attn_decode_dual_append(q, k_new, v_new, caches, src_visible_len, rsn_len
     if out is None:
         out = torch.empty_like(q)
     if workspace is None:
-        need = st_decode_workspace_bytes(batch, hq, hkv, d, q_len, max_src_len, max_rsn_len)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        need = st_decode_workspace_bytes(batch, hq, hkv, d, q_len, max_src_len, max_rsn_len, unit_tokens)
+        workspace = _temp_workspace(need, q.device, stream)
     st = caches.struct()
-    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len))
+    lens = _DualLensStruct(src_visible_len.data_ptr(), rsn_len.data_ptr(), q_len, int(max_src_len), int(max_rsn_len), int(unit_tokens))
     _check(lib.st_attn_decode_dual_append(_ptr(out), _ptr(lse), _ptr(q), _ptr(k_new), _ptr(v_new), C.byref(st), C.byref(lens), batch, hq,
                                           float(scale), float(theta_base), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                           _stream(stream)))
@@ -612,7 +634,7 @@ def st_attn_source_chunk(q, caches, src_len, max_src_len, n_new=None, scale=0.0,
         out = torch.zeros_like(q)
     if workspace is None:
         need = st_source_chunk_workspace_bytes(batch, hq, caches.source.n_kv_heads, d, max_new, max_src_len)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q.device, stream)
     st = caches.struct()
     if rope_theta is None:
         _check(lib.st_attn_source_chunk(_ptr(out), _ptr(lse), _ptr(q), C.byref(st), _ptr(src_len), _ptr(n_new), max_new,

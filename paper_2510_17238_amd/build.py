@@ -1,4 +1,5 @@
-"""Compile the HIP sources under csrc/ into libst.so for gfx950 (explicit hipcc, in-tree)."""
+"""Compile the HIP sources under csrc/ for gfx950 (explicit hipcc, in-tree): libst.so, the library of the path, and
+libst_probe.so, the machine probes of the benchmark (a library of their own: the path does not need them)."""
 import os
 import subprocess
 import sys
@@ -8,8 +9,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libst.so")
+PROBE_LIB = os.path.join(HERE, "libst_probe.so")
 
-SOURCES = ["st_error.hip", "st_rope.hip", "st_plan.hip", "st_prefill.hip", "st_prefill_bwd.hip", "st_cache.hip", "st_decode.hip", "st_sched.hip", "st_probe.hip"]
+SOURCES = ["st_error.hip", "st_rope.hip", "st_plan.hip", "st_prefill.hip", "st_prefill_bwd.hip", "st_cache.hip", "st_decode.hip", "st_sched.hip"]
+PROBE_SOURCES = ["st_probe.hip"]            # (linked with st_error.o for the error text)
 
 FLAGS = [
     "--offload-arch=gfx950:xnack-", "-O3", "-std=c++17", "-fPIC",
@@ -39,7 +42,7 @@ def build_library(verbose=True):
     hipcc = _hipcc()
     objs = []
     procs = []
-    for src in SOURCES:
+    for src in SOURCES + PROBE_SOURCES:
         obj = os.path.join(BUILD, src.replace(".hip", ".o"))
         cmd = [hipcc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -51,12 +54,14 @@ def build_library(verbose=True):
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    cmd = [hipcc, "--offload-arch=gfx950:xnack-", "-shared", "-fPIC", "-o", LIB] + objs
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stdout)
-    if verbose:
-        print("built", LIB)
+    n_main = len(SOURCES)
+    for lib, members in ((LIB, objs[:n_main]), (PROBE_LIB, objs[n_main:] + [objs[SOURCES.index("st_error.hip")]])):
+        cmd = [hipcc, "--offload-arch=gfx950:xnack-", "-shared", "-fPIC", "-o", lib] + members
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stdout)
+        if verbose:
+            print("built", lib)
     return LIB
 
 

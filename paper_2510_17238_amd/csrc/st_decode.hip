@@ -17,7 +17,6 @@
 #include <type_traits>
 
 #include "st_cache.h"
-#include <atomic>
 #include <mutex>
 
 #include "st_tiles.h"
@@ -1262,16 +1261,14 @@ static inline size_t decode_partial_bytes(int unit, int64_t batch, int hkv, int 
     const size_t slots = size_t(batch) * hkv * nc * rows;
     return align256(slots * d * sizeof(float)) + align256(slots * 2 * sizeof(float)) + 256;
 }
-static std::atomic<int> g_decode_unit{0};     // 0: by the rule below; else the pinned unit (st_decode_unit_set)
 // Tokens per work unit of the one-wave decode kernels (<= 16 query rows): a wave walks its unit serially, one
 // memory round trip per 32 tokens, so the unit is as long as still leaves enough units -- 1024 tokens when that
 // gives four thousand (fewest partial results; measured best on 64 streams of 36 layers), else 512 if that gives a
 // thousand (measured best on configs[2]: 32 streams), down to 128 for a few sequences, where the step is bound by
 // that serial walk and not by bandwidth.
-static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_src, int max_rsn, bool fp8 = false) {
+static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_src, int max_rsn, int pinned, bool fp8 = false) {
     if (rows > 16) return kChunk;
-    const int pinned = g_decode_unit.load(std::memory_order_relaxed);
-    if (pinned) return pinned;
+    if (pinned) return pinned;               // the caller's choice (st_dual_lens::unit_tokens)
     auto units = [&](int unit) { return batch * hkv * ((max_src + unit - 1) / unit + (max_rsn + unit - 1) / unit); };
     // (counted with the length BOUNDS: about half are real; the 8-bit kernel, which walks 64 tokens per step and
     // keeps four waves per SIMD, is best with the long unit from a thousand on)
@@ -1285,21 +1282,17 @@ static inline int decode_unit_tokens(int64_t batch, int hkv, int rows, int max_s
 
 using namespace st;
 
-extern "C" int32_t st_decode_unit_set(int32_t tokens) {
-    const int prev = g_decode_unit.load(std::memory_order_relaxed);
-    if (tokens == 0 || tokens == 128 || tokens == 256 || tokens == 512 || tokens == 1024)
-        g_decode_unit.store(tokens, std::memory_order_relaxed);
-    return prev;
-}
+static inline bool valid_unit(int tokens) { return tokens == 0 || tokens == 128 || tokens == 256 || tokens == 512 || tokens == 1024; }
 
 extern "C" size_t st_decode_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                            int32_t q_len, int32_t max_src_len, int32_t max_rsn_len) {
-    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || q_len <= 0 || head_dim <= 0 || max_src_len < 0 || max_rsn_len < 0)
+                                            int32_t q_len, int32_t max_src_len, int32_t max_rsn_len, int32_t unit_tokens) {
+    if (batch <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || q_len <= 0 || head_dim <= 0 || max_src_len < 0 || max_rsn_len < 0 ||
+        !valid_unit(unit_tokens))
         return 0;
     const int rows = q_len * (n_q_heads / n_kv_heads);
     // enough for 512-token units whatever the bounds of a later call, and for the unit this very call would use
     const size_t base = decode_partial_bytes(kChunk, batch, n_kv_heads, rows, head_dim, max_src_len, max_rsn_len);
-    const int unit = decode_unit_tokens(batch, n_kv_heads, rows, max_src_len, max_rsn_len);
+    const int unit = decode_unit_tokens(batch, n_kv_heads, rows, max_src_len, max_rsn_len, unit_tokens);
     const size_t own = decode_partial_bytes(unit, batch, n_kv_heads, rows, head_dim, max_src_len, max_rsn_len);
     return base > own ? base : own;
 }
@@ -1366,6 +1359,7 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     if (fp8 && lens->q_len * group > 16)
         return fail(ST_ERR_UNSUPPORTED, "st_attn_decode_dual: 8-bit caches take q_len %d x group %d up to 16", lens->q_len, group);
     if (lens->max_src_len < 0 || lens->max_rsn_len < 0) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: negative length bound");
+    if (!valid_unit(lens->unit_tokens)) return fail(ST_ERR_INVALID_ARG, "st_attn_decode_dual: unit_tokens %d (0, 128, 256, 512 or 1024)", lens->unit_tokens);
     if (int64_t(lens->max_src_len) > int64_t(cs.max_pages_per_seq) * kPage || int64_t(lens->max_rsn_len) > int64_t(cr.max_pages_per_seq) * kPage)
         return fail(ST_ERR_CAPACITY, "st_attn_decode_dual: length bound exceeds the page table");
     const size_t need = decode_partial_bytes(kChunk, batch, hkv, lens->q_len * group, d, lens->max_src_len, lens->max_rsn_len);
@@ -1387,7 +1381,7 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.group = group;
     a.rows = lens->q_len * group;
     // Work unit: see decode_unit_tokens; a workspace sized for other length bounds may only hold longer units.
-    a.chunk = decode_unit_tokens(batch, hkv, a.rows, lens->max_src_len, lens->max_rsn_len, fp8);
+    a.chunk = decode_unit_tokens(batch, hkv, a.rows, lens->max_src_len, lens->max_rsn_len, lens->unit_tokens, fp8);
     while (a.chunk < kChunk && decode_partial_bytes(a.chunk, batch, hkv, a.rows, d, lens->max_src_len, lens->max_rsn_len) > workspace_bytes)
         a.chunk *= 2;
     a.ncs = (lens->max_src_len + a.chunk - 1) / a.chunk;
@@ -1585,7 +1579,9 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
             constexpr int STAGES = ST_CHUNK_STAGES, TOK = ST_CHUNK_TOK;
             const size_t smem = sizeof(ChunkSmem<HD, STAGES, TOK>);
             ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_split_lds_kernel<HD, STAGES, TOK>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
+            prof_begin(kProfSourceChunk, s);
             hipLaunchKernelGGL((chunk_split_lds_kernel<HD, STAGES, TOK>), dim3((unsigned)wgs), dim3(256), smem, s, a);
+            prof_end(kProfSourceChunk, s);
             return ST_OK;
         };
         const st_status lr = d == 64 ? launch(std::integral_constant<int, 64>{}) : launch(std::integral_constant<int, 128>{});

@@ -1,8 +1,6 @@
 // Error text and version of the C ABI.
 #include <string.h>
 
-#include <atomic>
-#include <mutex>
 #include <vector>
 
 #include "st_internal.h"
@@ -21,17 +19,17 @@ const char* get_error() { return g_error; }
 
 namespace st {
 namespace {
+// Kernel timing is a property of the CALLING THREAD (like the error text): a thread that switches it on gets events
+// around the kernels of its own calls and reads back its own measurements; other threads are not affected.
 struct Region { hipEvent_t a, b; };
-std::mutex g_prof_mutex;
-std::atomic<bool> g_prof_on{false};
-std::vector<Region> g_regions[kProfCount];
+thread_local bool t_prof_on = false;
+thread_local std::vector<Region> t_regions[kProfCount];
 }  // namespace
 
-bool prof_enabled() { return g_prof_on.load(); }
+bool prof_enabled() { return t_prof_on; }
 
 void prof_begin(int which, hipStream_t stream) {
-    if (!g_prof_on.load()) return;
-    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!t_prof_on) return;
     Region r{};
     if (hipEventCreate(&r.a) != hipSuccess) return;
     if (hipEventCreate(&r.b) != hipSuccess) {
@@ -39,28 +37,23 @@ void prof_begin(int which, hipStream_t stream) {
         return;
     }
     (void)hipEventRecord(r.a, stream);
-    g_regions[which].push_back(r);
+    t_regions[which].push_back(r);
 }
 
 void prof_end(int which, hipStream_t stream) {
-    if (!g_prof_on.load()) return;
-    std::lock_guard<std::mutex> lock(g_prof_mutex);
-    if (!g_regions[which].empty()) (void)hipEventRecord(g_regions[which].back().b, stream);
+    if (!t_prof_on) return;
+    if (!t_regions[which].empty()) (void)hipEventRecord(t_regions[which].back().b, stream);
 }
 }  // namespace st
 
-extern "C" void st_profile_enable(int32_t on) {
-    std::lock_guard<std::mutex> lock(st::g_prof_mutex);
-    st::g_prof_on.store(on != 0);
-}
+extern "C" void st_profile_enable(int32_t on) { st::t_prof_on = on != 0; }
 
 extern "C" st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count) {
     using namespace st;
     if (which < 0 || which >= kProfCount || !mean_ms || !count) return fail(ST_ERR_INVALID_ARG, "st_profile_read: bad argument");
-    std::lock_guard<std::mutex> lock(g_prof_mutex);
     double total = 0.0;
     int n = 0;
-    for (Region& r : g_regions[which]) {
+    for (Region& r : t_regions[which]) {
         float ms = 0.f;
         if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
             total += ms;
@@ -69,11 +62,11 @@ extern "C" st_status st_profile_read(int32_t which, double* mean_ms, int32_t* co
         (void)hipEventDestroy(r.a);
         (void)hipEventDestroy(r.b);
     }
-    g_regions[which].clear();
+    t_regions[which].clear();
     *mean_ms = n ? total / n : 0.0;
     *count = n;
     return ST_OK;
 }
 
 extern "C" const char* st_last_error(void) { return st::get_error(); }
-extern "C" int32_t st_version(void) { return 1; }
+extern "C" int32_t st_version(void) { return 2; }

@@ -37,9 +37,9 @@ inline st_status fail(st_status code, const char* fmt, ...) {
             return st::fail(ST_ERR_RUNTIME, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
     } while (0)
 
-// Optional kernel timing (st_profile_enable): HIP events recorded on the launch stream right
+// Optional kernel timing (st_profile_enable, per calling thread): HIP events recorded on the launch stream right
 // before and after one kernel, read back by st_profile_read.
-enum { kProfPrefillAttn = 0, kProfDecodeSplit = 1, kProfBwdDq = 2, kProfBwdDkv = 3, kProfCount = 4 };
+enum { kProfPrefillAttn = 0, kProfDecodeSplit = 1, kProfBwdDq = 2, kProfBwdDkv = 3, kProfTilePack = 4, kProfSourceChunk = 5, kProfCount = 6 };
 bool prof_enabled();
 void prof_begin(int which, hipStream_t stream);
 void prof_end(int which, hipStream_t stream);

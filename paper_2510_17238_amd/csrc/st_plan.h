@@ -65,11 +65,15 @@ struct st_plan {
     void* ws = nullptr;
     bool owns_ws = false;
     hipStream_t stream = nullptr;
+    hipEvent_t built = nullptr;        // recorded on `stream` behind the kernels that build the tables
     int32_t *cu = nullptr, *slot_base = nullptr, *pack_base = nullptr, *n_src = nullptr, *n_rsn = nullptr;
     int32_t *perm = nullptr, *seg_c = nullptr, *vis = nullptr, *cost = nullptr, *flag = nullptr;
     unsigned long long* pairs = nullptr;
     st::WorkItem* items = nullptr;    // slot order (sequence by sequence)
     st::WorkItem* sorted = nullptr;   // longest first
+
+    // Orders `s` behind the build of the tables (nothing to do on the stream that built them).
+    hipError_t wait_built(hipStream_t s) const { return (s == stream || !built) ? hipSuccess : hipStreamWaitEvent(s, built, 0); }
 
     st::PlanView view() const { return st::PlanView{cu, n_src, perm, vis, sorted, m_max, pack_base, pack_tiles, batch}; }
 };

@@ -452,6 +452,9 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
         hipLaunchKernelGGL(plan_order_kernel, dim3(mb), dim3(256), 0, s, p->cost, p->m_max, p->items, p->sorted);
     }
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "launch of plan kernels");
+    // calls that use the plan on another stream wait for this point
+    if ((e = hipEventCreateWithFlags(&p->built, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreateWithFlags");
+    if ((e = hipEventRecord(p->built, s)) != hipSuccess) return bail(e, "hipEventRecord");
     if (validate) {
         int32_t flag = 0;
         if ((e = hipMemcpyAsync(&flag, p->flag, sizeof(flag), hipMemcpyDeviceToHost, s)) != hipSuccess)
@@ -472,6 +475,7 @@ extern "C" st_status st_plan_create(st_plan** plan_out, const int32_t* segment_i
 extern "C" void st_plan_destroy(st_plan* plan) {
     if (!plan) return;
     if (plan->owns_ws && plan->ws) (void)hipFree(plan->ws);
+    if (plan->built) (void)hipEventDestroy(plan->built);
     delete plan;
 }
 

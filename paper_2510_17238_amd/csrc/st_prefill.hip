@@ -818,6 +818,7 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
     const int64_t pack_blocks = int64_t(plan->pack_tiles) * n_kv_heads;
     if (blocks > 0x7fffffff || pack_blocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_prefill: grid too large");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    ST_HIP(plan->wait_built(s));
     const PlanView pv = plan->view();
     if (dt == ST_F32) {
         const size_t smem = sizeof(float) * kTileM * (head_dim + 1);
@@ -850,6 +851,7 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
     const bool pair = can_pair && (heads_wanted == 2 || (heads_wanted == 0 && plan->n_tokens / plan->batch >= 8192));
     auto launch = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
+        prof_begin(kProfTilePack, s);
         if (rope) {
             hipLaunchKernelGGL((rope_table_kernel<HD>), dim3((unsigned)plan->pack_tiles), dim3(256), 0, s, tab, positions, pv, freq);
             hipLaunchKernelGGL((tile_pack_rope_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const float2*)tab,
@@ -857,6 +859,7 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
         } else
             hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const uint16_t*)k,
                                (const uint16_t*)v, pv, n_kv_heads);
+        prof_end(kProfTilePack, s);
         auto run = [&](auto nh_tag, auto rope_tag) -> st_status {
             constexpr int NH = decltype(nh_tag)::value;
             constexpr bool ROPE = decltype(rope_tag)::value;

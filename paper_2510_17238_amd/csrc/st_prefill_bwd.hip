@@ -753,6 +753,7 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
     const int64_t qblocks = int64_t(plan->m_max) * n_q_heads, kblocks = int64_t(plan->m_max) * n_kv_heads;
     if (qblocks > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_prefill_bwd: grid too large");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    ST_HIP(plan->wait_built(s));
     const PlanView pv = plan->view();
     float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + L.delta);
     auto run = [&](auto ttag, auto dtag) -> st_status {

@@ -6,17 +6,8 @@
 //                            kernel's per-lane addressing (16 loads of 16 bytes per lane), and folds them with XOR.
 //   probe_mfma_kernel        4 waves per workgroup; every wave issues independent v_mfma_f32_32x32x16_bf16 on
 //                            register operands with random mantissas, nothing else in the loop.
-#include <atomic>
-
 #include "st_internal.h"
-
-// plain loads, as in the decode kernels (-DST_PROBE_NT builds the probe with the non-temporal hint: on a working
-// set that partly fits the 256 MB memory-side cache the hint reads faster, on the decode step's 20 GB it is 4 % slower)
-#ifdef ST_PROBE_NT
-#define PROBE_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define PROBE_LOAD(p) (*(p))
-#endif
+#include "st_probe.h"
 
 namespace st {
 
@@ -32,24 +23,16 @@ __global__ __launch_bounds__(64, 4) void probe_paged_read_kernel(const unsigned 
         size_t pg[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) pg[u] = size_t(uint32_t((base + u) * 2654435761ull + 12345u + salt) & page_mask) * 4096;
-#ifdef ST_PROBE_FULL_LINES
-        const unsigned char* kp = pool + pg[n >> 3] + g4 * 256 + (n & 7) * 16;
-#else
         const unsigned char* kp = pool + pg[n >> 3] + g4 * 256 + (8 * ((n >> 2) & 1) + (n & 3)) * 16;
-#endif
         const unsigned char* vp = pool + pg[2 + (g4 >> 1)] + n * 32 + 16 * (g4 & 1);
         u32x4 t[16];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            t[2 * j] = PROBE_LOAD(reinterpret_cast<const u32x4*>(kp + j * 1024));
-#ifdef ST_PROBE_FULL_LINES
-            t[2 * j + 1] = PROBE_LOAD(reinterpret_cast<const u32x4*>(kp + j * 1024 + 128));
-#else
-            t[2 * j + 1] = PROBE_LOAD(reinterpret_cast<const u32x4*>(kp + j * 1024 + 64));
-#endif
+            t[2 * j] = *reinterpret_cast<const u32x4*>(kp + j * 1024);
+            t[2 * j + 1] = *reinterpret_cast<const u32x4*>(kp + j * 1024 + 64);
         }
 #pragma unroll
-        for (int db = 0; db < 8; ++db) t[8 + db] = PROBE_LOAD(reinterpret_cast<const u32x4*>(vp + db * 512));
+        for (int db = 0; db < 8; ++db) t[8 + db] = *reinterpret_cast<const u32x4*>(vp + db * 512);
 #pragma unroll
         for (int u = 0; u < 16; ++u) acc ^= t[u];
     }
@@ -109,24 +92,20 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sin
 
 using namespace st;
 
-extern "C" st_status st_probe_paged_read(const void* pool, size_t pool_bytes, int32_t n_waves, int32_t steps_per_wave,
-                                         uint32_t* sink, void* hip_stream) {
+extern "C" int32_t st_probe_paged_read(const void* pool, size_t pool_bytes, int32_t n_waves, int32_t steps_per_wave, uint32_t salt,
+                                       uint32_t* sink, void* hip_stream) {
     if (!pool || !sink) return fail(ST_ERR_INVALID_ARG, "st_probe_paged_read: null pointer");
     if (!aligned16(pool)) return fail(ST_ERR_INVALID_ARG, "st_probe_paged_read: pool must be 16-byte aligned");
     if (pool_bytes < 4096 || (pool_bytes & (pool_bytes - 1)) != 0 || pool_bytes > (size_t(1) << 43))
         return fail(ST_ERR_INVALID_ARG, "st_probe_paged_read: pool_bytes must be a power of two in [4 KiB, 8 TiB]");
     if (n_waves <= 0 || steps_per_wave <= 0) return fail(ST_ERR_INVALID_ARG, "st_probe_paged_read: bad sizes");
-    // every launch reads other pages than the one before (a decode step never finds its caches in the memory-side
-    // cache either): the page hash is shifted by a per-call salt
-    static std::atomic<uint32_t> calls{0};
-    const uint32_t salt = calls.fetch_add(1, std::memory_order_relaxed) * 0x9E3779B1u;
     hipLaunchKernelGGL(probe_paged_read_kernel, dim3((unsigned)n_waves), dim3(64), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const unsigned char*>(pool), uint32_t(pool_bytes / 4096 - 1), steps_per_wave, salt, sink);
+                       static_cast<const unsigned char*>(pool), uint32_t(pool_bytes / 4096 - 1), steps_per_wave, salt * 0x9E3779B1u, sink);
     ST_LAUNCH_CHECK("probe_paged_read_kernel");
     return ST_OK;
 }
 
-extern "C" st_status st_probe_mfma_bf16(int32_t n_workgroups, int32_t iterations, float* sink, void* hip_stream) {
+extern "C" int32_t st_probe_mfma_bf16(int32_t n_workgroups, int32_t iterations, float* sink, void* hip_stream) {
     if (!sink) return fail(ST_ERR_INVALID_ARG, "st_probe_mfma_bf16: null pointer");
     if (n_workgroups <= 0 || iterations <= 0) return fail(ST_ERR_INVALID_ARG, "st_probe_mfma_bf16: bad sizes");
     hipLaunchKernelGGL(probe_mfma_kernel, dim3((unsigned)n_workgroups), dim3(256), 0, static_cast<hipStream_t>(hip_stream), sink,

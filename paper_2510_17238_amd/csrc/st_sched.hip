@@ -184,7 +184,7 @@ struct Runner {
         hipLaunchKernelGGL(stage_in_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<u32x4*>(stg->q), reinterpret_cast<u32x4*>(stg->k),
                            reinterpret_cast<u32x4*>(stg->v), static_cast<const u32x4*>(job.rsn_q), static_cast<const u32x4*>(job.rsn_k),
                            static_cast<const u32x4*>(job.rsn_v), stg->step, stg->len, job.batch, q_pieces, kv_pieces);
-        st_dual_lens lens;
+        st_dual_lens lens = {};
         lens.src_visible_len = stg->vis;
         lens.rsn_len = stg->len;
         lens.q_len = 1;
@@ -237,7 +237,7 @@ struct Runner {
         }
         for (int j = 0; j < n; ++j) {
             const int64_t g = lay.step0[t] + j;
-            st_dual_lens lens;
+            st_dual_lens lens = {};
             lens.src_visible_len = vis_dev + int64_t(vis_unit) * job.batch;
             lens.rsn_len = len_dev + g * job.batch;
             lens.q_len = 1;

@@ -19,8 +19,8 @@ def lib():
     return st.load_library()
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "st.h")).read()
+def _declared_functions(header="st.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(st_[a-z0-9_]+)\s*\(", text)))
 
@@ -30,6 +30,18 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"st_rope_apply", "st_attn_prefill", "st_kv_append", "st_attn_decode_dual", "st_plan_create"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
+
+
+def test_probe_library_exports_its_header(lib):
+    """The machine probes of the benchmark live in a library of their own; libst.so does not carry them."""
+    import paper_2510_17238_amd as st
+    probe = st.load_probe_library()
+    names = _declared_functions("st_probe.h")
+    assert names == ["st_probe_mfma_bf16", "st_probe_paged_read"]
+    for name in names:
+        assert hasattr(probe, name), name
+        assert not hasattr(lib, name), name
+    assert probe.st_probe_mfma_bf16(0, 1, None, None) == 1 and probe.st_probe_paged_read(None, 4096, 1, 1, 0, None, None) == 1
 
 
 def test_version_and_error_string(lib):
@@ -85,30 +97,28 @@ def test_cache_argument_checks(lib):
     assert lib.st_kv_append(C.byref(bad), B.ST_SOURCE, fp, fp, None, 8, 1, 64, None) == 5
     bad = B._DualCacheStruct(cache(), cache(dtype=B.ST_F32))
     assert lib.st_kv_append(C.byref(bad), B.ST_REASONING, fp, fp, None, 8, 1, 64, None) == 5
-    lens = B._DualLensStruct(fake, fake, 9, 64, 64)
+    lens = B._DualLensStruct(fake, fake, 9, 64, 64, 0)
     # q_len 9 x group 4 > 32 rows
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 5
-    lens = B._DualLensStruct(fake, fake, 1, 64, 65)
+    lens = B._DualLensStruct(fake, fake, 1, 64, 65, 0)
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 4
-    lens = B._DualLensStruct(fake, fake, 1, 64, 64)
+    lens = B._DualLensStruct(fake, fake, 1, 64, 64, 0)
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, C.c_void_p(0x1100), 16, None) == 4
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, fp, 1 << 20, None) == 2
-    need = lib.st_decode_workspace_bytes(1, 8, 2, 128, 1, 64, 64)
+    need = lib.st_decode_workspace_bytes(1, 8, 2, 128, 1, 64, 64, 0)
     assert need >= 2 * 4 * (128 + 2) * 4
-    # the work unit of the decode step: pinned sizes change the workspace (more, shorter units need more slots), other
-    # values are ignored, and the size by launch shrinks the unit for small launches
-    prev = lib.st_decode_unit_set(128)
-    try:
-        w128 = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144)
-        assert lib.st_decode_unit_set(1024) == 128
-        w1024 = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144)
-        assert lib.st_decode_unit_set(100) == 1024 and lib.st_decode_unit_set(0) == 1024
-        auto_big = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144)
-        auto_small = lib.st_decode_workspace_bytes(1, 16, 8, 128, 1, 2048, 6144)
-        # 512-token units are always provided for; 128-token units need about four times the slots
-        assert w128 > 3 * w1024 and auto_big == w1024 and auto_small * 32 > 3 * auto_big
-    finally:
-        lib.st_decode_unit_set(prev)
+    # the work unit of the decode step is an argument: shorter units need more slots, a value that is no unit size gives 0
+    # bytes (and ST_ERR_INVALID_ARG from the step), and the size by launch shrinks the unit for small launches
+    w128 = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144, 128)
+    w1024 = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144, 1024)
+    auto_big = lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144, 0)
+    auto_small = lib.st_decode_workspace_bytes(1, 16, 8, 128, 1, 2048, 6144, 0)
+    # 512-token units are always provided for; 128-token units need about four times the slots
+    assert w128 > 3 * w1024 and auto_big == w1024 and auto_small * 32 > 3 * auto_big
+    assert lib.st_decode_workspace_bytes(32, 16, 8, 128, 1, 2048, 6144, 100) == 0
+    lens = B._DualLensStruct(fake, fake, 1, 64, 64, 100)
+    assert lib.st_attn_decode_dual(fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 1
+    assert b"unit_tokens" in lib.st_last_error()
     # the fused forms take the same checks, plus the rotation base
     assert lib.st_kv_append_rope(C.byref(good), B.ST_SOURCE, fp, fp, None, 8, 1, 65, 1.0e6, None) == 4
     assert lib.st_kv_append_rope(C.byref(good), B.ST_SOURCE, fp, fp, None, 8, 1, 64, 0.0, None) == 1
@@ -123,7 +133,7 @@ def test_cache_argument_checks(lib):
     assert ap(fp, None, fp, None, fp, C.byref(good), C.byref(lens), 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 1
     assert b"st_attn_decode_dual_append" in lib.st_last_error()
     assert ap(fp, None, fp, fp, fp, C.byref(good), C.byref(lens), 1, 7, 0.0, 0.0, fp, 1 << 20, None) == 2
-    two = B._DualLensStruct(fake, fake, 2, 64, 64)
+    two = B._DualLensStruct(fake, fake, 2, 64, 64, 0)
     assert ap(fp, None, fp, fp, fp, C.byref(good), C.byref(two), 1, 8, 0.0, 1.0e6, fp, 1 << 20, None) == 5
     # 8-bit caches: need their scale arrays; append (unfused) and decode up to 16 rows take them, nothing else does
     c8 = lambda **kw: cache(dtype=B.ST_FP8_E4M3, k_scale=fake, v_scale=fake, **kw)
@@ -134,10 +144,10 @@ def test_cache_argument_checks(lib):
     assert b"scale" in lib.st_last_error()
     assert lib.st_kv_append_rope(C.byref(eight), B.ST_SOURCE, fp, fp, None, 8, 1, 64, 1.0e6, None) == 5
     assert lib.st_attn_source_chunk(fp, None, fp, C.byref(eight), fp, None, 8, 64, 1, 8, 0.0, fp, 1 << 20, None) == 5
-    lens = B._DualLensStruct(fake, fake, 5, 64, 64)                                                  # 5 x group 4 = 20 rows
+    lens = B._DualLensStruct(fake, fake, 5, 64, 64, 0)                                                  # 5 x group 4 = 20 rows
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(eight), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 5
     assert b"16" in lib.st_last_error()
-    lens = B._DualLensStruct(fake, fake, 1, 64, 64)
+    lens = B._DualLensStruct(fake, fake, 1, 64, 64, 0)
     mixed = B._DualCacheStruct(c8(), cache())
     assert lib.st_attn_decode_dual(fp, None, fp, C.byref(mixed), C.byref(lens), 1, 8, 0.0, fp, 1 << 20, None) == 5
 

@@ -527,7 +527,7 @@ def test_kv_append_capacity(st):
     assert cs.appended_len.cpu().tolist() == [32, 32]
 
 
-def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0, rope_theta=None, fp8=False):
+def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len=1, src_extra=0, rope_theta=None, fp8=False, unit_tokens=0):
     if fp8:
         # 8-bit caches take rotated keys (the fused append is bf16 only); the fused QUERY rotation works on either
         caches, ref, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens, src_extra, fp8=True, row_exponents=(-4, 1))
@@ -537,7 +537,8 @@ def _check_decode(st, rng, batch, hq, hkv, d, src_lens, rsn_lens, src_vis, q_len
     tq = to_dev(q, "bf16")
     lse = torch.empty((batch, q_len, hq), dtype=torch.float32, device=DEV)
     vis_t = torch.from_numpy(src_vis.astype(np.int32)).to(DEV); rl_t = torch.from_numpy(rsn_lens.astype(np.int32)).to(DEV)
-    out = st.st_attn_decode_dual(tq, caches, vis_t, rl_t, int(max(src_lens)), int(max(rsn_lens)), lse=lse, rope_theta=rope_theta)
+    out = st.st_attn_decode_dual(tq, caches, vis_t, rl_t, int(max(src_lens)), int(max(rsn_lens)), lse=lse, rope_theta=rope_theta,
+                                 unit_tokens=unit_tokens)
     torch.cuda.synchronize()
     for b in range(batch):
         args = (q[b].astype(np.float64), ref[st.ST_SOURCE][0][b], ref[st.ST_SOURCE][1][b], ref[st.ST_REASONING][0][b],
@@ -599,13 +600,7 @@ def test_decode_every_unit_size(st, unit, fp8):
     pinned here on caches that span several units with ragged ends, and gives the same rows."""
     rng = np.random.Generator(np.random.PCG64(413))
     src_lens = np.array([1100, 129, 640]); rsn_lens = np.array([700, 1500, 127]); src_vis = np.array([1025, 128, 0])
-    prev = st.st_decode_unit_set(unit)
-    try:
-        assert st.st_decode_unit_set(unit) == unit
-        assert st.st_decode_unit_set(100) == unit                 # not a unit size: nothing changes
-        _check_decode(st, rng, 3, 4, 2, 128, src_lens, rsn_lens, src_vis, fp8=fp8)
-    finally:
-        st.st_decode_unit_set(prev)
+    _check_decode(st, rng, 3, 4, 2, 128, src_lens, rsn_lens, src_vis, fp8=fp8, unit_tokens=unit)
 
 
 # ------------------------------------------------------- 8-bit caches --
