@@ -2,19 +2,20 @@
 """Benchmark of the streaming-constrained attention path on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic input:
-  plan build -> RoPE(q), RoPE(k) -> streaming-mask prefill attention   (Qwen3-0.6B-shaped layer,
-  batch 4, 16/8 heads, D = 128, bf16, 32 source + 32 reasoning segments per sequence)
+  plan build -> RoPE(q, k) -> tile packing + streaming-mask prefill attention   (configs[3]: Qwen3-4B-shaped layer,
+  batch 8 x 16,384 tokens, 32/8 heads, D = 128, bf16, source segments of 64-192 and reasoning segments of 64-256 tokens)
   -> paged append of a 64-token source chunk (second stream) and of one reasoning token
   -> dual-cache decode of that token over the batch's own source / reasoning caches.
-`value` is the effective (unmasked) prefill FLOPs divided by the WHOLE step time.  The decode half
-of the metric is measured in the same run on the Qwen3-1.7B-shaped decode workload (28 layers,
-batch 32, source cache 2K + reasoning cache 1-6K, concurrent 64-token source append) and reported
-in the "decode" object as GB/s of algorithmic cache bytes.
+`value` is the effective (unmasked) prefill FLOPs divided by the WHOLE step time.  The decode half of the metric is
+measured in the same run on configs[4] (Qwen3-8B-shaped streaming step: 36 layers, 64 streams, source caches to 8K and
+reasoning caches to 16K tokens, a 32-token source chunk appended per layer beside 8 decoded tokens) and reported in the
+"decode" object as GB/s of algorithmic cache bytes.
 
-Further objects of the same line (all by default; --no-extras leaves them out, naming some runs only those):
-"source_chunk" (Alg. 1's prefill loop on the streaming shape), "prefill_long" (16K-token sequences), "decode_fp8"
-(8-bit caches), "prefill_backward" (gradients), "stream_session" (Alg. 1 end to end), "stream_step" (the configs[4] streaming step), "probes" (what the machine
-sustains for the two kernels' access pattern / instruction).
+Further objects of the same line (all by default; --no-extras leaves out those marked *): "stages" (every stage of the
+step timed alone, the HBM-bound ones with a roofline of their own), "prefill_small" (the same step on configs[1]),
+"decode_small" (configs[2]: 28 layers, batch 32, with its concurrent source appends), "source_chunk" (Alg. 1's prefill loop
+on the streaming shape), "decode_fp8"* (8-bit caches), "prefill_backward"* (gradients), "stream_session"* (Alg. 1 end to
+end), "probes"* (what the machine sustains for the two kernels' access pattern / instruction).
 
 Prints ONE JSON line.  All inputs are seeded, synthetic and resident in HBM before timing starts.
 """
@@ -34,10 +35,22 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
-# HBM bytes per launch of the two dominant kernels on the default workloads, from the FETCH_SIZE and
-# WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB copy (x2.000 and x1.000);
-# see profiles/hbm_traffic_prefill_cfg2_decode_cfg3.txt for the runs.
-MEASURED_TRAFFIC = {"prefill_mfma_pipe_kernel<128, 1>": 261.7e6 + 65.7e6, "decode_split16_kernel<128>": 702.5e6 + 4.4e6}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel.txt")
+
+
+def measured_traffic(key):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by what the counters read for a plain copy) of one kernel on
+    one workload, from the lines `traffic <key> fetch_bytes=.. write_bytes=..` of the tracked rocprofv3 summary; None if
+    the summary has no such line.  The figure is from the profiled run that wrote the summary, not from this run."""
+    try:
+        for l in open(TRAFFIC_PROFILE):
+            f = l.split()
+            if len(f) >= 4 and f[0] == "traffic" and f[1] == key:
+                kv = dict(x.split("=") for x in f[2:])
+                return float(kv["fetch_bytes"]) + float(kv["write_bytes"])
+    except OSError:
+        pass
+    return None
 
 
 def _median(xs):
@@ -85,9 +98,21 @@ def _time_launch_modes(torch, steps, graph, eager_step):
     return times, min(times, key=times.get)
 
 
-def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=False):
+def _event_ms(torch, fn, reps, warm=2):
+    """Mean duration of fn() (a few launches on the current stream) over `reps` calls, from events on that stream."""
+    for _ in range(warm):
+        fn()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record(); torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def bench_prefill_step(st, torch, W, cfg, steps, warmup, use_graph=True, fused_rope=False, stage_reps=10):
     dev = "cuda"
-    cfg = W.config2()
     hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     n, batch = cfg.n_tokens, cfg.batch
     g = torch.Generator(device=dev); g.manual_seed(cfg.seed)
@@ -98,7 +123,6 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
     pos = torch.from_numpy(cfg.positions).to(dev)
     q_rot = torch.empty_like(q); k_rot = torch.empty_like(k); out = torch.empty_like(q)
     plan_ws = torch.empty(st.st_plan_workspace_bytes(batch, n), dtype=torch.uint8, device=dev)
-    pre_ws = None
 
     # the batch's own caches: source / reasoning K, V of each sequence, paged with shuffled ids
     S = np.array([int(s.sum()) for s in cfg.src_lens]); R = np.array([int(r.sum()) for r in cfg.rsn_lens])
@@ -119,11 +143,13 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
             idx = perm[c0:c0 + int(lens[b])]
             kn[b, :int(lens[b])] = k_rot[idx]; vn[b, :int(lens[b])] = v[idx]
         st.st_kv_append(caches, which, kn, vn, torch.from_numpy(lens.astype(np.int32)).to(dev))
+        del kn, vn
     torch.cuda.synchronize()
     pairs = plan.visible_pairs()
     assert [int(x) for x in pairs] == cfg.closed_form_pairs()
     pre_ws = torch.empty(st.st_prefill_workspace_bytes(plan, hkv, d, st.ST_BF16), dtype=torch.uint8, device=dev)
     flops = 4.0 * d * hq * float(pairs.sum())
+    two_heads = (n // batch >= 8192) and (hq // hkv) % 2 == 0            # the library's own choice (st_plan_heads_per_workgroup)
     plan.destroy()
 
     len_s0 = cs.appended_len.clone(); len_r0 = cr.appended_len.clone()
@@ -146,12 +172,11 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
         side.wait_stream(main)
         with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
             st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk, stream=side)
+        p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
         if fused_rope:
             # rotation inside the attention call: keys on their way into the key tiles, queries as they are loaded
-            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
             st.st_attn_prefill_rope(q, k, v, pos, cfg.theta, p, out=out, workspace=pre_ws)
         else:
-            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
             st.st_rope_apply_qk(q, k, pos, cfg.theta, q_out=q_rot, k_out=k_rot)      # queries and keys in one launch
             st.st_attn_prefill(q_rot, k_rot, v, p, out=out, workspace=pre_ws)
         # the decoded token: key rotated on its way into the reasoning cache, query rotated inside the decode
@@ -165,7 +190,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
     for _ in range(warmup):
         plans.append(step(None))
     torch.cuda.synchronize()
-    # kernel-only duration of the attention kernel (HIP events on its launch stream), from eager steps
+    # kernel-only durations of the packing and the attention kernel (HIP events on their launch stream), from eager steps
     st.st_profile_enable(True)
     n_prof = min(steps, 10)
     for i in range(n_prof):
@@ -173,8 +198,24 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
     torch.cuda.synchronize()
     st.st_profile_enable(False)
     kern_ms, n_rec = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    pack_ms, _ = st.st_profile_read(st.ST_PROF_TILE_PACK)
     st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
     assert n_rec == n_prof
+    # every stage alone (events on the stream; the launches of one stage back to back)
+    p_stage = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
+    plans.append(p_stage)
+    stage_ms = {
+        "plan": _event_ms(torch, lambda: plans.append(st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)), stage_reps),
+        "rope_qk": _event_ms(torch, lambda: st.st_rope_apply_qk(q, k, pos, cfg.theta, q_out=q_rot, k_out=k_rot), stage_reps),
+        "append_source_chunk": _event_ms(torch, lambda: (cs.appended_len.copy_(len_s0),
+                                                         st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk)), stage_reps),
+        "length_reset_only": _event_ms(torch, lambda: cs.appended_len.copy_(len_s0), stage_reps),
+        "decode_token_with_append": _event_ms(torch, lambda: (cr.appended_len.copy_(len_r0),
+                                                              st.st_attn_decode_dual_append(q_tok, k_tok, v_tok, caches, src_vis, rsn_len, max_s, max_r, theta_base=cfg.theta,
+                                                                                            out=out_tok, workspace=dec_ws)), stage_reps),
+        "tile_pack": pack_ms, "attention": kern_ms,
+    }
+    stage_ms["append_source_chunk"] = max(stage_ms["append_source_chunk"] - stage_ms.pop("length_reset_only"), 1e-6)
     # the timed steps, two ways: the whole step (two streams) recorded once into a HIP graph and replayed -- every
     # replay first checked against the eager step, side stream included -- and as plain launches; the faster one is
     # the step time, both are reported (graphs with a second branch replay slowly on this ROCm)
@@ -195,6 +236,7 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
                     raise RuntimeError("graph replay did not run the source append")
                 plans.append(step(None))
                 torch.cuda.synchronize()
+            del ref_out, ref_tok
             mode = "hip-graph"
         except Exception as exc:                           # noqa: BLE001
             print(f"bench.py: HIP graph capture not used ({exc}); timing eager launches", file=sys.stderr)
@@ -202,13 +244,17 @@ def bench_prefill_step(st, torch, W, steps, warmup, use_graph=True, fused_rope=F
     times, mode = _time_launch_modes(torch, steps, graph, lambda: plans.append(step(None)))
     for p in plans:
         p.destroy()
+    elt = 2                                                 # bytes per bf16 element
+    stage_bytes = {"rope_qk": 2.0 * n * (hq + hkv) * d * elt,                          # read + write of q and k
+                   "tile_pack": 2.0 * 2.0 * n * hkv * d * elt,                          # k, v read; K tiles, V^T tiles written
+                   "append_source_chunk": 2.0 * 2.0 * batch * chunk * hkv * d * elt}    # k, v rows read and stored
     return {"cfg": cfg, "flops": flops, "sec_per_step": times[mode], "prefill_kernel_ms": kern_ms, "n_tokens": n, "mode": mode,
-            "sec_per_step_by_launch": times}
+            "sec_per_step_by_launch": times, "stage_ms": stage_ms, "stage_bytes": stage_bytes, "two_heads": two_heads}
 
 
-def bench_prefill_long(st, torch, W, reps):
-    """Attention stage alone on configs[3] (8 x 16,384 tokens, 32 q / 8 kv heads): the size at which
-    st_attn_prefill takes its two-heads-per-workgroup kernel."""
+def bench_prefill_zero_inputs(st, torch, W, reps):
+    """The attention stage of configs[3] on random inputs and, the same launches, on ALL-ZERO inputs: the same instruction
+    stream with no operand bits toggling -- how much of the time is the power limit and not the schedule."""
     dev = "cuda"
     cfg = W.config4a()
     hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
@@ -219,34 +265,26 @@ def bench_prefill_long(st, torch, W, reps):
     seg = torch.from_numpy(cfg.segment_ids).to(dev); strm = torch.from_numpy(cfg.stream_ids).to(dev)
     pos = torch.from_numpy(cfg.positions).to(dev)
     plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
-    pairs = plan.visible_pairs()
-    assert [int(x) for x in pairs] == cfg.closed_form_pairs()
-    flops = 4.0 * d * hq * float(pairs.sum())
+    flops = 4.0 * d * hq * float(plan.visible_pairs().sum())
     out = torch.empty_like(q)
     ws = torch.empty(st.st_prefill_workspace_bytes(plan, hkv, d, st.ST_BF16), dtype=torch.uint8, device=dev)
-    for _ in range(2):
-        st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
-    torch.cuda.synchronize()
-    st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
-    st.st_profile_enable(True)
-    for _ in range(reps):
-        st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
-    torch.cuda.synchronize()
-    st.st_profile_enable(False)
-    ms, cnt = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
-    # the same launches on all-zero inputs: the same instruction stream with no bits toggling in the operands --
-    # how much of the time is the power limit and not the schedule
-    q.zero_(); k.zero_(); v.zero_()
-    st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
-    torch.cuda.synchronize()
-    st.st_profile_enable(True)
-    for _ in range(reps):
-        st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
-    torch.cuda.synchronize()
-    st.st_profile_enable(False)
-    zero_ms, _ = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    res = {}
+    for name in ("random", "zero"):
+        if name == "zero":
+            q.zero_(); k.zero_(); v.zero_()
+        for _ in range(2):
+            st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+        st.st_profile_enable(True)
+        for _ in range(reps):
+            st.st_attn_prefill(q, k, v, plan, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        st.st_profile_enable(False)
+        res[name], _ = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+        st.st_profile_read(st.ST_PROF_TILE_PACK)
     plan.destroy()
-    return {"kernel_ms": ms, "flops": flops, "n_tokens": n, "launches": cnt, "zero_input_kernel_ms": zero_ms}
+    return {"kernel_ms": res["random"], "zero_input_kernel_ms": res["zero"], "flops": flops}
 
 
 def bench_stream_session(st, torch, W, time_scale):
@@ -316,11 +354,11 @@ def bench_probes(st, torch):
     # the decode kernel's launch on configs[2]: about 2,800 one-wave units of up to 1024 tokens x 4 KB;
     # and a launch four times as large
     for name, waves, steps in (("paged_read_decode_sized", 2816, 16), ("paged_read_large", 11264, 16)):
-        for _ in range(3):
-            st.st_probe_paged_read(pool, waves, steps, sink)
+        for i in range(3):
+            st.st_probe_paged_read(pool, waves, steps, 1000 + i, sink)
         e0.record()
-        for _ in range(20):
-            st.st_probe_paged_read(pool, waves, steps, sink)
+        for i in range(20):
+            st.st_probe_paged_read(pool, waves, steps, i, sink)              # (other pages every launch)
         e1.record(); torch.cuda.synchronize()
         res[name] = {"bytes_per_launch": waves * steps * 16384, "GBps": round(waves * steps * 16384 * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)}
     st.st_probe_mfma_bf16(512, 2000, fsink)
@@ -459,12 +497,25 @@ def bench_stream_step(st, torch, W, steps, warmup, distinct_layers=None, use_gra
             graph = None
     times, mode = _time_launch_modes(torch, steps, graph, step)
     dt = times[mode]
+    # kernel-only duration of the split kernel (HIP events on the launch stream), from one eager step; and the source
+    # append of one layer alone
+    st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    st.st_profile_enable(True)
+    step(); torch.cuda.synchronize()
+    st.st_profile_enable(False)
+    split_ms, n_rec = st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    assert n_rec == n_tok * L
+    append_ms = _event_ms(torch, lambda: (len_s_all[0].copy_(src_vis),
+                                          st.st_kv_append_rope(layers[0], st.ST_SOURCE, k_src, v_src, 1.0e6, host_len_upper_bound=max_s + shp.src_append)), 20)
+    append_ms -= _event_ms(torch, lambda: len_s_all[0].copy_(src_vis), 20)
     tokens_read = float(sum((src0 + rsn0 + t + 1).sum() for t in range(n_tok)))
     read_bytes = tokens_read * hkv * d * 2 * 2 * L
     append_bytes = float(B * (shp.src_append + n_tok) * hkv * d * 2 * 2 * 2 * L)
     del layers
     return {"sec_per_step": dt, "read_bytes": read_bytes, "append_bytes": append_bytes, "mode": mode, "distinct_layers": n_phys,
-            "resident_gb": per_layer * n_phys / 1e9, "n_tok": n_tok, "sec_per_step_by_launch": times}
+            "resident_gb": per_layer * n_phys / 1e9, "n_tok": n_tok, "sec_per_step_by_launch": times, "split_kernel_ms": split_ms,
+            "bytes_per_launch": read_bytes / (n_tok * L), "append_layer_ms": max(append_ms, 1e-6),
+            "append_layer_bytes": float(B * shp.src_append * hkv * d * 2 * 2 * 2), "n_layers": L, "batch": B}
 
 
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8=False):
@@ -591,6 +642,13 @@ def bench_source_chunk(st, torch, W, steps, warmup):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    st.st_profile_read(st.ST_PROF_SOURCE_CHUNK)
+    st.st_profile_enable(True)
+    for _ in range(min(steps, 10)):
+        step()
+    torch.cuda.synchronize()
+    st.st_profile_enable(False)
+    kern_ms, _ = st.st_profile_read(st.ST_PROF_SOURCE_CHUNK)
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
@@ -598,61 +656,102 @@ def bench_source_chunk(st, torch, W, steps, warmup):
     dt = (time.perf_counter() - t0) / steps
     tok = shp.src_visible_len.astype(np.float64) + n_new
     flops = 4.0 * d * hq * float((n_new * tok - n_new * (n_new - 1) / 2).sum())      # causal inside the chunk
-    return {"ms_per_step": dt * 1e3, "cache_bytes": float(tok.sum()) * 2 * hkv * d * 2, "flops": flops, "batch": B, "n_new": n_new}
+    return {"ms_per_step": dt * 1e3, "cache_bytes": float(tok.sum()) * 2 * hkv * d * 2, "flops": flops, "batch": B, "n_new": n_new,
+            "kernel_ms": kern_ms}
 
 
-def cpu_baseline(W, O, flops_per_pair_head):
-    """The fp64 oracle, as it stands, on sequence 0 of the prefill workload (all heads)."""
-    cfg = W.config2()
-    q, k, v = cfg.tensors()
-    e = int(cfg.cu_seqlens[-1])
+def cpu_baseline(W, O):
+    """The fp64 oracle, as it stands, on a bounded sample of the headline workload (configs[3]): sequence 0, the two query
+    heads of KV head 0, interleaved quarters of its query rows until 10 s are spent (RoPE of the slice included)."""
+    cfg = W.config4a()
+    s, e = int(cfg.cu_seqlens[0]), int(cfg.cu_seqlens[1])
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 1000))
+    n, d = e - s, cfg.head_dim
+    q = W.normal(rng, (n, 2, d), "bf16"); k = W.normal(rng, (n, 1, d), "bf16"); v = W.normal(rng, (n, 1, d), "bf16")
+    stream, seg, pos = cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e]
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    t0 = time.perf_counter()
-    qr = O.rope(q[:e], cfg.positions[:e], cfg.theta); kr = O.rope(k[:e], cfg.positions[:e], cfg.theta)
-    O.attention_varlen(qr, kr, v[:e], cfg.stream_ids[:e], cfg.segment_ids[:e], cfg.positions[:e], cfg.cu_seqlens)
-    dt = time.perf_counter() - t0
-    fl = flops_per_pair_head * cfg.n_q_heads * sum(cfg.closed_form_pairs())
+    # rows 0, 4, 8, ... first, then 1, 5, 9, ... and so on: every pass has the sequence's mix of row lengths; passes
+    # stop once 10 s are spent (at most the four that cover every row)
+    dt, vis, n_rows, passes = 0.0, 0, 0, 0
+    for off in range(4):
+        rows = np.arange(off, n, 4)
+        t0 = time.perf_counter()
+        qr = O.rope(q, pos, cfg.theta); kr = O.rope(k, pos, cfg.theta)
+        O.attention_dense(qr, kr, v, stream, seg, pos, rows=rows)
+        dt += time.perf_counter() - t0
+        vis += int(O.mask_rows(stream, seg, pos, rows).sum())             # visible pairs of the sampled rows
+        n_rows += len(rows); passes += 1
+        if dt >= 10.0:
+            break
+    fl = 4.0 * d * 2 * vis
+    whole = cfg.closed_form_pairs()
+    total_pairs = float(sum(whole)) * cfg.n_q_heads
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"the whole prefill batch ({cfg.batch} sequences, {e} tokens, all {cfg.n_q_heads} heads): RoPE + dense-mask fp64 attention, {dt:.1f} s"}
+            "sample": f"configs[3], sequence 0 ({n} tokens), the 2 query heads of KV head 0, {passes} of 4 interleaved quarters of its "
+                      f"query rows ({n_rows} rows, {vis} visible pairs per head): RoPE + dense-mask fp64 attention in {dt:.1f} s; "
+                      f"extrapolated per visible pair, the whole batch (8 sequences x 32 heads, {total_pairs:.3g} pairs) would take "
+                      f"{dt * total_pairs / (2.0 * vis) / 60:.0f} min on these cores"}
+
+
+def _hbm_roofline(kernel, nbytes, ms, traffic_key=None, note=None):
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    r = {"kernel": kernel, "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+         "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": measured_traffic(traffic_key) if traffic_key else None,
+         "avg_kernel_ms": round(ms, 5), "algorithmic_bytes_per_launch": nbytes}
+    if note:
+        r["note"] = note
+    return r
+
+
+def _prefill_objects(pre, name, fused_rope):
+    """(step TFLOP/s, roofline object of the attention kernel, stages object) of one prefill step result."""
+    cfg = pre["cfg"]
+    tflops_step = pre["flops"] / pre["sec_per_step"] / 1e12
+    tflops_kernel = pre["flops"] / (pre["prefill_kernel_ms"] * 1e-3) / 1e12
+    kern = f"prefill_attn_kernel<{cfg.head_dim}, {2 if pre['two_heads'] else 1}, {'true' if fused_rope else 'false'}>"
+    roof = {"kernel": kern, "bound": "mfma", "achieved": round(tflops_kernel, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(f"prefill_attn_kernel@{name}"),
+            "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4), "algorithmic_flops_per_launch": pre["flops"]}
+    ms = pre["stage_ms"]
+    stages = {"note": "every stage of the step alone, back-to-back launches timed with events on the launch stream; tile_pack and attention "
+                      "from events around the kernel inside st_attn_prefill during whole steps",
+              "ms": {k: round(v, 5) for k, v in ms.items()},
+              "rope_qk": {"roofline": _hbm_roofline("rope_qk_kernel (st_rope_apply_qk: q and k of all tokens, read + write)", pre["stage_bytes"]["rope_qk"],
+                                                    ms["rope_qk"], f"rope_qk_kernel@{name}")},
+              "tile_pack": {"roofline": _hbm_roofline("tile_pack_kernel (k, v rows gathered into K tiles and V^T tiles)", pre["stage_bytes"]["tile_pack"],
+                                                      ms["tile_pack"], f"tile_pack_kernel@{name}")},
+              "append_source_chunk": {"roofline": _hbm_roofline("kv_append_kernel (64-token source chunk per sequence, alone on the GPU)",
+                                                                pre["stage_bytes"]["append_source_chunk"], ms["append_source_chunk"], None,
+                                                                "a launch of a few MB: bound by its own latency, not by bandwidth")}}
+    return tflops_step, roof, stages
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--decode-steps", type=int, default=None, help="steps of the 28-layer decode workload (default: min(steps, 10))")
+    ap.add_argument("--stream-steps", type=int, default=3, help="steps of the configs[4] streaming step (8 decoded tokens x 36 layers each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="leave out every decode leg (configs[4], configs[2], source chunk)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays of the steps")
     ap.add_argument("--fused-rope", action="store_true",
-                    help="prefill step: st_attn_prefill_rope on unrotated q, k instead of st_rope_apply (beside the plan build) + "
-                         "st_attn_prefill; measured slower in this step, where the rotations hide behind the plan build")
-    ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the decode workload (for profiling)")
-    ap.add_argument("--long-prefill", action="store_true",
-                    help="also time the attention kernel on configs[3] (8 x 16,384 tokens) and report it under 'prefill_long'")
-    ap.add_argument("--probes", action="store_true",
-                    help="also run the machine probes (paged read with the decode kernel's access pattern, register-only "
-                         "bf16 MFMA loop) and report them under 'probes'")
-    ap.add_argument("--fp8-cache", action="store_true",
-                    help="also run the decode workload with 8-bit (E4M3) caches and report it under 'decode_fp8'")
-    ap.add_argument("--backward", action="store_true",
-                    help="also time st_attn_prefill_bwd on configs[1] and report it under 'prefill_backward'")
-    ap.add_argument("--stream-session", action="store_true",
-                    help="also run one Alg. 1 session (streaming / alternating / batch schedules) and report it under 'stream_session'")
-    ap.add_argument("--stream-step", action="store_true",
-                    help="also run the configs[4] streaming step (36 layers, 64 streams: a 32-token source chunk appended per layer "
-                         "beside 8 decoded tokens) and report it under 'stream_step'; allocates the caches it needs (about 130 GB)")
+                    help="prefill steps: st_attn_prefill_rope on unrotated q, k instead of st_rope_apply_qk + st_attn_prefill")
+    ap.add_argument("--decode-layers", type=int, default=None, help="override the 28 layers of the configs[2] decode workload (for profiling)")
+    ap.add_argument("--only", default=None,
+                    help="comma-separated legs to run besides the headline step, e.g. 'decode,decode_small' (for profiling); names: decode, "
+                         "prefill_small, decode_small, source_chunk, decode_fp8, prefill_backward, stream_session, probes, power_check")
+    ap.add_argument("--no-headline", action="store_true", help="skip the configs[3] step (for profiling single legs); prints what was asked for")
     ap.add_argument("--stream-step-layers", type=int, default=None,
-                    help="distinct per-layer caches of --stream-step (default: all 36 if memory allows; fewer are cycled)")
-    ap.add_argument("--stream-time-scale", type=float, default=0.01, help="compression of the arrival times of --stream-session")
+                    help="distinct per-layer caches of the configs[4] step (default: all 36 if memory allows; fewer are cycled)")
+    ap.add_argument("--stream-time-scale", type=float, default=0.01, help="compression of the arrival times of the stream session")
     ap.add_argument("--no-extras", action="store_true",
-                    help="only the prefill step, the decode workload and the source chunk.  Without this flag, and when none of "
-                         "--long-prefill / --probes / --fp8-cache / --backward / --stream-session / --stream-step is given, ALL of them run")
+                    help="only the headline step, the two decode workloads, the configs[1] step and the source chunk")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -676,82 +775,123 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": a.numel() * 2, "bytes_written_per_copy": a.numel() * 2, "copies": 5}))
         return
-    pre = bench_prefill_step(st, torch, W, args.steps, args.warmup, not args.no_graph, args.fused_rope)
-    cfg = pre["cfg"]
-    tflops_step = pre["flops"] / pre["sec_per_step"] / 1e12
-    tflops_kernel = pre["flops"] / (pre["prefill_kernel_ms"] * 1e-3) / 1e12
-    line = {
-        "metric": "streaming-mask prefill TFLOP/s + dual-cache decode GB/s, % of MI355X peak",
-        "value": round(tflops_step, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(pre["sec_per_step"] * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": pre["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in pre["sec_per_step_by_launch"].items()},
-        "config": {"workload": "configs[1]: Qwen3-0.6B-shaped layer, batch 4, 16 q / 8 kv heads, head_dim 128, bf16, "
-                               "32 source (24-64 tok) + 32 reasoning (32-128 tok) segments per sequence, interleaved; "
-                               "step = plan + RoPE (" + ("inside st_attn_prefill_rope" if args.fused_rope else "st_rope_apply on q and k") +
-                               ") + streaming-mask prefill + paged append (64-token source chunk, 1 reasoning "
-                               "token) + dual-cache decode of one token",
-                   "n_tokens": pre["n_tokens"], "effective_flops_per_step": pre["flops"]},
-        "prefill_pct_of_peak": round(100.0 * tflops_kernel / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 1>", "bound": "mfma", "achieved": round(tflops_kernel, 3),
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_kernel / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC["prefill_mfma_pipe_kernel<128, 1>"], "avg_kernel_ms": round(pre["prefill_kernel_ms"], 4)},
-    }
-    if not args.no_decode:
-        dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
-        dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph)
-        gbps_step = dec["bytes_per_step"] / dec["sec_per_step"] / 1e9
-        gbps_kernel = dec["bytes_per_layer"] / (dec["layer_decode_ms"] * 1e-3) / 1e9
-        shp = dec["shape"]
-        line["decode"] = {
-            "workload": "configs[2]: Qwen3-1.7B-shaped decode, 28 layers, batch 32, 16 q / 8 kv heads, head_dim 128, bf16, "
-                        "source cache 2048 + reasoning cache U[1024,6144], 16-token pages (shuffled), one token per step, "
-                        "concurrent 64-token source append per layer on a second stream",
-            "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "launch": dec["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in dec["sec_per_step_by_launch"].items()}, "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
-            "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
-            "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
-            "roofline": {"kernel": "decode_split16_kernel<128> (one layer)", "bound": "hbm",
-                         "achieved": round(gbps_kernel, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                         "frac": round(gbps_kernel / PEAK_HBM_GBPS, 4), "traffic": MEASURED_TRAFFIC["decode_split16_kernel<128>"],
-                         "avg_kernel_ms": round(dec["layer_decode_ms"], 4)},
-        }
-    if not args.no_decode:
-        sc = bench_source_chunk(st, torch, W, min(args.steps, 20), min(args.warmup, 3))
-        line["source_chunk"] = {
-            "workload": "configs[4] source side, one layer: batch 64, 32 q / 8 kv heads, 32-token chunk appended to source caches "
-                        "U[1024,8192] (16-token pages) and attended causally over them (Alg. 1 prefill loop)",
-            "ms_per_step": round(sc["ms_per_step"], 4), "tflops": round(sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12, 2),
-            "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
-            "pct_of_bf16_peak": round(100.0 * sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
-            "note": "append + attention; the 128 (token, head) rows of a sequence and KV head are one workgroup (4 waves x 32 rows) "
-                    "that shares the cache pages through LDS"}
+    legs = ["decode", "prefill_small", "decode_small", "source_chunk"]
+    if not args.no_extras:
+        legs += ["decode_fp8", "prefill_backward", "stream_session", "probes", "power_check"]
+    if args.only is not None:
+        legs = [x for x in args.only.split(",") if x]
+    if args.no_decode:
+        legs = [x for x in legs if x not in ("decode", "decode_small", "source_chunk", "decode_fp8")]
+    use_graph = not args.no_graph
+    rope_text = "inside st_attn_prefill_rope" if args.fused_rope else "st_rope_apply_qk on q and k"
+    step_text = ("step = plan + RoPE (" + rope_text + ") + tile packing + streaming-mask prefill + paged append (64-token source chunk "
+                 "per sequence on a second stream, 1 reasoning token) + dual-cache decode of one token over the batch's own caches")
+    line = {"metric": "streaming-mask prefill TFLOP/s + dual-cache decode GB/s, % of MI355X peak"}
+    if not args.no_headline:
+        pre = bench_prefill_step(st, torch, W, W.config4a(), args.steps, args.warmup, use_graph, args.fused_rope)
+        tflops_step, roof, stages = _prefill_objects(pre, "cfg4a", args.fused_rope)
+        line.update({
+            "value": round(tflops_step, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(pre["sec_per_step"] * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "launch": pre["mode"],
+            "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in pre["sec_per_step_by_launch"].items()},
+            "config": {"workload": "configs[3] (the length-pinned reading, 4a): Qwen3-4B-shaped layer, batch 8 x 16,384 tokens, 32 q / 8 kv heads, "
+                                   "head_dim 128, bf16, source segments of 64-192 tokens interleaved with reasoning segments of 64-256 tokens; " + step_text,
+                       "n_tokens": pre["n_tokens"], "effective_flops_per_step": pre["flops"]},
+            "prefill_pct_of_peak": round(100.0 * roof["frac"], 2), "roofline": roof, "stages": stages})
+        del pre
+        gc.collect(); torch.cuda.empty_cache()
+    else:
+        line.update({"value": None, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
+                     "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "config": {"workload": "legs only: " + ",".join(legs)}})
     # the paper's own latency figures for context (Table 4, "Efficiency evaluation on Qwen3-4B": whole model, 100
     # GSM-Symbolic samples, input read at 150 words per minute); its text names no GPU
     line["paper_reference"] = {
         "source": "Table 4 (Qwen3-4B, whole model, another machine: context, not a target)", "hardware": "not stated in the paper",
         "prefill_s_per_sentence": {"streaming": 0.041, "batch": 0.052}, "decode_s_per_token": {"streaming": 0.037, "batch": 0.039},
         "decoded_tokens": {"streaming": 439, "batch": 436}, "first_token_latency_s": {"streaming": 6.231, "batch": 28.003}}
-    # the additional legs: those asked for, or all of them when none is named
-    named = args.long_prefill or args.probes or args.fp8_cache or args.backward or args.stream_session or args.stream_step
-    if not named and not args.no_extras:
-        args.long_prefill = args.probes = args.fp8_cache = args.backward = args.stream_session = args.stream_step = True
-    if args.probes:
+
+    if "decode" in legs:
+        with _leg(line, "decode", torch):
+            ss = bench_stream_step(st, torch, W, args.stream_steps, 1, args.stream_step_layers, use_graph)
+            gbps = ss["read_bytes"] / ss["sec_per_step"] / 1e9
+            line["decode"] = {
+                "workload": "configs[4]: Qwen3-8B-shaped end-to-end streaming step, 36 layers, 64 streams, 32 q / 8 kv heads, head_dim 128, "
+                            "bf16, source caches U[1024,8192] and reasoning caches U[2048,16384] tokens in 16-token pages (shuffled); per "
+                            "step every layer appends a 32-token source chunk on a second stream while 8 reasoning tokens are decoded one "
+                            "after the other through all layers (st_attn_decode_dual_append: store the token, attend over both caches)",
+                "value": round(gbps, 1), "unit": "GB/s", "pct_of_peak": round(100.0 * gbps / PEAK_HBM_GBPS, 2), "steps": args.stream_steps,
+                "ms_per_step": round(ss["sec_per_step"] * 1e3, 2), "ms_per_token": round(ss["sec_per_step"] * 1e3 / ss["n_tok"], 2),
+                "algorithmic_read_bytes_per_step": ss["read_bytes"], "append_bytes_per_step": ss["append_bytes"], "launch": ss["mode"],
+                "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ss["sec_per_step_by_launch"].items()},
+                "distinct_layer_caches": ss["distinct_layers"], "resident_cache_gb": round(ss["resident_gb"], 1),
+                "tokens_per_s": round(ss["batch"] * ss["n_tok"] / ss["sec_per_step"], 1),
+                "roofline": _hbm_roofline("decode_split16_kernel<128> (one layer, one token of all 64 streams)", ss["bytes_per_launch"],
+                                          ss["split_kernel_ms"], "decode_split16_kernel@cfg5"),
+                "append": {"roofline": _hbm_roofline("kv_append_kernel with rotation (32-token source chunk of 64 streams, one layer, alone on the GPU)",
+                                                     ss["append_layer_bytes"], ss["append_layer_ms"], None,
+                                                     "17 MB per launch: bound by its own latency, not by bandwidth")}}
+            del ss
+            gc.collect(); torch.cuda.empty_cache()
+    if "prefill_small" in legs:
+        with _leg(line, "prefill_small", torch):
+            ps = bench_prefill_step(st, torch, W, W.config2(), args.steps, args.warmup, use_graph, args.fused_rope)
+            tf, roof, stages = _prefill_objects(ps, "cfg2", args.fused_rope)
+            line["prefill_small"] = {
+                "workload": "configs[1]: Qwen3-0.6B-shaped layer, batch 4, 16 q / 8 kv heads, head_dim 128, bf16, 32 source (24-64 tok) + 32 "
+                            "reasoning (32-128 tok) segments per sequence, interleaved; " + step_text,
+                "value": round(tf, 3), "unit": "TFLOP/s", "ms_per_step": round(ps["sec_per_step"] * 1e3, 4), "launch": ps["mode"],
+                "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ps["sec_per_step_by_launch"].items()},
+                "n_tokens": ps["n_tokens"], "effective_flops_per_step": ps["flops"], "roofline": roof, "stages": stages}
+            del ps
+    dec = None
+    if "decode_small" in legs:
+        with _leg(line, "decode_small", torch):
+            dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
+            dec = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, use_graph)
+            gbps_step = dec["bytes_per_step"] / dec["sec_per_step"] / 1e9
+            line["decode_small"] = {
+                "workload": "configs[2]: Qwen3-1.7B-shaped decode, 28 layers, batch 32, 16 q / 8 kv heads, head_dim 128, bf16, "
+                            "source cache 2048 + reasoning cache U[1024,6144], 16-token pages (shuffled), one token per step, "
+                            "concurrent 64-token source append per layer on a second stream",
+                "value": round(gbps_step, 1), "unit": "GB/s", "steps": dsteps, "launch": dec["mode"],
+                "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in dec["sec_per_step_by_launch"].items()},
+                "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
+                "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
+                "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
+                "roofline": _hbm_roofline("decode_split16_kernel<128> (one layer)", dec["bytes_per_layer"], dec["layer_decode_ms"],
+                                          "decode_split16_kernel@cfg3")}
+    if "source_chunk" in legs:
+        with _leg(line, "source_chunk", torch):
+            sc = bench_source_chunk(st, torch, W, min(args.steps, 20), min(args.warmup, 3))
+            # 125 flop per cache byte: below the ridge (312 flop / byte), so the roof is the HBM one
+            line["source_chunk"] = {
+                "workload": "configs[4] source side, one layer: batch 64, 32 q / 8 kv heads, 32-token chunk appended to source caches "
+                            "U[1024,8192] (16-token pages) and attended causally over them (Alg. 1 prefill loop)",
+                "ms_per_step": round(sc["ms_per_step"], 4), "tflops": round(sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12, 2),
+                "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
+                "roofline": _hbm_roofline("chunk_split_lds_kernel<128> (the cache read once)", sc["cache_bytes"], sc["kernel_ms"], None,
+                                          f"{sc['flops'] / sc['cache_bytes']:.0f} flop per cache byte, below the ridge of 312: HBM is the roof; the kernel's "
+                                          f"matrix rate is {sc['flops'] / (sc['kernel_ms'] * 1e-3) / 1e12:.0f} TFLOP/s"),
+                "note": "append + attention; the 128 (token, head) rows of a sequence and KV head are one workgroup (4 waves x 32 rows) "
+                        "that shares the cache pages through LDS"}
+    if "probes" in legs:
         with _leg(line, "probes", torch):
             line["probes"] = bench_probes(st, torch)
-    if args.fp8_cache and not args.no_decode:
+    if "decode_fp8" in legs:
         with _leg(line, "decode_fp8", torch):
-            d8 = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, not args.no_graph, fp8=True)
+            dsteps = args.decode_steps if args.decode_steps is not None else min(args.steps, 10)
+            d8 = bench_decode(st, torch, W, dsteps, min(args.warmup, 3), args.decode_layers, use_graph, fp8=True)
             g8_step = d8["bytes_per_step"] / d8["sec_per_step"] / 1e9
-            g8_kernel = d8["bytes_per_layer"] / (d8["layer_decode_ms"] * 1e-3) / 1e9
             line["decode_fp8"] = {
                 "workload": "configs[2] with both caches stored in 8 bits (E4M3 codes + one fp32 power-of-two scale per key row and per "
-                            "value row: 264 B instead of 512 B per cached token and KV head); same step as 'decode'",
-                "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in d8["sec_per_step_by_launch"].items()},
+                            "value row: 264 B instead of 512 B per cached token and KV head); same step as 'decode_small'",
+                "value": round(g8_step, 1), "unit": "GB/s", "steps": dsteps, "launch": d8["mode"],
+                "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in d8["sec_per_step_by_launch"].items()},
                 "ms_per_step": round(d8["sec_per_step"] * 1e3, 4), "algorithmic_bytes_per_step": d8["bytes_per_step"],
-                "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3),
-                "roofline": {"kernel": "decode_split16_fp8_kernel<128> (one layer)", "bound": "hbm", "achieved": round(g8_kernel, 1),
-                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g8_kernel / PEAK_HBM_GBPS, 4), "traffic": None,
-                             "avg_kernel_ms": round(d8["layer_decode_ms"], 4)}}
-    if args.backward:
+                "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3) if dec else None,
+                "roofline": _hbm_roofline("decode_split16_fp8_kernel<128> (one layer)", d8["bytes_per_layer"], d8["layer_decode_ms"], None)}
+    if "prefill_backward" in legs:
         with _leg(line, "prefill_backward", torch):
             bw = bench_prefill_backward(st, torch, W, 10)
             tf = bw["flops"] / (bw["ms"] * 1e-3) / 1e12
@@ -769,39 +909,21 @@ def main():
                              "traffic": None,
                              "note": "algorithmic = 5 products of 2 D flop per visible (query, key, head) triple (2.5x the forward); the two "
                                      "kernels execute 7 (scores and dP are recomputed on the key side); executed_tflops counts those"}}
-    if args.stream_session:
+    if "stream_session" in legs:
         with _leg(line, "stream_session", torch):
             line["stream_session"] = bench_stream_session(st, torch, W, args.stream_time_scale)
-    if args.stream_step:
-        with _leg(line, "stream_step", torch):
-            ss = bench_stream_step(st, torch, W, 3, 1, args.stream_step_layers, not args.no_graph)
-            gbps = ss["read_bytes"] / ss["sec_per_step"] / 1e9
-            line["stream_step"] = {
-                "workload": "configs[4]: Qwen3-8B-shaped end-to-end streaming step, 36 layers, 64 streams, 32 q / 8 kv heads, head_dim 128, "
-                            "bf16, source caches U[1024,8192] and reasoning caches U[2048,16384] tokens in 16-token pages (shuffled); per "
-                            "step every layer appends a 32-token source chunk on a second stream while 8 reasoning tokens are decoded one "
-                            "after the other through all layers (st_attn_decode_dual_append: store the token, attend over both caches)",
-                "ms_per_step": round(ss["sec_per_step"] * 1e3, 2), "ms_per_token": round(ss["sec_per_step"] * 1e3 / ss["n_tok"], 2),
-                "value": round(gbps, 1), "unit": "GB/s", "pct_of_peak": round(100.0 * gbps / PEAK_HBM_GBPS, 2),
-                "algorithmic_read_bytes_per_step": ss["read_bytes"], "append_bytes_per_step": ss["append_bytes"], "launch": ss["mode"], "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ss["sec_per_step_by_launch"].items()},
-                "distinct_layer_caches": ss["distinct_layers"], "resident_cache_gb": round(ss["resident_gb"], 1),
-                "tokens_per_s": round(64 * ss["n_tok"] / ss["sec_per_step"], 1)}
-    if args.long_prefill:
-        with _leg(line, "prefill_long", torch):
-            lp = bench_prefill_long(st, torch, W, 5)
-            tf = lp["flops"] / (lp["kernel_ms"] * 1e-3) / 1e12
-            line["prefill_long"] = {
-                "workload": "configs[3]: Qwen3-4B-shaped long-context prefill layer, 8 sequences x 16,384 tokens, 32 q / 8 kv heads, "
-                            "head_dim 128, bf16; attention kernel only (two query heads per workgroup)",
-                "avg_kernel_ms": round(lp["kernel_ms"], 3), "effective_flops": lp["flops"],
-                "same_launch_on_all_zero_inputs": {"avg_kernel_ms": round(lp["zero_input_kernel_ms"], 3),
-                                                   "tflops": round(lp["flops"] / (lp["zero_input_kernel_ms"] * 1e-3) / 1e12, 1),
-                                                   "note": "same instruction stream, no operand bits toggling: the difference is the power limit"},
-                "roofline": {"kernel": "prefill_mfma_pipe_kernel<128, 2>", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS,
-                             "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}
+    if "power_check" in legs:
+        with _leg(line, "power_check", torch):
+            pc = bench_prefill_zero_inputs(st, torch, W, 5)
+            line["power_check"] = {
+                "workload": "configs[3], attention kernel alone: the same launches on random and on all-zero inputs (the same instruction "
+                            "stream, no operand bits toggling: the difference is the power limit, not the schedule)",
+                "random_inputs": {"avg_kernel_ms": round(pc["kernel_ms"], 3), "tflops": round(pc["flops"] / (pc["kernel_ms"] * 1e-3) / 1e12, 1)},
+                "all_zero_inputs": {"avg_kernel_ms": round(pc["zero_input_kernel_ms"], 3),
+                                    "tflops": round(pc["flops"] / (pc["zero_input_kernel_ms"] * 1e-3) / 1e12, 1)}}
     if not args.no_cpu_baseline:
         from oracle import streaming_attention as O
-        line["cpu_baseline"] = cpu_baseline(W, O, 4.0 * cfg.head_dim)
+        line["cpu_baseline"] = cpu_baseline(W, O)
     print(json.dumps(line))
 
 
