@@ -35,6 +35,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
+# launches of a timed kernel between its two events (st_profile_repeat): a pair of events around a single launch adds
+# several microseconds of dispatch and completion that are no part of the kernel and that a kernel trace does not count
+PROF_REPEAT = 8
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel.txt")
 
 
@@ -764,6 +767,7 @@ def main():
     import paper_2510_17238_amd as st
     import workloads as W
     st.load_library()
+    st.st_profile_repeat(PROF_REPEAT)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)

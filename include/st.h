@@ -70,10 +70,16 @@ int32_t st_version(void);
  * st_attn_prefill_bwd its two attention kernels (ST_PROF_BWD_DQ, ST_PROF_BWD_DKV),
  * st_attn_source_chunk(_rope) its attention kernel (ST_PROF_SOURCE_CHUNK).  st_profile_read WAITS
  * for the launches the thread recorded, returns their mean duration in milliseconds and their
- * number in host variables, and forgets them.  (Creating events allocates: not under graph capture.) */
+ * number in host variables, and forgets them.  (Creating events allocates: not under graph capture.)
+ * A pair of events around ONE launch also measures the dispatch of that launch and the completion of
+ * the second event, several microseconds that are no part of the kernel: st_profile_repeat(n),
+ * 1 <= n <= 64, makes the thread's calls, while timing is enabled, launch each timed kernel n times
+ * back to back between its two events (every timed kernel writes the same results again), and the
+ * reading is the mean over those launches, as a kernel trace reports it.  n = 1 is the default. */
 enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1, ST_PROF_BWD_DQ = 2, ST_PROF_BWD_DKV = 3,
        ST_PROF_TILE_PACK = 4, ST_PROF_SOURCE_CHUNK = 5 };
 void st_profile_enable(int32_t on);
+st_status st_profile_repeat(int32_t launches);
 st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
 
 /* ------------------------------------------------------------------------

@@ -82,6 +82,8 @@ def load_library():
     lib.st_plan_heads_per_workgroup.argtypes = [vp, i32]
     lib.st_profile_enable.restype = None
     lib.st_profile_enable.argtypes = [i32]
+    lib.st_profile_repeat.restype = i32
+    lib.st_profile_repeat.argtypes = [i32]
     lib.st_profile_read.restype = i32
     lib.st_profile_read.argtypes = [i32, C.POINTER(f64), C.POINTER(i32)]
     lib.st_rope_apply.restype = i32
@@ -233,6 +235,10 @@ def st_probe_mfma_bf16(n_workgroups, iterations, sink, stream=None):
 
 def st_profile_enable(on):
     load_library().st_profile_enable(1 if on else 0)
+
+
+def st_profile_repeat(launches):
+    _check(load_library().st_profile_repeat(int(launches)))
 
 
 def st_profile_read(which):

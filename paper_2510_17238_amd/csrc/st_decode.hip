@@ -1,10 +1,10 @@
 // Dual-cache decode (Sec. 3.3 "Parallel KV caches"; Alg. 1: merge the visible source
 // slice with the reasoning cache, then decode).
 //
-// Nothing is merged in memory.  The two caches are cut into chunks of 256 tokens; one
-// WAVE takes one (sequence, KV head, chunk), streams that chunk's K and V pages from HBM
-// exactly once for all query heads of the group, and emits an un-normalised partial
-// (o, m, l).  A second kernel merges all partials of BOTH caches per (sequence, query
+// Nothing is merged in memory.  The two caches are cut into work units of 128 to 1,024 tokens
+// (decode_unit_tokens; 512 for the 32-row kernel); one WAVE takes one (sequence, KV head, unit),
+// streams that unit's K and V pages from HBM exactly once for all query heads of the group, and
+// emits an un-normalised partial (o, m, l).  A second kernel merges all partials of BOTH caches per (sequence, query
 // row, head) by log-sum-exp -- identical to a softmax over the concatenated cache.
 //
 // HBM-bound: 4 * D bytes per cached token and KV head, 2 * G * D useful flops for it.
@@ -28,12 +28,17 @@ constexpr int kSmallDecodeTokens = 1024;    // both caches together: below this 
 constexpr int kChunkMin = 128;              // ... of the one-token decode step of a few sequences
 constexpr int kChunkLong = 1024;            // ... of the one-token decode step when there is plenty of work (64 pages: one id per lane)
 
-// 16 bytes of a VALUE pool: read once and never again by this launch, whole 128-byte lines per instruction, so the
-// load carries the non-temporal hint -- measured on the decode step of 28 layers: 3 to 4 % faster.  (The same hint on
-// the KEY loads, whose instructions each take half of every line they touch, costs 7 %; a pure read with the key
-// loads' pattern gains from it, so the cause is not the pattern alone -- left as measured.)
+// 16 bytes of a pool that this launch reads once and never again, taken in whole 128-byte lines per instruction: the
+// load carries the non-temporal hint.  Value loads always do (measured on the decode step of 28 layers: 3 to 4 %
+// faster).  Key loads do in launches of up to about 2 GB (STREAM_KEYS; 1 to 2.5 % faster on 0.7 GB per launch,
+// 2 to 4 % slower on 3.8 GB per launch, A/B on one box each time).
 template <typename T>
 __device__ __forceinline__ u32x4 stream_load(const T* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+template <bool STREAM, typename T>
+__device__ __forceinline__ u32x4 key_load(const T* p) {
+    if (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return *reinterpret_cast<const u32x4*>(p);
+}
 
 struct DecodeArgs {
     CacheView src, rsn;
@@ -251,7 +256,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeArgs a) {
 // than kLazyRise above it (or the first finite score): the common step then needs no exchange between lanes and no
 // rescale of the accumulator -- probabilities are bounded by 2^kLazyRise instead of 1, which fp32 and bf16 do not
 // mind, and whoever finishes the row divides by l anyway.
-template <int D, bool PREFETCH = false>
+template <int D, bool PREFETCH = false, bool STREAM_KEYS = false>
 __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, int lane, int tok0, int tok_end, int len, int limit,
                                             int limit_min, float scale_log2, const bf16x8 (&qf)[D / 32], f32x4 (&o_acc)[D / 16],
                                             float& m_ref, float& l_run, bool& has_ref) {
@@ -268,10 +273,11 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
     my_page = min(max(my_page, 0), cv.n_pages - 1);
     const int64_t page_k = int64_t(cv.n_kv_heads) * KCH * (kPage * 8);
     const int64_t page_v = int64_t(cv.n_kv_heads) * D * kPage;
-    // K: lane (m = n, g4) reads d-chunk 4 j + g4 of key row m; row m = 4 gq + i lives in page
-    // gq / 2, slot 8 (gq % 2) + i for X and + 4 for Y
+    // K: lane (m = n, g4) reads d-chunk 4 j + g4 of key row m; row m lives in page m / 8, slot m % 8 for X and
+    // + 8 for Y -- the 64 lanes of one load instruction take whole 128-byte lines (eight slots of a d-chunk), none
+    // shared with another instruction
     const bool k_second_page = (n >> 3) != 0;
-    const uint16_t* k_lane = cv.k_pool + int64_t(h) * KCH * (kPage * 8) + g4 * (kPage * 8) + (8 * ((n >> 2) & 1) + (n & 3)) * 8;
+    const uint16_t* k_lane = cv.k_pool + int64_t(h) * KCH * (kPage * 8) + g4 * (kPage * 8) + (n & 7) * 8;
     // V: lane (m = n, g4) reads slots 8 (g4 % 2) .. + 7 of row d = 16 db + m in page g4 / 2
     const bool v_second_page = (g4 >> 1) != 0;
     const uint16_t* v_lane = cv.v_pool + int64_t(h) * D * kPage + n * kPage + 8 * (g4 & 1);
@@ -296,14 +302,16 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
         const uint16_t* vp = v_lane + int64_t(v_second_page ? id1 : id0) * page_v;
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
-            kx[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8));
-            ky[j] = *reinterpret_cast<const u32x4*>(kp + 4 * j * (kPage * 8) + 4 * 8);
+            kx[j] = key_load<STREAM_KEYS>(kp + 4 * j * (kPage * 8));
+            ky[j] = key_load<STREAM_KEYS>(kp + 4 * j * (kPage * 8) + 8 * 8);
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) vv[db] = stream_load(vp + db * 16 * kPage);
     };
     auto compute = [&](int s, const u32x4 (&kx)[KS], const u32x4 (&ky)[KS], u32x4 (&vv)[DB]) {
-        const int first = tok0 + 32 * s + 8 * g4;       // token of this lane's first slot
+        const int first = tok0 + 32 * s + 8 * g4;       // token of this lane's first VALUE slot
+        // scores of this lane: X rows 4 g4 .. + 3 and the Y rows eight slots further on
+        const int first_k = tok0 + 32 * s + 16 * (g4 >> 1) + 4 * (g4 & 1);
         f32x4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
@@ -315,7 +323,7 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
         for (int e = 0; e < 8; ++e) t[e] = fmaf(e < 4 ? sx[e] : sy[e - 4], scale_log2, -m_ref);
         if (tok0 + 32 * s + 32 > limit_min) {           // uniform: a step that reaches some row's limit
 #pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] = first + e < limit ? t[e] : -INFINITY;
+            for (int e = 0; e < 8; ++e) t[e] = first_k + (e & 3) + 8 * (e >> 2) < limit ? t[e] : -INFINITY;
         }
         float mx = -INFINITY;
 #pragma unroll
@@ -336,16 +344,23 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
             m_ref += shift;
             has_ref = has_ref || move;
         }
-        bf16x8 pb;
+        u32x4 pw;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
             bf16x2 p2;
             p2[0] = (__bf16)__builtin_amdgcn_exp2f(t[e]);
             p2[1] = (__bf16)__builtin_amdgcn_exp2f(t[e + 1]);
             l_run = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, l_run, false);
-            pb[e] = p2[0];
-            pb[e + 1] = p2[1];
+            pw[e / 2] = __builtin_bit_cast(uint32_t, p2);
         }
+        // The value operand of lane group g4 holds slots 8 (g4 % 2) .. + 7 of page g4 / 2, in order; the weights
+        // of those slots sit half in this lane (X for even, Y for odd groups) and half in the lane of group g4 ^ 1:
+        // one exchange of 16-lane rows per register pair (odd rows of the X words against even rows of the Y words)
+        // leaves every lane with the eight weights of its value slots, in slot order.
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+            asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(pw[r]), "+v"(pw[2 + r]));
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
         if (tok0 + 32 * s + 32 > len) {                 // uniform: only the step that holds the end of the cache
             u32x4 keep;
 #pragma unroll
@@ -382,11 +397,8 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
     }
 }
 
-#ifndef ST_DECODE_PREFETCH
-#define ST_DECODE_PREFETCH 1
-#endif
-template <int D>
-__global__ __launch_bounds__(64, ST_DECODE_PREFETCH ? 2 : 4) void decode_split16_kernel(DecodeArgs a) {
+template <int D, bool STREAM_KEYS>
+__global__ __launch_bounds__(64, 2) void decode_split16_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
     const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr + a.append;             // (append: one more slot per sequence and head, the new token's)
@@ -463,7 +475,7 @@ __global__ __launch_bounds__(64, ST_DECODE_PREFETCH ? 2 : 4) void decode_split16
         }
         if (h == 0 && lane == 0) a.rsn.appended_len[b] = len_all;
     } else {
-        scan_unit16<D, ST_DECODE_PREFETCH != 0>(cv, b, h, lane, tok0, tok_end, len, min(limit, len), min(limit_min, len), a.scale_log2, qf, o_acc, m_ref, l_run,
+        scan_unit16<D, true, STREAM_KEYS>(cv, b, h, lane, tok0, tok_end, len, min(limit, len), min(limit_min, len), a.scale_log2, qf, o_acc, m_ref, l_run,
                                                 has_ref);
     }
 
@@ -487,13 +499,7 @@ __global__ __launch_bounds__(64, ST_DECODE_PREFETCH ? 2 : 4) void decode_split16
 // tokens, so the tokens of BOTH caches are dealt out in short units to the waves of the workgroup (wave w folds
 // units w, w + W, ... into one running state), and the waves' states meet in LDS, where all threads merge them
 // (log-sum-exp, fixed order) and write the finished rows.
-#ifndef ST_SMALL_WAVES
-#define ST_SMALL_WAVES 8
-#endif
-#ifndef ST_SMALL_UNIT
-#define ST_SMALL_UNIT 64
-#endif
-constexpr int kSmallWaves = ST_SMALL_WAVES, kSmallUnit = ST_SMALL_UNIT;
+constexpr int kSmallWaves = 8, kSmallUnit = 64;
 
 // Rotation of a fragment set (layout of rotate_query<KS, 32>) by cos / sin values parked in LDS: entry i belongs
 // to head dims i and D/2 + i.
@@ -1433,11 +1439,22 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
         if (a.rows <= 16) {
             if (units > 0x7fffffff) return fail(ST_ERR_SHAPE, "st_attn_decode_dual: grid too large");
             if (!no_alloc) prof_begin(kProfDecodeSplit, s);      // (the timing hooks create events)
+            for (int rep = 0, n_rep = no_alloc ? 1 : prof_repeat(); rep < n_rep; ++rep)
             if (fp8) {
                 if (d == 64) hipLaunchKernelGGL((decode_split16_fp8_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
                 else hipLaunchKernelGGL((decode_split16_fp8_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
-            } else if (d == 64) hipLaunchKernelGGL((decode_split16_kernel<64>), dim3((unsigned)units), dim3(64), 0, s, a);
-            else hipLaunchKernelGGL((decode_split16_kernel<128>), dim3((unsigned)units), dim3(64), 0, s, a);
+            } else {
+                // (bytes of the launch from the length bounds: about half are real)
+                const double bound_bytes = double(batch) * hkv * (double(lens->max_src_len) + lens->max_rsn_len) * 4.0 * d;
+                const bool stream_keys = bound_bytes <= 4.0e9;
+                if (d == 64) {
+                    if (stream_keys) hipLaunchKernelGGL((decode_split16_kernel<64, true>), dim3((unsigned)units), dim3(64), 0, s, a);
+                    else hipLaunchKernelGGL((decode_split16_kernel<64, false>), dim3((unsigned)units), dim3(64), 0, s, a);
+                } else {
+                    if (stream_keys) hipLaunchKernelGGL((decode_split16_kernel<128, true>), dim3((unsigned)units), dim3(64), 0, s, a);
+                    else hipLaunchKernelGGL((decode_split16_kernel<128, false>), dim3((unsigned)units), dim3(64), 0, s, a);
+                }
+            }
             if (!no_alloc) prof_end(kProfDecodeSplit, s);
         } else {
             if (d == 64) hipLaunchKernelGGL((decode_split_kernel<64>), grid, block, 0, s, a);
@@ -1580,7 +1597,8 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
             const size_t smem = sizeof(ChunkSmem<HD, STAGES, TOK>);
             ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_split_lds_kernel<HD, STAGES, TOK>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfSourceChunk, s);
-            hipLaunchKernelGGL((chunk_split_lds_kernel<HD, STAGES, TOK>), dim3((unsigned)wgs), dim3(256), smem, s, a);
+            for (int rep = 0; rep < prof_repeat(); ++rep)
+                hipLaunchKernelGGL((chunk_split_lds_kernel<HD, STAGES, TOK>), dim3((unsigned)wgs), dim3(256), smem, s, a);
             prof_end(kProfSourceChunk, s);
             return ST_OK;
         };

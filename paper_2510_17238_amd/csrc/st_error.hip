@@ -21,16 +21,19 @@ namespace st {
 namespace {
 // Kernel timing is a property of the CALLING THREAD (like the error text): a thread that switches it on gets events
 // around the kernels of its own calls and reads back its own measurements; other threads are not affected.
-struct Region { hipEvent_t a, b; };
+struct Region { hipEvent_t a, b; int launches; };
 thread_local bool t_prof_on = false;
+thread_local int t_prof_repeat = 1;
 thread_local std::vector<Region> t_regions[kProfCount];
 }  // namespace
 
 bool prof_enabled() { return t_prof_on; }
+int prof_repeat() { return t_prof_on ? t_prof_repeat : 1; }
 
 void prof_begin(int which, hipStream_t stream) {
     if (!t_prof_on) return;
     Region r{};
+    r.launches = t_prof_repeat;
     if (hipEventCreate(&r.a) != hipSuccess) return;
     if (hipEventCreate(&r.b) != hipSuccess) {
         (void)hipEventDestroy(r.a);
@@ -47,6 +50,11 @@ void prof_end(int which, hipStream_t stream) {
 }  // namespace st
 
 extern "C" void st_profile_enable(int32_t on) { st::t_prof_on = on != 0; }
+extern "C" st_status st_profile_repeat(int32_t launches) {
+    if (launches < 1 || launches > 64) return st::fail(ST_ERR_INVALID_ARG, "st_profile_repeat: %d launches (1 .. 64)", launches);
+    st::t_prof_repeat = launches;
+    return ST_OK;
+}
 
 extern "C" st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count) {
     using namespace st;
@@ -56,7 +64,7 @@ extern "C" st_status st_profile_read(int32_t which, double* mean_ms, int32_t* co
     for (Region& r : t_regions[which]) {
         float ms = 0.f;
         if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
-            total += ms;
+            total += ms / r.launches;
             ++n;
         }
         (void)hipEventDestroy(r.a);

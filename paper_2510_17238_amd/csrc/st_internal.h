@@ -38,9 +38,13 @@ inline st_status fail(st_status code, const char* fmt, ...) {
     } while (0)
 
 // Optional kernel timing (st_profile_enable, per calling thread): HIP events recorded on the launch stream right
-// before and after one kernel, read back by st_profile_read.
+// before and after one kernel, read back by st_profile_read.  A pair of events around a single launch adds several
+// microseconds of its own (the launch's dispatch after the first event, the second event's completion), so a timed
+// kernel is launched prof_repeat() times back to back between its two events (1 unless timing is on; all timed
+// kernels write the same results again) and the reading is divided by that.
 enum { kProfPrefillAttn = 0, kProfDecodeSplit = 1, kProfBwdDq = 2, kProfBwdDkv = 3, kProfTilePack = 4, kProfSourceChunk = 5, kProfCount = 6 };
 bool prof_enabled();
+int prof_repeat();
 void prof_begin(int which, hipStream_t stream);
 void prof_end(int which, hipStream_t stream);
 

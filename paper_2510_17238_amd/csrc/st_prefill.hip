@@ -852,6 +852,7 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
     auto launch = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
         prof_begin(kProfTilePack, s);
+        for (int rep = 0; rep < prof_repeat(); ++rep)
         if (rope) {
             hipLaunchKernelGGL((rope_table_kernel<HD>), dim3((unsigned)plan->pack_tiles), dim3(256), 0, s, tab, positions, pv, freq);
             hipLaunchKernelGGL((tile_pack_rope_kernel<HD>), dim3((unsigned)pack_blocks), dim3(256), 0, s, kc, vc, (const float2*)tab,
@@ -867,8 +868,9 @@ static st_status prefill_impl(void* out, float* lse, const void* q, const void* 
             auto* kern = &prefill_attn_kernel<HD, NH, ROPE>;
             ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfPrefillAttn, s);
-            hipLaunchKernelGGL(kern, dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
-                               lse, (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2, (const float2*)tab);
+            for (int rep = 0; rep < prof_repeat(); ++rep)
+                hipLaunchKernelGGL(kern, dim3((unsigned)(blocks / NH)), dim3(256), smem, s, (uint16_t*)out,
+                                   lse, (const uint16_t*)q, kc, vc, pv, n_q_heads, n_kv_heads, scale_log2, (const float2*)tab);
             prof_end(kProfPrefillAttn, s);
             return ST_OK;
         };

@@ -792,10 +792,12 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
         ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dq_mfma_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem_q)));
         ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_dkv_mfma_kernel<HD>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem_k)));
         prof_begin(kProfBwdDq, s);
+        for (int rep = 0; rep < prof_repeat(); ++rep)
         hipLaunchKernelGGL((bwd_dq_mfma_kernel<HD>), dim3((unsigned)qblocks), dim3(256), smem_q, s, (uint16_t*)dq, (const uint16_t*)d_out,
                            (const uint16_t*)q, at(L.krows), at(L.vrows), at(L.ktr), lse, delta, pv, n_q_heads, n_kv_heads, scale);
         prof_end(kProfBwdDq, s);
         prof_begin(kProfBwdDkv, s);
+        for (int rep = 0; rep < prof_repeat(); ++rep)
         hipLaunchKernelGGL((bwd_dkv_mfma_kernel<HD>), dim3((unsigned)kblocks), dim3(256), smem_k, s, (uint16_t*)dk, (uint16_t*)dv,
                            (const uint16_t*)k, (const uint16_t*)v, at(L.qrows), at(L.qtr), at(L.dorows), at(L.dotr), stats, pv,
                            n_q_heads, n_kv_heads, scale);

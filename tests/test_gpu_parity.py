@@ -311,6 +311,38 @@ def test_prefill_rope_fused(st, heads):
     assert e.value.status == 1
 
 
+def test_kernel_timing_with_repeated_launches_changes_no_result(st):
+    """st_profile_enable + st_profile_repeat: the timed kernels are launched several times between their two events;
+    outputs keep their bits, one reading per call comes back, and the state is the thread's own."""
+    cfg = W.config2()
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv = to_dev(q, cfg.dtype), to_dev(k, cfg.dtype), to_dev(v, cfg.dtype)
+    plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    lse0 = torch.empty((cfg.n_tokens, cfg.n_q_heads), dtype=torch.float32, device=DEV); lse1 = torch.empty_like(lse0)
+    out0 = st.st_attn_prefill(tq, tk, tv, plan, lse=lse0)
+    for which in (st.ST_PROF_PREFILL_ATTN, st.ST_PROF_TILE_PACK):
+        st.st_profile_read(which)
+    st.st_profile_repeat(4)
+    st.st_profile_enable(True)
+    try:
+        out1 = st.st_attn_prefill(tq, tk, tv, plan, lse=lse1)
+        out2 = st.st_attn_prefill(tq, tk, tv, plan)
+    finally:
+        st.st_profile_enable(False)
+        st.st_profile_repeat(1)
+    torch.cuda.synchronize()
+    assert torch.equal(out0, out1) and torch.equal(out0, out2) and torch.equal(lse0, lse1)
+    ms_attn, n_attn = st.st_profile_read(st.ST_PROF_PREFILL_ATTN)
+    ms_pack, n_pack = st.st_profile_read(st.ST_PROF_TILE_PACK)
+    assert n_attn == 2 and n_pack == 2
+    assert 0.0 < ms_pack < ms_attn < 50.0
+    assert st.st_profile_read(st.ST_PROF_PREFILL_ATTN) == (0.0, 0)           # read forgets
+    with pytest.raises(st.StError):
+        st.st_profile_repeat(0)
+    plan.destroy()
+
+
 def test_prefill_mfma_agrees_with_plain_kernel(st):
     """bf16 inputs through the MFMA kernel vs the same values through the fp32 kernel."""
     cfg = W.random_prefill(311, 2, 10, (10, 80), (10, 100), 4, 2, 128, "bf16")
