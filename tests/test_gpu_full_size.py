@@ -161,7 +161,7 @@ def _decode_full(st, shp, q_len, check_seqs, seed, fp8=False, one_call=False):
             assert np.array_equal(rk[-q_len:], stored(k_tok[b])) and np.array_equal(rv[-q_len:], stored(v_tok[b]))
             o_ref, l_ref = O.decode_dual_fp8(to_f64(q[b]), sk, sv, rk, rv, int(shp.src_visible_len[b]), int(shp.rsn_len[b]))
             assert np.abs(to_f64(out[b]) - o_ref).max() <= 2e-2 * max(1.0, np.abs(o_ref).max()), b
-            assert np.abs(to_f64(lse[b]) - l_ref).max() <= 4e-2, b
+            assert np.abs(to_f64(lse[b]) - l_ref).max() <= 2e-2, b
             continue
         assert np.array_equal(rk[-q_len:], to_f64(k_tok[b])) and np.array_equal(rv[-q_len:], to_f64(v_tok[b]))
         o_ref, l_ref = O.decode_dual_concat(to_f64(q[b]), sk, sv, rk, rv, int(shp.src_visible_len[b]), int(shp.rsn_len[b]))
@@ -178,18 +178,17 @@ def test_config3_decode_one_layer(st):
 
 def test_config3_decode_one_layer_in_one_call(st):
     """The same step the way bench.py issues it: st_attn_decode_dual_append stores the token and attends (512-token
-    units chosen by launch size, the token through the split kernel's extra work unit)."""
+    units chosen by launch size, the token through the split kernel's extra work unit); the whole output, all 32
+    sequences, against the oracle."""
     shp = W.config3()
-    longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
-    _decode_full(st, shp, 1, sorted({1, 9, longest, shortest}), seed=33, one_call=True)
+    _decode_full(st, shp, 1, range(shp.batch), seed=33, one_call=True)             # every row of all 32 sequences
 
 
 def test_config5_decode_token_in_one_call(st):
     """One token of the Qwen3-8B-shaped streaming step (64 streams, caches up to 8K + 16K tokens: 1024-token units), one
-    layer, issued as bench.py's streaming-step leg issues it."""
+    layer, issued as bench.py's streaming-step leg issues it; the whole output, all 64 streams, against the oracle."""
     shp = W.config5()
-    longest, shortest = int(np.argmax(shp.rsn_len)), int(np.argmin(shp.rsn_len))
-    _decode_full(st, shp, 1, sorted({2, longest, shortest}), seed=34, one_call=True)
+    _decode_full(st, shp, 1, range(shp.batch), seed=34, one_call=True)             # every row of all 64 streams
 
 
 def test_config3_decode_one_layer_8bit_caches(st):
