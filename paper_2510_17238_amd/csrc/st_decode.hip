@@ -954,7 +954,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
 }
 
 // Source-chunk prefill (Alg. 1, prefill loop) with the cache pages SHARED through LDS: one workgroup per
-// (sequence, KV head, group of 128 query rows, 512-token chunk of the source cache), wave w = the w-th block of
+// (sequence, KV head, group of 128 query rows, work unit of the source cache: chunk_units), wave w = the w-th block of
 // 32 (token, head) rows.  Per step the four waves copy four pages (64 tokens) of K and of V -- 4 KB each at
 // D = 128, verbatim, with asynchronous global -> LDS copies, one step ahead -- and every wave takes its matrix
 // operands from there, so a page is fetched from L2 once per workgroup and not once per row block.  The pool
@@ -962,12 +962,22 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
 // are not, so the copy swaps the two halves of every second group of 8 rows (by choosing what each lane fetches).
 // Softmax with the lazy reference exponent of the other kernels; partial results [B][Hkv][row block][unit][32 rows],
 // merged by chunk_combine_kernel.
-#ifndef ST_CHUNK_STAGES
-#define ST_CHUNK_STAGES 2
-#endif
-#ifndef ST_CHUNK_TOK
-#define ST_CHUNK_TOK 64
-#endif
+// Work units of one sequence's source cache: as few as keep a unit within `target` tokens, all of the same length
+// (a multiple of 64 tokens) -- equal units finish together, a long one beside a short remainder does not.
+struct ChunkUnits {
+    int len;      // tokens of the cache
+    int size;     // tokens per unit
+    int count;    // units
+};
+__device__ __forceinline__ ChunkUnits chunk_units(int len, int target) {
+    ChunkUnits u;
+    u.len = len;
+    u.count = max((len + target - 1) / target, 1);
+    u.size = ((len + u.count - 1) / u.count + 63) & ~63;
+    return u;
+}
+constexpr int kChunkRankMax = 256;
+
 template <int D, int STAGES, int TOK>
 struct ChunkSmem {
     uint16_t k[STAGES][TOK * D];
@@ -989,16 +999,51 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rb_groups = (a.row_blocks + 3) / 4;
-    unsigned unit = blockIdx.x;
-    const int c = int(unit % unsigned(a.ncs));
-    unit /= unsigned(a.ncs);
-    const int rbg = int(unit % unsigned(rb_groups));
-    unit /= unsigned(rb_groups);
-    const int h = int(unit % unsigned(a.n_kv_heads));
-    const int b = int(unit / unsigned(a.n_kv_heads));
     const CacheView& cv = a.src;
+    // Which unit: the workgroups of a launch are handed out in index order and a unit keeps its compute unit for as
+    // long as it has tokens, so the LONGEST units go first -- workgroup index / (heads x row groups) is a rank in the
+    // order of decreasing unit length over all (sequence, unit) pairs (ties by index), worked out by every
+    // workgroup from the lengths themselves (one entry per thread and pass; kChunkRankMax entries at most, beyond
+    // that the units go in index order).
+    __shared__ __align__(16) int s_unit_len[kChunkRankMax];
+    __shared__ int s_pick;
+    const int per_rank = a.n_kv_heads * rb_groups;
+    const int rank = int(blockIdx.x / unsigned(per_rank));
+    const int hr = int(blockIdx.x % unsigned(per_rank));
+    const int h = hr / rb_groups, rbg = hr % rb_groups;
+    const int n_entries = a.batch * a.ncs;
+    int entry = rank;
+    if (n_entries <= kChunkRankMax) {
+        const int padded = (n_entries + 3) & ~3;     // (entries past the end: -1, behind every real one)
+        for (int e = threadIdx.x; e < padded; e += 256) {
+            int tokens = -1;
+            if (e < n_entries) {
+                const int bb = e / a.ncs, cc = e % a.ncs;
+                const ChunkUnits u = chunk_units(min(max(a.src_len[bb], 0), cv.max_pages * kPage), a.chunk);
+                tokens = max(min(u.len - cc * u.size, u.size), 0);
+            }
+            s_unit_len[e] = tokens;
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < n_entries; e += 256) {
+            const int mine = s_unit_len[e];
+            int before = 0;
+            for (int o = 0; o < padded; o += 4) {
+                const int4 other = *reinterpret_cast<const int4*>(&s_unit_len[o]);
+                before += (other.x > mine || (other.x == mine && o < e)) ? 1 : 0;
+                before += (other.y > mine || (other.y == mine && o + 1 < e)) ? 1 : 0;
+                before += (other.z > mine || (other.z == mine && o + 2 < e)) ? 1 : 0;
+                before += (other.w > mine || (other.w == mine && o + 3 < e)) ? 1 : 0;
+            }
+            if (before == rank) s_pick = e;          // exactly one entry has this rank
+        }
+        __syncthreads();
+        entry = s_pick;
+    }
+    const int b = __builtin_amdgcn_readfirstlane(entry / a.ncs), c = __builtin_amdgcn_readfirstlane(entry % a.ncs);
     const int len = min(max(a.src_len[b], 0), cv.max_pages * kPage);
-    const int tok0 = c * a.chunk;
+    const ChunkUnits units_b = chunk_units(len, a.chunk);
+    const int tok0 = c * units_b.size;
     if (tok0 >= len) return;
     const int q_len = min(min(max(a.n_new ? a.n_new[b] : a.max_new, 0), a.max_new), len);
     const int n_rows = q_len * a.group;
@@ -1006,7 +1051,7 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
     // the group's last row sees the most: a chunk past its limit holds nothing for any of its blocks
     const int group_last_t = min(q_len - 1, (rbg * 128 + 127) / a.group);
     if (tok0 >= len - q_len + group_last_t + 1) return;
-    const int tok_end = min(len, tok0 + a.chunk);
+    const int tok_end = min(len, tok0 + units_b.size);
     const int n_steps = (tok_end - tok0 + TOK - 1) / TOK;
 
     const int n = lane & 31, hg = lane >> 5;
@@ -1027,6 +1072,11 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
     for (int j = 0; j < KS; ++j)
         qf[j] = *reinterpret_cast<const bf16x8*>(a.q + ((int64_t(b) * a.max_new + t_row) * a.n_q_heads + hq) * D + 16 * j + 8 * hg);
     if (a.rope) rotate_query<KS, 16>(qf, 8 * hg, max(len - q_len + t_row, 0), a.freq);
+    // queries times scale * log2(e), rounded to bf16 again: K q' is the exponent of the softmax weight
+#pragma unroll
+    for (int j = 0; j < KS; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[j][e] = (__bf16)(float(qf[j][e]) * a.scale_log2);
 
     // Copies.  A step is PG pages of K and PG pages of V; the four waves share them out, PER_WAVE page copies each:
     // copy number x = wave * PER_WAVE + u is page x % PG of K (x < PG) or of V.
@@ -1076,7 +1126,7 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
-    constexpr float kLazyRise = 8.f;
+    constexpr float kRise = 16777216.f;               // 2^24
     float m_ref = 0.f, l_run = 0.f;
     bool has_ref = false;
     // operand addresses inside a stage (elements): K lane (m = n, hg): page n / 16 of the 32-key block, slot
@@ -1084,7 +1134,12 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
     // for every second group of 8 rows, see above)
     const int k_off = (n >> 4) * PAGE + swap23(n & 15) * 8 + hg * (kPage * 8);
     const int v_off = n * kPage + 8 * (hg ^ ((n >> 3) & 1));
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // Score blocks of a step.  Between steps the LAST one holds -m_ref of this lane's row in all sixteen registers:
+    // the first matrix instruction of every block takes it as its accumulator input (the last block in place, after
+    // the others have read it), so the scores come out relative to the reference without a subtraction.
+    f32x16 s_acc[SBN];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_acc[SBN - 1][i] = 0.f;
 
     int stage = 0;
     for (int s = 0; s < n_steps; ++s) {
@@ -1098,7 +1153,6 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
         if (!wave_works || tok >= len - q_len + block_last_t + 1) continue;      // (uniform) nothing for this block here
         // operands leave LDS ahead of the matrix instructions that take them: all key fragments now, all value
         // fragments before the exponentials (scheduling barriers keep the compiler from moving them back)
-        f32x16 s_acc[SBN];
         bf16x8 fk[SBN * KS];
 #pragma unroll
         for (int f = 0; f < SBN * KS; ++f)
@@ -1106,28 +1160,50 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int f = 0; f < SBN * KS; ++f)
-            s_acc[f % SBN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[f], qf[f / SBN], f < SBN ? zero16 : s_acc[f % SBN], 0, 0, 0);
+            s_acc[f % SBN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[f], qf[f / SBN], f < SBN ? s_acc[SBN - 1] : s_acc[f % SBN], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         u32x4 fv[PG * DB];
 #pragma unroll
         for (int f = 0; f < PG * DB; ++f)
             fv[f] = *reinterpret_cast<const u32x4*>(vb + (f / DB) * PAGE + 32 * (f % DB) * kPage + v_off);
         __builtin_amdgcn_sched_barrier(0);
-        // block sb, register i  <->  token tok + 32 sb + 16 (i/8) + 8 hg + i%8
-        float t[SBN][16];
-        float mx = -INFINITY;
+        // block sb, register i  <->  token tok + 32 sb + 16 (i/8) + 8 hg + i%8.  The scores leave the matrix pipe as
+        // exponents relative to the row's reference (queries prescaled, -m_ref where the accumulators start).
         const bool masked = tok + TOK > limit_min || !valid_row;                 // (uniform up to the row validity)
+        if (masked) {
 #pragma unroll
-        for (int sb = 0; sb < SBN; ++sb)
+            for (int sb = 0; sb < SBN; ++sb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float x = fmaf(s_acc[sb][i], a.scale_log2, -m_ref);
-                if (masked) x = tok + 32 * sb + 16 * (i >> 3) + 8 * hg + (i & 7) < limit ? x : -INFINITY;
-                t[sb][i] = x;
-                mx = fmaxf(mx, x);
-            }
-        if (__any(mx > kLazyRise || (!has_ref && mx > -INFINITY))) {
+                for (int i = 0; i < 16; ++i)
+                    s_acc[sb][i] = tok + 32 * sb + 16 * (i >> 3) + 8 * hg + (i & 7) < limit ? s_acc[sb][i] : -INFINITY;
+        }
+        bf16x8 pb[PG];
+        float psum;
+        auto weights = [&]() {
+            psum = 0.f;
+#pragma unroll
+            for (int sb = 0; sb < SBN; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(s_acc[sb][i]);
+                    psum += p;
+                    pb[2 * sb + (i >> 3)][i & 7] = (__bf16)p;
+                }
+        };
+        // No running maximum: the reference only moves when a row has none yet, or when a step's weights say that
+        // the scores have risen far above it (their sum beyond 2^24, overflow included).
+        bool slow = __any(!has_ref && limit > tok);
+        if (!slow) {
+            weights();
+            slow = __any(!(psum <= kRise));
+        }
+        if (slow) {
             // out of line: move the reference of the rows that need it (a row lives in lanes n and n + 32)
+            float mx = -INFINITY;
+#pragma unroll
+            for (int sb = 0; sb < SBN; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_acc[sb][i]);
             const float rise = fmaxf(mx, __shfl_xor(mx, 32));
             const bool move = has_ref ? rise > 0.f : rise > -INFINITY;
             const float shift = move ? rise : 0.f;
@@ -1135,7 +1211,7 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
 #pragma unroll
             for (int sb = 0; sb < SBN; ++sb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) t[sb][i] -= shift;
+                for (int i = 0; i < 16; ++i) s_acc[sb][i] -= shift;
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -1143,35 +1219,30 @@ __global__ __launch_bounds__(256, 2) void chunk_split_lds_kernel(DecodeArgs a) {
                 for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
             m_ref += shift;
             has_ref = has_ref || move;
+            weights();
         }
-        bf16x8 pb[PG];
-        float psum = 0.f;
+        // the last score block is where the next step's accumulators start: -m_ref again
 #pragma unroll
-        for (int sb = 0; sb < SBN; ++sb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(t[sb][i]);
-                psum += p;
-                pb[2 * sb + (i >> 3)][i & 7] = (__bf16)p;
-            }
+        for (int i = 0; i < 16; ++i) s_acc[SBN - 1][i] = -m_ref;
         l_run += psum;
-        const bool tail = tok + TOK > len;                                       // (uniform) the step that holds the end of the cache
+        if (tok + TOK > len) {                                                   // (uniform) the step that holds the end of the cache
+            // slots past the visible length may hold anything (0 x NaN): remove them by bit mask
 #pragma unroll
-        for (int t4 = 0; t4 < PG; ++t4) {
-            u32x4 keep = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
-            if (tail) {
-                // slots past the visible length may hold anything (0 x NaN): remove them by bit mask
+            for (int t4 = 0; t4 < PG; ++t4) {
+                u32x4 keep;
                 const int first = tok + 16 * t4 + 8 * hg;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     keep[e] = (first + 2 * e < len ? 0x0000ffffu : 0u) | (first + 2 * e + 1 < len ? 0xffff0000u : 0u);
-            }
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const u32x4 av = fv[t4 * DB + db] & keep;
-                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb[t4], o_acc[db], 0, 0, 0);
+                for (int db = 0; db < DB; ++db) fv[t4 * DB + db] &= keep;
             }
         }
+#pragma unroll
+        for (int t4 = 0; t4 < PG; ++t4)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fv[t4 * DB + db]), pb[t4], o_acc[db], 0, 0, 0);
     }
     wait_vmcnt<0>();
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -1209,7 +1280,8 @@ __global__ __launch_bounds__(64) void chunk_combine_kernel(DecodeArgs a, uint16_
     const int h = hq / a.group;
     const int r = t * a.group + hq % a.group, rb = r / 32, n = r % 32;
     const int last_t = min(q_len - 1, (rb * 32 + 31) / a.group);
-    const int n_tot = min((len - q_len + last_t + 1 + a.chunk - 1) / a.chunk, a.ncs);   // chunks the split kernel wrote for this block
+    const int unit_size = chunk_units(len, a.chunk).size;
+    const int n_tot = min((len - q_len + last_t + 1 + unit_size - 1) / unit_size, a.ncs);   // units the split kernel wrote for this block
     const int64_t base = ((int64_t(b) * a.n_kv_heads + h) * a.row_blocks + rb) * a.ncs;
 
     float acc[PER];
@@ -1593,7 +1665,7 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
         const int64_t wgs = int64_t(batch) * hkv * ((a.row_blocks + 3) / 4) * a.ncs;
         auto launch = [&](auto dtag) -> st_status {
             constexpr int HD = decltype(dtag)::value;
-            constexpr int STAGES = ST_CHUNK_STAGES, TOK = ST_CHUNK_TOK;
+            constexpr int STAGES = 2, TOK = 64;      // (measured: three to five stages of 32 tokens, or four of 64 with one workgroup per compute unit, are no faster)
             const size_t smem = sizeof(ChunkSmem<HD, STAGES, TOK>);
             ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_split_lds_kernel<HD, STAGES, TOK>), hipFuncAttributeMaxDynamicSharedMemorySize, int(smem)));
             prof_begin(kProfSourceChunk, s);

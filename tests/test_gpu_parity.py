@@ -1065,6 +1065,18 @@ def test_source_chunk_many_row_blocks(st):
     _check_source_chunk(st, rng, 2, 4, 4, 64, [70, 0], [33, 64], 64)
 
 
+def test_source_chunk_unit_order(st):
+    """The work units of a launch go longest first (a rank worked out from the lengths by every workgroup) for up to
+    256 (sequence, unit) pairs and in index order beyond: a batch on either side, lengths from empty to several
+    units, equal lengths among them (ties)."""
+    rng = np.random.Generator(np.random.PCG64(445))
+    before = [0, 1500, 300, 300, 5000, 64, 4096, 300, 2047, 9]
+    _check_source_chunk(st, rng, len(before), 4, 2, 128, before, [8] * len(before), 8)
+    before = list(rng.integers(0, 700, size=300))
+    before[17] = 0; before[18] = before[19] = 333
+    _check_source_chunk(st, rng, 300, 2, 1, 64, before, list(rng.integers(0, 5, size=300)), 4)
+
+
 def test_source_chunk_rope_fused(st):
     """Unrotated keys and queries through st_kv_append_rope + st_attn_source_chunk_rope."""
     rng = np.random.Generator(np.random.PCG64(444))
