@@ -723,7 +723,7 @@ def _prefill_objects(pre, name, fused_rope):
     stages = {"note": "every stage of the step alone, back-to-back launches timed with events on the launch stream; tile_pack and attention "
                       "from events around the kernel inside st_attn_prefill during whole steps",
               "ms": {k: round(v, 5) for k, v in ms.items()},
-              "rope_qk": {"roofline": _hbm_roofline("rope_qk_kernel (st_rope_apply_qk: q and k of all tokens, read + write)", pre["stage_bytes"]["rope_qk"],
+              "rope_qk": {"roofline": _hbm_roofline("rope_kernel<bf16, 128> (st_rope_apply_qk: q and k of all tokens in one launch, read + write)", pre["stage_bytes"]["rope_qk"],
                                                     ms["rope_qk"], f"rope_qk_kernel@{name}")},
               "tile_pack": {"roofline": _hbm_roofline("tile_pack_kernel (k, v rows gathered into K tiles and V^T tiles)", pre["stage_bytes"]["tile_pack"],
                                                       ms["tile_pack"], f"tile_pack_kernel@{name}")},
