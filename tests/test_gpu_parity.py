@@ -311,6 +311,35 @@ def test_prefill_rope_fused(st, heads):
     assert e.value.status == 1
 
 
+def test_plan_built_on_one_stream_used_on_others(st):
+    """A plan built (unvalidated, so nothing waits on the host) on stream A, the forward on stream B and the backward on
+    stream C, each with the binding's temporary workspaces: the entry points order themselves against the build, and
+    the results have the bits of the same calls on one stream."""
+    cfg = W.config2()
+    q, k, v = cfg.tensors()
+    seg, strm, pos = ids_to_dev(cfg)
+    tq, tk, tv = to_dev(q, cfg.dtype), to_dev(k, cfg.dtype), to_dev(v, cfg.dtype)
+    go = to_dev(W.normal(np.random.Generator(np.random.PCG64(77)), q.shape, cfg.dtype), cfg.dtype)
+    plan0 = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
+    lse0 = torch.empty((cfg.n_tokens, cfg.n_q_heads), dtype=torch.float32, device=DEV)
+    out0 = st.st_attn_prefill(tq, tk, tv, plan0, lse=lse0)
+    g0 = st.st_attn_prefill_bwd(go, tq, tk, tv, out0, lse0, plan0)
+    torch.cuda.synchronize()
+    sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):
+        plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, stream=sa)
+        lse1 = torch.empty_like(lse0)
+        out1 = st.st_attn_prefill(tq, tk, tv, plan, lse=lse1, stream=sb)
+        sc.wait_stream(sb)
+        g1 = st.st_attn_prefill_bwd(go, tq, tk, tv, out1, lse1, plan, stream=sc)
+        torch.cuda.synchronize()
+        assert torch.equal(out0, out1) and torch.equal(lse0, lse1)
+        for a, b in zip(g0, g1):
+            assert torch.equal(a, b)
+        plan.destroy()
+    plan0.destroy()
+
+
 def test_kernel_timing_with_repeated_launches_changes_no_result(st):
     """st_profile_enable + st_profile_repeat: the timed kernels are launched several times between their two events;
     outputs keep their bits, one reading per call comes back, and the state is the thread's own."""
