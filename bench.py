@@ -521,6 +521,41 @@ def bench_stream_step(st, torch, W, steps, warmup, distinct_layers=None, use_gra
             "append_layer_bytes": float(B * shp.src_append * hkv * d * 2 * 2 * 2), "n_layers": L, "batch": B}
 
 
+def _wave_timeline(st, torch, launch, reset, n_pairs=1 << 16, bin_us=10.0):
+    """One launch of the decode split kernel with st_profile_wave_trace on (one launch between the events): when its waves
+    (one per work unit) start and end on the 100 MHz wall clock -- how many are in flight over the launch."""
+    buf = torch.zeros((n_pairs, 2), dtype=torch.int64, device="cuda")
+    reset(); launch(); torch.cuda.synchronize()
+    st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    st.st_profile_repeat(1); st.st_profile_wave_trace(buf); st.st_profile_enable(True)
+    try:
+        reset(); launch(); torch.cuda.synchronize()
+    finally:
+        st.st_profile_enable(False); st.st_profile_wave_trace(None); st.st_profile_repeat(PROF_REPEAT)
+    ev_ms, _ = st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    a = buf.cpu().numpy()
+    a = a[a[:, 1] > 0]
+    if not len(a):
+        return None
+    t0 = a[:, 0].min()
+    start = (a[:, 0] - t0) / 100.0; end = (a[:, 1] - t0) / 100.0          # microseconds
+    dur = end - start
+    real = dur > 2.0                                                        # units past a cache's length (and the token's unit) end at once
+    span = float(end.max())
+    bins = []
+    lo = 0.0
+    while lo < span:
+        bins.append(int(((start < lo + bin_us) & (end > lo) & real).sum()))
+        lo += bin_us
+    return {"note": "one launch, every workgroup (one wave, one work unit) stamped at start and end with the 100 MHz wall clock (st_profile_wave_trace)",
+            "workgroups": int(len(a)), "units_with_tokens": int(real.sum()), "first_start_to_last_end_us": round(span, 1),
+            "events_around_this_single_launch_us": round(ev_ms * 1e3, 1),
+            "unit_duration_us": {"mean": round(float(dur[real].mean()), 1), "p10": round(float(np.percentile(dur[real], 10)), 1),
+                                 "p90": round(float(np.percentile(dur[real], 90)), 1), "max": round(float(dur[real].max()), 1)},
+            "last_unit_started_at_us": round(float(start[real].max()), 1),
+            f"waves_in_flight_per_{int(bin_us)}us_bin": bins}
+
+
 def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8=False):
     dev = "cuda"
     shp = W.config3() if n_layers is None else W.config3(n_layers=n_layers)
@@ -580,6 +615,10 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
     st.st_profile_enable(False)
     layer_ms, n_rec = st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
     assert n_rec == min(steps, 3) * L
+    timeline = None
+    if not fp8:
+        timeline = _wave_timeline(st, torch, lambda: st.st_attn_decode_dual_append(q, k_tok, v_tok, layers[L - 1], src_vis, rsn_len, max_s, max_r, out=out,
+                                                                                  workspace=ws), lambda: len_r_all[L - 1].copy_(rsn_before))
     # the timed steps, two ways: the whole 28-layer step (both streams) as replays of one HIP graph (checked against the
     # eager step, second stream included) and as plain launches; the faster one is the step time, both are reported
     mode = "hip-graph"
@@ -611,7 +650,7 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
     # bytes per cached token and KV head: K and V rows of D elements; 8-bit rows carry an fp32 scale each
     per_layer = tokens * hkv * ((2 * d + 8) if fp8 else 2 * d * 2)
     append_bytes = float(B * (shp.src_append + 1)) * hkv * (2 * d * 2 + ((2 * d + 8) if fp8 else 2 * d * 2)) * L
-    return {"shape": shp, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
+    return {"shape": shp, "wave_timeline": timeline, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
             "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode, "sec_per_step_by_launch": times}
 
 
@@ -830,7 +869,7 @@ def main():
                 "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in ss["sec_per_step_by_launch"].items()},
                 "distinct_layer_caches": ss["distinct_layers"], "resident_cache_gb": round(ss["resident_gb"], 1),
                 "tokens_per_s": round(ss["batch"] * ss["n_tok"] / ss["sec_per_step"], 1),
-                "roofline": _hbm_roofline("decode_split16_kernel<128> (one layer, one token of all 64 streams)", ss["bytes_per_launch"],
+                "roofline": _hbm_roofline("decode_split16_kernel<128, false> (one layer, one token of all 64 streams)", ss["bytes_per_launch"],
                                           ss["split_kernel_ms"], "decode_split16_kernel@cfg5"),
                 "append": {"roofline": _hbm_roofline("kv_append_kernel with rotation (32-token source chunk of 64 streams, one layer, alone on the GPU)",
                                                      ss["append_layer_bytes"], ss["append_layer_ms"], None,
@@ -863,8 +902,9 @@ def main():
                 "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
                 "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
                 "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
-                "roofline": _hbm_roofline("decode_split16_kernel<128> (one layer)", dec["bytes_per_layer"], dec["layer_decode_ms"],
-                                          "decode_split16_kernel@cfg3")}
+                "roofline": _hbm_roofline("decode_split16_kernel<128, true> (one layer)", dec["bytes_per_layer"], dec["layer_decode_ms"],
+                                          "decode_split16_kernel@cfg3"),
+                "wave_timeline": dec["wave_timeline"]}
     if "source_chunk" in legs:
         with _leg(line, "source_chunk", torch):
             sc = bench_source_chunk(st, torch, W, min(args.steps, 20), min(args.warmup, 3))

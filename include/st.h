@@ -80,6 +80,13 @@ enum { ST_PROF_PREFILL_ATTN = 0, ST_PROF_DECODE_SPLIT = 1, ST_PROF_BWD_DQ = 2, S
        ST_PROF_TILE_PACK = 4, ST_PROF_SOURCE_CHUNK = 5 };
 void st_profile_enable(int32_t on);
 st_status st_profile_repeat(int32_t launches);
+/* Wave timeline of the decode split kernel (<= 16 query rows per sequence and KV head, bf16 caches), for the calling
+ * thread's calls while timing is enabled: workgroup i of a launch (one wave: one work unit of one cache of one
+ * sequence and KV head, in the order sequence, head, unit; units past a cache's length end at once) writes the
+ * 100 MHz wall clock at its start and at its end to device_buffer[2 i], device_buffer[2 i + 1] (uint64; device
+ * memory of the caller, 16-byte aligned, n_pairs pairs; workgroups beyond n_pairs write nothing).  Every launch
+ * overwrites the buffer; a null buffer switches the timeline off.  The results of the call are not affected. */
+st_status st_profile_wave_trace(void* device_buffer, int32_t n_pairs);
 st_status st_profile_read(int32_t which, double* mean_ms, int32_t* count);
 
 /* ------------------------------------------------------------------------

@@ -84,6 +84,8 @@ def load_library():
     lib.st_profile_enable.argtypes = [i32]
     lib.st_profile_repeat.restype = i32
     lib.st_profile_repeat.argtypes = [i32]
+    lib.st_profile_wave_trace.restype = i32
+    lib.st_profile_wave_trace.argtypes = [vp, i32]
     lib.st_profile_read.restype = i32
     lib.st_profile_read.argtypes = [i32, C.POINTER(f64), C.POINTER(i32)]
     lib.st_rope_apply.restype = i32
@@ -239,6 +241,15 @@ def st_profile_enable(on):
 
 def st_profile_repeat(launches):
     _check(load_library().st_profile_repeat(int(launches)))
+
+
+def st_profile_wave_trace(buffer):
+    """buffer: int64 / uint64 device tensor of 2 n entries (n (start, end) pairs), or None to switch the timeline off."""
+    if buffer is None:
+        _check(load_library().st_profile_wave_trace(None, 0))
+        return
+    assert buffer.is_cuda and buffer.is_contiguous() and buffer.element_size() == 8
+    _check(load_library().st_profile_wave_trace(_ptr(buffer), buffer.numel() // 2))
 
 
 def st_profile_read(which):

@@ -65,6 +65,27 @@ struct DecodeArgs {
     int append;
     const uint16_t* k_new;
     const uint16_t* v_new;
+    // wave timeline (st_profile_wave_trace): (start, end) wall-clock pairs per workgroup, or null
+    unsigned long long* trace;
+    int trace_cap;
+};
+
+// Stamps the workgroup's start and end into the timeline buffer, whichever way the kernel is left.
+struct WaveStamp {
+    unsigned long long* slot;
+    unsigned long long t0;
+    __device__ __forceinline__ WaveStamp(const DecodeArgs& a) : slot(nullptr), t0(0) {
+        if (a.trace && int(blockIdx.x) < a.trace_cap) {
+            slot = a.trace + 2 * size_t(blockIdx.x);
+            t0 = wall_clock64();
+        }
+    }
+    __device__ __forceinline__ ~WaveStamp() {
+        if (slot && threadIdx.x == 0) {
+            slot[0] = t0;
+            slot[1] = wall_clock64();
+        }
+    }
 };
 
 // Fused query rotation (Sec. 3.2, stream-local position ids): fragments j and j + KS/2 of a lane hold the
@@ -400,6 +421,7 @@ __device__ __forceinline__ void scan_unit16(const CacheView& cv, int b, int h, i
 template <int D, bool STREAM_KEYS>
 __global__ __launch_bounds__(64, 2) void decode_split16_kernel(DecodeArgs a) {
     constexpr int KS = D / 32, DB = D / 16, KCH = D / 8;
+    const WaveStamp stamp(a);
     const int lane = threadIdx.x;
     const int nc = a.ncs + a.ncr + a.append;             // (append: one more slot per sequence and head, the new token's)
     const int c = int(blockIdx.x % unsigned(nc));
@@ -1476,6 +1498,11 @@ static st_status decode_dual_impl(void* out, float* lse, const void* q, const st
     a.append = fuse_token ? 1 : 0;
     a.k_new = static_cast<const uint16_t*>(k_new);
     a.v_new = static_cast<const uint16_t*>(v_new);
+    {
+        const WaveTrace wt = no_alloc ? WaveTrace{nullptr, 0} : prof_wave_trace();
+        a.trace = wt.buf;
+        a.trace_cap = wt.capacity;
+    }
     const size_t slots = size_t(batch) * hkv * size_t(a.ncs + a.ncr + a.append) * a.rows;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + align256(slots * d * sizeof(float)));
@@ -1647,6 +1674,8 @@ static st_status source_chunk_impl(void* out, float* lse, const void* q, const s
     a.ncr = 0;
     a.append = 0;
     a.k_new = a.v_new = nullptr;
+    a.trace = nullptr;
+    a.trace_cap = 0;
     a.scale_log2 = scale * kLog2e;
     a.n_new = n_new;
     a.max_new = max_new;

@@ -24,11 +24,13 @@ namespace {
 struct Region { hipEvent_t a, b; int launches; };
 thread_local bool t_prof_on = false;
 thread_local int t_prof_repeat = 1;
+thread_local WaveTrace t_wave_trace = {nullptr, 0};
 thread_local std::vector<Region> t_regions[kProfCount];
 }  // namespace
 
 bool prof_enabled() { return t_prof_on; }
 int prof_repeat() { return t_prof_on ? t_prof_repeat : 1; }
+WaveTrace prof_wave_trace() { return t_prof_on ? t_wave_trace : WaveTrace{nullptr, 0}; }
 
 void prof_begin(int which, hipStream_t stream) {
     if (!t_prof_on) return;
@@ -53,6 +55,13 @@ extern "C" void st_profile_enable(int32_t on) { st::t_prof_on = on != 0; }
 extern "C" st_status st_profile_repeat(int32_t launches) {
     if (launches < 1 || launches > 64) return st::fail(ST_ERR_INVALID_ARG, "st_profile_repeat: %d launches (1 .. 64)", launches);
     st::t_prof_repeat = launches;
+    return ST_OK;
+}
+
+extern "C" st_status st_profile_wave_trace(void* device_buffer, int32_t n_pairs) {
+    if (device_buffer && (n_pairs <= 0 || (reinterpret_cast<uintptr_t>(device_buffer) & 15u)))
+        return st::fail(ST_ERR_INVALID_ARG, "st_profile_wave_trace: buffer must be 16-byte aligned and hold at least one pair");
+    st::t_wave_trace = st::WaveTrace{static_cast<unsigned long long*>(device_buffer), device_buffer ? n_pairs : 0};
     return ST_OK;
 }
 

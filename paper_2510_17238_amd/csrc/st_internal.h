@@ -47,6 +47,13 @@ bool prof_enabled();
 int prof_repeat();
 void prof_begin(int which, hipStream_t stream);
 void prof_end(int which, hipStream_t stream);
+// Wave timeline (st_profile_wave_trace, per calling thread; only while timing is on): a device buffer of
+// (start, end) pairs of the 100 MHz wall clock, one per workgroup of the decode split kernel's launch.
+struct WaveTrace {
+    unsigned long long* buf;
+    int capacity;        // pairs
+};
+WaveTrace prof_wave_trace();
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -889,6 +889,39 @@ def test_decode_append_in_one_call_random_lengths(st):
         assert (lse_f - lse_u).abs().max().item() <= 1e-2, tag
 
 
+def test_decode_wave_timeline_changes_no_result(st):
+    """st_profile_wave_trace: every workgroup of the split kernel's launch leaves a (start, end) pair of the wall clock in
+    the caller's buffer; the step's output keeps its bits; without timing enabled nothing is written."""
+    rng = np.random.Generator(np.random.PCG64(460))
+    batch, hq, hkv, d = 3, 8, 2, 128
+    src_lens = np.array([1500, 40, 700]); rsn_lens = np.array([900, 2100, 0])
+    caches, _, _ = _fill_dual(st, rng, batch, hkv, d, src_lens, rsn_lens)
+    tq = to_dev(W.normal(rng, (batch, 1, hq, d), "bf16"), "bf16")
+    vis = torch.from_numpy(src_lens.astype(np.int32)).to(DEV); rl = torch.from_numpy(rsn_lens.astype(np.int32)).to(DEV)
+    max_s, max_r = int(src_lens.max()), int(rsn_lens.max())
+    ref = st.st_attn_decode_dual(tq, caches, vis, rl, max_s, max_r)
+    buf = torch.zeros((4096, 2), dtype=torch.int64, device=DEV)
+    st.st_profile_wave_trace(buf)
+    out_off = st.st_attn_decode_dual(tq, caches, vis, rl, max_s, max_r)       # timing not enabled: no stamps
+    torch.cuda.synchronize()
+    assert int(buf.abs().sum()) == 0
+    st.st_profile_enable(True)
+    try:
+        out_on = st.st_attn_decode_dual(tq, caches, vis, rl, max_s, max_r)
+    finally:
+        st.st_profile_enable(False)
+        st.st_profile_wave_trace(None)
+    torch.cuda.synchronize()
+    st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    assert torch.equal(ref, out_off) and torch.equal(ref, out_on)
+    a = buf.cpu().numpy()
+    n = int((a[:, 1] > 0).sum())
+    # one workgroup per (sequence, KV head, unit slot of either cache): a multiple of batch x heads, all stamped, contiguous
+    assert n > 0 and n % (batch * hkv) == 0 and (a[:n, 1] > 0).all() and (a[n:] == 0).all()
+    assert (a[:n, 1] >= a[:n, 0]).all()
+    assert (a[:n, 1].max() - a[:n, 0].min()) < 100 * 1000 * 100             # the launch took less than 100 ms of the 100 MHz clock
+
+
 def test_decode_empty_row(st):
     """Both lengths zero: out = 0, lse = -inf."""
     rng = np.random.Generator(np.random.PCG64(413))
