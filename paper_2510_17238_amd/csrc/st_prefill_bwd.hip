@@ -252,6 +252,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
         qf[j] = *reinterpret_cast<const bf16x8*>(q + rowhead * D + 8 * hg + 16 * j);
         dof[j] = *reinterpret_cast<const bf16x8*>(d_out + rowhead * D + 8 * hg + 16 * j);
     }
+    // queries times scale * log2(e), rounded to bf16 again (as in the forward kernel): K q' is a score in exponent units
+#pragma unroll
+    for (int j = 0; j < KS; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[j][e] = (__bf16)(float(qf[j][e]) * scale_log2);
     f32x16 acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -266,7 +271,17 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
     }
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // Score and dP blocks of a tile.  A lane owns one query row, so what has to be taken off every score (the row's
+    // log-sum-exp) and off every dP (the row's delta) is one number per lane: between tiles the LAST block of each
+    // kind holds it, negated, in all sixteen registers, and the first matrix instruction of every block takes that as
+    // its accumulator input (the last block in place, after the others have read it).
+    f32x16 s_acc[SB], dp_acc[SB];
+    const float neg_lse2 = -lse2, neg_delta = -my_delta;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        asm volatile("v_mov_b32 %0, %1" : "=v"(s_acc[SB - 1][i]) : "v"(neg_lse2));
+        asm volatile("v_mov_b32 %0, %1" : "=v"(dp_acc[SB - 1][i]) : "v"(neg_delta));
+    }
 
     for (int ti = 0; ti < n_tiles; ++ti) {
         const int buf = ti & 1;
@@ -282,7 +297,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
 
         // operands leave LDS a group of matrix instructions ahead of their use (one wave per SIMD: nobody else hides
         // that latency); scheduling barriers keep the order
-        f32x16 s_acc[SB], dp_acc[SB];
         const uint16_t* kb = &sm.k[buf][0];
         const uint16_t* vb = &sm.v[buf][0];
         const uint16_t* tb = &sm.kt[0][0];
@@ -311,25 +325,36 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
 #pragma unroll
             for (int u = 0; u < G; ++u) {
                 const int f = g * G + u, sb = f % SB, j = f / SB;
-                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[g & 1][u], qf[j], j == 0 ? zero16 : s_acc[sb], 0, 0, 0);
-                dp_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[g & 1][u], dof[j], j == 0 ? zero16 : dp_acc[sb], 0, 0, 0);
+                s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[g & 1][u], qf[j], j == 0 ? s_acc[SB - 1] : s_acc[sb], 0, 0, 0);
+                dp_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[g & 1][u], dof[j], j == 0 ? dp_acc[SB - 1] : dp_acc[sb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
         // lane (n, hg), block sb, register i  <->  key column kt*64 + 32 sb + 16 (i/8) + 8 hg + i%8
         bf16x8 dsb[SB][2];
-        const int c0 = kt * kTileN + 8 * hg;
+        if (partial) {                   // (uniform) only the tiles on the edge of what the rows may see
+            const int c0 = kt * kTileN + 8 * hg;
+#pragma unroll
+            for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int col = c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
+                    s_acc[sb][i] = col < limit ? s_acc[sb][i] : -INFINITY;
+                }
+        }
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(fmaf(s_acc[sb][i], scale_log2, -lse2));
-                if (partial) {
-                    const int col = c0 + 32 * sb + 16 * (i >> 3) + (i & 7);
-                    p = col < limit ? p : 0.f;
-                }
-                dsb[sb][i >> 3][i & 7] = (__bf16)(p * (dp_acc[sb][i] - my_delta));
+                const float p = __builtin_amdgcn_exp2f(s_acc[sb][i]);
+                dsb[sb][i >> 3][i & 7] = (__bf16)(p * dp_acc[sb][i]);
             }
+        // (written as instructions: left to the compiler, the two constant blocks become thirty-two more live registers)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            asm volatile("v_mov_b32 %0, %1" : "=v"(s_acc[SB - 1][i]) : "v"(neg_lse2));
+            asm volatile("v_mov_b32 %0, %1" : "=v"(dp_acc[SB - 1][i]) : "v"(neg_delta));
+        }
         wait_vmcnt<2 * NL>();            // K^T of this tile has landed (the next row tiles may still fly) ...
         __syncthreads();                 // ... for every wave
         load2(0, NG1 & 1);
