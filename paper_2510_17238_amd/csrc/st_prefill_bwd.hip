@@ -388,8 +388,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
 
 
 // Row statistics of the backward in tile order: for every 64-row tile of a stream and every query head one
-// 1 KB block of 256 floats -- [0, 64) lse in base-2 units (+inf for rows past the end of the stream: their
-// probabilities become 0), [64, 128) delta, [128, 192) the visible-source count of the row (as int bits) --
+// 1 KB block of 256 floats -- [0, 64) MINUS lse in base-2 units (-inf for rows past the end of the stream: their
+// probabilities become 0), [64, 128) MINUS delta, [128, 192) the visible-source count of the row (as int bits) --
 // so that the key-side kernel fetches them with ONE asynchronous copy per tile.  delta is also written in
 // token order for the query-side kernel.
 template <int D>
@@ -433,8 +433,8 @@ __global__ __launch_bounds__(256) void bwd_rowstats_kernel(float* __restrict__ s
         delta_tok[rh] = dl;
     }
     float* blk = stats + (size_t(h) * pv.pack_tiles + tile) * 256;
-    blk[r] = l2;
-    blk[64 + r] = dl;
+    blk[r] = -l2;                                                // (negated: where the key-side kernel's accumulators start)
+    blk[64 + r] = -dl;
     blk[128 + r] = __int_as_float(vs);
     blk[192 + r] = 0.f;
 }
@@ -449,6 +449,13 @@ __global__ __launch_bounds__(256) void bwd_rowstats_kernel(float* __restrict__ s
 //   dK^T += Q^T dS  (Q^T tile from LDS, dS from the accumulators)
 // Rows run along the accumulator registers here, so lse / delta / visible count of the rows come from the
 // tile's 1 KB statistics block in LDS.  Two buffers per tile kind (130 KB), one barrier per query tile.
+// acc += A B with the accumulator in ACCUMULATION registers, whatever form the compiler gives the file's other matrix
+// instructions: the key-side kernel's two output accumulators (128 registers) live there for the whole kernel, the
+// score and dP blocks in vector registers where the exponentials read them -- no copies between the two files.
+__device__ __forceinline__ void mfma_into_agprs(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 template <int D>
 struct BwdDkvSmem {
     uint16_t qr[2][kTileN * D];       // Q rows
@@ -516,6 +523,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         kf[j] = *reinterpret_cast<const bf16x8*>(k + keyhead * D + 8 * hg + 16 * j);
         vf[j] = *reinterpret_cast<const bf16x8*>(v + keyhead * D + 8 * hg + 16 * j);
     }
+    // keys times scale * log2(e), rounded to bf16 again: Q k' is a score in exponent units (dK takes Q, not K)
+#pragma unroll
+    for (int j = 0; j < KS; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kf[j][e] = (__bf16)(float(kf[j][e]) * (scale * kLog2e));
 #pragma unroll
     for (int j = 0; j < KS; ++j) {                              // landed before the loop (it counts its own copies)
         u32x4 t = __builtin_bit_cast(u32x4, kf[j]), u = __builtin_bit_cast(u32x4, vf[j]);
@@ -578,8 +590,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
     }
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const float scale_log2 = scale * kLog2e;
 
     for (int x = 0; x < n_iter; ++x) {
         const int buf = x & 1;
@@ -614,6 +624,23 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
                 fq[slot][u] = *reinterpret_cast<const bf16x8*>(tq + 32 * db * kTileN + voff[stp]);
             }
         };
+        // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key.
+        // The accumulators start at minus the rows' log-sum-exp (scores) and minus their delta (dP), straight from the
+        // tile's statistics block: what comes out is the exponent of P and dP - delta.
+        const float* st = &sm.stats[buf][0];
+#pragma unroll
+        for (int rb = 0; rb < SB; ++rb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int r0 = 32 * rb + 16 * (q4 >> 1) + 8 * hg + 4 * (q4 & 1);
+                const f32x4 a = *reinterpret_cast<const f32x4*>(st + r0);
+                const f32x4 b2 = *reinterpret_cast<const f32x4*>(st + 64 + r0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    s_acc[rb][4 * q4 + e] = a[e];
+                    dp_acc[rb][4 * q4 + e] = b2[e];
+                }
+            }
         load1(0, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -623,14 +650,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 #pragma unroll
             for (int u = 0; u < G; ++u) {
                 const int f = g * G + u, rb = f % SB, j = f / SB;
-                s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[g & 1][u], kf[j], j == 0 ? zero16 : s_acc[rb], 0, 0, 0);
-                dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[g & 1][u], vf[j], j == 0 ? zero16 : dp_acc[rb], 0, 0, 0);
+                s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[g & 1][u], kf[j], s_acc[rb], 0, 0, 0);
+                dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[g & 1][u], vf[j], dp_acc[rb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key
         bf16x8 pb[SB][2], dsb[SB][2];
-        const float* st = &sm.stats[buf][0];
         // every row of the tile sees every key of this wave?  (rows are ordered, visible counts do not decrease)
         const int first_vis = __builtin_amdgcn_readfirstlane(__float_as_int(st[128]));
         const bool all_seen = cur.rs ? first_vis > wave_last_key : cur.row0 >= wave_last_key;
@@ -638,20 +663,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 #pragma unroll
             for (int rb = 0; rb < SB; ++rb)
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int r0 = 32 * rb + 16 * half + 8 * hg;
-#pragma unroll
-                    for (int q4 = 0; q4 < 2; ++q4) {
-                        const f32x4 a = *reinterpret_cast<const f32x4*>(st + r0 + 4 * q4);
-                        const f32x4 b2 = *reinterpret_cast<const f32x4*>(st + 64 + r0 + 4 * q4);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int i = 8 * half + 4 * q4 + e;
-                            const float p = __builtin_amdgcn_exp2f(fmaf(s_acc[rb][i], scale_log2, -a[e]));
-                            pb[rb][half][4 * q4 + e] = (__bf16)p;
-                            dsb[rb][half][4 * q4 + e] = (__bf16)(p * (dp_acc[rb][i] - b2[e]));
-                        }
-                    }
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(s_acc[rb][i]);
+                    pb[rb][i >> 3][i & 7] = (__bf16)p;
+                    dsb[rb][i >> 3][i & 7] = (__bf16)(p * dp_acc[rb][i]);
                 }
         } else
 #pragma unroll
@@ -659,29 +674,22 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int r0 = 32 * rb + 16 * half + 8 * hg;           // first of the 8 consecutive rows of these registers
-                float l2[8], dl[8];
                 int vs[8];
 #pragma unroll
                 for (int q4 = 0; q4 < 2; ++q4) {
-                    const f32x4 a = *reinterpret_cast<const f32x4*>(st + r0 + 4 * q4);
-                    const f32x4 b2 = *reinterpret_cast<const f32x4*>(st + 64 + r0 + 4 * q4);
                     const f32x4 c2 = *reinterpret_cast<const f32x4*>(st + 128 + r0 + 4 * q4);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        l2[4 * q4 + e] = a[e];
-                        dl[4 * q4 + e] = b2[e];
-                        vs[4 * q4 + e] = __float_as_int(c2[e]);
-                    }
+                    for (int e = 0; e < 4; ++e) vs[4 * q4 + e] = __float_as_int(c2[e]);
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int i = 8 * half + e;
                     const int row = cur.row0 + r0 + e;
                     const bool seen = cur.rs ? vs[e] > my_key : row >= my_key;
-                    float p = __builtin_amdgcn_exp2f(fmaf(s_acc[rb][i], scale_log2, -l2[e]));
+                    float p = __builtin_amdgcn_exp2f(s_acc[rb][i]);
                     p = seen ? p : 0.f;
                     pb[rb][half][e] = (__bf16)p;
-                    dsb[rb][half][e] = (__bf16)(p * (dp_acc[rb][i] - dl[e]));
+                    dsb[rb][half][e] = (__bf16)(p * dp_acc[rb][i]);
                 }
             }
         __builtin_amdgcn_sched_barrier(0);
@@ -692,13 +700,16 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 #pragma unroll
             for (int u = 0; u < G; ++u) {
                 const int f = g * G + u, db = f % DB, stp = f / DB;  // rows 16 stp .. 16 stp + 15 of the tile
-                dv_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[slot][u], pb[stp >> 1][stp & 1], dv_acc[db], 0, 0, 0);
-                dk_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[slot][u], dsb[stp >> 1][stp & 1], dk_acc[db], 0, 0, 0);
+                mfma_into_agprs(dv_acc[db], fo[slot][u], pb[stp >> 1][stp & 1]);
+                mfma_into_agprs(dk_acc[db], fq[slot][u], dsb[stp >> 1][stp & 1]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
     wait_vmcnt<0>();
+    // (the matrix instructions above are written as text: the compiler does not know that their results need some
+    // cycles before an ordinary instruction may read them)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     if (!active) return;
     uint16_t* pk = dk + keyhead * D;
     uint16_t* pvv = dv + keyhead * D;
