@@ -173,9 +173,11 @@ def bench_prefill_step(st, torch, W, cfg, steps, warmup, use_graph=True, fused_r
         main = torch.cuda.current_stream()
         cs.appended_len.copy_(len_s0); cr.appended_len.copy_(len_r0)      # same state every step
         side.wait_stream(main)
-        with torch.cuda.stream(side):                                       # arriving source chunk (Alg. 1, prefill loop)
+        with torch.cuda.stream(side):
+            # the plan needs the ids only: it is built beside the rotation (the attention call orders itself against the
+            # build); then the arriving source chunk (Alg. 1, prefill loop)
+            p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws, stream=side)
             st.st_kv_append(caches, st.ST_SOURCE, k_src_new, v_src_new, host_len_upper_bound=max_s + chunk, stream=side)
-        p = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens, workspace=plan_ws)
         if fused_rope:
             # rotation inside the attention call: keys on their way into the key tiles, queries as they are loaded
             st.st_attn_prefill_rope(q, k, v, pos, cfg.theta, p, out=out, workspace=pre_ws)
