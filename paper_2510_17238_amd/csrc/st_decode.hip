@@ -982,7 +982,8 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(DecodeArgs a, uint16
 // operands from there, so a page is fetched from L2 once per workgroup and not once per row block.  The pool
 // layout of K is conflict-free as it is (16 slots x 16 bytes contiguous per 8-dim chunk); the 32-byte rows of V
 // are not, so the copy swaps the two halves of every second group of 8 rows (by choosing what each lane fetches).
-// Softmax with the lazy reference exponent of the other kernels; partial results [B][Hkv][row block][unit][32 rows],
+// Softmax as in the prefill kernel (prescaled queries, reference parked in the last score block, no running maximum);
+// partial results [B][Hkv][row block][unit][32 rows],
 // merged by chunk_combine_kernel.
 // Work units of one sequence's source cache: as few as keep a unit within `target` tokens, all of the same length
 // (a multiple of 64 tokens) -- equal units finish together, a long one beside a short remainder does not.

@@ -154,13 +154,10 @@ __global__ __launch_bounds__(kTileM) void prefill_simple_kernel(T* __restrict__ 
 // Either way a wave cannot count on other waves to fill the matrix pipe while it does its softmax, so
 // the loop is software-pipelined by hand, in the exact instruction order wanted:
 //   phase X of tile t:  scores of tile t+1   beside  exp2 / bf16 P / row sum of tile t
-//   phase Y of tile t:  O^T += V^T P^T        beside  exponents and row maximum of tile t+1
-// with ONE barrier per key tile.
-// The running maximum of a row is lazy: the reference exponent m_ref is only moved when the maximum of a
-// new tile exceeds it by more than kLazyMax (base-2 exponent units).  Probabilities are then bounded by
-// 2^kLazyMax instead of 1, which neither fp32 nor bf16 minds, the final division by l is unchanged, and
-// the rescale of l and of the output accumulator (an out-of-line block) becomes a rare event instead of a
-// per-tile one.
+//   phase Y of tile t:  O^T += V^T P^T        beside  the moves of tile t+1's scores out of the accumulation registers
+// with ONE barrier per key tile.  There is no running maximum of a row (see the list at the kernel): the reference
+// exponent m_ref is the row maximum of the first tile and only moves when a tile's weights sum beyond 2^kRiseLog2,
+// an out-of-line block.
 // Fused rotation (Sec. 3.2), step 1: the (cos, sin) pairs of every packed row -- `tab` [packed tile][64 rows][D/2]
 // float2, row r of a stream's tile t at (tile t) * 64 + r -- evaluated ONCE per token (not once per head): the key
 // pack below and the attention kernel's query load both rotate with them.  The angle position * theta^(-2i/D) is
