@@ -600,28 +600,33 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 
         // Operands come out of LDS a group of matrix instructions ahead of their use (one wave per SIMD: nobody else
         // hides that latency): groups of 4 fragments per tensor, the next group requested before the current one is
-        // multiplied; scheduling barriers keep that order.
+        // multiplied; scheduling barriers keep that order.  The tile's two 32-row halves are staggered so that the
+        // vector work of one half runs beside matrix work of the other:
+        //     matrix pipe:  S, dP of half 0 | S, dP of half 1     | dV, dK of half 0    | dV, dK of half 1
+        //     vector ALU :                  | P, dS of half 0     | P, dS of half 1     |
+        // (two scores' worth of vector work behind every second matrix instruction; tiles on the edge of what the
+        // rows may see form P and dS with their masks between the blocks instead).
+        static_assert(SB == 2 && (DB == 4 || DB == 2) && KS == 2 * DB, "the stagger below is written for 64-row tiles of 64 or 128 dims");
         f32x16 s_acc[SB], dp_acc[SB];
         const uint16_t* qb = &sm.qr[buf][0];
         const uint16_t* ob = &sm.dor[buf][0];
         const uint16_t* tq = &sm.qt[buf][0];
         const uint16_t* to = &sm.dot[buf][0];
-        constexpr int G = 4, NG1 = SB * KS / G, NG2 = DB * SB * 2 / G;
+        constexpr int G = DB;                                // fragments per tensor and group; eight score pairs per half go beside 2 G pairs of matrix instructions
+        constexpr int PIECES = 4 / G;
         bf16x8 fq[2][G], fo[2][G];
-        auto load1 = [&](int g, int slot) {
+        auto load1 = [&](int rb, int g, int slot) {          // Q and dO rows of half rb, k-steps G g .. G g + G - 1
 #pragma unroll
             for (int u = 0; u < G; ++u) {
-                const int f = g * G + u, rb = f % SB, j = f / SB;
-                fq[slot][u] = *reinterpret_cast<const bf16x8*>(qb + 32 * rb * D + koff[j]);
-                fo[slot][u] = *reinterpret_cast<const bf16x8*>(ob + 32 * rb * D + koff[j]);
+                fq[slot][u] = *reinterpret_cast<const bf16x8*>(qb + 32 * rb * D + koff[G * g + u]);
+                fo[slot][u] = *reinterpret_cast<const bf16x8*>(ob + 32 * rb * D + koff[G * g + u]);
             }
         };
-        auto load2 = [&](int g, int slot) {
+        auto load2 = [&](int stp, int slot) {                // dO^T and Q^T of rows 16 stp .. 16 stp + 15, all d blocks
 #pragma unroll
             for (int u = 0; u < G; ++u) {
-                const int f = g * G + u, db = f % DB, stp = f / DB;
-                fo[slot][u] = *reinterpret_cast<const bf16x8*>(to + 32 * db * kTileN + voff[stp]);
-                fq[slot][u] = *reinterpret_cast<const bf16x8*>(tq + 32 * db * kTileN + voff[stp]);
+                fo[slot][u] = *reinterpret_cast<const bf16x8*>(to + 32 * u * kTileN + voff[stp]);
+                fq[slot][u] = *reinterpret_cast<const bf16x8*>(tq + 32 * u * kTileN + voff[stp]);
             }
         };
         // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key.
@@ -641,36 +646,20 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
                     dp_acc[rb][4 * q4 + e] = b2[e];
                 }
             }
-        load1(0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int g = 0; g < NG1; ++g) {
-            if (g + 1 < NG1) load1(g + 1, (g + 1) & 1);
-            else load2(0, NG1 & 1);                          // the first group of the last two products
-#pragma unroll
-            for (int u = 0; u < G; ++u) {
-                const int f = g * G + u, rb = f % SB, j = f / SB;
-                s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[g & 1][u], kf[j], s_acc[rb], 0, 0, 0);
-                dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[g & 1][u], vf[j], dp_acc[rb], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        bf16x8 pb[SB][2], dsb[SB][2];
         // every row of the tile sees every key of this wave?  (rows are ordered, visible counts do not decrease)
         const int first_vis = __builtin_amdgcn_readfirstlane(__float_as_int(st[128]));
         const bool all_seen = cur.rs ? first_vis > wave_last_key : cur.row0 >= wave_last_key;
-        if (all_seen) {
-#pragma unroll
-            for (int rb = 0; rb < SB; ++rb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(s_acc[rb][i]);
-                    pb[rb][i >> 3][i & 7] = (__bf16)p;
-                    dsb[rb][i >> 3][i & 7] = (__bf16)(p * dp_acc[rb][i]);
-                }
-        } else
-#pragma unroll
-        for (int rb = 0; rb < SB; ++rb)
+        bf16x8 pb[SB][2], dsb[SB][2];
+        // P and dS of two neighbouring registers of half rb (no mask)
+        auto soft2 = [&](int rb, int i) {
+            const float p0 = __builtin_amdgcn_exp2f(s_acc[rb][i]), p1 = __builtin_amdgcn_exp2f(s_acc[rb][i + 1]);
+            pb[rb][i >> 3][i & 7] = (__bf16)p0;
+            pb[rb][i >> 3][(i & 7) + 1] = (__bf16)p1;
+            dsb[rb][i >> 3][i & 7] = (__bf16)(p0 * dp_acc[rb][i]);
+            dsb[rb][i >> 3][(i & 7) + 1] = (__bf16)(p1 * dp_acc[rb][i + 1]);
+        };
+        // ... of a whole half, with the rows' masks
+        auto soft_masked = [&](int rb) {
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int r0 = 32 * rb + 16 * half + 8 * hg;           // first of the 8 consecutive rows of these registers
@@ -692,19 +681,72 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
                     dsb[rb][half][e] = (__bf16)(p * dp_acc[rb][i]);
                 }
             }
-        __builtin_amdgcn_sched_barrier(0);
+        };
+        // S, dP of half rb: 16 matrix instructions in two groups; `next` requests the fragments that follow the block;
+        // SOFT >= 0: P and dS of that (other) half beside them
+        auto scores = [&](auto soft_tag, int rb, int slot0, auto next) {
+            constexpr int SOFT = decltype(soft_tag)::value;
 #pragma unroll
-        for (int g = 0; g < NG2; ++g) {
-            const int slot = (NG1 + g) & 1;
-            if (g + 1 < NG2) load2(g + 1, slot ^ 1);
+            for (int g = 0; g < 2; ++g) {
+                const int slot = slot0 ^ g;
+                if (g == 0) load1(rb, 1, slot ^ 1);
+                else next(slot ^ 1);
 #pragma unroll
-            for (int u = 0; u < G; ++u) {
-                const int f = g * G + u, db = f % DB, stp = f / DB;  // rows 16 stp .. 16 stp + 15 of the tile
-                mfma_into_agprs(dv_acc[db], fo[slot][u], pb[stp >> 1][stp & 1]);
-                mfma_into_agprs(dk_acc[db], fq[slot][u], dsb[stp >> 1][stp & 1]);
+                for (int u = 0; u < G; ++u) {
+                    s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[slot][u], kf[G * g + u], s_acc[rb], 0, 0, 0);
+                    if (SOFT >= 0) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (all_seen) {                      // (uniform; only the vector work is conditional: a branch
+                                                             //  around matrix instructions makes the compiler copy their accumulators)
+#pragma unroll
+                            for (int k = 0; k < PIECES; ++k) soft2(SOFT, 2 * ((G * g + u) * PIECES + k));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    dp_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[slot][u], vf[G * g + u], dp_acc[rb], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+        };
+        // dV, dK of half rb: 16 matrix instructions in two groups (rows 16 stp .. + 15 each)
+        auto grads = [&](auto soft_tag, int rb, int slot0, auto next) {
+            constexpr int SOFT = decltype(soft_tag)::value;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int slot = slot0 ^ g;
+                if (g == 0) load2(2 * rb + 1, slot ^ 1);
+                else next(slot ^ 1);
+#pragma unroll
+                for (int u = 0; u < G; ++u) {
+                    mfma_into_agprs(dv_acc[u], fo[slot][u], pb[rb][g]);
+                    if (SOFT >= 0) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (all_seen) {                      // (uniform; only the vector work is conditional: a branch
+                                                             //  around matrix instructions makes the compiler copy their accumulators)
+#pragma unroll
+                            for (int k = 0; k < PIECES; ++k) soft2(SOFT, 2 * ((G * g + u) * PIECES + k));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    mfma_into_agprs(dk_acc[u], fq[slot][u], dsb[rb][g]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        using None = std::integral_constant<int, -1>;
+        using Half0 = std::integral_constant<int, 0>;
+        using Half1 = std::integral_constant<int, 1>;
+        load1(0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        scores(None{}, 0, 0, [&](int slot) { load1(1, 0, slot); });
+        scores(Half0{}, 1, 0, [&](int slot) { load2(0, slot); });
+        if (!all_seen) {
+            soft_masked(0);
+            soft_masked(1);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        grads(Half1{}, 0, 0, [&](int slot) { load2(2, slot); });
+        grads(None{}, 1, 0, [&](int) {});
     }
     wait_vmcnt<0>();
     // (the matrix instructions above are written as text: the compiler does not know that their results need some
