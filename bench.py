@@ -705,40 +705,44 @@ def bench_source_chunk(st, torch, W, steps, warmup):
 
 
 def cpu_baseline(W, O):
-    """The fp64 oracle, as it stands, on a bounded sample of the headline workload (configs[3]): sequence 0, the two query
-    heads of KV head 0, interleaved quarters of its query rows until 10 s are spent (RoPE of the slice included)."""
+    """The fp64 oracle, as it stands, on a bounded sample of the headline workload (configs[3]): the two query heads of KV
+    head 0, sequence by sequence and, within a sequence, one interleaved quarter of its query rows at a time, until 10 s
+    are spent (RoPE of the slice included)."""
     cfg = W.config4a()
-    s, e = int(cfg.cu_seqlens[0]), int(cfg.cu_seqlens[1])
-    rng = np.random.Generator(np.random.PCG64(cfg.seed + 1000))
-    n, d = e - s, cfg.head_dim
-    q = W.normal(rng, (n, 2, d), "bf16"); k = W.normal(rng, (n, 1, d), "bf16"); v = W.normal(rng, (n, 1, d), "bf16")
-    stream, seg, pos = cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e]
+    d = cfg.head_dim
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    # rows 0, 4, 8, ... first, then 1, 5, 9, ... and so on: every pass has the sequence's mix of row lengths; passes
-    # stop once 10 s are spent (at most the four that cover every row)
+    # rows 0, 4, 8, ... first, then 1, 5, 9, ... and so on: every pass has the sequence's mix of row lengths
     dt, vis, n_rows, passes = 0.0, 0, 0, 0
-    for off in range(4):
-        rows = np.arange(off, n, 4)
-        t0 = time.perf_counter()
-        qr = O.rope(q, pos, cfg.theta); kr = O.rope(k, pos, cfg.theta)
-        O.attention_dense(qr, kr, v, stream, seg, pos, rows=rows)
-        dt += time.perf_counter() - t0
-        vis += int(O.mask_rows(stream, seg, pos, rows).sum())             # visible pairs of the sampled rows
-        n_rows += len(rows); passes += 1
+    for b in range(cfg.batch):
+        s, e = int(cfg.cu_seqlens[b]), int(cfg.cu_seqlens[b + 1])
+        n = e - s
+        rng = np.random.Generator(np.random.PCG64(cfg.seed + 1000 + b))
+        q = W.normal(rng, (n, 2, d), "bf16"); k = W.normal(rng, (n, 1, d), "bf16"); v = W.normal(rng, (n, 1, d), "bf16")
+        stream, seg, pos = cfg.stream_ids[s:e], cfg.segment_ids[s:e], cfg.positions[s:e]
+        for off in range(4):
+            rows = np.arange(off, n, 4)
+            t0 = time.perf_counter()
+            qr = O.rope(q, pos, cfg.theta); kr = O.rope(k, pos, cfg.theta)
+            O.attention_dense(qr, kr, v, stream, seg, pos, rows=rows)
+            dt += time.perf_counter() - t0
+            vis += int(O.mask_rows(stream, seg, pos, rows).sum())         # visible pairs of the sampled rows
+            n_rows += len(rows); passes += 1
+            if dt >= 10.0:
+                break
         if dt >= 10.0:
             break
     fl = 4.0 * d * 2 * vis
     whole = cfg.closed_form_pairs()
     total_pairs = float(sum(whole)) * cfg.n_q_heads
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"configs[3], sequence 0 ({n} tokens), the 2 query heads of KV head 0, {passes} of 4 interleaved quarters of its "
-                      f"query rows ({n_rows} rows, {vis} visible pairs per head): RoPE + dense-mask fp64 attention in {dt:.1f} s; "
-                      f"extrapolated per visible pair, the whole batch (8 sequences x 32 heads, {total_pairs:.3g} pairs) would take "
-                      f"{dt * total_pairs / (2.0 * vis) / 60:.0f} min on these cores"}
+            "sample": f"configs[3], the 2 query heads of KV head 0, {passes} passes of a quarter of a sequence's query rows each (interleaved "
+                      f"rows; {passes / 4.0:g} of the 8 sequences, {n_rows} rows, {vis} visible pairs per head): RoPE + dense-mask fp64 "
+                      f"attention in {dt:.1f} s; extrapolated per visible pair, the whole batch (8 sequences x 32 heads, "
+                      f"{total_pairs:.3g} pairs) would take {dt * total_pairs / (2.0 * vis) / 60:.0f} min on these cores"}
 
 
 def _hbm_roofline(kernel, nbytes, ms, traffic_key=None, note=None):
