@@ -920,6 +920,20 @@ def test_decode_wave_timeline_changes_no_result(st):
     assert n > 0 and n % (batch * hkv) == 0 and (a[:n, 1] > 0).all() and (a[n:] == 0).all()
     assert (a[:n, 1] >= a[:n, 0]).all()
     assert (a[:n, 1].max() - a[:n, 0].min()) < 100 * 1000 * 100             # the launch took less than 100 ms of the 100 MHz clock
+    # a buffer shorter than the launch: only its pairs are written
+    small = torch.zeros((16, 2), dtype=torch.int64, device=DEV)
+    st.st_profile_wave_trace(small[:10])
+    st.st_profile_enable(True)
+    try:
+        out_small = st.st_attn_decode_dual(tq, caches, vis, rl, max_s, max_r)
+    finally:
+        st.st_profile_enable(False)
+        st.st_profile_wave_trace(None)
+    torch.cuda.synchronize()
+    st.st_profile_read(st.ST_PROF_DECODE_SPLIT)
+    assert torch.equal(ref, out_small)
+    b2 = small.cpu().numpy()
+    assert (b2[:10, 1] > 0).all() and (b2[10:] == 0).all()
 
 
 def test_decode_empty_row(st):
