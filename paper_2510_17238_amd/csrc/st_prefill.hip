@@ -310,20 +310,6 @@ struct PipeSmem {
 // --------------------------------------------------------------------------
 constexpr float kRiseLog2 = 24.f;
 
-// NL wave-wide 16-byte copies global -> LDS, 1 KB apart on both sides: the instruction's immediate offset moves
-// the global address and the LDS address alike, so the LDS base goes into m0 once.
-template <int NL>
-__device__ __forceinline__ void async_copy_rows(const void* base, uint32_t lane_off, uint32_t lds_off) {
-    static_assert(NL == 2 || NL == 4, "tile sizes of head_dim 64 and 128");
-    if constexpr (NL == 4)
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024\n\t"
-                     "global_load_lds_dwordx4 %0, %1 offset:2048\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072"
-                     ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory", "m0");
-    else
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024"
-                     ::"v"(lane_off), "s"(base), "s"(lds_off) : "memory", "m0");
-}
-
 template <int D, int NH, bool ROPE>
 __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_attn_kernel(uint16_t* __restrict__ out, float* __restrict__ lse,
                                                                    const uint16_t* __restrict__ q,

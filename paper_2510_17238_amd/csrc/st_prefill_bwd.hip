@@ -215,7 +215,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
     const int n = lane & 31, hg = lane >> 5;
     const int n_tiles = it.a_total + it.b_total;
 
-    const size_t head_off = size_t(hk) * pv.pack_tiles * TILE + (wave * NL) * 512 + lane * 8;
+    const size_t head_off = size_t(hk) * pv.pack_tiles * TILE + size_t(__builtin_amdgcn_readfirstlane(wave) * NL) * 512;   // (+ 16 bytes per lane)
+    const uint32_t lane_off = uint32_t(lane) * 16u;
     auto tile_of = [&](int ti) {
         ti = min(ti, n_tiles - 1);
         return ti < it.a_total ? it.tile_a0 + ti : it.tile_b0 + (ti - it.a_total);
@@ -225,15 +226,12 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
                    lds_kt = uint32_t(uintptr_t(&sm.kt[0][0])) + wave_off;
     auto issue_rows = [&](int ti, int buf) {
         const size_t off = head_off + size_t(tile_of(ti)) * TILE;
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(krows + off + u * 512, lds_k + buf * (TILE * 2) + u * 1024);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(vrows + off + u * 512, lds_v + buf * (TILE * 2) + u * 1024);
+        async_copy_rows<NL>(krows + off, lane_off, lds_k + buf * (TILE * 2));
+        async_copy_rows<NL>(vrows + off, lane_off, lds_v + buf * (TILE * 2));
     };
     auto issue_kt = [&](int ti) {
         const size_t off = head_off + size_t(tile_of(ti)) * TILE;
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(ktr + off + u * 512, lds_kt + u * 1024);
+        async_copy_rows<NL>(ktr + off, lane_off, lds_kt);
     };
     issue_rows(0, 0);
 
@@ -561,15 +559,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto issue = [&](int x, int buf) {
         const Iter r = iter_of(x);
-        const size_t off = (size_t(r.hq) * pv.pack_tiles + r.tile) * TILE + (wave * NL) * 512 + lane * 8;
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(qrows + off + u * 512, lds_qr + buf * (TILE * 2) + u * 1024);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(dorows + off + u * 512, lds_dor + buf * (TILE * 2) + u * 1024);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(qtr + off + u * 512, lds_qt + buf * (TILE * 2) + u * 1024);
-#pragma unroll
-        for (int u = 0; u < NL; ++u) async_copy16(dotr + off + u * 512, lds_dot + buf * (TILE * 2) + u * 1024);
+        const size_t off = (size_t(r.hq) * pv.pack_tiles + r.tile) * TILE + size_t(wave_u * NL) * 512;      // (+ 16 bytes per lane)
+        const uint32_t lane_off = uint32_t(lane) * 16u;
+        async_copy_rows<NL>(qrows + off, lane_off, lds_qr + buf * (TILE * 2));
+        async_copy_rows<NL>(dorows + off, lane_off, lds_dor + buf * (TILE * 2));
+        async_copy_rows<NL>(qtr + off, lane_off, lds_qt + buf * (TILE * 2));
+        async_copy_rows<NL>(dotr + off, lane_off, lds_dot + buf * (TILE * 2));
         if (wave_u == 0) async_copy16(stats + (size_t(r.hq) * pv.pack_tiles + r.tile) * 256 + lane * 4, lds_st + buf * 1024);
     };
     if (n_iter > 0) issue(0, 0);
