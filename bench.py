@@ -393,12 +393,17 @@ def bench_prefill_backward(st, torch, W, reps):
     st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    st.st_profile_read(st.ST_PROF_BWD_DQ); st.st_profile_read(st.ST_PROF_BWD_DKV)
-    st.st_profile_enable(True)
     e0.record()
     for _ in range(reps):
         st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
     e1.record(); torch.cuda.synchronize()
+    # the per-kernel times come from a pass of their own: with kernel timing on, every timed kernel is launched
+    # several times between its events, which must not count in the call's own time
+    st.st_profile_read(st.ST_PROF_BWD_DQ); st.st_profile_read(st.ST_PROF_BWD_DKV)
+    st.st_profile_enable(True)
+    for _ in range(reps):
+        st.st_attn_prefill_bwd(go, q, k, v, out, lse, plan)
+    torch.cuda.synchronize()
     st.st_profile_enable(False)
     dq_ms, _ = st.st_profile_read(st.ST_PROF_BWD_DQ)
     dkv_ms, _ = st.st_profile_read(st.ST_PROF_BWD_DKV)
@@ -592,13 +597,14 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
     ws = torch.empty(st.st_decode_workspace_bytes(B, hq, hkv, d, 1, max_s, max_r), dtype=torch.uint8, device=dev)
     side = torch.cuda.Stream()
 
-    def step(i_timed):
+    def step(i_timed, source_appends=True):
         main = torch.cuda.current_stream()                              # (under capture: the capturing stream)
         len_s_all.copy_(src_vis.expand(L, B)); len_r_all.copy_(rsn_before.expand(L, B))
         side.wait_stream(main)
         for li, dc in enumerate(layers):
-            with torch.cuda.stream(side):
-                st.st_kv_append(dc, st.ST_SOURCE, k_src, v_src, host_len_upper_bound=shp.max_src_len, stream=side)
+            if source_appends:
+                with torch.cuda.stream(side):
+                    st.st_kv_append(dc, st.ST_SOURCE, k_src, v_src, host_len_upper_bound=shp.max_src_len, stream=side)
             if fp8:
                 st.st_kv_append(dc, st.ST_REASONING, k_tok, v_tok, host_len_upper_bound=max_r)
                 st.st_attn_decode_dual(q, dc, src_vis, rsn_len, max_s, max_r, out=out, workspace=ws)
@@ -648,12 +654,15 @@ def bench_decode(st, torch, W, steps, warmup, n_layers=None, use_graph=True, fp8
             graph = None
     times, mode = _time_launch_modes(torch, steps, graph, lambda: step(None))
     dt = times[mode] * steps
+    # the decode stream of the same step with nothing on the second stream (what the concurrent source appends cost)
+    alone_ms = _event_ms(torch, lambda: step(None, source_appends=False), steps)
     tokens = float((shp.src_visible_len.astype(np.int64) + shp.rsn_len).sum())
     # bytes per cached token and KV head: K and V rows of D elements; 8-bit rows carry an fp32 scale each
     per_layer = tokens * hkv * ((2 * d + 8) if fp8 else 2 * d * 2)
     append_bytes = float(B * (shp.src_append + 1)) * hkv * (2 * d * 2 + ((2 * d + 8) if fp8 else 2 * d * 2)) * L
     return {"shape": shp, "wave_timeline": timeline, "bytes_per_step": per_layer * L, "append_bytes_per_step": append_bytes, "sec_per_step": dt / steps,
-            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode, "sec_per_step_by_launch": times}
+            "layer_decode_ms": layer_ms, "bytes_per_layer": per_layer, "mode": mode, "sec_per_step_by_launch": times,
+            "sec_per_step_decode_stream_alone": alone_ms * 1e-3}
 
 
 def bench_source_chunk(st, torch, W, steps, warmup):
@@ -908,6 +917,10 @@ def main():
                 "ms_per_step": round(dec["sec_per_step"] * 1e3, 4),
                 "algorithmic_bytes_per_step": dec["bytes_per_step"], "append_bytes_per_step": dec["append_bytes_per_step"],
                 "pct_of_peak": round(100.0 * gbps_step / PEAK_HBM_GBPS, 2),
+                "decode_stream_alone": {
+                    "note": "the same 28-layer step with no source appends on the second stream, plain launches",
+                    "ms_per_step": round(dec["sec_per_step_decode_stream_alone"] * 1e3, 4),
+                    "pct_of_peak": round(100.0 * dec["bytes_per_step"] / dec["sec_per_step_decode_stream_alone"] / 1e9 / PEAK_HBM_GBPS, 2)},
                 "roofline": _hbm_roofline("decode_split16_kernel<128, true> (one layer)", dec["bytes_per_layer"], dec["layer_decode_ms"],
                                           "decode_split16_kernel@cfg3"),
                 "wave_timeline": dec["wave_timeline"]}
@@ -920,7 +933,7 @@ def main():
                             "U[1024,8192] (16-token pages) and attended causally over them (Alg. 1 prefill loop)",
                 "ms_per_step": round(sc["ms_per_step"], 4), "tflops": round(sc["flops"] / (sc["ms_per_step"] * 1e-3) / 1e12, 2),
                 "cache_read_once_gbps": round(sc["cache_bytes"] / (sc["ms_per_step"] * 1e-3) / 1e9, 1),
-                "roofline": _hbm_roofline("chunk_split_lds_kernel<128> (the cache read once)", sc["cache_bytes"], sc["kernel_ms"], None,
+                "roofline": _hbm_roofline("chunk_split_lds_kernel<128> (the cache read once)", sc["cache_bytes"], sc["kernel_ms"], "chunk_split_lds_kernel@cfg5",
                                           f"{sc['flops'] / sc['cache_bytes']:.0f} flop per cache byte, below the ridge of 312: HBM is the roof; the kernel's "
                                           f"matrix rate is {sc['flops'] / (sc['kernel_ms'] * 1e-3) / 1e12:.0f} TFLOP/s"),
                 "note": "append + attention; the 128 (token, head) rows of a sequence and KV head are one workgroup (4 waves x 32 rows) "
@@ -940,7 +953,8 @@ def main():
                 "ms_per_step_by_launch": {k: round(v * 1e3, 4) for k, v in d8["sec_per_step_by_launch"].items()},
                 "ms_per_step": round(d8["sec_per_step"] * 1e3, 4), "algorithmic_bytes_per_step": d8["bytes_per_step"],
                 "speedup_vs_bf16_step": round(dec["sec_per_step"] / d8["sec_per_step"], 3) if dec else None,
-                "roofline": _hbm_roofline("decode_split16_fp8_kernel<128> (one layer)", d8["bytes_per_layer"], d8["layer_decode_ms"], None)}
+                "roofline": _hbm_roofline("decode_split16_fp8_kernel<128> (one layer)", d8["bytes_per_layer"], d8["layer_decode_ms"],
+                                          "decode_split16_fp8_kernel@cfg3")}
     if "prefill_backward" in legs:
         with _leg(line, "prefill_backward", torch):
             bw = bench_prefill_backward(st, torch, W, 10)
@@ -956,7 +970,8 @@ def main():
                 "roofline": {"kernel": "bwd_dq_mfma_kernel<128> + bwd_dkv_mfma_kernel<128>", "bound": "mfma",
                              "achieved": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12, 1), "peak": PEAK_BF16_TFLOPS,
                              "unit": "TFLOP/s", "frac": round(bw["flops"] / ((bw["dq_ms"] + bw["dkv_ms"]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                             "traffic": None,
+                             "traffic": (lambda a, b: a + b if a is not None and b is not None else None)(
+                                 measured_traffic("bwd_dq_mfma_kernel@cfg2"), measured_traffic("bwd_dkv_mfma_kernel@cfg2")),
                              "note": "algorithmic = 5 products of 2 D flop per visible (query, key, head) triple (2.5x the forward); the two "
                                      "kernels execute 7 (scores and dP are recomputed on the key side); executed_tflops counts those"}}
     if "stream_session" in legs:
