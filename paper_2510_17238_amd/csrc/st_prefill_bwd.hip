@@ -179,22 +179,21 @@ __global__ __launch_bounds__(kTileM) void bwd_dkv_kernel(T* __restrict__ dkv, co
 // owns one query row), with three products per key tile:
 //   S^T  = K  Q^T     (K row tile from LDS, Q^T in registers)        -> P^T = exp2(S^T scale - lse)
 //   dP^T = V  dO^T    (V row tile from LDS, dO^T in registers)       -> dS^T = P^T (dP^T - delta)
-//   dQ^T += K^T dS^T  (K^T tile from LDS, dS^T from the accumulators, rounded to bf16)
+//   dQ^T += K^T dS^T  (K^T read out of the same K row tile with transposing LDS reads; dS^T from the accumulators,
+//                      rounded to bf16)
 // The kernel fits 256 registers, so TWO workgroups share a CU (two waves per SIMD fill each other's gaps between
-// matrix and vector work) if each stays within 80 KB of LDS: the K and V row tiles are double-buffered and copied
-// one tile ahead, K^T -- needed only by the last product -- has ONE buffer, filled at the top of its own
-// iteration and awaited (second barrier) before that product.
+// matrix and vector work); the K and V row tiles are double-buffered and copied one tile ahead (64 KB of LDS per
+// workgroup), one barrier per key tile.
 template <int D>
 struct BwdDqSmem {
     uint16_t k[2][kTileN * D];        // K rows
     uint16_t v[2][kTileN * D];        // V rows
-    uint16_t kt[1][D * kTileN];       // K^T
 };
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restrict__ dq, const uint16_t* __restrict__ d_out,
                                                              const uint16_t* __restrict__ q, const uint16_t* __restrict__ krows,
-                                                             const uint16_t* __restrict__ vrows, const uint16_t* __restrict__ ktr,
+                                                             const uint16_t* __restrict__ vrows,
                                                              const float* __restrict__ lse, const float* __restrict__ delta,
                                                              PlanView pv, int n_q_heads, int n_kv_heads, float scale) {
     constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
@@ -222,16 +221,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
         return ti < it.a_total ? it.tile_a0 + ti : it.tile_b0 + (ti - it.a_total);
     };
     const uint32_t wave_off = uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
-    const uint32_t lds_k = uint32_t(uintptr_t(&sm.k[0][0])) + wave_off, lds_v = uint32_t(uintptr_t(&sm.v[0][0])) + wave_off,
-                   lds_kt = uint32_t(uintptr_t(&sm.kt[0][0])) + wave_off;
+    const uint32_t lds_k = uint32_t(uintptr_t(&sm.k[0][0])) + wave_off, lds_v = uint32_t(uintptr_t(&sm.v[0][0])) + wave_off;
     auto issue_rows = [&](int ti, int buf) {
         const size_t off = head_off + size_t(tile_of(ti)) * TILE;
         async_copy_rows<NL>(krows + off, lane_off, lds_k + buf * (TILE * 2));
         async_copy_rows<NL>(vrows + off, lane_off, lds_v + buf * (TILE * 2));
-    };
-    auto issue_kt = [&](int ti) {
-        const size_t off = head_off + size_t(tile_of(ti)) * TILE;
-        async_copy_rows<NL>(ktr + off, lane_off, lds_kt);
     };
     issue_rows(0, 0);
 
@@ -261,14 +255,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-    int koff[KS], voff[4];
+    int koff[KS];
     {
-        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+        const int xk = swizzle_key<2 * D>(n) ^ hg;
 #pragma unroll
         for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
     }
+    const TrOffsets<D> tr(lane);
     // Score and dP blocks of a tile.  A lane owns one query row, so what has to be taken off every score (the row's
     // log-sum-exp) and off every dP (the row's delta) is one number per lane: between tiles the LAST block of each
     // kind holds it, negated, in all sixteen registers, and the first matrix instruction of every block takes that as
@@ -285,7 +278,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
         const int buf = ti & 1;
         wait_vmcnt<0>();                 // the row tiles of ti have landed; everybody is done with tile ti - 1
         __syncthreads();
-        issue_kt(ti);                    // (always the same number of copies per iteration: the wait below counts them)
         issue_rows(ti + 1, buf ^ 1);     // (past the end: the last tile again, never used)
 
         const bool in_a = ti < it.a_total;
@@ -297,7 +289,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
         // that latency); scheduling barriers keep the order
         const uint16_t* kb = &sm.k[buf][0];
         const uint16_t* vb = &sm.v[buf][0];
-        const uint16_t* tb = &sm.kt[0][0];
         constexpr int G = 4, NG1 = SB * KS / G, NG2 = DB * SB * 2 / (2 * G);
         bf16x8 fk[2][G], fv[2][G];
         auto load1 = [&](int g, int slot) {
@@ -308,11 +299,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
                 fv[slot][u] = *reinterpret_cast<const bf16x8*>(vb + 32 * sb * D + koff[j]);
             }
         };
-        auto load2 = [&](int g, int slot) {                 // 2 G fragments of K^T: fk then fv of the slot
+        auto load2 = [&](int g, int slot) {                 // 2 G fragments of K^T (transposing reads of the K rows): fk then fv of the slot
 #pragma unroll
             for (int u = 0; u < 2 * G; ++u) {
                 const int f = g * 2 * G + u;
-                (u < G ? fk[slot][u] : fv[slot][u - G]) = *reinterpret_cast<const bf16x8*>(tb + 32 * (f % DB) * kTileN + voff[f / DB]);
+                (u < G ? fk[slot][u] : fv[slot][u - G]) = tr.fragment(kb, f / DB, f % DB);
             }
         };
         load1(0, 0);
@@ -353,8 +344,6 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(uint16_t* __restric
             asm volatile("v_mov_b32 %0, %1" : "=v"(s_acc[SB - 1][i]) : "v"(neg_lse2));
             asm volatile("v_mov_b32 %0, %1" : "=v"(dp_acc[SB - 1][i]) : "v"(neg_delta));
         }
-        wait_vmcnt<2 * NL>();            // K^T of this tile has landed (the next row tiles may still fly) ...
-        __syncthreads();                 // ... for every wave
         load2(0, NG1 & 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -443,10 +432,10 @@ __global__ __launch_bounds__(256) void bwd_rowstats_kernel(float* __restrict__ s
 // first row whose visible-source count exceeds its first key on), for every query head of its group:
 //   S   = Q  K^T    (Q row tile from LDS, K^T in registers)      -> P  = exp2(S scale - lse_row)
 //   dP  = dO V^T    (dO row tile from LDS, V^T in registers)     -> dS = P (dP - delta_row)
-//   dV^T += dO^T P  (dO^T tile from LDS, P from the accumulators, rounded to bf16)
-//   dK^T += Q^T dS  (Q^T tile from LDS, dS from the accumulators)
+//   dV^T += dO^T P  (dO^T out of the dO row tile with transposing LDS reads, P from the accumulators, rounded to bf16)
+//   dK^T += Q^T dS  (Q^T out of the Q row tile likewise, dS from the accumulators)
 // Rows run along the accumulator registers here, so lse / delta / visible count of the rows come from the
-// tile's 1 KB statistics block in LDS.  Two buffers per tile kind (130 KB), one barrier per query tile.
+// tile's 1 KB statistics block in LDS.  Two buffers per tile kind (66 KB), one barrier per query tile.
 // acc += A B with the accumulator in ACCUMULATION registers, whatever form the compiler gives the file's other matrix
 // instructions: the key-side kernel's two output accumulators (128 registers) live there for the whole kernel, the
 // score and dP blocks in vector registers where the exponentials read them -- no copies between the two files.
@@ -458,16 +447,13 @@ template <int D>
 struct BwdDkvSmem {
     uint16_t qr[2][kTileN * D];       // Q rows
     uint16_t dor[2][kTileN * D];      // dO rows
-    uint16_t qt[2][D * kTileN];       // Q^T
-    uint16_t dot[2][D * kTileN];      // dO^T
     float stats[2][256];
 };
 
 template <int D>
 __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
                                                               const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                                                              const uint16_t* __restrict__ qrows, const uint16_t* __restrict__ qtr,
-                                                              const uint16_t* __restrict__ dorows, const uint16_t* __restrict__ dotr,
+                                                              const uint16_t* __restrict__ qrows, const uint16_t* __restrict__ dorows,
                                                               const float* __restrict__ stats, PlanView pv, int n_q_heads,
                                                               int n_kv_heads, float scale) {
     constexpr int KS = D / 16, DB = D / 32, SB = kTileN / 32;
@@ -556,10 +542,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     };
     const uint32_t wave_off = uint32_t(__builtin_amdgcn_readfirstlane(wave)) * (NL * 1024);
     const uint32_t lds_qr = uint32_t(uintptr_t(&sm.qr[0][0])) + wave_off, lds_dor = uint32_t(uintptr_t(&sm.dor[0][0])) + wave_off,
-                   lds_qt = uint32_t(uintptr_t(&sm.qt[0][0])) + wave_off, lds_dot = uint32_t(uintptr_t(&sm.dot[0][0])) + wave_off,
                    lds_st = uint32_t(uintptr_t(&sm.stats[0][0]));
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    // the copies of one iteration go out in four pieces (one tensor each; the statistics with the first), so that the loop
+    // the copies of one iteration go out in two pieces (one tensor each; the statistics with the first), so that the loop
     // can issue them from the shadows of its first matrix instructions
     const uint32_t lane_off = uint32_t(lane) * 16u;
     auto issue_piece = [&](const Iter& r, int buf, int piece) {
@@ -567,18 +552,14 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         if (piece == 0) {
             if (wave_u == 0) async_copy16(stats + (size_t(r.hq) * pv.pack_tiles + r.tile) * 256 + lane * 4, lds_st + buf * 1024);
             async_copy_rows<NL>(qrows + off, lane_off, lds_qr + buf * (TILE * 2));
-        } else if (piece == 1) {
-            async_copy_rows<NL>(dorows + off, lane_off, lds_dor + buf * (TILE * 2));
-        } else if (piece == 2) {
-            async_copy_rows<NL>(qtr + off, lane_off, lds_qt + buf * (TILE * 2));
         } else {
-            async_copy_rows<NL>(dotr + off, lane_off, lds_dot + buf * (TILE * 2));
+            async_copy_rows<NL>(dorows + off, lane_off, lds_dor + buf * (TILE * 2));
         }
     };
     if (n_iter > 0) {
         const Iter r0 = iter_of(0);
 #pragma unroll
-        for (int piece = 0; piece < 4; ++piece) issue_piece(r0, 0, piece);
+        for (int piece = 0; piece < 2; ++piece) issue_piece(r0, 0, piece);
     }
 
     f32x16 dk_acc[DB], dv_acc[DB];
@@ -589,14 +570,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
             dk_acc[db][i] = 0.f;
             dv_acc[db][i] = 0.f;
         }
-    int koff[KS], voff[4];
+    int koff[KS];
     {
-        const int xk = swizzle_key<2 * D>(n) ^ hg, xv = swizzle_key<2 * kTileN>(n) ^ hg;
+        const int xk = swizzle_key<2 * D>(n) ^ hg;
 #pragma unroll
         for (int j = 0; j < KS; ++j) koff[j] = n * D + ((2 * j) ^ xk) * 8;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) voff[qd] = n * kTileN + ((2 * qd) ^ xv) * 8;
     }
+    const TrOffsets<D> tr(lane);
 
     for (int x = 0; x < n_iter; ++x) {
         const int buf = x & 1;
@@ -617,8 +597,6 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         f32x16 s_acc[SB], dp_acc[SB];
         const uint16_t* qb = &sm.qr[buf][0];
         const uint16_t* ob = &sm.dor[buf][0];
-        const uint16_t* tq = &sm.qt[buf][0];
-        const uint16_t* to = &sm.dot[buf][0];
         constexpr int G = DB;                                // fragments per tensor and group; eight score pairs per half go beside 2 G pairs of matrix instructions
         constexpr int PIECES = 4 / G;
         bf16x8 fq[2][G], fo[2][G];
@@ -632,8 +610,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         auto load2 = [&](int stp, int slot) {                // dO^T and Q^T of rows 16 stp .. 16 stp + 15, all d blocks
 #pragma unroll
             for (int u = 0; u < G; ++u) {
-                fo[slot][u] = *reinterpret_cast<const bf16x8*>(to + 32 * u * kTileN + voff[stp]);
-                fq[slot][u] = *reinterpret_cast<const bf16x8*>(tq + 32 * u * kTileN + voff[stp]);
+                fo[slot][u] = tr.fragment(ob, stp, u);
+                fq[slot][u] = tr.fragment(qb, stp, u);
             }
         };
         // lane (n, hg), block rb, register i  <->  query row cur.row0 + 32 rb + 16 (i/8) + 8 hg + i%8, key my_key.
@@ -701,13 +679,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
 #pragma unroll
                 for (int u = 0; u < G; ++u) {
                     s_acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[slot][u], kf[G * g + u], s_acc[rb], 0, 0, 0);
-                    if (SOFT == -2) {                        // the first block of an iteration: the next iteration's copies
-                        const int piece = (G * g + u) * 4 / (2 * G);
-                        if ((G * g + u) * 4 % (2 * G) == 0) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (more) issue_piece(nxt, buf ^ 1, piece);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+                    if (SOFT == -2 && u == 0) {              // the first block of an iteration: the next iteration's copies
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (more) issue_piece(nxt, buf ^ 1, g);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     if (SOFT >= 0) {
                         __builtin_amdgcn_sched_barrier(0);
@@ -793,9 +768,9 @@ using namespace st;
 
 namespace {
 inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
-// workspace of the bf16 path: delta (token order) | row statistics | K rows | K^T | V rows | Q rows | Q^T | dO rows | dO^T
+// workspace of the bf16 path: delta (token order) | row statistics | K rows | V rows | Q rows | dO rows
 struct BwdLayout {
-    size_t delta, stats, krows, ktr, vrows, qrows, qtr, dorows, dotr, total;
+    size_t delta, stats, krows, vrows, qrows, dorows, total;
 };
 BwdLayout bwd_layout(const st_plan* plan, int n_q_heads, int n_kv_heads, int head_dim, st_dtype dt) {
     BwdLayout L{};
@@ -807,12 +782,9 @@ BwdLayout bwd_layout(const st_plan* plan, int n_q_heads, int n_kv_heads, int hea
         const size_t kvt = size_t(n_kv_heads) * plan->pack_tiles * tile, qt = size_t(n_q_heads) * plan->pack_tiles * tile;
         L.stats = take(size_t(n_q_heads) * plan->pack_tiles * 256 * sizeof(float));
         L.krows = take(kvt);
-        L.ktr = take(kvt);
         L.vrows = take(kvt);
         L.qrows = take(qt);
-        L.qtr = take(qt);
         L.dorows = take(qt);
-        L.dotr = take(qt);
     }
     L.total = off + 256;
     return L;
@@ -872,13 +844,13 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
         auto at = [&](size_t o) { return reinterpret_cast<uint16_t*>(w + o); };
         float* stats = reinterpret_cast<float*>(w + L.stats);
         const unsigned kv_tiles = unsigned(plan->pack_tiles) * n_kv_heads, q_tiles = unsigned(plan->pack_tiles) * n_q_heads;
-        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(kv_tiles), dim3(256), 0, s, at(L.krows), at(L.ktr), (const uint16_t*)k,
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(kv_tiles), dim3(256), 0, s, at(L.krows), (uint16_t*)nullptr, (const uint16_t*)k,
                            (const uint16_t*)k, pv, n_kv_heads);
         hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(kv_tiles), dim3(256), 0, s, at(L.vrows), (uint16_t*)nullptr, (const uint16_t*)v,
                            (const uint16_t*)v, pv, n_kv_heads);
-        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.qrows), at(L.qtr), (const uint16_t*)q,
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.qrows), (uint16_t*)nullptr, (const uint16_t*)q,
                            (const uint16_t*)q, pv, n_q_heads);
-        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.dorows), at(L.dotr), (const uint16_t*)d_out,
+        hipLaunchKernelGGL((tile_pack_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, at(L.dorows), (uint16_t*)nullptr, (const uint16_t*)d_out,
                            (const uint16_t*)d_out, pv, n_q_heads);
         hipLaunchKernelGGL((bwd_rowstats_kernel<HD>), dim3(q_tiles), dim3(256), 0, s, stats, delta, (const uint16_t*)d_out,
                            (const uint16_t*)out, lse, pv, n_q_heads);
@@ -888,12 +860,12 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
         prof_begin(kProfBwdDq, s);
         for (int rep = 0; rep < prof_repeat(); ++rep)
         hipLaunchKernelGGL((bwd_dq_mfma_kernel<HD>), dim3((unsigned)qblocks), dim3(256), smem_q, s, (uint16_t*)dq, (const uint16_t*)d_out,
-                           (const uint16_t*)q, at(L.krows), at(L.vrows), at(L.ktr), lse, delta, pv, n_q_heads, n_kv_heads, scale);
+                           (const uint16_t*)q, at(L.krows), at(L.vrows), lse, delta, pv, n_q_heads, n_kv_heads, scale);
         prof_end(kProfBwdDq, s);
         prof_begin(kProfBwdDkv, s);
         for (int rep = 0; rep < prof_repeat(); ++rep)
         hipLaunchKernelGGL((bwd_dkv_mfma_kernel<HD>), dim3((unsigned)kblocks), dim3(256), smem_k, s, (uint16_t*)dk, (uint16_t*)dv,
-                           (const uint16_t*)k, (const uint16_t*)v, at(L.qrows), at(L.qtr), at(L.dorows), at(L.dotr), stats, pv,
+                           (const uint16_t*)k, (const uint16_t*)v, at(L.qrows), at(L.dorows), stats, pv,
                            n_q_heads, n_kv_heads, scale);
         prof_end(kProfBwdDkv, s);
         return ST_OK;

@@ -62,11 +62,47 @@ __device__ __forceinline__ void wait_vmcnt() {
 // LDS tiles of the MFMA kernel: no padding; inside every row the 16-byte chunks are stored at
 // position chunk ^ key(row).  The LDS has 64 four-byte banks, so a 16-byte operand read serves 16
 // lanes (16 consecutive rows) per cycle, and the key must send those 16 rows to 16 different
-// 16-byte columns of the 256-byte bank line: key = row % 16 for 256-byte rows, (row / 2) % 8 for
-// 128-byte rows (two rows per bank line).  The packed global tiles already have this arrangement,
-// so a tile travels global -> LDS as a plain linear copy.
+// 16-byte columns of the 256-byte bank line: for 256-byte rows the key is row % 16 with its two
+// 2-bit halves exchanged -- any one-to-one key serves the 16-byte reads, and this one also sends
+// four CONSECUTIVE rows to four different 64-byte quarters of the bank line, which is what the
+// transposing reads below (four rows x 64 bytes per pass) need; (row / 2) % 8 for 128-byte rows
+// (two rows per bank line).  The packed global tiles already have this arrangement, so a tile
+// travels global -> LDS as a plain linear copy.
 template <int ROW_BYTES>
-__device__ __forceinline__ int swizzle_key(int row) { return ROW_BYTES == 256 ? (row & 15) : ((row >> 1) & 7); }
+__device__ __forceinline__ int swizzle_key(int row) {
+    return ROW_BYTES == 256 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((row >> 1) & 7);
+}
+
+// A transposed operand fragment straight out of a ROW tile ([64 rows][D], rows parked in swap23 order, chunks
+// swizzled as above): ds_read_b64_tr_b16 gives lane l of a 16-lane group, as its element j, the (l % 4)-th 16-bit
+// value of the 8 bytes that lane 4 j + l / 4 of the group points at.  With lane i of a group pointing at row
+// i / 4, columns 4 (i % 4) .. + 3 of a 4-row x 16-column block, every lane receives one COLUMN of the block: two
+// such reads (rows 0-3 and 4-7 of an 8-row group) are the eight k-values of an A operand whose M index runs
+// along the tile's columns.  TrOffsets holds a lane's element offsets inside a 16-row step for the two reads
+// and every 32-column block; the step's first row (a multiple of 16) is added as a constant.
+template <int D>
+struct TrOffsets {
+    int off[2][D / 32];
+    __device__ __forceinline__ explicit TrOffsets(int lane) {
+        const int l16 = lane & 15, mg = (lane >> 4) & 1, hg = lane >> 5;
+        const int j = l16 >> 2, cm = 2 * mg + ((l16 & 3) >> 1);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            // logical row 8 hg + 4 t + j of the step sits at position 8 t + 4 hg + j (bits 2 and 3 swapped)
+            const int lr = 8 * t + 4 * hg + j;
+#pragma unroll
+            for (int u = 0; u < D / 32; ++u) off[t][u] = lr * D + ((4 * u + cm) ^ swizzle_key<2 * D>(lr)) * 8 + 4 * (l16 & 1);
+        }
+    }
+    // columns 32 u .. 32 u + 31 (M index = lane % 32), rows 16 step .. + 15 (k index 8 (lane / 32) .. + 7) of `tile`
+    __device__ __forceinline__ bf16x8 fragment(const uint16_t* tile, int step, int u) const {
+        typedef __bf16 lds_bf16x4 __attribute__((ext_vector_type(4), address_space(3)));
+        const uint16_t* p = tile + step * 16 * D;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + off[0][u]));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + off[1][u]));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+};
 
 // swap bits 2 and 3: the row order in which K is parked in LDS, so that after the
 // first MFMA each half-wave holds 8 CONSECUTIVE keys per 16-key step
