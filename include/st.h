@@ -257,7 +257,7 @@ st_status st_attn_prefill_ids(void* out, float* lse, const void* q, const void* 
  * all of dtype dt, same plan as the forward.  Deterministic (no atomics).
  * ST_BF16: products on the matrix cores (bf16 operands -- P and dS are rounded to bf16 before the
  * second products, as the forward rounds P -- fp32 accumulation); every operand is first gathered
- * into 64-row tiles in the workspace, which therefore holds about 2.2x the bytes of q, k, v, d_out.
+ * into 64-row tiles in the workspace, which therefore holds about 1.1x the bytes of q, k, v, d_out.
  * ST_F32: a plain one-thread-per-row path in fp32, not tuned.
  * workspace: at least st_prefill_bwd_workspace_bytes(plan, n_q_heads, n_kv_heads, head_dim, dt)
  * bytes, 256-byte aligned.  Errors as for st_attn_prefill.

@@ -4,8 +4,9 @@
 // one tensor as a "row tile" ([64 rows][D], rows parked in the order the first-type MFMA wants, 16-byte chunks
 // XOR-swizzled) and the rows of a second tensor as a "transposed tile" ([D][64 rows], swizzled), 16 KB each at
 // D = 128, contiguous -- so that a kernel streams tiles with plain linear copies and needs no per-row token lookup
-// and no transpose in its inner loop.  Either destination may be null (that half is skipped).  The forward packs (K rows, V^T); the backward also (V rows, K^T),
-// (Q rows, Q^T) and (dO rows, dO^T).
+// and no transpose in its inner loop.  Either destination may be null (that half is skipped).  The forward packs
+// (K rows, V^T); the backward packs row tiles only (K, V, Q, dO) and takes its transposed operands out of them with
+// transposing LDS reads (TrOffsets below).
 #pragma once
 #include "st_plan.h"
 
