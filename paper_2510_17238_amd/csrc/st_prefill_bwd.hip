@@ -480,11 +480,24 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     const int a_first = it.row0 / kTileN, a_end = (it.n_stream + kTileN - 1) / kTileN;
     int b_first = 0, b_end = 0;
     if (key_is_src) {
-        int lo = 0, hi = n_rsn;                                 // first reasoning row whose visible count exceeds row0
+        // first reasoning row whose visible count exceeds row0 (counts do not decrease along the stream), searched by
+        // the whole wave: every lane tests the end of one 64th of the range, so the range shrinks 64-fold per memory
+        // round trip (three for a few thousand rows, where a bisection takes a dozen)
+        int lo = 0, hi = n_rsn;                                 // the answer lies in [lo, hi]; hi == n_rsn: no such row
         const int32_t* vr = pv.vis + it.b_base + S;
         while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (vr[mid] > it.row0) hi = mid; else lo = mid + 1;
+            const int span = hi - lo, step = (span + 63) >> 6;
+            const int last = min(span - 1, lane * step + step - 1);             // end of this lane's piece
+            const unsigned long long seen = __ballot(vr[lo + last] > it.row0);  // (monotone along the lanes)
+            if (seen == 0ull) {
+                lo = hi;
+            } else {
+                const int first = __ffsll((long long)seen) - 1;
+                hi = lo + min(span - 1, first * step + step - 1);               // this row exceeds row0 ...
+                lo = lo + first * step;                                         // ... and none before this piece does
+            }
+            lo = __builtin_amdgcn_readfirstlane(lo);
+            hi = __builtin_amdgcn_readfirstlane(hi);
         }
         b_first = lo / kTileN;
         b_end = (n_rsn + kTileN - 1) / kTileN;
