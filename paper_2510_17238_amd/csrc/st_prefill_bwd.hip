@@ -537,9 +537,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     // down (reasoning tiles, then the own stream's) -- every key block of a sequence then starts at the same query tile, and
     // the blocks that start together read the same tiles at about the same time (a quarter less traffic into L2)
     struct Iter { int tile; int hq; int row0; bool rs; };
-    auto iter_of = [&](int x) {
-        x = min(x, n_iter - 1);
-        const int t = (n_a + n_b - 1) - x / group, g = x % group;
+    auto iter_at = [&](int t, int g) {                          // (tile count t of the walk, head g of the group)
         Iter r;
         r.hq = hk * group + g;
         if (t < n_a) {
@@ -570,7 +568,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
         }
     };
     if (n_iter > 0) {
-        const Iter r0 = iter_of(0);
+        const Iter r0 = iter_at(n_a + n_b - 1, 0);
 #pragma unroll
         for (int piece = 0; piece < 2; ++piece) issue_piece(r0, 0, piece);
     }
@@ -591,12 +589,21 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_mfma_kernel(uint16_t* __restri
     }
     const TrOffsets<D> tr(lane);
 
+    int t_next = n_a + n_b - 1, g_next = 0;
+    Iter nxt = iter_at(t_next, g_next);
     for (int x = 0; x < n_iter; ++x) {
         const int buf = x & 1;
         wait_vmcnt<0>();                 // the tiles of iteration x have landed; everybody is done with x - 1
         __syncthreads();
         const bool more = x + 1 < n_iter;
-        const Iter cur = iter_of(x), nxt = iter_of(x + 1);
+        const Iter cur = nxt;
+        if (more) {                      // (no division in the loop: the walk is stepped)
+            if (++g_next == group) {
+                g_next = 0;
+                --t_next;
+            }
+            nxt = iter_at(t_next, g_next);
+        }
 
         // Operands come out of LDS a group of matrix instructions ahead of their use (one wave per SIMD: nobody else
         // hides that latency): groups of 4 fragments per tensor, the next group requested before the current one is
