@@ -473,14 +473,15 @@ def test_prefill_bwd_is_deterministic_and_checks_arguments(st):
 
 # ------------------------------------------------- many random structures --
 def test_forward_and_backward_over_many_random_structures(st):
-    """Thirty seeded structures -- segment counts, empty and one-token segments, both layouts, both head sizes, grouped
-    heads, tile multiples by chance -- through the bf16 forward (both kernels) and backward, and a few in fp32."""
+    """Sixty seeded structures -- segment counts, empty and one-token segments, both layouts, both head sizes, grouped
+    heads, tile multiples by chance, reasoning streams from a few to a few thousand tokens -- through the bf16 forward
+    (both kernels) and backward, and a few in fp32."""
     rng = np.random.Generator(np.random.PCG64(9000))
-    for trial in range(30):
+    for trial in range(60):
         d = int(rng.choice([64, 128])); hkv = int(rng.choice([1, 2])); hq = hkv * int(rng.choice([1, 2, 4]))
         layout = "interleaved" if trial % 2 else "grouped"
-        hi_s, hi_r = int(rng.choice([3, 40, 130])), int(rng.choice([3, 50, 150]))
-        cfg = W.random_prefill(9100 + trial, int(rng.integers(1, 4)), int(rng.integers(1, 7)), (0, hi_s), (0, hi_r), hq, hkv, d,
+        hi_s, hi_r = int(rng.choice([3, 40, 130, 300])), int(rng.choice([3, 50, 150, 500]))
+        cfg = W.random_prefill(9100 + trial, int(rng.integers(1, 4)), int(rng.integers(1, 9)), (0, hi_s), (0, hi_r), hq, hkv, d,
                                "f32" if trial % 10 == 9 else "bf16", layout)
         if cfg.n_tokens == 0:
             continue
