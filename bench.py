@@ -376,14 +376,17 @@ def bench_probes(st, torch):
     return res
 
 
-def bench_prefill_backward(st, torch, W, reps):
-    """Forward + backward of the attention stage on configs[1] (the plain backward path)."""
+def bench_prefill_backward(st, torch, W, reps, zero_inputs=False):
+    """Forward + backward of the attention stage on configs[1]; zero_inputs: the same launches on all-zero q, k, v, dO."""
     dev = "cuda"
     cfg = W.config2()
     hq, hkv, d, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_tokens
     g = torch.Generator(device=dev); g.manual_seed(cfg.seed + 9)
     rnd = lambda h: torch.randn((n, h, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     q, k, v, go = rnd(hq), rnd(hkv), rnd(hkv), rnd(hq)
+    if zero_inputs:
+        for t in (q, k, v, go):
+            t.zero_()
     seg = torch.from_numpy(cfg.segment_ids).to(dev); strm = torch.from_numpy(cfg.stream_ids).to(dev)
     pos = torch.from_numpy(cfg.positions).to(dev)
     plan = st.st_plan_create(seg, strm, pos, cfg.cu_seqlens)
@@ -986,6 +989,11 @@ def main():
                 "random_inputs": {"avg_kernel_ms": round(pc["kernel_ms"], 3), "tflops": round(pc["flops"] / (pc["kernel_ms"] * 1e-3) / 1e12, 1)},
                 "all_zero_inputs": {"avg_kernel_ms": round(pc["zero_input_kernel_ms"], 3),
                                     "tflops": round(pc["flops"] / (pc["zero_input_kernel_ms"] * 1e-3) / 1e12, 1)}}
+            br = bench_prefill_backward(st, torch, W, 5)
+            bz = bench_prefill_backward(st, torch, W, 5, zero_inputs=True)
+            line["power_check"]["backward_kernels_configs1"] = {
+                "random_inputs": {"bwd_dq_mfma_kernel_ms": round(br["dq_ms"], 4), "bwd_dkv_mfma_kernel_ms": round(br["dkv_ms"], 4)},
+                "all_zero_inputs": {"bwd_dq_mfma_kernel_ms": round(bz["dq_ms"], 4), "bwd_dkv_mfma_kernel_ms": round(bz["dkv_ms"], 4)}}
     if not args.no_cpu_baseline:
         from oracle import streaming_attention as O
         line["cpu_baseline"] = cpu_baseline(W, O)
