@@ -857,7 +857,7 @@ extern "C" st_status st_attn_prefill_bwd(void* dq, void* dk, void* dv, const voi
                            (const T*)q, (const T*)k, (const T*)v, lse, pv, n_q_heads, n_kv_heads, scale);
         return ST_OK;
     };
-    // bf16: every operand gathered once into 64-row tiles (rows and transposed), then two MFMA kernels
+    // bf16: every operand gathered once into 64-row row tiles, then two MFMA kernels
     auto run_mfma = [&](auto dtag) -> st_status {
         constexpr int HD = decltype(dtag)::value;
         unsigned char* w = static_cast<unsigned char*>(workspace);
