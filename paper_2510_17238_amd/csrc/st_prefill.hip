@@ -546,14 +546,26 @@ __global__ __launch_bounds__(256, NH == 2 ? 1 : 2) void prefill_attn_kernel(uint
     bf16x8 pb[NH][SB][2];                                // probabilities of the current tile, as the second product's operand
     float psum[NH];
     // slot m of NH SB KS: PER elements of the probabilities of the tile in sv, in the order (head, block, register)
+    // (the two-head form sums the probabilities as the second product will see them, rounded to bf16, two per
+    // instruction: one vector instruction less per pair, +0.8 % there; the one-head form measured 1 % slower with it
+    // and keeps its fp32 adds)
+    bf16x2 ones2;
+    ones2[0] = (__bf16)1.f;
+    ones2[1] = (__bf16)1.f;
+    static_assert(PER % 2 == 0, "probabilities are formed in pairs");
     auto exp_slot = [&](int m) {
 #pragma unroll
-        for (int u = 0; u < PER; ++u) {
+        for (int u = 0; u < PER; u += 2) {
             const int e = m * PER + u;
             const int hh = e / (SB * 16), sb2 = (e / 16) % SB, i = e % 16;
-            const float pr = __builtin_amdgcn_exp2f(sv[hh][sb2][i]);
-            psum[hh] += pr;
-            pb[hh][sb2][i >> 3][i & 7] = (__bf16)pr;
+            const float pr0 = __builtin_amdgcn_exp2f(sv[hh][sb2][i]), pr1 = __builtin_amdgcn_exp2f(sv[hh][sb2][i + 1]);
+            bf16x2 p2;
+            p2[0] = (__bf16)pr0;
+            p2[1] = (__bf16)pr1;
+            if constexpr (NH == 2) psum[hh] = __builtin_amdgcn_fdot2_f32_bf16(p2, ones2, psum[hh], false);
+            else psum[hh] += pr0 + pr1;
+            pb[hh][sb2][i >> 3][i & 7] = p2[0];
+            pb[hh][sb2][i >> 3][(i & 7) + 1] = p2[1];
         }
     };
     // A row sum beyond 2^kRiseLog2 (or not finite) means the tile's exponents outgrew the reference: move it to the
