@@ -188,3 +188,22 @@ def test_stream_argument_checks(lib):
     rep = B._StreamReportStruct()
     assert lib.st_stream_run(C.byref(job), 5, C.byref(rep)) == 1
     assert lib.st_stream_run(C.byref(job), 0, C.byref(rep)) == 1 and b"sizes" in lib.st_last_error()
+
+
+def test_bench_finds_its_traffic_figures_in_the_tracked_summary():
+    """Every `traffic` key that bench.py asks for is a line of profiles/hbm_traffic_per_kernel.txt (so that no roofline
+    object silently reports null), and the figures are plausible byte counts."""
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    src = open(os.path.join(root, "bench.py")).read()
+    keys = set(re.findall(r'"([a-z0-9_]+@cfg[0-9a-z]+)"', src))
+    keys |= {f"prefill_attn_kernel@{name}" for name in ("cfg4a", "cfg2")}
+    assert len(keys) >= 8
+    for key in sorted(keys):
+        v = bench.measured_traffic(key)
+        assert v is not None, f"no `traffic {key} ...` line in {bench.TRAFFIC_PROFILE}"
+        assert 1e6 < v < 1e11
+    assert bench.measured_traffic("no_such_kernel@cfg0") is None
